@@ -1,0 +1,270 @@
+"""CPU oracle for selective KV recomputation over reused chunk-caches (Cache-Craft).
+
+TEST INFRASTRUCTURE ONLY.  Plain, slow, fp64 numpy; written from the paper's
+definitions, one step at a time, with no blocking, fusion or paging tricks.
+It shares no code with the HIP library and must never be imported by the
+product path: only tests/, __graft_entry__.smoke() and bench.py's
+cpu_baseline leg may call it.
+
+What is computed, for one attention layer and a batch of prompts
+S = C_1 .. C_k U (Sec. 2.2):
+
+  shift   re-position every cached chunk's keys: the rotary embedding of a key
+          cached at position s and now placed at position p is turned by the
+          angle (p - s) * inv_freq (Sec. 3.4.3 "Handling Partial Prefill",
+          Sec. 4 "RPE Management").  Values are position-free and unchanged.
+  score   for each token of a chunk, its attention mass on all *prior* chunks:
+          sum over j < i of inter(C_j, t) with a_kl the rows of the causal
+          softmax of Eq. (1) (Eq. (2), the block matrix below Eq. (3), Eq. (10)).
+  select  the N tokens of each chunk with the largest score (Eq. (10)),
+          N given per chunk as an integer.
+  fix     recomputed K (rotated to its new position) and V of the selected
+          tokens and of the question tokens replace the stale rows (Sec. 3.4.3).
+  attend  causal attention of only those tokens against the whole merged K, V
+          (Sec. 2.1 per-token form of Eq. (1); Sec. 4 "Selective Token
+          Recomputation").
+
+Readings taken where the paper leaves a choice (each is a reading, not a fact
+of the paper): rotate-half pairing (x = first half of the head, y = second
+half; "upper and lower 64-dimensional components", Sec. 4); frequencies
+theta^(-2i/d); logits scaled by 1/sqrt(d) and masked entries excluded from the
+softmax; queries of the later chunk attend keys of the earlier chunk; the
+softmax denominator runs over every key up to and including the token itself;
+a token's score is the mean over query heads; ties go to the lower index;
+padding slots of a partly filled block are never keys; grouped-query mapping
+kv_head = q_head // (Hq / Hkv).
+
+Parity pins (tests/test_oracle_pins.py): every function below is pinned by
+closed forms, invariants, limiting cases or brute force -- none is unpinned.
+The scoring *definition* (mean over heads, scores in the new context) is pinned
+to the reading above, which the paper does not fix.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+BLOCK = 16
+
+
+# --------------------------------------------------------------------------
+# rotary position embedding
+# --------------------------------------------------------------------------
+def inv_freq(d: int, theta: float) -> np.ndarray:
+    """Rotation frequency of pair i: theta^(-2i/d), i = 0 .. d/2-1."""
+    i = np.arange(d // 2, dtype=np.float64)
+    return np.float64(theta) ** (-2.0 * i / d)
+
+
+def rotate(x: np.ndarray, pos: np.ndarray, theta: float) -> np.ndarray:
+    """Turn every (x_i, y_i) = (v[i], v[i+d/2]) pair of the last axis by pos * inv_freq_i.
+
+    x: [n, H, d] fp64; pos: [n] (any integer, negative allowed).
+    Forward rotation: x' = x cos(phi) - y sin(phi), y' = y cos(phi) + x sin(phi)  (Sec. 4).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    d = x.shape[-1]
+    h = d // 2
+    phi = np.asarray(pos, dtype=np.float64)[:, None] * inv_freq(d, theta)[None, :]   # [n, d/2]
+    c, s = np.cos(phi)[:, None, :], np.sin(phi)[:, None, :]
+    a, b = x[..., :h], x[..., h:]
+    return np.concatenate([a * c - b * s, b * c + a * s], axis=-1)
+
+
+# --------------------------------------------------------------------------
+# reading / writing the paged pools (only at the two ends of the oracle)
+# --------------------------------------------------------------------------
+def read_k_pages(k_pool: np.ndarray, blocks: Sequence[int], n_tokens: int) -> np.ndarray:
+    """K pool [nb, Hkv, 16, d] -> logical [n_tokens, Hkv, d] (padding slots dropped)."""
+    pages = np.asarray(k_pool)[np.asarray(blocks, dtype=np.int64)]          # [p, Hkv, 16, d]
+    p, hkv, _, d = pages.shape
+    return pages.transpose(0, 2, 1, 3).reshape(p * BLOCK, hkv, d)[:n_tokens].astype(np.float64)
+
+
+def read_v_pages(v_pool: np.ndarray, blocks: Sequence[int], n_tokens: int) -> np.ndarray:
+    """V pool [nb, Hkv, d, 16] -> logical [n_tokens, Hkv, d]."""
+    pages = np.asarray(v_pool)[np.asarray(blocks, dtype=np.int64)]          # [p, Hkv, d, 16]
+    p, hkv, d, _ = pages.shape
+    return pages.transpose(0, 3, 1, 2).reshape(p * BLOCK, hkv, d)[:n_tokens].astype(np.float64)
+
+
+# --------------------------------------------------------------------------
+# the steps
+# --------------------------------------------------------------------------
+def shift_keys(k: np.ndarray, delta: int, theta: float) -> np.ndarray:
+    """Keys of one chunk [n, Hkv, d] cached at position s, re-placed at s + delta."""
+    n = k.shape[0]
+    return rotate(k, np.full(n, delta, dtype=np.int64), theta)
+
+
+def prior_mass(q_rot: np.ndarray, k_ctx: np.ndarray, pos: np.ndarray, chunk_start: int) -> np.ndarray:
+    """Per-head attention mass of each query on keys before `chunk_start`.
+
+    q_rot [n, Hq, d]: rotated queries at positions pos [n];
+    k_ctx [>= max(pos)+1, Hkv, d]: keys of the context in logical order.
+    Returns [n, Hq]: sum_{l < chunk_start} a_{p,l}, a = softmax over l <= p of q.k_l / sqrt(d).
+    """
+    n, hq, d = q_rot.shape
+    hkv = k_ctx.shape[1]
+    g = hq // hkv
+    out = np.zeros((n, hq), dtype=np.float64)
+    n_keys = int(pos.max()) + 1 if n else 0
+    key_idx = np.arange(n_keys)
+    for h in range(hq):
+        logits = q_rot[:, h, :] @ k_ctx[:n_keys, h // g, :].T / np.sqrt(np.float64(d))   # [n, n_keys]
+        visible = key_idx[None, :] <= pos[:, None]
+        logits = np.where(visible, logits, -np.inf)
+        m = logits.max(axis=1, keepdims=True)
+        e = np.exp(logits - m)
+        a = e / e.sum(axis=1, keepdims=True)
+        out[:, h] = a[:, :chunk_start].sum(axis=1)
+    return out
+
+
+def top_n(scores: np.ndarray, n_sel: int) -> np.ndarray:
+    """Indices of the n_sel largest scores, lower index first among equals; ascending."""
+    order = np.lexsort((np.arange(len(scores)), -np.asarray(scores, dtype=np.float64)))
+    return np.sort(order[:n_sel]).astype(np.int64)
+
+
+def causal_attention_rows(q_rot: np.ndarray, pos: np.ndarray, k_ctx: np.ndarray, v_ctx: np.ndarray):
+    """out_j = softmax(q_j K_{:j}^T / sqrt(d)) V_{:j} for the given rows only.
+
+    q_rot [n, Hq, d] (already rotated), pos [n]; k_ctx, v_ctx [n_ctx, Hkv, d] logical order.
+    Returns out [n, Hq, d] and lse [n, Hq] (natural log of the softmax denominator).
+    """
+    n, hq, d = q_rot.shape
+    g = hq // k_ctx.shape[1]
+    out = np.zeros((n, hq, d), dtype=np.float64)
+    lse = np.zeros((n, hq), dtype=np.float64)
+    for j in range(n):
+        p = int(pos[j])
+        for h in range(hq):
+            s = k_ctx[: p + 1, h // g, :] @ q_rot[j, h, :] / np.sqrt(np.float64(d))
+            m = s.max()
+            e = np.exp(s - m)
+            z = e.sum()
+            out[j, h, :] = (e / z) @ v_ctx[: p + 1, h // g, :]
+            lse[j, h] = m + np.log(z)
+    return out, lse
+
+
+# --------------------------------------------------------------------------
+# whole path on a workload (the structure produced by workload.generate.build)
+# --------------------------------------------------------------------------
+@dataclass
+class RequestResult:
+    k_shifted: np.ndarray        # [n_ctx, Hkv, d] after shift, before fix (question rows = 0)
+    k_ctx: np.ndarray            # [n_ctx, Hkv, d] after fix
+    v_ctx: np.ndarray            # [n_ctx, Hkv, d] after fix
+    scores: List[np.ndarray]     # per chunk segment, [n_c]
+    selected: List[np.ndarray]   # per chunk segment, ascending indices within the chunk
+    q_pos: np.ndarray            # [n_q] logical positions of the compact query list
+    q_row: np.ndarray            # [n_q] rows of q / k_new / v_new
+    out: np.ndarray              # [n_q, Hq, d]
+    lse: np.ndarray              # [n_q, Hq]
+
+
+def _segments_of(w, r):
+    s0, s1 = int(w.req_seg_off[r]), int(w.req_seg_off[r + 1])
+    return [tuple(int(v) for v in w.segments[i]) for i in range(s0, s1)]
+
+
+def shifted_context(w, r: int):
+    """Steps gather + shift for request r: logical K (shifted), V, context length."""
+    theta = w.spec.rope_theta
+    segs = _segments_of(w, r)
+    n_ctx = segs[-1][2] + segs[-1][3] if segs else 0
+    hkv, d = w.spec.n_kv_heads, w.spec.head_dim
+    k = np.zeros((n_ctx, hkv, d), dtype=np.float64)
+    v = np.zeros((n_ctx, hkv, d), dtype=np.float64)
+    by_dst = {int(dsc[1]): dsc for dsc in w.shift_descs}
+    for (_, kind, start, n, tab, _, _, _) in segs:
+        if kind != 0:
+            continue
+        src_tab, _, n_tok, delta = (int(x) for x in by_dst[tab])
+        assert n_tok == n
+        blocks = w.store_tab[src_tab: src_tab + (n + BLOCK - 1) // BLOCK]
+        k[start:start + n] = shift_keys(read_k_pages(w.k_store, blocks, n), delta, theta)
+        v[start:start + n] = read_v_pages(w.v_store, blocks, n)
+    return k, v, n_ctx
+
+
+def score_request(w, r: int, k_shifted: np.ndarray, only_segments: Optional[Sequence[int]] = None):
+    """Step score: per chunk segment of request r, mean-over-heads prior-chunk mass of each token."""
+    theta = w.spec.rope_theta
+    scores = []
+    for si, (_, kind, start, n, _, _, tok, _) in enumerate(_segments_of(w, r)):
+        if kind != 0:
+            continue
+        if only_segments is not None and si not in only_segments:
+            scores.append(None)
+            continue
+        if start == 0:
+            scores.append(np.zeros(n, dtype=np.float64))     # first chunk: no prior chunk
+            continue
+        pos = start + np.arange(n, dtype=np.int64)
+        q_rot = rotate(np.asarray(w.q[tok:tok + n], dtype=np.float64), pos, theta)
+        scores.append(prior_mass(q_rot, k_shifted, pos, start).mean(axis=1))
+    return scores
+
+
+def query_list(w, r: int, selected: Sequence[np.ndarray]):
+    """Compact query list of request r: selected tokens chunk by chunk, then the question."""
+    q_pos, q_row, ci = [], [], 0
+    for (_, kind, start, n, _, _, tok, _) in _segments_of(w, r):
+        idx = np.arange(n, dtype=np.int64) if kind != 0 else np.asarray(selected[ci], dtype=np.int64)
+        ci += kind == 0
+        q_pos.append(start + idx)
+        q_row.append(tok + idx)
+    cat = lambda xs: np.concatenate(xs) if xs else np.zeros(0, dtype=np.int64)
+    return cat(q_pos), cat(q_row)
+
+
+def fix_and_attend(w, r: int, k_shifted, v_cached, selected, k_new=None, v_new=None, q=None,
+                   only_queries: Optional[np.ndarray] = None):
+    """Steps fix + attend for request r given the chosen token sets."""
+    theta = w.spec.rope_theta
+    k_new = w.k_new if k_new is None else k_new
+    v_new = w.v_new if v_new is None else v_new
+    q = w.q if q is None else q
+    q_pos, q_row = query_list(w, r, selected)
+    k_ctx, v_ctx = k_shifted.copy(), v_cached.copy()
+    if len(q_pos):
+        k_ctx[q_pos] = rotate(np.asarray(k_new[q_row], dtype=np.float64), q_pos, theta)
+        v_ctx[q_pos] = np.asarray(v_new[q_row], dtype=np.float64)
+    which = np.arange(len(q_pos)) if only_queries is None else np.asarray(only_queries, dtype=np.int64)
+    q_rot = rotate(np.asarray(q[q_row[which]], dtype=np.float64), q_pos[which], theta)
+    out, lse = causal_attention_rows(q_rot, q_pos[which], k_ctx, v_ctx)
+    return k_ctx, v_ctx, q_pos, q_row, out, lse
+
+
+def run_request(w, r: int, selected_override: Optional[Sequence[np.ndarray]] = None,
+                k_new=None, v_new=None, q=None) -> RequestResult:
+    k_sh, v_c, _ = shifted_context(w, r)
+    scores = score_request(w, r, k_sh)
+    chunk_segs = [s for s in _segments_of(w, r) if s[1] == 0]
+    selected = [top_n(sc, seg[5]) for sc, seg in zip(scores, chunk_segs)]
+    if selected_override is not None:
+        selected = [np.asarray(s, dtype=np.int64) for s in selected_override]
+    k_ctx, v_ctx, q_pos, q_row, out, lse = fix_and_attend(w, r, k_sh, v_c, selected, k_new, v_new, q)
+    return RequestResult(k_sh, k_ctx, v_ctx, scores, selected, q_pos, q_row, out, lse)
+
+
+def run(w, selected_override: Optional[Dict[int, Sequence[np.ndarray]]] = None) -> List[RequestResult]:
+    """Whole path over every request of the batch (requests are independent)."""
+    return [run_request(w, r, None if selected_override is None else selected_override.get(r))
+            for r in range(w.n_requests)]
+
+
+def qkv_project(hidden_rows: np.ndarray, w_qkv: np.ndarray, hq: int, hkv: int, d: int):
+    """Q, K, V of the given token rows: X W, split by heads (Sec. 3.4.3: computed only for
+    the recomputation and question tokens).  Returns q [n,Hq,d], k [n,Hkv,d], v [n,Hkv,d]."""
+    y = np.asarray(hidden_rows, dtype=np.float64) @ np.asarray(w_qkv, dtype=np.float64)
+    n = y.shape[0]
+    q = y[:, : hq * d].reshape(n, hq, d)
+    k = y[:, hq * d: (hq + hkv) * d].reshape(n, hkv, d)
+    v = y[:, (hq + hkv) * d:].reshape(n, hkv, d)
+    return q, k, v

@@ -1,0 +1,350 @@
+"""Pins for the CPU oracle: closed forms, invariants, limiting cases, library routines, brute force.
+
+Each test fixes the oracle to something other than itself, so that a dropped term, a wrong
+sign or index, or a transposed operand anywhere in oracle/cachecraft_oracle.py fails here.
+The paper prints no worked numeric example of this path, so the pins are mathematical:
+the textbook rotary embedding (cited in Sec. 2.1), the per-token causal attention of Sec. 2.1,
+the block structure of inter/intra attention (Eq. (2), Eq. (3) and the matrix below them),
+and the selection rule of Eq. (10).
+"""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import workload as W
+from oracle import cachecraft_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ----------------------------------------------------------------------------- independent helpers
+def rope_complex(x, pos, theta):
+    """Textbook rotary embedding written with complex numbers: (x_i + i y_i) * exp(i pos w_i)."""
+    x = np.asarray(x, dtype=np.float64)
+    d = x.shape[-1]
+    h = d // 2
+    w = np.array([theta ** (-(2.0 * i) / d) for i in range(h)])
+    z = (x[..., :h] + 1j * x[..., h:]) * np.exp(1j * np.asarray(pos, dtype=np.float64)[:, None, None] * w)
+    return np.concatenate([z.real, z.imag], axis=-1)
+
+
+def dense_causal_gqa(q_rot, k_rot, v, lib=True):
+    """Full causal GQA attention over a whole prompt, via torch's library routine (fp64, CPU)."""
+    n, hq, d = q_rot.shape
+    hkv = k_rot.shape[1]
+    g = hq // hkv
+    qt = torch.from_numpy(q_rot).permute(1, 0, 2)[None]                 # [1,Hq,n,d]
+    kt = torch.from_numpy(np.repeat(k_rot, g, axis=1)).permute(1, 0, 2)[None]
+    vt = torch.from_numpy(np.repeat(v, g, axis=1)).permute(1, 0, 2)[None]
+    o = torch.nn.functional.scaled_dot_product_attention(qt, kt, vt, is_causal=True)
+    return o[0].permute(1, 0, 2).numpy()
+
+
+def attention_matrix(q_rot, k_rot):
+    """Dense [Hq, n, n] causal softmax weights of Eq. (1), for block-sum checks."""
+    n, hq, d = q_rot.shape
+    g = hq // k_rot.shape[1]
+    a = np.zeros((hq, n, n))
+    for h in range(hq):
+        s = q_rot[:, h] @ k_rot[:, h // g].T / math.sqrt(d)
+        s[np.triu_indices(n, 1)] = -np.inf
+        a[h] = torch.softmax(torch.from_numpy(s), dim=-1).numpy()
+    return a
+
+
+def small_workload(fracs=(0.25, 0.25, 0.25), lens=(20, 33, 16), question=5, offsets=(0, 0, 0),
+                   order=(0, 1, 2), dtype="f32", Hq=4, Hkv=2, d=16, theta=1.0e4, scale=1.0, seed=11):
+    req = W.RequestSpec(list(order), list(fracs), question)
+    return W.custom("pin", dtype, Hq, Hkv, d, theta, lens, offsets, [req], scale, seed)
+
+
+# ----------------------------------------------------------------------------- rotation (shift)
+def test_rotate_matches_textbook_complex_form():
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((7, 3, 32))
+    pos = np.array([0, 1, 5, 17, 1000, 31999, -40])
+    np.testing.assert_allclose(O.rotate(x, pos, 5.0e5), rope_complex(x, pos, 5.0e5), rtol=0, atol=1e-12)
+
+
+def test_rotate_one_hot_closed_form():
+    d, theta, p = 64, 1.0e4, 37
+    for i in (0, 1, 13, 31):
+        k = np.zeros((1, 1, d)); k[0, 0, i] = 1.0
+        r = O.rotate(k, np.array([p]), theta)[0, 0]
+        phi = p * theta ** (-2.0 * i / d)
+        expect = np.zeros(d); expect[i] = math.cos(phi); expect[i + d // 2] = math.sin(phi)
+        np.testing.assert_allclose(r, expect, atol=1e-15)
+        k = np.zeros((1, 1, d)); k[0, 0, i + d // 2] = 1.0         # y component: (-sin, cos)
+        r = O.rotate(k, np.array([p]), theta)[0, 0]
+        expect = np.zeros(d); expect[i] = -math.sin(phi); expect[i + d // 2] = math.cos(phi)
+        np.testing.assert_allclose(r, expect, atol=1e-15)
+
+
+def test_shift_composes_and_inverts():
+    rng = np.random.default_rng(1)
+    k = rng.standard_normal((9, 2, 128))
+    a, b = 1536, -411
+    ab = O.shift_keys(O.shift_keys(k, a, 5.0e5), b, 5.0e5)
+    np.testing.assert_allclose(ab, O.shift_keys(k, a + b, 5.0e5), atol=1e-12)
+    np.testing.assert_allclose(O.shift_keys(O.shift_keys(k, a, 5.0e5), -a, 5.0e5), k, atol=1e-12)
+    assert np.array_equal(O.shift_keys(k, 0, 5.0e5), k)             # zero shift is bit-exact
+
+
+def test_shift_preserves_pair_norms():
+    rng = np.random.default_rng(2)
+    k = rng.standard_normal((5, 2, 64))
+    s = O.shift_keys(k, 777, 1.0e4)
+    n0 = k[..., :32] ** 2 + k[..., 32:] ** 2
+    n1 = s[..., :32] ** 2 + s[..., 32:] ** 2
+    np.testing.assert_allclose(n1, n0, rtol=1e-13)
+
+
+def test_rotation_gives_relative_position_logits():
+    rng = np.random.default_rng(3)
+    q = rng.standard_normal((1, 1, 64)); k = rng.standard_normal((1, 1, 64))
+    base = None
+    for p, s in ((10, 3), (107, 100), (5007, 5000)):
+        v = float(O.rotate(q, np.array([p]), 1.0e4)[0, 0] @ O.rotate(k, np.array([s]), 1.0e4)[0, 0])
+        base = v if base is None else base
+        assert abs(v - base) < 1e-10
+    # and it does depend on the distance
+    v2 = float(O.rotate(q, np.array([10]), 1.0e4)[0, 0] @ O.rotate(k, np.array([4]), 1.0e4)[0, 0])
+    assert abs(v2 - base) > 1e-3
+
+
+# ----------------------------------------------------------------------------- paged pool readers
+def test_page_readers_follow_the_two_layouts():
+    hkv, d = 2, 8
+    kp = np.arange(3 * hkv * 16 * d, dtype=np.float64).reshape(3, hkv, 16, d)
+    vp = np.arange(3 * hkv * d * 16, dtype=np.float64).reshape(3, hkv, d, 16)
+    k = O.read_k_pages(kp, [2, 0], 21)
+    v = O.read_v_pages(vp, [2, 0], 21)
+    assert k.shape == v.shape == (21, hkv, d)
+    for t, (blk, slot) in {0: (2, 0), 15: (2, 15), 16: (0, 0), 20: (0, 4)}.items():
+        for h in range(hkv):
+            for c in range(d):
+                assert k[t, h, c] == kp[blk, h, slot, c]
+                assert v[t, h, c] == vp[blk, h, c, slot]
+
+
+# ----------------------------------------------------------------------------- scoring
+def test_score_uniform_softmax_closed_form():
+    w = small_workload()
+    w.q[:] = 0.0                                                     # all logits equal -> uniform rows
+    k_sh, _, _ = O.shifted_context(w, 0)
+    sc = O.score_request(w, 0, k_sh)
+    assert np.array_equal(sc[0], np.zeros(20))                       # first chunk has no prior chunk
+    for c, (start, n) in enumerate(((20, 33), (53, 16)), start=1):
+        t = np.arange(n)
+        np.testing.assert_allclose(sc[c], start / (start + t + 1.0), rtol=1e-13)
+
+
+def test_score_bruteforce_and_complement():
+    w = small_workload(lens=(6, 9, 7), question=3, d=8)
+    k_sh, _, _ = O.shifted_context(w, 0)
+    sc = O.score_request(w, 0, k_sh)
+    hq, hkv, d, theta = 4, 2, 8, 1.0e4
+    starts = (0, 6, 15)
+    for c, n in enumerate((6, 9, 7)):
+        for t in range(n):
+            p = starts[c] + t
+            tot = 0.0
+            for h in range(hq):
+                qv = rope_complex(w.q[p][None].astype(np.float64), [p], theta)[0, h]
+                logit = [sum(qv[e] * k_sh[l, h // 2, e] for e in range(d)) / math.sqrt(d) for l in range(p + 1)]
+                mx = max(logit)
+                ex = [math.exp(v - mx) for v in logit]
+                prior = sum(ex[: starts[c]]) / sum(ex)
+                own = sum(ex[starts[c]:]) / sum(ex)
+                assert abs(prior + own - 1.0) < 1e-14
+                tot += prior
+            assert 0.0 <= sc[c][t] <= 1.0
+            assert abs(sc[c][t] - tot / hq) < 1e-13
+
+
+def test_score_block_sums_equal_inter_attention():
+    # sum over the tokens of C_i of the per-token mass == sum_{j<i} inter(C_j, C_i)  (Eq. (2), block matrix)
+    w = small_workload(lens=(12, 10, 14), question=4)
+    k_sh, _, n_ctx = O.shifted_context(w, 0)
+    pos = np.arange(40)                                              # chunk tokens only (question keys come later)
+    q_rot = rope_complex(w.q[:36].astype(np.float64), pos[:36], 1.0e4)
+    a = attention_matrix(q_rot, k_sh[:36])                           # [Hq, 36, 36]
+    sc = O.score_request(w, 0, k_sh)
+    bounds = [(0, 12), (12, 22), (22, 36)]
+    for i, (s0, s1) in enumerate(bounds):
+        inter_sum = sum(a[:, s0:s1, b0:b1].sum(axis=(1, 2)) for (b0, b1) in bounds[:i]) if i else np.zeros(4)
+        np.testing.assert_allclose(sc[i].sum(), np.mean(inter_sum), atol=1e-12)
+
+
+def test_score_goes_to_one_with_a_dominant_prior_key():
+    w = small_workload(lens=(8, 8, 8), question=2, d=16, theta=1.0e4)
+    k_sh, _, _ = O.shifted_context(w, 0)
+    # make key 3 (in chunk 0) line up with every query of chunk 2 at huge magnitude, un-rotated frame
+    pos = 16 + np.arange(8)
+    q_rot = O.rotate(w.q[16:24].astype(np.float64), pos, 1.0e4)
+    k_sh[3] = 0.0
+    k_sh[3, :, :] = 200.0 * np.sign(q_rot[4, 0, :])                  # aligns with token 4, head 0
+    m = O.prior_mass(q_rot, k_sh, pos, 16)
+    assert m[4, 0] > 1.0 - 1e-9
+
+
+# ----------------------------------------------------------------------------- selection
+def test_top_n_against_full_sort_and_edges():
+    rng = np.random.default_rng(5)
+    for n, k in ((1, 1), (17, 5), (64, 13), (100, 0), (100, 100)):
+        s = rng.random(n)
+        got = O.top_n(s, k)
+        expect = sorted(sorted(range(n), key=lambda i: (-s[i], i))[:k])
+        assert list(got) == expect
+    assert list(O.top_n(np.array([0.0, 0.0, 0.0, 0.0]), 2)) == [0, 1]          # ties: lower index wins
+    assert list(O.top_n(np.array([0.1, 0.5, 0.5, 0.2]), 1)) == [1]
+    assert list(O.top_n(np.arange(10.0), 3)) == [7, 8, 9]                        # monotone -> the tail
+    assert list(O.top_n(-np.arange(10.0), 3)) == [0, 1, 2]
+
+
+def test_token_budget_rule():
+    facts = json.load(open(os.path.join(GOLDEN, "paper_storage_facts.json")))
+    assert facts["block_tokens"]["value"] == W.BLOCK == O.BLOCK
+    # N = ceil(f |C|), robust to fp noise: 0.07*100 must give 7, not 8
+    assert W.n_select_for(0.07, 100) == 7
+    assert [W.n_select_for(f, n) for f, n in ((0.2, 64), (0.15, 512), (0.10, 1024), (0.10, 1000))] == [13, 77, 103, 100]
+    assert W.n_select_for(0.0, 50) == 0 and W.n_select_for(1.0, 50) == 50
+    # storage facts: bytes per token, all layers, K+V, 16-bit
+    for name, f in facts["kv_mb_per_token"].items():
+        mib = f["layers"] * f["kv_heads"] * f["head_dim"] * 2 * 2 / 2 ** 20
+        assert abs(mib - f["value"]) / f["value"] < 0.3
+
+
+# ----------------------------------------------------------------------------- fix + attend
+def full_prefill_reference(w, theta):
+    n = w.n_tok
+    pos = np.arange(n)
+    q = rope_complex(w.q.astype(np.float64), pos, theta)
+    k = rope_complex(w.k_new.astype(np.float64), pos, theta)
+    return dense_causal_gqa(q, k, w.v_new.astype(np.float64)), k
+
+
+def test_full_recompute_equals_full_causal_prefill():
+    w = small_workload(fracs=(1.0, 1.0, 1.0), lens=(20, 33, 16), question=5, offsets=(0, 7, 3))
+    res = O.run_request(w, 0)
+    ref, k_ref = full_prefill_reference(w, 1.0e4)
+    assert np.array_equal(res.q_pos, np.arange(w.n_tok))
+    np.testing.assert_allclose(res.out, ref, atol=1e-12)
+    np.testing.assert_allclose(res.k_ctx, k_ref, atol=1e-12)
+    np.testing.assert_allclose(res.v_ctx, w.v_new, atol=0)
+
+
+def test_zero_recompute_at_cached_offsets_leaves_cache_unchanged():
+    lens = (32, 16, 48)
+    w = small_workload(fracs=(0.0, 0.0, 0.0), lens=lens, question=6, offsets=(0, 32, 48), order=(0, 1, 2))
+    assert np.all(w.shift_descs[:, W.SHIFT_DELTA] == 0)
+    res = O.run_request(w, 0)
+    n_chunk = sum(lens)
+    # cached rows come back bit-exact
+    for c in range(3):
+        blocks = w.store_tab[w.store_tab_off[c]: w.store_tab_off[c + 1]]
+        s = int(w.segments[c][W.SEG_START])
+        assert np.array_equal(res.k_ctx[s:s + lens[c]], O.read_k_pages(w.k_store, blocks, lens[c]))
+        assert np.array_equal(res.v_ctx[s:s + lens[c]], O.read_v_pages(w.v_store, blocks, lens[c]))
+    # only question tokens are queries; they equal plain attention of the question over cache + question
+    assert np.array_equal(res.q_pos, n_chunk + np.arange(6))
+    k_all = res.k_ctx.copy(); v_all = res.v_ctx.copy()
+    q_full = np.zeros((w.n_tok, 4, 16))
+    q_full[n_chunk:] = rope_complex(w.q[n_chunk:].astype(np.float64), res.q_pos, 1.0e4)
+    ref = dense_causal_gqa(q_full, k_all, v_all)[n_chunk:]
+    np.testing.assert_allclose(res.out, ref, atol=1e-12)
+
+
+def test_attention_invariant_to_a_global_position_offset():
+    base = small_workload(offsets=(0, 0, 0))
+    k_sh, v_c, _ = O.shifted_context(base, 0)
+    sel = [np.array([1, 5, 6]), np.array([0, 9, 30]), np.array([2, 3])]
+    _, _, q_pos, q_row, out0, lse0 = O.fix_and_attend(base, 0, k_sh, v_c, sel)
+    # same data, every position (cached keys, new keys, queries) moved by +1000
+    off = 1000
+    theta = base.spec.rope_theta
+    k2 = O.rotate(k_sh, np.full(k_sh.shape[0], off), theta)
+    k_ctx = k2.copy(); v_ctx = v_c.copy()
+    k_ctx[q_pos] = O.rotate(base.k_new[q_row].astype(np.float64), q_pos + off, theta)
+    v_ctx[q_pos] = base.v_new[q_row]
+    q_rot = O.rotate(base.q[q_row].astype(np.float64), q_pos + off, theta)
+    out1, lse1 = O.causal_attention_rows(q_rot, q_pos, k_ctx, v_ctx)
+    np.testing.assert_allclose(out1, out0, atol=1e-10)
+    np.testing.assert_allclose(lse1, lse0, atol=1e-10)
+
+
+def test_zero_queries_average_the_values_and_lse_is_log_count():
+    w = small_workload()
+    w.q[:] = 0.0
+    k_sh, v_c, _ = O.shifted_context(w, 0)
+    sel = [np.array([0, 19]), np.array([4]), np.array([], dtype=np.int64)]
+    k_ctx, v_ctx, q_pos, _, out, lse = O.fix_and_attend(w, 0, k_sh, v_c, sel)
+    for j, p in enumerate(q_pos):
+        for h in range(4):
+            np.testing.assert_allclose(out[j, h], v_ctx[: p + 1, h // 2].mean(axis=0), atol=1e-13)
+            assert abs(lse[j, h] - math.log(p + 1)) < 1e-13
+
+
+def test_attention_bruteforce_scalar_loops_and_visibility_of_fixed_rows():
+    w = W.config(1)                                                   # the tiny benchmark config
+    res = O.run_request(w, 0)
+    hq, hkv, d = 4, 2, 64
+    assert res.out.shape == (55, hq, d)
+    rng = np.random.default_rng(9)
+    for j in rng.choice(55, size=6, replace=False):
+        p = int(res.q_pos[j]); h = int(rng.integers(hq))
+        qv = rope_complex(w.q[res.q_row[j]][None].astype(np.float64), [p], 1.0e4)[0, h]
+        logits = []
+        for l in range(p + 1):
+            logits.append(sum(float(qv[e]) * float(res.k_ctx[l, h // 2, e]) for e in range(d)) / math.sqrt(d))
+        mx = max(logits); z = sum(math.exp(v - mx) for v in logits)
+        o = [sum(math.exp(logits[l] - mx) / z * float(res.v_ctx[l, h // 2, e]) for l in range(p + 1)) for e in range(d)]
+        np.testing.assert_allclose(res.out[j, h], o, atol=1e-12)
+        assert abs(res.lse[j, h] - (mx + math.log(z))) < 1e-12
+    # fixed rows are the recomputed ones, stale rows are the shifted cache
+    is_q = np.zeros(208, dtype=bool); is_q[res.q_pos] = True
+    assert np.array_equal(res.k_ctx[~is_q], res.k_shifted[~is_q])
+    np.testing.assert_allclose(res.k_ctx[is_q], rope_complex(w.k_new[res.q_row].astype(np.float64), res.q_pos, 1.0e4), atol=1e-12)
+    assert np.array_equal(res.v_ctx[is_q], w.v_new[res.q_row].astype(np.float64))
+    # 13 of 64 per chunk, first chunk takes its first 13 (all scores zero)
+    assert [len(s) for s in res.selected] == [13, 13, 13]
+    assert list(res.selected[0]) == list(range(13))
+
+
+def test_query_row_order_does_not_matter():
+    w = small_workload()
+    k_sh, v_c, _ = O.shifted_context(w, 0)
+    sel = [np.array([1, 5]), np.array([0, 9, 30]), np.array([2])]
+    k_ctx, v_ctx, q_pos, q_row, out, lse = O.fix_and_attend(w, 0, k_sh, v_c, sel)
+    perm = np.random.default_rng(4).permutation(len(q_pos))
+    q_rot = O.rotate(w.q[q_row[perm]].astype(np.float64), q_pos[perm], 1.0e4)
+    out_p, lse_p = O.causal_attention_rows(q_rot, q_pos[perm], k_ctx, v_ctx)
+    np.testing.assert_allclose(out_p, out[perm], atol=1e-14)
+    np.testing.assert_allclose(lse_p, lse[perm], atol=1e-14)
+
+
+def test_padding_slots_are_never_keys():
+    # chunk lengths that are not multiples of 16: poison the padding slots of the store
+    w = small_workload(lens=(20, 33, 17), question=5)
+    res0 = O.run_request(w, 0)
+    for c, n in enumerate((20, 33, 17)):
+        last = int(w.store_tab[w.store_tab_off[c + 1] - 1])
+        w.k_store[last, :, n % 16:, :] = 1.0e6
+        w.v_store[last, :, :, n % 16:] = -1.0e6
+    res1 = O.run_request(w, 0)
+    assert np.array_equal(res0.out, res1.out)
+    assert all(np.array_equal(a, b) for a, b in zip(res0.scores, res1.scores))
+
+
+def test_qkv_projection_splits_heads_in_q_k_v_order():
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal((3, 8)); wq = rng.standard_normal((8, (4 + 2 * 2) * 4))
+    q, k, v = O.qkv_project(x, wq, 4, 2, 4)
+    y = torch.from_numpy(x) @ torch.from_numpy(wq)
+    np.testing.assert_allclose(q[1, 2], y[1, 8:12].numpy(), atol=1e-13)
+    np.testing.assert_allclose(k[2, 1], y[2, 16 + 4:16 + 8].numpy(), atol=1e-13)
+    np.testing.assert_allclose(v[0, 0], y[0, 24:28].numpy(), atol=1e-13)
