@@ -1,0 +1,180 @@
+/*
+ * libcachecraft -- selective KV recomputation for reused RAG chunk-caches on MI355X (gfx950).
+ *
+ * C ABI of the data-parallel hot path of Cache-Craft for ONE attention layer and one batch of
+ * prompts S = C_1 .. C_k U (cached chunks followed by the question, Sec. 2.2):
+ *
+ *   cc_rope_shift      re-position cached keys (Sec. 3.4.3, Sec. 4 "RPE Management")
+ *   cc_select          score chunk tokens by attention mass on prior chunks, keep the top N
+ *                      (Eq. (2), Eq. (10), Sec. 3.2.1)
+ *   cc_gather_rows     compact the rows of the chosen tokens
+ *   cc_qkv_project     Q, K, V of the chosen tokens only (Sec. 3.4.3)
+ *   cc_sparse_prefill  causal attention of the chosen tokens + question over the whole merged
+ *                      paged KV, after writing their recomputed K, V into it
+ *                      (Eq. (1), Sec. 3.4.3, Sec. 4 "Selective Token Recomputation")
+ *
+ * Conventions
+ *   - Every tensor and every metadata array is DEVICE memory owned by the caller; the library
+ *     never allocates, frees or synchronises.  Scratch comes from a caller-supplied workspace
+ *     whose size the matching *_workspace_bytes() call returns.  Pointers must be 16-byte aligned.
+ *   - Every call only enqueues kernels on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and returns.  Arguments that are visible from host scalars are checked
+ *     before any launch; on error nothing is enqueued and nothing is written.
+ *   - Return value: CC_OK (0) or a negative cc_status.  cc_last_error(ctx) gives a message.
+ *   - Element type `dtype`: CC_F32 (float) or CC_BF16 (bfloat16 storage, fp32 accumulation).
+ *   - Paged KV, 16-token blocks (Sec. 4 "Chunk Storage Management"); chunks are padded to whole
+ *     blocks and the padding slots are never read as keys and never written:
+ *         K pool  [n_blocks][Hkv][16][d]     token-major rows of d elements
+ *         V pool  [n_blocks][Hkv][d][16]     dimension-major rows of 16 token slots
+ *   - Rotary embedding: pair i of a head is (v[i], v[i + d/2]), i in [0, d/2), frequency
+ *     theta^(-2i/d); a rotation by angle phi maps (x, y) to (x cos phi - y sin phi,
+ *     y cos phi + x sin phi)  (Sec. 4 "RPE Management").
+ *   - Grouped-query attention: query head h reads KV head h / (Hq / Hkv).
+ *   - Logits are q.k / sqrt(d); a token at logical position p sees keys at positions <= p of its
+ *     own request (per-token form of Eq. (1), Sec. 2.1).
+ */
+#ifndef CACHECRAFT_CC_H
+#define CACHECRAFT_CC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cc_ctx cc_ctx;
+
+typedef enum {
+  CC_OK = 0,
+  CC_ERR_INVALID_ARG = -1,          /* null / misaligned pointer, negative or inconsistent size */
+  CC_ERR_UNSUPPORTED = -2,          /* dtype, head_dim, block size or head grouping not built    */
+  CC_ERR_WORKSPACE_TOO_SMALL = -3,
+  CC_ERR_HIP = -4                   /* a HIP runtime call failed; see cc_last_error              */
+} cc_status;
+
+enum { CC_F32 = 0, CC_BF16 = 1 };
+enum { CC_SEG_CHUNK = 0, CC_SEG_QUESTION = 1 };
+enum { CC_IMPL_AUTO = 0, CC_IMPL_SCALAR = 1 };   /* cc_set_impl: AUTO uses the MFMA kernels where built */
+
+typedef struct {
+  int32_t n_q_heads;     /* Hq                                   */
+  int32_t n_kv_heads;    /* Hkv, divides Hq                      */
+  int32_t head_dim;      /* d: 64 or 128                         */
+  int32_t block_size;    /* tokens per KV block: 16              */
+  int32_t dtype;         /* CC_F32 | CC_BF16                     */
+  int32_t reserved;      /* 0                                    */
+  double  rope_theta;    /* rotary base, e.g. 10000 or 500000    */
+} cc_config;
+
+/* One cached chunk placed into one request (a chunk *instance*).  Sec. 3: the chunk-cache is the
+ * per-layer (K_C, V_C) of the chunk's tokens; Sec. 4: it maps to a list of 16-token blocks. */
+typedef struct {
+  int32_t src_tab_off;   /* index into src_block_tab of the instance's first block (shared store) */
+  int32_t dst_tab_off;   /* index into dst_block_tab of its first request-owned block             */
+  int32_t n_tokens;      /* chunk length |C|; occupies ceil(n_tokens/16) blocks                   */
+  int32_t delta_pos;     /* new position of token 0 minus the position it was cached at           */
+} cc_shift_desc;
+
+/* One segment of a prompt, in prompt order: a cached chunk instance or the question. */
+typedef struct {
+  int32_t req;           /* request index                                                          */
+  int32_t kind;          /* CC_SEG_CHUNK | CC_SEG_QUESTION                                         */
+  int32_t logical_start; /* position of the segment's first token in its prompt (padding excluded) */
+  int32_t n_tokens;
+  int32_t tab_off;       /* index into block_tab of the segment's first request-owned block        */
+  int32_t n_select;      /* chunk: N tokens to recompute (0..n_tokens); question: n_tokens         */
+  int32_t tok_off;       /* row of the segment's first token in per-token tensors (q, scores)      */
+  int32_t sel_off;       /* position of the segment's first entry in the compact query list        */
+} cc_segment;
+
+/* ---- context ----------------------------------------------------------------------------- */
+/* Validates cfg and creates a context (host memory only).  *out is NULL on error. */
+int cc_create(cc_ctx** out, const cc_config* cfg);
+void cc_destroy(cc_ctx* ctx);
+const char* cc_status_string(int status);
+/* Message of the last failing call on this context (valid until the next call on it). */
+const char* cc_last_error(const cc_ctx* ctx);
+/* Kernel family used by cc_select / cc_sparse_prefill / cc_qkv_project: CC_IMPL_AUTO (default)
+ * picks the MFMA kernels for bf16 with head_dim 128, CC_IMPL_SCALAR forces the plain ones. */
+int cc_set_impl(cc_ctx* ctx, int impl);
+
+/* ---- (a) re-position cached keys ----------------------------------------------------------
+ * For every instance i and token t < n_tokens, every KV head: read the key from the shared
+ * store (block src_block_tab[src_tab_off + t/16], slot t%16), rotate every pair by
+ * delta_pos * theta^(-2i/d), write it to block dst_block_tab[dst_tab_off + t/16], slot t%16 of
+ * the destination pool.  If v_src_pool and v_dst_pool are non-NULL the instance's V blocks are
+ * copied whole (values carry no position).  Source pools are never written.  Source and
+ * destination may be the same allocation as long as the block ids differ.
+ *   descs [n_instances] device; block tables device int32; max_tokens = max n_tokens (host).
+ *   n_src_blocks / n_dst_blocks: pool sizes in blocks; a table entry outside them is skipped.
+ * Sec. 3.4.3, Sec. 4 "RPE Management". */
+int cc_rope_shift(cc_ctx* ctx,
+                  const void* k_src_pool, const void* v_src_pool, int32_t n_src_blocks,
+                  void* k_dst_pool, void* v_dst_pool, int32_t n_dst_blocks,
+                  const int32_t* src_block_tab, const int32_t* dst_block_tab,
+                  const cc_shift_desc* descs, int32_t n_instances, int32_t max_tokens,
+                  void* stream);
+
+/* ---- (b) choose the tokens to recompute ---------------------------------------------------
+ * For every chunk segment with logical_start > 0 and every token t (position p = start + t):
+ *   mass_h(t) = sum over keys l < logical_start of softmax_{l <= p}(q_h(p).k_l / sqrt(d))
+ *   score(t)  = mean over query heads of mass_h(t)
+ * with q rotated to position p on load and k the (already shifted) keys of the request's pages.
+ * A chunk at logical_start 0 scores 0.  Per chunk the n_select largest scores win (lower index
+ * among equals) and are emitted in ascending index order.  Question segments emit all tokens.
+ * Outputs, all [n_q_tot] int32 laid out by seg.sel_off (any of q_row/q_pos/slot_map may be NULL):
+ *   sel_idx   index of the token inside its segment
+ *   q_row     seg.tok_off + index        (row in per-token tensors)
+ *   q_pos     seg.logical_start + index  (logical position)
+ *   slot_map  block_tab[seg.tab_off + index/16] * 16 + index%16  (physical KV slot)
+ * scores [n_tok] float (rows by tok_off; question rows untouched) or NULL.
+ *   q [n_tok][Hq][d] pre-rotation, read-only.  segs [n_segs], req_seg_off [n_requests+1] device.
+ *   max_seg_tokens: max n_tokens over segments (host scalar, sizes the launch).
+ * Eq. (2), block matrix below Eq. (3), Eq. (10), Sec. 3.2.1. */
+size_t cc_select_workspace_bytes(const cc_ctx* ctx, int32_t n_tok, int32_t n_segs);
+int cc_select(cc_ctx* ctx, const void* q, int32_t n_tok,
+              const void* k_pool, int32_t n_blocks, const int32_t* block_tab,
+              const cc_segment* segs, int32_t n_segs,
+              const int32_t* req_seg_off, int32_t n_requests, int32_t max_seg_tokens,
+              int32_t* sel_idx, int32_t* q_row, int32_t* q_pos, int32_t* slot_map, int32_t n_q_tot,
+              float* scores, void* workspace, size_t workspace_bytes, void* stream);
+
+/* dst[i][:] = src[row_idx[i]][:] for i < n_rows; row_bytes a multiple of 16.  Compacts the rows
+ * of the chosen tokens (hidden states before the projection, or given q / k / v rows). */
+int cc_gather_rows(cc_ctx* ctx, const void* src, int32_t n_src_rows, const int32_t* row_idx,
+                   int32_t n_rows, size_t row_bytes, void* dst, void* stream);
+
+/* ---- Q, K, V of the chosen tokens ---------------------------------------------------------
+ * [q | k | v] = x W with x [n_rows][hidden], W [hidden][(Hq + 2 Hkv) d] row-major, columns
+ * ordered q heads, then k heads, then v heads; outputs q [n_rows][Hq][d], k, v [n_rows][Hkv][d].
+ * hidden must be a multiple of 64.  Sec. 3.4.3 (K, V and Q are computed only for new and
+ * recomputation tokens). */
+int cc_qkv_project(cc_ctx* ctx, const void* x, const void* w_qkv, int32_t n_rows, int32_t hidden,
+                   void* q, void* k, void* v, void* stream);
+
+/* ---- (c) partial prefill ------------------------------------------------------------------
+ * For every row j < n_q_tot of the compact query list (requests delimited by cu_q):
+ *   1. rotate k_new[j] to position q_pos[j] and write it, with v_new[j], into physical slot
+ *      slot_map[j] of the request-owned pools (inputs are not modified);
+ *   2. out[j][h] = softmax_{l <= q_pos[j]}(q'[j][h].k_l / sqrt(d)) v_l over all keys of the row's
+ *      request (stale shifted rows, fixed rows, question rows), with q' = q[j] rotated to
+ *      q_pos[j]; lse[j][h] = natural log of the softmax denominator.
+ * Step 2 of every row sees step 1 of every row.  Keys are enumerated through segs/block_tab;
+ * rows of one request must be contiguous, any order inside a request is accepted.
+ *   q [n_q_tot][Hq][d], k_new, v_new [n_q_tot][Hkv][d]; out like q; lse [n_q_tot][Hq] or NULL.
+ *   max_q_per_req: max rows of one request (host scalar, sizes the launch).
+ * Eq. (1), Sec. 3.4.3, Sec. 4 "Selective Token Recomputation". */
+size_t cc_sparse_prefill_workspace_bytes(const cc_ctx* ctx, int32_t n_q_tot, int32_t n_requests);
+int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void* v_new,
+                      const int32_t* q_pos, const int32_t* slot_map, const int32_t* cu_q,
+                      int32_t n_q_tot, int32_t max_q_per_req,
+                      void* k_pool, void* v_pool, int32_t n_blocks, const int32_t* block_tab,
+                      const cc_segment* segs, int32_t n_segs,
+                      const int32_t* req_seg_off, int32_t n_requests,
+                      void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CACHECRAFT_CC_H */

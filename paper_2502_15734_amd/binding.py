@@ -1,0 +1,159 @@
+"""ctypes binding of libcachecraft's C ABI (include/cc.h).  Same names, tensors in, tensors out.
+
+The library is loaded from this package directory (built in-tree by build.py); a missing library
+is a hard error -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+CC_F32, CC_BF16 = 0, 1
+CC_IMPL_AUTO, CC_IMPL_SCALAR = 0, 1
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB: Optional[C.CDLL] = None
+
+
+class CacheCraftError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"libcachecraft status {status}: {message}")
+        self.status = status
+
+
+class _Config(C.Structure):
+    _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("block_size", C.c_int32), ("dtype", C.c_int32), ("reserved", C.c_int32),
+                ("rope_theta", C.c_double)]
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "libcachecraft.so")
+
+
+def load_library() -> C.CDLL:
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -m paper_2502_15734_amd.build` "
+                          "(there is no CPU fallback)")
+    lib = C.CDLL(path)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    lib.cc_create.argtypes = [C.POINTER(vp), C.POINTER(_Config)]
+    lib.cc_create.restype = C.c_int
+    lib.cc_destroy.argtypes = [vp]
+    lib.cc_destroy.restype = None
+    lib.cc_status_string.argtypes = [C.c_int]
+    lib.cc_status_string.restype = C.c_char_p
+    lib.cc_last_error.argtypes = [vp]
+    lib.cc_last_error.restype = C.c_char_p
+    lib.cc_set_impl.argtypes = [vp, C.c_int]
+    lib.cc_set_impl.restype = C.c_int
+    lib.cc_rope_shift.argtypes = [vp, vp, vp, i32, vp, vp, i32, vp, vp, vp, i32, i32, vp]
+    lib.cc_rope_shift.restype = C.c_int
+    lib.cc_select_workspace_bytes.argtypes = [vp, i32, i32]
+    lib.cc_select_workspace_bytes.restype = sz
+    lib.cc_select.argtypes = [vp, vp, i32, vp, i32, vp, vp, i32, vp, i32, i32,
+                              vp, vp, vp, vp, i32, vp, vp, sz, vp]
+    lib.cc_select.restype = C.c_int
+    lib.cc_gather_rows.argtypes = [vp, vp, i32, vp, i32, sz, vp, vp]
+    lib.cc_gather_rows.restype = C.c_int
+    lib.cc_qkv_project.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp]
+    lib.cc_qkv_project.restype = C.c_int
+    lib.cc_sparse_prefill_workspace_bytes.argtypes = [vp, i32, i32]
+    lib.cc_sparse_prefill_workspace_bytes.restype = sz
+    lib.cc_sparse_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, vp, i32,
+                                      vp, i32, vp, vp, vp, sz, vp]
+    lib.cc_sparse_prefill.restype = C.c_int
+    _LIB = lib
+    return lib
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("libcachecraft takes contiguous tensors")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Context:
+    """cc_ctx handle.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, n_q_heads: int, n_kv_heads: int, head_dim: int, rope_theta: float,
+                 dtype: int, block_size: int = 16):
+        self._lib = load_library()
+        self._h = C.c_void_p()
+        cfg = _Config(n_q_heads, n_kv_heads, head_dim, block_size, dtype, 0, rope_theta)
+        st = self._lib.cc_create(C.byref(self._h), C.byref(cfg))
+        if st != 0:
+            raise CacheCraftError(st, self._lib.cc_status_string(st).decode())
+        self.n_q_heads, self.n_kv_heads, self.head_dim = n_q_heads, n_kv_heads, head_dim
+        self.dtype = dtype
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h:
+            self._lib.cc_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st: int):
+        if st != 0:
+            raise CacheCraftError(st, self._lib.cc_last_error(self._h).decode())
+
+    def set_impl(self, impl: int):
+        self._check(self._lib.cc_set_impl(self._h, impl))
+
+    # -- cc_rope_shift ---------------------------------------------------------------------
+    def rope_shift(self, k_src, v_src, k_dst, v_dst, src_tab, dst_tab, descs, n_instances, max_tokens):
+        self._check(self._lib.cc_rope_shift(
+            self._h, _ptr(k_src), _ptr(v_src), k_src.shape[0], _ptr(k_dst), _ptr(v_dst), k_dst.shape[0],
+            _ptr(src_tab), _ptr(dst_tab), _ptr(descs), n_instances, max_tokens, _stream()))
+
+    # -- cc_select ---------------------------------------------------------------------------
+    def select_workspace_bytes(self, n_tok: int, n_segs: int) -> int:
+        return int(self._lib.cc_select_workspace_bytes(self._h, n_tok, n_segs))
+
+    def select(self, q, k_pool, block_tab, segs, req_seg_off, n_requests, max_seg_tokens,
+               sel_idx, q_row, q_pos, slot_map, scores, workspace):
+        self._check(self._lib.cc_select(
+            self._h, _ptr(q), q.shape[0], _ptr(k_pool), k_pool.shape[0], _ptr(block_tab), _ptr(segs),
+            segs.shape[0], _ptr(req_seg_off), n_requests, max_seg_tokens, _ptr(sel_idx), _ptr(q_row),
+            _ptr(q_pos), _ptr(slot_map), sel_idx.shape[0], _ptr(scores), _ptr(workspace),
+            workspace.numel() * workspace.element_size(), _stream()))
+
+    # -- cc_gather_rows ----------------------------------------------------------------------
+    def gather_rows(self, src, row_idx, dst):
+        row_bytes = src[0].numel() * src.element_size()
+        self._check(self._lib.cc_gather_rows(self._h, _ptr(src), src.shape[0], _ptr(row_idx),
+                                             row_idx.shape[0], row_bytes, _ptr(dst), _stream()))
+
+    # -- cc_qkv_project ----------------------------------------------------------------------
+    def qkv_project(self, x, w_qkv, q, k, v):
+        self._check(self._lib.cc_qkv_project(self._h, _ptr(x), _ptr(w_qkv), x.shape[0], x.shape[1],
+                                             _ptr(q), _ptr(k), _ptr(v), _stream()))
+
+    # -- cc_sparse_prefill -------------------------------------------------------------------
+    def sparse_prefill_workspace_bytes(self, n_q_tot: int, n_requests: int) -> int:
+        return int(self._lib.cc_sparse_prefill_workspace_bytes(self._h, n_q_tot, n_requests))
+
+    def sparse_prefill(self, q, k_new, v_new, q_pos, slot_map, cu_q, max_q_per_req, k_pool, v_pool,
+                       block_tab, segs, req_seg_off, n_requests, out, lse, workspace):
+        self._check(self._lib.cc_sparse_prefill(
+            self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(q_pos), _ptr(slot_map), _ptr(cu_q),
+            q.shape[0], max_q_per_req, _ptr(k_pool), _ptr(v_pool), k_pool.shape[0], _ptr(block_tab),
+            _ptr(segs), segs.shape[0], _ptr(req_seg_off), n_requests, _ptr(out), _ptr(lse),
+            _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))

@@ -1,0 +1,205 @@
+// C ABI of libcachecraft: argument checks and kernel dispatch.  See include/cc.h.
+#include <cmath>
+#include <cstdio>
+#include <new>
+
+#include "common.h"
+
+namespace cc {
+
+int fail(cc_ctx* ctx, int status, const std::string& msg) {
+  if (ctx) ctx->last_error = msg;
+  return status;
+}
+
+int check_launch(cc_ctx* ctx, const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess)
+    return fail(ctx, CC_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+  return CC_OK;
+}
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace cc
+
+using cc::aligned16;
+using cc::fail;
+
+#define CC_REQUIRE(cond, msg)                                         \
+  do {                                                                \
+    if (!(cond)) return fail(ctx, CC_ERR_INVALID_ARG, std::string(fn) + ": " + (msg)); \
+  } while (0)
+
+extern "C" {
+
+const char* cc_status_string(int status) {
+  switch (status) {
+    case CC_OK: return "ok";
+    case CC_ERR_INVALID_ARG: return "invalid argument";
+    case CC_ERR_UNSUPPORTED: return "unsupported configuration";
+    case CC_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case CC_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int cc_create(cc_ctx** out, const cc_config* cfg) {
+  if (out == nullptr) return CC_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (cfg == nullptr) return CC_ERR_INVALID_ARG;
+  if (cfg->n_q_heads <= 0 || cfg->n_kv_heads <= 0 || cfg->n_q_heads % cfg->n_kv_heads != 0 ||
+      !(cfg->rope_theta > 0.0) || !std::isfinite(cfg->rope_theta))
+    return CC_ERR_INVALID_ARG;
+  if ((cfg->head_dim != 64 && cfg->head_dim != 128) || cfg->block_size != cc::kBlock ||
+      (cfg->dtype != CC_F32 && cfg->dtype != CC_BF16) || cfg->n_q_heads > 1024)
+    return CC_ERR_UNSUPPORTED;
+  cc_ctx* ctx = new (std::nothrow) cc_ctx();
+  if (ctx == nullptr) return CC_ERR_INVALID_ARG;
+  ctx->cfg = *cfg;
+  ctx->impl = CC_IMPL_AUTO;
+  const int half = cfg->head_dim / 2;
+  for (int i = 0; i < cc::kMaxHalf; ++i)
+    ctx->inv_freq.f[i] = i < half ? std::pow(cfg->rope_theta, -2.0 * i / cfg->head_dim) : 0.0;
+  *out = ctx;
+  return CC_OK;
+}
+
+void cc_destroy(cc_ctx* ctx) { delete ctx; }
+
+const char* cc_last_error(const cc_ctx* ctx) { return ctx ? ctx->last_error.c_str() : "null context"; }
+
+int cc_set_impl(cc_ctx* ctx, int impl) {
+  if (ctx == nullptr) return CC_ERR_INVALID_ARG;
+  if (impl != CC_IMPL_AUTO && impl != CC_IMPL_SCALAR)
+    return fail(ctx, CC_ERR_INVALID_ARG, "cc_set_impl: unknown implementation id");
+  ctx->impl = impl;
+  return CC_OK;
+}
+
+int cc_rope_shift(cc_ctx* ctx, const void* k_src_pool, const void* v_src_pool, int32_t n_src_blocks,
+                  void* k_dst_pool, void* v_dst_pool, int32_t n_dst_blocks,
+                  const int32_t* src_block_tab, const int32_t* dst_block_tab,
+                  const cc_shift_desc* descs, int32_t n_instances, int32_t max_tokens,
+                  void* stream) {
+  static const char* fn = "cc_rope_shift";
+  if (ctx == nullptr) return CC_ERR_INVALID_ARG;
+  CC_REQUIRE(n_instances >= 0 && max_tokens >= 0, "negative count");
+  CC_REQUIRE(n_instances <= 65535, "more than 65535 chunk instances in one call");
+  if (n_instances == 0 || max_tokens == 0) return CC_OK;
+  CC_REQUIRE(k_src_pool && k_dst_pool && src_block_tab && dst_block_tab && descs, "null pointer");
+  CC_REQUIRE((v_src_pool == nullptr) == (v_dst_pool == nullptr), "v_src_pool and v_dst_pool must both be given or both be NULL");
+  CC_REQUIRE(aligned16(k_src_pool) && aligned16(k_dst_pool) && aligned16(v_src_pool) && aligned16(v_dst_pool),
+             "pools must be 16-byte aligned");
+  CC_REQUIRE(n_src_blocks > 0 && n_dst_blocks > 0, "pool sizes must be positive");
+  cc::launch_rope_shift(ctx, k_src_pool, v_src_pool, n_src_blocks, k_dst_pool, v_dst_pool,
+                        n_dst_blocks, src_block_tab, dst_block_tab, descs, n_instances, max_tokens,
+                        static_cast<hipStream_t>(stream));
+  return cc::check_launch(ctx, fn);
+}
+
+// workspace of cc_select: [mass: n_tok * Hq floats][keys: n_tok uint32]
+size_t cc_select_workspace_bytes(const cc_ctx* ctx, int32_t n_tok, int32_t n_segs) {
+  if (ctx == nullptr || n_tok < 0 || n_segs < 0) return 0;
+  return cc::align_up(static_cast<size_t>(n_tok) * ctx->cfg.n_q_heads * sizeof(float), 256) +
+         cc::align_up(static_cast<size_t>(n_tok) * sizeof(uint32_t), 256) + 256;
+}
+
+int cc_select(cc_ctx* ctx, const void* q, int32_t n_tok, const void* k_pool, int32_t n_blocks,
+              const int32_t* block_tab, const cc_segment* segs, int32_t n_segs,
+              const int32_t* req_seg_off, int32_t n_requests, int32_t max_seg_tokens,
+              int32_t* sel_idx, int32_t* q_row, int32_t* q_pos, int32_t* slot_map, int32_t n_q_tot,
+              float* scores, void* workspace, size_t workspace_bytes, void* stream) {
+  static const char* fn = "cc_select";
+  if (ctx == nullptr) return CC_ERR_INVALID_ARG;
+  CC_REQUIRE(n_tok >= 0 && n_segs >= 0 && n_requests >= 0 && max_seg_tokens >= 0 && n_q_tot >= 0,
+             "negative count");
+  CC_REQUIRE(n_segs <= 65535, "more than 65535 segments in one call");
+  if (n_segs == 0 || max_seg_tokens == 0) return CC_OK;
+  CC_REQUIRE(q && k_pool && block_tab && segs && req_seg_off && sel_idx, "null pointer");
+  CC_REQUIRE(n_blocks > 0 && n_requests > 0, "pool size and request count must be positive");
+  CC_REQUIRE(aligned16(q) && aligned16(k_pool), "tensors must be 16-byte aligned");
+  CC_REQUIRE(workspace != nullptr && aligned16(workspace), "workspace missing or misaligned");
+  if (workspace_bytes < cc_select_workspace_bytes(ctx, n_tok, n_segs))
+    return fail(ctx, CC_ERR_WORKSPACE_TOO_SMALL, "cc_select: workspace smaller than cc_select_workspace_bytes()");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float* mass = static_cast<float*>(workspace);
+  uint32_t* keys = reinterpret_cast<uint32_t*>(
+      static_cast<char*>(workspace) +
+      cc::align_up(static_cast<size_t>(n_tok) * ctx->cfg.n_q_heads * sizeof(float), 256));
+  if (ctx->impl == CC_IMPL_AUTO && cc::score_mfma_supported(ctx))
+    cc::launch_score_mfma(ctx, q, k_pool, n_blocks, block_tab, segs, n_segs, req_seg_off,
+                          max_seg_tokens, mass, st);
+  else
+    cc::launch_score_scalar(ctx, q, k_pool, n_blocks, block_tab, segs, n_segs, req_seg_off,
+                            max_seg_tokens, mass, st);
+  cc::launch_topn(ctx, mass, block_tab, segs, n_segs, sel_idx, q_row, q_pos, slot_map, scores, keys, st);
+  return cc::check_launch(ctx, fn);
+}
+
+int cc_gather_rows(cc_ctx* ctx, const void* src, int32_t n_src_rows, const int32_t* row_idx,
+                   int32_t n_rows, size_t row_bytes, void* dst, void* stream) {
+  static const char* fn = "cc_gather_rows";
+  if (ctx == nullptr) return CC_ERR_INVALID_ARG;
+  CC_REQUIRE(n_rows >= 0 && n_src_rows >= 0, "negative count");
+  if (n_rows == 0) return CC_OK;
+  CC_REQUIRE(src && row_idx && dst, "null pointer");
+  CC_REQUIRE(row_bytes > 0 && row_bytes % 16 == 0, "row_bytes must be a positive multiple of 16");
+  CC_REQUIRE(aligned16(src) && aligned16(dst), "tensors must be 16-byte aligned");
+  cc::launch_gather_rows(src, n_src_rows, row_idx, n_rows, row_bytes, dst,
+                         static_cast<hipStream_t>(stream));
+  return cc::check_launch(ctx, fn);
+}
+
+int cc_qkv_project(cc_ctx* ctx, const void* x, const void* w_qkv, int32_t n_rows, int32_t hidden,
+                   void* q, void* k, void* v, void* stream) {
+  static const char* fn = "cc_qkv_project";
+  if (ctx == nullptr) return CC_ERR_INVALID_ARG;
+  CC_REQUIRE(n_rows >= 0 && hidden > 0, "bad sizes");
+  CC_REQUIRE(hidden % 64 == 0, "hidden must be a multiple of 64");
+  if (n_rows == 0) return CC_OK;
+  CC_REQUIRE(x && w_qkv && q && k && v, "null pointer");
+  CC_REQUIRE(aligned16(x) && aligned16(w_qkv) && aligned16(q) && aligned16(k) && aligned16(v),
+             "tensors must be 16-byte aligned");
+  cc::launch_qkv_project(ctx, x, w_qkv, n_rows, hidden, q, k, v, static_cast<hipStream_t>(stream));
+  return cc::check_launch(ctx, fn);
+}
+
+size_t cc_sparse_prefill_workspace_bytes(const cc_ctx* ctx, int32_t n_q_tot, int32_t n_requests) {
+  if (ctx == nullptr || n_q_tot < 0 || n_requests < 0) return 0;
+  return 256;
+}
+
+int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void* v_new,
+                      const int32_t* q_pos, const int32_t* slot_map, const int32_t* cu_q,
+                      int32_t n_q_tot, int32_t max_q_per_req, void* k_pool, void* v_pool,
+                      int32_t n_blocks, const int32_t* block_tab, const cc_segment* segs,
+                      int32_t n_segs, const int32_t* req_seg_off, int32_t n_requests, void* out,
+                      float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+  static const char* fn = "cc_sparse_prefill";
+  if (ctx == nullptr) return CC_ERR_INVALID_ARG;
+  CC_REQUIRE(n_q_tot >= 0 && max_q_per_req >= 0 && n_segs >= 0 && n_requests >= 0, "negative count");
+  CC_REQUIRE(max_q_per_req <= n_q_tot, "max_q_per_req exceeds n_q_tot");
+  if (n_q_tot == 0) return CC_OK;
+  CC_REQUIRE(q && k_new && v_new && q_pos && slot_map && cu_q && k_pool && v_pool && block_tab &&
+                 segs && req_seg_off && out, "null pointer");
+  CC_REQUIRE(n_blocks > 0 && n_requests > 0 && n_segs > 0 && max_q_per_req > 0, "sizes must be positive");
+  CC_REQUIRE(n_requests <= 65535, "more than 65535 requests in one call");
+  CC_REQUIRE(aligned16(q) && aligned16(k_new) && aligned16(v_new) && aligned16(k_pool) &&
+                 aligned16(v_pool) && aligned16(out), "tensors must be 16-byte aligned");
+  if (workspace_bytes < cc_sparse_prefill_workspace_bytes(ctx, n_q_tot, n_requests) ||
+      (workspace == nullptr && cc_sparse_prefill_workspace_bytes(ctx, n_q_tot, n_requests) > 0))
+    return fail(ctx, CC_ERR_WORKSPACE_TOO_SMALL,
+                "cc_sparse_prefill: workspace smaller than cc_sparse_prefill_workspace_bytes()");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_q_tot, k_pool, v_pool, n_blocks, st);
+  if (ctx->impl == CC_IMPL_AUTO && cc::attn_mfma_supported(ctx))
+    cc::launch_attn_mfma(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks,
+                         block_tab, segs, req_seg_off, n_requests, out, lse, st);
+  else
+    cc::launch_attn_scalar(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks,
+                           block_tab, segs, req_seg_off, n_requests, out, lse, st);
+  return cc::check_launch(ctx, fn);
+}
+
+}  // extern "C"

@@ -1,0 +1,79 @@
+// Shared declarations of libcachecraft's translation units (host + gfx950 device code).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+
+#include "cc.h"
+
+namespace cc {
+
+constexpr int kBlock = 16;        // tokens per KV block (Sec. 4, chunk storage management)
+constexpr int kMaxHalf = 64;      // d/2 for the largest supported head_dim (128)
+
+// Rotation frequencies theta^(-2i/d), computed once on the host in fp64 and passed by value
+// as a kernel argument (512 bytes), so no device table has to be allocated.
+struct InvFreq {
+  double f[kMaxHalf];
+};
+
+}  // namespace cc
+
+struct cc_ctx {
+  cc_config cfg;
+  cc::InvFreq inv_freq;
+  int impl;
+  std::string last_error;
+};
+
+namespace cc {
+
+int fail(cc_ctx* ctx, int status, const std::string& msg);
+int check_launch(cc_ctx* ctx, const char* what);
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ---- launchers implemented in the .hip files -------------------------------------------------
+void launch_rope_shift(const cc_ctx* ctx, const void* k_src, const void* v_src, int n_src_blocks,
+                       void* k_dst, void* v_dst, int n_dst_blocks, const int32_t* src_tab,
+                       const int32_t* dst_tab, const cc_shift_desc* descs, int n_instances,
+                       int max_tokens, hipStream_t stream);
+
+void launch_gather_rows(const void* src, int n_src_rows, const int32_t* row_idx, int n_rows,
+                        size_t row_bytes, void* dst, hipStream_t stream);
+
+// scores: per (token, query head) prior-chunk mass -> mass [n_tok][Hq] fp32
+void launch_score_scalar(const cc_ctx* ctx, const void* q, const void* k_pool, int n_blocks,
+                         const int32_t* block_tab, const cc_segment* segs, int n_segs,
+                         const int32_t* req_seg_off, int max_seg_tokens, float* mass,
+                         hipStream_t stream);
+bool score_mfma_supported(const cc_ctx* ctx);
+void launch_score_mfma(const cc_ctx* ctx, const void* q, const void* k_pool, int n_blocks,
+                       const int32_t* block_tab, const cc_segment* segs, int n_segs,
+                       const int32_t* req_seg_off, int max_seg_tokens, float* mass,
+                       hipStream_t stream);
+void launch_topn(const cc_ctx* ctx, const float* mass, const int32_t* block_tab,
+                 const cc_segment* segs, int n_segs, int32_t* sel_idx, int32_t* q_row,
+                 int32_t* q_pos, int32_t* slot_map, float* scores, uint32_t* key_buf,
+                 hipStream_t stream);
+
+void launch_rope_scatter(const cc_ctx* ctx, const void* k_new, const void* v_new,
+                         const int32_t* q_pos, const int32_t* slot_map, int n_q_tot, void* k_pool,
+                         void* v_pool, int n_blocks, hipStream_t stream);
+void launch_attn_scalar(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
+                        int n_q_tot, int max_q_per_req, const void* k_pool, const void* v_pool,
+                        int n_blocks, const int32_t* block_tab, const cc_segment* segs,
+                        const int32_t* req_seg_off, int n_requests, void* out, float* lse,
+                        hipStream_t stream);
+bool attn_mfma_supported(const cc_ctx* ctx);
+void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
+                      int n_q_tot, int max_q_per_req, const void* k_pool, const void* v_pool,
+                      int n_blocks, const int32_t* block_tab, const cc_segment* segs,
+                      const int32_t* req_seg_off, int n_requests, void* out, float* lse,
+                      hipStream_t stream);
+
+void launch_qkv_project(const cc_ctx* ctx, const void* x, const void* w, int n_rows, int hidden,
+                        void* q, void* k, void* v, hipStream_t stream);
+
+}  // namespace cc

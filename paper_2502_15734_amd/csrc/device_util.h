@@ -1,0 +1,56 @@
+// Device-side helpers shared by the gfx950 kernels: element conversion, rotary angles,
+// wavefront (64-lane) reductions.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "common.h"
+
+namespace cc {
+
+typedef __bf16 bf16_t;
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+__device__ __forceinline__ float to_float(float v) { return v; }
+__device__ __forceinline__ float to_float(bf16_t v) { return static_cast<float>(v); }
+template <typename T> __device__ __forceinline__ T from_float(float v);
+template <> __device__ __forceinline__ float from_float<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_float<bf16_t>(float v) { return static_cast<bf16_t>(v); }
+
+// cos/sin of pos * inv_freq.  The product and its reduction to (-pi, pi] are done in fp64 so that
+// positions up to ~10^5 with frequency 1 do not lose the angle in fp32; the sine/cosine of the
+// reduced angle are then taken in fp32.  pos == 0 yields exactly (1, 0).
+__device__ __forceinline__ void rot_cos_sin(int pos, double inv_freq, float* c, float* s) {
+  const double kInvTwoPi = 0.15915494309189533576888;
+  const double kTwoPi = 6.28318530717958647692529;
+  double t = static_cast<double>(pos) * inv_freq * kInvTwoPi;
+  t -= rint(t);
+  float r = static_cast<float>(t * kTwoPi);
+  sincosf(r, s, c);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ int wave_max_i(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ int wave_min_i(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+}  // namespace cc

@@ -1,0 +1,160 @@
+// cc_sparse_prefill, plain kernels: row gather, rotate-and-scatter of the recomputed K/V into the
+// paged cache ("fix", Sec. 3.4.3), and the scalar reference-grade attention (per-token form of
+// Eq. (1)); Sec. 4 "Selective Token Recomputation".
+#include "device_util.h"
+
+namespace cc {
+
+// dst[i] = src[row_idx[i]], 16 bytes per lane.
+__global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restrict__ src,
+                                                          int n_src_rows,
+                                                          const int32_t* __restrict__ row_idx,
+                                                          int n_rows, int vec_per_row,
+                                                          uint4* __restrict__ dst) {
+  const int rows_per_block = max(1, 256 / vec_per_row);
+  const int v_stride = (vec_per_row >= 256) ? 256 : vec_per_row;
+  const int local_row = (vec_per_row >= 256) ? 0 : threadIdx.x / vec_per_row;
+  const int v0 = (vec_per_row >= 256) ? threadIdx.x : threadIdx.x % vec_per_row;
+  const int row = blockIdx.x * rows_per_block + local_row;
+  if (row >= n_rows || local_row >= rows_per_block) return;
+  const int s = row_idx[row];
+  if (s < 0 || s >= n_src_rows) return;
+  const uint4* sp = src + static_cast<size_t>(s) * vec_per_row;
+  uint4* dp = dst + static_cast<size_t>(row) * vec_per_row;
+  for (int v = v0; v < vec_per_row; v += v_stride) dp[v] = sp[v];
+}
+
+void launch_gather_rows(const void* src, int n_src_rows, const int32_t* row_idx, int n_rows,
+                        size_t row_bytes, void* dst, hipStream_t stream) {
+  const int vec_per_row = static_cast<int>(row_bytes / 16);
+  const int rows_per_block = vec_per_row >= 256 ? 1 : 256 / vec_per_row;
+  dim3 grid((n_rows + rows_per_block - 1) / rows_per_block);
+  hipLaunchKernelGGL(gather_rows_kernel, grid, dim3(256), 0, stream,
+                     static_cast<const uint4*>(src), n_src_rows, row_idx, n_rows, vec_per_row,
+                     static_cast<uint4*>(dst));
+}
+
+// One workgroup (64 lanes) per query row: rotate k_new to the row's position and write it into
+// its K slot; write v_new into its V slot (dimension-major block, 16-element stride).
+template <typename T, int D>
+__global__ __launch_bounds__(64) void rope_scatter_kernel(
+    const T* __restrict__ k_new, const T* __restrict__ v_new, const int32_t* __restrict__ q_pos,
+    const int32_t* __restrict__ slot_map, int hkv, InvFreq inv_freq, T* __restrict__ k_pool,
+    T* __restrict__ v_pool, int n_blocks) {
+  const int j = blockIdx.x, lane = threadIdx.x;
+  const int slot = slot_map[j];
+  if (slot < 0 || slot >= n_blocks * kBlock) return;
+  const int p = q_pos[j], blk = slot / kBlock, sl = slot % kBlock;
+  const int n_pairs = hkv * (D / 2);
+  for (int e = lane; e < n_pairs; e += 64) {
+    const int h = e / (D / 2), i = e % (D / 2);
+    const T* kp = k_new + (static_cast<size_t>(j) * hkv + h) * D;
+    const T* vp = v_new + (static_cast<size_t>(j) * hkv + h) * D;
+    float c, s;
+    rot_cos_sin(p, inv_freq.f[i], &c, &s);
+    const float x = to_float(kp[i]), y = to_float(kp[i + D / 2]);
+    T* ko = k_pool + ((static_cast<size_t>(blk) * hkv + h) * kBlock + sl) * D;
+    ko[i] = from_float<T>(x * c - y * s);
+    ko[i + D / 2] = from_float<T>(y * c + x * s);
+    T* vo = v_pool + (static_cast<size_t>(blk) * hkv + h) * D * kBlock + sl;
+    vo[static_cast<size_t>(i) * kBlock] = vp[i];
+    vo[static_cast<size_t>(i + D / 2) * kBlock] = vp[i + D / 2];
+  }
+}
+
+void launch_rope_scatter(const cc_ctx* ctx, const void* k_new, const void* v_new,
+                         const int32_t* q_pos, const int32_t* slot_map, int n_q_tot, void* k_pool,
+                         void* v_pool, int n_blocks, hipStream_t stream) {
+  if (n_q_tot <= 0) return;
+  const bool bf = ctx->cfg.dtype == CC_BF16;
+  const int d = ctx->cfg.head_dim, hkv = ctx->cfg.n_kv_heads;
+#define CC_LAUNCH(T, D)                                                                          \
+  hipLaunchKernelGGL((rope_scatter_kernel<T, D>), dim3(n_q_tot), dim3(64), 0, stream,            \
+                     static_cast<const T*>(k_new), static_cast<const T*>(v_new), q_pos, slot_map, \
+                     hkv, ctx->inv_freq, static_cast<T*>(k_pool), static_cast<T*>(v_pool), n_blocks)
+  if (bf && d == 128) CC_LAUNCH(bf16_t, 128);
+  else if (bf && d == 64) CC_LAUNCH(bf16_t, 64);
+  else if (!bf && d == 128) CC_LAUNCH(float, 128);
+  else CC_LAUNCH(float, 64);
+#undef CC_LAUNCH
+}
+
+// Scalar attention: one wavefront per (query row, query head).  Lane i owns rotation pair
+// (i, i + d/2) of q and the same two output dimensions.
+template <typename T, int D>
+__global__ __launch_bounds__(64) void attn_scalar_kernel(
+    const T* __restrict__ q, const int32_t* __restrict__ q_pos, const int32_t* __restrict__ cu_q,
+    int n_requests, const T* __restrict__ k_pool, const T* __restrict__ v_pool, int n_blocks,
+    const int32_t* __restrict__ block_tab, const cc_segment* __restrict__ segs,
+    const int32_t* __restrict__ req_seg_off, int hq, int hkv, InvFreq inv_freq,
+    T* __restrict__ out, float* __restrict__ lse) {
+  const int j = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
+  int r = 0;
+  while (r + 1 < n_requests && cu_q[r + 1] <= j) ++r;
+  const int p = q_pos[j];
+  const int kvh = h / (hq / hkv);
+  const bool own = lane < D / 2;
+  float qx = 0.f, qy = 0.f;
+  if (own) {
+    const T* qp = q + (static_cast<size_t>(j) * hq + h) * D;
+    float x = to_float(qp[lane]), y = to_float(qp[lane + D / 2]), c, s;
+    rot_cos_sin(p, inv_freq.f[lane], &c, &s);
+    qx = x * c - y * s;
+    qy = y * c + x * s;
+  }
+  const float scale = rsqrtf(static_cast<float>(D));
+  float m = -INFINITY, z = 0.f, ox = 0.f, oy = 0.f;
+  for (int s = req_seg_off[r]; s < req_seg_off[r + 1]; ++s) {
+    const cc_segment ks = segs[s];
+    const int n_vis = min(ks.n_tokens, p - ks.logical_start + 1);
+    for (int tk = 0; tk < n_vis; ++tk) {
+      const int blk = block_tab[ks.tab_off + tk / kBlock];
+      if (blk < 0 || blk >= n_blocks) continue;
+      const size_t bh = static_cast<size_t>(blk) * hkv + kvh;
+      const T* kp = k_pool + (bh * kBlock + tk % kBlock) * D;
+      float part = own ? qx * to_float(kp[lane]) + qy * to_float(kp[lane + D / 2]) : 0.f;
+      const float logit = wave_sum(part) * scale;
+      if (logit > m) {
+        const float a = expf(m - logit);
+        z *= a; ox *= a; oy *= a;
+        m = logit;
+      }
+      const float e = expf(logit - m);
+      z += e;
+      if (own) {
+        const T* vp = v_pool + bh * D * kBlock + tk % kBlock;
+        ox += e * to_float(vp[static_cast<size_t>(lane) * kBlock]);
+        oy += e * to_float(vp[static_cast<size_t>(lane + D / 2) * kBlock]);
+      }
+    }
+  }
+  if (own) {
+    T* op = out + (static_cast<size_t>(j) * hq + h) * D;
+    op[lane] = from_float<T>(ox / z);
+    op[lane + D / 2] = from_float<T>(oy / z);
+  }
+  if (lse != nullptr && lane == 0) lse[static_cast<size_t>(j) * hq + h] = m + logf(z);
+}
+
+void launch_attn_scalar(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
+                        int n_q_tot, int max_q_per_req, const void* k_pool, const void* v_pool,
+                        int n_blocks, const int32_t* block_tab, const cc_segment* segs,
+                        const int32_t* req_seg_off, int n_requests, void* out, float* lse,
+                        hipStream_t stream) {
+  (void)max_q_per_req;
+  if (n_q_tot <= 0) return;
+  const bool bf = ctx->cfg.dtype == CC_BF16;
+  const int d = ctx->cfg.head_dim, hq = ctx->cfg.n_q_heads, hkv = ctx->cfg.n_kv_heads;
+#define CC_LAUNCH(T, D)                                                                         \
+  hipLaunchKernelGGL((attn_scalar_kernel<T, D>), dim3(n_q_tot, hq), dim3(64), 0, stream,        \
+                     static_cast<const T*>(q), q_pos, cu_q, n_requests,                         \
+                     static_cast<const T*>(k_pool), static_cast<const T*>(v_pool), n_blocks,    \
+                     block_tab, segs, req_seg_off, hq, hkv, ctx->inv_freq, static_cast<T*>(out), lse)
+  if (bf && d == 128) CC_LAUNCH(bf16_t, 128);
+  else if (bf && d == 64) CC_LAUNCH(bf16_t, 64);
+  else if (!bf && d == 128) CC_LAUNCH(float, 128);
+  else CC_LAUNCH(float, 64);
+#undef CC_LAUNCH
+}
+
+}  // namespace cc

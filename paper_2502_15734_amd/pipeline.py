@@ -1,0 +1,124 @@
+"""Device-side staging of one batch and the call sequence of the hot path.
+
+Marshalling only: uploads a workload (numpy arrays from workload.generate) into torch device
+tensors, allocates outputs and workspaces once, and issues the library calls in order:
+
+    cc_rope_shift -> cc_select -> cc_gather_rows (+ cc_qkv_project) -> cc_sparse_prefill
+
+All arithmetic happens inside libcachecraft's kernels.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from .binding import CC_BF16, CC_F32, CC_IMPL_AUTO, Context
+
+
+def _dev(a: np.ndarray, dtype=None, device="cuda") -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(a)).to(device)
+    return t if dtype is None else t.to(dtype)
+
+
+class DeviceBatch:
+    def __init__(self, w, device: str = "cuda", impl: int = CC_IMPL_AUTO, poison: bool = False):
+        sp = w.spec
+        self.w = w
+        self.device = device
+        self.dt = torch.bfloat16 if sp.dtype == "bf16" else torch.float32
+        self.ctx = Context(sp.n_q_heads, sp.n_kv_heads, sp.head_dim, sp.rope_theta,
+                           CC_BF16 if sp.dtype == "bf16" else CC_F32)
+        self.ctx.set_impl(impl)
+        hq, hkv, d = sp.n_q_heads, sp.n_kv_heads, sp.head_dim
+        dt = self.dt
+        # shared chunk store (read-only) and request-owned pages
+        self.k_store = _dev(w.k_store, dt, device)
+        self.v_store = _dev(w.v_store, dt, device)
+        nb = max(1, w.n_req_blocks)
+        fill = float("nan") if poison else 0.0
+        self.k_req = torch.full((nb, hkv, 16, d), fill, dtype=dt, device=device)
+        self.v_req = torch.full((nb, hkv, d, 16), fill, dtype=dt, device=device)
+        # metadata
+        self.store_tab = _dev(w.store_tab, None, device)
+        self.req_tab = _dev(w.req_tab, None, device)
+        self.shift_descs = _dev(w.shift_descs, None, device)
+        self.segments = _dev(w.segments, None, device)
+        self.req_seg_off = _dev(w.req_seg_off, None, device)
+        self.cu_q = _dev(w.cu_q, None, device)
+        self.n_instances = int(w.shift_descs.shape[0])
+        self.max_shift_tokens = int(w.shift_descs[:, 2].max()) if self.n_instances else 0
+        self.max_seg_tokens = w.max_seg_tokens
+        self.n_requests = w.n_requests
+        self.n_tok, self.n_q_tot = w.n_tok, w.n_q_tot
+        self.max_q_per_req = int(np.diff(w.cu_q).max()) if self.n_requests else 0
+        # per-token inputs
+        self.q = _dev(w.q, dt, device)
+        self.projected = w.hidden is not None
+        if self.projected:
+            self.hidden = _dev(w.hidden, dt, device)
+            self.w_qkv = _dev(w.w_qkv, dt, device)
+            self.x_c = torch.empty((max(1, self.n_q_tot), w.hidden.shape[1]), dtype=dt, device=device)
+        else:
+            self.k_new = _dev(w.k_new, dt, device)
+            self.v_new = _dev(w.v_new, dt, device)
+        # outputs
+        nq = max(1, self.n_q_tot)
+        i32 = dict(dtype=torch.int32, device=device)
+        self.sel_idx = torch.zeros(nq, **i32)
+        self.q_row = torch.zeros(nq, **i32)
+        self.q_pos = torch.zeros(nq, **i32)
+        self.slot_map = torch.zeros(nq, **i32)
+        self.scores = torch.zeros(max(1, self.n_tok), dtype=torch.float32, device=device)
+        self.q_c = torch.empty((nq, hq, d), dtype=dt, device=device)
+        self.k_c = torch.empty((nq, hkv, d), dtype=dt, device=device)
+        self.v_c = torch.empty((nq, hkv, d), dtype=dt, device=device)
+        self.out = torch.zeros((nq, hq, d), dtype=dt, device=device)
+        self.lse = torch.zeros((nq, hq), dtype=torch.float32, device=device)
+        self.ws_select = torch.empty(max(256, self.ctx.select_workspace_bytes(self.n_tok, len(w.segments))),
+                                     dtype=torch.uint8, device=device)
+        self.ws_prefill = torch.empty(max(256, self.ctx.sparse_prefill_workspace_bytes(self.n_q_tot, self.n_requests)),
+                                      dtype=torch.uint8, device=device)
+
+    # ---- the calls, in path order ------------------------------------------------------------
+    def rope_shift(self, with_v: bool = True):
+        self.ctx.rope_shift(self.k_store, self.v_store if with_v else None, self.k_req,
+                            self.v_req if with_v else None, self.store_tab, self.req_tab,
+                            self.shift_descs, self.n_instances, self.max_shift_tokens)
+
+    def select(self):
+        self.ctx.select(self.q, self.k_req, self.req_tab, self.segments, self.req_seg_off,
+                        self.n_requests, self.max_seg_tokens, self.sel_idx, self.q_row, self.q_pos,
+                        self.slot_map, self.scores, self.ws_select)
+
+    def gather(self):
+        """Compact the chosen tokens' rows (and project them when the workload has hidden states)."""
+        if self.n_q_tot == 0:
+            return
+        if self.projected:
+            self.ctx.gather_rows(self.hidden, self.q_row, self.x_c)
+            self.ctx.qkv_project(self.x_c, self.w_qkv, self.q_c, self.k_c, self.v_c)
+        else:
+            self.ctx.gather_rows(self.q, self.q_row, self.q_c)
+            self.ctx.gather_rows(self.k_new, self.q_row, self.k_c)
+            self.ctx.gather_rows(self.v_new, self.q_row, self.v_c)
+
+    def sparse_prefill(self):
+        if self.n_q_tot == 0:
+            return
+        self.ctx.sparse_prefill(self.q_c, self.k_c, self.v_c, self.q_pos, self.slot_map, self.cu_q,
+                                self.max_q_per_req, self.k_req, self.v_req, self.req_tab,
+                                self.segments, self.req_seg_off, self.n_requests, self.out, self.lse,
+                                self.ws_prefill)
+
+    def step(self):
+        """One pass of the whole hot path over the batch."""
+        self.rope_shift()
+        self.select()
+        self.gather()
+        self.sparse_prefill()
+
+    # ---- test helper: impose a selection computed elsewhere ------------------------------------
+    def set_selection(self, sel_idx: np.ndarray, q_row: np.ndarray, q_pos: np.ndarray, slot_map: np.ndarray):
+        for dst, src in ((self.sel_idx, sel_idx), (self.q_row, q_row), (self.q_pos, q_pos), (self.slot_map, slot_map)):
+            if self.n_q_tot:
+                dst.copy_(torch.from_numpy(np.ascontiguousarray(src, dtype=np.int32)))

@@ -1,0 +1,167 @@
+"""HIP path vs CPU oracle, element by element, through the C ABI.  Needs an MI355X (-m gpu)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import workload as W
+from oracle import cachecraft_oracle as O
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _pools(batch):
+    return batch.k_req.float().cpu().numpy(), batch.v_req.float().cpu().numpy()
+
+
+def check_workload(w, impl, score_tol=5e-5):
+    """shift -> select -> (oracle's selection) prefill, each compared with the oracle; then the
+    whole path end to end with the library's own selection."""
+    import paper_2502_15734_amd as P
+    from paper_2502_15734_amd.pipeline import DeviceBatch
+    tol = H.TOL[w.spec.dtype]
+    res = O.run(w)
+    b = DeviceBatch(w, impl=impl, poison=True)
+
+    # ---- (a) shift ---------------------------------------------------------------------------
+    b.rope_shift(); torch.cuda.synchronize()
+    kp, vp = _pools(b)
+    num = den = 0.0
+    for r in range(w.n_requests):
+        for sg in H.chunk_segments(w, r):
+            s, n, tab = int(sg[W.SEG_START]), int(sg[W.SEG_NTOK]), int(sg[W.SEG_TAB])
+            blocks = w.req_tab[tab: tab + (n + 15) // 16]
+            got_k = O.read_k_pages(kp, blocks, n); got_v = O.read_v_pages(vp, blocks, n)
+            ref_k = res[r].k_shifted[s:s + n]
+            num += ((got_k - ref_k) ** 2).sum(); den += (ref_k ** 2).sum()
+            src = next(d for d in w.shift_descs if d[W.SHIFT_DST_TAB] == tab)
+            sblocks = w.store_tab[src[W.SHIFT_SRC_TAB]: src[W.SHIFT_SRC_TAB] + (n + 15) // 16]
+            assert np.array_equal(got_v, O.read_v_pages(w.v_store, sblocks, n)), "V must be copied bit-exactly"
+    if den > 0:
+        assert math.sqrt(num / den) <= tol, f"shifted K rel L2 {math.sqrt(num / den):.3e}"
+
+    # ---- (b) select ----------------------------------------------------------------------------
+    b.select(); torch.cuda.synchronize()
+    scores = b.scores.cpu().numpy(); sel = b.sel_idx.cpu().numpy()
+    gsel = H.gpu_selection(w, sel)
+    for r in range(w.n_requests):
+        for c, sg in enumerate(H.chunk_segments(w, r)):
+            t0, n = int(sg[W.SEG_TOK]), int(sg[W.SEG_NTOK])
+            err = np.abs(scores[t0:t0 + n] - res[r].scores[c]).max() if n else 0.0
+            assert err <= score_tol, f"request {r} chunk {c}: score error {err:.3e}"
+        H.assert_selection_matches(w, r, gsel[r], res[r].scores, res[r].selected)
+    # cc_select's auxiliary outputs agree with its own index sets
+    if w.n_q_tot:
+        si, qr, qp, sm = H.selection_arrays(w, gsel)
+        assert np.array_equal(sel[: w.n_q_tot], si)
+        assert np.array_equal(b.q_row.cpu().numpy()[: w.n_q_tot], qr)
+        assert np.array_equal(b.q_pos.cpu().numpy()[: w.n_q_tot], qp)
+        assert np.array_equal(b.slot_map.cpu().numpy()[: w.n_q_tot], sm)
+
+    # ---- (c) prefill on the oracle's selection ---------------------------------------------------
+    def compare_prefill(batch, results, what):
+        torch.cuda.synchronize()
+        out = batch.out.float().cpu().numpy(); lse = batch.lse.cpu().numpy()
+        kp2, vp2 = _pools(batch)
+        for r in range(w.n_requests):
+            q0, q1 = int(w.cu_q[r]), int(w.cu_q[r + 1])
+            if q1 > q0:
+                e = H.rel_l2(out[q0:q1], results[r].out)
+                assert e <= tol, f"{what}: request {r} out rel L2 {e:.3e}"
+                le = np.abs(lse[q0:q1] - results[r].lse).max()
+                assert le <= (2e-3 if w.spec.dtype == "bf16" else 2e-5), f"{what}: request {r} lse err {le:.3e}"
+            k, v = H.request_context_from_pools(w, r, kp2, vp2)
+            if k.size:
+                assert H.rel_l2(k, results[r].k_ctx) <= tol, f"{what}: request {r} fixed K"
+                assert H.rel_l2(v, results[r].v_ctx) <= tol, f"{what}: request {r} fixed V"
+
+    if w.spec.hidden:
+        pytest.skip("projection workloads are checked in test_projection_*")
+    b.set_selection(*H.selection_arrays(w, [res[r].selected for r in range(w.n_requests)]))
+    b.gather(); b.sparse_prefill()
+    compare_prefill(b, res, "oracle selection")
+
+    # ---- end to end with the library's own selection -----------------------------------------
+    b2 = DeviceBatch(w, impl=impl, poison=True)
+    b2.step(); torch.cuda.synchronize()
+    gsel2 = H.gpu_selection(w, b2.sel_idx.cpu().numpy())
+    same = all(np.array_equal(a, o) for r in range(w.n_requests) for a, o in zip(gsel2[r], res[r].selected))
+    res2 = res if same else [O.run_request(w, r, selected_override=gsel2[r]) for r in range(w.n_requests)]
+    compare_prefill(b2, res2, "end to end")
+    # the shared store is read-only for the whole path
+    assert torch.equal(b2.k_store.float().cpu(), torch.from_numpy(w.k_store))
+    assert torch.equal(b2.v_store.float().cpu(), torch.from_numpy(w.v_store))
+
+
+def _impls():
+    import paper_2502_15734_amd as P
+    return {"auto": P.CC_IMPL_AUTO, "scalar": P.CC_IMPL_SCALAR}
+
+
+def test_config1_tiny_fp32():
+    check_workload(W.config(1), _impls()["auto"], score_tol=2e-6)
+
+
+@pytest.mark.parametrize("impl", ["auto", "scalar"])
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (16, 2), (4, 2), (2, 2)])
+def test_small_bf16_ragged(impl, hq, hkv):
+    # chunk lengths off the 16-token grid, several 64-key tiles, ragged query tiles, two requests
+    # sharing a stored chunk at different offsets
+    reqs = [W.RequestSpec([0, 1, 2, 3], [0.3, 0.2, 0.25, 0.1], 21),
+            W.RequestSpec([3, 0, 4], [0.5, 0.15, 0.35], 40)]
+    w = W.custom("ragged", "bf16", hq, hkv, 128, 5.0e5, [100, 77, 130, 64, 201], [0, 5, 0, 17, 3],
+                 reqs, 1.0 / math.sqrt(128), seed=100 + hq)
+    check_workload(w, _impls()[impl])
+
+
+@pytest.mark.parametrize("impl", ["auto", "scalar"])
+def test_small_bf16_stronger_logits(impl):
+    # larger logit spread (scores genuinely scattered); still inside what bf16 keys can rank
+    reqs = [W.RequestSpec([1, 0, 2], [0.2, 0.3, 0.25], 19)]
+    w = W.custom("spread", "bf16", 8, 2, 128, 5.0e5, [96, 150, 83], [0, 0, 0], reqs, 0.35, seed=7)
+    check_workload(w, _impls()[impl], score_tol=2e-4)
+
+
+def test_small_fp32_d128_and_d64():
+    reqs = [W.RequestSpec([2, 0, 1], [0.2, 0.4, 0.1], 9), W.RequestSpec([1], [0.5], 3)]
+    for d in (64, 128):
+        w = W.custom("f32", "f32", 4, 2, d, 1.0e4, [50, 33, 70], [0, 9, 2], reqs, 1.0, seed=d)
+        check_workload(w, _impls()["auto"], score_tol=2e-6)
+
+
+@pytest.mark.parametrize("fracs,question", [((0.0, 0.0, 0.0), 12), ((1.0, 1.0, 1.0), 7), ((0.3, 0.0, 1.0), 0)])
+def test_edge_fractions_bf16(fracs, question):
+    reqs = [W.RequestSpec([0, 1, 2], list(fracs), question)]
+    w = W.custom("edge", "bf16", 8, 2, 128, 5.0e5, [48, 70, 33], [0, 0, 0], reqs, 1.0 / math.sqrt(128), seed=3)
+    if w.n_q_tot == 0:
+        pytest.skip("no query at all")
+    check_workload(w, _impls()["auto"])
+
+
+def test_zero_shift_is_bit_exact():
+    from paper_2502_15734_amd.pipeline import DeviceBatch
+    reqs = [W.RequestSpec([0, 1], [0.1, 0.1], 4)]
+    for dtype in ("bf16", "f32"):
+        w = W.custom("noshift", dtype, 8, 2, 128, 5.0e5, [40, 64], [0, 40], reqs, 1.0, seed=5)
+        assert np.all(w.shift_descs[:, W.SHIFT_DELTA] == 0)
+        b = DeviceBatch(w)
+        b.rope_shift(); torch.cuda.synchronize()
+        kp, vp = _pools(b)
+        for c in range(2):
+            n = [40, 64][c]
+            src = w.store_tab[w.store_tab_off[c]: w.store_tab_off[c + 1]]
+            tab = int(w.segments[c][W.SEG_TAB])
+            dst = w.req_tab[tab: tab + (n + 15) // 16]
+            assert np.array_equal(O.read_k_pages(kp, dst, n), O.read_k_pages(w.k_store, src, n))
+            assert np.array_equal(O.read_v_pages(vp, dst, n), O.read_v_pages(w.v_store, src, n))
+
+
+def test_config2_llama3_8b_layer_full():
+    check_workload(W.config(2), _impls()["auto"])
+
+
+@pytest.mark.parametrize("cid,scale", [(3, 0.08), (4, 0.12)])
+def test_scaled_batch_configs(cid, scale):
+    check_workload(W.config(cid, scale), _impls()["auto"])
