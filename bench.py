@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the selective-KV-recompute hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic batch that is already resident in HBM:
+cc_rope_shift -> cc_select -> cc_gather_rows (+ cc_qkv_project) -> cc_sparse_prefill.
+Prints ONE JSON line: recomputed tokens/s for the whole path, the roofline of the kernel that
+dominates the step (plus every stage's own figure), and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
+PEAK_FP32_VALU_TFLOPS = 157.3
+
+
+def algorithmic_work(w):
+    """Algorithmic flops / bytes of each stage for workload w (only causally visible keys count)."""
+    import workload as W
+    sp = w.spec
+    hq, hkv, d = sp.n_q_heads, sp.n_kv_heads, sp.head_dim
+    e = 2 if sp.dtype == "bf16" else 4
+    seg = w.segments
+    chunk = seg[seg[:, W.SEG_KIND] == W.KIND_CHUNK]
+    n_chunk_tok = int(chunk[:, W.SEG_NTOK].sum())
+    # score: every token of every chunk that has a prior chunk, against keys 0..p
+    score_pairs = 0
+    for s in chunk:
+        st, n = int(s[W.SEG_START]), int(s[W.SEG_NTOK])
+        if st > 0:
+            score_pairs += n * st + n * (n + 1) // 2
+    return {
+        "n_chunk_tok": n_chunk_tok,
+        "shift_bytes": n_chunk_tok * hkv * d * e * 2 * 2,      # K read+write and V read+write
+        "score_flops": 2.0 * d * hq * score_pairs,
+        "recomputed_tokens": w.n_q_tot,
+    }
+
+
+def attention_flops(w, q_pos: np.ndarray) -> float:
+    sp = w.spec
+    return 4.0 * sp.head_dim * sp.n_q_heads * float((q_pos.astype(np.int64) + 1).sum())
+
+
+def time_stages(batch, steps: int):
+    """Average ms of each library call over `steps` steps (HIP events on the calls' stream)."""
+    import torch
+    names = ["rope_shift", "select", "gather", "sparse_prefill"]
+    fns = [batch.rope_shift, batch.select, batch.gather, batch.sparse_prefill]
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(fns) + 1)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    for i in range(steps):
+        ev[i][0].record()
+        for j, f in enumerate(fns):
+            f()
+            ev[i][j + 1].record()
+    torch.cuda.synchronize()
+    return {n: float(np.mean([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(steps)]))
+            for j, n in enumerate(names)}
+
+
+def cpu_baseline(w, budget_s: float = 20.0):
+    """The fp64 oracle as it stands, on a bounded sample: whole requests, in order, until about
+    `budget_s` seconds of CPU work are spent (at least one request)."""
+    from oracle import cachecraft_oracle as O
+    t0 = time.perf_counter()
+    tokens = 0
+    done = 0
+    for r in range(w.n_requests):
+        O.run_request(w, r)
+        tokens += int(w.cu_q[r + 1] - w.cu_q[r])
+        done += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    try:
+        import threadpoolctl
+        cores = max((p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()), default=1)
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": tokens / dt, "unit": "recomputed tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {done} of {w.n_requests} requests, all stages (shift, score, select, fix, attend), "
+                      f"{tokens} recomputed tokens in {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=3, help="benchmark config 1..5 (default 3)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget", type=float, default=20.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workload as W
+    import paper_2502_15734_amd as P
+    from paper_2502_15734_amd.pipeline import DeviceBatch
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    P.load_library()
+    w = W.config(args.workload)
+    batch = DeviceBatch(w)
+    work = algorithmic_work(w)
+
+    for _ in range(args.warmup):
+        batch.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        batch.step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    tokens_per_s = work["recomputed_tokens"] / (dt / args.steps)
+
+    stage_ms = time_stages(batch, args.steps)
+    q_pos = batch.q_pos.cpu().numpy()[: w.n_q_tot]
+    attn_flops = attention_flops(w, q_pos)
+    proj_flops = 0.0
+    if w.hidden is not None:
+        sp = w.spec
+        proj_flops = 2.0 * w.hidden.shape[1] * (sp.n_q_heads + 2 * sp.n_kv_heads) * sp.head_dim * w.n_q_tot
+
+    stages = {
+        "cc_rope_shift": {"bound": "hbm", "ms": stage_ms["rope_shift"], "unit": "GB/s", "peak": PEAK_HBM_GBS,
+                          "achieved": work["shift_bytes"] / (stage_ms["rope_shift"] * 1e-3) / 1e9},
+        "cc_select": {"bound": "mfma", "ms": stage_ms["select"], "unit": "TFLOP/s", "peak": PEAK_MFMA_BF16_TFLOPS,
+                      "achieved": work["score_flops"] / (stage_ms["select"] * 1e-3) / 1e12},
+        "cc_gather_rows(+cc_qkv_project)": {"bound": "mfma" if proj_flops else "hbm", "ms": stage_ms["gather"],
+                                            "unit": "TFLOP/s" if proj_flops else "GB/s",
+                                            "peak": PEAK_MFMA_BF16_TFLOPS if proj_flops else PEAK_HBM_GBS,
+                                            "achieved": (proj_flops / (stage_ms["gather"] * 1e-3) / 1e12) if proj_flops else
+                                            (2.0 * w.n_q_tot * (w.spec.n_q_heads + 2 * w.spec.n_kv_heads) * w.spec.head_dim *
+                                             (2 if w.spec.dtype == "bf16" else 4) / (stage_ms["gather"] * 1e-3) / 1e9)},
+        "cc_sparse_prefill": {"bound": "mfma", "ms": stage_ms["sparse_prefill"], "unit": "TFLOP/s",
+                              "peak": PEAK_MFMA_BF16_TFLOPS,
+                              "achieved": attn_flops / (stage_ms["sparse_prefill"] * 1e-3) / 1e12},
+    }
+    for s in stages.values():
+        s["frac"] = s["achieved"] / s["peak"]
+    dominant = max(stages, key=lambda k: stages[k]["ms"])
+    dom = stages[dominant]
+    roofline = {"kernel": dominant, "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
+                "unit": dom["unit"], "frac": dom["frac"], "traffic": None, "avg_ms": dom["ms"]}
+
+    result = {
+        "metric": "recomputed tokens/sec in selective chunk prefill",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.spec.dtype, "data": "synthetic",
+        "config": {"workload": W.CONFIG_NAMES[args.workload], "config_id": args.workload,
+                   "n_requests": w.n_requests, "prompt_tokens": w.n_tok, "recomputed_tokens": w.n_q_tot,
+                   "n_q_heads": w.spec.n_q_heads, "n_kv_heads": w.spec.n_kv_heads, "head_dim": w.spec.head_dim},
+        "roofline": roofline,
+        "stages": stages,
+        "sparse_prefill_tokens_per_s": w.n_q_tot / (stage_ms["sparse_prefill"] * 1e-3),
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, args.cpu_budget)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

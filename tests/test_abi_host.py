@@ -1,0 +1,101 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol that
+include/cc.h declares, and rejects bad arguments before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2502_15734_amd as P
+    if not os.path.exists(P.library_path()):
+        from paper_2502_15734_amd import build
+        build.build(verbose=False)
+    return P.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "cc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cc_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"cc_rope_shift", "cc_select", "cc_sparse_prefill", "cc_gather_rows", "cc_qkv_project",
+            "cc_create", "cc_destroy"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in cc.h but not exported"
+
+
+def test_status_strings(lib):
+    assert lib.cc_status_string(0) == b"ok"
+    for s in (-1, -2, -3, -4):
+        assert len(lib.cc_status_string(s)) > 0
+
+
+def test_create_validates_config():
+    import paper_2502_15734_amd as P
+    P.Context(32, 8, 128, 5.0e5, P.CC_BF16).close()
+    P.Context(4, 2, 64, 1.0e4, P.CC_F32).close()
+    for args, status in (((32, 8, 96, 5.0e5, P.CC_BF16), -2), ((32, 5, 128, 5.0e5, P.CC_BF16), -1),
+                         ((32, 8, 128, -1.0, P.CC_BF16), -1), ((32, 8, 128, 5.0e5, 7), -2),
+                         ((0, 8, 128, 5.0e5, P.CC_BF16), -1)):
+        with pytest.raises(P.CacheCraftError) as e:
+            P.Context(*args)
+        assert e.value.status == status
+    with pytest.raises(P.CacheCraftError):
+        P.Context(32, 8, 128, 5.0e5, P.CC_BF16, block_size=32)
+
+
+def test_calls_reject_bad_arguments_before_launch(lib):
+    import paper_2502_15734_amd as P
+    ctx = P.Context(8, 2, 128, 5.0e5, P.CC_BF16)
+    h = ctx._h
+    good = C.c_void_p(4096)          # a well-aligned non-null address; never dereferenced on these paths
+    odd = C.c_void_p(4100)
+    # cc_rope_shift: null pool, misaligned pool, V given on one side only, negative count
+    assert lib.cc_rope_shift(h, None, None, 4, good, None, 4, good, good, good, 1, 16, None) == -1
+    assert b"null" in lib.cc_last_error(h)
+    assert lib.cc_rope_shift(h, odd, None, 4, good, None, 4, good, good, good, 1, 16, None) == -1
+    assert lib.cc_rope_shift(h, good, good, 4, good, None, 4, good, good, good, 1, 16, None) == -1
+    assert lib.cc_rope_shift(h, good, None, 4, good, None, 4, good, good, good, -1, 16, None) == -1
+    assert lib.cc_rope_shift(h, good, None, 4, good, None, 4, good, good, good, 0, 16, None) == 0   # empty batch
+    # cc_select: workspace too small / missing
+    need = lib.cc_select_workspace_bytes(h, 100, 3)
+    assert need >= 100 * 8 * 4
+    assert lib.cc_select(h, good, 100, good, 8, good, good, 3, good, 1, 64, good, None, None, None, 10,
+                         None, good, need - 1, None) == -3
+    assert lib.cc_select(h, good, 100, good, 8, good, good, 3, good, 1, 64, good, None, None, None, 10,
+                         None, None, need, None) == -1
+    assert lib.cc_select(h, None, 100, good, 8, good, good, 3, good, 1, 64, good, None, None, None, 10,
+                         None, good, need, None) == -1
+    # cc_gather_rows: row size not a multiple of 16
+    assert lib.cc_gather_rows(h, good, 10, good, 4, 24, good, None) == -1
+    # cc_qkv_project: hidden not a multiple of 64
+    assert lib.cc_qkv_project(h, good, good, 4, 100, good, good, good, None) == -1
+    # cc_sparse_prefill: null output, max_q_per_req > n_q_tot, empty query list
+    ws = lib.cc_sparse_prefill_workspace_bytes(h, 10, 1)
+    args = [h, good, good, good, good, good, good, 10, 10, good, good, 8, good, good, 3, good, 1]
+    assert lib.cc_sparse_prefill(*args, None, None, good, ws, None) == -1
+    args[8] = 11
+    assert lib.cc_sparse_prefill(*args, good, None, good, ws, None) == -1
+    args[7], args[8] = 0, 0
+    assert lib.cc_sparse_prefill(*args, good, None, good, ws, None) == 0
+    # null context
+    assert lib.cc_rope_shift(None, good, None, 4, good, None, 4, good, good, good, 1, 16, None) == -1
+    assert lib.cc_set_impl(h, 99) == -1
+    ctx.close()
+
+
+def test_product_path_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2502_15734_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f"{f} mentions the oracle"
