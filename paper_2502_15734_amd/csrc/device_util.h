@@ -32,6 +32,17 @@ __device__ __forceinline__ void rot_cos_sin(int pos, double inv_freq, float* c, 
   sincosf(r, s, c);
 }
 
+// Same angle, hardware sine/cosine (their argument is in revolutions, which is what the fp64
+// reduction produces); absolute error ~1e-6, used where the result is rounded to bf16 anyway.
+__device__ __forceinline__ void rot_cos_sin_fast(int pos, double inv_freq, float* c, float* s) {
+  const double kInvTwoPi = 0.15915494309189533576888;
+  double t = static_cast<double>(pos) * inv_freq * kInvTwoPi;
+  t -= rint(t);
+  const float tf = static_cast<float>(t);
+  *c = __builtin_amdgcn_cosf(tf);
+  *s = __builtin_amdgcn_sinf(tf);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

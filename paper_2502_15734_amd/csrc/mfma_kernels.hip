@@ -61,49 +61,107 @@ struct TileIter {
   __device__ __forceinline__ int tab0() const { return seg_tab + (kTile / kBlock) * kt; }
 };
 
-// Copies one key tile (and, if WITH_V, the value tile) of KV head `kvh` into LDS.  Global reads are
-// contiguous 16-byte pieces in pool order; slots past the segment's end are written as zeros so
-// that stale or non-finite padding can never reach a product.
+// Staging of one key tile (and, if WITH_V, the value tile) of KV head `kvh`: every thread owns
+// PER 16-byte pieces, piece c = tid + NT*i of the tile in pool order (K pages 0..3, then V pages
+// 0..3), so a wavefront instruction reads one contiguous KiB.  With NT a multiple of 256 a thread
+// keeps the same place inside every page, and its LDS destination is one base per pool plus a
+// constant per piece.  load() leaves the pieces in registers (issued one tile ahead of their
+// use), store() writes them to LDS.  Slots past the segment's end are staged as zeros so that
+// stale or non-finite padding can never reach a product.
 template <int NT, bool WITH_V>
-__device__ __forceinline__ void stage_tile(uint4* lds, const bf16_t* __restrict__ k_pool,
-                                           const bf16_t* __restrict__ v_pool, int n_blocks,
-                                           const int32_t* __restrict__ block_tab, int tab0, int nvalid,
-                                           int hkv, int kvh, int tid) {
-  constexpr int kPieces = WITH_V ? 2048 : 1024;
-#pragma unroll
-  for (int i = 0; i < kPieces / NT; ++i) {
-    const int c = tid + NT * i;
-    const bool is_v = WITH_V && c >= 1024;
-    const int c1 = c & 1023, pg = c1 >> 8, cc_ = c1 & 255;
-    const int nv = min(max(nvalid - kBlock * pg, 0), kBlock);
-    int blk = -1;
-    if (nv > 0) blk = block_tab[tab0 + pg];
-    const bool ok = blk >= 0 && blk < n_blocks;
-    const size_t page_off = (static_cast<size_t>(ok ? blk : 0) * hkv + kvh) * (kBlock * kD);
-    uint4 val = make_uint4(0u, 0u, 0u, 0u);
-    int dst;
-    if (!is_v) {
+struct Stager {
+  static_assert(NT % 256 == 0 || NT == 64 || NT == 128, "unsupported workgroup size");
+  static constexpr int kPieces = WITH_V ? 2048 : 1024;
+  static constexpr int PER = kPieces / NT;
+  static constexpr int kBatch = PER < 8 ? PER : 8;      // pieces held in registers at a time
+  static constexpr bool kPrefetch = PER <= 8;           // whole tile fits in registers
+  uint4 reg[kBatch];
+  const bf16_t* k_head;  // pools offset to this KV head
+  const bf16_t* v_head;
+  size_t blk_stride;     // elements per block (all heads)
+  int n_blocks;
+  int tid;
+
+  __device__ __forceinline__ int piece(int i) const { return tid + NT * i; }
+  __device__ __forceinline__ int page_of(int i) const { return (piece(i) & 1023) >> 8; }
+  __device__ __forceinline__ bool is_v(int i) const { return WITH_V && piece(i) >= 1024; }
+  __device__ __forceinline__ int src_of(int i) const { return (piece(i) & 255) * 8; }
+  __device__ __forceinline__ int dst_of(int i) const {
+    const int cc_ = piece(i) & 255, pg = page_of(i);
+    if (!is_v(i)) {
       const int slot = cc_ >> 4, ch = cc_ & 15;
-      if (ok && slot < nv) val = *reinterpret_cast<const uint4*>(k_pool + page_off + cc_ * 8);
-      const int a = pg * kBlock + slot, b = a >> 5, m = swap23(a & 31);
-      dst = (b * 8 + (ch >> 1)) * 64 + (ch & 1) * 32 + (m ^ (ch & 7));
-    } else {
-      const int dcol = cc_ >> 1, hh = cc_ & 1;
-      if (ok) {
-        val = *reinterpret_cast<const uint4*>(v_pool + page_off + cc_ * 8);
-        if (nv < kBlock) {                   // zero the padding slots of a partly filled block
-          unsigned short e[8];
-          *reinterpret_cast<uint4*>(e) = val;
+      // key a = 16*pg + slot of the tile -> block a/32, MFMA row swap23(a%32)
+      return ((pg >> 1) * 8 + (ch >> 1)) * 64 + (ch & 1) * 32 + (((pg & 1) * 16 + swap23(slot)) ^ (ch & 7));
+    }
+    const int dcol = cc_ >> 1, hh = cc_ & 1;
+    return 1024 + (pg * 4 + (dcol >> 5)) * 64 + hh * 32 + ((dcol & 31) ^ (4 * hh));
+  }
+
+  __device__ __forceinline__ void init(const bf16_t* k_pool, const bf16_t* v_pool, int n_blocks_,
+                                       int hkv, int kvh, int tid_) {
+    k_head = k_pool + static_cast<size_t>(kvh) * (kBlock * kD);
+    v_head = WITH_V ? v_pool + static_cast<size_t>(kvh) * (kBlock * kD) : nullptr;
+    blk_stride = static_cast<size_t>(hkv) * (kBlock * kD);
+    n_blocks = n_blocks_;
+    tid = tid_;
+  }
+
+  // pieces [i0, i0 + kBatch) of the tile -> reg
+  __device__ __forceinline__ void load(const int32_t* __restrict__ block_tab, int tab0, int nvalid, int i0 = 0) {
+    if (nvalid == kTile) {                         // whole tile present (wave-uniform)
 #pragma unroll
-          for (int j = 0; j < 8; ++j) if (8 * hh + j >= nv) e[j] = 0;
-          val = *reinterpret_cast<uint4*>(e);
+      for (int j = 0; j < kBatch; ++j) {
+        const int i = i0 + j;
+        const int blk = block_tab[tab0 + page_of(i)];
+        const bool ok = blk >= 0 && blk < n_blocks;
+        const bf16_t* base = (is_v(i) ? v_head : k_head) + static_cast<size_t>(ok ? blk : 0) * blk_stride;
+        reg[j] = ok ? *reinterpret_cast<const uint4*>(base + src_of(i)) : make_uint4(0u, 0u, 0u, 0u);
+      }
+      return;
+    }
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j) {
+      const int i = i0 + j;
+      const int pg = page_of(i), src = src_of(i);
+      const int nv = min(max(nvalid - kBlock * pg, 0), kBlock);
+      int blk = -1;
+      if (nv > 0) blk = block_tab[tab0 + pg];
+      const bool ok = blk >= 0 && blk < n_blocks;
+      uint4 val = make_uint4(0u, 0u, 0u, 0u);
+      if (ok) {
+        if (!is_v(i)) {
+          if ((src >> 7) < nv)                     // src/8 = piece in page, /16 = token slot
+            val = *reinterpret_cast<const uint4*>(k_head + static_cast<size_t>(blk) * blk_stride + src);
+        } else {
+          val = *reinterpret_cast<const uint4*>(v_head + static_cast<size_t>(blk) * blk_stride + src);
+          if (nv < kBlock) {                       // zero the padding slots of a partly filled block
+            const int hh = (src >> 3) & 1;
+            unsigned short e[8];
+            *reinterpret_cast<uint4*>(e) = val;
+#pragma unroll
+            for (int jj = 0; jj < 8; ++jj) if (8 * hh + jj >= nv) e[jj] = 0;
+            val = *reinterpret_cast<uint4*>(e);
+          }
         }
       }
-      dst = 1024 + (pg * 4 + (dcol >> 5)) * 64 + hh * 32 + ((dcol & 31) ^ (4 * hh));
+      reg[j] = val;
     }
-    lds[dst] = val;
   }
-}
+
+  __device__ __forceinline__ void store(uint4* lds, int i0 = 0) const {
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j) lds[dst_of(i0 + j)] = reg[j];
+  }
+
+  // small workgroups: the tile does not fit in registers, copy it batch by batch
+  __device__ __forceinline__ void copy(uint4* lds, const int32_t* __restrict__ block_tab, int tab0, int nvalid) {
+#pragma unroll 1
+    for (int i0 = 0; i0 < PER; i0 += kBatch) {
+      load(block_tab, tab0, nvalid, i0);
+      store(lds, i0);
+    }
+  }
+};
 
 __device__ __forceinline__ float max16(const f32x16& v) {
   float a = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
@@ -118,14 +176,15 @@ __device__ __forceinline__ float max16(const f32x16& v) {
 // SCORE = false: queries are 32 rows of the compact query list; result is the attention output
 //                and log-sum-exp (Eq. (1)).
 template <int G, bool SCORE>
-__global__ __launch_bounds__(64 * G) void sparse_qk_kernel(
+__global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
     const bf16_t* __restrict__ q, const int32_t* __restrict__ q_pos, const int32_t* __restrict__ cu_q,
     const bf16_t* __restrict__ k_pool, const bf16_t* __restrict__ v_pool, int n_blocks,
     const int32_t* __restrict__ block_tab, const cc_segment* __restrict__ segs,
     const int32_t* __restrict__ req_seg_off, int hq, int hkv, int n_tiles_x, InvFreq inv_freq,
     bf16_t* __restrict__ out, float* __restrict__ lse, float* __restrict__ mass) {
   constexpr int NT = 64 * G;
-  __shared__ uint4 lds[SCORE ? 1024 : 2048];
+  constexpr int kImage = SCORE ? 1024 : 2048;      // 16-byte pieces per tile image
+  __shared__ uint4 lds_all[2 * kImage];            // double-buffered
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 31, hh = lane >> 5;
   const int kvh = blockIdx.x % hkv;
@@ -171,7 +230,7 @@ __global__ __launch_bounds__(64 * G) void sparse_qk_kernel(
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         float c, s;
-        rot_cos_sin(p, inv_freq.f[16 * kk + 8 * hh + j], &c, &s);
+        rot_cos_sin_fast(p, inv_freq.f[16 * kk + 8 * hh + j], &c, &s);
         const float x = static_cast<float>(qreg[kk][j]), y = static_cast<float>(qreg[kk + 4][j]);
         qreg[kk][j] = static_cast<bf16_t>(x * c - y * s);
         qreg[kk + 4][j] = static_cast<bf16_t>(y * c + x * s);
@@ -187,17 +246,23 @@ __global__ __launch_bounds__(64 * G) void sparse_qk_kernel(
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
 
+  Stager<NT, !SCORE> stg;
+  stg.init(k_pool, v_pool, n_blocks, hkv, kvh, tid);
   TileIter it;
   it.init(segs, s_begin, s_end, p_max);
+  constexpr bool kPrefetch = Stager<NT, !SCORE>::kPrefetch;
+  if (it.valid) stg.copy(lds_all, block_tab, it.tab0(), it.nvalid());
+  __syncthreads();
+  int buf = 0;
   while (it.valid) {
     if constexpr (SCORE) {
       // entering the query's own segment: everything summed so far is prior-chunk mass
       if (it.s == s_self && it.kt == 0) { l_prior = l_run; l_run = 0.f; }
     }
     const int kpos0 = it.kpos0(), nvalid = it.nvalid();
-    __syncthreads();
-    stage_tile<NT, !SCORE>(lds, k_pool, v_pool, n_blocks, block_tab, it.tab0(), nvalid, hkv, kvh, tid);
-    __syncthreads();
+    const uint4* lds = lds_all + buf * kImage;
+    it.advance();
+    if (kPrefetch && it.valid) stg.load(block_tab, it.tab0(), it.nvalid());   // next tile: loads in flight
 
     // ---- S^T = K Q^T : 2 blocks of 32 keys x 32 queries ------------------------------------
     f32x16 sacc[2];
@@ -269,7 +334,12 @@ __global__ __launch_bounds__(64 * G) void sparse_qk_kernel(
         }
       }
     }
-    it.advance();
+    if (it.valid) {
+      if (kPrefetch) stg.store(lds_all + (buf ^ 1) * kImage);
+      else stg.copy(lds_all + (buf ^ 1) * kImage, block_tab, it.tab0(), it.nvalid());
+    }
+    __syncthreads();
+    buf ^= 1;
   }
 
   // ---- epilogue ---------------------------------------------------------------------------------
