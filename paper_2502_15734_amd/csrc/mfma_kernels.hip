@@ -18,9 +18,10 @@
 // Softmax bookkeeping: the query is pre-multiplied by log2(e)/sqrt(d) before it is rounded to
 // bf16, so S is in log2 units; the first MFMA of every S block takes -m_ref (the query's current
 // reference maximum, splat over the accumulator) as its C operand, so the accumulator comes out
-// as S - m_ref and p = exp2(acc) needs no further arithmetic.  m_ref only moves when some entry
-// exceeds it by more than kLazy (then sums and O are rescaled), which is rare after the first
-// tiles; p stays below 2^kLazy, harmless in fp32 and in bf16.
+// as S - m_ref and p = exp2(acc) needs no further arithmetic.  m_ref is set by the first tile and
+// afterwards moves only when a tile's sum of exponentials exceeds kBig (entries far above the
+// reference); that tile is then redone with the reference raised and the sums and O rescaled.
+// Until then p is merely "large": fp32 and bf16 share the exponent range, so nothing is lost.
 //
 // LDS image of a tile (16-byte pieces; every MFMA operand read is one conflict-free 1 KiB run):
 //   K piece (block b of 32 keys, k-step kk, half hh, row m):  (b*8+kk)*64 + hh*32 + (m ^ ((2kk+hh)&7))
@@ -36,7 +37,7 @@ constexpr int kD = 128;
 constexpr int kTile = 64;                      // keys per tile
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr float kLazy = 8.f;                   // slack (log2 units) before the reference max moves
+constexpr float kBig = 1.0e12f;                // a tile sum above this moves the reference maximum
 
 __device__ __forceinline__ int swap23(int m) { return (m & ~12) | ((m & 4) << 1) | ((m & 8) >> 1); }
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -229,6 +230,7 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
   // affordable; otherwise it is subtracted before the exponential.
   constexpr bool kNegM = QB == 1;
   constexpr int kImage = SCORE ? 1024 : 2048;       // 16-byte pieces per tile image
+  constexpr int kDepth = 4;                         // operand reads in flight ahead of the MFMAs
   __shared__ uint4 lds_all[2 * kImage];             // double-buffered
   const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
   const int n = lane & 31, hh = lane >> 5;
@@ -314,6 +316,7 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
     for (int db = 0; db < (SCORE ? 1 : 4); ++db) o[qb][db] = splat16(0.f);
   }
   bool first = true;
+  float lsum_t[QB];
 
   Stager<kPrefetch ? NT : 256, !SCORE> stg;
   TileIter it;
@@ -341,98 +344,122 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
       if (it.valid) stg.load(block_tab, it.tab0(), it.nvalid());      // next tile: loads in flight
     }
 
-    // ---- S^T - m_ref = K Q^T - m_ref : per query block, 2 blocks of 32 keys x 32 queries -------
+    // ---- S^T = K Q^T and p = exp2(S - m_ref) ---------------------------------------------------------
+    // The exponentials are taken against the current reference without looking at the tile's
+    // maximum; only if a tile's sum shows that entries ran far above the reference (or on the
+    // very first tile, which sets it) is the tile redone with the reference moved up and the
+    // running sums / O rescaled.  The redo recomputes S from the LDS image, which is still there.
     f32x16 sacc[QB][2];
+    const bool edge = nvalid < kTile || kpos0 + kTile - 1 > p_min;   // padding or causal edge
+    bool redo = first;
+    for (;;) {
+      // operand reads run kDepth steps ahead of the MFMAs that consume them; the scheduling
+      // fences keep that order, so LDS latency hides behind matrix work of the same wave
+      {
+        uint4 ring[kDepth];
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
+        for (int st = 0; st < kDepth; ++st) ring[st] = lds[((st & 1) * 8 + (st >> 1)) * 64 + kx[(st >> 1) & 3]];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        const bf16x8 a = __builtin_bit_cast(bf16x8, lds[(b * 8 + kk) * 64 + kx[kk & 3]]);
+        for (int st = 0; st < 16; ++st) {
+          const int kk = st >> 1, b = st & 1;
+          const bf16x8 a = __builtin_bit_cast(bf16x8, ring[st % kDepth]);
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-          sacc[qb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              a, qreg[qb][kk], kk == 0 ? (kNegM ? negm[qb] : splat16(0.f)) : sacc[qb][b], 0, 0, 0);
-      }
-    }
-    // accumulator register i of block b holds key 32b + 16(i/8) + 8hh + i%8 of the tile
-    if (nvalid < kTile || kpos0 + kTile - 1 > p_min) {     // wave-uniform: padding or causal edge
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        const int lim = min(nvalid - 1, p[qb] - kpos0) - 8 * hh;
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-          for (int i = 0; i < 16; ++i)
-            sacc[qb][b][i] = (32 * b + 16 * (i / 8) + (i % 8) <= lim) ? sacc[qb][b][i] : -INFINITY;
-      }
-    }
-    // ---- reference maximum: moves only when an entry exceeds it by more than kLazy ---------------
-    float tmax[QB];
-    bool move = first;
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      tmax[qb] = fmaxf(max16(sacc[qb][0]), max16(sacc[qb][1])) - (kNegM ? 0.f : m_ref[qb]);
-      move = move || tmax[qb] > kLazy;
-    }
-    if (__any(move)) {
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        const float t = fmaxf(tmax[qb], __shfl_xor(tmax[qb], 32, 64));
-        const float d = first ? t : fmaxf(t, 0.f);
-        const float alpha = first ? 1.f : __builtin_amdgcn_exp2f(-d);
-        l_run[qb] *= alpha;
-        if constexpr (SCORE) l_prior[qb] *= alpha;
-        else {
-#pragma unroll
-          for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[qb][db][i] *= alpha;
+          for (int qb = 0; qb < QB; ++qb)
+            sacc[qb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                a, qreg[qb][kk], kk == 0 ? (kNegM ? negm[qb] : splat16(0.f)) : sacc[qb][b], 0, 0, 0);
+          if (st + kDepth < 16) {
+            const int s2 = st + kDepth;
+            ring[st % kDepth] = lds[((s2 & 1) * 8 + (s2 >> 1)) * 64 + kx[(s2 >> 1) & 3]];
+          }
+          __builtin_amdgcn_sched_barrier(0);
         }
-        m_ref[qb] += d;
-        if constexpr (kNegM) {
+      }
+      // accumulator register i of block b holds key 32b + 16(i/8) + 8hh + i%8 of the tile
+      if (edge) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+          int lim = min(nvalid - 1, p[qb] - kpos0) - 8 * hh;
+          asm volatile("" : "+v"(lim));                    // the compares must not be hoisted out
 #pragma unroll
           for (int b = 0; b < 2; ++b)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) sacc[qb][b][i] -= d;
-          negm[qb] = splat16(-m_ref[qb]);
+            for (int i = 0; i < 16; ++i)
+              sacc[qb][b][i] = (32 * b + 16 * (i / 8) + (i % 8) <= lim) ? sacc[qb][b][i] : -INFINITY;
+          // opaque to the optimiser, so that the masking stays inside this rarely taken branch
+          asm volatile("" : "+v"(sacc[qb][0]), "+v"(sacc[qb][1]));
         }
       }
-      first = false;
-    }
-    // ---- p = exp2(S - m_ref), running sums ----------------------------------------------------------
+      if (redo) {
+        asm volatile("" ::: "memory");
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      float lsum = 0.f;
+        for (int qb = 0; qb < QB; ++qb) {
+          float t = fmaxf(max16(sacc[qb][0]), max16(sacc[qb][1])) - (kNegM ? 0.f : m_ref[qb]);
+          t = fmaxf(t, __shfl_xor(t, 32, 64));
+          const float d = first ? t : fmaxf(t, 0.f);
+          const float alpha = first ? 1.f : __builtin_amdgcn_exp2f(-d);
+          l_run[qb] *= alpha;
+          if constexpr (SCORE) l_prior[qb] *= alpha;
+          else {
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
+            for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          sacc[qb][b][i] = __builtin_amdgcn_exp2f(kNegM ? sacc[qb][b][i] : sacc[qb][b][i] - m_ref[qb]);
-          lsum += sacc[qb][b][i];
+              for (int i = 0; i < 16; ++i) o[qb][db][i] *= alpha;
+          }
+          m_ref[qb] += d;
+          if constexpr (kNegM) {
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+              for (int i = 0; i < 16; ++i) sacc[qb][b][i] -= d;
+            negm[qb] = splat16(-m_ref[qb]);
+          }
         }
-      l_run[qb] += lsum;
+        first = false;
+      }
+      bool big = false;
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        float lsum = 0.f;
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            sacc[qb][b][i] = __builtin_amdgcn_exp2f(kNegM ? sacc[qb][b][i] : sacc[qb][b][i] - m_ref[qb]);
+            lsum += sacc[qb][b][i];
+          }
+        big = big || !(lsum < kBig);                         // also catches inf
+        lsum_t[qb] = lsum;
+      }
+      if (redo || !__any(big)) break;
+      redo = true;
     }
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) l_run[qb] += lsum_t[qb];
 
     if constexpr (!SCORE) {
       // ---- O^T += V^T P^T : P^T comes straight from the accumulator registers ----------------
+      // step st = (pg, db): page pg = 2b + u of the tile, 32-dim group db
+      uint4 ring[kDepth];
 #pragma unroll
-      for (int b = 0; b < 2; ++b) {
+      for (int st = 0; st < kDepth; ++st) ring[st] = lds[st * 64 + vx];
+      __builtin_amdgcn_sched_barrier(0);
+      bf16x8 pb[QB];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          bf16x8 pb[QB];
+      for (int st = 0; st < 16; ++st) {
+        const int pg = st >> 2, db = st & 3, b = pg >> 1, u = pg & 1;
+        if (db == 0) {
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
             for (int j = 0; j < 8; ++j) pb[qb][j] = static_cast<bf16_t>(sacc[qb][b][8 * u + j]);
-          const int pg = 2 * b + u;
-#pragma unroll
-          for (int db = 0; db < 4; ++db) {
-            const bf16x8 a = __builtin_bit_cast(bf16x8, lds[(pg * 4 + db) * 64 + vx]);
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-              o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qb], o[qb][db], 0, 0, 0);
-          }
         }
+        const bf16x8 a = __builtin_bit_cast(bf16x8, ring[st % kDepth]);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+          o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qb], o[qb][db], 0, 0, 0);
+        if (st + kDepth < 16) ring[st % kDepth] = lds[(st + kDepth) * 64 + vx];
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
     if (it.valid) {
