@@ -229,9 +229,15 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
   // -m_ref rides in through the MFMA C operand when the 16 extra registers per query block are
   // affordable; otherwise it is subtracted before the exponential.
   constexpr bool kNegM = QB == 1;
+  static_assert(!(SCORE && kNegM), "the deferred score block assumes an explicit subtraction of the reference");
   constexpr int kImage = SCORE ? 1024 : 2048;       // 16-byte pieces per tile image
-  constexpr int kDepth = 4;                         // operand reads in flight ahead of the MFMAs
-  __shared__ uint4 lds_all[2 * kImage];             // double-buffered
+  // operand reads in flight ahead of the MFMAs (16 bytes per lane each); the 256-thread attention
+  // kernel carries twice the staging registers per thread and affords two fewer
+  constexpr int kDepth = (!SCORE && NT == 256) ? 6 : 8;
+  // attention: double-buffered.  score: three images, because the previous tile's image must stay
+  // readable (repair path of its deferred block) while the next tile is being stored.
+  constexpr int kBufs = SCORE ? 3 : 2;
+  __shared__ uint4 lds_all[kBufs * kImage];
   const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
   const int n = lane & 31, hh = lane >> 5;
   const int kvh = blockIdx.x % hkv;
@@ -308,6 +314,7 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
   float m_ref[QB], l_run[QB], l_prior[QB];
   f32x16 negm[QB];
   f32x16 o[QB][SCORE ? 1 : 4];
+  f32x16 sacc[QB][2];                 // S (then p) of the two 32-key blocks in flight
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     m_ref[qb] = 0.f; l_run[qb] = 0.f; l_prior[qb] = 0.f;
@@ -315,8 +322,137 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
 #pragma unroll
     for (int db = 0; db < (SCORE ? 1 : 4); ++db) o[qb][db] = splat16(0.f);
   }
-  bool first = true;
-  float lsum_t[QB];
+
+  // ---- building blocks of the tile pipeline -----------------------------------------------------
+  // S block b of the tile image `img`: 8 k-steps, operand reads kDepth steps ahead of the MFMAs;
+  // `side(kk)` is VALU work of ANOTHER block that is slotted in after every k-step so that it runs
+  // while the matrix pipe is busy.  raw = true ignores the reference (used by the repair path).
+  // The MFMA operands of a tile form one stream of kSteps 16-byte pieces per lane (K pieces of S
+  // block 0, S block 1, then the V pieces of the four pages); `ring` keeps kDepth of them in flight
+  // ahead of the MFMA that consumes them, across the stages of the tile, so that LDS latency is
+  // paid once per tile and not once per stage.
+  constexpr int kSteps = SCORE ? 16 : 32;
+  uint4 ring[kDepth];
+  auto issue = [&](const uint4* img, int t) {          // t: compile-time step index
+    if (t < kSteps)
+      ring[t % kDepth] = t < 16 ? img[t * 64 + kx[t & 3]] : img[(t - 16) * 64 + vx];
+  };
+  auto prime = [&](const uint4* img) {
+#pragma unroll
+    for (int t = 0; t < kDepth; ++t) issue(img, t);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto qk_block = [&](const uint4* img, int b, auto&& side) {
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const int t = b * 8 + kk;
+      const bf16x8 a = __builtin_bit_cast(bf16x8, ring[t % kDepth]);
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb)
+        sacc[qb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+            a, qreg[qb][kk], kk == 0 ? (kNegM ? negm[qb] : splat16(0.f)) : sacc[qb][b], 0, 0, 0);
+      issue(img, t + kDepth);
+      side(kk);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  // repair path only: raw S of block b straight from the image (does not touch the ring)
+  auto qk_block_raw = [&](const uint4* img, int b) {
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const bf16x8 a = __builtin_bit_cast(bf16x8, img[(b * 8 + kk) * 64 + kx[kk & 3]]);
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb)
+        sacc[qb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+            a, qreg[qb][kk], kk == 0 ? splat16(0.f) : sacc[qb][b], 0, 0, 0);
+    }
+  };
+  // exponentials of elements 2kk, 2kk+1 of block b (all query blocks); sums go to lsum[]
+  float lsum[QB];
+  auto exp_pair = [&](int b, int kk) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const int i = 2 * kk + e;
+        const float v = __builtin_amdgcn_exp2f(kNegM ? sacc[qb][b][i] : sacc[qb][b][i] - m_ref[qb]);
+        sacc[qb][b][i] = v;
+        lsum[qb] += v;
+      }
+  };
+  auto no_side = [&](int) {};
+  // padding / causal edge: entries of block b that the query must not see become -inf
+  // (accumulator register i of block b holds key 32b + 16(i/8) + 8hh + i%8 of the tile)
+  auto mask_block = [&](int b, int kpos0, int nvalid) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      int lim = min(nvalid - 1, p[qb] - kpos0) - 8 * hh - 32 * b;
+      asm volatile("" : "+v"(lim));                        // keep the compares inside the branch
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        sacc[qb][b][i] = (16 * (i / 8) + (i % 8) <= lim) ? sacc[qb][b][i] : -INFINITY;
+      asm volatile("" : "+v"(sacc[qb][b]));
+    }
+  };
+  // move the reference of every query up to the maximum of block b (raw S, frame given by
+  // `in_frame`: true if the block already has -m_ref in it); rescale what has been summed so far.
+  auto raise_ref = [&](int b, bool in_frame, bool adjust_other, bool init) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      float t = max16(sacc[qb][b]) - (in_frame ? 0.f : m_ref[qb]);
+      t = fmaxf(t, __shfl_xor(t, 32, 64));
+      const float d = init ? t : fmaxf(t, 0.f);
+      const float alpha = init ? 1.f : __builtin_amdgcn_exp2f(-d);
+      l_run[qb] *= alpha;
+      if constexpr (SCORE) l_prior[qb] *= alpha;
+      else {
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) o[qb][db][i] *= alpha;
+      }
+      m_ref[qb] += d;
+      if constexpr (kNegM) {
+        negm[qb] = splat16(-m_ref[qb]);
+        if (in_frame) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) sacc[qb][b][i] -= d;
+        }
+        if (adjust_other) {                                // a block still waiting for its exponentials
+#pragma unroll
+          for (int i = 0; i < 16; ++i) sacc[qb][1 - b][i] -= d;
+        }
+      }
+    }
+  };
+  // close block b after its exponentials: normally just add the sums.  If a sum is huge or not
+  // finite, entries ran far above the reference: recompute the block's S from the LDS image,
+  // raise the reference (rescaling sums and O), and redo the exponentials.  Rare.
+  auto close_block = [&](const uint4* img, int b, int kpos0, int nvalid, bool edge, bool other_waiting) {
+    bool bad = false;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) bad = bad || !(lsum[qb] < kBig);
+    if (__any(bad)) {
+      asm volatile("" ::: "memory");
+      qk_block_raw(img, b);
+      if (edge) mask_block(b, kpos0, nvalid);
+      raise_ref(b, false, other_waiting, false);
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        lsum[qb] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float v = __builtin_amdgcn_exp2f(sacc[qb][b][i] - m_ref[qb]);
+          sacc[qb][b][i] = v;
+          lsum[qb] += v;
+        }
+      }
+    }
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) { l_run[qb] += lsum[qb]; lsum[qb] = 0.f; }
+  };
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) lsum[qb] = 0.f;
 
   Stager<kPrefetch ? NT : 256, !SCORE> stg;
   TileIter it;
@@ -329,145 +465,93 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
   }
   __syncthreads();
   int buf = 0;
+  bool first = true;
+  // SCORE: block 1 of the previous tile waits in sacc[*][1] for its exponentials, which are
+  // slotted under the next tile's first S block
+  bool pending = false;
+  int prev_kpos0 = 0, prev_nvalid = 0;
+  bool prev_edge = false;
   while (it.valid) {
-    if constexpr (SCORE) {
-      // entering the query's own segment: everything summed so far is prior-chunk mass
-      if (it.s == s_self && it.kt == 0) {
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) { l_prior[qb] = l_run[qb]; l_run[qb] = 0.f; }
-      }
-    }
+    const bool enter_own = SCORE && it.s == s_self && it.kt == 0;
     const int kpos0 = it.kpos0(), nvalid = it.nvalid();
-    const uint4* lds = lds_all + buf * kImage;
+    const bool edge = nvalid < kTile || kpos0 + kTile - 1 > p_min;   // padding or causal edge
+    const uint4* img = lds_all + buf * kImage;
+    const uint4* prev_img = lds_all + ((buf + kBufs - 1) % kBufs) * kImage;
+    const int next_buf = (buf + 1) % kBufs;
     it.advance();
     if constexpr (kPrefetch) {
       if (it.valid) stg.load(block_tab, it.tab0(), it.nvalid());      // next tile: loads in flight
     }
 
-    // ---- S^T = K Q^T and p = exp2(S - m_ref) ---------------------------------------------------------
-    // The exponentials are taken against the current reference without looking at the tile's
-    // maximum; only if a tile's sum shows that entries ran far above the reference (or on the
-    // very first tile, which sets it) is the tile redone with the reference moved up and the
-    // running sums / O rescaled.  The redo recomputes S from the LDS image, which is still there.
-    f32x16 sacc[QB][2];
-    const bool edge = nvalid < kTile || kpos0 + kTile - 1 > p_min;   // padding or causal edge
-    bool redo = first;
-    for (;;) {
-      // operand reads run kDepth steps ahead of the MFMAs that consume them; the scheduling
-      // fences keep that order, so LDS latency hides behind matrix work of the same wave
-      {
-        uint4 ring[kDepth];
+    prime(img);
+    // ---- stage 0: S block 0 ----------------------------------------------------------------------
+    if constexpr (SCORE) {
+      if (pending) {
+        qk_block(img, 0, [&](int kk) { exp_pair(1, kk); });
+        close_block(prev_img, 1, prev_kpos0, prev_nvalid, prev_edge, false);
+      } else {
+        qk_block(img, 0, no_side);
+      }
+      // entering the query's own segment: everything summed so far is prior-chunk mass
+      if (enter_own) {
 #pragma unroll
-        for (int st = 0; st < kDepth; ++st) ring[st] = lds[((st & 1) * 8 + (st >> 1)) * 64 + kx[(st >> 1) & 3]];
-        __builtin_amdgcn_sched_barrier(0);
+        for (int qb = 0; qb < QB; ++qb) { l_prior[qb] = l_run[qb]; l_run[qb] = 0.f; }
+      }
+    } else {
+      qk_block(img, 0, no_side);
+    }
+    if (edge) mask_block(0, kpos0, nvalid);
+    if (first) {                       // key 0 of the request is in this block and visible to all
+      raise_ref(0, kNegM, false, true);
+      first = false;
+    }
+    // ---- stage 1: S block 1, exponentials of block 0 underneath -------------------------------------
+    qk_block(img, 1, [&](int kk) { exp_pair(0, kk); });
+    if (edge) mask_block(1, kpos0, nvalid);
+    close_block(img, 0, kpos0, nvalid, edge, true);
+
+    if constexpr (SCORE) {
+      pending = true; prev_kpos0 = kpos0; prev_nvalid = nvalid; prev_edge = edge;
+    } else {
+      // ---- stages 2, 3: O^T += V^T P^T, P^T straight from the accumulator registers ------------------
+      // block b covers pages 2b, 2b+1 of the tile; step st = (u, db): page 2b+u, 32-dim group db
+      auto pv_block = [&](int b, auto&& side) {
+        bf16x8 pb[QB];
 #pragma unroll
-        for (int st = 0; st < 16; ++st) {
-          const int kk = st >> 1, b = st & 1;
-          const bf16x8 a = __builtin_bit_cast(bf16x8, ring[st % kDepth]);
+        for (int st = 0; st < 8; ++st) {
+          const int u = st >> 2, db = st & 3, t = 16 + b * 8 + st;
+          if (db == 0) {
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+              for (int j = 0; j < 8; ++j) pb[qb][j] = static_cast<bf16_t>(sacc[qb][b][8 * u + j]);
+          }
+          const bf16x8 a = __builtin_bit_cast(bf16x8, ring[t % kDepth]);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb)
-            sacc[qb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                a, qreg[qb][kk], kk == 0 ? (kNegM ? negm[qb] : splat16(0.f)) : sacc[qb][b], 0, 0, 0);
-          if (st + kDepth < 16) {
-            const int s2 = st + kDepth;
-            ring[st % kDepth] = lds[((s2 & 1) * 8 + (s2 >> 1)) * 64 + kx[(s2 >> 1) & 3]];
-          }
+            o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qb], o[qb][db], 0, 0, 0);
+          issue(img, t + kDepth);
+          side(st);
           __builtin_amdgcn_sched_barrier(0);
         }
-      }
-      // accumulator register i of block b holds key 32b + 16(i/8) + 8hh + i%8 of the tile
-      if (edge) {
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-          int lim = min(nvalid - 1, p[qb] - kpos0) - 8 * hh;
-          asm volatile("" : "+v"(lim));                    // the compares must not be hoisted out
-#pragma unroll
-          for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-              sacc[qb][b][i] = (32 * b + 16 * (i / 8) + (i % 8) <= lim) ? sacc[qb][b][i] : -INFINITY;
-          // opaque to the optimiser, so that the masking stays inside this rarely taken branch
-          asm volatile("" : "+v"(sacc[qb][0]), "+v"(sacc[qb][1]));
-        }
-      }
-      if (redo) {
-        asm volatile("" ::: "memory");
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-          float t = fmaxf(max16(sacc[qb][0]), max16(sacc[qb][1])) - (kNegM ? 0.f : m_ref[qb]);
-          t = fmaxf(t, __shfl_xor(t, 32, 64));
-          const float d = first ? t : fmaxf(t, 0.f);
-          const float alpha = first ? 1.f : __builtin_amdgcn_exp2f(-d);
-          l_run[qb] *= alpha;
-          if constexpr (SCORE) l_prior[qb] *= alpha;
-          else {
-#pragma unroll
-            for (int db = 0; db < 4; ++db)
-#pragma unroll
-              for (int i = 0; i < 16; ++i) o[qb][db][i] *= alpha;
-          }
-          m_ref[qb] += d;
-          if constexpr (kNegM) {
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-#pragma unroll
-              for (int i = 0; i < 16; ++i) sacc[qb][b][i] -= d;
-            negm[qb] = splat16(-m_ref[qb]);
-          }
-        }
-        first = false;
-      }
-      bool big = false;
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        float lsum = 0.f;
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            sacc[qb][b][i] = __builtin_amdgcn_exp2f(kNegM ? sacc[qb][b][i] : sacc[qb][b][i] - m_ref[qb]);
-            lsum += sacc[qb][b][i];
-          }
-        big = big || !(lsum < kBig);                         // also catches inf
-        lsum_t[qb] = lsum;
-      }
-      if (redo || !__any(big)) break;
-      redo = true;
-    }
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) l_run[qb] += lsum_t[qb];
-
-    if constexpr (!SCORE) {
-      // ---- O^T += V^T P^T : P^T comes straight from the accumulator registers ----------------
-      // step st = (pg, db): page pg = 2b + u of the tile, 32-dim group db
-      uint4 ring[kDepth];
-#pragma unroll
-      for (int st = 0; st < kDepth; ++st) ring[st] = lds[st * 64 + vx];
-      __builtin_amdgcn_sched_barrier(0);
-      bf16x8 pb[QB];
-#pragma unroll
-      for (int st = 0; st < 16; ++st) {
-        const int pg = st >> 2, db = st & 3, b = pg >> 1, u = pg & 1;
-        if (db == 0) {
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) pb[qb][j] = static_cast<bf16_t>(sacc[qb][b][8 * u + j]);
-        }
-        const bf16x8 a = __builtin_bit_cast(bf16x8, ring[st % kDepth]);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-          o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qb], o[qb][db], 0, 0, 0);
-        if (st + kDepth < 16) ring[st % kDepth] = lds[(st + kDepth) * 64 + vx];
-        __builtin_amdgcn_sched_barrier(0);
-      }
+      };
+      pv_block(0, [&](int st) { exp_pair(1, st); });
+      close_block(img, 1, kpos0, nvalid, edge, false);
+      pv_block(1, no_side);
     }
     if (it.valid) {
-      if constexpr (kPrefetch) stg.store(lds_all + (buf ^ 1) * kImage);
-      else stage_direct<NT, !SCORE>(lds_all + (buf ^ 1) * kImage, k_pool, v_pool, n_blocks, block_tab, it.tab0(), it.nvalid(), hkv, kvh, tid);
+      if constexpr (kPrefetch) stg.store(lds_all + next_buf * kImage);
+      else stage_direct<NT, !SCORE>(lds_all + next_buf * kImage, k_pool, v_pool, n_blocks, block_tab, it.tab0(), it.nvalid(), hkv, kvh, tid);
     }
     __syncthreads();
-    buf ^= 1;
+    buf = next_buf;
+  }
+  if constexpr (SCORE) {
+    if (pending) {                     // exponentials of the very last block
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) exp_pair(1, kk);
+      close_block(lds_all + ((buf + kBufs - 1) % kBufs) * kImage, 1, prev_kpos0, prev_nvalid, prev_edge, false);
+    }
   }
 
   // ---- epilogue ---------------------------------------------------------------------------------
