@@ -98,11 +98,15 @@ int cc_rope_shift(cc_ctx* ctx, const void* k_src_pool, const void* v_src_pool, i
   return cc::check_launch(ctx, fn);
 }
 
-// workspace of cc_select: [mass: n_tok * Hq floats][keys: n_tok uint32]
+// upper bound on the number of 64-key tiles of n_tok tokens spread over n_segs segments
+static int max_tiles_for(int32_t n_tok, int32_t n_segs) { return n_tok / 64 + n_segs + 1; }
+
+// workspace of cc_select: [mass: n_tok * Hq floats][keys: n_tok uint32][tile plan]
 size_t cc_select_workspace_bytes(const cc_ctx* ctx, int32_t n_tok, int32_t n_segs) {
   if (ctx == nullptr || n_tok < 0 || n_segs < 0) return 0;
   return cc::align_up(static_cast<size_t>(n_tok) * ctx->cfg.n_q_heads * sizeof(float), 256) +
-         cc::align_up(static_cast<size_t>(n_tok) * sizeof(uint32_t), 256) + 256;
+         cc::align_up(static_cast<size_t>(n_tok) * sizeof(uint32_t), 256) +
+         cc::align_up(cc::mfma_plan_bytes(n_segs, max_tiles_for(n_tok, n_segs)), 256) + 256;
 }
 
 int cc_select(cc_ctx* ctx, const void* q, int32_t n_tok, const void* k_pool, int32_t n_blocks,
@@ -127,9 +131,10 @@ int cc_select(cc_ctx* ctx, const void* q, int32_t n_tok, const void* k_pool, int
   uint32_t* keys = reinterpret_cast<uint32_t*>(
       static_cast<char*>(workspace) +
       cc::align_up(static_cast<size_t>(n_tok) * ctx->cfg.n_q_heads * sizeof(float), 256));
+  void* plan_ws = reinterpret_cast<char*>(keys) + cc::align_up(static_cast<size_t>(n_tok) * sizeof(uint32_t), 256);
   if (ctx->impl == CC_IMPL_AUTO && cc::score_mfma_supported(ctx))
     cc::launch_score_mfma(ctx, q, k_pool, n_blocks, block_tab, segs, n_segs, req_seg_off,
-                          max_seg_tokens, mass, st);
+                          max_seg_tokens, mass, plan_ws, max_tiles_for(n_tok, n_segs), st);
   else
     cc::launch_score_scalar(ctx, q, k_pool, n_blocks, block_tab, segs, n_segs, req_seg_off,
                             max_seg_tokens, mass, st);
@@ -165,20 +170,22 @@ int cc_qkv_project(cc_ctx* ctx, const void* x, const void* w_qkv, int32_t n_rows
   return cc::check_launch(ctx, fn);
 }
 
-size_t cc_sparse_prefill_workspace_bytes(const cc_ctx* ctx, int32_t n_q_tot, int32_t n_requests) {
-  if (ctx == nullptr || n_q_tot < 0 || n_requests < 0) return 0;
-  return 256;
+size_t cc_sparse_prefill_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_tokens, int32_t n_segs) {
+  if (ctx == nullptr || n_ctx_tokens < 0 || n_segs < 0) return 0;
+  return cc::align_up(cc::mfma_plan_bytes(n_segs, max_tiles_for(n_ctx_tokens, n_segs)), 256) + 256;
 }
 
 int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void* v_new,
                       const int32_t* q_pos, const int32_t* slot_map, const int32_t* cu_q,
                       int32_t n_q_tot, int32_t max_q_per_req, void* k_pool, void* v_pool,
                       int32_t n_blocks, const int32_t* block_tab, const cc_segment* segs,
-                      int32_t n_segs, const int32_t* req_seg_off, int32_t n_requests, void* out,
-                      float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+                      int32_t n_segs, const int32_t* req_seg_off, int32_t n_requests,
+                      int32_t n_ctx_tokens, void* out, float* lse, void* workspace,
+                      size_t workspace_bytes, void* stream) {
   static const char* fn = "cc_sparse_prefill";
   if (ctx == nullptr) return CC_ERR_INVALID_ARG;
-  CC_REQUIRE(n_q_tot >= 0 && max_q_per_req >= 0 && n_segs >= 0 && n_requests >= 0, "negative count");
+  CC_REQUIRE(n_q_tot >= 0 && max_q_per_req >= 0 && n_segs >= 0 && n_requests >= 0 && n_ctx_tokens >= 0,
+             "negative count");
   CC_REQUIRE(max_q_per_req <= n_q_tot, "max_q_per_req exceeds n_q_tot");
   if (n_q_tot == 0) return CC_OK;
   CC_REQUIRE(q && k_new && v_new && q_pos && slot_map && cu_q && k_pool && v_pool && block_tab &&
@@ -187,15 +194,16 @@ int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void*
   CC_REQUIRE(n_requests <= 65535, "more than 65535 requests in one call");
   CC_REQUIRE(aligned16(q) && aligned16(k_new) && aligned16(v_new) && aligned16(k_pool) &&
                  aligned16(v_pool) && aligned16(out), "tensors must be 16-byte aligned");
-  if (workspace_bytes < cc_sparse_prefill_workspace_bytes(ctx, n_q_tot, n_requests) ||
-      (workspace == nullptr && cc_sparse_prefill_workspace_bytes(ctx, n_q_tot, n_requests) > 0))
+  CC_REQUIRE(workspace != nullptr && aligned16(workspace), "workspace missing or misaligned");
+  if (workspace_bytes < cc_sparse_prefill_workspace_bytes(ctx, n_ctx_tokens, n_segs))
     return fail(ctx, CC_ERR_WORKSPACE_TOO_SMALL,
                 "cc_sparse_prefill: workspace smaller than cc_sparse_prefill_workspace_bytes()");
   hipStream_t st = static_cast<hipStream_t>(stream);
   cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_q_tot, k_pool, v_pool, n_blocks, st);
   if (ctx->impl == CC_IMPL_AUTO && cc::attn_mfma_supported(ctx))
     cc::launch_attn_mfma(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks,
-                         block_tab, segs, req_seg_off, n_requests, out, lse, st);
+                         block_tab, segs, n_segs, req_seg_off, n_requests, out, lse, workspace,
+                         max_tiles_for(n_ctx_tokens, n_segs), st);
   else
     cc::launch_attn_scalar(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks,
                            block_tab, segs, req_seg_off, n_requests, out, lse, st);

@@ -49,10 +49,12 @@ void launch_score_scalar(const cc_ctx* ctx, const void* q, const void* k_pool, i
                          const int32_t* req_seg_off, int max_seg_tokens, float* mass,
                          hipStream_t stream);
 bool score_mfma_supported(const cc_ctx* ctx);
+// bytes of the tile plan (per-segment tile offsets + tile descriptors) the MFMA kernels need
+size_t mfma_plan_bytes(int n_segs, int max_tiles);
 void launch_score_mfma(const cc_ctx* ctx, const void* q, const void* k_pool, int n_blocks,
                        const int32_t* block_tab, const cc_segment* segs, int n_segs,
                        const int32_t* req_seg_off, int max_seg_tokens, float* mass,
-                       hipStream_t stream);
+                       void* plan_ws, int max_tiles, hipStream_t stream);
 void launch_topn(const cc_ctx* ctx, const float* mass, const int32_t* block_tab,
                  const cc_segment* segs, int n_segs, int32_t* sel_idx, int32_t* q_row,
                  int32_t* q_pos, int32_t* slot_map, float* scores, uint32_t* key_buf,
@@ -69,9 +71,9 @@ void launch_attn_scalar(const cc_ctx* ctx, const void* q, const int32_t* q_pos, 
 bool attn_mfma_supported(const cc_ctx* ctx);
 void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
                       int n_q_tot, int max_q_per_req, const void* k_pool, const void* v_pool,
-                      int n_blocks, const int32_t* block_tab, const cc_segment* segs,
+                      int n_blocks, const int32_t* block_tab, const cc_segment* segs, int n_segs,
                       const int32_t* req_seg_off, int n_requests, void* out, float* lse,
-                      hipStream_t stream);
+                      void* plan_ws, int max_tiles, hipStream_t stream);
 
 void launch_qkv_project(const cc_ctx* ctx, const void* x, const void* w, int n_rows, int hidden,
                         void* q, void* k, void* v, hipStream_t stream);

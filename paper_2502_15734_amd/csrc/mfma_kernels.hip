@@ -42,35 +42,40 @@ constexpr float kBig = 1.0e12f;                // a tile sum above this moves th
 __device__ __forceinline__ int swap23(int m) { return (m & ~12) | ((m & 4) << 1) | ((m & 8) >> 1); }
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
-// Walks the key tiles of one request in prompt order, up to logical position p_max.  All state is
-// wave-uniform (scalar registers).
-struct TileIter {
-  const cc_segment* segs;
-  int s, s_end, p_max;
-  int kt, n_kt, seg_start, seg_ntok, seg_tab;
-  bool valid;
-  __device__ __forceinline__ void init(const cc_segment* sg, int s_begin, int s_end_, int p_max_) {
-    segs = sg; s = s_begin - 1; s_end = s_end_; p_max = p_max_;
-    kt = 0; n_kt = 0; seg_start = 0; seg_ntok = 0; seg_tab = 0; valid = true;
-    advance();
-  }
-  __device__ __forceinline__ void advance() {
-    ++kt;
-    while (kt >= n_kt) {
-      ++s;
-      if (s >= s_end) { valid = false; return; }
-      const cc_segment g = segs[s];
-      if (g.logical_start > p_max) { valid = false; return; }
-      seg_start = g.logical_start; seg_ntok = g.n_tokens; seg_tab = g.tab_off;
-      const int n_keys = min(g.n_tokens, p_max - g.logical_start + 1);
-      n_kt = (n_keys + kTile - 1) / kTile;
-      kt = 0;
-    }
-  }
-  __device__ __forceinline__ int kpos0() const { return seg_start + kTile * kt; }
-  __device__ __forceinline__ int nvalid() const { return min(kTile, seg_ntok - kTile * kt); }
-  __device__ __forceinline__ int tab0() const { return seg_tab + (kTile / kBlock) * kt; }
+// One key tile as the plan kernels lay it out (32 bytes, read with two 16-byte loads).
+struct TileDesc {
+  int32_t kpos0;     // logical position of the tile's first key
+  int32_t nvalid;    // keys of the tile that exist (1..64); the rest is block padding
+  int32_t blk[4];    // physical block of each of the four 16-token pages (-1: none)
+  int32_t seg;       // segment the tile belongs to
+  int32_t pad;
 };
+static_assert(sizeof(TileDesc) == 32, "descriptor is read as two 16-byte vectors");
+
+// a descriptor that came in through a (broadcast) vector load, moved to scalar registers
+__device__ __forceinline__ TileDesc to_scalar(const TileDesc& v) {
+  TileDesc d;
+  d.kpos0 = __builtin_amdgcn_readfirstlane(v.kpos0);
+  d.nvalid = __builtin_amdgcn_readfirstlane(v.nvalid);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) d.blk[i] = __builtin_amdgcn_readfirstlane(v.blk[i]);
+  d.seg = 0;
+  d.pad = 0;
+  return d;
+}
+
+// The index is laundered through a vector register on purpose: a scalar (SMEM) load here would
+// share the LDS operand reads' completion counter, return out of order, and force a full drain
+// of the operand ring every tile; a broadcast vector load is counted with the global loads.
+__device__ __forceinline__ TileDesc fetch_desc(const TileDesc* __restrict__ tiles, int j, int max_tiles) {
+  int jj = min(max(j, 0), max_tiles - 1);
+  asm volatile("" : "+v"(jj));
+  const uint4* src = reinterpret_cast<const uint4*>(tiles + jj);
+  union { uint4 v[2]; TileDesc d; } u;
+  u.v[0] = src[0];
+  u.v[1] = src[1];
+  return u.d;
+}
 
 // LDS piece index of piece `cc_` (0..255, pool order) of page `pg` of the K / V tile image.
 __device__ __forceinline__ int k_piece_dst(int pg, int cc_) {
@@ -95,8 +100,9 @@ __device__ __forceinline__ uint4 zero_pad_slots(uint4 val, int hh, int nv) {
 // or 512 threads.  A thread owns the same 16-byte piece of every page it stages (thread t ->
 // piece t % 256, so a wavefront instruction reads one contiguous KiB of a page); with 512 threads
 // the lower half of the workgroup takes pages {0,1} and the upper half pages {2,3}.  Block ids
-// are fetched with scalar loads first, then all data loads are issued back to back, one tile
-// ahead of their use (load), and written to the LDS image after the current tile's math (store).
+// come from the tile descriptor (already in registers), so all data loads are issued back to back
+// with no memory access in between, one tile ahead of their use (load), and are written to the
+// LDS image later (store).
 // Slots past the segment's end are staged as zeros so that stale or non-finite padding can never
 // reach a product.
 template <int NT, bool WITH_V>
@@ -120,13 +126,13 @@ struct Stager {
     n_blocks = n_blocks_;
   }
 
-  __device__ __forceinline__ void load(const int32_t* __restrict__ block_tab, int tab0, int nvalid) {
+  __device__ __forceinline__ void load(const TileDesc& d) {
+    const int nvalid = uniform(d.nvalid);
     int blk[kPagesPerThread];
     bool all_ok = nvalid == kTile;
 #pragma unroll
     for (int j = 0; j < kPagesPerThread; ++j) {
-      const int pg = pg0 + j;
-      blk[j] = (kBlock * pg < nvalid) ? block_tab[tab0 + pg] : -1;
+      blk[j] = uniform(NT == 512 ? (pg0 ? d.blk[2 + j] : d.blk[j]) : d.blk[j]);
       all_ok = all_ok && blk[j] >= 0 && blk[j] < n_blocks;
     }
     if (all_ok) {                                            // whole tile present (wave-uniform)
@@ -142,7 +148,7 @@ struct Stager {
     for (int j = 0; j < kPagesPerThread; ++j) {
       const int pg = pg0 + j;
       const int nv = min(max(nvalid - kBlock * pg, 0), kBlock);
-      const bool ok = blk[j] >= 0 && blk[j] < n_blocks;
+      const bool ok = nv > 0 && blk[j] >= 0 && blk[j] < n_blocks;
       uint4 kv = make_uint4(0u, 0u, 0u, 0u), vv = make_uint4(0u, 0u, 0u, 0u);
       if (ok) {
         if ((in_page >> 4) < nv)                             // token slot of this K piece
@@ -171,8 +177,8 @@ struct Stager {
 template <int NT, bool WITH_V>
 __device__ __forceinline__ void stage_direct(uint4* lds, const bf16_t* __restrict__ k_pool,
                                              const bf16_t* __restrict__ v_pool, int n_blocks,
-                                             const int32_t* __restrict__ block_tab, int tab0,
-                                             int nvalid, int hkv, int kvh, int tid) {
+                                             const TileDesc& d, int hkv, int kvh, int tid) {
+  const int nvalid = d.nvalid;
   constexpr int kPieces = WITH_V ? 2048 : 1024;
 #pragma unroll 4
   for (int i = 0; i < kPieces / NT; ++i) {
@@ -180,9 +186,8 @@ __device__ __forceinline__ void stage_direct(uint4* lds, const bf16_t* __restric
     const bool is_v = WITH_V && c >= 1024;
     const int pg = (c & 1023) >> 8, cc_ = c & 255;
     const int nv = min(max(nvalid - kBlock * pg, 0), kBlock);
-    int blk = -1;
-    if (nv > 0) blk = block_tab[tab0 + pg];
-    const bool ok = blk >= 0 && blk < n_blocks;
+    const int blk = d.blk[pg];
+    const bool ok = nv > 0 && blk >= 0 && blk < n_blocks;
     const size_t off = (static_cast<size_t>(ok ? blk : 0) * hkv + kvh) * (kBlock * kD) + cc_ * 8;
     uint4 val = make_uint4(0u, 0u, 0u, 0u);
     if (ok) {
@@ -220,9 +225,10 @@ template <int G, bool SCORE, int QB>
 __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
     const bf16_t* __restrict__ q, const int32_t* __restrict__ q_pos, const int32_t* __restrict__ cu_q,
     const bf16_t* __restrict__ k_pool, const bf16_t* __restrict__ v_pool, int n_blocks,
-    const int32_t* __restrict__ block_tab, const cc_segment* __restrict__ segs,
-    const int32_t* __restrict__ req_seg_off, int hq, int hkv, int n_tiles_x, InvFreq inv_freq,
-    bf16_t* __restrict__ out, float* __restrict__ lse, float* __restrict__ mass) {
+    const TileDesc* __restrict__ tiles, const int32_t* __restrict__ seg_tile_off, int max_tiles,
+    const cc_segment* __restrict__ segs, const int32_t* __restrict__ req_seg_off, int hq, int hkv,
+    int n_tiles_x, InvFreq inv_freq, bf16_t* __restrict__ out, float* __restrict__ lse,
+    float* __restrict__ mass) {
   constexpr int NT = 64 * G;
   constexpr int TQ = 32 * QB;                       // query tokens per workgroup
   constexpr bool kPrefetch = NT >= 256;
@@ -231,9 +237,9 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
   constexpr bool kNegM = QB == 1;
   static_assert(!(SCORE && kNegM), "the deferred score block assumes an explicit subtraction of the reference");
   constexpr int kImage = SCORE ? 1024 : 2048;       // 16-byte pieces per tile image
-  // operand reads in flight ahead of the MFMAs (16 bytes per lane each); the 256-thread attention
-  // kernel carries twice the staging registers per thread and affords two fewer
-  constexpr int kDepth = (!SCORE && NT == 256) ? 6 : 8;
+  // operand reads in flight ahead of the MFMAs (16 bytes per lane each)
+  constexpr int kDepth = 8;
+  static_assert(16 % kDepth == 0, "ring slots must line up from one tile to the next");
   // attention: double-buffered.  score: three images, because the previous tile's image must stay
   // readable (repair path of its deferred block) while the next tile is being stored.
   constexpr int kBufs = SCORE ? 3 : 2;
@@ -333,16 +339,22 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
   // paid once per tile and not once per stage.
   constexpr int kSteps = SCORE ? 16 : 32;
   uint4 ring[kDepth];
-  auto issue = [&](const uint4* img, int t) {          // t: compile-time step index
-    if (t < kSteps)
+  // step t of the current image; steps >= kSteps are the first K pieces of the next image `nimg`
+  // (nullptr: there is no next tile, or it may not be read yet)
+  auto issue = [&](const uint4* img, const uint4* nimg, int t) {   // t: compile-time step index
+    if (t < kSteps) {
       ring[t % kDepth] = t < 16 ? img[t * 64 + kx[t & 3]] : img[(t - 16) * 64 + vx];
+    } else if (nimg != nullptr) {
+      const int t2 = t - kSteps;
+      ring[t % kDepth] = nimg[t2 * 64 + kx[t2 & 3]];
+    }
   };
   auto prime = [&](const uint4* img) {
 #pragma unroll
-    for (int t = 0; t < kDepth; ++t) issue(img, t);
+    for (int t = 0; t < kDepth; ++t) issue(img, nullptr, t);
     __builtin_amdgcn_sched_barrier(0);
   };
-  auto qk_block = [&](const uint4* img, int b, auto&& side) {
+  auto qk_block = [&](const uint4* img, const uint4* nimg, int b, auto&& side) {
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
       const int t = b * 8 + kk;
@@ -351,7 +363,7 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
       for (int qb = 0; qb < QB; ++qb)
         sacc[qb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
             a, qreg[qb][kk], kk == 0 ? (kNegM ? negm[qb] : splat16(0.f)) : sacc[qb][b], 0, 0, 0);
-      issue(img, t + kDepth);
+      issue(img, nimg, t + kDepth);
       side(kk);
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -454,43 +466,62 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) lsum[qb] = 0.f;
 
+  // ---- the tile loop ------------------------------------------------------------------------------
+  // Tiles of the request are listed by the plan kernels; tile j is usable if j < j_end and its
+  // first key is visible to some query of the workgroup.  Three things run ahead of the math of
+  // tile t: the descriptor of tile t+3 (a broadcast vector load), the global loads of tile t+2
+  // (into registers, issued right after the barrier), and the LDS image of tile t+1 (stored in the
+  // middle of tile t).  The workgroup barrier sits before the last stage of a tile, whose operands
+  // are already in registers, so that the first operand reads of the next image are in flight
+  // while that stage's MFMAs run.
+  const int j_begin = seg_tile_off[s_begin];
+  const int j_end = min(seg_tile_off[s_end], max_tiles);
+  const int j_own = SCORE ? seg_tile_off[s_self] : -1;
+  auto usable = [&](const TileDesc& d, int j) { return j < j_end && uniform(d.kpos0) <= p_max; };
+
   Stager<kPrefetch ? NT : 256, !SCORE> stg;
-  TileIter it;
-  it.init(segs, s_begin, s_end, p_max);
-  if constexpr (kPrefetch) {
-    stg.init(k_pool, v_pool, n_blocks, hkv, kvh, tid);
-    if (it.valid) { stg.load(block_tab, it.tab0(), it.nvalid()); stg.store(lds_all); }
-  } else {
-    if (it.valid) stage_direct<NT, !SCORE>(lds_all, k_pool, v_pool, n_blocks, block_tab, it.tab0(), it.nvalid(), hkv, kvh, tid);
-  }
-  __syncthreads();
+  if constexpr (kPrefetch) stg.init(k_pool, v_pool, n_blocks, hkv, kvh, tid);
+  auto stage_load = [&](const TileDesc& d) {            // global -> registers
+    if constexpr (kPrefetch) stg.load(d);
+  };
+  auto stage_store = [&](const TileDesc& d, int b_) {   // registers (or global) -> LDS image b_
+    if constexpr (kPrefetch) stg.store(lds_all + b_ * kImage);
+    else stage_direct<NT, !SCORE>(lds_all + b_ * kImage, k_pool, v_pool, n_blocks, d, hkv, kvh, tid);
+  };
+
+  int j = j_begin;
+  TileDesc d0 = to_scalar(fetch_desc(tiles, j, max_tiles));
+  TileDesc d1 = to_scalar(fetch_desc(tiles, j + 1, max_tiles));
+  TileDesc d2 = to_scalar(fetch_desc(tiles, j + 2, max_tiles));
+  bool v0 = usable(d0, j), v1 = v0 && usable(d1, j + 1), v2 = v1 && usable(d2, j + 2);
   int buf = 0;
+  if (v0) { stage_load(d0); stage_store(d0, 0); }
+  if (v1) stage_load(d1);
+  __syncthreads();
+  if (v0) prime(lds_all);
   bool first = true;
   // SCORE: block 1 of the previous tile waits in sacc[*][1] for its exponentials, which are
   // slotted under the next tile's first S block
   bool pending = false;
   int prev_kpos0 = 0, prev_nvalid = 0;
   bool prev_edge = false;
-  while (it.valid) {
-    const bool enter_own = SCORE && it.s == s_self && it.kt == 0;
-    const int kpos0 = it.kpos0(), nvalid = it.nvalid();
+  while (v0) {
+    const bool enter_own = SCORE && j == j_own;
+    const int kpos0 = uniform(d0.kpos0), nvalid = uniform(d0.nvalid);
     const bool edge = nvalid < kTile || kpos0 + kTile - 1 > p_min;   // padding or causal edge
-    const uint4* img = lds_all + buf * kImage;
-    const uint4* prev_img = lds_all + ((buf + kBufs - 1) % kBufs) * kImage;
     const int next_buf = (buf + 1) % kBufs;
-    it.advance();
-    if constexpr (kPrefetch) {
-      if (it.valid) stg.load(block_tab, it.tab0(), it.nvalid());      // next tile: loads in flight
-    }
+    const uint4* img = lds_all + buf * kImage;
+    const uint4* next_img = lds_all + next_buf * kImage;
+    const uint4* prev_img = lds_all + ((buf + kBufs - 1) % kBufs) * kImage;
+    TileDesc d3 = fetch_desc(tiles, j + 3, max_tiles);             // three tiles ahead
 
-    prime(img);
     // ---- stage 0: S block 0 ----------------------------------------------------------------------
     if constexpr (SCORE) {
       if (pending) {
-        qk_block(img, 0, [&](int kk) { exp_pair(1, kk); });
+        qk_block(img, nullptr, 0, [&](int kk) { exp_pair(1, kk); });
         close_block(prev_img, 1, prev_kpos0, prev_nvalid, prev_edge, false);
       } else {
-        qk_block(img, 0, no_side);
+        qk_block(img, nullptr, 0, no_side);
       }
       // entering the query's own segment: everything summed so far is prior-chunk mass
       if (enter_own) {
@@ -498,24 +529,32 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
         for (int qb = 0; qb < QB; ++qb) { l_prior[qb] = l_run[qb]; l_run[qb] = 0.f; }
       }
     } else {
-      qk_block(img, 0, no_side);
+      qk_block(img, nullptr, 0, no_side);
     }
     if (edge) mask_block(0, kpos0, nvalid);
     if (first) {                       // key 0 of the request is in this block and visible to all
       raise_ref(0, kNegM, false, true);
       first = false;
     }
-    // ---- stage 1: S block 1, exponentials of block 0 underneath -------------------------------------
-    qk_block(img, 1, [&](int kk) { exp_pair(0, kk); });
-    if (edge) mask_block(1, kpos0, nvalid);
-    close_block(img, 0, kpos0, nvalid, edge, true);
-
     if constexpr (SCORE) {
+      // all operand reads of this image are issued; publish the next image and meet
+      if (v1) stage_store(d1, next_buf);
+      __syncthreads();
+      if (v2) stage_load(d2);
+      // ---- stage 1: S block 1, exponentials of block 0 underneath; first reads of the next image
+      qk_block(img, v1 ? next_img : nullptr, 1, [&](int kk) { exp_pair(0, kk); });
+      if (edge) mask_block(1, kpos0, nvalid);
+      close_block(img, 0, kpos0, nvalid, edge, false);
       pending = true; prev_kpos0 = kpos0; prev_nvalid = nvalid; prev_edge = edge;
     } else {
+      // ---- stage 1: S block 1, exponentials of block 0 underneath -----------------------------------
+      qk_block(img, nullptr, 1, [&](int kk) { exp_pair(0, kk); });
+      if (edge) mask_block(1, kpos0, nvalid);
+      close_block(img, 0, kpos0, nvalid, edge, true);
+      if (v1) stage_store(d1, next_buf);
       // ---- stages 2, 3: O^T += V^T P^T, P^T straight from the accumulator registers ------------------
       // block b covers pages 2b, 2b+1 of the tile; step st = (u, db): page 2b+u, 32-dim group db
-      auto pv_block = [&](int b, auto&& side) {
+      auto pv_block = [&](const uint4* nimg, int b, auto&& side) {
         bf16x8 pb[QB];
 #pragma unroll
         for (int st = 0; st < 8; ++st) {
@@ -524,26 +563,28 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-              for (int j = 0; j < 8; ++j) pb[qb][j] = static_cast<bf16_t>(sacc[qb][b][8 * u + j]);
+              for (int jj = 0; jj < 8; ++jj) pb[qb][jj] = static_cast<bf16_t>(sacc[qb][b][8 * u + jj]);
           }
           const bf16x8 a = __builtin_bit_cast(bf16x8, ring[t % kDepth]);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb)
             o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qb], o[qb][db], 0, 0, 0);
-          issue(img, t + kDepth);
+          issue(img, nimg, t + kDepth);
           side(st);
           __builtin_amdgcn_sched_barrier(0);
         }
       };
-      pv_block(0, [&](int st) { exp_pair(1, st); });
+      pv_block(nullptr, 0, [&](int st) { exp_pair(1, st); });
       close_block(img, 1, kpos0, nvalid, edge, false);
-      pv_block(1, no_side);
+      // every read of this image has been issued; meet, then finish the tile out of registers
+      // while the first operand reads of the next image are in flight
+      __syncthreads();
+      if (v2) stage_load(d2);
+      pv_block(v1 ? next_img : nullptr, 1, no_side);
     }
-    if (it.valid) {
-      if constexpr (kPrefetch) stg.store(lds_all + next_buf * kImage);
-      else stage_direct<NT, !SCORE>(lds_all + next_buf * kImage, k_pool, v_pool, n_blocks, block_tab, it.tab0(), it.nvalid(), hkv, kvh, tid);
-    }
-    __syncthreads();
+    ++j;
+    d0 = d1; d1 = d2; d2 = to_scalar(d3);
+    v0 = v1; v1 = v2; v2 = v2 && usable(d2, j + 2);
     buf = next_buf;
   }
   if constexpr (SCORE) {
@@ -582,35 +623,111 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
   }
 }
 
+// ---- plan: the key tiles of every segment, in prompt order ---------------------------------------
+// seg_tile_off[s] = number of tiles before segment s (exclusive scan of ceil(n_tokens/64)).
+__global__ __launch_bounds__(256) void plan_scan_kernel(const cc_segment* __restrict__ segs, int n_segs,
+                                                         int32_t* __restrict__ seg_tile_off) {
+  __shared__ int wsum[4];
+  __shared__ int carry_s;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  if (tid == 0) carry_s = 0;
+  __syncthreads();
+  for (int s0 = 0; s0 < n_segs; s0 += 256) {
+    const int s = s0 + tid;
+    const int nt = s < n_segs ? (max(segs[s].n_tokens, 0) + kTile - 1) / kTile : 0;
+    int incl = nt;                                   // inclusive scan inside the wavefront
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int up = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += up;
+    }
+    if (lane == 63) wsum[w] = incl;
+    __syncthreads();
+    int base = carry_s;
+    for (int ww = 0; ww < w; ++ww) base += wsum[ww];
+    if (s < n_segs) seg_tile_off[s] = base + incl - nt;
+    __syncthreads();
+    if (tid == 255) carry_s = base + incl;
+    __syncthreads();
+  }
+  if (tid == 0) seg_tile_off[n_segs] = carry_s;
+}
+
+__global__ __launch_bounds__(256) void plan_fill_kernel(const cc_segment* __restrict__ segs, int n_segs,
+                                                         const int32_t* __restrict__ seg_tile_off,
+                                                         const int32_t* __restrict__ block_tab, int n_blocks,
+                                                         int max_tiles, TileDesc* __restrict__ tiles) {
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= min(seg_tile_off[n_segs], max_tiles)) return;
+  int lo = 0, hi = n_segs - 1;                       // last segment with seg_tile_off[s] <= j
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (seg_tile_off[mid] <= j) lo = mid; else hi = mid - 1;
+  }
+  const cc_segment sg = segs[lo];
+  const int kt = j - seg_tile_off[lo];
+  TileDesc d;
+  d.kpos0 = sg.logical_start + kTile * kt;
+  d.nvalid = min(kTile, sg.n_tokens - kTile * kt);
+  for (int i = 0; i < 4; ++i) {
+    int b = -1;
+    if (kBlock * i < d.nvalid) b = block_tab[sg.tab_off + (kTile / kBlock) * kt + i];
+    d.blk[i] = (b >= 0 && b < n_blocks) ? b : -1;
+  }
+  d.seg = lo;
+  d.pad = 0;
+  tiles[j] = d;
+}
+
 constexpr int kAttnQB = 1;     // 32 query tokens per workgroup in the attention kernel
 constexpr int kScoreQB = 2;    // 64 in the score kernel (no O accumulator, so registers allow it)
+
+size_t plan_bytes_impl(int n_segs, int max_tiles) {
+  return (static_cast<size_t>(n_segs + 1) * sizeof(int32_t) + 255) / 256 * 256 +
+         static_cast<size_t>(max_tiles) * sizeof(TileDesc);
+}
+
+struct Plan { int32_t* seg_tile_off; TileDesc* tiles; int max_tiles; };
+
+Plan run_plan(void* ws, const cc_segment* segs, int n_segs, const int32_t* block_tab, int n_blocks,
+              int max_tiles, hipStream_t stream) {
+  Plan pl;
+  pl.seg_tile_off = static_cast<int32_t*>(ws);
+  pl.tiles = reinterpret_cast<TileDesc*>(static_cast<char*>(ws) +
+                                         (static_cast<size_t>(n_segs + 1) * sizeof(int32_t) + 255) / 256 * 256);
+  pl.max_tiles = max_tiles;
+  hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(256), 0, stream, segs, n_segs, pl.seg_tile_off);
+  hipLaunchKernelGGL(plan_fill_kernel, dim3((max_tiles + 255) / 256), dim3(256), 0, stream, segs, n_segs,
+                     pl.seg_tile_off, block_tab, n_blocks, max_tiles, pl.tiles);
+  return pl;
+}
 
 template <int G>
 void launch_attn_g(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
                    int max_q_per_req, const void* k_pool, const void* v_pool, int n_blocks,
-                   const int32_t* block_tab, const cc_segment* segs, const int32_t* req_seg_off,
+                   const Plan& pl, const cc_segment* segs, const int32_t* req_seg_off,
                    int n_requests, void* out, float* lse, hipStream_t stream) {
   const int hkv = ctx->cfg.n_kv_heads, n_tiles = (max_q_per_req + 32 * kAttnQB - 1) / (32 * kAttnQB);
   dim3 grid(hkv * n_tiles, n_requests);
   hipLaunchKernelGGL((sparse_qk_kernel<G, false, kAttnQB>), grid, dim3(64 * G), 0, stream,
                      static_cast<const bf16_t*>(q), q_pos, cu_q, static_cast<const bf16_t*>(k_pool),
-                     static_cast<const bf16_t*>(v_pool), n_blocks, block_tab, segs, req_seg_off,
-                     ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq, static_cast<bf16_t*>(out), lse,
-                     static_cast<float*>(nullptr));
+                     static_cast<const bf16_t*>(v_pool), n_blocks, pl.tiles, pl.seg_tile_off, pl.max_tiles,
+                     segs, req_seg_off, ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq,
+                     static_cast<bf16_t*>(out), lse, static_cast<float*>(nullptr));
 }
 
 template <int G>
-void launch_score_g(const cc_ctx* ctx, const void* q, const void* k_pool, int n_blocks,
-                    const int32_t* block_tab, const cc_segment* segs, int n_segs,
-                    const int32_t* req_seg_off, int max_seg_tokens, float* mass, hipStream_t stream) {
+void launch_score_g(const cc_ctx* ctx, const void* q, const void* k_pool, int n_blocks, const Plan& pl,
+                    const cc_segment* segs, int n_segs, const int32_t* req_seg_off, int max_seg_tokens,
+                    float* mass, hipStream_t stream) {
   const int hkv = ctx->cfg.n_kv_heads, n_tiles = (max_seg_tokens + 32 * kScoreQB - 1) / (32 * kScoreQB);
   dim3 grid(hkv * n_tiles, n_segs);
   hipLaunchKernelGGL((sparse_qk_kernel<G, true, kScoreQB>), grid, dim3(64 * G), 0, stream,
                      static_cast<const bf16_t*>(q), static_cast<const int32_t*>(nullptr),
                      static_cast<const int32_t*>(nullptr), static_cast<const bf16_t*>(k_pool),
-                     static_cast<const bf16_t*>(nullptr), n_blocks, block_tab, segs, req_seg_off,
-                     ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq, static_cast<bf16_t*>(nullptr),
-                     static_cast<float*>(nullptr), mass);
+                     static_cast<const bf16_t*>(nullptr), n_blocks, pl.tiles, pl.seg_tile_off, pl.max_tiles,
+                     segs, req_seg_off, ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq,
+                     static_cast<bf16_t*>(nullptr), static_cast<float*>(nullptr), mass);
 }
 
 bool group_supported(const cc_ctx* ctx) {
@@ -624,13 +741,16 @@ bool group_supported(const cc_ctx* ctx) {
 bool attn_mfma_supported(const cc_ctx* ctx) { return group_supported(ctx); }
 bool score_mfma_supported(const cc_ctx* ctx) { return group_supported(ctx); }
 
+size_t mfma_plan_bytes(int n_segs, int max_tiles) { return plan_bytes_impl(n_segs, max_tiles); }
+
 void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
                       int n_q_tot, int max_q_per_req, const void* k_pool, const void* v_pool,
-                      int n_blocks, const int32_t* block_tab, const cc_segment* segs,
+                      int n_blocks, const int32_t* block_tab, const cc_segment* segs, int n_segs,
                       const int32_t* req_seg_off, int n_requests, void* out, float* lse,
-                      hipStream_t stream) {
+                      void* plan_ws, int max_tiles, hipStream_t stream) {
   (void)n_q_tot;
-#define CC_ARGS ctx, q, q_pos, cu_q, max_q_per_req, k_pool, v_pool, n_blocks, block_tab, segs, req_seg_off, n_requests, out, lse, stream
+  const Plan pl = run_plan(plan_ws, segs, n_segs, block_tab, n_blocks, max_tiles, stream);
+#define CC_ARGS ctx, q, q_pos, cu_q, max_q_per_req, k_pool, v_pool, n_blocks, pl, segs, req_seg_off, n_requests, out, lse, stream
   switch (ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads) {
     case 1: launch_attn_g<1>(CC_ARGS); break;
     case 2: launch_attn_g<2>(CC_ARGS); break;
@@ -643,8 +763,9 @@ void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, co
 void launch_score_mfma(const cc_ctx* ctx, const void* q, const void* k_pool, int n_blocks,
                        const int32_t* block_tab, const cc_segment* segs, int n_segs,
                        const int32_t* req_seg_off, int max_seg_tokens, float* mass,
-                       hipStream_t stream) {
-#define CC_ARGS ctx, q, k_pool, n_blocks, block_tab, segs, n_segs, req_seg_off, max_seg_tokens, mass, stream
+                       void* plan_ws, int max_tiles, hipStream_t stream) {
+  const Plan pl = run_plan(plan_ws, segs, n_segs, block_tab, n_blocks, max_tiles, stream);
+#define CC_ARGS ctx, q, k_pool, n_blocks, pl, segs, n_segs, req_seg_off, max_seg_tokens, mass, stream
   switch (ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads) {
     case 1: launch_score_g<1>(CC_ARGS); break;
     case 2: launch_score_g<2>(CC_ARGS); break;

@@ -76,7 +76,7 @@ class DeviceBatch:
         self.lse = torch.zeros((nq, hq), dtype=torch.float32, device=device)
         self.ws_select = torch.empty(max(256, self.ctx.select_workspace_bytes(self.n_tok, len(w.segments))),
                                      dtype=torch.uint8, device=device)
-        self.ws_prefill = torch.empty(max(256, self.ctx.sparse_prefill_workspace_bytes(self.n_q_tot, self.n_requests)),
+        self.ws_prefill = torch.empty(max(256, self.ctx.sparse_prefill_workspace_bytes(self.n_tok, len(w.segments))),
                                       dtype=torch.uint8, device=device)
 
     # ---- the calls, in path order ------------------------------------------------------------
@@ -107,7 +107,7 @@ class DeviceBatch:
             return
         self.ctx.sparse_prefill(self.q_c, self.k_c, self.v_c, self.q_pos, self.slot_map, self.cu_q,
                                 self.max_q_per_req, self.k_req, self.v_req, self.req_tab,
-                                self.segments, self.req_seg_off, self.n_requests, self.out, self.lse,
+                                self.segments, self.req_seg_off, self.n_requests, self.n_tok, self.out, self.lse,
                                 self.ws_prefill)
 
     def step(self):

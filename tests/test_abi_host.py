@@ -79,8 +79,8 @@ def test_calls_reject_bad_arguments_before_launch(lib):
     # cc_qkv_project: hidden not a multiple of 64
     assert lib.cc_qkv_project(h, good, good, 4, 100, good, good, good, None) == -1
     # cc_sparse_prefill: null output, max_q_per_req > n_q_tot, empty query list
-    ws = lib.cc_sparse_prefill_workspace_bytes(h, 10, 1)
-    args = [h, good, good, good, good, good, good, 10, 10, good, good, 8, good, good, 3, good, 1]
+    ws = lib.cc_sparse_prefill_workspace_bytes(h, 100, 3)
+    args = [h, good, good, good, good, good, good, 10, 10, good, good, 8, good, good, 3, good, 1, 100]
     assert lib.cc_sparse_prefill(*args, None, None, good, ws, None) == -1
     args[8] = 11
     assert lib.cc_sparse_prefill(*args, good, None, good, ws, None) == -1
