@@ -232,13 +232,12 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
   constexpr int NT = 64 * G;
   constexpr int TQ = 32 * QB;                       // query tokens per workgroup
   constexpr bool kPrefetch = NT >= 256;
-  // -m_ref rides in through the MFMA C operand when the 16 extra registers per query block are
-  // affordable; otherwise it is subtracted before the exponential.
-  constexpr bool kNegM = QB == 1;
-  static_assert(!(SCORE && kNegM), "the deferred score block assumes an explicit subtraction of the reference");
+  // -m_ref rides in through the MFMA C operand (16 registers per query block), which saves the
+  // subtraction in front of every exponential
+  constexpr bool kNegM = true;
   constexpr int kImage = SCORE ? 1024 : 2048;       // 16-byte pieces per tile image
   // operand reads in flight ahead of the MFMAs (16 bytes per lane each)
-  constexpr int kDepth = 8;
+  constexpr int kDepth = (QB == 2 || NT <= 256) ? 4 : 8;
   static_assert(16 % kDepth == 0, "ring slots must line up from one tile to the next");
   // attention: double-buffered.  score: three images, because the previous tile's image must stay
   // readable (repair path of its deferred block) while the next tile is being stored.
@@ -519,7 +518,7 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
     if constexpr (SCORE) {
       if (pending) {
         qk_block(img, nullptr, 0, [&](int kk) { exp_pair(1, kk); });
-        close_block(prev_img, 1, prev_kpos0, prev_nvalid, prev_edge, false);
+        close_block(prev_img, 1, prev_kpos0, prev_nvalid, prev_edge, true);
       } else {
         qk_block(img, nullptr, 0, no_side);
       }
@@ -544,7 +543,7 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
       // ---- stage 1: S block 1, exponentials of block 0 underneath; first reads of the next image
       qk_block(img, v1 ? next_img : nullptr, 1, [&](int kk) { exp_pair(0, kk); });
       if (edge) mask_block(1, kpos0, nvalid);
-      close_block(img, 0, kpos0, nvalid, edge, false);
+      close_block(img, 0, kpos0, nvalid, edge, true);
       pending = true; prev_kpos0 = kpos0; prev_nvalid = nvalid; prev_edge = edge;
     } else {
       // ---- stage 1: S block 1, exponentials of block 0 underneath -----------------------------------
