@@ -101,6 +101,9 @@ def main():
     ap.add_argument("--workload", type=int, default=3, help="benchmark config 1..5 (default 3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain 512 MiB device copy (identity cc_gather_rows) so that a "
+                         "rocprofv3 --pmc run of this command has a kernel of known HBM traffic to scale by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -119,6 +122,15 @@ def main():
     w = W.config(args.workload)
     batch = DeviceBatch(w)
     work = algorithmic_work(w)
+
+    if args.calibrate_copy:
+        rows, row_bytes = 1 << 15, 1 << 14                      # 32768 rows x 16 KiB = 512 MiB
+        src = torch.empty((rows, row_bytes), dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        idx = torch.arange(rows, dtype=torch.int32, device="cuda")
+        batch.ctx.gather_rows(src, idx, dst)
+        torch.cuda.synchronize()
+        del src, dst, idx
 
     for _ in range(args.warmup):
         batch.step()

@@ -161,7 +161,8 @@ int cc_qkv_project(cc_ctx* ctx, const void* x, const void* w_qkv, int32_t n_rows
  *      request (stale shifted rows, fixed rows, question rows), with q' = q[j] rotated to
  *      q_pos[j]; lse[j][h] = natural log of the softmax denominator.
  * Step 2 of every row sees step 1 of every row.  Keys are enumerated through segs/block_tab;
- * rows of one request must be contiguous, any order inside a request is accepted.
+ * rows of one request must be contiguous, and rows whose slots lie in the same 16-token block
+ * must be adjacent (the order cc_select emits); otherwise any order inside a request is accepted.
  *   q [n_q_tot][Hq][d], k_new, v_new [n_q_tot][Hkv][d]; out like q; lse [n_q_tot][Hq] or NULL.
  *   max_q_per_req: max rows of one request (host scalar, sizes the launch).
  *   n_ctx_tokens: sum of n_tokens over all segments, or any upper bound of it (host scalar; sizes
