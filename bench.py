@@ -22,6 +22,15 @@ sys.path.insert(0, ROOT)
 PEAK_MFMA_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
 PEAK_FP32_VALU_TFLOPS = 157.3
+# Back-to-back v_mfma_f32_32x32x16_bf16 on all 1024 SIMDs sustains this on the box (clock drops
+# under matrix load); quoted beside the vendor peak, never instead of it.
+MEASURED_MFMA_BF16_TFLOPS = 2054.0
+# HBM bytes per launch of each call's main kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# of this command scaled by a 512 MiB copy (profiles/hot_path_kernels_config3_8b_continuous_batch.md).
+MEASURED_TRAFFIC_BYTES = {
+    3: {"cc_rope_shift": (570.1 + 646.5) * 2 ** 20, "cc_select": (1446.1 + 69.3) * 2 ** 20,
+        "cc_sparse_prefill": (995.0 + 319.7 + 165.8 + 159.0) * 2 ** 20},
+}
 
 
 def algorithmic_work(w):
@@ -170,8 +179,14 @@ def main():
         s["frac"] = s["achieved"] / s["peak"]
     dominant = max(stages, key=lambda k: stages[k]["ms"])
     dom = stages[dominant]
-    roofline = {"kernel": dominant, "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
-                "unit": dom["unit"], "frac": dom["frac"], "traffic": None, "avg_ms": dom["ms"]}
+    kernel_of = {"cc_select": "sparse_qk_kernel<SCORE> (+ top-N, plan: ~1.5 % of the call)",
+                 "cc_sparse_prefill": "sparse_qk_kernel<ATTN> (+ rope_scatter, plan: ~9 % of the call)",
+                 "cc_rope_shift": "rope_shift_kernel", "cc_gather_rows(+cc_qkv_project)": "qkv_project / gather_rows"}
+    roofline = {"kernel": kernel_of[dominant], "call": dominant, "bound": dom["bound"], "achieved": dom["achieved"],
+                "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"],
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get(dominant), "avg_ms": dom["ms"]}
+    if dom["bound"] == "mfma":
+        roofline["frac_of_measured_mfma_rate"] = dom["achieved"] / MEASURED_MFMA_BF16_TFLOPS
 
     result = {
         "metric": "recomputed tokens/sec in selective chunk prefill",
