@@ -248,3 +248,75 @@ def test_projection_fp32_small():
     ctx.qkv_project(xd, wd, q, k, v); torch.cuda.synchronize()
     qf, kf, vf = O.qkv_project(x, wq, 4, 2, 64)
     assert H.rel_l2(q.cpu().numpy(), qf) <= 1e-5 and H.rel_l2(k.cpu().numpy(), kf) <= 1e-5 and H.rel_l2(v.cpu().numpy(), vf) <= 1e-5
+
+
+@pytest.mark.parametrize("cid", [3, 4, 5])
+def test_full_size_configs_on_sampled_outputs(cid):
+    """The benchmark configurations at full size, in the launch configuration bench.py times,
+    checked where the oracle can follow: whole chunks of shifted keys and scores, index sets of
+    those chunks, and sampled attention rows (oracle re-run on the library's own selection)."""
+    from paper_2502_15734_amd.pipeline import DeviceBatch
+    w = W.config(cid)
+    b = DeviceBatch(w)
+    b.step(); torch.cuda.synchronize()
+    rng = np.random.default_rng(100 + cid)
+    sel = b.sel_idx.cpu().numpy(); scores = b.scores.cpu().numpy()
+    out = b.out.float().cpu().numpy(); lse = b.lse.cpu().numpy()
+    kp, vp = _pools(b)
+    gsel = H.gpu_selection(w, sel)
+    hq, hkv, d = w.spec.n_q_heads, w.spec.n_kv_heads, w.spec.head_dim
+    for r in sorted(rng.choice(w.n_requests, size=min(2, w.n_requests), replace=False)):
+        k_sh, v_c, n_ctx = O.shifted_context(w, r)
+        segs = H.all_segments(w, r)
+        chunk_ids = [i for i, sg in enumerate(segs) if sg[W.SEG_KIND] == W.KIND_CHUNK]
+        # -- shifted keys of the whole request (stale rows only; fixed rows are checked below)
+        k_gpu, v_gpu = H.request_context_from_pools(w, r, kp, vp)
+        q_pos_r = np.concatenate([int(sg[W.SEG_START]) + (gsel[r][chunk_ids.index(i)] if sg[W.SEG_KIND] == W.KIND_CHUNK
+                                  else np.arange(int(sg[W.SEG_NTOK]))) for i, sg in enumerate(segs)])
+        stale = np.ones(n_ctx, dtype=bool); stale[q_pos_r] = False
+        assert H.rel_l2(k_gpu[stale], k_sh[stale]) <= 1e-2
+        assert np.array_equal(v_gpu[stale], v_c[stale])
+        # -- scores and index sets of two chunks (a middle one and the last one)
+        for ci in {chunk_ids[len(chunk_ids) // 2], chunk_ids[-1]}:
+            sg = segs[ci]
+            sc = O.score_request(w, r, k_sh, only_segments=[ci])[chunk_ids.index(ci)]
+            t0, n = int(sg[W.SEG_TOK]), int(sg[W.SEG_NTOK])
+            assert np.abs(scores[t0:t0 + n] - sc).max() <= 5e-5, f"config {cid} request {r} segment {ci}"
+            g = gsel[r][chunk_ids.index(ci)]
+            o = O.top_n(sc, int(sg[W.SEG_NSEL]))
+            diff = np.setxor1d(g, o)
+            if len(diff):
+                nth = np.sort(sc)[::-1][int(sg[W.SEG_NSEL]) - 1]
+                assert np.abs(sc[diff] - nth).max() <= H.TIE_GAP
+        # -- sampled attention rows on the library's own selection
+        q0, q1 = int(w.cu_q[r]), int(w.cu_q[r + 1])
+        which = np.sort(rng.choice(q1 - q0, size=min(24, q1 - q0), replace=False))
+        which[-1] = q1 - q0 - 1                                   # always include the last prompt token
+        if w.hidden is not None:                                  # q/k/v of the chosen rows come from x W
+            rows = b.q_row.cpu().numpy()[q0:q1]
+            qf, kf, vf = O.qkv_project(w.hidden[rows].astype(np.float64), w.w_qkv.astype(np.float64), hq, hkv, d)
+            full = lambda a, nh: _scatter_rows(a, rows, w.n_tok, nh, d)
+            ref = O.fix_and_attend(w, r, k_sh, v_c, gsel[r], k_new=full(kf, hkv), v_new=full(vf, hkv), q=full(qf, hq),
+                                   only_queries=which)
+        else:
+            ref = O.fix_and_attend(w, r, k_sh, v_c, gsel[r], only_queries=which)
+        k_ctx, v_ctx, q_pos, q_row, o_ref, l_ref = ref
+        e = H.rel_l2(out[q0:q1][which], o_ref)
+        assert e <= 1e-2, f"config {cid} request {r}: sampled out rel L2 {e:.3e}"
+        # projected q/k are bf16 roundings of GEMM outputs of magnitude ~1.3: logits carry more rounding
+        lse_err = float(np.abs(lse[q0:q1][which] - l_ref).max())
+        assert lse_err <= (2e-3 if w.hidden is None else 1e-2), f"config {cid} request {r}: lse error {lse_err:.3e}"
+        assert H.rel_l2(k_gpu, k_ctx) <= 1e-2 and H.rel_l2(v_gpu, v_ctx) <= 1e-2
+
+
+class _SparseRows:
+    """Row-indexable stand-in for a [n_tok, H, d] tensor of which only some rows exist."""
+    def __init__(self, data, rows):
+        self.data, self.index = data, {int(r): i for i, r in enumerate(rows)}
+
+    def __getitem__(self, rows):
+        return self.data[[self.index[int(r)] for r in np.atleast_1d(rows)]]
+
+
+def _scatter_rows(a, rows, n_tok, nh, d):
+    return _SparseRows(a, rows)

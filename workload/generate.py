@@ -21,6 +21,7 @@ values so the oracle can upcast them exactly.
 from __future__ import annotations
 
 import math
+import os
 from dataclasses import dataclass, field
 from typing import Dict, List, Optional, Sequence
 
@@ -123,11 +124,33 @@ class Workload:
         return int(last[SEG_START] + last[SEG_NTOK]) if s1 > s0 else 0
 
 
-def _draw(rng: np.random.Generator, shape, scale: float, dtype: str) -> np.ndarray:
-    x = rng.standard_normal(size=shape, dtype=np.float32)
-    if scale != 1.0:
-        x *= np.float32(scale)
-    return round_to_bf16(x) if dtype == "bf16" else x
+_DRAW_ROWS = 1 << 22          # elements per independently seeded slab
+
+
+def _draw(seed: np.random.SeedSequence, shape, scale: float, dtype: str) -> np.ndarray:
+    """N(0,1)*scale of the given shape.  The flat array is cut into slabs, each with its own child
+    seed, so that slabs can be filled by a thread pool and the result does not depend on the
+    number of threads."""
+    n = int(np.prod(shape))
+    out = np.empty(n, dtype=np.float32)
+    n_slabs = max(1, (n + _DRAW_ROWS - 1) // _DRAW_ROWS)
+    children = seed.spawn(n_slabs)
+
+    def fill(i):
+        a, b = i * _DRAW_ROWS, min(n, (i + 1) * _DRAW_ROWS)
+        g = np.random.Generator(np.random.PCG64(children[i]))
+        x = g.standard_normal(size=b - a, dtype=np.float32)
+        if scale != 1.0:
+            x *= np.float32(scale)
+        out[a:b] = round_to_bf16(x) if dtype == "bf16" else x
+
+    if n_slabs == 1:
+        fill(0)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+            list(ex.map(fill, range(n_slabs)))
+    return out.reshape(shape)
 
 
 def build(spec: Spec) -> Workload:
@@ -146,10 +169,8 @@ def build(spec: Spec) -> Workload:
     store_tab_off = np.zeros(len(store_pages) + 1, dtype=np.int32)
     store_tab_off[1:] = np.cumsum(store_pages)
     store_tab = ids
-    k_store = _draw(np.random.Generator(np.random.PCG64(s_k)),
-                    (n_store_blocks, Hkv, BLOCK, d), spec.value_scale, spec.dtype)
-    v_store = _draw(np.random.Generator(np.random.PCG64(s_v)),
-                    (n_store_blocks, Hkv, d, BLOCK), spec.value_scale, spec.dtype)
+    k_store = _draw(s_k, (n_store_blocks, Hkv, BLOCK, d), spec.value_scale, spec.dtype)
+    v_store = _draw(s_v, (n_store_blocks, Hkv, d, BLOCK), spec.value_scale, spec.dtype)
 
     # ---- requests: segments, request-owned pages, descriptors -------------
     segs, descs, req_seg_off, cu_q = [], [], [0], [0]
@@ -179,14 +200,13 @@ def build(spec: Spec) -> Workload:
         rs.shuffle(req_ids)
     n_tok = tok_cursor
 
-    q = _draw(np.random.Generator(np.random.PCG64(s_q)), (n_tok, Hq, d), spec.value_scale, spec.dtype)
-    k_new = _draw(np.random.Generator(np.random.PCG64(s_kn)), (n_tok, Hkv, d), spec.value_scale, spec.dtype)
-    v_new = _draw(np.random.Generator(np.random.PCG64(s_vn)), (n_tok, Hkv, d), spec.value_scale, spec.dtype)
+    q = _draw(s_q, (n_tok, Hq, d), spec.value_scale, spec.dtype)
+    k_new = _draw(s_kn, (n_tok, Hkv, d), spec.value_scale, spec.dtype)
+    v_new = _draw(s_vn, (n_tok, Hkv, d), spec.value_scale, spec.dtype)
     hidden = w_qkv = None
     if spec.hidden:
-        hidden = _draw(np.random.Generator(np.random.PCG64(s_x)), (n_tok, spec.hidden), 1.0, spec.dtype)
-        w_qkv = _draw(np.random.Generator(np.random.PCG64(s_w)),
-                      (spec.hidden, (Hq + 2 * Hkv) * d), 0.02, spec.dtype)
+        hidden = _draw(s_x, (n_tok, spec.hidden), 1.0, spec.dtype)
+        w_qkv = _draw(s_w, (spec.hidden, (Hq + 2 * Hkv) * d), 0.02, spec.dtype)
 
     return Workload(
         spec=spec, k_store=k_store, v_store=v_store,
