@@ -146,9 +146,10 @@ int cc_gather_rows(cc_ctx* ctx, const void* src, int32_t n_src_rows, const int32
                    int32_t n_rows, size_t row_bytes, void* dst, void* stream);
 
 /* ---- Q, K, V of the chosen tokens ---------------------------------------------------------
- * [q | k | v] = x W with x [n_rows][hidden], W [hidden][(Hq + 2 Hkv) d] row-major, columns
- * ordered q heads, then k heads, then v heads; outputs q [n_rows][Hq][d], k, v [n_rows][Hkv][d].
- * hidden must be a multiple of 64.  Sec. 3.4.3 (K, V and Q are computed only for new and
+ * [q | k | v] = x W^T with x [n_rows][hidden] and W [(Hq + 2 Hkv) d][hidden] row-major (one row
+ * of `hidden` weights per output feature: q heads, then k heads, then v heads -- both operands
+ * have the contraction index contiguous, which is what the matrix cores want); outputs
+ * q [n_rows][Hq][d], k, v [n_rows][Hkv][d].  hidden must be a multiple of 64.  Sec. 3.4.3 (K, V and Q are computed only for new and
  * recomputation tokens). */
 int cc_qkv_project(cc_ctx* ctx, const void* x, const void* w_qkv, int32_t n_rows, int32_t hidden,
                    void* q, void* k, void* v, void* stream);

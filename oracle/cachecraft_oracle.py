@@ -260,9 +260,10 @@ def run(w, selected_override: Optional[Dict[int, Sequence[np.ndarray]]] = None) 
 
 
 def qkv_project(hidden_rows: np.ndarray, w_qkv: np.ndarray, hq: int, hkv: int, d: int):
-    """Q, K, V of the given token rows: X W, split by heads (Sec. 3.4.3: computed only for
+    """Q, K, V of the given token rows: X W^T with W [(Hq+2Hkv)d, hidden] (one row per output
+    feature: q heads, then k heads, then v heads), split by heads (Sec. 3.4.3: computed only for
     the recomputation and question tokens).  Returns q [n,Hq,d], k [n,Hkv,d], v [n,Hkv,d]."""
-    y = np.asarray(hidden_rows, dtype=np.float64) @ np.asarray(w_qkv, dtype=np.float64)
+    y = np.asarray(hidden_rows, dtype=np.float64) @ np.asarray(w_qkv, dtype=np.float64).T
     n = y.shape[0]
     q = y[:, : hq * d].reshape(n, hq, d)
     k = y[:, hq * d: (hq + hkv) * d].reshape(n, hkv, d)

@@ -1,8 +1,12 @@
-// cc_qkv_project: [q | k | v] = x W for the chosen tokens only (Sec. 3.4.3).
+// cc_qkv_project: [q | k | v] = x W^T for the chosen tokens only (Sec. 3.4.3).
 //
-// bf16: MFMA GEMM, 128x128 output tile per workgroup (4 wavefronts, 64x64 each as 2x2 blocks of
-// v_mfma_f32_32x32x16_bf16), K-step 32 staged through LDS.  fp32: plain LDS-tiled FMA kernel.
-// The epilogue splits the fused output columns into the three tensors.
+// x [n_rows][hidden], W [(Hq+2Hkv)d][hidden]: both operands have the contraction index contiguous.
+// bf16: MFMA GEMM.  A workgroup of 8 wavefronts owns a 256 (features) x 256 (tokens) tile of the
+// transposed product D^T = W x^T; wavefront (wn, wm) owns 64 features x 128 tokens = 2 x 4 blocks
+// of v_mfma_f32_32x32x16_bf16, so 6 operand reads from LDS feed 8 MFMAs per 16-wide k-step.
+// K-steps of 32 are double-buffered in LDS (2 x 32 KiB) with the next step's global loads held in
+// registers.  In the transposed product a lane holds 4 consecutive features of ONE token, so the
+// epilogue writes 8-byte pieces of an output row.  fp32 (and odd shapes): plain LDS-tiled kernel.
 #include "device_util.h"
 
 namespace cc {
@@ -28,8 +32,7 @@ __global__ __launch_bounds__(256) void qkv_project_plain_kernel(
     for (int i = threadIdx.x; i < 64 * 16; i += 256) {
       const int r = i / 16, kk = i % 16;
       xs[kk][r] = (row0 + r < n_rows) ? to_float(x[static_cast<size_t>(row0 + r) * hidden + k0 + kk]) : 0.f;
-      const int kk2 = i / 64, c = i % 64;
-      ws[kk2][c] = (col0 + c < n_cols) ? to_float(w[static_cast<size_t>(k0 + kk2) * n_cols + col0 + c]) : 0.f;
+      ws[kk][r] = (col0 + r < n_cols) ? to_float(w[static_cast<size_t>(col0 + r) * hidden + k0 + kk]) : 0.f;
     }
     __syncthreads();
 #pragma unroll
@@ -51,10 +54,120 @@ __global__ __launch_bounds__(256) void qkv_project_plain_kernel(
     }
 }
 
+// ---- MFMA kernel (bf16) -----------------------------------------------------------------------
+namespace {
+
+constexpr int kTN = 256, kTM = 256, kTK = 32;         // workgroup tile: features x tokens x k-step
+constexpr int kTilePieces = (kTN + kTM) * kTK * 2 / 16;   // 16-byte pieces per k-step image (2048)
+
+// A row of a k-step image is 32 bf16 = 4 pieces of 16 bytes; piece c of row r is kept at
+// c ^ ((r >> 1) & 3), which makes both the staging writes and the MFMA operand reads (32 rows,
+// same piece) touch all LDS banks evenly.
+__device__ __forceinline__ int gemm_piece(int r, int c) { return r * 4 + (c ^ ((r >> 1) & 3)); }
+
+__global__ __launch_bounds__(512, 2) void qkv_project_mfma_kernel(
+    const bf16_t* __restrict__ x, const bf16_t* __restrict__ w, int n_rows, int hidden, int nq, int nk,
+    bf16_t* __restrict__ q, bf16_t* __restrict__ k, bf16_t* __restrict__ v) {
+  __shared__ uint4 lds[2 * kTilePieces];               // [buffer][W rows 0..255 | x rows 0..255][4 pieces]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nl = lane & 31, hh = lane >> 5;
+  const int wn = wave & 3, wm = wave >> 2;             // 4 x 2 wavefronts: 64 features x 128 tokens each
+  const int n0 = blockIdx.x * kTN, m0 = blockIdx.y * kTM;
+
+  // staging: thread t owns pieces t, t+512, t+1024, t+1536 of the image: rows t/4 (+128 ...), piece t%4
+  const bf16_t* src[4];
+  int dst[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int pc = tid + 512 * i, r = pc >> 2, c = pc & 3;      // r in [0, 512): W rows then x rows
+    if (r < kTN) src[i] = w + static_cast<size_t>(n0 + r) * hidden + c * 8;
+    else src[i] = x + static_cast<size_t>(min(m0 + r - kTN, n_rows - 1)) * hidden + c * 8;
+    dst[i] = (r < kTN ? 0 : kTN * 4) + gemm_piece(r < kTN ? r : r - kTN, c);
+  }
+  uint4 reg[4];
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+  const int n_k = hidden / kTK;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) reg[i] = *reinterpret_cast<const uint4*>(src[i]);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) lds[dst[i]] = reg[i];
+  __syncthreads();
+  for (int ks = 0; ks < n_k; ++ks) {
+    const uint4* img = lds + (ks & 1) * kTilePieces;
+    if (ks + 1 < n_k) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) reg[i] = *reinterpret_cast<const uint4*>(src[i] + (ks + 1) * kTK);
+    }
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {                   // two 16-wide k-steps
+      bf16x8 af[2], bfr[4];
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+        af[a] = __builtin_bit_cast(bf16x8, img[gemm_piece(wn * 64 + a * 32 + nl, 2 * kk + hh)]);
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+        bfr[b] = __builtin_bit_cast(bf16x8, img[kTN * 4 + gemm_piece(wm * 128 + b * 32 + nl, 2 * kk + hh)]);
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
+    }
+    if (ks + 1 < n_k) {
+      uint4* nxt = lds + ((ks + 1) & 1) * kTilePieces;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) nxt[dst[i]] = reg[i];
+    }
+    __syncthreads();
+  }
+
+  // D^T block (a, b): lane (nl, hh) holds token m0 + wm*128 + b*32 + nl, features
+  // n0 + wn*64 + a*32 + 8*(i/4) + 4*hh + i%4
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    const int row = m0 + wm * 128 + b * 32 + nl;
+    if (row >= n_rows) continue;
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+      const int col0 = n0 + wn * 64 + a * 32;         // a 32-feature block never straddles q | k | v
+      bf16_t* base;
+      int c_in, width;
+      if (col0 < nq) { base = q; c_in = col0; width = nq; }
+      else if (col0 < nq + nk) { base = k; c_in = col0 - nq; width = nk; }
+      else { base = v; c_in = col0 - nq - nk; width = nk; }
+      bf16_t* op = base + static_cast<size_t>(row) * width + c_in + 4 * hh;
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        bf16_t v4[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v4[e] = static_cast<bf16_t>(acc[a][b][4 * g4 + e]);
+        *reinterpret_cast<uint2*>(op + 8 * g4) = *reinterpret_cast<uint2*>(v4);
+      }
+    }
+  }
+}
+
+}  // namespace
+
 void launch_qkv_project(const cc_ctx* ctx, const void* x, const void* w, int n_rows, int hidden,
                         void* q, void* k, void* v, hipStream_t stream) {
   const int d = ctx->cfg.head_dim;
   const int nq = ctx->cfg.n_q_heads * d, nk = ctx->cfg.n_kv_heads * d, n_cols = nq + 2 * nk;
+  if (ctx->cfg.dtype == CC_BF16 && ctx->impl == CC_IMPL_AUTO && n_cols % kTN == 0 && hidden % kTK == 0 &&
+      nq % 32 == 0 && nk % 32 == 0) {
+    dim3 grid(n_cols / kTN, (n_rows + kTM - 1) / kTM);
+    hipLaunchKernelGGL(qkv_project_mfma_kernel, grid, dim3(512), 0, stream,
+                       static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(w), n_rows, hidden, nq, nk,
+                       static_cast<bf16_t*>(q), static_cast<bf16_t*>(k), static_cast<bf16_t*>(v));
+    return;
+  }
   dim3 grid((n_cols + 63) / 64, (n_rows + 63) / 64);
   if (ctx->cfg.dtype == CC_BF16)
     hipLaunchKernelGGL(qkv_project_plain_kernel<bf16_t>, grid, dim3(256), 0, stream,

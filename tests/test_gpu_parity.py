@@ -242,7 +242,7 @@ def test_projection_fp32_small():
     rng = np.random.default_rng(3)
     ctx = P.Context(4, 2, 64, 1.0e4, P.CC_F32)
     x = rng.standard_normal((37, 128)).astype(np.float32)
-    wq = (rng.standard_normal((128, (4 + 4) * 64)) * 0.05).astype(np.float32)
+    wq = (rng.standard_normal(((4 + 4) * 64, 128)) * 0.05).astype(np.float32)
     xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(wq).cuda()
     q = torch.empty((37, 4, 64), device="cuda"); k = torch.empty((37, 2, 64), device="cuda"); v = torch.empty_like(k)
     ctx.qkv_project(xd, wd, q, k, v); torch.cuda.synchronize()

@@ -342,9 +342,9 @@ def test_padding_slots_are_never_keys():
 
 def test_qkv_projection_splits_heads_in_q_k_v_order():
     rng = np.random.default_rng(6)
-    x = rng.standard_normal((3, 8)); wq = rng.standard_normal((8, (4 + 2 * 2) * 4))
+    x = rng.standard_normal((3, 8)); wq = rng.standard_normal(((4 + 2 * 2) * 4, 8))
     q, k, v = O.qkv_project(x, wq, 4, 2, 4)
-    y = torch.from_numpy(x) @ torch.from_numpy(wq)
+    y = torch.nn.functional.linear(torch.from_numpy(x), torch.from_numpy(wq))
     np.testing.assert_allclose(q[1, 2], y[1, 8:12].numpy(), atol=1e-13)
     np.testing.assert_allclose(k[2, 1], y[2, 16 + 4:16 + 8].numpy(), atol=1e-13)
     np.testing.assert_allclose(v[0, 0], y[0, 24:28].numpy(), atol=1e-13)

@@ -99,7 +99,7 @@ class Workload:
     k_new: np.ndarray            # [n_tok, Hkv, d]  pre-rotation recomputed keys
     v_new: np.ndarray            # [n_tok, Hkv, d]  recomputed values
     hidden: Optional[np.ndarray] = None   # [n_tok, hidden]
-    w_qkv: Optional[np.ndarray] = None    # [hidden, (Hq+2Hkv)*d]
+    w_qkv: Optional[np.ndarray] = None    # [(Hq+2Hkv)*d, hidden]  (out_features x in_features)
     extras: Dict[str, object] = field(default_factory=dict)
 
     @property
@@ -206,7 +206,7 @@ def build(spec: Spec) -> Workload:
     hidden = w_qkv = None
     if spec.hidden:
         hidden = _draw(s_x, (n_tok, spec.hidden), 1.0, spec.dtype)
-        w_qkv = _draw(s_w, (spec.hidden, (Hq + 2 * Hkv) * d), 0.02, spec.dtype)
+        w_qkv = _draw(s_w, ((Hq + 2 * Hkv) * d, spec.hidden), 0.02, spec.dtype)
 
     return Workload(
         spec=spec, k_store=k_store, v_store=v_store,
