@@ -16,17 +16,19 @@
 // of the dimension-major V block.
 //
 // Softmax bookkeeping: the query is pre-multiplied by log2(e)/sqrt(d) before it is rounded to
-// bf16, so S is in log2 units; the first MFMA of every S block takes -m_ref (the query's current
-// reference maximum, splat over the accumulator) as its C operand, so the accumulator comes out
-// as S - m_ref and p = exp2(acc) needs no further arithmetic.  m_ref is set by the first tile and
-// afterwards moves only when a tile's sum of exponentials exceeds kBig (entries far above the
-// reference); that tile is then redone with the reference raised and the sums and O rescaled.
-// Until then p is merely "large": fp32 and bf16 share the exponent range, so nothing is lost.
+// bf16, so S is in log2 units and p = exp2(S - m_ref).  The reference m_ref is fixed by the first
+// block of the request -- 0 if that block's maximum is within +-2^24 of it (then the subtraction
+// is skipped altogether), else that maximum -- and afterwards moves only when a block's sum of
+// exponentials exceeds kBig (entries far above the reference); that block is then redone with the
+// reference raised and the sums and O rescaled.  Until then p is merely "large": fp32 and bf16
+// share the exponent range, so nothing is lost.
 //
 // LDS image of a tile (16-byte pieces; every MFMA operand read is one conflict-free 1 KiB run):
 //   K piece (block b of 32 keys, k-step kk, half hh, row m):  (b*8+kk)*64 + hh*32 + (m ^ ((2kk+hh)&7))
 //   V piece (page pg, 32-dim group db, half hh, dim n):       1024 + (pg*4+db)*64 + hh*32 + (n ^ 4hh)
 // The XOR terms spread the *writes* of a coalesced global read over the LDS banks.
+#include <type_traits>
+
 #include "device_util.h"
 
 namespace cc {
@@ -38,6 +40,7 @@ constexpr int kTile = 64;                      // keys per tile
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kBig = 1.0e12f;                // a tile sum above this moves the reference maximum
+constexpr float kZeroBand = 24.f;              // first-block maxima within this keep the reference at 0
 
 __device__ __forceinline__ int swap23(int m) { return (m & ~12) | ((m & 4) << 1) | ((m & 8) >> 1); }
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -232,9 +235,6 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
   constexpr int NT = 64 * G;
   constexpr int TQ = 32 * QB;                       // query tokens per workgroup
   constexpr bool kPrefetch = NT >= 256;
-  // -m_ref rides in through the MFMA C operand (16 registers per query block), which saves the
-  // subtraction in front of every exponential
-  constexpr bool kNegM = true;
   constexpr int kImage = SCORE ? 1024 : 2048;       // 16-byte pieces per tile image
   // operand reads in flight ahead of the MFMAs (16 bytes per lane each)
   constexpr int kDepth = (QB == 2 || NT <= 256) ? 4 : 8;
@@ -317,13 +317,11 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
   const int vx = 1024 + hh * 32 + (n ^ (4 * hh));
 
   float m_ref[QB], l_run[QB], l_prior[QB];
-  f32x16 negm[QB];
   f32x16 o[QB][SCORE ? 1 : 4];
   f32x16 sacc[QB][2];                 // S (then p) of the two 32-key blocks in flight
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     m_ref[qb] = 0.f; l_run[qb] = 0.f; l_prior[qb] = 0.f;
-    negm[qb] = splat16(0.f);
 #pragma unroll
     for (int db = 0; db < (SCORE ? 1 : 4); ++db) o[qb][db] = splat16(0.f);
   }
@@ -361,7 +359,7 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb)
         sacc[qb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-            a, qreg[qb][kk], kk == 0 ? (kNegM ? negm[qb] : splat16(0.f)) : sacc[qb][b], 0, 0, 0);
+            a, qreg[qb][kk], kk == 0 ? splat16(0.f) : sacc[qb][b], 0, 0, 0);
       issue(img, nimg, t + kDepth);
       side(kk);
       __builtin_amdgcn_sched_barrier(0);
@@ -380,17 +378,24 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
   };
   // exponentials of elements 2kk, 2kk+1 of block b (all query blocks); sums go to lsum[]
   float lsum[QB];
-  auto exp_pair = [&](int b, int kk) {
+  // While every query's reference is still exactly 0 (zero_ref: the first block's maximum was
+  // small, which is the normal case for attention logits) the subtraction is skipped; the
+  // accumulators always hold raw S, so switching between the two forms needs no fix-up.
+  bool zero_ref = true;
+  auto exp_pair = [&](auto zero, int b, int kk) {
+    constexpr bool kZero = decltype(zero)::value;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
       for (int e = 0; e < 2; ++e) {
         const int i = 2 * kk + e;
-        const float v = __builtin_amdgcn_exp2f(kNegM ? sacc[qb][b][i] : sacc[qb][b][i] - m_ref[qb]);
+        const float v = __builtin_amdgcn_exp2f(kZero ? sacc[qb][b][i] : sacc[qb][b][i] - m_ref[qb]);
         sacc[qb][b][i] = v;
         lsum[qb] += v;
       }
   };
+  using ZeroT = std::integral_constant<bool, true>;
+  using SubT = std::integral_constant<bool, false>;
   auto no_side = [&](int) {};
   // padding / causal edge: entries of block b that the query must not see become -inf
   // (accumulator register i of block b holds key 32b + 16(i/8) + 8hh + i%8 of the tile)
@@ -405,14 +410,22 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
       asm volatile("" : "+v"(sacc[qb][b]));
     }
   };
-  // move the reference of every query up to the maximum of block b (raw S, frame given by
-  // `in_frame`: true if the block already has -m_ref in it); rescale what has been summed so far.
-  auto raise_ref = [&](int b, bool in_frame, bool adjust_other, bool init) {
+  // move the reference of every query up to the maximum of block b (raw S); rescale what has been
+  // summed so far.  init: first block of the request -- the reference stays 0 if every query's
+  // maximum is within +-kZeroBand, else it becomes that maximum.
+  auto raise_ref = [&](int b, bool init) {
+    float t[QB];
+    bool small = true;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-      float t = max16(sacc[qb][b]) - (in_frame ? 0.f : m_ref[qb]);
-      t = fmaxf(t, __shfl_xor(t, 32, 64));
-      const float d = init ? t : fmaxf(t, 0.f);
+      t[qb] = max16(sacc[qb][b]);
+      t[qb] = fmaxf(t[qb], __shfl_xor(t[qb], 32, 64));
+      small = small && fabsf(t[qb]) <= kZeroBand;
+    }
+    if (init && __all(small)) return;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      const float d = init ? t[qb] : fmaxf(t[qb] - m_ref[qb], 0.f);
       const float alpha = init ? 1.f : __builtin_amdgcn_exp2f(-d);
       l_run[qb] *= alpha;
       if constexpr (SCORE) l_prior[qb] *= alpha;
@@ -423,23 +436,13 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
           for (int i = 0; i < 16; ++i) o[qb][db][i] *= alpha;
       }
       m_ref[qb] += d;
-      if constexpr (kNegM) {
-        negm[qb] = splat16(-m_ref[qb]);
-        if (in_frame) {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) sacc[qb][b][i] -= d;
-        }
-        if (adjust_other) {                                // a block still waiting for its exponentials
-#pragma unroll
-          for (int i = 0; i < 16; ++i) sacc[qb][1 - b][i] -= d;
-        }
-      }
     }
+    zero_ref = false;
   };
   // close block b after its exponentials: normally just add the sums.  If a sum is huge or not
   // finite, entries ran far above the reference: recompute the block's S from the LDS image,
   // raise the reference (rescaling sums and O), and redo the exponentials.  Rare.
-  auto close_block = [&](const uint4* img, int b, int kpos0, int nvalid, bool edge, bool other_waiting) {
+  auto close_block = [&](const uint4* img, int b, int kpos0, int nvalid, bool edge) {
     bool bad = false;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) bad = bad || !(lsum[qb] < kBig);
@@ -447,7 +450,7 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
       asm volatile("" ::: "memory");
       qk_block_raw(img, b);
       if (edge) mask_block(b, kpos0, nvalid);
-      raise_ref(b, false, other_waiting, false);
+      raise_ref(b, false);
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
         lsum[qb] = 0.f;
@@ -517,8 +520,9 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
     // ---- stage 0: S block 0 ----------------------------------------------------------------------
     if constexpr (SCORE) {
       if (pending) {
-        qk_block(img, nullptr, 0, [&](int kk) { exp_pair(1, kk); });
-        close_block(prev_img, 1, prev_kpos0, prev_nvalid, prev_edge, true);
+        if (zero_ref) qk_block(img, nullptr, 0, [&](int kk) { exp_pair(ZeroT{}, 1, kk); });
+        else qk_block(img, nullptr, 0, [&](int kk) { exp_pair(SubT{}, 1, kk); });
+        close_block(prev_img, 1, prev_kpos0, prev_nvalid, prev_edge);
       } else {
         qk_block(img, nullptr, 0, no_side);
       }
@@ -532,7 +536,7 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
     }
     if (edge) mask_block(0, kpos0, nvalid);
     if (first) {                       // key 0 of the request is in this block and visible to all
-      raise_ref(0, kNegM, false, true);
+      raise_ref(0, true);
       first = false;
     }
     if constexpr (SCORE) {
@@ -541,15 +545,17 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
       __syncthreads();
       if (v2) stage_load(d2);
       // ---- stage 1: S block 1, exponentials of block 0 underneath; first reads of the next image
-      qk_block(img, v1 ? next_img : nullptr, 1, [&](int kk) { exp_pair(0, kk); });
+      if (zero_ref) qk_block(img, v1 ? next_img : nullptr, 1, [&](int kk) { exp_pair(ZeroT{}, 0, kk); });
+      else qk_block(img, v1 ? next_img : nullptr, 1, [&](int kk) { exp_pair(SubT{}, 0, kk); });
       if (edge) mask_block(1, kpos0, nvalid);
-      close_block(img, 0, kpos0, nvalid, edge, true);
+      close_block(img, 0, kpos0, nvalid, edge);
       pending = true; prev_kpos0 = kpos0; prev_nvalid = nvalid; prev_edge = edge;
     } else {
       // ---- stage 1: S block 1, exponentials of block 0 underneath -----------------------------------
-      qk_block(img, nullptr, 1, [&](int kk) { exp_pair(0, kk); });
+      // (the attention kernel is bound by LDS operand reads, not by the VALU: one form is enough)
+      qk_block(img, nullptr, 1, [&](int kk) { exp_pair(SubT{}, 0, kk); });
       if (edge) mask_block(1, kpos0, nvalid);
-      close_block(img, 0, kpos0, nvalid, edge, true);
+      close_block(img, 0, kpos0, nvalid, edge);
       if (v1) stage_store(d1, next_buf);
       // ---- stages 2, 3: O^T += V^T P^T, P^T straight from the accumulator registers ------------------
       // block b covers pages 2b, 2b+1 of the tile; step st = (u, db): page 2b+u, 32-dim group db
@@ -573,8 +579,8 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
           __builtin_amdgcn_sched_barrier(0);
         }
       };
-      pv_block(nullptr, 0, [&](int st) { exp_pair(1, st); });
-      close_block(img, 1, kpos0, nvalid, edge, false);
+      pv_block(nullptr, 0, [&](int st) { exp_pair(SubT{}, 1, st); });
+      close_block(img, 1, kpos0, nvalid, edge);
       // every read of this image has been issued; meet, then finish the tile out of registers
       // while the first operand reads of the next image are in flight
       __syncthreads();
@@ -589,8 +595,8 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
   if constexpr (SCORE) {
     if (pending) {                     // exponentials of the very last block
 #pragma unroll
-      for (int kk = 0; kk < 8; ++kk) exp_pair(1, kk);
-      close_block(lds_all + ((buf + kBufs - 1) % kBufs) * kImage, 1, prev_kpos0, prev_nvalid, prev_edge, false);
+      for (int kk = 0; kk < 8; ++kk) exp_pair(SubT{}, 1, kk);
+      close_block(lds_all + ((buf + kBufs - 1) % kBufs) * kImage, 1, prev_kpos0, prev_nvalid, prev_edge);
     }
   }
 
