@@ -192,6 +192,7 @@ int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void*
                  segs && req_seg_off && out, "null pointer");
   CC_REQUIRE(n_blocks > 0 && n_requests > 0 && n_segs > 0 && max_q_per_req > 0, "sizes must be positive");
   CC_REQUIRE(n_requests <= 65535, "more than 65535 requests in one call");
+  CC_REQUIRE(n_requests <= n_segs, "every request needs at least one segment");
   CC_REQUIRE(aligned16(q) && aligned16(k_new) && aligned16(v_new) && aligned16(k_pool) &&
                  aligned16(v_pool) && aligned16(out), "tensors must be 16-byte aligned");
   CC_REQUIRE(workspace != nullptr && aligned16(workspace), "workspace missing or misaligned");

@@ -229,7 +229,7 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
     const bf16_t* __restrict__ q, const int32_t* __restrict__ q_pos, const int32_t* __restrict__ cu_q,
     const bf16_t* __restrict__ k_pool, const bf16_t* __restrict__ v_pool, int n_blocks,
     const TileDesc* __restrict__ tiles, const int32_t* __restrict__ seg_tile_off, int max_tiles,
-    const cc_segment* __restrict__ segs, const int32_t* __restrict__ req_seg_off, int hq, int hkv,
+    const int32_t* __restrict__ order, const cc_segment* __restrict__ segs, const int32_t* __restrict__ req_seg_off, int hq, int hkv,
     int n_tiles_x, InvFreq inv_freq, bf16_t* __restrict__ out, float* __restrict__ lse,
     float* __restrict__ mass) {
   constexpr int NT = 64 * G;
@@ -253,7 +253,8 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
   int row[QB], p[QB], s_begin, s_end, s_self = -1;
   bool row_valid[QB];
   if constexpr (SCORE) {
-    const cc_segment sg = segs[blockIdx.y];
+    const int seg_id = order[blockIdx.y];              // heaviest segments are dispatched first
+    const cc_segment sg = segs[seg_id];
     const int t0 = tile * TQ;
     if (sg.kind != CC_SEG_CHUNK || t0 >= sg.n_tokens || sg.logical_start == 0) return;
 #pragma unroll
@@ -264,10 +265,10 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
       p[qb] = sg.logical_start + t;
     }
     s_begin = req_seg_off[sg.req];
-    s_self = blockIdx.y;
+    s_self = seg_id;
     s_end = s_self + 1;
   } else {
-    const int r = blockIdx.y;
+    const int r = order[blockIdx.y];                   // longest contexts are dispatched first
     const int q0 = cu_q[r] + tile * TQ, q_end = cu_q[r + 1];
     if (q0 >= q_end) return;
 #pragma unroll
@@ -516,6 +517,7 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
     const uint4* next_img = lds_all + next_buf * kImage;
     const uint4* prev_img = lds_all + ((buf + kBufs - 1) % kBufs) * kImage;
     TileDesc d3 = fetch_desc(tiles, j + 3, max_tiles);             // three tiles ahead
+    TileDesc d3s;                                                  // ... made wave-uniform mid-tile
 
     // ---- stage 0: S block 0 ----------------------------------------------------------------------
     if constexpr (SCORE) {
@@ -543,6 +545,7 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
       // all operand reads of this image are issued; publish the next image and meet
       if (v1) stage_store(d1, next_buf);
       __syncthreads();
+      d3s = to_scalar(d3);             // its load is the only one in flight here: waiting is free
       if (v2) stage_load(d2);
       // ---- stage 1: S block 1, exponentials of block 0 underneath; first reads of the next image
       if (zero_ref) qk_block(img, v1 ? next_img : nullptr, 1, [&](int kk) { exp_pair(ZeroT{}, 0, kk); });
@@ -584,11 +587,12 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
       // every read of this image has been issued; meet, then finish the tile out of registers
       // while the first operand reads of the next image are in flight
       __syncthreads();
+      d3s = to_scalar(d3);             // its load is the only one in flight here: waiting is free
       if (v2) stage_load(d2);
       pv_block(v1 ? next_img : nullptr, 1, no_side);
     }
     ++j;
-    d0 = d1; d1 = d2; d2 = to_scalar(d3);
+    d0 = d1; d1 = d2; d2 = d3s;
     v0 = v1; v1 = v2; v2 = v2 && usable(d2, j + 2);
     buf = next_buf;
   }
@@ -684,23 +688,72 @@ __global__ __launch_bounds__(256) void plan_fill_kernel(const cc_segment* __rest
   tiles[j] = d;
 }
 
+// Dispatch order of the grid's y index: items sorted by decreasing key-side work, so that the last
+// workgroups to start are the short ones.  BY_REQUEST: item = request, key = end of its context;
+// otherwise item = segment, key = end of the segment (0 for segments that are not scored).
+// order[rank] = item; ties keep index order, so the result is always a permutation.  More than
+// kMaxOrdered items: identity.
+constexpr int kMaxOrdered = 4096;
+
+template <bool BY_REQUEST>
+__global__ __launch_bounds__(256) void plan_order_kernel(const cc_segment* __restrict__ segs,
+                                                          const int32_t* __restrict__ req_seg_off,
+                                                          int n_items, int32_t* __restrict__ order) {
+  __shared__ int key[kMaxOrdered];
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (n_items > kMaxOrdered) {
+    if (i < n_items) order[i] = i;
+    return;
+  }
+  for (int j = threadIdx.x; j < n_items; j += 256) {
+    int kv = 0;
+    if constexpr (BY_REQUEST) {
+      const int s_last = req_seg_off[j + 1] - 1;
+      if (s_last >= req_seg_off[j]) kv = segs[s_last].logical_start + segs[s_last].n_tokens;
+    } else {
+      const cc_segment sg = segs[j];
+      if (sg.kind == CC_SEG_CHUNK && sg.logical_start > 0) kv = sg.logical_start + sg.n_tokens;
+    }
+    key[j] = kv;
+  }
+  __syncthreads();
+  if (i >= n_items) return;
+  const int mine = key[i];
+  int rank = 0;
+  for (int j = 0; j < n_items; ++j) {
+    const int other = key[j];
+    rank += (other > mine || (other == mine && j < i)) ? 1 : 0;
+  }
+  order[rank] = i;
+}
+
 constexpr int kAttnQB = 1;     // 32 query tokens per workgroup in the attention kernel
 constexpr int kScoreQB = 2;    // 64 in the score kernel (no O accumulator, so registers allow it)
 
-size_t plan_bytes_impl(int n_segs, int max_tiles) {
-  return (static_cast<size_t>(n_segs + 1) * sizeof(int32_t) + 255) / 256 * 256 +
-         static_cast<size_t>(max_tiles) * sizeof(TileDesc);
+// workspace: seg_tile_off[n_segs + 1] | order[n_segs] (requests never outnumber segments) | tiles
+size_t plan_head_bytes(int n_segs) {
+  return (static_cast<size_t>(2 * n_segs + 1) * sizeof(int32_t) + 255) / 256 * 256;
 }
 
-struct Plan { int32_t* seg_tile_off; TileDesc* tiles; int max_tiles; };
+size_t plan_bytes_impl(int n_segs, int max_tiles) {
+  return plan_head_bytes(n_segs) + static_cast<size_t>(max_tiles) * sizeof(TileDesc);
+}
 
-Plan run_plan(void* ws, const cc_segment* segs, int n_segs, const int32_t* block_tab, int n_blocks,
-              int max_tiles, hipStream_t stream) {
+struct Plan { int32_t* seg_tile_off; int32_t* order; TileDesc* tiles; int max_tiles; };
+
+Plan run_plan(void* ws, const cc_segment* segs, int n_segs, const int32_t* req_seg_off, int n_requests,
+              const int32_t* block_tab, int n_blocks, int max_tiles, hipStream_t stream) {
   Plan pl;
   pl.seg_tile_off = static_cast<int32_t*>(ws);
-  pl.tiles = reinterpret_cast<TileDesc*>(static_cast<char*>(ws) +
-                                         (static_cast<size_t>(n_segs + 1) * sizeof(int32_t) + 255) / 256 * 256);
+  pl.order = pl.seg_tile_off + n_segs + 1;
+  pl.tiles = reinterpret_cast<TileDesc*>(static_cast<char*>(ws) + plan_head_bytes(n_segs));
   pl.max_tiles = max_tiles;
+  if (n_requests > 0)                                  // attention: the grid's y index walks requests
+    hipLaunchKernelGGL(plan_order_kernel<true>, dim3((n_requests + 255) / 256), dim3(256), 0, stream, segs,
+                       req_seg_off, n_requests, pl.order);
+  else                                                 // score: it walks segments
+    hipLaunchKernelGGL(plan_order_kernel<false>, dim3((n_segs + 255) / 256), dim3(256), 0, stream, segs,
+                       req_seg_off, n_segs, pl.order);
   hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(256), 0, stream, segs, n_segs, pl.seg_tile_off);
   hipLaunchKernelGGL(plan_fill_kernel, dim3((max_tiles + 255) / 256), dim3(256), 0, stream, segs, n_segs,
                      pl.seg_tile_off, block_tab, n_blocks, max_tiles, pl.tiles);
@@ -717,7 +770,7 @@ void launch_attn_g(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const
   hipLaunchKernelGGL((sparse_qk_kernel<G, false, kAttnQB>), grid, dim3(64 * G), 0, stream,
                      static_cast<const bf16_t*>(q), q_pos, cu_q, static_cast<const bf16_t*>(k_pool),
                      static_cast<const bf16_t*>(v_pool), n_blocks, pl.tiles, pl.seg_tile_off, pl.max_tiles,
-                     segs, req_seg_off, ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq,
+                     pl.order, segs, req_seg_off, ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq,
                      static_cast<bf16_t*>(out), lse, static_cast<float*>(nullptr));
 }
 
@@ -731,7 +784,7 @@ void launch_score_g(const cc_ctx* ctx, const void* q, const void* k_pool, int n_
                      static_cast<const bf16_t*>(q), static_cast<const int32_t*>(nullptr),
                      static_cast<const int32_t*>(nullptr), static_cast<const bf16_t*>(k_pool),
                      static_cast<const bf16_t*>(nullptr), n_blocks, pl.tiles, pl.seg_tile_off, pl.max_tiles,
-                     segs, req_seg_off, ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq,
+                     pl.order, segs, req_seg_off, ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq,
                      static_cast<bf16_t*>(nullptr), static_cast<float*>(nullptr), mass);
 }
 
@@ -754,7 +807,7 @@ void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, co
                       const int32_t* req_seg_off, int n_requests, void* out, float* lse,
                       void* plan_ws, int max_tiles, hipStream_t stream) {
   (void)n_q_tot;
-  const Plan pl = run_plan(plan_ws, segs, n_segs, block_tab, n_blocks, max_tiles, stream);
+  const Plan pl = run_plan(plan_ws, segs, n_segs, req_seg_off, n_requests, block_tab, n_blocks, max_tiles, stream);
 #define CC_ARGS ctx, q, q_pos, cu_q, max_q_per_req, k_pool, v_pool, n_blocks, pl, segs, req_seg_off, n_requests, out, lse, stream
   switch (ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads) {
     case 1: launch_attn_g<1>(CC_ARGS); break;
@@ -769,7 +822,7 @@ void launch_score_mfma(const cc_ctx* ctx, const void* q, const void* k_pool, int
                        const int32_t* block_tab, const cc_segment* segs, int n_segs,
                        const int32_t* req_seg_off, int max_seg_tokens, float* mass,
                        void* plan_ws, int max_tiles, hipStream_t stream) {
-  const Plan pl = run_plan(plan_ws, segs, n_segs, block_tab, n_blocks, max_tiles, stream);
+  const Plan pl = run_plan(plan_ws, segs, n_segs, req_seg_off, 0, block_tab, n_blocks, max_tiles, stream);
 #define CC_ARGS ctx, q, k_pool, n_blocks, pl, segs, n_segs, req_seg_off, max_seg_tokens, mass, stream
   switch (ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads) {
     case 1: launch_score_g<1>(CC_ARGS); break;
