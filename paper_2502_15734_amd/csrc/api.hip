@@ -71,7 +71,7 @@ const char* cc_last_error(const cc_ctx* ctx) { return ctx ? ctx->last_error.c_st
 
 int cc_set_impl(cc_ctx* ctx, int impl) {
   if (ctx == nullptr) return CC_ERR_INVALID_ARG;
-  if (impl != CC_IMPL_AUTO && impl != CC_IMPL_SCALAR)
+  if (impl != CC_IMPL_AUTO && impl != CC_IMPL_SCALAR && impl != CC_IMPL_MFMA_NARROW)
     return fail(ctx, CC_ERR_INVALID_ARG, "cc_set_impl: unknown implementation id");
   ctx->impl = impl;
   return CC_OK;
@@ -106,7 +106,7 @@ size_t cc_select_workspace_bytes(const cc_ctx* ctx, int32_t n_tok, int32_t n_seg
   if (ctx == nullptr || n_tok < 0 || n_segs < 0) return 0;
   return cc::align_up(static_cast<size_t>(n_tok) * ctx->cfg.n_q_heads * sizeof(float), 256) +
          cc::align_up(static_cast<size_t>(n_tok) * sizeof(uint32_t), 256) +
-         cc::align_up(cc::mfma_plan_bytes(n_segs, max_tiles_for(n_tok, n_segs)), 256) + 256;
+         cc::align_up(cc::mfma_plan_bytes(n_segs, max_tiles_for(n_tok, n_segs), 0), 256) + 256;
 }
 
 int cc_select(cc_ctx* ctx, const void* q, int32_t n_tok, const void* k_pool, int32_t n_blocks,
@@ -132,7 +132,7 @@ int cc_select(cc_ctx* ctx, const void* q, int32_t n_tok, const void* k_pool, int
       static_cast<char*>(workspace) +
       cc::align_up(static_cast<size_t>(n_tok) * ctx->cfg.n_q_heads * sizeof(float), 256));
   void* plan_ws = reinterpret_cast<char*>(keys) + cc::align_up(static_cast<size_t>(n_tok) * sizeof(uint32_t), 256);
-  if (ctx->impl == CC_IMPL_AUTO && cc::score_mfma_supported(ctx))
+  if (ctx->impl != CC_IMPL_SCALAR && cc::score_mfma_supported(ctx))
     cc::launch_score_mfma(ctx, q, k_pool, n_blocks, block_tab, segs, n_segs, req_seg_off,
                           max_seg_tokens, mass, plan_ws, max_tiles_for(n_tok, n_segs), st);
   else
@@ -172,7 +172,8 @@ int cc_qkv_project(cc_ctx* ctx, const void* x, const void* w_qkv, int32_t n_rows
 
 size_t cc_sparse_prefill_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_tokens, int32_t n_segs) {
   if (ctx == nullptr || n_ctx_tokens < 0 || n_segs < 0) return 0;
-  return cc::align_up(cc::mfma_plan_bytes(n_segs, max_tiles_for(n_ctx_tokens, n_segs)), 256) + 256;
+  // queries are a subset of the context tokens, so n_ctx_tokens bounds the rows of the compact list
+  return cc::align_up(cc::mfma_plan_bytes(n_segs, max_tiles_for(n_ctx_tokens, n_segs), n_ctx_tokens), 256) + 256;
 }
 
 int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void* v_new,
@@ -201,7 +202,7 @@ int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void*
                 "cc_sparse_prefill: workspace smaller than cc_sparse_prefill_workspace_bytes()");
   hipStream_t st = static_cast<hipStream_t>(stream);
   cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_q_tot, k_pool, v_pool, n_blocks, st);
-  if (ctx->impl == CC_IMPL_AUTO && cc::attn_mfma_supported(ctx))
+  if (ctx->impl != CC_IMPL_SCALAR && cc::attn_mfma_supported(ctx))
     cc::launch_attn_mfma(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks,
                          block_tab, segs, n_segs, req_seg_off, n_requests, out, lse, workspace,
                          max_tiles_for(n_ctx_tokens, n_segs), st);

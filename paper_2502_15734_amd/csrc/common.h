@@ -49,8 +49,9 @@ void launch_score_scalar(const cc_ctx* ctx, const void* q, const void* k_pool, i
                          const int32_t* req_seg_off, int max_seg_tokens, float* mass,
                          hipStream_t stream);
 bool score_mfma_supported(const cc_ctx* ctx);
-// bytes of the tile plan (per-segment tile offsets + tile descriptors) the MFMA kernels need
-size_t mfma_plan_bytes(int n_segs, int max_tiles);
+// bytes of the tile plan (per-segment tile offsets + tile descriptors, and the redo flags of up to
+// n_q_max query rows) the MFMA kernels need
+size_t mfma_plan_bytes(int n_segs, int max_tiles, int n_q_max);
 void launch_score_mfma(const cc_ctx* ctx, const void* q, const void* k_pool, int n_blocks,
                        const int32_t* block_tab, const cc_segment* segs, int n_segs,
                        const int32_t* req_seg_off, int max_seg_tokens, float* mass,
@@ -74,6 +75,9 @@ void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, co
                       int n_blocks, const int32_t* block_tab, const cc_segment* segs, int n_segs,
                       const int32_t* req_seg_off, int n_requests, void* out, float* lse,
                       void* plan_ws, int max_tiles, hipStream_t stream);
+
+// attention for head groups that are a multiple of 4: 64 query rows per wavefront (attn_mfma2.hip)
+bool attn_v2_supported(const cc_ctx* ctx);
 
 void launch_qkv_project(const cc_ctx* ctx, const void* x, const void* w, int n_rows, int hidden,
                         void* q, void* k, void* v, hipStream_t stream);

@@ -29,151 +29,13 @@
 // The XOR terms spread the *writes* of a coalesced global read over the LDS banks.
 #include <type_traits>
 
-#include "device_util.h"
+#include "mfma_tile.h"
 
 namespace cc {
 
+using namespace tile;
+
 namespace {
-
-constexpr int kD = 128;
-constexpr int kTile = 64;                      // keys per tile
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
-constexpr float kBig = 1.0e12f;                // a tile sum above this moves the reference maximum
-constexpr float kZeroBand = 24.f;              // first-block maxima within this keep the reference at 0
-
-__device__ __forceinline__ int swap23(int m) { return (m & ~12) | ((m & 4) << 1) | ((m & 8) >> 1); }
-__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
-
-// One key tile as the plan kernels lay it out (32 bytes, read with two 16-byte loads).
-struct TileDesc {
-  int32_t kpos0;     // logical position of the tile's first key
-  int32_t nvalid;    // keys of the tile that exist (1..64); the rest is block padding
-  int32_t blk[4];    // physical block of each of the four 16-token pages (-1: none)
-  int32_t seg;       // segment the tile belongs to
-  int32_t pad;
-};
-static_assert(sizeof(TileDesc) == 32, "descriptor is read as two 16-byte vectors");
-
-// a descriptor that came in through a (broadcast) vector load, moved to scalar registers
-__device__ __forceinline__ TileDesc to_scalar(const TileDesc& v) {
-  TileDesc d;
-  d.kpos0 = __builtin_amdgcn_readfirstlane(v.kpos0);
-  d.nvalid = __builtin_amdgcn_readfirstlane(v.nvalid);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) d.blk[i] = __builtin_amdgcn_readfirstlane(v.blk[i]);
-  d.seg = 0;
-  d.pad = 0;
-  return d;
-}
-
-// The index is laundered through a vector register on purpose: a scalar (SMEM) load here would
-// share the LDS operand reads' completion counter, return out of order, and force a full drain
-// of the operand ring every tile; a broadcast vector load is counted with the global loads.
-__device__ __forceinline__ TileDesc fetch_desc(const TileDesc* __restrict__ tiles, int j, int max_tiles) {
-  int jj = min(max(j, 0), max_tiles - 1);
-  asm volatile("" : "+v"(jj));
-  const uint4* src = reinterpret_cast<const uint4*>(tiles + jj);
-  union { uint4 v[2]; TileDesc d; } u;
-  u.v[0] = src[0];
-  u.v[1] = src[1];
-  return u.d;
-}
-
-// LDS piece index of piece `cc_` (0..255, pool order) of page `pg` of the K / V tile image.
-__device__ __forceinline__ int k_piece_dst(int pg, int cc_) {
-  const int slot = cc_ >> 4, ch = cc_ & 15;
-  // key a = 16*pg + slot of the tile -> block a/32, MFMA row swap23(a%32)
-  return ((pg >> 1) * 8 + (ch >> 1)) * 64 + (ch & 1) * 32 + (((pg & 1) * 16 + swap23(slot)) ^ (ch & 7));
-}
-__device__ __forceinline__ int v_piece_dst(int pg, int cc_) {
-  const int dcol = cc_ >> 1, hh = cc_ & 1;
-  return 1024 + (pg * 4 + (dcol >> 5)) * 64 + hh * 32 + ((dcol & 31) ^ (4 * hh));
-}
-// V piece with the slots >= nv (padding of a partly filled block) zeroed.
-__device__ __forceinline__ uint4 zero_pad_slots(uint4 val, int hh, int nv) {
-  unsigned short e[8];
-  *reinterpret_cast<uint4*>(e) = val;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) if (8 * hh + j >= nv) e[j] = 0;
-  return *reinterpret_cast<uint4*>(e);
-}
-
-// Staging of one key tile (and, if WITH_V, the value tile) of KV head `kvh` for workgroups of 256
-// or 512 threads.  A thread owns the same 16-byte piece of every page it stages (thread t ->
-// piece t % 256, so a wavefront instruction reads one contiguous KiB of a page); with 512 threads
-// the lower half of the workgroup takes pages {0,1} and the upper half pages {2,3}.  Block ids
-// come from the tile descriptor (already in registers), so all data loads are issued back to back
-// with no memory access in between, one tile ahead of their use (load), and are written to the
-// LDS image later (store).
-// Slots past the segment's end are staged as zeros so that stale or non-finite padding can never
-// reach a product.
-template <int NT, bool WITH_V>
-struct Stager {
-  static_assert(NT == 256 || NT == 512, "register-prefetch staging needs 256 or 512 threads");
-  static constexpr int kPagesPerThread = 1024 / NT;          // 4 or 2 pages of each pool
-  static constexpr int PER = kPagesPerThread * (WITH_V ? 2 : 1);
-  uint4 reg[PER];
-  const bf16_t* k_src;   // pool + head offset + this thread's piece
-  const bf16_t* v_src;
-  size_t blk_stride;     // elements per block (all heads)
-  int n_blocks, in_page, pg0;
-
-  __device__ __forceinline__ void init(const bf16_t* k_pool, const bf16_t* v_pool, int n_blocks_,
-                                       int hkv, int kvh, int tid) {
-    in_page = tid & 255;
-    pg0 = NT == 512 ? uniform(tid >> 8) * 2 : 0;             // first page this thread stages
-    k_src = k_pool + static_cast<size_t>(kvh) * (kBlock * kD) + in_page * 8;
-    v_src = WITH_V ? v_pool + static_cast<size_t>(kvh) * (kBlock * kD) + in_page * 8 : nullptr;
-    blk_stride = static_cast<size_t>(hkv) * (kBlock * kD);
-    n_blocks = n_blocks_;
-  }
-
-  __device__ __forceinline__ void load(const TileDesc& d) {
-    const int nvalid = uniform(d.nvalid);
-    int blk[kPagesPerThread];
-    bool all_ok = nvalid == kTile;
-#pragma unroll
-    for (int j = 0; j < kPagesPerThread; ++j) {
-      blk[j] = uniform(NT == 512 ? (pg0 ? d.blk[2 + j] : d.blk[j]) : d.blk[j]);
-      all_ok = all_ok && blk[j] >= 0 && blk[j] < n_blocks;
-    }
-    if (all_ok) {                                            // whole tile present (wave-uniform)
-#pragma unroll
-      for (int j = 0; j < kPagesPerThread; ++j) {
-        reg[j] = *reinterpret_cast<const uint4*>(k_src + static_cast<size_t>(blk[j]) * blk_stride);
-        if constexpr (WITH_V)
-          reg[kPagesPerThread + j] = *reinterpret_cast<const uint4*>(v_src + static_cast<size_t>(blk[j]) * blk_stride);
-      }
-      return;
-    }
-#pragma unroll
-    for (int j = 0; j < kPagesPerThread; ++j) {
-      const int pg = pg0 + j;
-      const int nv = min(max(nvalid - kBlock * pg, 0), kBlock);
-      const bool ok = nv > 0 && blk[j] >= 0 && blk[j] < n_blocks;
-      uint4 kv = make_uint4(0u, 0u, 0u, 0u), vv = make_uint4(0u, 0u, 0u, 0u);
-      if (ok) {
-        if ((in_page >> 4) < nv)                             // token slot of this K piece
-          kv = *reinterpret_cast<const uint4*>(k_src + static_cast<size_t>(blk[j]) * blk_stride);
-        if constexpr (WITH_V) {
-          vv = *reinterpret_cast<const uint4*>(v_src + static_cast<size_t>(blk[j]) * blk_stride);
-          if (nv < kBlock) vv = zero_pad_slots(vv, in_page & 1, nv);
-        }
-      }
-      reg[j] = kv;
-      if constexpr (WITH_V) reg[kPagesPerThread + j] = vv;
-    }
-  }
-
-  __device__ __forceinline__ void store(uint4* lds) const {
-#pragma unroll
-    for (int j = 0; j < kPagesPerThread; ++j) {
-      lds[k_piece_dst(pg0 + j, in_page)] = reg[j];
-      if constexpr (WITH_V) lds[v_piece_dst(pg0 + j, in_page)] = reg[kPagesPerThread + j];
-    }
-  }
-};
 
 // Small workgroups (64 or 128 threads; head groups of 1 or 2): the tile does not fit in registers,
 // so it is copied piece by piece without prefetch.  Correct, not fast.
@@ -205,21 +67,6 @@ __device__ __forceinline__ void stage_direct(uint4* lds, const bf16_t* __restric
   }
 }
 
-__device__ __forceinline__ float max16(const f32x16& v) {
-  float a = fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3]));
-  float b = fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7]));
-  float c = fmaxf(fmaxf(v[8], v[9]), fmaxf(v[10], v[11]));
-  float d = fmaxf(fmaxf(v[12], v[13]), fmaxf(v[14], v[15]));
-  return fmaxf(fmaxf(a, b), fmaxf(c, d));
-}
-
-__device__ __forceinline__ f32x16 splat16(float v) {
-  f32x16 r;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) r[i] = v;
-  return r;
-}
-
 // SCORE = true : queries are 32*QB consecutive tokens of a chunk segment; result is the share of
 //                the softmax mass that falls on keys of earlier segments (Eq. (2), Eq. (10)).
 // SCORE = false: queries are 32*QB rows of the compact query list; result is the attention
@@ -231,7 +78,7 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
     const TileDesc* __restrict__ tiles, const int32_t* __restrict__ seg_tile_off, int max_tiles,
     const int32_t* __restrict__ order, const cc_segment* __restrict__ segs, const int32_t* __restrict__ req_seg_off, int hq, int hkv,
     int n_tiles_x, InvFreq inv_freq, bf16_t* __restrict__ out, float* __restrict__ lse,
-    float* __restrict__ mass) {
+    float* __restrict__ mass, const int32_t* __restrict__ redo) {
   constexpr int NT = 64 * G;
   constexpr int TQ = 32 * QB;                       // query tokens per workgroup
   constexpr bool kPrefetch = NT >= 256;
@@ -271,6 +118,8 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
     const int r = order[blockIdx.y];                   // longest contexts are dispatched first
     const int q0 = cu_q[r] + tile * TQ, q_end = cu_q[r + 1];
     if (q0 >= q_end) return;
+    // second pass behind the wide kernel: only the 64-row tiles it flagged
+    if (redo != nullptr && redo[redo_index(cu_q[r] + (tile * TQ / 64) * 64)] == 0) return;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       row[qb] = min(q0 + 32 * qb + n, q_end - 1);
@@ -665,8 +514,10 @@ __global__ __launch_bounds__(256) void plan_scan_kernel(const cc_segment* __rest
 __global__ __launch_bounds__(256) void plan_fill_kernel(const cc_segment* __restrict__ segs, int n_segs,
                                                          const int32_t* __restrict__ seg_tile_off,
                                                          const int32_t* __restrict__ block_tab, int n_blocks,
-                                                         int max_tiles, TileDesc* __restrict__ tiles) {
+                                                         int max_tiles, TileDesc* __restrict__ tiles,
+                                                         int32_t* __restrict__ redo, int n_redo) {
   const int j = blockIdx.x * 256 + threadIdx.x;
+  for (int i = j; i < n_redo; i += gridDim.x * 256) redo[i] = 0;
   if (j >= min(seg_tile_off[n_segs], max_tiles)) return;
   int lo = 0, hi = n_segs - 1;                       // last segment with seg_tile_off[s] <= j
   while (lo < hi) {
@@ -730,48 +581,18 @@ __global__ __launch_bounds__(256) void plan_order_kernel(const cc_segment* __res
 constexpr int kAttnQB = 1;     // 32 query tokens per workgroup in the attention kernel
 constexpr int kScoreQB = 2;    // 64 in the score kernel (no O accumulator, so registers allow it)
 
-// workspace: seg_tile_off[n_segs + 1] | order[n_segs] (requests never outnumber segments) | tiles
-size_t plan_head_bytes(int n_segs) {
-  return (static_cast<size_t>(2 * n_segs + 1) * sizeof(int32_t) + 255) / 256 * 256;
-}
-
-size_t plan_bytes_impl(int n_segs, int max_tiles) {
-  return plan_head_bytes(n_segs) + static_cast<size_t>(max_tiles) * sizeof(TileDesc);
-}
-
-struct Plan { int32_t* seg_tile_off; int32_t* order; TileDesc* tiles; int max_tiles; };
-
-Plan run_plan(void* ws, const cc_segment* segs, int n_segs, const int32_t* req_seg_off, int n_requests,
-              const int32_t* block_tab, int n_blocks, int max_tiles, hipStream_t stream) {
-  Plan pl;
-  pl.seg_tile_off = static_cast<int32_t*>(ws);
-  pl.order = pl.seg_tile_off + n_segs + 1;
-  pl.tiles = reinterpret_cast<TileDesc*>(static_cast<char*>(ws) + plan_head_bytes(n_segs));
-  pl.max_tiles = max_tiles;
-  if (n_requests > 0)                                  // attention: the grid's y index walks requests
-    hipLaunchKernelGGL(plan_order_kernel<true>, dim3((n_requests + 255) / 256), dim3(256), 0, stream, segs,
-                       req_seg_off, n_requests, pl.order);
-  else                                                 // score: it walks segments
-    hipLaunchKernelGGL(plan_order_kernel<false>, dim3((n_segs + 255) / 256), dim3(256), 0, stream, segs,
-                       req_seg_off, n_segs, pl.order);
-  hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(256), 0, stream, segs, n_segs, pl.seg_tile_off);
-  hipLaunchKernelGGL(plan_fill_kernel, dim3((max_tiles + 255) / 256), dim3(256), 0, stream, segs, n_segs,
-                     pl.seg_tile_off, block_tab, n_blocks, max_tiles, pl.tiles);
-  return pl;
-}
-
 template <int G>
 void launch_attn_g(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
                    int max_q_per_req, const void* k_pool, const void* v_pool, int n_blocks,
                    const Plan& pl, const cc_segment* segs, const int32_t* req_seg_off,
-                   int n_requests, void* out, float* lse, hipStream_t stream) {
+                   int n_requests, void* out, float* lse, const int32_t* redo, hipStream_t stream) {
   const int hkv = ctx->cfg.n_kv_heads, n_tiles = (max_q_per_req + 32 * kAttnQB - 1) / (32 * kAttnQB);
   dim3 grid(hkv * n_tiles, n_requests);
   hipLaunchKernelGGL((sparse_qk_kernel<G, false, kAttnQB>), grid, dim3(64 * G), 0, stream,
                      static_cast<const bf16_t*>(q), q_pos, cu_q, static_cast<const bf16_t*>(k_pool),
                      static_cast<const bf16_t*>(v_pool), n_blocks, pl.tiles, pl.seg_tile_off, pl.max_tiles,
                      pl.order, segs, req_seg_off, ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq,
-                     static_cast<bf16_t*>(out), lse, static_cast<float*>(nullptr));
+                     static_cast<bf16_t*>(out), lse, static_cast<float*>(nullptr), redo);
 }
 
 template <int G>
@@ -785,7 +606,8 @@ void launch_score_g(const cc_ctx* ctx, const void* q, const void* k_pool, int n_
                      static_cast<const int32_t*>(nullptr), static_cast<const bf16_t*>(k_pool),
                      static_cast<const bf16_t*>(nullptr), n_blocks, pl.tiles, pl.seg_tile_off, pl.max_tiles,
                      pl.order, segs, req_seg_off, ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq,
-                     static_cast<bf16_t*>(nullptr), static_cast<float*>(nullptr), mass);
+                     static_cast<bf16_t*>(nullptr), static_cast<float*>(nullptr), mass,
+                     static_cast<const int32_t*>(nullptr));
 }
 
 bool group_supported(const cc_ctx* ctx) {
@@ -796,19 +618,57 @@ bool group_supported(const cc_ctx* ctx) {
 
 }  // namespace
 
+// workspace: seg_tile_off[n_segs + 1] | order[n_segs] (requests never outnumber segments) | tiles
+size_t plan_head_bytes(int n_segs) {
+  return (static_cast<size_t>(2 * n_segs + 1) * sizeof(int32_t) + 255) / 256 * 256;
+}
+
+static size_t plan_bytes_impl(int n_segs, int max_tiles) {
+  return plan_head_bytes(n_segs) + static_cast<size_t>(max_tiles) * sizeof(TileDesc);
+}
+
+Plan run_plan(void* ws, const cc_segment* segs, int n_segs, const int32_t* req_seg_off, int n_requests,
+              const int32_t* block_tab, int n_blocks, int max_tiles, int n_redo, hipStream_t stream) {
+  Plan pl;
+  pl.seg_tile_off = static_cast<int32_t*>(ws);
+  pl.order = pl.seg_tile_off + n_segs + 1;
+  pl.tiles = reinterpret_cast<TileDesc*>(static_cast<char*>(ws) + plan_head_bytes(n_segs));
+  pl.max_tiles = max_tiles;
+  pl.redo = n_redo > 0 ? reinterpret_cast<int32_t*>(pl.tiles + max_tiles) : nullptr;
+  if (n_requests > 0)                                  // attention: the grid's y index walks requests
+    hipLaunchKernelGGL(plan_order_kernel<true>, dim3((n_requests + 255) / 256), dim3(256), 0, stream, segs,
+                       req_seg_off, n_requests, pl.order);
+  else                                                 // score: it walks segments
+    hipLaunchKernelGGL(plan_order_kernel<false>, dim3((n_segs + 255) / 256), dim3(256), 0, stream, segs,
+                       req_seg_off, n_segs, pl.order);
+  hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(256), 0, stream, segs, n_segs, pl.seg_tile_off);
+  hipLaunchKernelGGL(plan_fill_kernel, dim3((max_tiles + 255) / 256), dim3(256), 0, stream, segs, n_segs,
+                     pl.seg_tile_off, block_tab, n_blocks, max_tiles, pl.tiles, pl.redo, n_redo);
+  return pl;
+}
+
 bool attn_mfma_supported(const cc_ctx* ctx) { return group_supported(ctx); }
 bool score_mfma_supported(const cc_ctx* ctx) { return group_supported(ctx); }
 
-size_t mfma_plan_bytes(int n_segs, int max_tiles) { return plan_bytes_impl(n_segs, max_tiles); }
+size_t mfma_plan_bytes(int n_segs, int max_tiles, int n_q_max) {
+  return plan_bytes_impl(n_segs, max_tiles) + redo_entries(n_q_max) * sizeof(int32_t);
+}
 
 void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
                       int n_q_tot, int max_q_per_req, const void* k_pool, const void* v_pool,
                       int n_blocks, const int32_t* block_tab, const cc_segment* segs, int n_segs,
                       const int32_t* req_seg_off, int n_requests, void* out, float* lse,
                       void* plan_ws, int max_tiles, hipStream_t stream) {
-  (void)n_q_tot;
-  const Plan pl = run_plan(plan_ws, segs, n_segs, req_seg_off, n_requests, block_tab, n_blocks, max_tiles, stream);
-#define CC_ARGS ctx, q, q_pos, cu_q, max_q_per_req, k_pool, v_pool, n_blocks, pl, segs, req_seg_off, n_requests, out, lse, stream
+  // Wide kernel first where the head group allows it; the narrow kernel then redoes the 64-row
+  // tiles the wide one flagged (normally none: its workgroups read one flag and exit).
+  const bool wide = ctx->impl != CC_IMPL_MFMA_NARROW && attn_v2_supported(ctx);
+  const int n_redo = wide ? static_cast<int>(redo_entries(n_q_tot)) : 0;
+  const Plan pl = run_plan(plan_ws, segs, n_segs, req_seg_off, n_requests, block_tab, n_blocks, max_tiles, n_redo, stream);
+  if (wide)
+    launch_attn_v2(ctx, q, q_pos, cu_q, max_q_per_req, k_pool, v_pool, n_blocks, pl, req_seg_off, n_requests,
+                   out, lse, pl.redo, stream);
+  const int32_t* redo = pl.redo;
+#define CC_ARGS ctx, q, q_pos, cu_q, max_q_per_req, k_pool, v_pool, n_blocks, pl, segs, req_seg_off, n_requests, out, lse, redo, stream
   switch (ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads) {
     case 1: launch_attn_g<1>(CC_ARGS); break;
     case 2: launch_attn_g<2>(CC_ARGS); break;
@@ -822,7 +682,7 @@ void launch_score_mfma(const cc_ctx* ctx, const void* q, const void* k_pool, int
                        const int32_t* block_tab, const cc_segment* segs, int n_segs,
                        const int32_t* req_seg_off, int max_seg_tokens, float* mass,
                        void* plan_ws, int max_tiles, hipStream_t stream) {
-  const Plan pl = run_plan(plan_ws, segs, n_segs, req_seg_off, 0, block_tab, n_blocks, max_tiles, stream);
+  const Plan pl = run_plan(plan_ws, segs, n_segs, req_seg_off, 0, block_tab, n_blocks, max_tiles, 0, stream);
 #define CC_ARGS ctx, q, k_pool, n_blocks, pl, segs, n_segs, req_seg_off, max_seg_tokens, mass, stream
   switch (ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads) {
     case 1: launch_score_g<1>(CC_ARGS); break;
