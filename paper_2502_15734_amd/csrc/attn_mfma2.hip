@@ -22,11 +22,19 @@
 // only if a block's sum of exponentials explodes; that block is then redone from its LDS image
 // with the reference raised and everything summed so far rescaled.
 //
-// Staging: three tile images in LDS.  In iteration t the wavefronts read image t and (for S of the
-// next tile's first block) image t+1, write image t+2 from registers and start the global loads
-// of tile t+3.  One s_barrier per tile.  LDS operations of a wavefront complete in order, so when
-// a wavefront reaches the barrier its stores to image t+2 have landed and its reads of image t
-// have returned; no counter has to be drained at the barrier.
+// Staging: four tile images in LDS, filled by loads that write LDS directly (global_load_lds, 16
+// bytes per lane: lane L of an instruction fills piece base + L, so the image layout is chosen by
+// the global address each lane is given).  Image of a tile (16-byte pieces):
+//   K piece (block b of 32 keys, k-step kk, half hh, MFMA row m):  (b*8+kk)*64 + hh*32 + m
+//   V piece (page pg, 32-dim group db, half hh, dim n):            1024 + (pg*4+db)*64 + hh*32 + n
+// so every MFMA operand read is the contiguous KiB  step*64 + lane.  In iteration t the wavefronts
+// read image t and (for S of the next tile's first block) image t+1 and start the loads of image
+// t+3; before the iteration's barrier each wavefront waits until its loads of image t+2 have
+// landed.  One s_barrier per tile.  LDS reads of a wavefront return in order, so when it reaches
+// the barrier its reads of image t have returned.  Block padding: K padding never reaches a
+// product (its S entries are masked by selection); V padding would, as 0 x garbage, so the
+// wavefront that loaded a V page blanks the page's padding slots in LDS before the barrier, in a
+// branch only a segment's last tile takes.
 #include <type_traits>
 
 #include "mfma_tile.h"
@@ -42,7 +50,7 @@ typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 
 constexpr int kImage = 2048;    // 16-byte pieces per tile image (K: 1024, V: 1024)
-constexpr int kBufs = 3;
+constexpr int kBufs = 4;
 constexpr int kDepth = 4;       // operand reads in flight ahead of the MFMAs
 // p = exp2(S - reference) may be large (fp32 and bf16 share the exponent range); a block sum
 // beyond this leaves no headroom for the row sum and O
@@ -53,51 +61,6 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-
-// Staging of one 64-key tile (K and V of one KV head) for 256 threads: a thread owns the same
-// 16-byte piece of each of the tile's four pages in both pools (thread t -> piece t, so a wavefront
-// instruction reads one contiguous KiB).  The loads are unconditional -- a page the tile does not
-// have is read from block 0 -- so the hot loop has no branch in them; padding slots and missing
-// pages are blanked in the registers when the image is stored, in a branch only a segment's last
-// tile takes.  (K padding never reaches a product: its S entries are masked by selection.  V
-// padding would, as 0 x garbage, so it must be exactly zero.)
-struct TileStager {
-  uint4 reg[8];                  // K pages 0..3, V pages 0..3
-  const bf16_t* k_src;           // pool + head offset + this thread's piece
-  const bf16_t* v_src;
-  size_t blk_stride;             // elements per block (all heads)
-  int piece;
-
-  __device__ __forceinline__ void init(const bf16_t* k_pool, const bf16_t* v_pool, int hkv, int kvh, int tid) {
-    piece = tid;
-    k_src = k_pool + static_cast<size_t>(kvh) * (kBlock * kD) + tid * 8;
-    v_src = v_pool + static_cast<size_t>(kvh) * (kBlock * kD) + tid * 8;
-    blk_stride = static_cast<size_t>(hkv) * (kBlock * kD);
-  }
-  __device__ __forceinline__ void load(const TileDesc& d) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const size_t off = static_cast<size_t>(max(d.blk[j], 0)) * blk_stride;
-      reg[j] = *reinterpret_cast<const uint4*>(k_src + off);
-      reg[4 + j] = *reinterpret_cast<const uint4*>(v_src + off);
-    }
-  }
-  __device__ __forceinline__ void store(uint4* lds, const TileDesc& d) {
-    if (d.nvalid < kTile || (d.blk[0] | d.blk[1] | d.blk[2] | d.blk[3]) < 0) {     // wave-uniform, rare
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int nv = d.blk[j] < 0 ? 0 : min(max(d.nvalid - kBlock * j, 0), kBlock);
-        if ((piece >> 4) >= nv) reg[j] = make_uint4(0u, 0u, 0u, 0u);
-        if (nv < kBlock) reg[4 + j] = zero_pad_slots(reg[4 + j], piece & 1, nv);
-      }
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      lds[k_piece_dst(j, piece)] = reg[j];
-      lds[v_piece_dst(j, piece)] = reg[4 + j];
-    }
-  }
-};
 
 // MFMA forms with fixed register classes (the compiler's own choice shuffles accumulators between
 // the two register files once a wavefront uses more than 256 registers): S accumulates in vector
@@ -121,6 +84,13 @@ __device__ __forceinline__ void zero_acc(f32x16& d) {
 // 32 idle issue slots: longer than the 8 passes of the MFMA plus its write-back
 __device__ __forceinline__ void mfma_result_wait() {
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+}
+// 64 lanes x 16 bytes from global memory straight into LDS: lane L's 16 bytes land at
+// lds_addr + 16 L (lds_addr wave-uniform).  Written as an instruction the compiler does not model:
+// it would otherwise drain every outstanding load before the next LDS read, because it cannot see
+// that the image being filled is not the image being read.  Completion is counted by vmcnt.
+__device__ __forceinline__ void load_to_lds(const void* src, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(src), "s"(lds_addr) : "memory", "m0");
 }
 // one 16-byte LDS piece straight into accumulation registers
 __device__ __forceinline__ u32x4 lds_to_acc(const uint4* p) {
@@ -207,12 +177,9 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
     }
   }
 
-  // lane-dependent part of the operand addresses (pieces), constant over the whole loop
-  int kx[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) kx[j] = hh * 32 + (n ^ ((2 * j + hh) & 7));
-  const int vx = 1024 + hh * 32 + (n ^ (4 * hh));
-
+  // byte offset of this lane's piece inside every 64-piece operand group
+  const int lane16 = lane * 16;
+  const char* lds_bytes = reinterpret_cast<const char*>(lds_all);
   float m_ref[QB], l_run[QB], lsum[QB], ev[QB];
   f32x16 o[QB][4];                    // running output, accumulation registers for the whole loop
   f32x16 sacc[QB][2];                 // S of the two 32-key blocks in flight (vector registers)
@@ -234,17 +201,16 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
   //   32..35  = steps 0..3 of the next iteration
   // Without a next tile steps 16..23 are the V pieces of pages 2, 3 and nothing follows.
   u32x4 ring[kDepth];
-  auto k_piece = [&](const uint4* im, int blk, int kk) __attribute__((always_inline)) { return *reinterpret_cast<const u32x4*>(&im[(blk * 8 + kk) * 64 + kx[kk & 3]]); };
-  auto v_piece = [&](const uint4* im, int idx) __attribute__((always_inline)) { return *reinterpret_cast<const u32x4*>(&im[idx * 64 + vx]); };
-  auto issue = [&](const uint4* img, const uint4* nimg, bool has_next, int s) __attribute__((always_inline)) {   // s: compile-time
-    if (s < 8) ring[s % kDepth] = k_piece(img, 1, s);
-    else if (s < 16) ring[s % kDepth] = v_piece(img, s - 8);
-    else if (s < 24) {
-      const uint4* a = &nimg[(s - 16) * 64 + kx[s & 3]];
-      const uint4* b = &img[(s - 8) * 64 + vx];
-      ring[s % kDepth] = *reinterpret_cast<const u32x4*>(has_next ? a : b);
-    } else if (s < 32) ring[s % kDepth] = v_piece(img, s - 16);
-    else ring[s % kDepth] = k_piece(nimg, 1, s - 32);       // harmless when there is no next tile
+  // operand group `step` of an image: 0..15 = K (block*8 + k-step), 16..31 = V (page*4 + dim group)
+  auto piece = [&](int img_off, int step) __attribute__((always_inline)) {
+    return *reinterpret_cast<const u32x4*>(lds_bytes + img_off + step * 1024 + lane16);
+  };
+  auto issue = [&](int img, int nimg, bool has_next, int s) __attribute__((always_inline)) {   // s: compile-time
+    if (s < 8) ring[s % kDepth] = piece(img, 8 + s);
+    else if (s < 16) ring[s % kDepth] = piece(img, 16 + (s - 8));
+    else if (s < 24) ring[s % kDepth] = has_next ? piece(nimg, s - 16) : piece(img, 16 + (s - 8));
+    else if (s < 32) ring[s % kDepth] = piece(img, 16 + (s - 16));
+    else ring[s % kDepth] = piece(nimg, 8 + (s - 32));      // harmless when there is no next tile
   };
 
   // one exponential: element i (0..15) of block parity bp; pairs are packed as they complete
@@ -258,7 +224,7 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
     else asm volatile("" :: "v"(lsum[qb]), "v"(pk[qb][bp][i >> 3][(i & 7) >> 1]));
   };
   // S block into parity bp from the ring; side(kk, qb) runs after each MFMA
-  auto s_slot = [&](const uint4* img, const uint4* nimg, bool has_next, int s0, int bp, auto&& side) __attribute__((always_inline)) {
+  auto s_slot = [&](int img, int nimg, bool has_next, int s0, int bp, auto&& side) __attribute__((always_inline)) {
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
 #pragma unroll
@@ -272,7 +238,7 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
     }
   };
   // PV of block parity bp: step st = (u, db): 16-key half u (page), 32-dim group db
-  auto pv_slot = [&](const uint4* img, const uint4* nimg, bool has_next, int s0, int bp, auto&& side) __attribute__((always_inline)) {
+  auto pv_slot = [&](int img, int nimg, bool has_next, int s0, int bp, auto&& side) __attribute__((always_inline)) {
 #pragma unroll
     for (int st = 0; st < 8; ++st) {
       const int u = st >> 2, db = st & 3;
@@ -315,29 +281,95 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
   };
 
   // ---- descriptors and staging --------------------------------------------------------------------
-  TileStager stg;
-  stg.init(k_pool, v_pool, hkv, kvh, tid);
-  auto image = [&](int t) __attribute__((always_inline)) { return lds_all + (t % kBufs) * kImage; };   // t >= 0
-  auto desc_at = [&](int t) __attribute__((always_inline)) { return fetch_desc(tiles, j_begin + min(t, n_t - 1), max_tiles); };
+  // The descriptors of 64 consecutive tiles sit in vector registers, one tile per lane, and are
+  // handed out with v_readlane: no memory access per tile.
+  int win_base = 0;
+  TileDesc win = fetch_desc(tiles, j_begin + min(lane, n_t - 1), max_tiles);
+  auto desc_of = [&](int t) __attribute__((always_inline)) {           // t in [win_base, win_base + 64)
+    const int l = t - win_base;
+    TileDesc d;
+    d.kpos0 = __builtin_amdgcn_readlane(win.kpos0, l);
+    d.nvalid = __builtin_amdgcn_readlane(win.nvalid, l);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) d.blk[i] = __builtin_amdgcn_readlane(win.blk[i], l);
+    d.seg = 0; d.pad = 0;
+    return d;
+  };
+  auto image_off = [&](int t) __attribute__((always_inline)) { return (t & (kBufs - 1)) * (kImage * 16); };   // bytes
+  // Loads of one tile, straight into image `img_off`.  Wavefront w brings K operand groups
+  // 4w..4w+3 (half a 32-key block over all 16 slots of two pages) and V page w.
+  const size_t blk_bytes = static_cast<size_t>(hkv) * (kBlock * kD) * sizeof(bf16_t);
+  const char* k_head = reinterpret_cast<const char*>(k_pool) + static_cast<size_t>(kvh) * (kBlock * kD * sizeof(bf16_t));
+  const char* v_head = reinterpret_cast<const char*>(v_pool) + static_cast<size_t>(kvh) * (kBlock * kD * sizeof(bf16_t));
+  // K: lane (hh, m) of group (b, kk) reads slot swap23(m % 16) of page 2b + m / 16, 16 bytes at dim 16kk + 8hh
+  const int k_lane_off = swap23(n & 15) * (kD * 2) + hh * 16;
+  const bool k_second_page = (n >> 4) != 0;
+  // V: lane (hh, n) of group (pg, db) reads slots 8hh.. of dim row 32db + n
+  const int v_lane_off = n * 32 + hh * 16;
+  typedef __attribute__((address_space(3))) const uint4 lds_piece;
+  const uint32_t lds_base = uniform(static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_piece*)lds_all)));   // LDS byte address
+  // (selections instead of indexing: the descriptor lives in scalar registers)
+  auto own_page = [&](const TileDesc& d) __attribute__((always_inline)) {
+    return wave == 0 ? d.blk[0] : wave == 1 ? d.blk[1] : wave == 2 ? d.blk[2] : d.blk[3];
+  };
+  const char* k_src = nullptr;                                           // of the tile being loaded
+  const char* v_src = nullptr;
+  uint32_t k_dst = 0;
+  auto dma_begin = [&](const TileDesc& d, int img_off) __attribute__((always_inline)) {
+    const bool upper = wave >= 2;                                        // K block this wavefront feeds
+    const size_t o0 = static_cast<size_t>(max(upper ? d.blk[2] : d.blk[0], 0)) * blk_bytes;
+    const size_t o1 = static_cast<size_t>(max(upper ? d.blk[3] : d.blk[1], 0)) * blk_bytes;
+    k_src = k_head + (k_second_page ? o1 : o0) + k_lane_off + (wave & 1) * 128;
+    v_src = v_head + static_cast<size_t>(max(own_page(d), 0)) * blk_bytes + v_lane_off;
+    k_dst = lds_base + img_off + (4 * wave) * 1024;
+  };
+  auto dma_part = [&](int j) __attribute__((always_inline)) {           // j = 0..3: one K group, one V group
+    load_to_lds(k_src + 32 * j, k_dst + 1024 * j);
+    load_to_lds(v_src + 1024 * j, k_dst + 16 * 1024 + 1024 * j);
+  };
+  auto dma_tile = [&](const TileDesc& d, int img_off) __attribute__((always_inline)) {
+    dma_begin(d, img_off);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) dma_part(j);
+  };
+  // blank the padding slots of the V page this wavefront loaded (rare; after its loads have landed)
+  auto blank_padding = [&](const TileDesc& d, int img_off) __attribute__((always_inline)) {
+    if (d.nvalid < kTile || (d.blk[0] | d.blk[1] | d.blk[2] | d.blk[3]) < 0) {
+      const int nv = own_page(d) < 0 ? 0 : min(max(d.nvalid - kBlock * wave, 0), kBlock);
+      if (nv < kBlock) {
+        uint4* vp = reinterpret_cast<uint4*>(const_cast<char*>(lds_bytes) + img_off + (16 + 4 * wave) * 1024 + lane16);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) vp[j * 64] = zero_pad_slots(vp[j * 64], hh, nv);
+      }
+    }
+  };
+  // wait until at most `newer` of this wavefront's vector-memory operations are outstanding
+  auto wait_loads = [&](auto newer) __attribute__((always_inline)) {
+    constexpr int kN = decltype(newer)::value;
+    __builtin_amdgcn_s_waitcnt((kN & 15) | ((kN >> 4) << 14) | (7 << 4) | (15 << 8));
+    asm volatile("" ::: "memory");
+  };
   auto barrier = [&]() __attribute__((always_inline)) {
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
   };
 
-  // prologue: images 0 and 1, loads of tile 2, S of block 0 and the first half of its exponentials
-  TileDesc d0 = to_scalar(desc_at(0)), d1 = to_scalar(desc_at(1)), d2 = to_scalar(desc_at(2));
-  TileDesc d3 = to_scalar(desc_at(3));
-  stg.load(d0); stg.store(image(0), d0);
-  if (n_t > 1) { stg.load(d1); stg.store(image(1), d1); }
-  stg.load(d2);
-  TileDesc d4v = desc_at(4), d4 = d3;
+  // prologue: images 0, 1, 2; S of block 0 and the first half of its exponentials
+  TileDesc d0 = desc_of(0), d1 = desc_of(min(1, n_t - 1)), d2 = desc_of(min(2, n_t - 1)), d3 = d2;
+  dma_tile(d0, image_off(0));
+  dma_tile(d1, image_off(1));
+  dma_tile(d2, image_off(2));
+  wait_loads(std::integral_constant<int, 0>{});
+  blank_padding(d0, image_off(0));
+  blank_padding(d1, image_off(1));
+  blank_padding(d2, image_off(2));
   __syncthreads();
   {
-    const uint4* img = image(0);
+    const int img = image_off(0);
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
-      const u32x4 a = k_piece(img, 0, kk);
+      const u32x4 a = piece(img, kk);
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
         if (kk == 0) mfma_s_first(sacc[qb][0], a, qreg[qb][kk]);
@@ -368,18 +400,16 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
   // from the masking branches.
   auto tile_front = [&](auto next_tag, int t) __attribute__((always_inline)) {
     constexpr bool kNext = decltype(next_tag)::value;
-    const uint4* img = image(t);
-    const uint4* nimg = kNext ? image(t + 1) : img;
+    const int img = image_off(t);
+    const int nimg = kNext ? image_off(t + 1) : img;
     // slot 1: S of the tile's second block; second half of the first block's exponentials.
-    // Underneath: image t+2 out of the staging registers, loads of tile t+3, descriptor of tile
-    // t+5 (past the last tile these repeat the last tile into an image nobody reads).
-    uint4* wimg = image(t + 2);
+    // Underneath: the loads of image t+3 (past the last tile they repeat the last tile into an
+    // image nobody reads).
     s_slot(img, nimg, kNext, 0, 1, [&](int kk, int qb) __attribute__((always_inline)) {
       exp_one(qb, 0, 8 + kk);
-      if (qb == QB - 1) {
-        if (kk == 1) stg.store(wimg, d2);
-        if (kk == 3) { d4 = to_scalar(d4v); stg.load(d3); }
-        if (kk == 5) d4v = desc_at(t + 5);
+      if (kNext && qb == QB - 1) {                       // two loads under each of four k-steps
+        if (kk == 0) { d3 = desc_of(min(t + 3, n_t - 1)); dma_begin(d3, image_off(t + 3)); }
+        if (kk >= 1 && kk <= 4) dma_part(kk - 1);
       }
     });
     close_block();
@@ -391,8 +421,12 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
   using LastT = std::integral_constant<bool, false>;
   int t = 0;
   for (; t + 1 < n_t; ++t) {
-    const uint4* img = image(t);
-    const uint4* nimg = image(t + 1);
+    const int img = image_off(t), nimg = image_off(t + 1);
+    if (t + 3 - win_base >= 64) {                        // next 64 descriptors (rare)
+      win_base += 64;
+      win = fetch_desc(tiles, j_begin + min(win_base + lane, n_t - 1), max_tiles);
+      __builtin_amdgcn_s_waitcnt((7 << 4) | (15 << 8));      // vmcnt(0) here, so the hot path never waits for it
+    }
     tile_front(NextT{}, t);
     // slot 3: S of the next tile's first block; second half of the second block's exponentials
     s_slot(img, nimg, true, 16, 0, [&](int kk, int qb) __attribute__((always_inline)) { exp_one(qb, 1, 8 + kk); });
@@ -400,8 +434,11 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
     if (d1.nvalid < kTile || d1.kpos0 + kTile - 1 > p_min) mask_block(0, 0, d1.kpos0, d1.nvalid);
     // slot 4: PV of the second block; first half of the next block's exponentials
     pv_slot(img, nimg, true, 24, 1, [&](int st, int qb) __attribute__((always_inline)) { exp_one(qb, 0, st); });
+    // image t+2 (loads started one iteration ago) must be whole before anyone reads it
+    wait_loads(std::integral_constant<int, 8>{});
+    blank_padding(d2, image_off(t + 2));
     barrier();
-    d0 = d1; d1 = d2; d2 = d3; d3 = d4;
+    d0 = d1; d1 = d2; d2 = d3;
   }
   {
     tile_front(LastT{}, t);
@@ -410,7 +447,7 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) exp_one(qb, 1, i);
     close_block();
-    pv_slot(image(t), image(t), false, 16, 1, no_side);
+    pv_slot(image_off(t), image_off(t), false, 16, 1, no_side);
   }
   mfma_result_wait();
 

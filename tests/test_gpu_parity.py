@@ -97,14 +97,14 @@ def check_workload(w, impl, score_tol=5e-5):
 
 def _impls():
     import paper_2502_15734_amd as P
-    return {"auto": P.CC_IMPL_AUTO, "scalar": P.CC_IMPL_SCALAR}
+    return {"auto": P.CC_IMPL_AUTO, "scalar": P.CC_IMPL_SCALAR, "narrow": P.CC_IMPL_MFMA_NARROW}
 
 
 def test_config1_tiny_fp32():
     check_workload(W.config(1), _impls()["auto"], score_tol=2e-6)
 
 
-@pytest.mark.parametrize("impl", ["auto", "scalar"])
+@pytest.mark.parametrize("impl", ["auto", "scalar", "narrow"])
 @pytest.mark.parametrize("hq,hkv", [(8, 2), (16, 2), (4, 2), (2, 2)])
 def test_small_bf16_ragged(impl, hq, hkv):
     # chunk lengths off the 16-token grid, several 64-key tiles, ragged query tiles, two requests
@@ -116,7 +116,7 @@ def test_small_bf16_ragged(impl, hq, hkv):
     check_workload(w, _impls()[impl])
 
 
-@pytest.mark.parametrize("impl", ["auto", "scalar"])
+@pytest.mark.parametrize("impl", ["auto", "scalar", "narrow"])
 def test_small_bf16_stronger_logits(impl):
     # larger logit spread (scores genuinely scattered); still inside what bf16 keys can rank
     reqs = [W.RequestSpec([1, 0, 2], [0.2, 0.3, 0.25], 19)]
@@ -187,7 +187,7 @@ def test_reference_repair_path_when_later_keys_dwarf_the_first_tile(kval):
     w.k_new[:64, :, 124:128] = 0.0
     res = O.run(w)
     assert res[0].lse.min() < -30 and res[0].lse[res[0].q_pos >= 64].min() > -5      # the intended regime
-    for impl in ("auto", "scalar"):
+    for impl in ("auto", "scalar", "narrow"):
         b = DeviceBatch(w, impl=_impls()[impl], poison=True)
         b.step(); torch.cuda.synchronize()
         gsel = H.gpu_selection(w, b.sel_idx.cpu().numpy())
