@@ -106,7 +106,7 @@ size_t cc_select_workspace_bytes(const cc_ctx* ctx, int32_t n_tok, int32_t n_seg
   if (ctx == nullptr || n_tok < 0 || n_segs < 0) return 0;
   return cc::align_up(static_cast<size_t>(n_tok) * ctx->cfg.n_q_heads * sizeof(float), 256) +
          cc::align_up(static_cast<size_t>(n_tok) * sizeof(uint32_t), 256) +
-         cc::align_up(cc::mfma_plan_bytes(n_segs, max_tiles_for(n_tok, n_segs), 0), 256) + 256;
+         cc::align_up(cc::mfma_plan_bytes(n_segs, max_tiles_for(n_tok, n_segs), n_tok), 256) + 256;
 }
 
 int cc_select(cc_ctx* ctx, const void* q, int32_t n_tok, const void* k_pool, int32_t n_blocks,
@@ -134,7 +134,7 @@ int cc_select(cc_ctx* ctx, const void* q, int32_t n_tok, const void* k_pool, int
   void* plan_ws = reinterpret_cast<char*>(keys) + cc::align_up(static_cast<size_t>(n_tok) * sizeof(uint32_t), 256);
   if (ctx->impl != CC_IMPL_SCALAR && cc::score_mfma_supported(ctx))
     cc::launch_score_mfma(ctx, q, k_pool, n_blocks, block_tab, segs, n_segs, req_seg_off,
-                          max_seg_tokens, mass, plan_ws, max_tiles_for(n_tok, n_segs), st);
+                          max_seg_tokens, mass, plan_ws, max_tiles_for(n_tok, n_segs), n_tok, st);
   else
     cc::launch_score_scalar(ctx, q, k_pool, n_blocks, block_tab, segs, n_segs, req_seg_off,
                             max_seg_tokens, mass, st);

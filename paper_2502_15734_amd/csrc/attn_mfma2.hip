@@ -92,6 +92,16 @@ __device__ __forceinline__ void mfma_result_wait() {
 __device__ __forceinline__ void load_to_lds(const void* src, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(src), "s"(lds_addr) : "memory", "m0");
 }
+// v = exp2(a - m); l += pending (the previous element's exponential).  Written out so that it stays
+// where it is placed, under one MFMA (the compiler otherwise lumps the exponentials of a block
+// together or sinks them to their use), and so that the transcendental result is not read by
+// the instruction right behind it.
+__device__ __forceinline__ float exp2_sub_sum(float& l, float pending, float a, float m) {
+  float t, v;
+  asm volatile("v_sub_f32 %1, %4, %5\n\tv_exp_f32 %2, %1\n\tv_add_f32 %0, %0, %3"
+               : "+v"(l), "=&v"(t), "=&v"(v) : "v"(pending), "v"(a), "v"(m));
+  return v;
+}
 // one 16-byte LDS piece straight into accumulation registers
 __device__ __forceinline__ u32x4 lds_to_acc(const uint4* p) {
   typedef __attribute__((address_space(3))) const uint4 lds_piece;
@@ -180,14 +190,14 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
   // byte offset of this lane's piece inside every 64-piece operand group
   const int lane16 = lane * 16;
   const char* lds_bytes = reinterpret_cast<const char*>(lds_all);
-  float m_ref[QB], l_run[QB], lsum[QB], ev[QB];
+  float m_ref[QB], l_run[QB], lsum[QB], ev[QB], vprev[QB];
   f32x16 o[QB][4];                    // running output, accumulation registers for the whole loop
   f32x16 sacc[QB][2];                 // S of the two 32-key blocks in flight (vector registers)
   uint32_t pk[QB][2][2][4];           // P^T of [block parity][16-key half], packed bf16 pairs
   bool overflow = false;              // some block's sum of exponentials left the safe range
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
-    m_ref[qb] = 0.f; l_run[qb] = 0.f; lsum[qb] = 0.f; ev[qb] = 0.f;
+    m_ref[qb] = 0.f; l_run[qb] = 0.f; lsum[qb] = 0.f; ev[qb] = 0.f; vprev[qb] = 0.f;
 #pragma unroll
     for (int db = 0; db < 4; ++db) zero_acc(o[qb][db]);
   }
@@ -213,15 +223,17 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
     else ring[s % kDepth] = piece(nimg, 8 + (s - 32));      // harmless when there is no next tile
   };
 
-  // one exponential: element i (0..15) of block parity bp; pairs are packed as they complete
+  // one exponential: element i (0..15) of block parity bp; pairs are packed as they complete.  The
+  // add into the row sum runs one element behind (vprev), so that no instruction reads a
+  // transcendental result right after it was issued.
   auto exp_one = [&](int qb, int bp, int i) __attribute__((always_inline)) {
-    const float v = __builtin_amdgcn_exp2f(sacc[qb][bp][i] - m_ref[qb]);
-    lsum[qb] += v;
+    const float v = exp2_sub_sum(lsum[qb], vprev[qb], sacc[qb][bp][i], m_ref[qb]);
+    vprev[qb] = v;
     if ((i & 1) == 0) ev[qb] = v;
-    else pk[qb][bp][i >> 3][(i & 7) >> 1] = pack_bf16(ev[qb], v);
-    // fake uses: keep the work under the MFMA it was placed under (otherwise it is sunk to its use)
-    if ((i & 1) == 0) asm volatile("" :: "v"(lsum[qb]), "v"(ev[qb]));
-    else asm volatile("" :: "v"(lsum[qb]), "v"(pk[qb][bp][i >> 3][(i & 7) >> 1]));
+    else {
+      pk[qb][bp][i >> 3][(i & 7) >> 1] = pack_bf16(ev[qb], v);
+      asm volatile("" :: "v"(pk[qb][bp][i >> 3][(i & 7) >> 1]));     // keep the pack here, not at its use
+    }
   };
   // S block into parity bp from the ring; side(kk, qb) runs after each MFMA
   auto s_slot = [&](int img, int nimg, bool has_next, int s0, int bp, auto&& side) __attribute__((always_inline)) {
@@ -274,6 +286,8 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
   auto close_block = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
+      lsum[qb] += vprev[qb];
+      vprev[qb] = 0.f;
       overflow = overflow || !(lsum[qb] < kSafeSum);
       l_run[qb] += lsum[qb];
       lsum[qb] = 0.f;

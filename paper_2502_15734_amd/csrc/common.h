@@ -55,7 +55,7 @@ size_t mfma_plan_bytes(int n_segs, int max_tiles, int n_q_max);
 void launch_score_mfma(const cc_ctx* ctx, const void* q, const void* k_pool, int n_blocks,
                        const int32_t* block_tab, const cc_segment* segs, int n_segs,
                        const int32_t* req_seg_off, int max_seg_tokens, float* mass,
-                       void* plan_ws, int max_tiles, hipStream_t stream);
+                       void* plan_ws, int max_tiles, int n_tok, hipStream_t stream);
 void launch_topn(const cc_ctx* ctx, const float* mass, const int32_t* block_tab,
                  const cc_segment* segs, int n_segs, int32_t* sel_idx, int32_t* q_row,
                  int32_t* q_pos, int32_t* slot_map, float* scores, uint32_t* key_buf,
@@ -78,6 +78,8 @@ void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, co
 
 // attention for head groups that are a multiple of 4: 64 query rows per wavefront (attn_mfma2.hip)
 bool attn_v2_supported(const cc_ctx* ctx);
+// score stage for the same head groups: 128 tokens per wavefront (score_mfma2.hip)
+bool score_v2_supported(const cc_ctx* ctx);
 
 void launch_qkv_project(const cc_ctx* ctx, const void* x, const void* w, int n_rows, int hidden,
                         void* q, void* k, void* v, hipStream_t stream);

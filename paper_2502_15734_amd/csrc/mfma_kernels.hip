@@ -104,6 +104,8 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
     const cc_segment sg = segs[seg_id];
     const int t0 = tile * TQ;
     if (sg.kind != CC_SEG_CHUNK || t0 >= sg.n_tokens || sg.logical_start == 0) return;
+    // second pass behind the wide kernel: only the 64-row granules it flagged
+    if (redo != nullptr && (redo[(sg.tok_off + t0) >> 6] | redo[(sg.tok_off + t0 + TQ - 1) >> 6]) == 0) return;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       const int t = min(t0 + 32 * qb + n, sg.n_tokens - 1);
@@ -598,7 +600,7 @@ void launch_attn_g(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const
 template <int G>
 void launch_score_g(const cc_ctx* ctx, const void* q, const void* k_pool, int n_blocks, const Plan& pl,
                     const cc_segment* segs, int n_segs, const int32_t* req_seg_off, int max_seg_tokens,
-                    float* mass, hipStream_t stream) {
+                    float* mass, const int32_t* redo, hipStream_t stream) {
   const int hkv = ctx->cfg.n_kv_heads, n_tiles = (max_seg_tokens + 32 * kScoreQB - 1) / (32 * kScoreQB);
   dim3 grid(hkv * n_tiles, n_segs);
   hipLaunchKernelGGL((sparse_qk_kernel<G, true, kScoreQB>), grid, dim3(64 * G), 0, stream,
@@ -606,8 +608,7 @@ void launch_score_g(const cc_ctx* ctx, const void* q, const void* k_pool, int n_
                      static_cast<const int32_t*>(nullptr), static_cast<const bf16_t*>(k_pool),
                      static_cast<const bf16_t*>(nullptr), n_blocks, pl.tiles, pl.seg_tile_off, pl.max_tiles,
                      pl.order, segs, req_seg_off, ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq,
-                     static_cast<bf16_t*>(nullptr), static_cast<float*>(nullptr), mass,
-                     static_cast<const int32_t*>(nullptr));
+                     static_cast<bf16_t*>(nullptr), static_cast<float*>(nullptr), mass, redo);
 }
 
 bool group_supported(const cc_ctx* ctx) {
@@ -681,9 +682,16 @@ void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, co
 void launch_score_mfma(const cc_ctx* ctx, const void* q, const void* k_pool, int n_blocks,
                        const int32_t* block_tab, const cc_segment* segs, int n_segs,
                        const int32_t* req_seg_off, int max_seg_tokens, float* mass,
-                       void* plan_ws, int max_tiles, hipStream_t stream) {
-  const Plan pl = run_plan(plan_ws, segs, n_segs, req_seg_off, 0, block_tab, n_blocks, max_tiles, 0, stream);
-#define CC_ARGS ctx, q, k_pool, n_blocks, pl, segs, n_segs, req_seg_off, max_seg_tokens, mass, stream
+                       void* plan_ws, int max_tiles, int n_tok, hipStream_t stream) {
+  // Wide kernel first where the head group allows it; the narrow kernel then redoes the granules
+  // the wide one flagged (normally none: its workgroups read two flags and exit).
+  const bool wide = ctx->impl != CC_IMPL_MFMA_NARROW && score_v2_supported(ctx);
+  const int n_redo = wide ? static_cast<int>(score_redo_entries(n_tok)) : 0;
+  const Plan pl = run_plan(plan_ws, segs, n_segs, req_seg_off, 0, block_tab, n_blocks, max_tiles, n_redo, stream);
+  if (wide)
+    launch_score_v2(ctx, q, k_pool, n_blocks, pl, segs, n_segs, req_seg_off, max_seg_tokens, mass, pl.redo, stream);
+  const int32_t* redo = pl.redo;
+#define CC_ARGS ctx, q, k_pool, n_blocks, pl, segs, n_segs, req_seg_off, max_seg_tokens, mass, redo, stream
   switch (ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads) {
     case 1: launch_score_g<1>(CC_ARGS); break;
     case 2: launch_score_g<2>(CC_ARGS); break;

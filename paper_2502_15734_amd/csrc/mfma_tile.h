@@ -193,4 +193,11 @@ void launch_attn_v2(const cc_ctx* ctx, const void* q, const int32_t* q_pos, cons
                     const Plan& pl, const int32_t* req_seg_off, int n_requests, void* out, float* lse,
                     int32_t* redo, hipStream_t stream);
 
+// The wide score kernel (128 tokens per wavefront, no softmax reference) flags 64-row granules of
+// the per-token tensors whose sums left the safe range; the narrow kernel redoes them.
+inline size_t score_redo_entries(int n_tok) { return static_cast<size_t>(n_tok) / 64 + 2; }
+void launch_score_v2(const cc_ctx* ctx, const void* q, const void* k_pool, int n_blocks, const Plan& pl,
+                     const cc_segment* segs, int n_segs, const int32_t* req_seg_off, int max_seg_tokens,
+                     float* mass, int32_t* redo, hipStream_t stream);
+
 }  // namespace cc
