@@ -548,14 +548,36 @@ __global__ __launch_bounds__(256) void plan_fill_kernel(const cc_segment* __rest
 // kMaxOrdered items: identity.
 constexpr int kMaxOrdered = 4096;
 
+//
+// Beside order[] the kernel writes one 32-byte work item per rank, so that a workgroup of the
+// wide kernels finds everything it needs to start with ONE load instead of a chain of dependent
+// ones (order -> segment -> request -> tile offsets).
 template <bool BY_REQUEST>
 __global__ __launch_bounds__(256) void plan_order_kernel(const cc_segment* __restrict__ segs,
                                                           const int32_t* __restrict__ req_seg_off,
-                                                          int n_items, int32_t* __restrict__ order) {
+                                                          const int32_t* __restrict__ seg_tile_off,
+                                                          int n_items, int32_t* __restrict__ order,
+                                                          WorkItem* __restrict__ items) {
   __shared__ int key[kMaxOrdered];
   const int i = blockIdx.x * 256 + threadIdx.x;
+  auto emit = [&](int rank, int item) {
+    order[rank] = item;
+    WorkItem w;
+    if constexpr (BY_REQUEST) {
+      w.id = item; w.kind = 0; w.start = 0; w.n_tokens = 0; w.tok_off = 0;
+      w.j_begin = seg_tile_off[req_seg_off[item]];
+      w.j_own = seg_tile_off[req_seg_off[item + 1]];           // end of the request's tiles
+    } else {
+      const cc_segment sg = segs[item];
+      w.id = item; w.kind = sg.kind; w.start = sg.logical_start; w.n_tokens = sg.n_tokens; w.tok_off = sg.tok_off;
+      w.j_begin = seg_tile_off[req_seg_off[sg.req]];
+      w.j_own = seg_tile_off[item];
+    }
+    w.pad = 0;
+    items[rank] = w;
+  };
   if (n_items > kMaxOrdered) {
-    if (i < n_items) order[i] = i;
+    if (i < n_items) emit(i, i);
     return;
   }
   for (int j = threadIdx.x; j < n_items; j += 256) {
@@ -577,7 +599,7 @@ __global__ __launch_bounds__(256) void plan_order_kernel(const cc_segment* __res
     const int other = key[j];
     rank += (other > mine || (other == mine && j < i)) ? 1 : 0;
   }
-  order[rank] = i;
+  emit(rank, i);
 }
 
 constexpr int kAttnQB = 1;     // 32 query tokens per workgroup in the attention kernel
@@ -619,9 +641,13 @@ bool group_supported(const cc_ctx* ctx) {
 
 }  // namespace
 
-// workspace: seg_tile_off[n_segs + 1] | order[n_segs] (requests never outnumber segments) | tiles
-size_t plan_head_bytes(int n_segs) {
+// workspace: seg_tile_off[n_segs + 1] | order[n_segs] (requests never outnumber segments) |
+//            items[n_segs] | tiles | redo flags
+static size_t plan_ints_bytes(int n_segs) {
   return (static_cast<size_t>(2 * n_segs + 1) * sizeof(int32_t) + 255) / 256 * 256;
+}
+size_t plan_head_bytes(int n_segs) {
+  return plan_ints_bytes(n_segs) + (static_cast<size_t>(n_segs) * sizeof(WorkItem) + 255) / 256 * 256;
 }
 
 static size_t plan_bytes_impl(int n_segs, int max_tiles) {
@@ -633,16 +659,17 @@ Plan run_plan(void* ws, const cc_segment* segs, int n_segs, const int32_t* req_s
   Plan pl;
   pl.seg_tile_off = static_cast<int32_t*>(ws);
   pl.order = pl.seg_tile_off + n_segs + 1;
+  pl.items = reinterpret_cast<WorkItem*>(static_cast<char*>(ws) + plan_ints_bytes(n_segs));
   pl.tiles = reinterpret_cast<TileDesc*>(static_cast<char*>(ws) + plan_head_bytes(n_segs));
   pl.max_tiles = max_tiles;
   pl.redo = n_redo > 0 ? reinterpret_cast<int32_t*>(pl.tiles + max_tiles) : nullptr;
+  hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(256), 0, stream, segs, n_segs, pl.seg_tile_off);
   if (n_requests > 0)                                  // attention: the grid's y index walks requests
     hipLaunchKernelGGL(plan_order_kernel<true>, dim3((n_requests + 255) / 256), dim3(256), 0, stream, segs,
-                       req_seg_off, n_requests, pl.order);
+                       req_seg_off, pl.seg_tile_off, n_requests, pl.order, pl.items);
   else                                                 // score: it walks segments
     hipLaunchKernelGGL(plan_order_kernel<false>, dim3((n_segs + 255) / 256), dim3(256), 0, stream, segs,
-                       req_seg_off, n_segs, pl.order);
-  hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(256), 0, stream, segs, n_segs, pl.seg_tile_off);
+                       req_seg_off, pl.seg_tile_off, n_segs, pl.order, pl.items);
   hipLaunchKernelGGL(plan_fill_kernel, dim3((max_tiles + 255) / 256), dim3(256), 0, stream, segs, n_segs,
                      pl.seg_tile_off, block_tab, n_blocks, max_tiles, pl.tiles, pl.redo, n_redo);
   return pl;

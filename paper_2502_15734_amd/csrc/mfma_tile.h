@@ -174,7 +174,20 @@ __device__ __forceinline__ f32x16 splat16(float v) {
 }  // namespace tile
 
 // ---- tile plan (built by plan kernels on the stream, kept in the caller's workspace) ----------
-struct Plan { int32_t* seg_tile_off; int32_t* order; tile::TileDesc* tiles; int max_tiles; int32_t* redo; };
+// What the workgroups of grid row y need to start: the segment (score) or request (attention) of
+// dispatch rank y and where its key tiles begin.
+struct WorkItem {
+  int32_t id;         // segment / request index
+  int32_t kind;       // segment kind (score)
+  int32_t start;      // segment's logical start (score)
+  int32_t n_tokens;   // segment length (score)
+  int32_t tok_off;    // segment's first row in per-token tensors (score)
+  int32_t j_begin;    // first key tile of the request
+  int32_t j_own;      // first tile of the segment itself (score); end of the request's tiles (attention)
+  int32_t pad;
+};
+static_assert(sizeof(WorkItem) == 32, "read as two 16-byte vectors");
+struct Plan { int32_t* seg_tile_off; int32_t* order; WorkItem* items; tile::TileDesc* tiles; int max_tiles; int32_t* redo; };
 size_t plan_head_bytes(int n_segs);
 // n_requests > 0: dispatch order over requests (attention); 0: over segments (score).
 // n_redo > 0: the plan also holds n_redo redo flags (after the tiles), cleared by the plan kernels.

@@ -4,11 +4,12 @@
 //
 // One workgroup = 4 wavefronts = 4 query heads of one KV head x 128 consecutive tokens of a chunk;
 // a wavefront owns one head and all 128 tokens (four 32-row MFMA column blocks), so every K operand
-// it reads from LDS feeds four MFMAs and one staged K tile serves 512 (token, head) columns.  One
-// wavefront per SIMD: the four rotated query blocks sit in accumulation registers (128), two S
-// blocks in vector registers (128).  Keys advance in 32-key blocks; the matrix pipe sees S(b+1)
-// while the vector ALU takes the exponentials of S(b), two per MFMA -- the vector ALU, not the
-// matrix pipe, is what bounds this kernel (one exp2 and one add per 2 d flops).
+// it reads from LDS feeds four MFMAs and one staged K tile serves 512 (token, head) columns.  The
+// four rotated query blocks sit in accumulation registers (128), one S block in vector registers
+// (64): 256 registers in all, so two workgroups share a compute unit.  A wavefront alternates
+// between the 32 MFMAs of a 32-key block and the block's 64 exponentials; the two wavefronts of a
+// SIMD fall out of phase, so the matrix pipe works for one while the vector ALU works for the
+// other.  The two phases cost about the same (one exp2 and one add per 2 d flops).
 //
 // Orientation, key permutation and masking are those of mfma_tile.h: S^T = K Q^T with
 // v_mfma_f32_32x32x16_bf16, a lane holds one token column, the sums stay lane-local.  The query is
@@ -55,8 +56,7 @@ __device__ __forceinline__ void load_to_lds(const void* src, uint32_t lds_addr) 
 
 // MFMA forms with fixed register classes (see attn_mfma2.hip): S accumulates in vector registers,
 // the rotated query is the B operand out of accumulation registers.  The results are opaque to the
-// compiler's hazard handling, so every vector-ALU read of them is either a whole 32-MFMA slot
-// behind its producer (steady state) or behind mfma_result_wait().
+// compiler's hazard handling, so the vector ALU reads them only behind mfma_result_wait().
 __device__ __forceinline__ void mfma_s_first(f32x16& d, const u32x4& a, const u32x4& b) {
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
 }
@@ -84,11 +84,10 @@ __device__ __forceinline__ u32x4 lds_to_acc(const uint4* p) {
   return r;
 }
 
-__global__ __launch_bounds__(256, 1) void score_v2_kernel(
+__global__ __launch_bounds__(256, 2) void score_v2_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k_pool, int n_blocks,
-    const TileDesc* __restrict__ tiles, const int32_t* __restrict__ seg_tile_off, int max_tiles,
-    const int32_t* __restrict__ order, const cc_segment* __restrict__ segs,
-    const int32_t* __restrict__ req_seg_off, int hq, int hkv, int n_sub, int n_tiles_x,
+    const TileDesc* __restrict__ tiles, int max_tiles,
+    const WorkItem* __restrict__ items, int hq, int hkv, int n_sub, int n_tiles_x,
     InvFreq inv_freq, float* __restrict__ mass, int32_t* __restrict__ redo) {
   __shared__ uint4 lds_all[kBufs * kImageK];
   const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
@@ -100,12 +99,12 @@ __global__ __launch_bounds__(256, 1) void score_v2_kernel(
   const int h = kvh * (4 * n_sub) + hsub * 4 + wave;
 
   // ---- which tokens ---------------------------------------------------------------------------
-  const int seg_id = order[blockIdx.y];                      // heaviest segments are dispatched first
-  // (segment fields into scalar registers; token indices are recomputed from them where needed,
-  // which keeps the vector registers for the queries and the S block)
-  const int sg_kind = uniform(segs[seg_id].kind), sg_req = uniform(segs[seg_id].req);
-  const int sg_start = uniform(segs[seg_id].logical_start), sg_ntok = uniform(segs[seg_id].n_tokens);
-  const int sg_tok_off = uniform(segs[seg_id].tok_off);
+  // (one load; the fields go to scalar registers, token indices are recomputed from them where
+  // needed, which keeps the vector registers for the queries and the S blocks)
+  const uint4* ip = reinterpret_cast<const uint4*>(items + blockIdx.y);      // heaviest segments first
+  const uint4 i0 = ip[0], i1 = ip[1];
+  const int sg_kind = uniform(i0.y), sg_start = uniform(i0.z), sg_ntok = uniform(i0.w);
+  const int sg_tok_off = uniform(i1.x), j_begin = uniform(i1.y), j_own = uniform(i1.z);
   const int t0 = tile * kTQ;
   if (sg_kind != CC_SEG_CHUNK || t0 >= sg_ntok || sg_start == 0) return;
   // token of column block qb in this lane (clamped into the chunk)
@@ -114,8 +113,6 @@ __global__ __launch_bounds__(256, 1) void score_v2_kernel(
   const int p_max = sg_start + min(t0 + kTQ, sg_ntok) - 1;
 
   // ---- key tiles: everything before the chunk, then the chunk's own tiles up to the last token --
-  const int j_begin = seg_tile_off[req_seg_off[sg_req]];
-  const int j_own = seg_tile_off[seg_id];
   const int n_t = uniform(min(j_own + (p_max - sg_start) / kTile + 1, max_tiles) - j_begin);
   const int t_own = uniform(j_own - j_begin);                         // first tile of the token's own chunk
   if (n_t <= 0) return;
@@ -202,63 +199,47 @@ __global__ __launch_bounds__(256, 1) void score_v2_kernel(
     asm volatile("" ::: "memory");
   };
 
-  // ---- one slot: S of a 32-key block, the previous block's exponentials underneath -------------------
+  // ---- one 32-key block: S, masking, exponentials, sums ---------------------------------------------
   u32x4 ring[kDepth];
-  f32x16 sacc[kQB][2];                // S of the two blocks in flight
-  float lsum[kQB];
-#pragma unroll
-  for (int qb = 0; qb < kQB; ++qb) lsum[qb] = 0.f;
+  f32x16 sacc[kQB];
   auto piece = [&](int img_off, int step) __attribute__((always_inline)) {
     return *reinterpret_cast<const u32x4*>(lds_bytes + img_off + step * 1024 + lane16);
   };
-  // two exponentials of block parity bp: elements 2j, 2j+1 of column block qb
-  auto exp_two = [&](int qb, int bp, int j) __attribute__((always_inline)) {
-    exp2_sum2(lsum[qb], sacc[qb][bp][2 * j], sacc[qb][bp][2 * j + 1]);
-  };
-  // S of tile block blk of image img_off into parity bp; the ring holds the block's first kDepth
-  // pieces on entry and the next block's (nimg_off, nblk) on exit; with_exp: exponentials of the
-  // other parity run underneath, two per MFMA
-  auto s_slot = [&](int img_off, int blk, int nimg_off, int nblk, int bp, auto with_exp) __attribute__((always_inline)) {
-    constexpr bool kExp = decltype(with_exp)::value;
+  // tile block blk of image img_off; the ring holds the block's first kDepth pieces on entry and
+  // the next block's (nimg_off, nblk) on exit
+  auto block = [&](int img_off, int blk, int nimg_off, int nblk, const TileDesc& d) __attribute__((always_inline)) {
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
 #pragma unroll
       for (int qb = 0; qb < kQB; ++qb) {
-        if (kk == 0) mfma_s_first(sacc[qb][bp], ring[kk % kDepth], qreg[qb][kk]);
-        else mfma_s_acc(sacc[qb][bp], ring[kk % kDepth], qreg[qb][kk]);
-        if (qb == kQB - 1) {
-          const int s = kk + kDepth;
-          ring[kk % kDepth] = s < 8 ? piece(img_off, blk * 8 + s) : piece(nimg_off, nblk * 8 + (s - 8));
-        }
-        // MFMA number 4 kk + qb of the slot takes elements 2 (kk % 2 * 4 + qb) .. of column block kk / 2
-        if (kExp) exp_two(kk >> 1, bp ^ 1, (kk & 1) * 4 + qb);
-        __builtin_amdgcn_sched_barrier(0);
+        if (kk == 0) mfma_s_first(sacc[qb], ring[kk % kDepth], qreg[qb][kk]);
+        else mfma_s_acc(sacc[qb], ring[kk % kDepth], qreg[qb][kk]);
+      }
+      const int s = kk + kDepth;
+      ring[kk % kDepth] = s < 8 ? piece(img_off, blk * 8 + s) : piece(nimg_off, nblk * 8 + (s - 8));
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    mfma_result_wait();          // (idle issue slots: the SIMD's other wavefront runs meanwhile)
+    // padding / causal edge: entries the token must not see become -inf
+    // (accumulator register i holds key 32 blk + 16(i/8) + 8hh + i%8 of the tile)
+    if (d.nvalid < kTile || d.kpos0 + kTile - 1 > p_min) {
+#pragma unroll
+      for (int qb = 0; qb < kQB; ++qb) {
+        int lim = min(d.nvalid - 1, sg_start + token(qb) - d.kpos0) - 8 * hh - 32 * blk;
+        asm volatile("" : "+v"(lim));
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          sacc[qb][i] = (16 * (i / 8) + (i % 8) <= lim) ? sacc[qb][i] : -INFINITY;
       }
     }
-  };
-  using WithExp = std::integral_constant<bool, true>;
-  using NoExp = std::integral_constant<bool, false>;
-  // padding / causal edge: entries of parity bp (tile block blk) the token must not see become -inf
-  // (accumulator register i holds key 32 blk + 16(i/8) + 8hh + i%8 of the tile)
-  auto mask_block = [&](int bp, int blk, const TileDesc& d) __attribute__((always_inline)) {
-    mfma_result_wait();
+    // (an overflow shows in the sums: inf stays inf)
 #pragma unroll
-    for (int qb = 0; qb < kQB; ++qb) {
-      int lim = min(d.nvalid - 1, sg_start + token(qb) - d.kpos0) - 8 * hh - 32 * blk;
-      asm volatile("" : "+v"(lim));
+    for (int qb = 0; qb < kQB; ++qb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i)
-        sacc[qb][bp][i] = (16 * (i / 8) + (i % 8) <= lim) ? sacc[qb][bp][i] : -INFINITY;
-      asm volatile("" : "+v"(sacc[qb][bp]));
-    }
+      for (int j = 0; j < 8; ++j) exp2_sum2(l_run[qb], sacc[qb][2 * j], sacc[qb][2 * j + 1]);
   };
-  auto close_block = [&]() __attribute__((always_inline)) {       // (an overflow shows in the sums: inf stays inf)
-#pragma unroll
-    for (int qb = 0; qb < kQB; ++qb) { l_run[qb] += lsum[qb]; lsum[qb] = 0.f; }
-  };
-  auto edge = [&](const TileDesc& d) __attribute__((always_inline)) { return d.nvalid < kTile || d.kpos0 + kTile - 1 > p_min; };
 
-  // ---- prologue: images 0, 1, 2; S of block 0 ---------------------------------------------------------
+  // ---- prologue: images 0, 1, 2 ---------------------------------------------------------------------
   TileDesc d0 = desc_of(0), d1 = desc_of(min(1, n_t - 1)), d2 = desc_of(min(2, n_t - 1)), d3 = d2;
   dma_tile(d0, image_off(0));
   dma_tile(d1, image_off(1));
@@ -267,16 +248,11 @@ __global__ __launch_bounds__(256, 1) void score_v2_kernel(
   __syncthreads();
 #pragma unroll
   for (int s = 0; s < kDepth; ++s) ring[s] = piece(image_off(0), s);
-  s_slot(image_off(0), 0, image_off(0), 1, 0, NoExp{});
-  if (edge(d0)) mask_block(0, 0, d0);
 
   // ---- the tile loop --------------------------------------------------------------------------------
-  // on entry: parity 0 holds S of the tile's first block (masked), no exponentials taken yet; the
-  // ring holds the first pieces of the tile's second block
   for (int t = 0; t < n_t; ++t) {
     const int img = image_off(t);
-    const bool has_next = t + 1 < n_t;
-    const int nimg = has_next ? image_off(t + 1) : img;
+    const int nimg = t + 1 < n_t ? image_off(t + 1) : img;
     if (t + 3 - win_base >= 64) {                        // next 64 descriptors (rare)
       win_base += 64;
       win = fetch_desc(tiles, j_begin + min(win_base + lane, n_t - 1), max_tiles);
@@ -290,23 +266,8 @@ __global__ __launch_bounds__(256, 1) void score_v2_kernel(
     // loads of image t+3 (past the last tile they repeat the last tile into an image nobody reads)
     d3 = desc_of(min(t + 3, n_t - 1));
     dma_tile(d3, image_off(t + 3));
-    // slot 1: S of the tile's second block; exponentials of its first block
-    s_slot(img, 1, nimg, 0, 1, WithExp{});
-    close_block();
-    if (edge(d0)) mask_block(1, 1, d0);
-    if (has_next) {
-      // slot 2: S of the next tile's first block; exponentials of this tile's second block
-      s_slot(nimg, 0, nimg, 1, 0, WithExp{});
-      close_block();
-      if (edge(d1)) mask_block(0, 0, d1);
-    } else {
-      if (!edge(d0)) mfma_result_wait();                 // (mask_block has waited already)
-#pragma unroll
-      for (int qb = 0; qb < kQB; ++qb)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) exp_two(qb, 1, j);
-      close_block();
-    }
+    block(img, 0, img, 1, d0);
+    block(img, 1, nimg, 0, d0);
     // image t+2 (loads started one iteration ago) must be whole before anyone reads it
     wait_loads(std::integral_constant<int, 4>{});
     barrier();
@@ -349,8 +310,8 @@ void launch_score_v2(const cc_ctx* ctx, const void* q, const void* k_pool, int n
   const int n_tiles = (max_seg_tokens + kTQ - 1) / kTQ;
   dim3 grid(hkv * n_sub * n_tiles, n_segs);
   hipLaunchKernelGGL(score_v2_kernel, grid, dim3(256), 0, stream, static_cast<const bf16_t*>(q),
-                     static_cast<const bf16_t*>(k_pool), n_blocks, pl.tiles, pl.seg_tile_off, pl.max_tiles,
-                     pl.order, segs, req_seg_off, ctx->cfg.n_q_heads, hkv, n_sub, n_tiles, ctx->inv_freq,
+                     static_cast<const bf16_t*>(k_pool), n_blocks, pl.tiles, pl.max_tiles,
+                     pl.items, ctx->cfg.n_q_heads, hkv, n_sub, n_tiles, ctx->inv_freq,
                      mass, redo);
 }
 
