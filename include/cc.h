@@ -55,7 +55,7 @@ typedef enum {
 
 enum { CC_F32 = 0, CC_BF16 = 1 };
 enum { CC_SEG_CHUNK = 0, CC_SEG_QUESTION = 1 };
-enum { CC_IMPL_AUTO = 0, CC_IMPL_SCALAR = 1, CC_IMPL_MFMA_NARROW = 2 };   /* see cc_set_impl */
+enum { CC_IMPL_AUTO = 0, CC_IMPL_SCALAR = 1, CC_IMPL_MFMA_NARROW = 2, CC_IMPL_MFMA_WIDE = 3 };   /* see cc_set_impl */
 
 typedef struct {
   int32_t n_q_heads;     /* Hq                                   */
@@ -98,7 +98,9 @@ const char* cc_last_error(const cc_ctx* ctx);
 /* Kernel family used by cc_select / cc_sparse_prefill / cc_qkv_project: CC_IMPL_AUTO (default)
  * picks the fastest MFMA kernels built for the configuration (bf16, head_dim 128),
  * CC_IMPL_SCALAR forces the plain ones, CC_IMPL_MFMA_NARROW the MFMA kernels that give a
- * wavefront 32 query rows (the only MFMA form for head groups of 1 or 2). */
+ * wavefront 32 query rows (64 tokens in the score stage; the only MFMA form for head groups of
+ * 1 or 2), CC_IMPL_MFMA_WIDE the ones that give it 64 (128) even where AUTO would find the
+ * launch too small for them (head groups that are a multiple of 4; narrow otherwise). */
 int cc_set_impl(cc_ctx* ctx, int impl);
 
 /* ---- (a) re-position cached keys ----------------------------------------------------------

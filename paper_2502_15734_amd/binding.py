@@ -12,7 +12,7 @@ from typing import Optional
 import torch
 
 CC_F32, CC_BF16 = 0, 1
-CC_IMPL_AUTO, CC_IMPL_SCALAR, CC_IMPL_MFMA_NARROW = 0, 1, 2
+CC_IMPL_AUTO, CC_IMPL_SCALAR, CC_IMPL_MFMA_NARROW, CC_IMPL_MFMA_WIDE = 0, 1, 2, 3
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB: Optional[C.CDLL] = None
 

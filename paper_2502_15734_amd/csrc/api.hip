@@ -71,7 +71,7 @@ const char* cc_last_error(const cc_ctx* ctx) { return ctx ? ctx->last_error.c_st
 
 int cc_set_impl(cc_ctx* ctx, int impl) {
   if (ctx == nullptr) return CC_ERR_INVALID_ARG;
-  if (impl != CC_IMPL_AUTO && impl != CC_IMPL_SCALAR && impl != CC_IMPL_MFMA_NARROW)
+  if (impl != CC_IMPL_AUTO && impl != CC_IMPL_SCALAR && impl != CC_IMPL_MFMA_NARROW && impl != CC_IMPL_MFMA_WIDE)
     return fail(ctx, CC_ERR_INVALID_ARG, "cc_set_impl: unknown implementation id");
   ctx->impl = impl;
   return CC_OK;

@@ -675,6 +675,9 @@ Plan run_plan(void* ws, const cc_segment* segs, int n_segs, const int32_t* req_s
   return pl;
 }
 
+// fewest workgroups for which the wide kernels are chosen: 1.5 per compute unit of an MI355X
+constexpr int kMinWideGrid = 384;
+
 bool attn_mfma_supported(const cc_ctx* ctx) { return group_supported(ctx); }
 bool score_mfma_supported(const cc_ctx* ctx) { return group_supported(ctx); }
 
@@ -689,7 +692,11 @@ void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, co
                       void* plan_ws, int max_tiles, hipStream_t stream) {
   // Wide kernel first where the head group allows it; the narrow kernel then redoes the 64-row
   // tiles the wide one flagged (normally none: its workgroups read one flag and exit).
-  const bool wide = ctx->impl != CC_IMPL_MFMA_NARROW && attn_v2_supported(ctx);
+  // (a grid too small to give every compute unit a wide workgroup runs faster on the narrow
+  // kernel's twice as many, half as long workgroups)
+  const int wide_wgs = ctx->cfg.n_q_heads / 4 * ((max_q_per_req + 63) / 64) * n_requests;
+  const bool wide = ctx->impl != CC_IMPL_MFMA_NARROW && attn_v2_supported(ctx) &&
+                    (wide_wgs >= kMinWideGrid || ctx->impl == CC_IMPL_MFMA_WIDE);
   const int n_redo = wide ? static_cast<int>(redo_entries(n_q_tot)) : 0;
   const Plan pl = run_plan(plan_ws, segs, n_segs, req_seg_off, n_requests, block_tab, n_blocks, max_tiles, n_redo, stream);
   if (wide)
@@ -712,7 +719,9 @@ void launch_score_mfma(const cc_ctx* ctx, const void* q, const void* k_pool, int
                        void* plan_ws, int max_tiles, int n_tok, hipStream_t stream) {
   // Wide kernel first where the head group allows it; the narrow kernel then redoes the granules
   // the wide one flagged (normally none: its workgroups read two flags and exit).
-  const bool wide = ctx->impl != CC_IMPL_MFMA_NARROW && score_v2_supported(ctx);
+  const int wide_wgs = ctx->cfg.n_q_heads / 4 * ((max_seg_tokens + 127) / 128) * n_segs;
+  const bool wide = ctx->impl != CC_IMPL_MFMA_NARROW && score_v2_supported(ctx) &&
+                    (wide_wgs >= kMinWideGrid || ctx->impl == CC_IMPL_MFMA_WIDE);
   const int n_redo = wide ? static_cast<int>(score_redo_entries(n_tok)) : 0;
   const Plan pl = run_plan(plan_ws, segs, n_segs, req_seg_off, 0, block_tab, n_blocks, max_tiles, n_redo, stream);
   if (wide)

@@ -160,7 +160,7 @@ void launch_qkv_project(const cc_ctx* ctx, const void* x, const void* w, int n_r
                         void* q, void* k, void* v, hipStream_t stream) {
   const int d = ctx->cfg.head_dim;
   const int nq = ctx->cfg.n_q_heads * d, nk = ctx->cfg.n_kv_heads * d, n_cols = nq + 2 * nk;
-  if (ctx->cfg.dtype == CC_BF16 && ctx->impl == CC_IMPL_AUTO && n_cols % kTN == 0 && hidden % kTK == 0 &&
+  if (ctx->cfg.dtype == CC_BF16 && ctx->impl != CC_IMPL_SCALAR && n_cols % kTN == 0 && hidden % kTK == 0 &&
       nq % 32 == 0 && nk % 32 == 0) {
     dim3 grid(n_cols / kTN, (n_rows + kTM - 1) / kTM);
     hipLaunchKernelGGL(qkv_project_mfma_kernel, grid, dim3(512), 0, stream,

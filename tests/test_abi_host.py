@@ -89,6 +89,8 @@ def test_calls_reject_bad_arguments_before_launch(lib):
     # null context
     assert lib.cc_rope_shift(None, good, None, 4, good, None, 4, good, good, good, 1, 16, None) == -1
     assert lib.cc_set_impl(h, 99) == -1
+    for impl in (P.CC_IMPL_MFMA_NARROW, P.CC_IMPL_MFMA_WIDE, P.CC_IMPL_SCALAR, P.CC_IMPL_AUTO):
+        assert lib.cc_set_impl(h, impl) == 0
     ctx.close()
 
 

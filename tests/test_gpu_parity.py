@@ -97,14 +97,15 @@ def check_workload(w, impl, score_tol=5e-5):
 
 def _impls():
     import paper_2502_15734_amd as P
-    return {"auto": P.CC_IMPL_AUTO, "scalar": P.CC_IMPL_SCALAR, "narrow": P.CC_IMPL_MFMA_NARROW}
+    return {"auto": P.CC_IMPL_AUTO, "scalar": P.CC_IMPL_SCALAR, "narrow": P.CC_IMPL_MFMA_NARROW,
+            "wide": P.CC_IMPL_MFMA_WIDE}
 
 
 def test_config1_tiny_fp32():
     check_workload(W.config(1), _impls()["auto"], score_tol=2e-6)
 
 
-@pytest.mark.parametrize("impl", ["auto", "scalar", "narrow"])
+@pytest.mark.parametrize("impl", ["auto", "scalar", "narrow", "wide"])
 @pytest.mark.parametrize("hq,hkv", [(8, 2), (16, 2), (4, 2), (2, 2)])
 def test_small_bf16_ragged(impl, hq, hkv):
     # chunk lengths off the 16-token grid, several 64-key tiles, ragged query tiles, two requests
@@ -116,7 +117,7 @@ def test_small_bf16_ragged(impl, hq, hkv):
     check_workload(w, _impls()[impl])
 
 
-@pytest.mark.parametrize("impl", ["auto", "scalar", "narrow"])
+@pytest.mark.parametrize("impl", ["auto", "scalar", "narrow", "wide"])
 def test_small_bf16_stronger_logits(impl):
     # larger logit spread (scores genuinely scattered); still inside what bf16 keys can rank
     reqs = [W.RequestSpec([1, 0, 2], [0.2, 0.3, 0.25], 19)]
@@ -158,13 +159,14 @@ def test_zero_shift_is_bit_exact():
             assert np.array_equal(O.read_v_pages(vp, dst, n), O.read_v_pages(w.v_store, src, n))
 
 
-def test_config2_llama3_8b_layer_full():
-    check_workload(W.config(2), _impls()["auto"])
+@pytest.mark.parametrize("impl", ["auto", "wide"])
+def test_config2_llama3_8b_layer_full(impl):
+    check_workload(W.config(2), _impls()[impl])
 
 
 @pytest.mark.parametrize("cid,scale", [(3, 0.08), (4, 0.12)])
 def test_scaled_batch_configs(cid, scale):
-    check_workload(W.config(cid, scale), _impls()["auto"])
+    check_workload(W.config(cid, scale), _impls()["wide"])
 
 
 @pytest.mark.parametrize("kval", [-50.0, -141.0])
@@ -187,7 +189,7 @@ def test_reference_repair_path_when_later_keys_dwarf_the_first_tile(kval):
     w.k_new[:64, :, 124:128] = 0.0
     res = O.run(w)
     assert res[0].lse.min() < -30 and res[0].lse[res[0].q_pos >= 64].min() > -5      # the intended regime
-    for impl in ("auto", "scalar", "narrow"):
+    for impl in ("auto", "scalar", "narrow", "wide"):
         b = DeviceBatch(w, impl=_impls()[impl], poison=True)
         b.step(); torch.cuda.synchronize()
         gsel = H.gpu_selection(w, b.sel_idx.cpu().numpy())
@@ -217,7 +219,7 @@ def test_config5_scaled_with_projection(scale):
     from paper_2502_15734_amd.pipeline import DeviceBatch
     w = W.config(5, scale)
     assert w.hidden is not None
-    b = DeviceBatch(w, poison=True)
+    b = DeviceBatch(w, impl=_impls()["wide"], poison=True)
     b.step(); torch.cuda.synchronize()
     gsel = H.gpu_selection(w, b.sel_idx.cpu().numpy())
     res = O.run(w)
