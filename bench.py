@@ -28,8 +28,8 @@ MEASURED_MFMA_BF16_TFLOPS = 2054.0
 # HBM bytes per launch of each call's main kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # of this command scaled by a 512 MiB copy (profiles/hot_path_kernels_config3_8b_continuous_batch.md).
 MEASURED_TRAFFIC_BYTES = {
-    3: {"cc_rope_shift": (570.1 + 646.5) * 2 ** 20, "cc_select": (1446.1 + 69.3) * 2 ** 20,
-        "cc_sparse_prefill": (995.0 + 319.7 + 165.8 + 159.0) * 2 ** 20},
+    3: {"cc_rope_shift": (567.9 + 646.5) * 2 ** 20, "cc_select": (2653.0 + 34.3 + 17.3 + 1.3) * 2 ** 20,
+        "cc_sparse_prefill": (1042.9 + 319.6 + 165.8 + 159.0) * 2 ** 20},
 }
 
 
@@ -179,8 +179,8 @@ def main():
         s["frac"] = s["achieved"] / s["peak"]
     dominant = max(stages, key=lambda k: stages[k]["ms"])
     dom = stages[dominant]
-    kernel_of = {"cc_select": "sparse_qk_kernel<SCORE> (+ top-N, plan: ~1.5 % of the call)",
-                 "cc_sparse_prefill": "sparse_qk_kernel<ATTN> (+ rope_scatter, plan: ~9 % of the call)",
+    kernel_of = {"cc_select": "score_v2_kernel (+ top-N, plan, redo pass: ~2 % of the call)",
+                 "cc_sparse_prefill": "attn_v2_kernel (+ rope_scatter, plan, redo pass: ~8 % of the call)",
                  "cc_rope_shift": "rope_shift_kernel", "cc_gather_rows(+cc_qkv_project)": "qkv_project / gather_rows"}
     roofline = {"kernel": kernel_of[dominant], "call": dominant, "bound": dom["bound"], "achieved": dom["achieved"],
                 "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"],
