@@ -35,67 +35,77 @@ void launch_gather_rows(const void* src, int n_src_rows, const int32_t* row_idx,
 }
 
 // Rotate-and-scatter of the recomputed K/V rows into their cache slots.  Rows of the compact query
-// list that fall into the same 16-token block are adjacent (the order cc_select emits); the
-// workgroup of the first row of such a run handles the whole run, the others exit.  K rows are
-// token-major and written directly.  The V block is dimension-major -- a token is one element in
-// each of the block's d rows of 16 slots -- and isolated 2-byte stores cost a full memory write
-// each, so every (head, dim) row of the block is read, patched with the run's tokens in
-// registers, and written back whole.  This needs all rows of a block to sit in ONE run.
+// list that fall into the same 16-token block are adjacent (the order cc_select emits) and form a
+// run.  A workgroup looks at 16 consecutive rows and handles every run that STARTS among them (a
+// run may reach into the next workgroup's rows; it is still handled where it starts).
+//   K rows are token-major and written directly; the rotation angle of a (token, pair) is
+//   computed once and used for all KV heads.
+//   The V block is dimension-major -- a token is one element in each of the block's d rows of 16
+//   slots -- and isolated 2-byte stores cost a full memory write each, so every (head, dim) row
+//   of the block is read, patched with the run's tokens in registers, and written back whole.
+//   This needs all rows of a block to sit in ONE run.
+constexpr int kScatterRows = 16;     // candidate rows per workgroup
+
 template <typename T, int D>
 __global__ __launch_bounds__(256) void rope_scatter_kernel(
     const T* __restrict__ k_new, const T* __restrict__ v_new, const int32_t* __restrict__ q_pos,
     const int32_t* __restrict__ slot_map, int n_q_tot, int hkv, InvFreq inv_freq,
     T* __restrict__ k_pool, T* __restrict__ v_pool, int n_blocks) {
-  __shared__ int run_j[kBlock], run_sl[kBlock], run_n;
-  const int j0 = blockIdx.x, tid = threadIdx.x;
-  const int slot0 = slot_map[j0];
-  if (slot0 < 0 || slot0 >= n_blocks * kBlock) return;
-  const int blk = slot0 / kBlock;
-  if (j0 > 0) {
-    const int sp = slot_map[j0 - 1];
-    if (sp >= 0 && sp / kBlock == blk) return;      // not the first row of its run
-  }
-  if (tid == 0) {
-    int n = 0;
-    for (int j = j0; j < n_q_tot && n < kBlock; ++j) {
-      const int sl = slot_map[j];
-      if (sl < 0 || sl / kBlock != blk) break;
-      run_j[n] = j; run_sl[n] = sl % kBlock; ++n;
+  // slots of rows base-1 .. base+30: the row before the first candidate (is it the same block?) and
+  // the 15 rows a run starting at the last candidate can still cover; -1 = no row / invalid slot
+  __shared__ int sl[2 * kScatterRows];
+  const int tid = threadIdx.x, base = blockIdx.x * kScatterRows;
+  if (tid < 2 * kScatterRows) {
+    const int j = base - 1 + tid;
+    int v = -1;
+    if (j >= 0 && j < n_q_tot) {
+      v = slot_map[j];
+      if (v < 0 || v >= n_blocks * kBlock) v = -1;
     }
-    run_n = n;
+    sl[tid] = v;
   }
   __syncthreads();
-  const int n_run = run_n;
-  // K: one (token, head, pair) per thread and step
-  for (int idx = tid; idx < n_run * hkv * (D / 2); idx += 256) {
-    const int t = idx / (hkv * (D / 2)), rem = idx % (hkv * (D / 2)), h = rem / (D / 2), i = rem % (D / 2);
-    const int j = run_j[t];
-    float c, s;
-    rot_cos_sin(q_pos[j], inv_freq.f[i], &c, &s);
-    const T* kp = k_new + (static_cast<size_t>(j) * hkv + h) * D;
-    const float x = to_float(kp[i]), y = to_float(kp[i + D / 2]);
-    T* ko = k_pool + ((static_cast<size_t>(blk) * hkv + h) * kBlock + run_sl[t]) * D;
-    ko[i] = from_float<T>(x * c - y * s);
-    ko[i + D / 2] = from_float<T>(y * c + x * s);
-  }
-  // V: one (head, dim) row of 16 slots per thread and step
-  constexpr int kVec = kBlock * sizeof(T) / 16;      // 16-byte vectors per row
-  for (int idx = tid; idx < hkv * D; idx += 256) {
-    const int h = idx / D, dcol = idx % D;
-    uint4* rowp = reinterpret_cast<uint4*>(v_pool + ((static_cast<size_t>(blk) * hkv + h) * D + dcol) * kBlock);
-    T e[kBlock];
-    if (n_run < kBlock) {
-#pragma unroll
-      for (int v = 0; v < kVec; ++v) reinterpret_cast<uint4*>(e)[v] = rowp[v];
+  for (int c = 0; c < kScatterRows; ++c) {                 // candidate row base + c (workgroup-uniform loop)
+    const int slot0 = sl[c + 1];
+    if (slot0 < 0) continue;
+    const int blk = slot0 / kBlock;
+    if (sl[c] >= 0 && sl[c] / kBlock == blk) continue;     // not the first row of its run
+    int n_run = 1;
+    while (n_run < kBlock && sl[c + 1 + n_run] >= 0 && sl[c + 1 + n_run] / kBlock == blk) ++n_run;
+    const int j0 = base + c;
+    // K: one (token, pair) per thread and step, all KV heads
+    for (int idx = tid; idx < n_run * (D / 2); idx += 256) {
+      const int t = idx / (D / 2), i = idx % (D / 2);
+      const int j = j0 + t;
+      float cs, sn;
+      rot_cos_sin(q_pos[j], inv_freq.f[i], &cs, &sn);
+      const T* kp = k_new + static_cast<size_t>(j) * hkv * D;
+      T* ko = k_pool + (static_cast<size_t>(blk) * hkv * kBlock + sl[c + 1 + t] % kBlock) * D;
+      for (int h = 0; h < hkv; ++h) {
+        const float x = to_float(kp[h * D + i]), y = to_float(kp[h * D + i + D / 2]);
+        ko[static_cast<size_t>(h) * kBlock * D + i] = from_float<T>(x * cs - y * sn);
+        ko[static_cast<size_t>(h) * kBlock * D + i + D / 2] = from_float<T>(y * cs + x * sn);
+      }
     }
-    for (int t = 0; t < n_run; ++t) {
-      const T val = v_new[(static_cast<size_t>(run_j[t]) * hkv + h) * D + dcol];
-      const int sl = run_sl[t];
+    // V: one (head, dim) row of 16 slots per thread and step
+    constexpr int kVec = kBlock * sizeof(T) / 16;          // 16-byte vectors per row
+    for (int idx = tid; idx < hkv * D; idx += 256) {
+      const int h = idx / D, dcol = idx % D;
+      uint4* rowp = reinterpret_cast<uint4*>(v_pool + ((static_cast<size_t>(blk) * hkv + h) * D + dcol) * kBlock);
+      T e[kBlock];
+      if (n_run < kBlock) {
 #pragma unroll
-      for (int k = 0; k < kBlock; ++k) if (k == sl) e[k] = val;
+        for (int v = 0; v < kVec; ++v) reinterpret_cast<uint4*>(e)[v] = rowp[v];
+      }
+      for (int t = 0; t < n_run; ++t) {
+        const T val = v_new[(static_cast<size_t>(j0 + t) * hkv + h) * D + dcol];
+        const int s_ = sl[c + 1 + t] % kBlock;
+#pragma unroll
+        for (int k = 0; k < kBlock; ++k) if (k == s_) e[k] = val;
+      }
+#pragma unroll
+      for (int v = 0; v < kVec; ++v) rowp[v] = reinterpret_cast<uint4*>(e)[v];
     }
-#pragma unroll
-    for (int v = 0; v < kVec; ++v) rowp[v] = reinterpret_cast<uint4*>(e)[v];
   }
 }
 
@@ -106,7 +116,7 @@ void launch_rope_scatter(const cc_ctx* ctx, const void* k_new, const void* v_new
   const bool bf = ctx->cfg.dtype == CC_BF16;
   const int d = ctx->cfg.head_dim, hkv = ctx->cfg.n_kv_heads;
 #define CC_LAUNCH(T, D)                                                                          \
-  hipLaunchKernelGGL((rope_scatter_kernel<T, D>), dim3(n_q_tot), dim3(256), 0, stream,           \
+  hipLaunchKernelGGL((rope_scatter_kernel<T, D>), dim3((n_q_tot + kScatterRows - 1) / kScatterRows), dim3(256), 0, stream,           \
                      static_cast<const T*>(k_new), static_cast<const T*>(v_new), q_pos, slot_map, \
                      n_q_tot, hkv, ctx->inv_freq, static_cast<T*>(k_pool), static_cast<T*>(v_pool), n_blocks)
   if (bf && d == 128) CC_LAUNCH(bf16_t, 128);

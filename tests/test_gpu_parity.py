@@ -164,6 +164,17 @@ def test_config2_llama3_8b_layer_full(impl):
     check_workload(W.config(2), _impls()[impl])
 
 
+@pytest.mark.parametrize("impl", ["wide", "narrow"])
+def test_long_single_request_crosses_the_descriptor_window(impl):
+    # 69 key tiles for the last rows: the wide kernels hold 64 tile descriptors at a time and
+    # refill them in the loop; four LDS images are cycled 17 times.  Chunk lengths off the 64- and
+    # 128-token grids, a second short request for a ragged grid.
+    reqs = [W.RequestSpec([0, 1, 2], [0.02, 0.03, 0.2], 21), W.RequestSpec([2, 1], [0.1, 0.01], 9)]
+    w = W.custom("window", "bf16", 8, 2, 128, 5.0e5, [2045, 2050, 301], [0, 0, 0], reqs,
+                 1.0 / math.sqrt(128), seed=77)
+    check_workload(w, _impls()[impl])
+
+
 @pytest.mark.parametrize("cid,scale", [(3, 0.08), (4, 0.12)])
 def test_scaled_batch_configs(cid, scale):
     check_workload(W.config(cid, scale), _impls()["wide"])
