@@ -163,29 +163,32 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
   const float c2 = 0.08838834764831845f * kLog2e;            // log2(e) / sqrt(128)
   __shared__ uint4 q_bounce[256];     // one piece per lane: the way into the accumulation registers
   u32x4 qreg[QB][8];
+  // (called after the first tile loads are on their way, so that the trigonometry hides their latency)
+  auto load_queries = [&]() __attribute__((always_inline)) {
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const bf16_t* qp = q + (static_cast<size_t>(row[qb]) * hq + h) * kD + 8 * hh;
+    for (int qb = 0; qb < QB; ++qb) {
+      const bf16_t* qp = q + (static_cast<size_t>(row[qb]) * hq + h) * kD + 8 * hh;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      bf16x8 xv = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + 16 * kk));
-      bf16x8 yv = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + 16 * kk + 64));
+      for (int kk = 0; kk < 4; ++kk) {
+        bf16x8 xv = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + 16 * kk));
+        bf16x8 yv = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + 16 * kk + 64));
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        float c, s;
-        rot_cos_sin_fast(p[qb], inv_freq.f[16 * kk + 8 * hh + j], &c, &s);
-        c *= c2; s *= c2;
-        const float x = static_cast<float>(xv[j]), y = static_cast<float>(yv[j]);
-        xv[j] = static_cast<bf16_t>(x * c - y * s);
-        yv[j] = static_cast<bf16_t>(y * c + x * s);
+        for (int j = 0; j < 8; ++j) {
+          float c, s;
+          rot_cos_sin_fast(p[qb], inv_freq.f[16 * kk + 8 * hh + j], &c, &s);
+          c *= c2; s *= c2;
+          const float x = static_cast<float>(xv[j]), y = static_cast<float>(yv[j]);
+          xv[j] = static_cast<bf16_t>(x * c - y * s);
+          yv[j] = static_cast<bf16_t>(y * c + x * s);
+        }
+        q_bounce[tid] = __builtin_bit_cast(uint4, xv);
+        qreg[qb][kk] = lds_to_acc(&q_bounce[tid]);
+        q_bounce[tid] = __builtin_bit_cast(uint4, yv);
+        qreg[qb][kk + 4] = lds_to_acc(&q_bounce[tid]);
+        __builtin_amdgcn_sched_barrier(0);
       }
-      q_bounce[tid] = __builtin_bit_cast(uint4, xv);
-      qreg[qb][kk] = lds_to_acc(&q_bounce[tid]);
-      q_bounce[tid] = __builtin_bit_cast(uint4, yv);
-      qreg[qb][kk + 4] = lds_to_acc(&q_bounce[tid]);
-      __builtin_amdgcn_sched_barrier(0);
     }
-  }
+  };
 
   // byte offset of this lane's piece inside every 64-piece operand group
   const int lane16 = lane * 16;
@@ -374,6 +377,7 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
   dma_tile(d0, image_off(0));
   dma_tile(d1, image_off(1));
   dma_tile(d2, image_off(2));
+  load_queries();
   wait_loads(std::integral_constant<int, 0>{});
   blank_padding(d0, image_off(0));
   blank_padding(d1, image_off(1));
