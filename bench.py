@@ -153,6 +153,14 @@ def main():
     tokens_per_s = work["recomputed_tokens"] / (dt / args.steps)
 
     stage_ms = time_stages(batch, args.steps)
+    # selection from given scores (the scores cc_select just wrote, so the selection is unchanged)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    ev[0].record()
+    for i in range(args.steps):
+        batch.select_from_scores()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    from_scores_ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]))
     q_pos = batch.q_pos.cpu().numpy()[: w.n_q_tot]
     attn_flops = attention_flops(w, q_pos)
     proj_flops = 0.0
@@ -199,6 +207,8 @@ def main():
         "roofline": roofline,
         "stages": stages,
         "sparse_prefill_tokens_per_s": w.n_q_tot / (stage_ms["sparse_prefill"] * 1e-3),
+        # not part of the step: the selection half of cc_select alone, on scores the caller already has
+        "extra_calls": {"cc_select_from_scores": {"ms": from_scores_ms, "chunk_tokens": work["n_chunk_tok"]}},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, args.cpu_budget)

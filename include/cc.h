@@ -7,6 +7,7 @@
  *   cc_rope_shift      re-position cached keys (Sec. 3.4.3, Sec. 4 "RPE Management")
  *   cc_select          score chunk tokens by attention mass on prior chunks, keep the top N
  *                      (Eq. (2), Eq. (10), Sec. 3.2.1)
+ *   cc_select_from_scores  keep the top N of scores the caller already has (Sec. 3.2.1)
  *   cc_gather_rows     compact the rows of the chosen tokens
  *   cc_qkv_project     Q, K, V of the chosen tokens only (Sec. 3.4.3)
  *   cc_sparse_prefill  causal attention of the chosen tokens + question over the whole merged
@@ -143,6 +144,19 @@ int cc_select(cc_ctx* ctx, const void* q, int32_t n_tok,
               const int32_t* req_seg_off, int32_t n_requests, int32_t max_seg_tokens,
               int32_t* sel_idx, int32_t* q_row, int32_t* q_pos, int32_t* slot_map, int32_t n_q_tot,
               float* scores, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- (b') choose the tokens to recompute from given scores -----------------------------------
+ * The selection half of cc_select alone: the per-token scores are an input, e.g. the ordered
+ * token list a chunk's metadata keeps from cache time, when the attention weights came for free
+ * (Sec. 3.2.1; Sec. 3.4.3 "metadata").  Per chunk segment the n_select largest scores win (lower
+ * index among equals, ascending output); a chunk at logical_start 0 is treated like any other
+ * (its given scores count); question segments emit all tokens.  Outputs as for cc_select.
+ *   scores [n_tok] float, rows by tok_off (question rows ignored), read-only.
+ *   workspace: at least cc_select_workspace_bytes(ctx, n_tok, n_segs) bytes. */
+int cc_select_from_scores(cc_ctx* ctx, const float* scores, int32_t n_tok, const int32_t* block_tab,
+                          const cc_segment* segs, int32_t n_segs,
+                          int32_t* sel_idx, int32_t* q_row, int32_t* q_pos, int32_t* slot_map,
+                          int32_t n_q_tot, void* workspace, size_t workspace_bytes, void* stream);
 
 /* dst[i][:] = src[row_idx[i]][:] for i < n_rows; row_bytes a multiple of 16.  Compacts the rows
  * of the chosen tokens (hidden states before the projection, or given q / k / v rows). */

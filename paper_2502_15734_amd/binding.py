@@ -60,6 +60,8 @@ def load_library() -> C.CDLL:
     lib.cc_select.argtypes = [vp, vp, i32, vp, i32, vp, vp, i32, vp, i32, i32,
                               vp, vp, vp, vp, i32, vp, vp, sz, vp]
     lib.cc_select.restype = C.c_int
+    lib.cc_select_from_scores.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, vp, vp, i32, vp, sz, vp]
+    lib.cc_select_from_scores.restype = C.c_int
     lib.cc_gather_rows.argtypes = [vp, vp, i32, vp, i32, sz, vp, vp]
     lib.cc_gather_rows.restype = C.c_int
     lib.cc_qkv_project.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp]
@@ -133,6 +135,13 @@ class Context:
             self._h, _ptr(q), q.shape[0], _ptr(k_pool), k_pool.shape[0], _ptr(block_tab), _ptr(segs),
             segs.shape[0], _ptr(req_seg_off), n_requests, max_seg_tokens, _ptr(sel_idx), _ptr(q_row),
             _ptr(q_pos), _ptr(slot_map), sel_idx.shape[0], _ptr(scores), _ptr(workspace),
+            workspace.numel() * workspace.element_size(), _stream()))
+
+    # -- cc_select_from_scores ---------------------------------------------------------------
+    def select_from_scores(self, scores, block_tab, segs, sel_idx, q_row, q_pos, slot_map, workspace):
+        self._check(self._lib.cc_select_from_scores(
+            self._h, _ptr(scores), scores.shape[0], _ptr(block_tab), _ptr(segs), segs.shape[0],
+            _ptr(sel_idx), _ptr(q_row), _ptr(q_pos), _ptr(slot_map), sel_idx.shape[0], _ptr(workspace),
             workspace.numel() * workspace.element_size(), _stream()))
 
     # -- cc_gather_rows ----------------------------------------------------------------------

@@ -138,7 +138,30 @@ int cc_select(cc_ctx* ctx, const void* q, int32_t n_tok, const void* k_pool, int
   else
     cc::launch_score_scalar(ctx, q, k_pool, n_blocks, block_tab, segs, n_segs, req_seg_off,
                             max_seg_tokens, mass, st);
-  cc::launch_topn(ctx, mass, block_tab, segs, n_segs, sel_idx, q_row, q_pos, slot_map, scores, keys, st);
+  cc::launch_topn(ctx, mass, block_tab, segs, n_segs, sel_idx, q_row, q_pos, slot_map, scores, keys, false, st);
+  return cc::check_launch(ctx, fn);
+}
+
+int cc_select_from_scores(cc_ctx* ctx, const float* scores, int32_t n_tok, const int32_t* block_tab,
+                          const cc_segment* segs, int32_t n_segs, int32_t* sel_idx, int32_t* q_row,
+                          int32_t* q_pos, int32_t* slot_map, int32_t n_q_tot, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  static const char* fn = "cc_select_from_scores";
+  if (ctx == nullptr) return CC_ERR_INVALID_ARG;
+  CC_REQUIRE(n_tok >= 0 && n_segs >= 0 && n_q_tot >= 0, "negative count");
+  CC_REQUIRE(n_segs <= 65535, "more than 65535 segments in one call");
+  if (n_segs == 0) return CC_OK;
+  CC_REQUIRE(scores && block_tab && segs && sel_idx, "null pointer");
+  CC_REQUIRE(workspace != nullptr && aligned16(workspace), "workspace missing or misaligned");
+  if (workspace_bytes < cc_select_workspace_bytes(ctx, n_tok, n_segs))
+    return fail(ctx, CC_ERR_WORKSPACE_TOO_SMALL,
+                "cc_select_from_scores: workspace smaller than cc_select_workspace_bytes()");
+  // same workspace layout as cc_select: only the key buffer (chunks too long for LDS) is used
+  uint32_t* keys = reinterpret_cast<uint32_t*>(
+      static_cast<char*>(workspace) +
+      cc::align_up(static_cast<size_t>(n_tok) * ctx->cfg.n_q_heads * sizeof(float), 256));
+  cc::launch_topn(ctx, scores, block_tab, segs, n_segs, sel_idx, q_row, q_pos, slot_map, nullptr, keys, true,
+                  static_cast<hipStream_t>(stream));
   return cc::check_launch(ctx, fn);
 }
 

@@ -56,10 +56,12 @@ void launch_score_mfma(const cc_ctx* ctx, const void* q, const void* k_pool, int
                        const int32_t* block_tab, const cc_segment* segs, int n_segs,
                        const int32_t* req_seg_off, int max_seg_tokens, float* mass,
                        void* plan_ws, int max_tiles, int n_tok, hipStream_t stream);
+// given = false: mass [n_tok][Hq], score = mean over heads (0 for a chunk at position 0);
+// given = true: mass [n_tok] are the scores themselves
 void launch_topn(const cc_ctx* ctx, const float* mass, const int32_t* block_tab,
                  const cc_segment* segs, int n_segs, int32_t* sel_idx, int32_t* q_row,
                  int32_t* q_pos, int32_t* slot_map, float* scores, uint32_t* key_buf,
-                 hipStream_t stream);
+                 bool given, hipStream_t stream);
 
 void launch_rope_scatter(const cc_ctx* ctx, const void* k_new, const void* v_new,
                          const int32_t* q_pos, const int32_t* slot_map, int n_q_tot, void* k_pool,

@@ -111,7 +111,7 @@ __device__ __forceinline__ int block_sum_i(int v, int* red) {  // sum over 256 t
 }
 
 __global__ __launch_bounds__(kTopnThreads) void topn_kernel(
-    const float* __restrict__ mass, int hq, const int32_t* __restrict__ block_tab,
+    const float* __restrict__ mass, int hq, bool given, const int32_t* __restrict__ block_tab,
     const cc_segment* __restrict__ segs, int32_t* __restrict__ sel_idx, int32_t* __restrict__ q_row,
     int32_t* __restrict__ q_pos, int32_t* __restrict__ slot_map, float* __restrict__ scores,
     uint32_t* __restrict__ key_buf) {
@@ -136,7 +136,9 @@ __global__ __launch_bounds__(kTopnThreads) void topn_kernel(
   const float inv_h = 1.f / static_cast<float>(hq);
   for (int i = tid; i < n; i += kTopnThreads) {
     float sc = 0.f;
-    if (sg.logical_start > 0) {
+    if (given) {                            // scores supplied by the caller, one per token
+      sc = mass[static_cast<size_t>(sg.tok_off) + i];
+    } else if (sg.logical_start > 0) {
       const float* mp = mass + (static_cast<size_t>(sg.tok_off) + i) * hq;
       for (int h = 0; h < hq; ++h) sc += mp[h];
       sc *= inv_h;
@@ -188,9 +190,9 @@ __global__ __launch_bounds__(kTopnThreads) void topn_kernel(
 void launch_topn(const cc_ctx* ctx, const float* mass, const int32_t* block_tab,
                  const cc_segment* segs, int n_segs, int32_t* sel_idx, int32_t* q_row,
                  int32_t* q_pos, int32_t* slot_map, float* scores, uint32_t* key_buf,
-                 hipStream_t stream) {
+                 bool given, hipStream_t stream) {
   hipLaunchKernelGGL(topn_kernel, dim3(n_segs), dim3(kTopnThreads), 0, stream, mass,
-                     ctx->cfg.n_q_heads, block_tab, segs, sel_idx, q_row, q_pos, slot_map, scores,
+                     ctx->cfg.n_q_heads, given, block_tab, segs, sel_idx, q_row, q_pos, slot_map, scores,
                      key_buf);
 }
 

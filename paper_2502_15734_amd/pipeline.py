@@ -90,6 +90,11 @@ class DeviceBatch:
                         self.n_requests, self.max_seg_tokens, self.sel_idx, self.q_row, self.q_pos,
                         self.slot_map, self.scores, self.ws_select)
 
+    def select_from_scores(self, scores=None):
+        """Selection from given per-token scores (default: the scores cc_select wrote)."""
+        self.ctx.select_from_scores(self.scores if scores is None else scores, self.req_tab, self.segments,
+                                    self.sel_idx, self.q_row, self.q_pos, self.slot_map, self.ws_select)
+
     def gather(self):
         """Compact the chosen tokens' rows (and project them when the workload has hidden states)."""
         if self.n_q_tot == 0:

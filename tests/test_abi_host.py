@@ -26,8 +26,8 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert {"cc_rope_shift", "cc_select", "cc_sparse_prefill", "cc_gather_rows", "cc_qkv_project",
-            "cc_create", "cc_destroy"} <= set(names)
+    assert {"cc_rope_shift", "cc_select", "cc_select_from_scores", "cc_sparse_prefill", "cc_gather_rows",
+            "cc_qkv_project", "cc_create", "cc_destroy"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in cc.h but not exported"
 
@@ -74,6 +74,11 @@ def test_calls_reject_bad_arguments_before_launch(lib):
                          None, None, need, None) == -1
     assert lib.cc_select(h, None, 100, good, 8, good, good, 3, good, 1, 64, good, None, None, None, 10,
                          None, good, need, None) == -1
+    # cc_select_from_scores: null scores, workspace too small, empty segment list
+    ws_sel = lib.cc_select_workspace_bytes(h, 100, 3)
+    assert lib.cc_select_from_scores(h, None, 100, good, good, 3, good, None, None, None, 10, good, ws_sel, None) == -1
+    assert lib.cc_select_from_scores(h, good, 100, good, good, 3, good, None, None, None, 10, good, 16, None) == -3
+    assert lib.cc_select_from_scores(h, good, 100, good, good, 0, good, None, None, None, 10, good, ws_sel, None) == 0
     # cc_gather_rows: row size not a multiple of 16
     assert lib.cc_gather_rows(h, good, 10, good, 4, 24, good, None) == -1
     # cc_qkv_project: hidden not a multiple of 64

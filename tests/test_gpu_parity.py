@@ -175,6 +175,37 @@ def test_long_single_request_crosses_the_descriptor_window(impl):
     check_workload(w, _impls()[impl])
 
 
+def test_select_from_given_scores_is_exact():
+    # cc_select_from_scores does no arithmetic: on the same fp32 scores its index sets must equal the
+    # oracle's top-N exactly, ties (forced here by quantising the scores) going to the lower index;
+    # a chunk at position 0 is ranked by its given scores like any other
+    from paper_2502_15734_amd.pipeline import DeviceBatch
+    reqs = [W.RequestSpec([0, 1, 2, 3], [0.3, 0.0, 1.0, 0.13], 21), W.RequestSpec([3, 0, 4], [0.5, 0.15, 0.35], 40)]
+    w = W.custom("given", "bf16", 8, 2, 128, 5.0e5, [100, 77, 1300, 64, 201], [0, 5, 0, 17, 3], reqs,
+                 1.0 / math.sqrt(128), seed=5)
+    rng = np.random.default_rng(11)
+    given = np.round(rng.random(w.n_tok).astype(np.float32) * 50.0) / 50.0          # many exact ties
+    given[rng.random(w.n_tok) < 0.05] = -1.5                                           # and negative scores
+    b = DeviceBatch(w, poison=True)
+    b.select_from_scores(torch.from_numpy(given).cuda()); torch.cuda.synchronize()
+    gsel = H.gpu_selection(w, b.sel_idx.cpu().numpy())
+    want = []
+    for r in range(w.n_requests):
+        per_req = []
+        for sg in H.chunk_segments(w, r):
+            t0, n, ns = int(sg[W.SEG_TOK]), int(sg[W.SEG_NTOK]), int(sg[W.SEG_NSEL])
+            per_req.append(O.top_n(given[t0:t0 + n].astype(np.float64), ns))
+        want.append(per_req)
+        assert len(gsel[r]) == len(per_req)
+        for got, exp in zip(gsel[r], per_req):
+            assert np.array_equal(got, exp)
+    si, qr, qp, sm = H.selection_arrays(w, want)
+    assert np.array_equal(b.sel_idx.cpu().numpy()[: w.n_q_tot], si)
+    assert np.array_equal(b.q_row.cpu().numpy()[: w.n_q_tot], qr)
+    assert np.array_equal(b.q_pos.cpu().numpy()[: w.n_q_tot], qp)
+    assert np.array_equal(b.slot_map.cpu().numpy()[: w.n_q_tot], sm)
+
+
 @pytest.mark.parametrize("cid,scale", [(3, 0.08), (4, 0.12)])
 def test_scaled_batch_configs(cid, scale):
     check_workload(W.config(cid, scale), _impls()["wide"])
