@@ -123,30 +123,50 @@ __global__ __launch_bounds__(256, 2) void score_v2_kernel(
   __shared__ uint4 q_bounce[256];     // one piece per lane: the way into the accumulation registers
   u32x4 qreg[kQB][8];
   // (called after the first tile loads are on their way, so that the trigonometry hides their latency)
+  // The four column blocks of a lane sit 32 positions apart, so only the first block's angles take
+  // the double-precision path; each further block turns them by the fixed angle 32 f (a single-
+  // precision product is exact enough for that small angle).  Columns past the chunk's end get a
+  // query row and a position that do not belong together; nothing of theirs is written.
   auto load_queries = [&]() __attribute__((always_inline)) {
+    const bf16_t* qp[kQB];
 #pragma unroll
-    for (int qb = 0; qb < kQB; ++qb) {
-      const int pos = sg_start + token(qb);
-      const bf16_t* qp = q + (static_cast<size_t>(sg_tok_off + token(qb)) * hq + h) * kD + 8 * hh;
+    for (int qb = 0; qb < kQB; ++qb)
+      qp[qb] = q + (static_cast<size_t>(sg_tok_off + token(qb)) * hq + h) * kD + 8 * hh;
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        bf16x8 xv = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + 16 * kk));
-        bf16x8 yv = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + 16 * kk + 64));
+    for (int kk = 0; kk < 4; ++kk) {
+      bf16x8 xv[kQB], yv[kQB];
+#pragma unroll
+      for (int qb = 0; qb < kQB; ++qb) {
+        xv[qb] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp[qb] + 16 * kk));
+        yv[qb] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp[qb] + 16 * kk + 64));
+      }
+      float cs[8], sn[8], ct[8], st[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const double f = inv_freq.f[16 * kk + 8 * hh + j];
+        rot_cos_sin_fast(sg_start + t0 + n, f, &cs[j], &sn[j]);
+        cs[j] *= c2; sn[j] *= c2;
+        const float turn = static_cast<float>(f) * (32.f * 0.15915494309189535f);    // revolutions
+        ct[j] = __builtin_amdgcn_cosf(turn);
+        st[j] = __builtin_amdgcn_sinf(turn);
+      }
+#pragma unroll
+      for (int qb = 0; qb < kQB; ++qb) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-          float c, s;
-          rot_cos_sin_fast(pos, inv_freq.f[16 * kk + 8 * hh + j], &c, &s);
-          c *= c2; s *= c2;
-          const float x = static_cast<float>(xv[j]), y = static_cast<float>(yv[j]);
-          xv[j] = static_cast<bf16_t>(x * c - y * s);
-          yv[j] = static_cast<bf16_t>(y * c + x * s);
+          const float x = static_cast<float>(xv[qb][j]), y = static_cast<float>(yv[qb][j]);
+          xv[qb][j] = static_cast<bf16_t>(x * cs[j] - y * sn[j]);
+          yv[qb][j] = static_cast<bf16_t>(y * cs[j] + x * sn[j]);
+          const float c = cs[j], s_ = sn[j];
+          cs[j] = c * ct[j] - s_ * st[j];
+          sn[j] = s_ * ct[j] + c * st[j];
         }
-        q_bounce[tid] = __builtin_bit_cast(uint4, xv);
+        q_bounce[tid] = __builtin_bit_cast(uint4, xv[qb]);
         qreg[qb][kk] = lds_to_acc(&q_bounce[tid]);
-        q_bounce[tid] = __builtin_bit_cast(uint4, yv);
+        q_bounce[tid] = __builtin_bit_cast(uint4, yv[qb]);
         qreg[qb][kk + 4] = lds_to_acc(&q_bounce[tid]);
-        __builtin_amdgcn_sched_barrier(0);
       }
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
