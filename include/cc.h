@@ -13,6 +13,8 @@
  *   cc_sparse_prefill  causal attention of the chosen tokens + question over the whole merged
  *                      paged KV, after writing their recomputed K, V into it
  *                      (Eq. (1), Sec. 3.4.3, Sec. 4 "Selective Token Recomputation")
+ *   cc_question_mass   attention the question pays to every chunk in that layer, inter(C_i, U)
+ *                      (Sec. 3.2.2); cc_focus_* turns it into the set of focused chunks (Algorithm 1)
  *
  * Conventions
  *   - Every tensor and every metadata array is DEVICE memory owned by the caller; the library
@@ -195,6 +197,51 @@ int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void*
                       const cc_segment* segs, int32_t n_segs,
                       const int32_t* req_seg_off, int32_t n_requests, int32_t n_ctx_tokens,
                       void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- (d) attention between the question and every chunk -----------------------------------
+ * inter(C_i, U) of this layer (Sec. 3.2.2, with the weights of Eq. (1)): for every segment s of
+ * the batch, of request r,
+ *   seg_mass[s] = sum over the question rows u of r of
+ *                 (1/Hq) sum over query heads h of  sum_{keys l of segment s, l <= q_pos[u]} a^h_{u,l}
+ * where a^h_{u,.} are the softmax weights of step 2 of cc_sparse_prefill (same q, same pools, i.e.
+ * the keys after the fix) and the question rows of r are the rows of its part of the compact list
+ * with q_pos >= logical_start of r's CC_SEG_QUESTION segment (none: all its masses are 0).  For
+ * the question segment itself this is the mass the question keeps on its own tokens, so the masses
+ * of a request's segments add up to its number of question rows.
+ * Call it after cc_sparse_prefill, on the same stream, with the same q, q_pos, cu_q, pools and
+ * segment arrays, and with the lse that call wrote (required here).  The masses come from a pass
+ * of their own over the question rows (the attention kernels run once per (segment, question
+ * rows) pair and keep only the log-sum-exp); nothing but seg_mass and the workspace is written.
+ *   max_question_rows: max question rows of one request (host scalar; a request with more has
+ *   only its first max_question_rows counted).  seg_mass [n_segs] float.
+ *   workspace: cc_question_mass_workspace_bytes(ctx, n_ctx_tokens, n_segs, max_question_rows). */
+size_t cc_question_mass_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_tokens, int32_t n_segs,
+                                        int32_t max_question_rows);
+int cc_question_mass(cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
+                     int32_t n_q_tot, int32_t max_question_rows,
+                     const void* k_pool, const void* v_pool, int32_t n_blocks, const int32_t* block_tab,
+                     const cc_segment* segs, int32_t n_segs,
+                     const int32_t* req_seg_off, int32_t n_requests, int32_t n_ctx_tokens,
+                     const float* lse, float* seg_mass, void* workspace, size_t workspace_bytes,
+                     void* stream);
+
+/* ---- focused chunks (host only; no GPU work, HOST pointers) --------------------------------
+ * Algorithm 1 for ONE request with k chunks, fed once per layer l = 1, 2, ... with that layer's
+ * inter_l(C_i, U), i < k (e.g. the request's chunk entries of cc_question_mass's seg_mass, copied
+ * to the host): adds them to the cumulative scores, sorts the scores in descending order, turns
+ * the k-1 gaps between neighbours into a distribution p, and keeps the top i* chunks, where i* in
+ * 1..k-2 is the index that maximises h_{i+1} - h_i of the cumulative entropy h_i = -sum_{j<=i}
+ * p_j log p_j (first maximum; 0 log 0 = 0; with fewer than 3 chunks, or all scores equal, every
+ * chunk is kept).  focused[i] = 1 if chunk i is kept this layer, else 0; *n_focused (may be NULL)
+ * their number.  Returns 1 once the kept set has been the same for the last `window` layers
+ * (the caller stops recomputing the other chunks from here on: this layer is L*), 0 otherwise,
+ * negative cc_status on error (null pointer, non-finite score). */
+typedef struct cc_focus cc_focus;
+int cc_focus_create(cc_focus** out, int32_t n_chunks, int32_t window);
+void cc_focus_destroy(cc_focus* f);
+int cc_focus_update(cc_focus* f, const float* inter, int32_t* focused, int32_t* n_focused);
+/* number of layers fed so far (-1 for NULL) */
+int32_t cc_focus_layer(const cc_focus* f);
 
 #ifdef __cplusplus
 }

@@ -34,6 +34,21 @@ a token's score is the mean over query heads; ties go to the lower index;
 padding slots of a partly filled block are never keys; grouped-query mapping
 kv_head = q_head // (Hq / Hkv).
 
+Two further steps follow the question-to-chunk attention of Sec. 3.2.2:
+
+  question mass   inter(C_i, U): attention weight from the question's tokens to
+          the tokens of chunk C_i, the a_kl of Eq. (1) summed as in Eq. (2), with the
+          question as the later "chunk".  Reading: mean over query heads (as for the
+          token scores), summed over the question's tokens.
+  focused chunks  Algorithm 1, in the indexing its lines 5-9 print: gaps
+          diff_i = sorted_i - sorted_{i+1} for i = 1..k-1, p_i = diff_i / sum(diff),
+          h_i = -sum_{j<=i} p_j log p_j, i* = argmax over i = 1..k-2 of h_{i+1} - h_i,
+          F = the top i* chunks.  (Line 7's lower limit j = 0 is taken to be a slip
+          for j = 1: p has no element 0.)  0 log 0 = 0; first maximum among equals;
+          chunks with equal cumulative score keep prompt order; with k < 3 the range
+          of i is empty and with all gaps zero p is undefined -- every chunk is then
+          kept.  The stop rule compares the last w sets once l >= w.
+
 Parity pins (tests/test_oracle_pins.py): every function below is pinned by
 closed forms, invariants, limiting cases or brute force -- none is unpinned.
 The scoring *definition* (mean over heads, scores in the new context) is pinned
@@ -257,6 +272,83 @@ def run(w, selected_override: Optional[Dict[int, Sequence[np.ndarray]]] = None) 
     """Whole path over every request of the batch (requests are independent)."""
     return [run_request(w, r, None if selected_override is None else selected_override.get(r))
             for r in range(w.n_requests)]
+
+
+# --------------------------------------------------------------------------
+# question-to-chunk attention and the focused chunks (Sec. 3.2.2, Algorithm 1)
+# --------------------------------------------------------------------------
+def segment_mass_rows(q_rot: np.ndarray, pos: np.ndarray, k_ctx: np.ndarray, bounds: Sequence[int]) -> np.ndarray:
+    """Attention weight each given row puts on each segment.
+
+    q_rot [n, Hq, d] rotated queries at positions pos [n]; k_ctx [n_ctx, Hkv, d] logical order;
+    bounds [n_seg + 1] logical start of every segment and the end of the last one.
+    Returns [n, Hq, n_seg]: sum over keys l of segment s, l <= pos, of the softmax weight a_l
+    (softmax over all keys l <= pos, scaled by 1/sqrt(d): Eq. (1) per token).
+    """
+    n, hq, d = q_rot.shape
+    g = hq // k_ctx.shape[1]
+    n_seg = len(bounds) - 1
+    mass = np.zeros((n, hq, n_seg), dtype=np.float64)
+    for j in range(n):
+        p = int(pos[j])
+        for h in range(hq):
+            s = k_ctx[: p + 1, h // g, :] @ q_rot[j, h, :] / np.sqrt(np.float64(d))
+            a = np.exp(s - s.max())
+            a /= a.sum()
+            for i in range(n_seg):
+                lo, hi = int(bounds[i]), min(int(bounds[i + 1]), p + 1)
+                if hi > lo:
+                    mass[j, h, i] = a[lo:hi].sum()
+    return mass
+
+
+def question_chunk_mass(w, r: int, k_ctx: np.ndarray, q=None) -> np.ndarray:
+    """inter(C_i, U) for every segment of request r (the question segment's entry is the weight
+    the question keeps on itself): sum over question tokens of the mean over heads of the weight
+    on the segment's keys.  k_ctx is the request's K after the fix."""
+    theta = w.spec.rope_theta
+    q = w.q if q is None else q
+    segs = _segments_of(w, r)
+    bounds = [sg[2] for sg in segs] + [segs[-1][2] + segs[-1][3]]
+    total = np.zeros(len(segs), dtype=np.float64)
+    for (_, kind, start, n, _, _, tok, _) in segs:
+        if kind == 0:
+            continue
+        pos = start + np.arange(n, dtype=np.int64)
+        q_rot = rotate(np.asarray(q[tok:tok + n], dtype=np.float64), pos, theta)
+        total += segment_mass_rows(q_rot, pos, k_ctx, bounds).mean(axis=1).sum(axis=0)
+    return total
+
+
+def predict_focused(inter_layers: Sequence[Sequence[float]], window: int):
+    """Algorithm 1.  inter_layers[l][i] = inter_{l+1}(C_i, U) for chunks i < k.
+
+    Returns (F_star, L_star, F_all): the focused set (sorted chunk indices) and the 1-based layer
+    at which it was fixed (None, None if the stop rule never fires), and the set chosen at every
+    layer processed.
+    """
+    k = len(inter_layers[0])
+    cinter = np.zeros(k, dtype=np.float64)
+    f_all = []
+    for l, inter in enumerate(inter_layers, start=1):
+        cinter += np.asarray(inter, dtype=np.float64)
+        order = sorted(range(k), key=lambda i: (-cinter[i], i))
+        sorted_cinter = cinter[order]
+        chosen = list(order)
+        if k >= 3:
+            diff = sorted_cinter[:-1] - sorted_cinter[1:]              # diff_1 .. diff_{k-1}
+            if diff.sum() > 0:
+                p = diff / diff.sum()
+                plogp = np.where(p > 0, p * np.log(np.where(p > 0, p, 1.0)), 0.0)
+                h = -np.cumsum(plogp)                                  # h_1 .. h_{k-1}
+                jumps = h[1:] - h[:-1]                                 # h_{i+1} - h_i, i = 1 .. k-2
+                i_star = int(np.argmax(jumps)) + 1                     # 1-based
+                chosen = order[:i_star]
+        f = sorted(chosen)
+        f_all.append(f)
+        if l >= window and all(prev == f for prev in f_all[l - window:l]):
+            return f, l, f_all
+    return None, None, f_all
 
 
 def qkv_project(hidden_rows: np.ndarray, w_qkv: np.ndarray, hq: int, hkv: int, d: int):

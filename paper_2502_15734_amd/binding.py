@@ -71,6 +71,19 @@ def load_library() -> C.CDLL:
     lib.cc_sparse_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, vp, i32,
                                       vp, i32, i32, vp, vp, vp, sz, vp]
     lib.cc_sparse_prefill.restype = C.c_int
+    lib.cc_question_mass_workspace_bytes.argtypes = [vp, i32, i32, i32]
+    lib.cc_question_mass_workspace_bytes.restype = sz
+    lib.cc_question_mass.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, vp, i32, vp, i32, i32,
+                                     vp, vp, vp, sz, vp]
+    lib.cc_question_mass.restype = C.c_int
+    lib.cc_focus_create.argtypes = [C.POINTER(vp), i32, i32]
+    lib.cc_focus_create.restype = C.c_int
+    lib.cc_focus_destroy.argtypes = [vp]
+    lib.cc_focus_destroy.restype = None
+    lib.cc_focus_update.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(i32), C.POINTER(i32)]
+    lib.cc_focus_update.restype = C.c_int
+    lib.cc_focus_layer.argtypes = [vp]
+    lib.cc_focus_layer.restype = i32
     _LIB = lib
     return lib
 
@@ -166,3 +179,52 @@ class Context:
             q.shape[0], max_q_per_req, _ptr(k_pool), _ptr(v_pool), k_pool.shape[0], _ptr(block_tab),
             _ptr(segs), segs.shape[0], _ptr(req_seg_off), n_requests, n_ctx_tokens, _ptr(out), _ptr(lse),
             _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+    # -- cc_question_mass ----------------------------------------------------------------------
+    def question_mass_workspace_bytes(self, n_ctx_tokens: int, n_segs: int, max_question_rows: int) -> int:
+        return int(self._lib.cc_question_mass_workspace_bytes(self._h, n_ctx_tokens, n_segs, max_question_rows))
+
+    def question_mass(self, q, q_pos, cu_q, max_question_rows, k_pool, v_pool, block_tab, segs, req_seg_off,
+                      n_requests, n_ctx_tokens, lse, seg_mass, workspace):
+        self._check(self._lib.cc_question_mass(
+            self._h, _ptr(q), _ptr(q_pos), _ptr(cu_q), q.shape[0], max_question_rows, _ptr(k_pool), _ptr(v_pool),
+            k_pool.shape[0], _ptr(block_tab), _ptr(segs), segs.shape[0], _ptr(req_seg_off), n_requests,
+            n_ctx_tokens, _ptr(lse), _ptr(seg_mass), _ptr(workspace),
+            workspace.numel() * workspace.element_size(), _stream()))
+
+
+class FocusTracker:
+    """Algorithm 1 for one request (host only): feed one layer's inter(C_i, U) per call."""
+
+    def __init__(self, n_chunks: int, window: int):
+        self._lib = load_library()
+        h = C.c_void_p()
+        st = self._lib.cc_focus_create(C.byref(h), n_chunks, window)
+        if st != 0:
+            raise CacheCraftError(st, "cc_focus_create")
+        self._h, self.n_chunks = h, n_chunks
+
+    def update(self, inter):
+        """Returns (stop, focused chunk indices of this layer)."""
+        arr = (C.c_float * self.n_chunks)(*[float(v) for v in inter])
+        flags = (C.c_int32 * self.n_chunks)()
+        n = C.c_int32(0)
+        st = self._lib.cc_focus_update(self._h, arr, flags, C.byref(n))
+        if st < 0:
+            raise CacheCraftError(st, "cc_focus_update")
+        return bool(st), [i for i in range(self.n_chunks) if flags[i]]
+
+    @property
+    def layer(self) -> int:
+        return int(self._lib.cc_focus_layer(self._h))
+
+    def close(self):
+        if self._h:
+            self._lib.cc_focus_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -228,10 +228,50 @@ int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void*
   if (ctx->impl != CC_IMPL_SCALAR && cc::attn_mfma_supported(ctx))
     cc::launch_attn_mfma(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks,
                          block_tab, segs, n_segs, req_seg_off, n_requests, out, lse, workspace,
-                         max_tiles_for(n_ctx_tokens, n_segs), st);
+                         max_tiles_for(n_ctx_tokens, n_segs), nullptr, st);
   else
     cc::launch_attn_scalar(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks,
-                           block_tab, segs, req_seg_off, n_requests, out, lse, st);
+                           block_tab, segs, req_seg_off, n_requests, out, lse, nullptr, st);
+  return cc::check_launch(ctx, fn);
+}
+
+size_t cc_question_mass_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_tokens, int32_t n_segs,
+                                        int32_t max_question_rows) {
+  if (ctx == nullptr || n_ctx_tokens < 0 || n_segs < 0 || max_question_rows < 0) return 0;
+  return cc::question_mass_bytes(ctx, n_segs, max_tiles_for(n_ctx_tokens, n_segs), max_question_rows) + 256;
+}
+
+int cc_question_mass(cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
+                     int32_t n_q_tot, int32_t max_question_rows, const void* k_pool, const void* v_pool,
+                     int32_t n_blocks, const int32_t* block_tab, const cc_segment* segs, int32_t n_segs,
+                     const int32_t* req_seg_off, int32_t n_requests, int32_t n_ctx_tokens,
+                     const float* lse, float* seg_mass, void* workspace, size_t workspace_bytes,
+                     void* stream) {
+  static const char* fn = "cc_question_mass";
+  if (ctx == nullptr) return CC_ERR_INVALID_ARG;
+  CC_REQUIRE(n_q_tot >= 0 && max_question_rows >= 0 && n_segs >= 0 && n_requests >= 0 && n_ctx_tokens >= 0,
+             "negative count");
+  CC_REQUIRE(max_question_rows <= n_q_tot, "max_question_rows exceeds n_q_tot");
+  if (n_segs == 0) return CC_OK;
+  CC_REQUIRE(seg_mass != nullptr, "null pointer");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (n_q_tot == 0 || max_question_rows == 0) {          // no question rows: every mass is zero
+    cc::launch_fill_zero(seg_mass, n_segs, st);
+    return cc::check_launch(ctx, fn);
+  }
+  CC_REQUIRE(q && q_pos && cu_q && k_pool && v_pool && block_tab && segs && req_seg_off && lse, "null pointer");
+  CC_REQUIRE(n_blocks > 0 && n_requests > 0, "sizes must be positive");
+  CC_REQUIRE(n_segs <= 65535, "more than 65535 segments in one call");
+  CC_REQUIRE(n_requests <= n_segs, "every request needs at least one segment");
+  CC_REQUIRE(static_cast<int64_t>(n_segs) * max_question_rows <= 0x3fffffff, "n_segs * max_question_rows too large");
+  CC_REQUIRE(aligned16(q) && aligned16(k_pool) && aligned16(v_pool), "tensors must be 16-byte aligned");
+  CC_REQUIRE(workspace != nullptr && aligned16(workspace), "workspace missing or misaligned");
+  if (workspace_bytes < cc_question_mass_workspace_bytes(ctx, n_ctx_tokens, n_segs, max_question_rows))
+    return fail(ctx, CC_ERR_WORKSPACE_TOO_SMALL,
+                "cc_question_mass: workspace smaller than cc_question_mass_workspace_bytes()");
+  cc::launch_question_mass(ctx, q, q_pos, cu_q, max_question_rows, k_pool, v_pool, n_blocks, block_tab, segs,
+                           n_segs, req_seg_off, n_requests, lse, seg_mass, workspace,
+                           max_tiles_for(n_ctx_tokens, n_segs), st);
   return cc::check_launch(ctx, fn);
 }
 

@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
     const TileDesc* __restrict__ tiles, const int32_t* __restrict__ seg_tile_off, int max_tiles,
     const int32_t* __restrict__ order, const int32_t* __restrict__ req_seg_off, int hq, int hkv,
     int n_sub, int n_tiles_x, InvFreq inv_freq, bf16_t* __restrict__ out, float* __restrict__ lse,
-    int32_t* __restrict__ redo) {
+    int32_t* __restrict__ redo, const int32_t* __restrict__ q_map) {
   constexpr int TQ = 32 * QB;
   __shared__ uint4 lds_all[kBufs * kImage];
   const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
@@ -133,13 +133,16 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
   const int r = order[blockIdx.y];                           // longest contexts are dispatched first
   const int q0 = cu_q[r] + tile * TQ, q_end = cu_q[r + 1];
   if (q0 >= q_end) return;
-  int row[QB], p[QB];
+  // (with a row map, list row j takes its query and position from row q_map[j] of q and q_pos;
+  // results are always indexed by the list row)
+  int row[QB], src_row[QB], p[QB];
   bool row_valid[QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     row[qb] = min(q0 + 32 * qb + n, q_end - 1);
     row_valid[qb] = q0 + 32 * qb + n < q_end;
-    p[qb] = q_pos[row[qb]];
+    src_row[qb] = q_map != nullptr ? q_map[row[qb]] : row[qb];
+    p[qb] = q_pos[src_row[qb]];
   }
   int pmx = p[0], pmn = p[0];
 #pragma unroll
@@ -167,7 +170,7 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
   auto load_queries = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-      const bf16_t* qp = q + (static_cast<size_t>(row[qb]) * hq + h) * kD + 8 * hh;
+      const bf16_t* qp = q + (static_cast<size_t>(src_row[qb]) * hq + h) * kD + 8 * hh;
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
         bf16x8 xv = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + 16 * kk));
@@ -485,17 +488,19 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
   for (int qb = 0; qb < QB; ++qb) {
     const float inv = 1.f / l_tot[qb];
     if (row_valid[qb]) {
-      bf16_t* op = out + (static_cast<size_t>(row[qb]) * hq + h) * kD;
+      if (out != nullptr) {                  // (a caller that only wants the log-sum-exp passes none)
+        bf16_t* op = out + (static_cast<size_t>(row[qb]) * hq + h) * kD;
 #pragma unroll
-      for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-          bf16_t v4[4];
+          for (int g4 = 0; g4 < 4; ++g4) {
+            bf16_t v4[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v4[e] = static_cast<bf16_t>(o[qb][db][4 * g4 + e] * inv);
-          // accumulator register i holds output dim 32db + 8(i/4) + 4hh + i%4
-          *reinterpret_cast<uint2*>(op + 32 * db + 8 * g4 + 4 * hh) = *reinterpret_cast<uint2*>(v4);
-        }
+            for (int e = 0; e < 4; ++e) v4[e] = static_cast<bf16_t>(o[qb][db][4 * g4 + e] * inv);
+            // accumulator register i holds output dim 32db + 8(i/4) + 4hh + i%4
+            *reinterpret_cast<uint2*>(op + 32 * db + 8 * g4 + 4 * hh) = *reinterpret_cast<uint2*>(v4);
+          }
+      }
       if (lse != nullptr && hh == 0)
         lse[static_cast<size_t>(row[qb]) * hq + h] = kLn2 * (m_ref[qb] + __builtin_amdgcn_logf(l_tot[qb]));
     }
@@ -512,7 +517,7 @@ bool attn_v2_supported(const cc_ctx* ctx) {
 void launch_attn_v2(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
                     int max_q_per_req, const void* k_pool, const void* v_pool, int n_blocks,
                     const Plan& pl, const int32_t* req_seg_off, int n_requests, void* out, float* lse,
-                    int32_t* redo, hipStream_t stream) {
+                    int32_t* redo, const int32_t* q_map, hipStream_t stream) {
   constexpr int QB = 2;
   const int hkv = ctx->cfg.n_kv_heads, n_sub = ctx->cfg.n_q_heads / hkv / 4;
   const int n_tiles = (max_q_per_req + 32 * QB - 1) / (32 * QB);
@@ -520,7 +525,7 @@ void launch_attn_v2(const cc_ctx* ctx, const void* q, const int32_t* q_pos, cons
   hipLaunchKernelGGL((attn_v2_kernel<QB>), grid, dim3(256), 0, stream, static_cast<const bf16_t*>(q), q_pos,
                      cu_q, static_cast<const bf16_t*>(k_pool), static_cast<const bf16_t*>(v_pool), n_blocks,
                      pl.tiles, pl.seg_tile_off, pl.max_tiles, pl.order, req_seg_off, ctx->cfg.n_q_heads, hkv,
-                     n_sub, n_tiles, ctx->inv_freq, static_cast<bf16_t*>(out), lse, redo);
+                     n_sub, n_tiles, ctx->inv_freq, static_cast<bf16_t*>(out), lse, redo, q_map);
 }
 
 }  // namespace cc

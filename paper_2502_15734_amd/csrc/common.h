@@ -70,13 +70,22 @@ void launch_attn_scalar(const cc_ctx* ctx, const void* q, const int32_t* q_pos, 
                         int n_q_tot, int max_q_per_req, const void* k_pool, const void* v_pool,
                         int n_blocks, const int32_t* block_tab, const cc_segment* segs,
                         const int32_t* req_seg_off, int n_requests, void* out, float* lse,
-                        hipStream_t stream);
+                        const int32_t* q_map, hipStream_t stream);
 bool attn_mfma_supported(const cc_ctx* ctx);
 void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
                       int n_q_tot, int max_q_per_req, const void* k_pool, const void* v_pool,
                       int n_blocks, const int32_t* block_tab, const cc_segment* segs, int n_segs,
                       const int32_t* req_seg_off, int n_requests, void* out, float* lse,
-                      void* plan_ws, int max_tiles, hipStream_t stream);
+                      void* plan_ws, int max_tiles, const int32_t* q_map, hipStream_t stream);
+
+// attention mass of the question rows on every segment (focus.hip)
+void launch_fill_zero(float* p, int n, hipStream_t stream);
+size_t question_mass_bytes(const cc_ctx* ctx, int n_segs, int max_tiles, int max_question_rows);
+void launch_question_mass(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
+                          int max_question_rows, const void* k_pool, const void* v_pool, int n_blocks,
+                          const int32_t* block_tab, const cc_segment* segs, int n_segs,
+                          const int32_t* req_seg_off, int n_requests, const float* lse, float* seg_mass,
+                          void* workspace, int max_tiles, hipStream_t stream);
 
 // attention for head groups that are a multiple of 4: 64 query rows per wavefront (attn_mfma2.hip)
 bool attn_v2_supported(const cc_ctx* ctx);

@@ -78,7 +78,7 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
     const TileDesc* __restrict__ tiles, const int32_t* __restrict__ seg_tile_off, int max_tiles,
     const int32_t* __restrict__ order, const cc_segment* __restrict__ segs, const int32_t* __restrict__ req_seg_off, int hq, int hkv,
     int n_tiles_x, InvFreq inv_freq, bf16_t* __restrict__ out, float* __restrict__ lse,
-    float* __restrict__ mass, const int32_t* __restrict__ redo) {
+    float* __restrict__ mass, const int32_t* __restrict__ redo, const int32_t* __restrict__ q_map) {
   constexpr int NT = 64 * G;
   constexpr int TQ = 32 * QB;                       // query tokens per workgroup
   constexpr bool kPrefetch = NT >= 256;
@@ -97,7 +97,9 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
   const int h = kvh * G + wave;
 
   // ---- which queries ------------------------------------------------------------------------
-  int row[QB], p[QB], s_begin, s_end, s_self = -1;
+  // (attention with a row map: list row j takes its query and position from row q_map[j] of q
+  // and q_pos; results are always indexed by the list row)
+  int row[QB], src_row[QB], p[QB], s_begin, s_end, s_self = -1;
   bool row_valid[QB];
   if constexpr (SCORE) {
     const int seg_id = order[blockIdx.y];              // heaviest segments are dispatched first
@@ -111,6 +113,7 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
       const int t = min(t0 + 32 * qb + n, sg.n_tokens - 1);
       row_valid[qb] = t0 + 32 * qb + n < sg.n_tokens;
       row[qb] = sg.tok_off + t;
+      src_row[qb] = row[qb];
       p[qb] = sg.logical_start + t;
     }
     s_begin = req_seg_off[sg.req];
@@ -126,7 +129,8 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
     for (int qb = 0; qb < QB; ++qb) {
       row[qb] = min(q0 + 32 * qb + n, q_end - 1);
       row_valid[qb] = q0 + 32 * qb + n < q_end;
-      p[qb] = q_pos[row[qb]];
+      src_row[qb] = q_map != nullptr ? q_map[row[qb]] : row[qb];
+      p[qb] = q_pos[src_row[qb]];
     }
     s_begin = req_seg_off[r];
     s_end = req_seg_off[r + 1];
@@ -142,7 +146,7 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
   bf16x8 qreg[QB][8];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
-    const bf16_t* qp = q + (static_cast<size_t>(row[qb]) * hq + h) * kD + 8 * hh;
+    const bf16_t* qp = q + (static_cast<size_t>(src_row[qb]) * hq + h) * kD + 8 * hh;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       bf16x8 xv = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + 16 * kk));
@@ -465,17 +469,19 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
     } else {
       const float inv = 1.f / l_tot;
       if (row_valid[qb]) {
-        bf16_t* op = out + (static_cast<size_t>(row[qb]) * hq + h) * kD;
+        if (out != nullptr) {                // (a caller that only wants the log-sum-exp passes none)
+          bf16_t* op = out + (static_cast<size_t>(row[qb]) * hq + h) * kD;
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+          for (int db = 0; db < 4; ++db)
 #pragma unroll
-          for (int g4 = 0; g4 < 4; ++g4) {
-            bf16_t v4[4];
+            for (int g4 = 0; g4 < 4; ++g4) {
+              bf16_t v4[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v4[e] = static_cast<bf16_t>(o[qb][db][4 * g4 + e] * inv);
-            // accumulator register i holds output dim 32db + 8(i/4) + 4hh + i%4
-            *reinterpret_cast<uint2*>(op + 32 * db + 8 * g4 + 4 * hh) = *reinterpret_cast<uint2*>(v4);
-          }
+              for (int e = 0; e < 4; ++e) v4[e] = static_cast<bf16_t>(o[qb][db][4 * g4 + e] * inv);
+              // accumulator register i holds output dim 32db + 8(i/4) + 4hh + i%4
+              *reinterpret_cast<uint2*>(op + 32 * db + 8 * g4 + 4 * hh) = *reinterpret_cast<uint2*>(v4);
+            }
+        }
         if (lse != nullptr && hh == 0)
           lse[static_cast<size_t>(row[qb]) * hq + h] = kLn2 * (m_ref[qb] + __builtin_amdgcn_logf(l_tot));
       }
@@ -609,14 +615,15 @@ template <int G>
 void launch_attn_g(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
                    int max_q_per_req, const void* k_pool, const void* v_pool, int n_blocks,
                    const Plan& pl, const cc_segment* segs, const int32_t* req_seg_off,
-                   int n_requests, void* out, float* lse, const int32_t* redo, hipStream_t stream) {
+                   int n_requests, void* out, float* lse, const int32_t* redo, const int32_t* q_map,
+                   hipStream_t stream) {
   const int hkv = ctx->cfg.n_kv_heads, n_tiles = (max_q_per_req + 32 * kAttnQB - 1) / (32 * kAttnQB);
   dim3 grid(hkv * n_tiles, n_requests);
   hipLaunchKernelGGL((sparse_qk_kernel<G, false, kAttnQB>), grid, dim3(64 * G), 0, stream,
                      static_cast<const bf16_t*>(q), q_pos, cu_q, static_cast<const bf16_t*>(k_pool),
                      static_cast<const bf16_t*>(v_pool), n_blocks, pl.tiles, pl.seg_tile_off, pl.max_tiles,
                      pl.order, segs, req_seg_off, ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq,
-                     static_cast<bf16_t*>(out), lse, static_cast<float*>(nullptr), redo);
+                     static_cast<bf16_t*>(out), lse, static_cast<float*>(nullptr), redo, q_map);
 }
 
 template <int G>
@@ -630,7 +637,8 @@ void launch_score_g(const cc_ctx* ctx, const void* q, const void* k_pool, int n_
                      static_cast<const int32_t*>(nullptr), static_cast<const bf16_t*>(k_pool),
                      static_cast<const bf16_t*>(nullptr), n_blocks, pl.tiles, pl.seg_tile_off, pl.max_tiles,
                      pl.order, segs, req_seg_off, ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq,
-                     static_cast<bf16_t*>(nullptr), static_cast<float*>(nullptr), mass, redo);
+                     static_cast<bf16_t*>(nullptr), static_cast<float*>(nullptr), mass, redo,
+                     static_cast<const int32_t*>(nullptr));
 }
 
 bool group_supported(const cc_ctx* ctx) {
@@ -689,7 +697,7 @@ void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, co
                       int n_q_tot, int max_q_per_req, const void* k_pool, const void* v_pool,
                       int n_blocks, const int32_t* block_tab, const cc_segment* segs, int n_segs,
                       const int32_t* req_seg_off, int n_requests, void* out, float* lse,
-                      void* plan_ws, int max_tiles, hipStream_t stream) {
+                      void* plan_ws, int max_tiles, const int32_t* q_map, hipStream_t stream) {
   // Wide kernel first where the head group allows it; the narrow kernel then redoes the 64-row
   // tiles the wide one flagged (normally none: its workgroups read one flag and exit).
   // (a grid too small to give every compute unit a wide workgroup runs faster on the narrow
@@ -701,9 +709,9 @@ void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, co
   const Plan pl = run_plan(plan_ws, segs, n_segs, req_seg_off, n_requests, block_tab, n_blocks, max_tiles, n_redo, stream);
   if (wide)
     launch_attn_v2(ctx, q, q_pos, cu_q, max_q_per_req, k_pool, v_pool, n_blocks, pl, req_seg_off, n_requests,
-                   out, lse, pl.redo, stream);
+                   out, lse, pl.redo, q_map, stream);
   const int32_t* redo = pl.redo;
-#define CC_ARGS ctx, q, q_pos, cu_q, max_q_per_req, k_pool, v_pool, n_blocks, pl, segs, req_seg_off, n_requests, out, lse, redo, stream
+#define CC_ARGS ctx, q, q_pos, cu_q, max_q_per_req, k_pool, v_pool, n_blocks, pl, segs, req_seg_off, n_requests, out, lse, redo, q_map, stream
   switch (ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads) {
     case 1: launch_attn_g<1>(CC_ARGS); break;
     case 2: launch_attn_g<2>(CC_ARGS); break;

@@ -134,16 +134,19 @@ __global__ __launch_bounds__(64) void attn_scalar_kernel(
     int n_requests, const T* __restrict__ k_pool, const T* __restrict__ v_pool, int n_blocks,
     const int32_t* __restrict__ block_tab, const cc_segment* __restrict__ segs,
     const int32_t* __restrict__ req_seg_off, int hq, int hkv, InvFreq inv_freq,
-    T* __restrict__ out, float* __restrict__ lse) {
+    T* __restrict__ out, float* __restrict__ lse, const int32_t* __restrict__ q_map) {
   const int j = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
   int r = 0;
   while (r + 1 < n_requests && cu_q[r + 1] <= j) ++r;
-  const int p = q_pos[j];
+  if (j >= cu_q[n_requests]) return;                 // (the list may be shorter than its capacity)
+  // with a row map, list row j takes its query and position from row q_map[j] of q and q_pos
+  const int src = q_map != nullptr ? q_map[j] : j;
+  const int p = q_pos[src];
   const int kvh = h / (hq / hkv);
   const bool own = lane < D / 2;
   float qx = 0.f, qy = 0.f;
   if (own) {
-    const T* qp = q + (static_cast<size_t>(j) * hq + h) * D;
+    const T* qp = q + (static_cast<size_t>(src) * hq + h) * D;
     float x = to_float(qp[lane]), y = to_float(qp[lane + D / 2]), c, s;
     rot_cos_sin(p, inv_freq.f[lane], &c, &s);
     qx = x * c - y * s;
@@ -175,7 +178,7 @@ __global__ __launch_bounds__(64) void attn_scalar_kernel(
       }
     }
   }
-  if (own) {
+  if (own && out != nullptr) {
     T* op = out + (static_cast<size_t>(j) * hq + h) * D;
     op[lane] = from_float<T>(ox / z);
     op[lane + D / 2] = from_float<T>(oy / z);
@@ -187,7 +190,7 @@ void launch_attn_scalar(const cc_ctx* ctx, const void* q, const int32_t* q_pos, 
                         int n_q_tot, int max_q_per_req, const void* k_pool, const void* v_pool,
                         int n_blocks, const int32_t* block_tab, const cc_segment* segs,
                         const int32_t* req_seg_off, int n_requests, void* out, float* lse,
-                        hipStream_t stream) {
+                        const int32_t* q_map, hipStream_t stream) {
   (void)max_q_per_req;
   if (n_q_tot <= 0) return;
   const bool bf = ctx->cfg.dtype == CC_BF16;
@@ -196,7 +199,7 @@ void launch_attn_scalar(const cc_ctx* ctx, const void* q, const int32_t* q_pos, 
   hipLaunchKernelGGL((attn_scalar_kernel<T, D>), dim3(n_q_tot, hq), dim3(64), 0, stream,        \
                      static_cast<const T*>(q), q_pos, cu_q, n_requests,                         \
                      static_cast<const T*>(k_pool), static_cast<const T*>(v_pool), n_blocks,    \
-                     block_tab, segs, req_seg_off, hq, hkv, ctx->inv_freq, static_cast<T*>(out), lse)
+                     block_tab, segs, req_seg_off, hq, hkv, ctx->inv_freq, static_cast<T*>(out), lse, q_map)
   if (bf && d == 128) CC_LAUNCH(bf16_t, 128);
   else if (bf && d == 64) CC_LAUNCH(bf16_t, 64);
   else if (!bf && d == 128) CC_LAUNCH(float, 128);

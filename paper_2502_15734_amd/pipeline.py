@@ -115,6 +115,20 @@ class DeviceBatch:
                                 self.segments, self.req_seg_off, self.n_requests, self.n_tok, self.out, self.lse,
                                 self.ws_prefill)
 
+    def question_mass(self):
+        """inter(C_i, U) per segment, from the last sparse_prefill's lse (float32 [n_segs])."""
+        n_segs = int(self.segments.shape[0])
+        if not hasattr(self, "seg_mass"):
+            seg = self.w.segments
+            self.max_question_rows = int(seg[seg[:, 1] == 1, 3].max()) if (seg[:, 1] == 1).any() else 0
+            self.seg_mass = torch.zeros(max(1, n_segs), dtype=torch.float32, device=self.device)
+            nbytes = self.ctx.question_mass_workspace_bytes(self.n_tok, n_segs, self.max_question_rows)
+            self.ws_mass = torch.empty(max(256, nbytes), dtype=torch.uint8, device=self.device)
+        self.ctx.question_mass(self.q_c, self.q_pos, self.cu_q, self.max_question_rows, self.k_req, self.v_req,
+                               self.req_tab, self.segments, self.req_seg_off, self.n_requests, self.n_tok,
+                               self.lse, self.seg_mass, self.ws_mass)
+        return self.seg_mass
+
     def step(self):
         """One pass of the whole hot path over the batch."""
         self.rope_shift()

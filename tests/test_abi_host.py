@@ -27,7 +27,8 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"cc_rope_shift", "cc_select", "cc_select_from_scores", "cc_sparse_prefill", "cc_gather_rows",
-            "cc_qkv_project", "cc_create", "cc_destroy"} <= set(names)
+            "cc_qkv_project", "cc_create", "cc_destroy", "cc_question_mass", "cc_question_mass_workspace_bytes",
+            "cc_focus_create", "cc_focus_update", "cc_focus_destroy", "cc_focus_layer"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in cc.h but not exported"
 
@@ -91,12 +92,63 @@ def test_calls_reject_bad_arguments_before_launch(lib):
     assert lib.cc_sparse_prefill(*args, good, None, good, ws, None) == -1
     args[7], args[8] = 0, 0
     assert lib.cc_sparse_prefill(*args, good, None, good, ws, None) == 0
+    # cc_question_mass: missing lse, workspace too small, max_question_rows > n_q_tot, no segments
+    wm = lib.cc_question_mass_workspace_bytes(h, 100, 3, 8)
+    assert wm >= 3 * 8 * 8 * 4
+    qm = [h, good, good, good, 10, 8, good, good, 8, good, good, 3, good, 1, 100]
+    assert lib.cc_question_mass(*qm, None, good, good, wm, None) == -1
+    assert lib.cc_question_mass(*qm, good, good, good, wm - 1, None) == -3
+    assert lib.cc_question_mass(*qm, good, None, good, wm, None) == -1
+    qm[5] = 11
+    assert lib.cc_question_mass(*qm, good, good, good, wm, None) == -1
+    qm[5], qm[11] = 8, 0
+    assert lib.cc_question_mass(*qm, good, good, good, wm, None) == 0
     # null context
     assert lib.cc_rope_shift(None, good, None, 4, good, None, 4, good, good, good, 1, 16, None) == -1
     assert lib.cc_set_impl(h, 99) == -1
     for impl in (P.CC_IMPL_MFMA_NARROW, P.CC_IMPL_MFMA_WIDE, P.CC_IMPL_SCALAR, P.CC_IMPL_AUTO):
         assert lib.cc_set_impl(h, impl) == 0
     ctx.close()
+
+
+def test_focus_tracker_follows_algorithm_1():
+    """The library's host-side Algorithm 1 against the oracle's, layer by layer, on seeded score
+    sequences that drift and then settle (so both the changing sets and the stop rule are hit)."""
+    import numpy as np
+    import paper_2502_15734_amd as P
+    from oracle import cachecraft_oracle as O
+    rng = np.random.default_rng(2025)
+    stops = 0
+    for case in range(60):
+        k = int(rng.integers(1, 9))
+        window = int(rng.integers(1, 4))
+        n_layers = int(rng.integers(1, 12))
+        base = rng.random(k) * (rng.random(k) < 0.6)
+        layers = [np.float32(base * (1.0 if l >= 3 else 0.0) + rng.random(k) * (0.5 if l < 3 else 0.01))
+                  for l in range(n_layers)]
+        f_star, l_star, f_all = O.predict_focused([[float(v) for v in x] for x in layers], window)
+        tr = P.FocusTracker(k, window)
+        for l, x in enumerate(layers, start=1):
+            stop, focused = tr.update(x)
+            assert focused == f_all[l - 1], f"case {case} layer {l}"
+            assert tr.layer == l
+            if stop:
+                assert (focused, l) == (f_star, l_star)
+                stops += 1
+                break
+        else:
+            assert f_star is None
+        tr.close()
+    assert stops >= 10
+    # hand-worked layer (gaps 1, 7, 1, 0.5 -> the two top chunks) and argument checks
+    tr = P.FocusTracker(5, 1)
+    assert tr.update([2.0, 10.0, 0.5, 9.0, 1.0]) == (True, [1, 3])
+    with pytest.raises(P.CacheCraftError):
+        tr.update([float("nan")] * 5)
+    with pytest.raises(P.CacheCraftError):
+        P.FocusTracker(0, 1)
+    with pytest.raises(P.CacheCraftError):
+        P.FocusTracker(3, 0)
 
 
 def test_product_path_does_not_import_the_oracle():

@@ -82,6 +82,7 @@ def check_workload(w, impl, score_tol=5e-5):
     b.set_selection(*H.selection_arrays(w, [res[r].selected for r in range(w.n_requests)]))
     b.gather(); b.sparse_prefill()
     compare_prefill(b, res, "oracle selection")
+    check_question_mass(w, b, [res[r].k_ctx for r in range(w.n_requests)])
 
     # ---- end to end with the library's own selection -----------------------------------------
     b2 = DeviceBatch(w, impl=impl, poison=True)
@@ -93,6 +94,25 @@ def check_workload(w, impl, score_tol=5e-5):
     # the shared store is read-only for the whole path
     assert torch.equal(b2.k_store.float().cpu(), torch.from_numpy(w.k_store))
     assert torch.equal(b2.v_store.float().cpu(), torch.from_numpy(w.v_store))
+
+
+def check_question_mass(w, b, k_ctx_of, requests=None, exact=True):
+    """cc_question_mass after cc_sparse_prefill on batch b against the oracle's inter(C_i, U)."""
+    mass = b.question_mass().cpu().numpy()
+    torch.cuda.synchronize()
+    bf = w.spec.dtype == "bf16"
+    for r in (range(w.n_requests) if requests is None else requests):
+        s0, s1 = int(w.req_seg_off[r]), int(w.req_seg_off[r + 1])
+        m_r = sum(int(sg[W.SEG_NTOK]) for sg in H.all_segments(w, r) if sg[W.SEG_KIND] != W.KIND_CHUNK)
+        got = mass[s0:s1]
+        assert np.all(got >= 0.0) and np.all(np.isfinite(got))
+        # every question row's weights add up to one
+        assert abs(got.sum() - m_r) <= (3e-3 if bf else 2e-5) * max(1, m_r), f"request {r}: masses sum to {got.sum()} for {m_r} rows"
+        if exact:
+            want = O.question_chunk_mass(w, r, k_ctx_of[r])
+            err = np.abs(got - want)
+            bound = (1e-2 if bf else 1e-4) * want + (1e-4 if bf else 1e-6) * max(1, m_r)
+            assert np.all(err <= bound), f"request {r}: question mass {got} vs {want}"
 
 
 def _impls():
@@ -351,6 +371,9 @@ def test_full_size_configs_on_sampled_outputs(cid):
         lse_err = float(np.abs(lse[q0:q1][which] - l_ref).max())
         assert lse_err <= (2e-3 if w.hidden is None else 1e-2), f"config {cid} request {r}: lse error {lse_err:.3e}"
         assert H.rel_l2(k_gpu, k_ctx) <= 1e-2 and H.rel_l2(v_gpu, v_ctx) <= 1e-2
+        # -- attention of the question to every chunk (the projected workload's question is too
+        #    long for the oracle's row loops: there only the sums are checked)
+        check_question_mass(w, b, {r: k_ctx}, requests=[r], exact=w.hidden is None)
 
 
 class _SparseRows:

@@ -348,3 +348,116 @@ def test_qkv_projection_splits_heads_in_q_k_v_order():
     np.testing.assert_allclose(q[1, 2], y[1, 8:12].numpy(), atol=1e-13)
     np.testing.assert_allclose(k[2, 1], y[2, 16 + 4:16 + 8].numpy(), atol=1e-13)
     np.testing.assert_allclose(v[0, 0], y[0, 24:28].numpy(), atol=1e-13)
+
+
+# ----------------------------------------------------------------------------- question-to-chunk mass
+def _fixed_context(w, r=0):
+    res = O.run_request(w, r)
+    return res
+
+
+def test_question_mass_uniform_softmax_closed_form():
+    # all logits equal -> row at position p spreads 1/(p+1) on every visible key
+    w = small_workload(lens=(20, 33, 16), question=5)
+    w.q[:] = 0.0
+    res = _fixed_context(w)
+    got = O.question_chunk_mass(w, 0, res.k_ctx)
+    starts, lens = (0, 20, 53, 69), (20, 33, 16, 5)
+    want = np.zeros(4)
+    for u in range(5):
+        p = 69 + u
+        for i in range(3):
+            want[i] += lens[i] / (p + 1.0)
+        want[3] += (u + 1) / (p + 1.0)
+    np.testing.assert_allclose(got, want, rtol=1e-13)
+
+
+def test_question_mass_is_the_block_sum_of_the_attention_matrix():
+    # Eq. (2) with the question as the later chunk: sum of a_kl over question rows and chunk columns
+    w = small_workload(lens=(12, 10, 14), question=6)
+    res = _fixed_context(w)
+    n_ctx = 42
+    # every token's rotated query, in logical order (chunk rows are not needed but harmless)
+    q_log = np.zeros((n_ctx, 4, 16))
+    q_log[36:] = rope_complex(w.q[36:42].astype(np.float64), np.arange(36, 42), 1.0e4)
+    a = attention_matrix(q_log, res.k_ctx)                            # [Hq, 42, 42], library softmax
+    got = O.question_chunk_mass(w, 0, res.k_ctx)
+    bounds = [(0, 12), (12, 22), (22, 36), (36, 42)]
+    for i, (b0, b1) in enumerate(bounds):
+        np.testing.assert_allclose(got[i], a[:, 36:42, b0:b1].sum(axis=(1, 2)).mean(), atol=1e-12)
+    assert abs(got.sum() - 6.0) < 1e-12                               # every row's weights add up to one
+
+
+def test_question_mass_bruteforce_scalar_loops():
+    w = small_workload(lens=(5, 7), question=3, d=8, fracs=(0.4, 0.4), offsets=(0, 0), order=(1, 0))
+    res = _fixed_context(w)
+    segs = [tuple(int(v) for v in s) for s in w.segments]
+    starts = [s[2] for s in segs] + [segs[-1][2] + segs[-1][3]]
+    tok_q = segs[-1][6]
+    want = [0.0] * len(segs)
+    for u in range(3):
+        p = starts[-2] + u
+        for h in range(4):
+            qv = rope_complex(w.q[tok_q + u][None].astype(np.float64), [p], 1.0e4)[0, h]
+            logit = [sum(qv[e] * res.k_ctx[l, h // 2, e] for e in range(8)) / math.sqrt(8) for l in range(p + 1)]
+            mx = max(logit)
+            ex = [math.exp(v - mx) for v in logit]
+            z = sum(ex)
+            for i in range(len(segs)):
+                want[i] += sum(ex[starts[i]:min(starts[i + 1], p + 1)]) / z / 4.0
+    np.testing.assert_allclose(O.question_chunk_mass(w, 0, res.k_ctx), want, rtol=1e-12)
+
+
+def test_question_mass_follows_a_dominant_key():
+    w = small_workload(lens=(8, 8, 8), question=2)
+    res = _fixed_context(w)
+    k = res.k_ctx.copy()
+    pos = 24 + np.arange(2)
+    q_rot = O.rotate(w.q[24:26].astype(np.float64), pos, 1.0e4)
+    k[11] = 0.0                                                       # one key of chunk 1 aligned with heads 0 and 2 of row 0
+    k[11, 0, :] = 300.0 * np.sign(q_rot[0, 0, :])
+    k[11, 1, :] = 300.0 * np.sign(q_rot[0, 2, :])
+    m = O.segment_mass_rows(q_rot, pos, k, [0, 8, 16, 24, 26])
+    assert m[0, 0, 1] > 1.0 - 1e-9 and m[0, 2, 1] > 1.0 - 1e-9
+    np.testing.assert_allclose(m.sum(axis=2), 1.0, atol=1e-12)
+
+
+# ----------------------------------------------------------------------------- focused chunks (Algorithm 1)
+def test_focused_hand_worked_layer():
+    # sorted scores 10, 9, 2, 1, 0.5 -> gaps 1, 7, 1, 0.5 (sum 9.5), p = .1053 .7368 .1053 .0526,
+    # -p ln p = .2370 .2250 .2370 .1550; over i = 1..3 the jumps h_{i+1}-h_i are .2250 .2370 .1550:
+    # i* = 2, the two top chunks (worked by hand from the algorithm's lines 4-9)
+    inter = [2.0, 10.0, 0.5, 9.0, 1.0]
+    f, l, f_all = O.predict_focused([inter], window=1)
+    assert f == [1, 3] and l == 1 and f_all == [[1, 3]]
+    p = np.array([1, 7, 1, 0.5]) / 9.5
+    assert np.argmax((-p * np.log(p))[1:]) + 1 == 2
+
+
+def test_focused_scores_accumulate_and_stop_rule_needs_w_equal_sets():
+    a = [5.0, 1.0, 0.9, 0.8, 0.1]          # alone: sorted 5 1 .9 .8 .1 -> gaps 4 .1 .1 .7
+    b = [0.0, 6.0, 0.0, 0.0, 0.0]          # cumulative after a+b: 5 7 .9 .8 .1 -> sorted 7 5 .9 .8 .1 -> gaps 2 4.1 .1 .7
+    fa, la, _ = O.predict_focused([a], window=1)
+    # gaps 4 .1 .1 .7 (sum 4.9): -p ln p = .166 .079 .079 .278 -> jumps over i=1..3: .079 .079 .278 -> i* = 3
+    assert fa == [0, 1, 2] and la == 1
+    f, l, f_all = O.predict_focused([a, b, [0.0] * 5, [0.0] * 5], window=2)
+    # layer 2 cumulative gaps 2 4.1 .1 .7 (sum 6.9): -p ln p = .359 .309 .061 .232 -> jumps .309 .061 .232 -> i* = 1
+    assert f_all[0] == [0, 1, 2] and f_all[1] == [1]
+    assert f == [1] and l == 3 and len(f_all) == 3            # layers 2 and 3 agree -> stops at layer 3
+    f, l, f_all = O.predict_focused([a, b], window=2)
+    assert f is None and l is None and len(f_all) == 2         # never two equal sets in a row
+
+
+def test_focused_degenerate_cases_keep_every_chunk():
+    assert O.predict_focused([[1.0, 3.0]], window=1)[0] == [0, 1]                 # k < 3: no i in 1..k-2
+    assert O.predict_focused([[2.0, 2.0, 2.0, 2.0]], window=1)[0] == [0, 1, 2, 3]  # no gap at all
+    # k = 3: the only admissible i is 1
+    assert O.predict_focused([[0.1, 0.2, 5.0]], window=1)[0] == [2]
+    # invariants: result is a prefix of the descending order; scale of the scores does not matter
+    rng = np.random.default_rng(3)
+    for _ in range(50):
+        x = rng.random(7)
+        f1 = O.predict_focused([x], 1)[0]
+        f2 = O.predict_focused([1000.0 * x], 1)[0]
+        assert f1 == f2 and 1 <= len(f1) <= 5
+        assert set(f1) == set(np.argsort(-x)[:len(f1)])
