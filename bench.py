@@ -161,6 +161,15 @@ def main():
         ev[i + 1].record()
     torch.cuda.synchronize()
     from_scores_ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]))
+    # attention of the question to every chunk, from the last cc_sparse_prefill's log-sum-exp
+    batch.question_mass()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    ev[0].record()
+    for i in range(args.steps):
+        batch.question_mass()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    question_mass_ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]))
     q_pos = batch.q_pos.cpu().numpy()[: w.n_q_tot]
     attn_flops = attention_flops(w, q_pos)
     proj_flops = 0.0
@@ -207,8 +216,10 @@ def main():
         "roofline": roofline,
         "stages": stages,
         "sparse_prefill_tokens_per_s": w.n_q_tot / (stage_ms["sparse_prefill"] * 1e-3),
-        # not part of the step: the selection half of cc_select alone, on scores the caller already has
-        "extra_calls": {"cc_select_from_scores": {"ms": from_scores_ms, "chunk_tokens": work["n_chunk_tok"]}},
+        # not part of the step: the selection half of cc_select alone, on scores the caller already
+        # has, and the question-to-chunk attention mass computed after cc_sparse_prefill
+        "extra_calls": {"cc_select_from_scores": {"ms": from_scores_ms, "chunk_tokens": work["n_chunk_tok"]},
+                        "cc_question_mass": {"ms": question_mass_ms, "segments": int(len(w.segments))}},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, args.cpu_budget)
