@@ -15,6 +15,9 @@
  *                      (Eq. (1), Sec. 3.4.3, Sec. 4 "Selective Token Recomputation")
  *   cc_question_mass   attention the question pays to every chunk in that layer, inter(C_i, U)
  *                      (Sec. 3.2.2); cc_focus_* turns it into the set of focused chunks (Algorithm 1)
+ *   cc_chunk_attention inter / intra attention sums between the segments of a prompt (Eq. (2), (3));
+ *                      cc_chunk_ab / cc_chunk_cci / cc_chunk_reuse: CCI, beta, gamma, beta', CFO and
+ *                      the token budget from them on the host (Sec. 3.1, 3.3)
  *
  * Conventions
  *   - Every tensor and every metadata array is DEVICE memory owned by the caller; the library
@@ -224,6 +227,62 @@ int cc_question_mass(cc_ctx* ctx, const void* q, const int32_t* q_pos, const int
                      const int32_t* req_seg_off, int32_t n_requests, int32_t n_ctx_tokens,
                      const float* lse, float* seg_mass, void* workspace, size_t workspace_bytes,
                      void* stream);
+
+/* ---- (e) attention between segments: inter and intra of Eq. (2), Eq. (3) ---------------------
+ * For every request r and every pair of its segments t >= s (indices inside the request):
+ *   pair_mass[pair(r, t, s)] = sum over the rows u of the compact list whose position lies in
+ *       segment t of (1/Hq) sum_h sum_{keys l of segment s, l <= q_pos[u]} a^h_{u,l}
+ *   pair(r, t, s) = sum_{r' < r} n_{r'} (n_{r'} + 1) / 2  +  t (t + 1) / 2 + s,  n_r = segments of r
+ * and, if self_mass is not NULL, for every segment s of the batch
+ *   self_mass[s] = sum over the rows u in s of (1/Hq) sum_h a^h_{u,u}   (the row's own key)
+ * with a the softmax weights of step 2 of cc_sparse_prefill.  With every token of the prompt in
+ * the compact list (the full prefill that creates a chunk-cache, Sec. 3.4.3 "metadata") these are
+ * inter(C_s, C_t) for s < t, and intra(C_t) = pair_mass[pair(r, t, t)] - self_mass[t] (Eq. (3)
+ * sums strictly earlier tokens).  With fewer rows they are the same sums over the rows present.
+ * Call it after cc_sparse_prefill like cc_question_mass (same arguments, its lse; slot_map is
+ * needed for self_mass only).  The masses come from a pass of their own (the attention kernels
+ * once per (segment, rows that see it) pair, log-sum-exp only): about one more attention pass.
+ *   n_pairs: entries of pair_mass (host scalar, = sum_r n_r (n_r + 1) / 2); all are written
+ *   (0 where no row falls).  max_q_per_req as for cc_sparse_prefill.
+ *   workspace: cc_chunk_attention_workspace_bytes(ctx, n_ctx_tokens, n_segs, n_q_tot, max_q_per_req). */
+size_t cc_chunk_attention_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_tokens, int32_t n_segs,
+                                          int32_t n_q_tot, int32_t max_q_per_req);
+int cc_chunk_attention(cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* slot_map,
+                       const int32_t* cu_q, int32_t n_q_tot, int32_t max_q_per_req,
+                       const void* k_pool, const void* v_pool, int32_t n_blocks, const int32_t* block_tab,
+                       const cc_segment* segs, int32_t n_segs,
+                       const int32_t* req_seg_off, int32_t n_requests, int32_t n_ctx_tokens,
+                       int32_t n_pairs, const float* lse, float* pair_mass, float* self_mass,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- reuse scores of a chunk-cache (host only; no GPU work, HOST pointers) --------------------
+ * cc_chunk_ab: one layer's a(C_i) = sum_{j<i} inter(C_j, C_i) / (|C_i| |C_j|) and
+ *   b(C_i) = intra(C_i) / |C_i|^2 from the n_prefix inter sums of the chunk's prefix chunks, their
+ *   lengths, the chunk's intra sum and its length (Sec. 3.1).
+ * cc_chunk_cci: CCI = 1 / (1 + exp(-abar / bbar)) with abar, bbar the means of a and b over the
+ *   layers given (Sec. 3.1).  abar = 0 gives ratio 0 (CCI 0.5), bbar = 0 < abar an infinite one (1).
+ * cc_chunk_reuse: for a cache of chunk C_i made behind the ordered prefix old_prefix[n_old]
+ *   (chunk ids, with inter(i, j) of each in old_inter) and now wanted behind new_prefix[n_new]:
+ *     beta     = sum of old_inter over chunks also in the new prefix / sum of old_inter
+ *                (1 when the old sum is 0: a cache that depended on nothing has lost nothing)
+ *     gamma    = D / (m (m - 1) / 2): discordant pairs of the m common chunks between the two
+ *                orders, i.e. the normalised Kendall tau distance (0 when m < 2)
+ *     beta_adj = beta (1 - gamma)
+ *     cfo      = alpha * cci * (1 - beta_adj), clipped to [0, 1]              (Sec. 3.3)
+ *     n_recompute = ceil(cfo * chunk_len) (guarded against representation noise), clipped to
+ *                [0, chunk_len]                                                (Sec. 3.2.1)
+ * All return CC_OK or CC_ERR_INVALID_ARG (null pointer, non-finite or negative score). */
+typedef struct {
+  double beta, gamma, beta_adj, cfo;
+  int32_t n_recompute;
+  int32_t reserved;
+} cc_reuse;
+int cc_chunk_ab(const double* inter, const int32_t* prefix_len, int32_t n_prefix, double intra,
+                int32_t chunk_len, double* a, double* b);
+int cc_chunk_cci(const double* a, const double* b, int32_t n_layers, double* cci);
+int cc_chunk_reuse(const int64_t* old_prefix, const double* old_inter, int32_t n_old,
+                   const int64_t* new_prefix, int32_t n_new, double cci, double alpha,
+                   int32_t chunk_len, cc_reuse* out);
 
 /* ---- focused chunks (host only; no GPU work, HOST pointers) --------------------------------
  * Algorithm 1 for ONE request with k chunks, fed once per layer l = 1, 2, ... with that layer's

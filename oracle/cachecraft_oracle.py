@@ -49,6 +49,19 @@ Two further steps follow the question-to-chunk attention of Sec. 3.2.2:
           of i is empty and with all gaps zero p is undefined -- every chunk is then
           kept.  The stop rule compares the last w sets once l >= w.
 
+And the reuse scores of Sec. 3.1 / 3.3, from the same attention weights:
+
+  inter / intra   Eq. (2) and Eq. (3) between the segments of a prompt; a, b, CCI (sigmoid
+          of abar / bbar); prefix overlap beta; order penalty gamma = D / C(m, 2), the normalised
+          Kendall tau distance between the old and the new order of the common prefix chunks;
+          beta' = beta (1 - gamma); CFO = alpha CCI (1 - beta'); N = ceil(CFO |C|).
+          Readings: Eq. (3)'s "k < l" is taken as: a token's weights on strictly earlier tokens
+          of its own chunk (the weight on itself is left out); head aggregation is the mean, as
+          everywhere; beta = 1 when the old inter sum is zero (nothing was depended on),
+          gamma = 0 with fewer than two common chunks; abar = 0 gives ratio 0, bbar = 0 < abar an
+          infinite ratio; CFO is clipped to [0, 1]; the ceiling carries the same 1e-9 guard as the
+          workload generator's token budget.
+
 Parity pins (tests/test_oracle_pins.py): every function below is pinned by
 closed forms, invariants, limiting cases or brute force -- none is unpinned.
 The scoring *definition* (mean over heads, scores in the new context) is pinned
@@ -318,6 +331,73 @@ def question_chunk_mass(w, r: int, k_ctx: np.ndarray, q=None) -> np.ndarray:
         q_rot = rotate(np.asarray(q[tok:tok + n], dtype=np.float64), pos, theta)
         total += segment_mass_rows(q_rot, pos, k_ctx, bounds).mean(axis=1).sum(axis=0)
     return total
+
+
+def segment_attention_matrix(w, r: int, k_ctx: np.ndarray, q_pos: np.ndarray, q_row: np.ndarray, q=None):
+    """inter / intra sums between the segments of request r over the given rows (positions q_pos,
+    rows q_row of q): M[t, s] = sum over rows in segment t of the head-mean weight on the keys of
+    segment s (s <= t), and self_w[t] = the same for each row's own key alone.
+    inter(C_s, C_t) = M[t, s] for s < t (Eq. (2)); intra(C_t) = M[t, t] - self_w[t] (Eq. (3))."""
+    theta = w.spec.rope_theta
+    q = w.q if q is None else q
+    segs = _segments_of(w, r)
+    bounds = [sg[2] for sg in segs] + [segs[-1][2] + segs[-1][3]]
+    n_seg = len(segs)
+    m = np.zeros((n_seg, n_seg), dtype=np.float64)
+    self_w = np.zeros(n_seg, dtype=np.float64)
+    if len(q_pos) == 0:
+        return m, self_w
+    q_rot = rotate(np.asarray(q[q_row], dtype=np.float64), q_pos, theta)
+    mass = segment_mass_rows(q_rot, q_pos, k_ctx, bounds).mean(axis=1)          # [n, n_seg]
+    hq, d = q_rot.shape[1], q_rot.shape[2]
+    g = hq // k_ctx.shape[1]
+    _, lse = causal_attention_rows(q_rot, q_pos, k_ctx, np.zeros_like(k_ctx))
+    for j, p in enumerate(q_pos):
+        t = max(i for i in range(n_seg) if bounds[i] <= p)
+        m[t] += mass[j]
+        own = [np.exp(k_ctx[p, h // g, :] @ q_rot[j, h, :] / np.sqrt(np.float64(d)) - lse[j, h]) for h in range(hq)]
+        self_w[t] += np.mean(own)
+    return m, self_w
+
+
+def chunk_ab(inter: Sequence[float], prefix_len: Sequence[int], intra: float, chunk_len: int):
+    """a(C_i) = sum_j inter(C_j, C_i) / (|C_i| |C_j|), b(C_i) = intra(C_i) / |C_i|^2 (Sec. 3.1)."""
+    a = sum(float(x) / (chunk_len * int(n)) for x, n in zip(inter, prefix_len))
+    return a, float(intra) / (chunk_len * chunk_len)
+
+
+def cci(a_layers: Sequence[float], b_layers: Sequence[float]) -> float:
+    """CCI = sigmoid(abar / bbar) with the layer means of a and b (Sec. 3.1)."""
+    abar, bbar = float(np.mean(a_layers)), float(np.mean(b_layers))
+    ratio = 0.0 if abar == 0.0 else (np.inf if bbar == 0.0 else abar / bbar)
+    return float(1.0 / (1.0 + np.exp(-ratio)))
+
+
+def prefix_overlap(old_prefix: Sequence[int], old_inter: Sequence[float], new_prefix: Sequence[int]) -> float:
+    """beta(C_i | S_new): share of the old inter-attention that came from chunks still in the prefix."""
+    total = float(sum(old_inter))
+    if total == 0.0:
+        return 1.0
+    return float(sum(x for c, x in zip(old_prefix, old_inter) if c in set(new_prefix))) / total
+
+
+def order_penalty(old_prefix: Sequence[int], new_prefix: Sequence[int]) -> float:
+    """gamma: discordant pairs between the old and new order of the common chunks, over C(m, 2)."""
+    common = [c for c in old_prefix if c in set(new_prefix)]
+    m = len(common)
+    if m < 2:
+        return 0.0
+    rank_new = {c: i for i, c in enumerate(new_prefix)}
+    d = sum(1 for i in range(m) for j in range(i + 1, m) if rank_new[common[i]] > rank_new[common[j]])
+    return d / (m * (m - 1) / 2.0)
+
+
+def cache_fix_overhead(cci_value: float, beta: float, gamma: float, alpha: float, chunk_len: int):
+    """beta' = beta (1 - gamma); CFO = alpha CCI (1 - beta') in [0, 1]; N = ceil(CFO |C|) (Sec. 3.3, 3.2.1)."""
+    beta_adj = beta * (1.0 - gamma)
+    cfo = min(1.0, max(0.0, alpha * cci_value * (1.0 - beta_adj)))
+    n = int(min(chunk_len, max(0, np.ceil(cfo * chunk_len - 1e-9))))
+    return beta_adj, cfo, n
 
 
 def predict_focused(inter_layers: Sequence[Sequence[float]], window: int):

@@ -23,6 +23,11 @@ class CacheCraftError(RuntimeError):
         self.status = status
 
 
+class _Reuse(C.Structure):
+    _fields_ = [("beta", C.c_double), ("gamma", C.c_double), ("beta_adj", C.c_double), ("cfo", C.c_double),
+                ("n_recompute", C.c_int32), ("reserved", C.c_int32)]
+
+
 class _Config(C.Structure):
     _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("block_size", C.c_int32), ("dtype", C.c_int32), ("reserved", C.c_int32),
@@ -76,6 +81,19 @@ def load_library() -> C.CDLL:
     lib.cc_question_mass.argtypes = [vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, vp, i32, vp, i32, i32,
                                      vp, vp, vp, sz, vp]
     lib.cc_question_mass.restype = C.c_int
+    lib.cc_chunk_attention_workspace_bytes.argtypes = [vp, i32, i32, i32, i32]
+    lib.cc_chunk_attention_workspace_bytes.restype = sz
+    lib.cc_chunk_attention.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, vp, i32, vp, i32, i32, i32,
+                                       vp, vp, vp, vp, sz, vp]
+    lib.cc_chunk_attention.restype = C.c_int
+    dp = C.POINTER(C.c_double)
+    lib.cc_chunk_ab.argtypes = [dp, C.POINTER(i32), i32, C.c_double, i32, dp, dp]
+    lib.cc_chunk_ab.restype = C.c_int
+    lib.cc_chunk_cci.argtypes = [dp, dp, i32, dp]
+    lib.cc_chunk_cci.restype = C.c_int
+    lib.cc_chunk_reuse.argtypes = [C.POINTER(C.c_int64), dp, i32, C.POINTER(C.c_int64), i32, C.c_double, C.c_double,
+                                   i32, C.POINTER(_Reuse)]
+    lib.cc_chunk_reuse.restype = C.c_int
     lib.cc_focus_create.argtypes = [C.POINTER(vp), i32, i32]
     lib.cc_focus_create.restype = C.c_int
     lib.cc_focus_destroy.argtypes = [vp]
@@ -180,6 +198,18 @@ class Context:
             _ptr(segs), segs.shape[0], _ptr(req_seg_off), n_requests, n_ctx_tokens, _ptr(out), _ptr(lse),
             _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
+    # -- cc_chunk_attention --------------------------------------------------------------------
+    def chunk_attention_workspace_bytes(self, n_ctx_tokens: int, n_segs: int, n_q_tot: int, max_q_per_req: int) -> int:
+        return int(self._lib.cc_chunk_attention_workspace_bytes(self._h, n_ctx_tokens, n_segs, n_q_tot, max_q_per_req))
+
+    def chunk_attention(self, q, q_pos, slot_map, cu_q, max_q_per_req, k_pool, v_pool, block_tab, segs,
+                        req_seg_off, n_requests, n_ctx_tokens, lse, pair_mass, self_mass, workspace):
+        self._check(self._lib.cc_chunk_attention(
+            self._h, _ptr(q), _ptr(q_pos), _ptr(slot_map), _ptr(cu_q), q.shape[0], max_q_per_req, _ptr(k_pool),
+            _ptr(v_pool), k_pool.shape[0], _ptr(block_tab), _ptr(segs), segs.shape[0], _ptr(req_seg_off),
+            n_requests, n_ctx_tokens, pair_mass.shape[0], _ptr(lse), _ptr(pair_mass), _ptr(self_mass),
+            _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
     # -- cc_question_mass ----------------------------------------------------------------------
     def question_mass_workspace_bytes(self, n_ctx_tokens: int, n_segs: int, max_question_rows: int) -> int:
         return int(self._lib.cc_question_mass_workspace_bytes(self._h, n_ctx_tokens, n_segs, max_question_rows))
@@ -191,6 +221,44 @@ class Context:
             k_pool.shape[0], _ptr(block_tab), _ptr(segs), segs.shape[0], _ptr(req_seg_off), n_requests,
             n_ctx_tokens, _ptr(lse), _ptr(seg_mass), _ptr(workspace),
             workspace.numel() * workspace.element_size(), _stream()))
+
+
+# ---- host-only reuse scores (Sec. 3.1, 3.3) ------------------------------------------------------
+def _host_status(st: int, what: str):
+    if st != 0:
+        raise CacheCraftError(st, what)
+
+
+def chunk_ab(inter, prefix_len, intra: float, chunk_len: int):
+    """One layer's (a, b) of a chunk from its inter sums, its prefix chunks' lengths and its intra sum."""
+    n = len(inter)
+    a, b = C.c_double(), C.c_double()
+    _host_status(load_library().cc_chunk_ab((C.c_double * max(1, n))(*[float(v) for v in inter]),
+                                            (C.c_int32 * max(1, n))(*[int(v) for v in prefix_len]), n,
+                                            float(intra), int(chunk_len), C.byref(a), C.byref(b)), "cc_chunk_ab")
+    return a.value, b.value
+
+
+def chunk_cci(a_layers, b_layers) -> float:
+    n = len(a_layers)
+    out = C.c_double()
+    _host_status(load_library().cc_chunk_cci((C.c_double * max(1, n))(*[float(v) for v in a_layers]),
+                                             (C.c_double * max(1, n))(*[float(v) for v in b_layers]), n,
+                                             C.byref(out)), "cc_chunk_cci")
+    return out.value
+
+
+def chunk_reuse(old_prefix, old_inter, new_prefix, cci: float, alpha: float, chunk_len: int) -> dict:
+    """beta, gamma, beta', CFO and the token budget of a chunk-cache wanted behind a new prefix."""
+    n_old, n_new = len(old_prefix), len(new_prefix)
+    out = _Reuse()
+    _host_status(load_library().cc_chunk_reuse(
+        (C.c_int64 * max(1, n_old))(*[int(v) for v in old_prefix]),
+        (C.c_double * max(1, n_old))(*[float(v) for v in old_inter]), n_old,
+        (C.c_int64 * max(1, n_new))(*[int(v) for v in new_prefix]), n_new, float(cci), float(alpha),
+        int(chunk_len), C.byref(out)), "cc_chunk_reuse")
+    return {"beta": out.beta, "gamma": out.gamma, "beta_adj": out.beta_adj, "cfo": out.cfo,
+            "n_recompute": int(out.n_recompute)}
 
 
 class FocusTracker:

@@ -238,7 +238,7 @@ int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void*
 size_t cc_question_mass_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_tokens, int32_t n_segs,
                                         int32_t max_question_rows) {
   if (ctx == nullptr || n_ctx_tokens < 0 || n_segs < 0 || max_question_rows < 0) return 0;
-  return cc::question_mass_bytes(ctx, n_segs, max_tiles_for(n_ctx_tokens, n_segs), max_question_rows) + 256;
+  return cc::segment_mass_bytes(ctx, n_segs, max_tiles_for(n_ctx_tokens, n_segs), max_question_rows, 0) + 256;
 }
 
 int cc_question_mass(cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
@@ -272,6 +272,50 @@ int cc_question_mass(cc_ctx* ctx, const void* q, const int32_t* q_pos, const int
   cc::launch_question_mass(ctx, q, q_pos, cu_q, max_question_rows, k_pool, v_pool, n_blocks, block_tab, segs,
                            n_segs, req_seg_off, n_requests, lse, seg_mass, workspace,
                            max_tiles_for(n_ctx_tokens, n_segs), st);
+  return cc::check_launch(ctx, fn);
+}
+
+size_t cc_chunk_attention_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_tokens, int32_t n_segs,
+                                          int32_t n_q_tot, int32_t max_q_per_req) {
+  if (ctx == nullptr || n_ctx_tokens < 0 || n_segs < 0 || n_q_tot < 0 || max_q_per_req < 0) return 0;
+  return cc::segment_mass_bytes(ctx, n_segs, max_tiles_for(n_ctx_tokens, n_segs), max_q_per_req, n_q_tot) + 256;
+}
+
+int cc_chunk_attention(cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* slot_map,
+                       const int32_t* cu_q, int32_t n_q_tot, int32_t max_q_per_req, const void* k_pool,
+                       const void* v_pool, int32_t n_blocks, const int32_t* block_tab,
+                       const cc_segment* segs, int32_t n_segs, const int32_t* req_seg_off,
+                       int32_t n_requests, int32_t n_ctx_tokens, int32_t n_pairs, const float* lse,
+                       float* pair_mass, float* self_mass, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+  static const char* fn = "cc_chunk_attention";
+  if (ctx == nullptr) return CC_ERR_INVALID_ARG;
+  CC_REQUIRE(n_q_tot >= 0 && max_q_per_req >= 0 && n_segs >= 0 && n_requests >= 0 && n_ctx_tokens >= 0 &&
+                 n_pairs >= 0, "negative count");
+  CC_REQUIRE(max_q_per_req <= n_q_tot, "max_q_per_req exceeds n_q_tot");
+  if (n_segs == 0 || n_pairs == 0) return CC_OK;
+  CC_REQUIRE(pair_mass != nullptr, "null pointer");
+  CC_REQUIRE(n_pairs >= n_segs, "n_pairs is smaller than the number of segments");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (n_q_tot > 0) {
+    CC_REQUIRE(q && q_pos && cu_q && k_pool && v_pool && block_tab && segs && req_seg_off && lse, "null pointer");
+    CC_REQUIRE(self_mass == nullptr || slot_map != nullptr, "self_mass needs slot_map");
+    CC_REQUIRE(n_blocks > 0 && n_requests > 0 && max_q_per_req > 0, "sizes must be positive");
+    CC_REQUIRE(n_segs <= 65535, "more than 65535 segments in one call");
+    CC_REQUIRE(n_requests <= n_segs, "every request needs at least one segment");
+    CC_REQUIRE(static_cast<int64_t>(n_segs) * max_q_per_req <= 0x3fffffff, "n_segs * max_q_per_req too large");
+    CC_REQUIRE(aligned16(q) && aligned16(k_pool) && aligned16(v_pool), "tensors must be 16-byte aligned");
+    CC_REQUIRE(workspace != nullptr && aligned16(workspace), "workspace missing or misaligned");
+    if (workspace_bytes < cc_chunk_attention_workspace_bytes(ctx, n_ctx_tokens, n_segs, n_q_tot, max_q_per_req))
+      return fail(ctx, CC_ERR_WORKSPACE_TOO_SMALL,
+                  "cc_chunk_attention: workspace smaller than cc_chunk_attention_workspace_bytes()");
+  }
+  cc::launch_fill_zero(pair_mass, n_pairs, st);             // pairs no row of the list falls into stay 0
+  if (self_mass != nullptr) cc::launch_fill_zero(self_mass, n_segs, st);
+  if (n_q_tot == 0) return cc::check_launch(ctx, fn);
+  cc::launch_chunk_attention(ctx, q, q_pos, slot_map, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks,
+                             block_tab, segs, n_segs, req_seg_off, n_requests, lse, pair_mass, n_pairs, self_mass,
+                             workspace, max_tiles_for(n_ctx_tokens, n_segs), st);
   return cc::check_launch(ctx, fn);
 }
 

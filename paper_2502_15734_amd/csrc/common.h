@@ -80,7 +80,14 @@ void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, co
 
 // attention mass of the question rows on every segment (focus.hip)
 void launch_fill_zero(float* p, int n, hipStream_t stream);
-size_t question_mass_bytes(const cc_ctx* ctx, int n_segs, int max_tiles, int max_question_rows);
+// n_q_tot_self: rows of the compact list when the self weights are wanted too (else 0)
+size_t segment_mass_bytes(const cc_ctx* ctx, int n_segs, int max_tiles, int max_rows, int n_q_tot_self);
+void launch_chunk_attention(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* slot_map,
+                            const int32_t* cu_q, int n_q_tot, int max_q_per_req, const void* k_pool,
+                            const void* v_pool, int n_blocks, const int32_t* block_tab, const cc_segment* segs,
+                            int n_segs, const int32_t* req_seg_off, int n_requests, const float* lse,
+                            float* pair_mass, int n_pairs, float* self_mass, void* workspace, int max_tiles,
+                            hipStream_t stream);
 void launch_question_mass(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
                           int max_question_rows, const void* k_pool, const void* v_pool, int n_blocks,
                           const int32_t* block_tab, const cc_segment* segs, int n_segs,

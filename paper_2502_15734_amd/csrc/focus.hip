@@ -10,9 +10,15 @@
 // build the list (question rows per request, offsets per segment, the row map), one reduces
 // exp(lse_s - lse) over rows and heads in a fixed order.
 //
+// The same list with every row of the compact query list (each from the first segment it can see
+// on) gives the whole lower-triangular matrix of segment-to-segment attention: inter(C_j, C_i) of
+// Eq. (2) off the diagonal, intra(C_i) of Eq. (3) on it once the weight every row puts on its own
+// key is taken off (a small kernel of its own).
+//
 // Host part.  Algorithm 1: per-chunk cumulative scores over the layers, a split of the sorted
 // scores at the gap with the largest entropy term, and a stop once the chosen set has not changed
-// for w layers.
+// for w layers.  Reuse scores of Sec. 3.1 / 3.3: a, b, CCI, prefix overlap beta, order penalty
+// gamma (normalised Kendall tau distance), beta', CFO and the token budget N.
 #include <algorithm>
 #include <cmath>
 #include <new>
@@ -33,6 +39,15 @@ __device__ __forceinline__ int question_start(const cc_segment* __restrict__ seg
   for (int s = req_seg_off[r]; s < req_seg_off[r + 1]; ++s)
     if (segs[s].kind == CC_SEG_QUESTION) qs = min(qs, segs[s].logical_start);
   return qs;
+}
+
+// Rows of list entry s (= segment s as the only keys): the rows of its request at positions
+// >= this threshold.  question_only: the request's question rows; else every row that can see the
+// segment at all, i.e. from the segment's first position on.
+__device__ __forceinline__ int entry_threshold(const cc_segment* __restrict__ segs,
+                                               const int32_t* __restrict__ req_seg_off, int s, int r,
+                                               bool question_only) {
+  return question_only ? question_start(segs, req_seg_off, r) : segs[s].logical_start;
 }
 
 // inclusive scan of one int per thread over a 256-thread workgroup; *total gets the sum
@@ -58,35 +73,49 @@ __device__ __forceinline__ int block_scan_256(int v, int* total) {
   return incl + before;
 }
 
-// m_req[r] = number of rows of request r at question positions (at most max_rows are kept)
-__global__ __launch_bounds__(256) void question_count_kernel(
+// sum of one float per thread over a 256-thread workgroup, fixed tree (the same sum every run);
+// valid in thread 0
+__device__ __forceinline__ float block_sum_256(float v) {
+  __shared__ float part[256];
+  __syncthreads();
+  part[threadIdx.x] = v;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) part[threadIdx.x] += part[threadIdx.x + o];
+    __syncthreads();
+  }
+  return part[0];
+}
+
+// m_seg[s] = number of rows of entry s (at most max_rows are kept)
+__global__ __launch_bounds__(256) void entry_count_kernel(
     const int32_t* __restrict__ q_pos, const int32_t* __restrict__ cu_q,
-    const cc_segment* __restrict__ segs, const int32_t* __restrict__ req_seg_off, int max_rows,
-    int32_t* __restrict__ m_req) {
-  const int r = blockIdx.x;
-  const int qs = question_start(segs, req_seg_off, r);
+    const cc_segment* __restrict__ segs, const int32_t* __restrict__ req_seg_off, int n_requests,
+    int max_rows, bool question_only, int32_t* __restrict__ m_seg) {
+  const int s = blockIdx.x;
+  const int r = segs[s].req;
+  if (r < 0 || r >= n_requests) {
+    if (threadIdx.x == 0) m_seg[s] = 0;
+    return;
+  }
+  const int thr = entry_threshold(segs, req_seg_off, s, r, question_only);
   int cnt = 0;
   for (int j0 = cu_q[r]; j0 < cu_q[r + 1]; j0 += 256) {
     const int j = j0 + threadIdx.x;
-    cnt += __syncthreads_count(j < cu_q[r + 1] && q_pos[j] >= qs);
+    cnt += __syncthreads_count(j < cu_q[r + 1] && q_pos[j] >= thr);
   }
-  if (threadIdx.x == 0) m_req[r] = min(cnt, max_rows);
+  if (threadIdx.x == 0) m_seg[s] = min(cnt, max_rows);
 }
 
-// cu_v[s] = list rows before entry s (exclusive scan of m_req[segs[s].req]); seg_iota[s] = s
+// cu_v[s] = list rows before entry s (exclusive scan of m_seg); seg_iota[s] = s
 __global__ __launch_bounds__(256) void list_scan_kernel(
-    const cc_segment* __restrict__ segs, int n_segs, int n_requests, const int32_t* __restrict__ m_req,
-    int32_t* __restrict__ cu_v, int32_t* __restrict__ seg_iota) {
+    int n_segs, const int32_t* __restrict__ m_seg, int32_t* __restrict__ cu_v, int32_t* __restrict__ seg_iota) {
   __shared__ int carry_s;
   if (threadIdx.x == 0) carry_s = 0;
   __syncthreads();
   for (int s0 = 0; s0 < n_segs; s0 += 256) {
     const int s = s0 + threadIdx.x;
-    int m = 0;
-    if (s < n_segs) {
-      const int r = segs[s].req;
-      m = (r >= 0 && r < n_requests) ? m_req[r] : 0;
-    }
+    const int m = s < n_segs ? m_seg[s] : 0;
     int total;
     const int incl = block_scan_256(m, &total);
     const int carry = carry_s;
@@ -104,51 +133,136 @@ __global__ __launch_bounds__(256) void list_scan_kernel(
   }
 }
 
-// q_map[cu_v[s] + i] = i-th question row of segment s's request (rows in list order);
-// lse_seg of those rows starts at -inf (a row tile that sees no key of the segment writes nothing)
+// q_map[cu_v[s] + i] = i-th row of entry s (rows in list order); row_seg (optional) = the segment
+// that row's own position lies in; lse_seg of the entry's rows starts at -inf (a row tile that
+// sees no key of the segment writes nothing)
 __global__ __launch_bounds__(256) void row_map_kernel(
     const int32_t* __restrict__ q_pos, const int32_t* __restrict__ cu_q,
     const cc_segment* __restrict__ segs, const int32_t* __restrict__ req_seg_off, int n_requests,
-    const int32_t* __restrict__ cu_v, int hq, int32_t* __restrict__ q_map, float* __restrict__ lse_seg) {
+    const int32_t* __restrict__ cu_v, int hq, bool question_only, int32_t* __restrict__ q_map,
+    int32_t* __restrict__ row_seg, float* __restrict__ lse_seg) {
   const int s = blockIdx.x;
   const int r = segs[s].req;
   if (r < 0 || r >= n_requests) return;
   const int base = cu_v[s], m = cu_v[s + 1] - base;
   if (m <= 0) return;
-  const int qs = question_start(segs, req_seg_off, r);
+  const int thr = entry_threshold(segs, req_seg_off, s, r, question_only);
   int done = 0;
   for (int j0 = cu_q[r]; j0 < cu_q[r + 1]; j0 += 256) {      // (uniform trip count)
     const int j = j0 + threadIdx.x;
-    const int is_q = (j < cu_q[r + 1] && q_pos[j] >= qs) ? 1 : 0;
+    const int pos = j < cu_q[r + 1] ? q_pos[j] : -1;
+    const int take = pos >= thr ? 1 : 0;
     int total;
-    const int ord = done + block_scan_256(is_q, &total) - is_q;
-    if (is_q && ord < m) q_map[base + ord] = j;
+    const int ord = done + block_scan_256(take, &total) - take;
+    if (take && ord < m) {
+      q_map[base + ord] = j;
+      if (row_seg != nullptr) {
+        int own = -1;
+        for (int t = req_seg_off[r]; t < req_seg_off[r + 1]; ++t)
+          if (pos >= segs[t].logical_start && pos < segs[t].logical_start + segs[t].n_tokens) own = t;
+        row_seg[base + ord] = own;
+      }
+    }
     done += total;
   }
   for (int i = threadIdx.x; i < m * hq; i += 256) lse_seg[static_cast<size_t>(base) * hq + i] = -INFINITY;
+}
+
+// weight a list row's head puts on the entry's segment
+__device__ __forceinline__ float entry_weight(const float* __restrict__ lse_seg, const float* __restrict__ lse,
+                                              const int32_t* __restrict__ q_map, int list_row, int h, int hq) {
+  const float a = lse_seg[static_cast<size_t>(list_row) * hq + h];
+  const float b = lse[static_cast<size_t>(q_map[list_row]) * hq + h];
+  return a == -INFINITY ? 0.f : __expf(a - b);
 }
 
 // seg_mass[s] = (1/Hq) sum over the entry's rows and heads of exp(lse_seg - lse)
 __global__ __launch_bounds__(256) void seg_mass_kernel(
     const int32_t* __restrict__ cu_v, const int32_t* __restrict__ q_map, int hq,
     const float* __restrict__ lse_seg, const float* __restrict__ lse, float* __restrict__ seg_mass) {
-  __shared__ float part[256];
   const int s = blockIdx.x;
   const int base = cu_v[s], m = cu_v[s + 1] - base;
   float acc = 0.f;
   for (int i = threadIdx.x; i < m * hq; i += 256) {
-    const int u = i / hq, h = i - u * hq;
-    const float a = lse_seg[static_cast<size_t>(base + u) * hq + h];
-    const float b = lse[static_cast<size_t>(q_map[base + u]) * hq + h];
-    acc += a == -INFINITY ? 0.f : __expf(a - b);
+    const int u = i / hq;
+    acc += entry_weight(lse_seg, lse, q_map, base + u, i - u * hq, hq);
   }
-  part[threadIdx.x] = acc;
-  __syncthreads();
-  for (int o = 128; o > 0; o >>= 1) {                        // fixed tree: the same sum every run
-    if (threadIdx.x < o) part[threadIdx.x] += part[threadIdx.x + o];
-    __syncthreads();
+  const float tot = block_sum_256(acc);
+  if (threadIdx.x == 0) seg_mass[s] = tot / static_cast<float>(hq);
+}
+
+// pair_mass[pair(t, s)] for every segment t >= s of entry s's request: the entry's rows whose own
+// position lies in t.  pair(t, s) = pairs of earlier requests + tl (tl + 1) / 2 + sl with tl, sl
+// the segments' indices inside their request.
+__global__ __launch_bounds__(256) void pair_mass_kernel(
+    const cc_segment* __restrict__ segs, const int32_t* __restrict__ req_seg_off, int n_requests,
+    const int32_t* __restrict__ cu_v, const int32_t* __restrict__ q_map, const int32_t* __restrict__ row_seg,
+    int hq, const float* __restrict__ lse_seg, const float* __restrict__ lse, float* __restrict__ pair_mass,
+    int n_pairs) {
+  const int s = blockIdx.x;
+  const int r = segs[s].req;
+  if (r < 0 || r >= n_requests) return;
+  int pair_base = 0;
+  for (int r2 = 0; r2 < r; ++r2) {
+    const int n2 = req_seg_off[r2 + 1] - req_seg_off[r2];
+    pair_base += n2 * (n2 + 1) / 2;
   }
-  if (threadIdx.x == 0) seg_mass[s] = part[0] / static_cast<float>(hq);
+  const int s_first = req_seg_off[r], sl = s - s_first;
+  const int base = cu_v[s], m = cu_v[s + 1] - base;
+  for (int t = s; t < req_seg_off[r + 1]; ++t) {
+    float acc = 0.f;
+    for (int i = threadIdx.x; i < m * hq; i += 256) {
+      const int u = i / hq;
+      if (row_seg[base + u] == t) acc += entry_weight(lse_seg, lse, q_map, base + u, i - u * hq, hq);
+    }
+    const float tot = block_sum_256(acc);
+    const int tl = t - s_first;
+    const int pi = pair_base + tl * (tl + 1) / 2 + sl;
+    if (threadIdx.x == 0 && pi < n_pairs) pair_mass[pi] = tot / static_cast<float>(hq);
+  }
+}
+
+// self_mass[s] = (1/Hq) sum over the rows of the compact list that lie in segment s and over heads
+// of the weight the row puts on its own key: exp(q'.k_own / sqrt(d) - lse).  One wavefront per
+// (row, head); lane i owns rotation pair (i, i + d/2).  Written per row into row_self, then summed
+// per segment in a fixed order by self_sum_kernel.
+template <typename T, int D>
+__global__ __launch_bounds__(64) void self_weight_kernel(
+    const T* __restrict__ q, const int32_t* __restrict__ q_pos, const int32_t* __restrict__ slot_map,
+    const T* __restrict__ k_pool, int n_blocks, int hq, int hkv, InvFreq inv_freq,
+    const float* __restrict__ lse, float* __restrict__ row_self) {
+  const int j = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
+  const int slot = slot_map[j];
+  float part = 0.f;
+  const bool ok = slot >= 0 && slot / kBlock < n_blocks;
+  if (ok && lane < D / 2) {
+    const T* qp = q + (static_cast<size_t>(j) * hq + h) * D;
+    float x = to_float(qp[lane]), y = to_float(qp[lane + D / 2]), c, sn;
+    rot_cos_sin(q_pos[j], inv_freq.f[lane], &c, &sn);
+    const float qx = x * c - y * sn, qy = y * c + x * sn;
+    const int kvh = h / (hq / hkv);
+    const T* kp = k_pool + ((static_cast<size_t>(slot / kBlock) * hkv + kvh) * kBlock + slot % kBlock) * D;
+    part = qx * to_float(kp[lane]) + qy * to_float(kp[lane + D / 2]);
+  }
+  const float logit = wave_sum(part) * rsqrtf(static_cast<float>(D));
+  if (lane == 0) row_self[static_cast<size_t>(j) * hq + h] = ok ? __expf(logit - lse[static_cast<size_t>(j) * hq + h]) : 0.f;
+}
+
+__global__ __launch_bounds__(256) void self_sum_kernel(
+    const int32_t* __restrict__ q_pos, const int32_t* __restrict__ cu_q, const cc_segment* __restrict__ segs,
+    int n_requests, int hq, const float* __restrict__ row_self, float* __restrict__ self_mass) {
+  const int s = blockIdx.x;
+  const cc_segment sg = segs[s];
+  float acc = 0.f;
+  if (sg.req >= 0 && sg.req < n_requests) {
+    const int j0 = cu_q[sg.req], n = cu_q[sg.req + 1] - j0;
+    for (int i = threadIdx.x; i < n * hq; i += 256) {
+      const int u = i / hq, pos = q_pos[j0 + u];
+      if (pos >= sg.logical_start && pos < sg.logical_start + sg.n_tokens) acc += row_self[static_cast<size_t>(j0) * hq + i];
+    }
+  }
+  const float tot = block_sum_256(acc);
+  if (threadIdx.x == 0) self_mass[s] = tot / static_cast<float>(hq);
 }
 
 __global__ __launch_bounds__(256) void fill_zero_kernel(float* __restrict__ p, int n) {
@@ -158,18 +272,71 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(float* __restrict__ p, i
 
 size_t up256(size_t v) { return (v + 255) / 256 * 256; }
 
+// the workspace, cut up
+struct ListBuffers {
+  void* plan_ws;
+  int32_t *m_seg, *cu_v, *seg_iota, *q_map, *row_seg;
+  float *lse_seg, *row_self;
+};
+
 }  // namespace
 
 void launch_fill_zero(float* p, int n, hipStream_t stream) {
   if (n > 0) hipLaunchKernelGGL(fill_zero_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, p, n);
 }
 
-// workspace: tile plan | m_req[n_segs] | cu_v[n_segs+1] | seg_iota[n_segs+1] | q_map[cap] | lse_seg[cap][Hq]
-size_t question_mass_bytes(const cc_ctx* ctx, int n_segs, int max_tiles, int max_question_rows) {
-  const size_t cap = static_cast<size_t>(n_segs) * max_question_rows;
+// workspace: tile plan | m_seg[n_segs+1] | cu_v[n_segs+1] | seg_iota[n_segs+1] | q_map[cap] |
+//            row_seg[cap] | lse_seg[cap][Hq] | row_self[n_q_tot][Hq] (the last only for the pair matrix)
+size_t segment_mass_bytes(const cc_ctx* ctx, int n_segs, int max_tiles, int max_rows, int n_q_tot_self) {
+  const size_t cap = static_cast<size_t>(n_segs) * max_rows;
   return up256(mfma_plan_bytes(n_segs, max_tiles, static_cast<int>(cap))) +
-         3 * up256(static_cast<size_t>(n_segs + 1) * sizeof(int32_t)) + up256(cap * sizeof(int32_t)) +
-         up256(cap * ctx->cfg.n_q_heads * sizeof(float));
+         3 * up256(static_cast<size_t>(n_segs + 1) * sizeof(int32_t)) + 2 * up256(cap * sizeof(int32_t)) +
+         up256(cap * ctx->cfg.n_q_heads * sizeof(float)) +
+         up256(static_cast<size_t>(n_q_tot_self) * ctx->cfg.n_q_heads * sizeof(float));
+}
+
+static ListBuffers cut_workspace(const cc_ctx* ctx, void* workspace, int n_segs, int max_tiles, int max_rows) {
+  const size_t cap = static_cast<size_t>(n_segs) * max_rows;
+  ListBuffers b;
+  char* w = static_cast<char*>(workspace);
+  b.plan_ws = w;
+  w += up256(mfma_plan_bytes(n_segs, max_tiles, static_cast<int>(cap)));
+  b.m_seg = reinterpret_cast<int32_t*>(w);
+  w += up256(static_cast<size_t>(n_segs + 1) * sizeof(int32_t));
+  b.cu_v = reinterpret_cast<int32_t*>(w);
+  w += up256(static_cast<size_t>(n_segs + 1) * sizeof(int32_t));
+  b.seg_iota = reinterpret_cast<int32_t*>(w);
+  w += up256(static_cast<size_t>(n_segs + 1) * sizeof(int32_t));
+  b.q_map = reinterpret_cast<int32_t*>(w);
+  w += up256(cap * sizeof(int32_t));
+  b.row_seg = reinterpret_cast<int32_t*>(w);
+  w += up256(cap * sizeof(int32_t));
+  b.lse_seg = reinterpret_cast<float*>(w);
+  w += up256(cap * ctx->cfg.n_q_heads * sizeof(float));
+  b.row_self = reinterpret_cast<float*>(w);
+  return b;
+}
+
+// builds the list of one-segment requests and runs the attention kernels over it (log-sum-exp only)
+static void run_segment_list(const cc_ctx* ctx, const ListBuffers& b, const void* q, const int32_t* q_pos,
+                             const int32_t* cu_q, int max_rows, bool question_only, const void* k_pool,
+                             const void* v_pool, int n_blocks, const int32_t* block_tab, const cc_segment* segs,
+                             int n_segs, const int32_t* req_seg_off, int n_requests, int max_tiles,
+                             hipStream_t stream) {
+  const int hq = ctx->cfg.n_q_heads;
+  const int cap = n_segs * max_rows;
+  hipLaunchKernelGGL(entry_count_kernel, dim3(n_segs), dim3(256), 0, stream, q_pos, cu_q, segs, req_seg_off,
+                     n_requests, max_rows, question_only, b.m_seg);
+  hipLaunchKernelGGL(list_scan_kernel, dim3(1), dim3(256), 0, stream, n_segs, b.m_seg, b.cu_v, b.seg_iota);
+  hipLaunchKernelGGL(row_map_kernel, dim3(n_segs), dim3(256), 0, stream, q_pos, cu_q, segs, req_seg_off,
+                     n_requests, b.cu_v, hq, question_only, b.q_map, question_only ? nullptr : b.row_seg,
+                     b.lse_seg);
+  if (ctx->impl != CC_IMPL_SCALAR && attn_mfma_supported(ctx))
+    launch_attn_mfma(ctx, q, q_pos, b.cu_v, cap, max_rows, k_pool, v_pool, n_blocks, block_tab, segs, n_segs,
+                     b.seg_iota, n_segs, nullptr, b.lse_seg, b.plan_ws, max_tiles, b.q_map, stream);
+  else
+    launch_attn_scalar(ctx, q, q_pos, b.cu_v, cap, max_rows, k_pool, v_pool, n_blocks, block_tab, segs,
+                       b.seg_iota, n_segs, nullptr, b.lse_seg, b.q_map, stream);
 }
 
 void launch_question_mass(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
@@ -177,37 +344,40 @@ void launch_question_mass(const cc_ctx* ctx, const void* q, const int32_t* q_pos
                           const int32_t* block_tab, const cc_segment* segs, int n_segs,
                           const int32_t* req_seg_off, int n_requests, const float* lse, float* seg_mass,
                           void* workspace, int max_tiles, hipStream_t stream) {
-  const int hq = ctx->cfg.n_q_heads;
-  const size_t cap = static_cast<size_t>(n_segs) * max_question_rows;
-  char* w = static_cast<char*>(workspace);
-  void* plan_ws = w;
-  w += up256(mfma_plan_bytes(n_segs, max_tiles, static_cast<int>(cap)));
-  int32_t* m_req = reinterpret_cast<int32_t*>(w);
-  w += up256(static_cast<size_t>(n_segs + 1) * sizeof(int32_t));
-  int32_t* cu_v = reinterpret_cast<int32_t*>(w);
-  w += up256(static_cast<size_t>(n_segs + 1) * sizeof(int32_t));
-  int32_t* seg_iota = reinterpret_cast<int32_t*>(w);
-  w += up256(static_cast<size_t>(n_segs + 1) * sizeof(int32_t));
-  int32_t* q_map = reinterpret_cast<int32_t*>(w);
-  w += up256(cap * sizeof(int32_t));
-  float* lse_seg = reinterpret_cast<float*>(w);
+  const ListBuffers b = cut_workspace(ctx, workspace, n_segs, max_tiles, max_question_rows);
+  run_segment_list(ctx, b, q, q_pos, cu_q, max_question_rows, true, k_pool, v_pool, n_blocks, block_tab, segs,
+                   n_segs, req_seg_off, n_requests, max_tiles, stream);
+  hipLaunchKernelGGL(seg_mass_kernel, dim3(n_segs), dim3(256), 0, stream, b.cu_v, b.q_map, ctx->cfg.n_q_heads,
+                     b.lse_seg, lse, seg_mass);
+}
 
-  hipLaunchKernelGGL(question_count_kernel, dim3(n_requests), dim3(256), 0, stream, q_pos, cu_q, segs,
-                     req_seg_off, max_question_rows, m_req);
-  hipLaunchKernelGGL(list_scan_kernel, dim3(1), dim3(256), 0, stream, segs, n_segs, n_requests, m_req, cu_v,
-                     seg_iota);
-  hipLaunchKernelGGL(row_map_kernel, dim3(n_segs), dim3(256), 0, stream, q_pos, cu_q, segs, req_seg_off,
-                     n_requests, cu_v, hq, q_map, lse_seg);
-  // the attention kernels over the list: request = one segment, queries = its question rows
-  if (ctx->impl != CC_IMPL_SCALAR && attn_mfma_supported(ctx))
-    launch_attn_mfma(ctx, q, q_pos, cu_v, static_cast<int>(cap), max_question_rows, k_pool, v_pool, n_blocks,
-                     block_tab, segs, n_segs, seg_iota, n_segs, nullptr, lse_seg, plan_ws, max_tiles, q_map,
-                     stream);
-  else
-    launch_attn_scalar(ctx, q, q_pos, cu_v, static_cast<int>(cap), max_question_rows, k_pool, v_pool,
-                       n_blocks, block_tab, segs, seg_iota, n_segs, nullptr, lse_seg, q_map, stream);
-  hipLaunchKernelGGL(seg_mass_kernel, dim3(n_segs), dim3(256), 0, stream, cu_v, q_map, hq, lse_seg, lse,
-                     seg_mass);
+void launch_chunk_attention(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* slot_map,
+                            const int32_t* cu_q, int n_q_tot, int max_q_per_req, const void* k_pool,
+                            const void* v_pool, int n_blocks, const int32_t* block_tab, const cc_segment* segs,
+                            int n_segs, const int32_t* req_seg_off, int n_requests, const float* lse,
+                            float* pair_mass, int n_pairs, float* self_mass, void* workspace, int max_tiles,
+                            hipStream_t stream) {
+  const ListBuffers b = cut_workspace(ctx, workspace, n_segs, max_tiles, max_q_per_req);
+  const int hq = ctx->cfg.n_q_heads, hkv = ctx->cfg.n_kv_heads;
+  run_segment_list(ctx, b, q, q_pos, cu_q, max_q_per_req, false, k_pool, v_pool, n_blocks, block_tab, segs,
+                   n_segs, req_seg_off, n_requests, max_tiles, stream);
+  hipLaunchKernelGGL(pair_mass_kernel, dim3(n_segs), dim3(256), 0, stream, segs, req_seg_off, n_requests,
+                     b.cu_v, b.q_map, b.row_seg, hq, b.lse_seg, lse, pair_mass, n_pairs);
+  if (self_mass != nullptr) {
+    const bool bf = ctx->cfg.dtype == CC_BF16;
+    const int d = ctx->cfg.head_dim;
+#define CC_LAUNCH(T, D)                                                                              \
+  hipLaunchKernelGGL((self_weight_kernel<T, D>), dim3(n_q_tot, hq), dim3(64), 0, stream,             \
+                     static_cast<const T*>(q), q_pos, slot_map, static_cast<const T*>(k_pool), n_blocks, \
+                     hq, hkv, ctx->inv_freq, lse, b.row_self)
+    if (bf && d == 128) CC_LAUNCH(bf16_t, 128);
+    else if (bf && d == 64) CC_LAUNCH(bf16_t, 64);
+    else if (!bf && d == 128) CC_LAUNCH(float, 128);
+    else CC_LAUNCH(float, 64);
+#undef CC_LAUNCH
+    hipLaunchKernelGGL(self_sum_kernel, dim3(n_segs), dim3(256), 0, stream, q_pos, cu_q, segs, n_requests, hq,
+                       b.row_self, self_mass);
+  }
 }
 
 }  // namespace cc
@@ -280,5 +450,71 @@ int cc_focus_update(cc_focus* f, const float* inter, int32_t* focused, int32_t* 
 }
 
 int32_t cc_focus_layer(const cc_focus* f) { return f == nullptr ? -1 : f->layer; }
+
+// ---- reuse scores (host) ------------------------------------------------------------------------------
+int cc_chunk_ab(const double* inter, const int32_t* prefix_len, int32_t n_prefix, double intra,
+                int32_t chunk_len, double* a, double* b) {
+  if (a == nullptr || b == nullptr || chunk_len <= 0 || n_prefix < 0) return CC_ERR_INVALID_ARG;
+  if (n_prefix > 0 && (inter == nullptr || prefix_len == nullptr)) return CC_ERR_INVALID_ARG;
+  double acc = 0.0;
+  for (int j = 0; j < n_prefix; ++j) {
+    if (prefix_len[j] <= 0 || !std::isfinite(inter[j])) return CC_ERR_INVALID_ARG;
+    acc += inter[j] / (static_cast<double>(chunk_len) * prefix_len[j]);
+  }
+  if (!std::isfinite(intra)) return CC_ERR_INVALID_ARG;
+  *a = acc;
+  *b = intra / (static_cast<double>(chunk_len) * chunk_len);
+  return CC_OK;
+}
+
+int cc_chunk_cci(const double* a, const double* b, int32_t n_layers, double* cci) {
+  if (a == nullptr || b == nullptr || cci == nullptr || n_layers <= 0) return CC_ERR_INVALID_ARG;
+  double sa = 0.0, sb = 0.0;
+  for (int l = 0; l < n_layers; ++l) {
+    if (!std::isfinite(a[l]) || !std::isfinite(b[l]) || a[l] < 0.0 || b[l] < 0.0) return CC_ERR_INVALID_ARG;
+    sa += a[l];
+    sb += b[l];
+  }
+  const double abar = sa / n_layers, bbar = sb / n_layers;
+  // no outside influence at all: ratio 0 whatever b is; outside influence but none from inside: infinite ratio
+  const double ratio = abar == 0.0 ? 0.0 : (bbar == 0.0 ? INFINITY : abar / bbar);
+  *cci = 1.0 / (1.0 + std::exp(-ratio));
+  return CC_OK;
+}
+
+int cc_chunk_reuse(const int64_t* old_prefix, const double* old_inter, int32_t n_old,
+                   const int64_t* new_prefix, int32_t n_new, double cci, double alpha,
+                   int32_t chunk_len, cc_reuse* out) {
+  if (out == nullptr || n_old < 0 || n_new < 0 || chunk_len < 0) return CC_ERR_INVALID_ARG;
+  if ((n_old > 0 && (old_prefix == nullptr || old_inter == nullptr)) || (n_new > 0 && new_prefix == nullptr))
+    return CC_ERR_INVALID_ARG;
+  if (!std::isfinite(cci) || !std::isfinite(alpha) || alpha < 0.0) return CC_ERR_INVALID_ARG;
+  // position of every old prefix chunk in the new prefix (-1: not there)
+  std::vector<int> where(n_old, -1);
+  double kept = 0.0, all = 0.0;
+  for (int i = 0; i < n_old; ++i) {
+    if (!std::isfinite(old_inter[i]) || old_inter[i] < 0.0) return CC_ERR_INVALID_ARG;
+    for (int j = 0; j < n_new; ++j)
+      if (new_prefix[j] == old_prefix[i]) { where[i] = j; break; }
+    all += old_inter[i];
+    if (where[i] >= 0) kept += old_inter[i];
+  }
+  // a cache that depended on no prefix chunk has lost none of its context
+  out->beta = all > 0.0 ? kept / all : 1.0;
+  // discordant pairs among the common chunks: old order i < j, new order reversed
+  long long m = 0, discordant = 0;
+  for (int i = 0; i < n_old; ++i) {
+    if (where[i] < 0) continue;
+    ++m;
+    for (int j = i + 1; j < n_old; ++j)
+      if (where[j] >= 0 && where[j] < where[i]) ++discordant;
+  }
+  out->gamma = m >= 2 ? static_cast<double>(discordant) / (static_cast<double>(m) * (m - 1) / 2.0) : 0.0;
+  out->beta_adj = out->beta * (1.0 - out->gamma);
+  out->cfo = std::min(1.0, std::max(0.0, alpha * cci * (1.0 - out->beta_adj)));
+  const double n = std::ceil(out->cfo * chunk_len - 1e-9);
+  out->n_recompute = static_cast<int32_t>(std::min<double>(chunk_len, std::max(0.0, n)));
+  return CC_OK;
+}
 
 }  // extern "C"

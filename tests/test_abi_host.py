@@ -28,7 +28,8 @@ def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"cc_rope_shift", "cc_select", "cc_select_from_scores", "cc_sparse_prefill", "cc_gather_rows",
             "cc_qkv_project", "cc_create", "cc_destroy", "cc_question_mass", "cc_question_mass_workspace_bytes",
-            "cc_focus_create", "cc_focus_update", "cc_focus_destroy", "cc_focus_layer"} <= set(names)
+            "cc_focus_create", "cc_focus_update", "cc_focus_destroy", "cc_focus_layer", "cc_chunk_attention",
+            "cc_chunk_attention_workspace_bytes", "cc_chunk_ab", "cc_chunk_cci", "cc_chunk_reuse"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in cc.h but not exported"
 
@@ -103,6 +104,16 @@ def test_calls_reject_bad_arguments_before_launch(lib):
     assert lib.cc_question_mass(*qm, good, good, good, wm, None) == -1
     qm[5], qm[11] = 8, 0
     assert lib.cc_question_mass(*qm, good, good, good, wm, None) == 0
+    # cc_chunk_attention: n_pairs below the segment count, missing lse, self_mass without slot_map, tiny workspace
+    wc = lib.cc_chunk_attention_workspace_bytes(h, 100, 3, 10, 10)
+    ca = [h, good, good, good, good, 10, 10, good, good, 8, good, good, 3, good, 1, 100]
+    assert lib.cc_chunk_attention(*ca, 2, good, good, good, good, wc, None) == -1
+    assert lib.cc_chunk_attention(*ca, 6, None, good, good, good, wc, None) == -1
+    ca[3] = None
+    assert lib.cc_chunk_attention(*ca, 6, good, good, good, good, wc, None) == -1
+    ca[3] = good
+    assert lib.cc_chunk_attention(*ca, 6, good, good, good, good, wc - 1, None) == -3
+    assert lib.cc_chunk_attention(*ca, 0, good, good, good, good, wc, None) == 0
     # null context
     assert lib.cc_rope_shift(None, good, None, 4, good, None, 4, good, good, good, 1, 16, None) == -1
     assert lib.cc_set_impl(h, 99) == -1
@@ -149,6 +160,45 @@ def test_focus_tracker_follows_algorithm_1():
         P.FocusTracker(0, 1)
     with pytest.raises(P.CacheCraftError):
         P.FocusTracker(3, 0)
+
+
+def test_reuse_scores_follow_the_oracle():
+    """cc_chunk_ab / cc_chunk_cci / cc_chunk_reuse (host code of the library) against the oracle's
+    formulas on seeded inputs, plus the argument checks."""
+    import numpy as np
+    import paper_2502_15734_amd as P
+    from oracle import cachecraft_oracle as O
+    rng = np.random.default_rng(77)
+    for case in range(200):
+        n_old, n_new = int(rng.integers(0, 8)), int(rng.integers(0, 8))
+        old = [int(v) for v in rng.choice(10, size=n_old, replace=False)]
+        new = [int(v) for v in rng.choice(10, size=n_new, replace=False)]
+        inter = [float(v) for v in rng.random(n_old) * (rng.random(n_old) < 0.8)]
+        lens = [int(v) for v in rng.integers(1, 2000, size=n_old)]
+        clen = int(rng.integers(1, 1025))
+        intra = float(rng.random() * clen)
+        a, b = P.chunk_ab(inter, lens, intra, clen)
+        ao, bo = O.chunk_ab(inter, lens, intra, clen)
+        assert abs(a - ao) <= 1e-15 + 1e-12 * abs(ao) and abs(b - bo) <= 1e-15 + 1e-12 * abs(bo)
+        layers_a = [a * float(v) for v in rng.random(3)]; layers_b = [b * float(v) for v in rng.random(3)]
+        c = P.chunk_cci(layers_a, layers_b)
+        assert abs(c - O.cci(layers_a, layers_b)) < 1e-12
+        alpha = float(rng.choice([0.5, 1.0, 2.0]))
+        got = P.chunk_reuse(old, inter, new, c, alpha, clen)
+        beta, gamma = O.prefix_overlap(old, inter, new), O.order_penalty(old, new)
+        beta_adj, cfo, n = O.cache_fix_overhead(c, beta, gamma, alpha, clen)
+        assert abs(got["beta"] - beta) < 1e-12 and abs(got["gamma"] - gamma) < 1e-12
+        assert abs(got["beta_adj"] - beta_adj) < 1e-12 and abs(got["cfo"] - cfo) < 1e-12
+        assert got["n_recompute"] == n, f"case {case}"
+    # the paper's example: same prefix chunks, swapped order -> beta 1, gamma 1
+    r = P.chunk_reuse([1, 2], [0.4, 0.6], [2, 1], 0.7, 1.0, 100)
+    assert r["beta"] == 1.0 and r["gamma"] == 1.0 and r["n_recompute"] == 70
+    with pytest.raises(P.CacheCraftError):
+        P.chunk_cci([float("nan")], [1.0])
+    with pytest.raises(P.CacheCraftError):
+        P.chunk_reuse([1], [-0.5], [1], 0.5, 1.0, 10)
+    with pytest.raises(P.CacheCraftError):
+        P.chunk_ab([1.0], [0], 1.0, 10)
 
 
 def test_product_path_does_not_import_the_oracle():

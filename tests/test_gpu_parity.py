@@ -83,6 +83,7 @@ def check_workload(w, impl, score_tol=5e-5):
     b.gather(); b.sparse_prefill()
     compare_prefill(b, res, "oracle selection")
     check_question_mass(w, b, [res[r].k_ctx for r in range(w.n_requests)])
+    check_chunk_attention(w, b, res)
 
     # ---- end to end with the library's own selection -----------------------------------------
     b2 = DeviceBatch(w, impl=impl, poison=True)
@@ -113,6 +114,28 @@ def check_question_mass(w, b, k_ctx_of, requests=None, exact=True):
             err = np.abs(got - want)
             bound = (1e-2 if bf else 1e-4) * want + (1e-4 if bf else 1e-6) * max(1, m_r)
             assert np.all(err <= bound), f"request {r}: question mass {got} vs {want}"
+
+
+def check_chunk_attention(w, b, res):
+    """cc_chunk_attention after cc_sparse_prefill on batch b (oracle's selection imposed) against
+    the oracle's inter / intra sums over the same rows."""
+    pair, self_w, pair_off = b.chunk_attention()
+    torch.cuda.synchronize()
+    pair = pair.cpu().numpy(); self_w = self_w.cpu().numpy()
+    bf = w.spec.dtype == "bf16"
+    for r in range(w.n_requests):
+        s0, s1 = int(w.req_seg_off[r]), int(w.req_seg_off[r + 1])
+        m, sw = O.segment_attention_matrix(w, r, res[r].k_ctx, res[r].q_pos, res[r].q_row)
+        n_rows = np.zeros(s1 - s0)
+        segs = H.all_segments(w, r)
+        for p in res[r].q_pos:
+            n_rows[max(i for i, sg in enumerate(segs) if int(sg[W.SEG_START]) <= p)] += 1
+        for t in range(s1 - s0):
+            row = pair[int(pair_off[r]) + t * (t + 1) // 2: int(pair_off[r]) + t * (t + 1) // 2 + t + 1]
+            bound = (1e-2 if bf else 1e-4) * m[t, :t + 1] + (1e-4 if bf else 1e-6) * max(1.0, n_rows[t])
+            assert np.all(np.abs(row - m[t, :t + 1]) <= bound), f"request {r} segment {t}: {row} vs {m[t, :t + 1]}"
+            assert abs(row.sum() - n_rows[t]) <= (3e-3 if bf else 2e-5) * max(1.0, n_rows[t])
+            assert abs(self_w[s0 + t] - sw[t]) <= (1e-2 if bf else 1e-4) * sw[t] + (1e-4 if bf else 1e-6) * max(1.0, n_rows[t])
 
 
 def _impls():

@@ -461,3 +461,80 @@ def test_focused_degenerate_cases_keep_every_chunk():
         f2 = O.predict_focused([1000.0 * x], 1)[0]
         assert f1 == f2 and 1 <= len(f1) <= 5
         assert set(f1) == set(np.argsort(-x)[:len(f1)])
+
+
+# ----------------------------------------------------------------------------- inter / intra, CCI, beta, gamma, CFO
+def test_segment_matrix_is_the_block_sum_of_a_library_softmax():
+    # full prefill (every token a query): M[t, s] = head-mean of the (t, s) block of the attention
+    # matrix; the diagonal of that matrix is what intra leaves out (Eq. (2), Eq. (3))
+    w = small_workload(lens=(12, 10, 14), question=6, fracs=(1.0, 1.0, 1.0))
+    res = O.run_request(w, 0)
+    assert len(res.q_pos) == 42 and np.array_equal(np.sort(res.q_pos), np.arange(42))
+    order = np.argsort(res.q_pos)
+    q_rot = rope_complex(w.q[res.q_row[order]].astype(np.float64), np.arange(42), 1.0e4)
+    a = attention_matrix(q_rot, res.k_ctx)                            # [Hq, 42, 42]
+    m, self_w = O.segment_attention_matrix(w, 0, res.k_ctx, res.q_pos, res.q_row)
+    bounds = [(0, 12), (12, 22), (22, 36), (36, 42)]
+    for t, (t0, t1) in enumerate(bounds):
+        for s, (s0, s1) in enumerate(bounds):
+            want = a[:, t0:t1, s0:s1].sum(axis=(1, 2)).mean() if s <= t else 0.0
+            assert abs(m[t, s] - want) < 1e-12
+        diag = np.mean([np.trace(a[h, t0:t1, t0:t1]) for h in range(4)])
+        assert abs(self_w[t] - diag) < 1e-12
+        strict = np.mean([np.tril(a[h, t0:t1, t0:t1], -1).sum() for h in range(4)])
+        assert abs((m[t, t] - self_w[t]) - strict) < 1e-12            # intra: strictly earlier tokens
+        assert abs(m[t].sum() - (t1 - t0)) < 1e-12                    # every row's weights add up to one
+
+
+def test_segment_matrix_uniform_closed_form_and_row_subsets():
+    w = small_workload(lens=(8, 5), question=3, fracs=(0.5, 0.4), offsets=(0, 0), order=(0, 1))
+    w.q[:] = 0.0
+    res = O.run_request(w, 0)
+    m, self_w = O.segment_attention_matrix(w, 0, res.k_ctx, res.q_pos, res.q_row)
+    bounds = [0, 8, 13, 16]
+    want = np.zeros((3, 3)); want_self = np.zeros(3)
+    for p in res.q_pos:
+        t = max(i for i in range(3) if bounds[i] <= p)
+        for s in range(3):
+            want[t, s] += max(0, min(bounds[s + 1], p + 1) - bounds[s]) / (p + 1.0)
+        want_self[t] += 1.0 / (p + 1.0)
+    np.testing.assert_allclose(m, want, rtol=1e-13)
+    np.testing.assert_allclose(self_w, want_self, rtol=1e-13)
+
+
+def test_order_penalty_is_the_normalised_kendall_tau_distance():
+    from scipy.stats import kendalltau
+    rng = np.random.default_rng(8)
+    for _ in range(40):
+        n_old, n_new = int(rng.integers(2, 9)), int(rng.integers(2, 9))
+        old = list(rng.choice(12, size=n_old, replace=False)); new = list(rng.choice(12, size=n_new, replace=False))
+        common = [c for c in old if c in new]
+        g = O.order_penalty(old, new)
+        if len(common) < 2:
+            assert g == 0.0
+            continue
+        tau = kendalltau(range(len(common)), [new.index(c) for c in common]).statistic   # (C - D) / T, no ties
+        assert abs(g - (1.0 - tau) / 2.0) < 1e-12
+    # the paper's own example: C1-C2-C3 against C2-C1-C3 for chunk C3 -> beta = 1 yet the order differs
+    assert O.prefix_overlap([1, 2], [0.4, 0.6], [2, 1]) == 1.0
+    assert O.order_penalty([1, 2], [2, 1]) == 1.0 and O.order_penalty([1, 2], [1, 2]) == 0.0
+
+
+def test_prefix_overlap_cci_and_cfo_by_hand():
+    # beta: 0.5 + 0.2 of a total 1.0 survive
+    assert abs(O.prefix_overlap([7, 8, 9], [0.5, 0.3, 0.2], [9, 4, 7]) - 0.7) < 1e-15
+    assert O.prefix_overlap([7, 8], [0.0, 0.0], [1]) == 1.0 and O.prefix_overlap([], [], [1, 2]) == 1.0
+    assert O.prefix_overlap([7, 8], [0.5, 0.5], []) == 0.0
+    # a, b: inter 1 and 2 from prefix chunks of 10 and 20 tokens, own length 10, intra 5
+    a, b = O.chunk_ab([1.0, 2.0], [10, 20], 5.0, 10)
+    assert abs(a - (1.0 / 100 + 2.0 / 200)) < 1e-15 and abs(b - 0.05) < 1e-15
+    # CCI: sigmoid of the ratio of the layer means
+    assert abs(O.cci([0.02, 0.04], [0.05, 0.07]) - 1.0 / (1.0 + math.exp(-0.5))) < 1e-15
+    assert O.cci([0.0], [0.3]) == 0.5 and O.cci([0.0], [0.0]) == 0.5 and O.cci([0.1], [0.0]) == 1.0
+    assert O.cci([0.3], [0.1]) > O.cci([0.2], [0.1]) > O.cci([0.1], [0.1])
+    # CFO and N: beta' = 0.7 * (1 - 1/3), CFO = 1.0 * 0.6 * (1 - 0.4666..) = 0.32, N = ceil(0.32 * 100) = 32
+    beta_adj, cfo, n = O.cache_fix_overhead(0.6, 0.7, 1.0 / 3.0, 1.0, 100)
+    assert abs(beta_adj - 0.7 * 2.0 / 3.0) < 1e-15 and abs(cfo - 0.32) < 1e-12 and n == 32
+    assert O.cache_fix_overhead(0.7, 1.0, 0.0, 1.0, 100)[1:] == (0.0, 0)            # same prefix, same order
+    assert O.cache_fix_overhead(0.9, 0.0, 0.0, 2.0, 64)[1:] == (1.0, 64)            # clipped: recompute everything
+    assert O.cache_fix_overhead(0.5, 0.86, 0.0, 1.0, 100)[2] == 7                   # 0.07 * 100: no spurious ceiling
