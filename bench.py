@@ -170,6 +170,16 @@ def main():
         ev[i + 1].record()
     torch.cuda.synchronize()
     question_mass_ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]))
+    # inter / intra sums between all segments, over the rows of the last cc_sparse_prefill
+    batch.chunk_attention()
+    n_ca = max(1, min(args.steps, 5))
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_ca + 1)]
+    ev[0].record()
+    for i in range(n_ca):
+        batch.chunk_attention()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    chunk_attention_ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(n_ca)]))
     q_pos = batch.q_pos.cpu().numpy()[: w.n_q_tot]
     attn_flops = attention_flops(w, q_pos)
     proj_flops = 0.0
@@ -219,7 +229,8 @@ def main():
         # not part of the step: the selection half of cc_select alone, on scores the caller already
         # has, and the question-to-chunk attention mass computed after cc_sparse_prefill
         "extra_calls": {"cc_select_from_scores": {"ms": from_scores_ms, "chunk_tokens": work["n_chunk_tok"]},
-                        "cc_question_mass": {"ms": question_mass_ms, "segments": int(len(w.segments))}},
+                        "cc_question_mass": {"ms": question_mass_ms, "segments": int(len(w.segments))},
+                        "cc_chunk_attention": {"ms": chunk_attention_ms, "segment_pairs": int(batch.pair_off[-1])}},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, args.cpu_budget)
