@@ -5,6 +5,7 @@
  * prompts S = C_1 .. C_k U (cached chunks followed by the question, Sec. 2.2):
  *
  *   cc_rope_shift      re-position cached keys (Sec. 3.4.3, Sec. 4 "RPE Management")
+ *   cc_rope_place      the same for a store that keeps keys without rotation (Sec. 4)
  *   cc_select          score chunk tokens by attention mass on prior chunks, keep the top N
  *                      (Eq. (2), Eq. (10), Sec. 3.2.1)
  *   cc_select_from_scores  keep the top N of scores the caller already has (Sec. 3.2.1)
@@ -120,6 +121,20 @@ int cc_set_impl(cc_ctx* ctx, int impl);
  *   n_src_blocks / n_dst_blocks: pool sizes in blocks; a table entry outside them is skipped.
  * Sec. 3.4.3, Sec. 4 "RPE Management". */
 int cc_rope_shift(cc_ctx* ctx,
+                  const void* k_src_pool, const void* v_src_pool, int32_t n_src_blocks,
+                  void* k_dst_pool, void* v_dst_pool, int32_t n_dst_blocks,
+                  const int32_t* src_block_tab, const int32_t* dst_block_tab,
+                  const cc_shift_desc* descs, int32_t n_instances, int32_t max_tokens,
+                  void* stream);
+
+/* ---- (a') place keys that were stored WITHOUT rotation ---------------------------------------
+ * The store variant the paper describes (Sec. 4 "RPE Management": the rotation is taken off
+ * before a chunk-cache is kept, and put on at run time with the positions of the new prompt).
+ * Same arguments and layout as cc_rope_shift, but the source keys carry no rotation and token t of
+ * instance i is rotated by (delta_pos + t) * theta^(-2i/d): delta_pos is read as the NEW position
+ * of the instance's token 0.  Equivalent to cc_rope_shift on a store that was rotated at cached
+ * positions c + t with delta_pos = new - c (the rotations compose).  V as in cc_rope_shift. */
+int cc_rope_place(cc_ctx* ctx,
                   const void* k_src_pool, const void* v_src_pool, int32_t n_src_blocks,
                   void* k_dst_pool, void* v_dst_pool, int32_t n_dst_blocks,
                   const int32_t* src_block_tab, const int32_t* dst_block_tab,

@@ -127,6 +127,13 @@ def shift_keys(k: np.ndarray, delta: int, theta: float) -> np.ndarray:
     return rotate(k, np.full(n, delta, dtype=np.int64), theta)
 
 
+def place_keys(k: np.ndarray, start: int, theta: float) -> np.ndarray:
+    """Keys stored without rotation, put at positions start .. start + n - 1 (Sec. 4 "RPE
+    Management": the run-time rotation with the new prompt's positions)."""
+    pos = start + np.arange(k.shape[0], dtype=np.int64)
+    return rotate(k, pos, theta)
+
+
 def prior_mass(q_rot: np.ndarray, k_ctx: np.ndarray, pos: np.ndarray, chunk_start: int) -> np.ndarray:
     """Per-head attention mass of each query on keys before `chunk_start`.
 

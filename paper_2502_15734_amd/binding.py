@@ -59,6 +59,8 @@ def load_library() -> C.CDLL:
     lib.cc_set_impl.argtypes = [vp, C.c_int]
     lib.cc_set_impl.restype = C.c_int
     lib.cc_rope_shift.argtypes = [vp, vp, vp, i32, vp, vp, i32, vp, vp, vp, i32, i32, vp]
+    lib.cc_rope_place.argtypes = [vp, vp, vp, i32, vp, vp, i32, vp, vp, vp, i32, i32, vp]
+    lib.cc_rope_place.restype = C.c_int
     lib.cc_rope_shift.restype = C.c_int
     lib.cc_select_workspace_bytes.argtypes = [vp, i32, i32]
     lib.cc_select_workspace_bytes.restype = sz
@@ -153,6 +155,12 @@ class Context:
     # -- cc_rope_shift ---------------------------------------------------------------------
     def rope_shift(self, k_src, v_src, k_dst, v_dst, src_tab, dst_tab, descs, n_instances, max_tokens):
         self._check(self._lib.cc_rope_shift(
+            self._h, _ptr(k_src), _ptr(v_src), k_src.shape[0], _ptr(k_dst), _ptr(v_dst), k_dst.shape[0],
+            _ptr(src_tab), _ptr(dst_tab), _ptr(descs), n_instances, max_tokens, _stream()))
+
+    def rope_place(self, k_src, v_src, k_dst, v_dst, src_tab, dst_tab, descs, n_instances, max_tokens):
+        """cc_rope_shift for a store of unrotated keys: descs' delta_pos is the new position of token 0."""
+        self._check(self._lib.cc_rope_place(
             self._h, _ptr(k_src), _ptr(v_src), k_src.shape[0], _ptr(k_dst), _ptr(v_dst), k_dst.shape[0],
             _ptr(src_tab), _ptr(dst_tab), _ptr(descs), n_instances, max_tokens, _stream()))
 

@@ -77,12 +77,10 @@ int cc_set_impl(cc_ctx* ctx, int impl) {
   return CC_OK;
 }
 
-int cc_rope_shift(cc_ctx* ctx, const void* k_src_pool, const void* v_src_pool, int32_t n_src_blocks,
-                  void* k_dst_pool, void* v_dst_pool, int32_t n_dst_blocks,
-                  const int32_t* src_block_tab, const int32_t* dst_block_tab,
-                  const cc_shift_desc* descs, int32_t n_instances, int32_t max_tokens,
-                  void* stream) {
-  static const char* fn = "cc_rope_shift";
+static int rope_move(cc_ctx* ctx, const char* fn, bool absolute, const void* k_src_pool,
+                     const void* v_src_pool, int32_t n_src_blocks, void* k_dst_pool, void* v_dst_pool,
+                     int32_t n_dst_blocks, const int32_t* src_block_tab, const int32_t* dst_block_tab,
+                     const cc_shift_desc* descs, int32_t n_instances, int32_t max_tokens, void* stream) {
   if (ctx == nullptr) return CC_ERR_INVALID_ARG;
   CC_REQUIRE(n_instances >= 0 && max_tokens >= 0, "negative count");
   CC_REQUIRE(n_instances <= 65535, "more than 65535 chunk instances in one call");
@@ -94,8 +92,26 @@ int cc_rope_shift(cc_ctx* ctx, const void* k_src_pool, const void* v_src_pool, i
   CC_REQUIRE(n_src_blocks > 0 && n_dst_blocks > 0, "pool sizes must be positive");
   cc::launch_rope_shift(ctx, k_src_pool, v_src_pool, n_src_blocks, k_dst_pool, v_dst_pool,
                         n_dst_blocks, src_block_tab, dst_block_tab, descs, n_instances, max_tokens,
-                        static_cast<hipStream_t>(stream));
+                        absolute, static_cast<hipStream_t>(stream));
   return cc::check_launch(ctx, fn);
+}
+
+int cc_rope_shift(cc_ctx* ctx, const void* k_src_pool, const void* v_src_pool, int32_t n_src_blocks,
+                  void* k_dst_pool, void* v_dst_pool, int32_t n_dst_blocks,
+                  const int32_t* src_block_tab, const int32_t* dst_block_tab,
+                  const cc_shift_desc* descs, int32_t n_instances, int32_t max_tokens,
+                  void* stream) {
+  return rope_move(ctx, "cc_rope_shift", false, k_src_pool, v_src_pool, n_src_blocks, k_dst_pool, v_dst_pool,
+                   n_dst_blocks, src_block_tab, dst_block_tab, descs, n_instances, max_tokens, stream);
+}
+
+int cc_rope_place(cc_ctx* ctx, const void* k_src_pool, const void* v_src_pool, int32_t n_src_blocks,
+                  void* k_dst_pool, void* v_dst_pool, int32_t n_dst_blocks,
+                  const int32_t* src_block_tab, const int32_t* dst_block_tab,
+                  const cc_shift_desc* descs, int32_t n_instances, int32_t max_tokens,
+                  void* stream) {
+  return rope_move(ctx, "cc_rope_place", true, k_src_pool, v_src_pool, n_src_blocks, k_dst_pool, v_dst_pool,
+                   n_dst_blocks, src_block_tab, dst_block_tab, descs, n_instances, max_tokens, stream);
 }
 
 // upper bound on the number of 64-key tiles of n_tok tokens spread over n_segs segments

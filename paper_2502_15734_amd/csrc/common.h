@@ -38,7 +38,7 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 void launch_rope_shift(const cc_ctx* ctx, const void* k_src, const void* v_src, int n_src_blocks,
                        void* k_dst, void* v_dst, int n_dst_blocks, const int32_t* src_tab,
                        const int32_t* dst_tab, const cc_shift_desc* descs, int n_instances,
-                       int max_tokens, hipStream_t stream);
+                       int max_tokens, bool absolute, hipStream_t stream);
 
 void launch_gather_rows(const void* src, int n_src_rows, const int32_t* row_idx, int n_rows,
                         size_t row_bytes, void* dst, hipStream_t stream);

@@ -3,7 +3,10 @@
 // HBM-bound streaming kernel.  One workgroup moves one 16-token block of one chunk instance for
 // all KV heads: in both pools a block is one contiguous run of Hkv*16*d elements, so every
 // wavefront reads and writes whole contiguous kilobytes with 16-byte accesses per lane.  A lane
-// owns the same group of rotation pairs for the whole block, so it evaluates its cos/sin once.
+// owns the same group of rotation pairs AND the same token slot for the whole block (its rows are
+// 32 apart: two heads further, same slot), so it evaluates its cos/sin once - also in the mode
+// where the store holds keys without any rotation and every token is turned by its own absolute
+// position (ABSOLUTE: angle (delta_pos + t) f instead of delta_pos f).
 #include "device_util.h"
 
 namespace cc {
@@ -12,7 +15,7 @@ template <typename T> struct Vec16;   // 16 bytes of T
 template <> struct Vec16<float> { static constexpr int N = 4; };
 template <> struct Vec16<bf16_t> { static constexpr int N = 8; };
 
-template <typename T, int D>
+template <typename T, int D, bool ABSOLUTE>
 __global__ __launch_bounds__(256) void rope_shift_kernel(
     const T* __restrict__ k_src, const T* __restrict__ v_src, int n_src_blocks,
     T* __restrict__ k_dst, T* __restrict__ v_dst, int n_dst_blocks,
@@ -21,6 +24,7 @@ __global__ __launch_bounds__(256) void rope_shift_kernel(
   constexpr int N = Vec16<T>::N;          // elements per 16-byte vector
   constexpr int UPR = (D / 2) / N;        // vector pairs per (head, token) row
   static_assert(256 % UPR == 0, "a lane must keep its pair group across iterations");
+  static_assert((256 / UPR) % kBlock == 0, "a lane must keep its token slot across iterations");
   const cc_shift_desc dsc = descs[blockIdx.y];
   const int page = blockIdx.x;
   const int n_pages = (dsc.n_tokens + kBlock - 1) / kBlock;
@@ -35,9 +39,11 @@ __global__ __launch_bounds__(256) void rope_shift_kernel(
 
   const int tid = threadIdx.x;
   const int c = tid % UPR;                // pair group: pairs c*N .. c*N+N-1
+  // token of this lane's rows within the instance (fixed: rows advance by a multiple of 16)
+  const int turn = ABSOLUTE ? dsc.delta_pos + page * kBlock + (tid / UPR) % kBlock : dsc.delta_pos;
   float cs[N], sn[N];
 #pragma unroll
-  for (int j = 0; j < N; ++j) rot_cos_sin(dsc.delta_pos, inv_freq.f[c * N + j], &cs[j], &sn[j]);
+  for (int j = 0; j < N; ++j) rot_cos_sin(turn, inv_freq.f[c * N + j], &cs[j], &sn[j]);
 
   const int rows = hkv * kBlock;          // (head, slot) rows of the block
   for (int row = tid / UPR; row < rows; row += 256 / UPR) {
@@ -66,13 +72,13 @@ __global__ __launch_bounds__(256) void rope_shift_kernel(
   }
 }
 
-template <typename T, int D>
+template <typename T, int D, bool ABSOLUTE>
 static void launch_t(const cc_ctx* ctx, const void* k_src, const void* v_src, int n_src_blocks,
                      void* k_dst, void* v_dst, int n_dst_blocks, const int32_t* src_tab,
                      const int32_t* dst_tab, const cc_shift_desc* descs, int n_instances,
                      int max_tokens, hipStream_t stream) {
   dim3 grid((max_tokens + kBlock - 1) / kBlock, n_instances);
-  hipLaunchKernelGGL((rope_shift_kernel<T, D>), grid, dim3(256), 0, stream,
+  hipLaunchKernelGGL((rope_shift_kernel<T, D, ABSOLUTE>), grid, dim3(256), 0, stream,
                      static_cast<const T*>(k_src), static_cast<const T*>(v_src), n_src_blocks,
                      static_cast<T*>(k_dst), static_cast<T*>(v_dst), n_dst_blocks, src_tab, dst_tab,
                      descs, ctx->cfg.n_kv_heads, ctx->inv_freq);
@@ -81,14 +87,21 @@ static void launch_t(const cc_ctx* ctx, const void* k_src, const void* v_src, in
 void launch_rope_shift(const cc_ctx* ctx, const void* k_src, const void* v_src, int n_src_blocks,
                        void* k_dst, void* v_dst, int n_dst_blocks, const int32_t* src_tab,
                        const int32_t* dst_tab, const cc_shift_desc* descs, int n_instances,
-                       int max_tokens, hipStream_t stream) {
+                       int max_tokens, bool absolute, hipStream_t stream) {
   const bool bf = ctx->cfg.dtype == CC_BF16;
   const int d = ctx->cfg.head_dim;
 #define CC_ARGS ctx, k_src, v_src, n_src_blocks, k_dst, v_dst, n_dst_blocks, src_tab, dst_tab, descs, n_instances, max_tokens, stream
-  if (bf && d == 128) launch_t<bf16_t, 128>(CC_ARGS);
-  else if (bf && d == 64) launch_t<bf16_t, 64>(CC_ARGS);
-  else if (!bf && d == 128) launch_t<float, 128>(CC_ARGS);
-  else launch_t<float, 64>(CC_ARGS);
+  if (absolute) {
+    if (bf && d == 128) launch_t<bf16_t, 128, true>(CC_ARGS);
+    else if (bf && d == 64) launch_t<bf16_t, 64, true>(CC_ARGS);
+    else if (!bf && d == 128) launch_t<float, 128, true>(CC_ARGS);
+    else launch_t<float, 64, true>(CC_ARGS);
+  } else {
+    if (bf && d == 128) launch_t<bf16_t, 128, false>(CC_ARGS);
+    else if (bf && d == 64) launch_t<bf16_t, 64, false>(CC_ARGS);
+    else if (!bf && d == 128) launch_t<float, 128, false>(CC_ARGS);
+    else launch_t<float, 64, false>(CC_ARGS);
+  }
 #undef CC_ARGS
 }
 

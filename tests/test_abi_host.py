@@ -26,7 +26,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert {"cc_rope_shift", "cc_select", "cc_select_from_scores", "cc_sparse_prefill", "cc_gather_rows",
+    assert {"cc_rope_shift", "cc_rope_place", "cc_select", "cc_select_from_scores", "cc_sparse_prefill", "cc_gather_rows",
             "cc_qkv_project", "cc_create", "cc_destroy", "cc_question_mass", "cc_question_mass_workspace_bytes",
             "cc_focus_create", "cc_focus_update", "cc_focus_destroy", "cc_focus_layer", "cc_chunk_attention",
             "cc_chunk_attention_workspace_bytes", "cc_chunk_ab", "cc_chunk_cci", "cc_chunk_reuse"} <= set(names)
@@ -67,6 +67,8 @@ def test_calls_reject_bad_arguments_before_launch(lib):
     assert lib.cc_rope_shift(h, good, good, 4, good, None, 4, good, good, good, 1, 16, None) == -1
     assert lib.cc_rope_shift(h, good, None, 4, good, None, 4, good, good, good, -1, 16, None) == -1
     assert lib.cc_rope_shift(h, good, None, 4, good, None, 4, good, good, good, 0, 16, None) == 0   # empty batch
+    assert lib.cc_rope_place(h, None, None, 4, good, None, 4, good, good, good, 1, 16, None) == -1
+    assert lib.cc_rope_place(h, good, None, 4, good, None, 4, good, good, good, 0, 16, None) == 0
     # cc_select: workspace too small / missing
     need = lib.cc_select_workspace_bytes(h, 100, 3)
     assert need >= 100 * 8 * 4

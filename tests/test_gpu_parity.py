@@ -202,6 +202,37 @@ def test_zero_shift_is_bit_exact():
             assert np.array_equal(O.read_v_pages(vp, dst, n), O.read_v_pages(w.v_store, src, n))
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128)])
+def test_place_keys_stored_without_rotation(dtype, d):
+    # the store read as unrotated keys: every token is turned by its own new position
+    from paper_2502_15734_amd.pipeline import DeviceBatch
+    reqs = [W.RequestSpec([0, 1, 2, 3], [0.3, 0.2, 0.25, 0.1], 21), W.RequestSpec([3, 0, 4], [0.5, 0.15, 0.35], 40)]
+    w = W.custom("place", dtype, 8, 2, d, 5.0e5, [100, 77, 130, 64, 201], [0, 5, 0, 17, 3], reqs,
+                 1.0 / math.sqrt(d), seed=300 + d)
+    b = DeviceBatch(w, poison=True)
+    start_of = {int(sg[W.SEG_TAB]): int(sg[W.SEG_START]) for sg in w.segments if sg[W.SEG_KIND] == W.KIND_CHUNK}
+    descs = w.shift_descs.copy()
+    for dsc in descs:
+        dsc[W.SHIFT_DELTA] = start_of[int(dsc[W.SHIFT_DST_TAB])]
+    descs_dev = torch.from_numpy(np.ascontiguousarray(descs)).to("cuda")
+    b.ctx.rope_place(b.k_store, b.v_store, b.k_req, b.v_req, b.store_tab, b.req_tab, descs_dev,
+                     b.n_instances, b.max_shift_tokens)
+    torch.cuda.synchronize()
+    kp, vp = _pools(b)
+    num = den = 0.0
+    for dsc in descs:
+        n, start = int(dsc[W.SHIFT_NTOK]), int(dsc[W.SHIFT_DELTA])
+        src = w.store_tab[dsc[W.SHIFT_SRC_TAB]: dsc[W.SHIFT_SRC_TAB] + (n + 15) // 16]
+        dst = w.req_tab[dsc[W.SHIFT_DST_TAB]: dsc[W.SHIFT_DST_TAB] + (n + 15) // 16]
+        ref = O.place_keys(O.read_k_pages(w.k_store, src, n).astype(np.float64), start, w.spec.rope_theta)
+        got = O.read_k_pages(kp, dst, n)
+        num += ((got - ref) ** 2).sum(); den += (ref ** 2).sum()
+        assert np.array_equal(O.read_v_pages(vp, dst, n), O.read_v_pages(w.v_store, src, n))
+    assert math.sqrt(num / den) <= H.TOL[dtype], f"placed K rel L2 {math.sqrt(num / den):.3e}"
+    # padding slots of the destination pages are never written (they still hold the poison)
+    assert np.isnan(kp).any()
+
+
 @pytest.mark.parametrize("impl", ["auto", "wide"])
 def test_config2_llama3_8b_layer_full(impl):
     check_workload(W.config(2), _impls()[impl])

@@ -94,6 +94,19 @@ def test_shift_composes_and_inverts():
     assert np.array_equal(O.shift_keys(k, 0, 5.0e5), k)             # zero shift is bit-exact
 
 
+def test_place_unrotated_keys_is_the_rotation_at_absolute_positions():
+    rng = np.random.default_rng(21)
+    k = rng.standard_normal((37, 2, 16))
+    for start in (0, 5, 1000):
+        got = O.place_keys(k, start, 1.0e4)
+        np.testing.assert_allclose(got, rope_complex(k, start + np.arange(37), 1.0e4), atol=1e-12)
+    # a store rotated at cached positions c + t and shifted by new - c lands where the unrotated store is placed
+    cached = O.place_keys(k, 40, 1.0e4)
+    np.testing.assert_allclose(O.shift_keys(cached, 123 - 40, 1.0e4), O.place_keys(k, 123, 1.0e4), atol=1e-11)
+    # position 0 of an unrotated key is the key itself
+    np.testing.assert_array_equal(O.place_keys(k, 0, 1.0e4)[0], k[0])
+
+
 def test_shift_preserves_pair_norms():
     rng = np.random.default_rng(2)
     k = rng.standard_normal((5, 2, 64))
