@@ -16,6 +16,8 @@
  *                      (Eq. (1), Sec. 3.4.3, Sec. 4 "Selective Token Recomputation")
  *   cc_question_mass   attention the question pays to every chunk in that layer, inter(C_i, U)
  *                      (Sec. 3.2.2); cc_focus_* turns it into the set of focused chunks (Algorithm 1)
+ *   cc_preloader_*     layer-wise preloading of chunk-caches from host memory on a copy stream
+ *                      (Sec. 3.4.2, Algorithm 2)
  *   cc_chunk_attention inter / intra attention sums between the segments of a prompt (Eq. (2), (3));
  *                      cc_chunk_ab / cc_chunk_cci / cc_chunk_reuse: CCI, beta, gamma, beta', CFO and
  *                      the token budget from them on the host (Sec. 3.1, 3.3)
@@ -298,6 +300,34 @@ int cc_chunk_cci(const double* a, const double* b, int32_t n_layers, double* cci
 int cc_chunk_reuse(const int64_t* old_prefix, const double* old_inter, int32_t n_old,
                    const int64_t* new_prefix, int32_t n_new, double cci, double alpha,
                    int32_t chunk_len, cc_reuse* out);
+
+/* ---- layer-wise preloading of chunk-caches (Sec. 3.4.2, Eq. (12), Algorithm 2) ---------------
+ * Host-side runtime: copies each layer's chunk-caches from PINNED HOST memory into a device read
+ * buffer on a copy stream of the library's own (default priority), ahead of the compute stream.
+ *   cc_preload_depth: L_p = max(1, ceil((L - 1) (1 - T_prefill / T_load) + 1)), at most L; 1 when
+ *     T_prefill >= T_load (times in any common unit).  Negative on invalid arguments.
+ *   cc_preloader_create: L layers, preloading depth L_p, and a ring of n_slots >= min(L_p + 1, L)
+ *     slots in the caller's device read buffer: layer j is expected in slot j mod n_slots, and its
+ *     copy waits (on the GPU) until layer j - n_slots has been released.
+ *   cc_preloader_set_layer: where layer j comes from (pinned host pointer), where it goes (device
+ *     pointer: the caller's slot for it) and how many bytes; before the layer's copy is enqueued.
+ *   cc_preloader_acquire(layer, compute_stream): Algorithm 2's inner loop - enqueues, in layer
+ *     order, every copy up to layer + L_p that is not enqueued yet - then makes compute_stream wait
+ *     (hipStreamWaitEvent; the host does not block) until the layer's data has landed.
+ *   cc_preloader_release(layer, compute_stream): the layer's kernels have been enqueued; its slot
+ *     may be overwritten once compute_stream reaches this point.
+ *   cc_preloader_issued: number of copies enqueued so far; their layer order into order[] if given.
+ * Call acquire(i), enqueue layer i's work, release(i), for i = 0 .. L-1.  Nothing here allocates
+ * device or pinned memory; create makes one stream and 2 L events, destroy waits for the copy
+ * stream and frees them. */
+typedef struct cc_preloader cc_preloader;
+int32_t cc_preload_depth(int32_t n_layers, double t_prefill, double t_load);
+int cc_preloader_create(cc_preloader** out, int32_t n_layers, int32_t depth, int32_t n_slots);
+void cc_preloader_destroy(cc_preloader* p);
+int cc_preloader_set_layer(cc_preloader* p, int32_t layer, const void* host_src, void* dev_dst, size_t bytes);
+int cc_preloader_acquire(cc_preloader* p, int32_t layer, void* compute_stream);
+int cc_preloader_release(cc_preloader* p, int32_t layer, void* compute_stream);
+int32_t cc_preloader_issued(const cc_preloader* p, int32_t* order, int32_t capacity);
 
 /* ---- focused chunks (host only; no GPU work, HOST pointers) --------------------------------
  * Algorithm 1 for ONE request with k chunks, fed once per layer l = 1, 2, ... with that layer's

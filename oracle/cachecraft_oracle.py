@@ -438,6 +438,30 @@ def predict_focused(inter_layers: Sequence[Sequence[float]], window: int):
     return None, None, f_all
 
 
+# --------------------------------------------------------------------------
+# layer-wise preloading (Sec. 3.4.2, Eq. (12), Algorithm 2)
+# --------------------------------------------------------------------------
+def preload_depth(n_layers: int, t_prefill: float, t_load: float) -> int:
+    """L_p = max(1, (L - 1)(1 - T_prefill / T_load) + 1), taken up to the next integer (the loop of
+    Algorithm 2 needs a layer count) and at most L; 1 when loading is not slower than compute."""
+    if t_load <= 0 or t_prefill >= t_load:
+        return 1
+    lp = (n_layers - 1) * (1.0 - t_prefill / t_load) + 1.0
+    return int(max(1, min(n_layers, np.ceil(lp - 1e-9))))
+
+
+def preload_schedule(n_layers: int, depth: int):
+    """Algorithm 2 as printed: before layer i is computed, layers i .. min(i + L_p, L) are preloaded
+    (those not preloaded before).  Returns, for every layer i (0-based), the layers newly asked for
+    just before it."""
+    done, steps = set(), []
+    for i in range(n_layers):
+        new = [j for j in range(i, min(i + depth, n_layers - 1) + 1) if j not in done]
+        done.update(new)
+        steps.append(new)
+    return steps
+
+
 def qkv_project(hidden_rows: np.ndarray, w_qkv: np.ndarray, hq: int, hkv: int, d: int):
     """Q, K, V of the given token rows: X W^T with W [(Hq+2Hkv)d, hidden] (one row per output
     feature: q heads, then k heads, then v heads), split by heads (Sec. 3.4.3: computed only for

@@ -96,6 +96,20 @@ def load_library() -> C.CDLL:
     lib.cc_chunk_reuse.argtypes = [C.POINTER(C.c_int64), dp, i32, C.POINTER(C.c_int64), i32, C.c_double, C.c_double,
                                    i32, C.POINTER(_Reuse)]
     lib.cc_chunk_reuse.restype = C.c_int
+    lib.cc_preload_depth.argtypes = [i32, C.c_double, C.c_double]
+    lib.cc_preload_depth.restype = i32
+    lib.cc_preloader_create.argtypes = [C.POINTER(vp), i32, i32, i32]
+    lib.cc_preloader_create.restype = C.c_int
+    lib.cc_preloader_destroy.argtypes = [vp]
+    lib.cc_preloader_destroy.restype = None
+    lib.cc_preloader_set_layer.argtypes = [vp, i32, vp, vp, sz]
+    lib.cc_preloader_set_layer.restype = C.c_int
+    lib.cc_preloader_acquire.argtypes = [vp, i32, vp]
+    lib.cc_preloader_acquire.restype = C.c_int
+    lib.cc_preloader_release.argtypes = [vp, i32, vp]
+    lib.cc_preloader_release.restype = C.c_int
+    lib.cc_preloader_issued.argtypes = [vp, C.POINTER(i32), i32]
+    lib.cc_preloader_issued.restype = i32
     lib.cc_focus_create.argtypes = [C.POINTER(vp), i32, i32]
     lib.cc_focus_create.restype = C.c_int
     lib.cc_focus_destroy.argtypes = [vp]
@@ -267,6 +281,55 @@ def chunk_reuse(old_prefix, old_inter, new_prefix, cci: float, alpha: float, chu
         int(chunk_len), C.byref(out)), "cc_chunk_reuse")
     return {"beta": out.beta, "gamma": out.gamma, "beta_adj": out.beta_adj, "cfo": out.cfo,
             "n_recompute": int(out.n_recompute)}
+
+
+def preload_depth(n_layers: int, t_prefill: float, t_load: float) -> int:
+    """L_p of Eq. (12) / Algorithm 2, line 1."""
+    d = int(load_library().cc_preload_depth(n_layers, float(t_prefill), float(t_load)))
+    if d < 0:
+        raise CacheCraftError(d, "cc_preload_depth")
+    return d
+
+
+class Preloader:
+    """Layer-wise preloading (Algorithm 2): pinned host tensors -> slots of a device read buffer."""
+
+    def __init__(self, n_layers: int, depth: int, n_slots: int):
+        self._lib = load_library()
+        h = C.c_void_p()
+        _host_status(self._lib.cc_preloader_create(C.byref(h), n_layers, depth, n_slots), "cc_preloader_create")
+        self._h, self.n_layers = h, n_layers
+        self._keep = []
+
+    def set_layer(self, layer: int, host_src: torch.Tensor, dev_dst: torch.Tensor):
+        assert host_src.is_pinned() and dev_dst.is_cuda and host_src.is_contiguous() and dev_dst.is_contiguous()
+        nbytes = host_src.numel() * host_src.element_size()
+        assert nbytes <= dev_dst.numel() * dev_dst.element_size()
+        self._keep.append((host_src, dev_dst))
+        _host_status(self._lib.cc_preloader_set_layer(self._h, layer, host_src.data_ptr(), dev_dst.data_ptr(), nbytes),
+                     "cc_preloader_set_layer")
+
+    def acquire(self, layer: int):
+        _host_status(self._lib.cc_preloader_acquire(self._h, layer, _stream()), "cc_preloader_acquire")
+
+    def release(self, layer: int):
+        _host_status(self._lib.cc_preloader_release(self._h, layer, _stream()), "cc_preloader_release")
+
+    def issued(self):
+        buf = (C.c_int32 * self.n_layers)()
+        n = self._lib.cc_preloader_issued(self._h, buf, self.n_layers)
+        return [int(buf[i]) for i in range(n)]
+
+    def close(self):
+        if self._h:
+            self._lib.cc_preloader_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 class FocusTracker:

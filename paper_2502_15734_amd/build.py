@@ -12,7 +12,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libcachecraft.so")
-SOURCES = ["api.hip", "rope_shift.hip", "select.hip", "prefill.hip", "mfma_kernels.hip", "attn_mfma2.hip", "score_mfma2.hip", "project.hip", "focus.hip"]
+SOURCES = ["api.hip", "rope_shift.hip", "select.hip", "prefill.hip", "mfma_kernels.hip", "attn_mfma2.hip", "score_mfma2.hip", "project.hip", "focus.hip", "preload.hip"]
 # packed fp32 VALU forms are disabled on purpose (device pass only; the host pass warns and ignores it)
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -29,7 +29,9 @@ def test_every_declared_symbol_is_exported(lib):
     assert {"cc_rope_shift", "cc_rope_place", "cc_select", "cc_select_from_scores", "cc_sparse_prefill", "cc_gather_rows",
             "cc_qkv_project", "cc_create", "cc_destroy", "cc_question_mass", "cc_question_mass_workspace_bytes",
             "cc_focus_create", "cc_focus_update", "cc_focus_destroy", "cc_focus_layer", "cc_chunk_attention",
-            "cc_chunk_attention_workspace_bytes", "cc_chunk_ab", "cc_chunk_cci", "cc_chunk_reuse"} <= set(names)
+            "cc_chunk_attention_workspace_bytes", "cc_chunk_ab", "cc_chunk_cci", "cc_chunk_reuse", "cc_preload_depth",
+            "cc_preloader_create", "cc_preloader_set_layer", "cc_preloader_acquire", "cc_preloader_release",
+            "cc_preloader_issued", "cc_preloader_destroy"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in cc.h but not exported"
 
@@ -201,6 +203,20 @@ def test_reuse_scores_follow_the_oracle():
         P.chunk_reuse([1], [-0.5], [1], 0.5, 1.0, 10)
     with pytest.raises(P.CacheCraftError):
         P.chunk_ab([1.0], [0], 1.0, 10)
+
+
+def test_preload_depth_follows_the_oracle():
+    import numpy as np
+    import paper_2502_15734_amd as P
+    from oracle import cachecraft_oracle as O
+    assert P.preload_depth(5, 1.0, 2.0) == 3
+    rng = np.random.default_rng(12)
+    for _ in range(300):
+        L = int(rng.integers(1, 129)); tp = float(rng.uniform(0.0, 4.0)); tl = float(rng.uniform(0.0, 4.0))
+        assert P.preload_depth(L, tp, tl) == O.preload_depth(L, tp, tl)
+    for bad in ((0, 1.0, 1.0), (4, -1.0, 1.0), (4, 1.0, float("nan"))):
+        with pytest.raises(P.CacheCraftError):
+            P.preload_depth(*bad)
 
 
 def test_product_path_does_not_import_the_oracle():

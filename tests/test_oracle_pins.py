@@ -551,3 +551,31 @@ def test_prefix_overlap_cci_and_cfo_by_hand():
     assert O.cache_fix_overhead(0.7, 1.0, 0.0, 1.0, 100)[1:] == (0.0, 0)            # same prefix, same order
     assert O.cache_fix_overhead(0.9, 0.0, 0.0, 2.0, 64)[1:] == (1.0, 64)            # clipped: recompute everything
     assert O.cache_fix_overhead(0.5, 0.86, 0.0, 1.0, 100)[2] == 7                   # 0.07 * 100: no spurious ceiling
+
+
+# ----------------------------------------------------------------------------- layer-wise preloading (Algorithm 2)
+def test_preload_depth_formula():
+    # the paper's own example: 5 layers, prefill : load = 1 : 2 -> three layers ahead
+    assert O.preload_depth(5, 1.0, 2.0) == 3
+    assert O.preload_depth(5, 2.0, 2.0) == 1 and O.preload_depth(5, 3.0, 2.0) == 1 and O.preload_depth(7, 1.0, 0.0) == 1
+    # what the formula is for: the other L - L_p layers must load within the compute time of L - 1 layers;
+    # L_p is the smallest count that achieves it (brute force over all counts)
+    rng = np.random.default_rng(4)
+    for _ in range(200):
+        L = int(rng.integers(1, 81)); tp = float(rng.uniform(0.1, 5.0)); tl = float(rng.uniform(0.1, 5.0))
+        fits = [lp for lp in range(1, L + 1) if (L - lp) * (tl / L) <= (L - 1) * (tp / L) + 1e-12]
+        assert O.preload_depth(L, tp, tl) == min(fits)
+
+
+def test_preload_schedule_is_algorithm_2():
+    # written out for 5 layers, depth 3 (0-based): before layer 0 -> 0..3, before 1 -> 4, then nothing new
+    assert O.preload_schedule(5, 3) == [[0, 1, 2, 3], [4], [], [], []]
+    assert O.preload_schedule(4, 1) == [[0, 1], [2], [3], []]
+    for L in range(1, 12):
+        for depth in range(1, L + 2):
+            steps = O.preload_schedule(L, depth)
+            flat = [j for s in steps for j in s]
+            assert flat == list(range(L))                               # every layer once, in order
+            for i, s in enumerate(steps):
+                assert all(i <= j <= min(i + depth, L - 1) for j in s)   # never further than L_p ahead
+                assert i in [j for t in steps[: i + 1] for j in t]       # a layer is asked for before it is computed
