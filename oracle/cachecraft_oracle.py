@@ -26,7 +26,7 @@ S = C_1 .. C_k U (Sec. 2.2):
 
 Readings taken where the paper leaves a choice (each is a reading, not a fact
 of the paper): rotate-half pairing (x = first half of the head, y = second
-half; "upper and lower 64-dimensional components", Sec. 4); frequencies
+half: Sec. 4 names the two halves of a head as the rotated components); frequencies
 theta^(-2i/d); logits scaled by 1/sqrt(d) and masked entries excluded from the
 softmax; queries of the later chunk attend keys of the earlier chunk; the
 softmax denominator runs over every key up to and including the token itself;
