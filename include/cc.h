@@ -14,6 +14,8 @@
  *   cc_sparse_prefill  causal attention of the chosen tokens + question over the whole merged
  *                      paged KV, after writing their recomputed K, V into it
  *                      (Eq. (1), Sec. 3.4.3, Sec. 4 "Selective Token Recomputation")
+ *   cc_scatter_kv      the write half of cc_sparse_prefill alone: K, V of chunks without a cache
+ *                      (Sec. 3.4.1) go into the request's pages before the others are scored
  *   cc_question_mass   attention the question pays to every chunk in that layer, inter(C_i, U)
  *                      (Sec. 3.2.2); cc_focus_* turns it into the set of focused chunks (Algorithm 1)
  *   cc_preloader_*     layer-wise preloading of chunk-caches from host memory on a copy stream
@@ -217,6 +219,17 @@ int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void*
                       const cc_segment* segs, int32_t n_segs,
                       const int32_t* req_seg_off, int32_t n_requests, int32_t n_ctx_tokens,
                       void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- (c') step 1 of cc_sparse_prefill alone --------------------------------------------------
+ * Rotates k_new[j] to position q_pos[j] and writes it, with v_new[j], into physical slot
+ * slot_map[j] of the pools, for j < n_rows; nothing else.  For chunks that have NO chunk-cache
+ * in a batch that also reuses caches (C_miss next to C_hit, Sec. 3.4.1): their K and V are
+ * computed for every token and must be in the request's pages before cc_select scores the chunks
+ * behind them.  Rows whose slots lie in the same 16-token block must be adjacent, as for
+ * cc_sparse_prefill.  k_new, v_new [n_rows][Hkv][d]. */
+int cc_scatter_kv(cc_ctx* ctx, const void* k_new, const void* v_new, const int32_t* q_pos,
+                  const int32_t* slot_map, int32_t n_rows, void* k_pool, void* v_pool, int32_t n_blocks,
+                  void* stream);
 
 /* ---- (d) attention between the question and every chunk -----------------------------------
  * inter(C_i, U) of this layer (Sec. 3.2.2, with the weights of Eq. (1)): for every segment s of

@@ -207,8 +207,12 @@ def _segments_of(w, r):
     return [tuple(int(v) for v in w.segments[i]) for i in range(s0, s1)]
 
 
-def shifted_context(w, r: int):
-    """Steps gather + shift for request r: logical K (shifted), V, context length."""
+def shifted_context(w, r: int, miss_segments: Sequence[int] = ()):
+    """Steps gather + shift for request r: logical K (shifted), V, context length.
+
+    miss_segments: indices (within the request) of chunks that have no chunk-cache (C_miss,
+    Sec. 3.4.1): their K and V are the freshly computed ones of all their tokens (K rotated to
+    the new positions), present before anything is scored."""
     theta = w.spec.rope_theta
     segs = _segments_of(w, r)
     n_ctx = segs[-1][2] + segs[-1][3] if segs else 0
@@ -216,8 +220,13 @@ def shifted_context(w, r: int):
     k = np.zeros((n_ctx, hkv, d), dtype=np.float64)
     v = np.zeros((n_ctx, hkv, d), dtype=np.float64)
     by_dst = {int(dsc[1]): dsc for dsc in w.shift_descs}
-    for (_, kind, start, n, tab, _, _, _) in segs:
+    for si, (_, kind, start, n, tab, _, tok, _) in enumerate(segs):
         if kind != 0:
+            continue
+        if si in miss_segments:
+            pos = start + np.arange(n, dtype=np.int64)
+            k[start:start + n] = rotate(np.asarray(w.k_new[tok:tok + n], dtype=np.float64), pos, theta)
+            v[start:start + n] = np.asarray(w.v_new[tok:tok + n], dtype=np.float64)
             continue
         src_tab, _, n_tok, delta = (int(x) for x in by_dst[tab])
         assert n_tok == n
@@ -277,8 +286,8 @@ def fix_and_attend(w, r: int, k_shifted, v_cached, selected, k_new=None, v_new=N
 
 
 def run_request(w, r: int, selected_override: Optional[Sequence[np.ndarray]] = None,
-                k_new=None, v_new=None, q=None) -> RequestResult:
-    k_sh, v_c, _ = shifted_context(w, r)
+                k_new=None, v_new=None, q=None, miss_segments: Sequence[int] = ()) -> RequestResult:
+    k_sh, v_c, _ = shifted_context(w, r, miss_segments)
     scores = score_request(w, r, k_sh)
     chunk_segs = [s for s in _segments_of(w, r) if s[1] == 0]
     selected = [top_n(sc, seg[5]) for sc, seg in zip(scores, chunk_segs)]

@@ -251,6 +251,22 @@ int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void*
   return cc::check_launch(ctx, fn);
 }
 
+int cc_scatter_kv(cc_ctx* ctx, const void* k_new, const void* v_new, const int32_t* q_pos,
+                  const int32_t* slot_map, int32_t n_rows, void* k_pool, void* v_pool, int32_t n_blocks,
+                  void* stream) {
+  static const char* fn = "cc_scatter_kv";
+  if (ctx == nullptr) return CC_ERR_INVALID_ARG;
+  CC_REQUIRE(n_rows >= 0, "negative count");
+  if (n_rows == 0) return CC_OK;
+  CC_REQUIRE(k_new && v_new && q_pos && slot_map && k_pool && v_pool, "null pointer");
+  CC_REQUIRE(n_blocks > 0, "sizes must be positive");
+  CC_REQUIRE(aligned16(k_new) && aligned16(v_new) && aligned16(k_pool) && aligned16(v_pool),
+             "tensors must be 16-byte aligned");
+  cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_rows, k_pool, v_pool, n_blocks,
+                          static_cast<hipStream_t>(stream));
+  return cc::check_launch(ctx, fn);
+}
+
 size_t cc_question_mass_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_tokens, int32_t n_segs,
                                         int32_t max_question_rows) {
   if (ctx == nullptr || n_ctx_tokens < 0 || n_segs < 0 || max_question_rows < 0) return 0;

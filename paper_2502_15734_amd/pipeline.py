@@ -21,7 +21,11 @@ def _dev(a: np.ndarray, dtype=None, device="cuda") -> torch.Tensor:
 
 
 class DeviceBatch:
-    def __init__(self, w, device: str = "cuda", impl: int = CC_IMPL_AUTO, poison: bool = False):
+    def __init__(self, w, device: str = "cuda", impl: int = CC_IMPL_AUTO, poison: bool = False,
+                 miss_segments=()):
+        """miss_segments: global indices of chunk segments that have NO chunk-cache in this batch: they
+        are not shifted from the store; K, V of all their tokens are written into the request's pages
+        (fill_miss) before the other chunks are scored."""
         sp = w.spec
         self.w = w
         self.device = device
@@ -41,12 +45,24 @@ class DeviceBatch:
         # metadata
         self.store_tab = _dev(w.store_tab, None, device)
         self.req_tab = _dev(w.req_tab, None, device)
-        self.shift_descs = _dev(w.shift_descs, None, device)
+        miss_tabs = {int(w.segments[s][4]) for s in miss_segments}
+        shift_descs = np.ascontiguousarray([d for d in w.shift_descs if int(d[1]) not in miss_tabs],
+                                           dtype=w.shift_descs.dtype).reshape(-1, w.shift_descs.shape[1])
+        self.shift_descs = _dev(shift_descs, None, device)
+        rows, pos, slot = [], [], []
+        for s in miss_segments:
+            _, kind, start, n, tab, _, tok, _ = (int(v) for v in w.segments[s])
+            assert kind == 0, "only chunk segments can be misses"
+            t = np.arange(n)
+            rows.append(tok + t); pos.append(start + t)
+            slot.append(w.req_tab[tab + t // 16].astype(np.int64) * 16 + t % 16)
+        cat = lambda xs: np.concatenate(xs).astype(np.int32) if xs else np.zeros(0, dtype=np.int32)
+        self.miss_rows, self.miss_pos, self.miss_slot = (_dev(cat(a), None, device) for a in (rows, pos, slot))
         self.segments = _dev(w.segments, None, device)
         self.req_seg_off = _dev(w.req_seg_off, None, device)
         self.cu_q = _dev(w.cu_q, None, device)
-        self.n_instances = int(w.shift_descs.shape[0])
-        self.max_shift_tokens = int(w.shift_descs[:, 2].max()) if self.n_instances else 0
+        self.n_instances = int(shift_descs.shape[0])
+        self.max_shift_tokens = int(shift_descs[:, 2].max()) if self.n_instances else 0
         self.max_seg_tokens = w.max_seg_tokens
         self.n_requests = w.n_requests
         self.n_tok, self.n_q_tot = w.n_tok, w.n_q_tot
@@ -84,6 +100,19 @@ class DeviceBatch:
         self.ctx.rope_shift(self.k_store, self.v_store if with_v else None, self.k_req,
                             self.v_req if with_v else None, self.store_tab, self.req_tab,
                             self.shift_descs, self.n_instances, self.max_shift_tokens)
+
+    def fill_miss(self):
+        """K, V of every token of the chunks without a cache, into the request's pages."""
+        n = int(self.miss_rows.shape[0])
+        if n == 0:
+            return
+        if not hasattr(self, "k_miss"):
+            hkv, d = self.w.spec.n_kv_heads, self.w.spec.head_dim
+            self.k_miss = torch.empty((n, hkv, d), dtype=self.dt, device=self.device)
+            self.v_miss = torch.empty((n, hkv, d), dtype=self.dt, device=self.device)
+        self.ctx.gather_rows(self.k_new, self.miss_rows, self.k_miss)
+        self.ctx.gather_rows(self.v_new, self.miss_rows, self.v_miss)
+        self.ctx.scatter_kv(self.k_miss, self.v_miss, self.miss_pos, self.miss_slot, self.k_req, self.v_req)
 
     def select(self):
         self.ctx.select(self.q, self.k_req, self.req_tab, self.segments, self.req_seg_off,
@@ -148,6 +177,7 @@ class DeviceBatch:
     def step(self):
         """One pass of the whole hot path over the batch."""
         self.rope_shift()
+        self.fill_miss()
         self.select()
         self.gather()
         self.sparse_prefill()

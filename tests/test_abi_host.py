@@ -26,7 +26,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert {"cc_rope_shift", "cc_rope_place", "cc_select", "cc_select_from_scores", "cc_sparse_prefill", "cc_gather_rows",
+    assert {"cc_rope_shift", "cc_rope_place", "cc_scatter_kv", "cc_select", "cc_select_from_scores", "cc_sparse_prefill", "cc_gather_rows",
             "cc_qkv_project", "cc_create", "cc_destroy", "cc_question_mass", "cc_question_mass_workspace_bytes",
             "cc_focus_create", "cc_focus_update", "cc_focus_destroy", "cc_focus_layer", "cc_chunk_attention",
             "cc_chunk_attention_workspace_bytes", "cc_chunk_ab", "cc_chunk_cci", "cc_chunk_reuse", "cc_preload_depth",
@@ -97,6 +97,10 @@ def test_calls_reject_bad_arguments_before_launch(lib):
     assert lib.cc_sparse_prefill(*args, good, None, good, ws, None) == -1
     args[7], args[8] = 0, 0
     assert lib.cc_sparse_prefill(*args, good, None, good, ws, None) == 0
+    # cc_scatter_kv: null pool, misaligned rows, nothing to do
+    assert lib.cc_scatter_kv(h, good, good, good, good, 4, None, good, 8, None) == -1
+    assert lib.cc_scatter_kv(h, odd, good, good, good, 4, good, good, 8, None) == -1
+    assert lib.cc_scatter_kv(h, good, good, good, good, 0, good, good, 8, None) == 0
     # cc_question_mass: missing lse, workspace too small, max_question_rows > n_q_tot, no segments
     wm = lib.cc_question_mass_workspace_bytes(h, 100, 3, 8)
     assert wm >= 3 * 8 * 8 * 4

@@ -202,6 +202,36 @@ def test_zero_shift_is_bit_exact():
             assert np.array_equal(O.read_v_pages(vp, dst, n), O.read_v_pages(w.v_store, src, n))
 
 
+@pytest.mark.parametrize("impl", ["auto", "wide", "scalar"])
+def test_chunks_without_a_cache_next_to_reused_ones(impl):
+    # request 0: its second chunk has no chunk-cache (never shifted from the store; its destination
+    # pages keep their poison until cc_scatter_kv writes all its tokens); request 1 reuses everything
+    from paper_2502_15734_amd.pipeline import DeviceBatch
+    reqs = [W.RequestSpec([0, 1, 2, 3], [0.3, 1.0, 0.25, 0.1], 21), W.RequestSpec([3, 0, 4], [0.5, 0.15, 0.35], 40)]
+    w = W.custom("miss", "bf16", 8, 2, 128, 5.0e5, [100, 77, 130, 64, 201], [0, 5, 0, 17, 3], reqs,
+                 1.0 / math.sqrt(128), seed=77)
+    miss_local, miss_global = 1, int(w.req_seg_off[0]) + 1
+    b = DeviceBatch(w, impl=_impls()[impl], poison=True, miss_segments=[miss_global])
+    assert b.n_instances == len(w.shift_descs) - 1
+    b.step(); torch.cuda.synchronize()
+    gsel = H.gpu_selection(w, b.sel_idx.cpu().numpy())
+    tol = H.TOL["bf16"]
+    out = b.out.float().cpu().numpy(); lse = b.lse.cpu().numpy()
+    kp, vp = _pools(b)
+    for r in range(w.n_requests):
+        miss = [miss_local] if r == 0 else []
+        ref = O.run_request(w, r, miss_segments=miss)
+        H.assert_selection_matches(w, r, gsel[r], ref.scores, ref.selected)
+        if not all(np.array_equal(a, o) for a, o in zip(gsel[r], ref.selected)):
+            ref = O.run_request(w, r, selected_override=gsel[r], miss_segments=miss)
+        q0, q1 = int(w.cu_q[r]), int(w.cu_q[r + 1])
+        assert H.rel_l2(out[q0:q1], ref.out) <= tol
+        assert np.abs(lse[q0:q1] - ref.lse).max() <= 2e-3
+        k, v = H.request_context_from_pools(w, r, kp, vp)
+        assert H.rel_l2(k, ref.k_ctx) <= tol and H.rel_l2(v, ref.v_ctx) <= tol
+    assert np.array_equal(gsel[0][miss_local], np.arange(77))
+
+
 @pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128)])
 def test_place_keys_stored_without_rotation(dtype, d):
     # the store read as unrotated keys: every token is turned by its own new position

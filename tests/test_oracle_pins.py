@@ -579,3 +579,25 @@ def test_preload_schedule_is_algorithm_2():
             for i, s in enumerate(steps):
                 assert all(i <= j <= min(i + depth, L - 1) for j in s)   # never further than L_p ahead
                 assert i in [j for t in steps[: i + 1] for j in t]       # a layer is asked for before it is computed
+
+
+# ----------------------------------------------------------------------------- chunks without a cache next to reused ones
+def test_miss_chunk_equals_a_cache_that_already_holds_its_fresh_keys():
+    # A chunk with no chunk-cache (every token computed afresh) must give what a reused cache gives
+    # when that cache happens to hold exactly the fresh K (rotated at its cached positions) and V.
+    w = small_workload(lens=(20, 33, 16), question=5, fracs=(0.25, 1.0, 0.25), offsets=(0, 7, 0), dtype="f32")
+    miss = 1                                                          # the middle chunk of the request
+    ref = O.run_request(w, 0, miss_segments=[miss])
+    seg = [int(v) for v in w.segments[miss]]
+    start, n, tok = seg[2], seg[3], seg[6]
+    chunk = w.spec.requests[0].chunks[miss]
+    cached = rope_complex(w.k_new[tok:tok + n].astype(np.float64), 7 + np.arange(n), 1.0e4)
+    blocks = w.store_tab[w.store_tab_off[chunk]: w.store_tab_off[chunk + 1]]
+    for t in range(n):                                                # write the store pages (layouts of Sec. 4 paging)
+        w.k_store[blocks[t // 16], :, t % 16, :] = cached[t]
+        w.v_store[blocks[t // 16], :, :, t % 16] = w.v_new[tok + t]
+    hit = O.run_request(w, 0)
+    np.testing.assert_allclose(ref.k_shifted, hit.k_shifted, atol=2e-6)
+    np.testing.assert_allclose(ref.out, hit.out, atol=2e-5)
+    assert all(np.array_equal(a, b) for a, b in zip(ref.selected, hit.selected))
+    assert np.array_equal(ref.selected[miss], np.arange(n))            # a miss recomputes every token
