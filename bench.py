@@ -166,6 +166,17 @@ def time_layerwise_preload(batch, step_ms: float, n_layers: int = 6) -> dict:
             "step_ms": step_ms, "serial_ms": serial_ms, "pipelined_ms": pipelined_ms}
 
 
+def time_layer_loop(w, n_layers: int = 4, window: int = 2) -> dict:
+    """The loop over layers with Algorithm 1 deciding the focused chunks (identical synthetic layers, so
+    every request settles at layer `window`): rows recomputed and time per layer before and after."""
+    from paper_2502_15734_amd.layers import LayerLoop
+    loop = LayerLoop(w, n_layers, window, preload=False)
+    recs = loop.run()
+    loop.close()
+    return {"window": window, "layers": [{"layer": r["layer"], "rows": r["rows"], "ms": r["ms"]} for r in recs],
+            "requests_settled": sum(1 for s in recs[-1]["stop_layer"] if s is not None)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -245,6 +256,7 @@ def main():
     torch.cuda.synchronize()
     chunk_attention_ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(n_ca)]))
     preload = time_layerwise_preload(batch, ms_per_step)
+    layer_loop = time_layer_loop(w)
     q_pos = batch.q_pos.cpu().numpy()[: w.n_q_tot]
     attn_flops = attention_flops(w, q_pos)
     proj_flops = 0.0
@@ -300,7 +312,7 @@ def main():
         "extra_calls": {"cc_select_from_scores": {"ms": from_scores_ms, "chunk_tokens": work["n_chunk_tok"]},
                         "cc_question_mass": {"ms": question_mass_ms, "segments": int(len(w.segments))},
                         "cc_chunk_attention": {"ms": chunk_attention_ms, "segment_pairs": int(batch.pair_off[-1])},
-                        "layerwise_preload": preload},
+                        "layerwise_preload": preload, "layer_loop": layer_loop},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, args.cpu_budget)

@@ -471,6 +471,37 @@ def preload_schedule(n_layers: int, depth: int):
     return steps
 
 
+def layer_loop(w, r: int, n_layers: int, window: int, q_scales: Sequence[float], scores=None):
+    """The per-layer loop of Sec. 3.4 for request r on one layer's tensors reused for every layer
+    (queries of layer l scaled by q_scales[l]): tokens are chosen from one fixed score list (the
+    request's scores in the new context unless given), each layer recomputes and attends them, the
+    question's attention to the chunks feeds Algorithm 1, and from the layer after the focused set
+    settles the other chunks are not recomputed any more (their budget drops to 0).
+    Returns one dict per layer: selected sets, q_pos, out, lse, masses, focused set, stop layer."""
+    k_sh, v_c, _ = shifted_context(w, r)
+    segs = _segments_of(w, r)
+    chunk_ids = [i for i, sg in enumerate(segs) if sg[1] == 0]
+    if scores is None:
+        scores = score_request(w, r, k_sh)
+    budget = [segs[i][5] for i in chunk_ids]
+    inter_hist, stop_layer, focused, out = [], None, None, []
+    for l in range(n_layers):
+        selected = [top_n(sc, n) for sc, n in zip(scores, budget)]
+        q = np.asarray(w.q, dtype=np.float64) * float(q_scales[l])
+        k_ctx, v_ctx, q_pos, q_row, o, lse = fix_and_attend(w, r, k_sh, v_c, selected, q=q)
+        mass = question_chunk_mass(w, r, k_ctx, q=q)
+        rec = dict(selected=selected, q_pos=q_pos, out=o, lse=lse, mass=mass)
+        if stop_layer is None and chunk_ids:
+            inter_hist.append([mass[i] for i in chunk_ids])
+            f, l_star, _ = predict_focused(inter_hist, window)
+            if f is not None:
+                stop_layer, focused = l_star, f
+                budget = [b if c in f else 0 for c, b in enumerate(budget)]
+        rec["stop_layer"], rec["focused"] = stop_layer, focused
+        out.append(rec)
+    return out
+
+
 def qkv_project(hidden_rows: np.ndarray, w_qkv: np.ndarray, hq: int, hkv: int, d: int):
     """Q, K, V of the given token rows: X W^T with W [(Hq+2Hkv)d, hidden] (one row per output
     feature: q heads, then k heads, then v heads), split by heads (Sec. 3.4.3: computed only for

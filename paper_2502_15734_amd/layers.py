@@ -1,0 +1,117 @@
+"""A loop over attention layers built from the library's calls (Sec. 3.4): per layer the chunk store
+arrives through the layer-wise preloader, cached keys are re-positioned, the chosen tokens are
+recomputed and attended, the question's attention to every chunk feeds Algorithm 1, and once a
+request's focused chunks are settled the other chunks of that request are no longer recomputed.
+
+Argument marshalling and call order only; every step runs in libcachecraft.  The synthetic
+workloads hold ONE layer's tensors, so every layer reuses them with the queries scaled by a
+per-layer factor (a power of two, exact in bf16) to make the layers differ.
+"""
+from __future__ import annotations
+
+from typing import Callable, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from .binding import CC_IMPL_AUTO, FocusTracker, Preloader, preload_depth
+from .pipeline import DeviceBatch
+
+
+class LayerLoop:
+    def __init__(self, w, n_layers: int, window: int, q_scale: Callable[[int], float] = lambda l: 1.0,
+                 impl: int = CC_IMPL_AUTO, preload: bool = True, depth: Optional[int] = None,
+                 device: str = "cuda"):
+        self.w, self.n_layers, self.window, self.q_scale = w, n_layers, window, q_scale
+        self.batch = DeviceBatch(w, device=device, impl=impl)
+        b = self.batch
+        seg = w.segments
+        self.chunk_segs = [[s for s in range(int(w.req_seg_off[r]), int(w.req_seg_off[r + 1])) if seg[s][1] == 0]
+                           for r in range(w.n_requests)]
+        self.trackers = [FocusTracker(max(1, len(c)), window) for c in self.chunk_segs]
+        self.budget = np.array(seg[:, 5], dtype=np.int64)
+        self.stop_layer: List[Optional[int]] = [None] * w.n_requests
+        self.focused: List[Optional[List[int]]] = [None] * w.n_requests
+        self.mass_host = torch.zeros(max(1, len(seg)), dtype=torch.float32).pin_memory()
+        self.mass_ready = torch.cuda.Event()
+        self.pre = None
+        if preload:
+            self.k_host, self.v_host = b.k_store.cpu().pin_memory(), b.v_store.cpu().pin_memory()
+            self.depth = depth if depth is not None else 1
+            n_slots = min(self.depth + 1, n_layers)
+            self.slots = [(torch.empty_like(b.k_store), torch.empty_like(b.v_store)) for _ in range(n_slots)]
+            self.pre = (Preloader(n_layers, self.depth, n_slots), Preloader(n_layers, self.depth, n_slots))
+            for l in range(n_layers):
+                self.pre[0].set_layer(l, self.k_host, self.slots[l % n_slots][0])
+                self.pre[1].set_layer(l, self.v_host, self.slots[l % n_slots][1])
+
+    def run(self, scores: Optional[np.ndarray] = None, keep_outputs: bool = False):
+        """scores: per-token scores to select from (the ordered list a chunk's metadata keeps); by
+        default layer 0 computes them with cc_select and the later layers reuse them.
+        Returns one record per layer: rows recomputed, per-request focused sets decided so far."""
+        b, w = self.batch, self.w
+        if scores is not None:
+            b.scores.copy_(torch.from_numpy(np.ascontiguousarray(scores, dtype=np.float32)))
+        records = []
+        for l in range(self.n_layers):
+            t_start = torch.cuda.Event(enable_timing=True); t_end = torch.cuda.Event(enable_timing=True)
+            t_start.record()
+            if self.pre is not None:
+                self.pre[0].acquire(l); self.pre[1].acquire(l)
+                b.k_store, b.v_store = self.slots[l % len(self.slots)]
+            b.rope_shift()
+            if l == 0 and scores is None:
+                b.select()
+            else:
+                b.select_from_scores()
+            b.gather()
+            s = float(self.q_scale(l))
+            if s != 1.0 and b.n_q_tot:
+                b.q_c[: b.n_q_tot].mul_(s)
+            b.sparse_prefill()
+            mass = b.question_mass()
+            self.mass_host.copy_(mass, non_blocking=True)
+            self.mass_ready.record()
+            if self.pre is not None:
+                self.pre[0].release(l); self.pre[1].release(l)
+            t_end.record()
+            rec = {"layer": l + 1, "rows": b.n_q_tot, "_events": (t_start, t_end)}
+            if keep_outputs:
+                torch.cuda.synchronize()
+                rec["out"] = b.out[: b.n_q_tot].float().cpu().numpy()
+                rec["lse"] = b.lse[: b.n_q_tot].cpu().numpy()
+                rec["sel_idx"] = b.sel_idx[: b.n_q_tot].cpu().numpy()
+                rec["cu_q"] = np.array(getattr(b, "cu_q_host", w.cu_q), copy=True)
+            # Algorithm 1 on this layer's masses; a settled request drops its unfocused chunks
+            self.mass_ready.synchronize()
+            m = self.mass_host.numpy()
+            rec["mass"] = m[: len(w.segments)].copy()
+            changed = False
+            for r, segs in enumerate(self.chunk_segs):
+                if self.stop_layer[r] is not None or not segs:
+                    continue
+                stop, focused = self.trackers[r].update([float(m[s]) for s in segs])
+                if stop:
+                    self.stop_layer[r], self.focused[r] = l + 1, focused
+                    for i, sgi in enumerate(segs):
+                        if i not in focused:
+                            self.budget[sgi] = 0
+                            changed = True
+            rec["stop_layer"] = list(self.stop_layer)
+            rec["focused"] = [None if f is None else list(f) for f in self.focused]
+            if changed and l + 1 < self.n_layers:
+                b.set_budget(self.budget)
+            records.append(rec)
+        torch.cuda.synchronize()
+        for rec in records:
+            t_start, t_end = rec.pop("_events")
+            rec["ms"] = t_start.elapsed_time(t_end)
+        return records
+
+    def close(self):
+        for t in self.trackers:
+            t.close()
+        if self.pre is not None:
+            for p in self.pre:
+                p.close()
+            self.pre = None

@@ -114,34 +114,60 @@ class DeviceBatch:
         self.ctx.gather_rows(self.v_new, self.miss_rows, self.v_miss)
         self.ctx.scatter_kv(self.k_miss, self.v_miss, self.miss_pos, self.miss_slot, self.k_req, self.v_req)
 
+    def _rows(self, t):
+        """The first n_q_tot rows of a per-query buffer (the buffers are sized for the largest budget)."""
+        return t[: max(1, self.n_q_tot)] if self.n_q_tot < t.shape[0] else t
+
     def select(self):
+        r = self._rows
         self.ctx.select(self.q, self.k_req, self.req_tab, self.segments, self.req_seg_off,
-                        self.n_requests, self.max_seg_tokens, self.sel_idx, self.q_row, self.q_pos,
-                        self.slot_map, self.scores, self.ws_select)
+                        self.n_requests, self.max_seg_tokens, r(self.sel_idx), r(self.q_row), r(self.q_pos),
+                        r(self.slot_map), self.scores, self.ws_select)
 
     def select_from_scores(self, scores=None):
         """Selection from given per-token scores (default: the scores cc_select wrote)."""
+        r = self._rows
         self.ctx.select_from_scores(self.scores if scores is None else scores, self.req_tab, self.segments,
-                                    self.sel_idx, self.q_row, self.q_pos, self.slot_map, self.ws_select)
+                                    r(self.sel_idx), r(self.q_row), r(self.q_pos), r(self.slot_map), self.ws_select)
+
+    def set_budget(self, n_select):
+        """New token budgets N per segment (numpy int array over all segments; question segments keep
+        their length): rewrites n_select / sel_off of the segment table and the row offsets cu_q."""
+        seg = np.array(self.w.segments, dtype=np.int32, copy=True) if not hasattr(self, "_seg_host") else self._seg_host
+        n_select = np.asarray(n_select, dtype=np.int64)
+        is_q = seg[:, 1] != 0
+        nsel = np.where(is_q, seg[:, 3], np.minimum(n_select, seg[:, 3])).astype(np.int64)
+        seg[:, 5] = nsel
+        seg[:, 7] = np.concatenate([[0], np.cumsum(nsel)[:-1]])
+        cu_q = np.concatenate([seg[self.w.req_seg_off[:-1], 7], [int(nsel.sum())]]).astype(np.int32)
+        assert int(nsel.sum()) <= self.q_c.shape[0], "budget exceeds the buffers this batch was built with"
+        self._seg_host = seg
+        self.segments.copy_(torch.from_numpy(seg))
+        self.cu_q.copy_(torch.from_numpy(cu_q))
+        self.n_q_tot = int(nsel.sum())
+        self.max_q_per_req = int(np.diff(cu_q).max()) if self.n_requests else 0
+        self.cu_q_host = cu_q
 
     def gather(self):
         """Compact the chosen tokens' rows (and project them when the workload has hidden states)."""
         if self.n_q_tot == 0:
             return
+        r = self._rows
         if self.projected:
-            self.ctx.gather_rows(self.hidden, self.q_row, self.x_c)
-            self.ctx.qkv_project(self.x_c, self.w_qkv, self.q_c, self.k_c, self.v_c)
+            self.ctx.gather_rows(self.hidden, r(self.q_row), r(self.x_c))
+            self.ctx.qkv_project(r(self.x_c), self.w_qkv, r(self.q_c), r(self.k_c), r(self.v_c))
         else:
-            self.ctx.gather_rows(self.q, self.q_row, self.q_c)
-            self.ctx.gather_rows(self.k_new, self.q_row, self.k_c)
-            self.ctx.gather_rows(self.v_new, self.q_row, self.v_c)
+            self.ctx.gather_rows(self.q, r(self.q_row), r(self.q_c))
+            self.ctx.gather_rows(self.k_new, r(self.q_row), r(self.k_c))
+            self.ctx.gather_rows(self.v_new, r(self.q_row), r(self.v_c))
 
     def sparse_prefill(self):
         if self.n_q_tot == 0:
             return
-        self.ctx.sparse_prefill(self.q_c, self.k_c, self.v_c, self.q_pos, self.slot_map, self.cu_q,
+        r = self._rows
+        self.ctx.sparse_prefill(r(self.q_c), r(self.k_c), r(self.v_c), self.q_pos, self.slot_map, self.cu_q,
                                 self.max_q_per_req, self.k_req, self.v_req, self.req_tab,
-                                self.segments, self.req_seg_off, self.n_requests, self.n_tok, self.out, self.lse,
+                                self.segments, self.req_seg_off, self.n_requests, self.n_tok, r(self.out), self.lse,
                                 self.ws_prefill)
 
     def question_mass(self):
@@ -153,7 +179,7 @@ class DeviceBatch:
             self.seg_mass = torch.zeros(max(1, n_segs), dtype=torch.float32, device=self.device)
             nbytes = self.ctx.question_mass_workspace_bytes(self.n_tok, n_segs, self.max_question_rows)
             self.ws_mass = torch.empty(max(256, nbytes), dtype=torch.uint8, device=self.device)
-        self.ctx.question_mass(self.q_c, self.q_pos, self.cu_q, self.max_question_rows, self.k_req, self.v_req,
+        self.ctx.question_mass(self._rows(self.q_c), self.q_pos, self.cu_q, self.max_question_rows, self.k_req, self.v_req,
                                self.req_tab, self.segments, self.req_seg_off, self.n_requests, self.n_tok,
                                self.lse, self.seg_mass, self.ws_mass)
         return self.seg_mass
@@ -169,7 +195,7 @@ class DeviceBatch:
             self.self_mass = torch.zeros(max(1, n_segs), dtype=torch.float32, device=self.device)
             nbytes = self.ctx.chunk_attention_workspace_bytes(self.n_tok, n_segs, self.q_c.shape[0], self.max_q_per_req)
             self.ws_pairs = torch.empty(max(256, nbytes), dtype=torch.uint8, device=self.device)
-        self.ctx.chunk_attention(self.q_c, self.q_pos, self.slot_map, self.cu_q, self.max_q_per_req, self.k_req,
+        self.ctx.chunk_attention(self._rows(self.q_c), self.q_pos, self.slot_map, self.cu_q, self.max_q_per_req, self.k_req,
                                  self.v_req, self.req_tab, self.segments, self.req_seg_off, self.n_requests,
                                  self.n_tok, self.lse, self.pair_mass, self.self_mass, self.ws_pairs)
         return self.pair_mass, self.self_mass, self.pair_off

@@ -1,0 +1,47 @@
+"""The loop over layers (preloaded store -> shift -> select from a score list -> recompute + attend ->
+question-to-chunk mass -> Algorithm 1 -> budgets) against the oracle's loop, layer by layer."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import workload as W
+from oracle import cachecraft_oracle as O
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("preload", [True, False])
+def test_layer_loop_matches_the_oracle(preload):
+    from paper_2502_15734_amd.layers import LayerLoop
+    reqs = [W.RequestSpec([0, 1, 2, 3], [0.3, 0.2, 0.25, 0.4], 21), W.RequestSpec([3, 0, 4], [0.5, 0.15, 0.35], 40)]
+    w = W.custom("layers", "bf16", 8, 2, 128, 5.0e5, [100, 77, 130, 64, 201], [0, 5, 0, 17, 3], reqs, 0.35, seed=41)
+    n_layers, window = 5, 2
+    scale = lambda l: 2.0 ** ((l % 3) - 1)
+    # the score list both sides select from: the oracle's layer-0 scores, by token row
+    scores = np.zeros(w.n_tok, dtype=np.float32)
+    for r in range(w.n_requests):
+        k_sh, _, _ = O.shifted_context(w, r)
+        for sg, sc in zip(H.chunk_segments(w, r), O.score_request(w, r, k_sh)):
+            scores[int(sg[W.SEG_TOK]): int(sg[W.SEG_TOK]) + int(sg[W.SEG_NTOK])] = sc
+    ref = [O.layer_loop(w, r, n_layers, window, [scale(l) for l in range(n_layers)],
+                        scores=[scores[int(sg[W.SEG_TOK]): int(sg[W.SEG_TOK]) + int(sg[W.SEG_NTOK])].astype(np.float64)
+                                for sg in H.chunk_segments(w, r)]) for r in range(w.n_requests)]
+    loop = LayerLoop(w, n_layers, window, q_scale=scale, preload=preload, depth=2)
+    recs = loop.run(scores=scores, keep_outputs=True)
+    assert any(rec["stop_layer"][0] is not None for rec in recs), "the test should reach a stop"
+    for l, rec in enumerate(recs):
+        cu = rec["cu_q"]
+        for r in range(w.n_requests):
+            o = ref[r][l]
+            assert rec["stop_layer"][r] == o["stop_layer"] and rec["focused"][r] == o["focused"], f"layer {l + 1} request {r}"
+            q0, q1 = int(cu[r]), int(cu[r + 1])
+            assert q1 - q0 == len(o["q_pos"]), f"layer {l + 1} request {r}: rows"
+            assert H.rel_l2(rec["out"][q0:q1], o["out"]) <= H.TOL["bf16"], f"layer {l + 1} request {r}: out"
+            assert np.abs(rec["lse"][q0:q1] - o["lse"]).max() <= 4e-3
+            s0, s1 = int(w.req_seg_off[r]), int(w.req_seg_off[r + 1])
+            np.testing.assert_allclose(rec["mass"][s0:s1], o["mass"], rtol=1e-2, atol=1e-3)
+    assert recs[-1]["rows"] < recs[0]["rows"]                          # unfocused chunks are no longer recomputed
+    loop.close()

@@ -601,3 +601,32 @@ def test_miss_chunk_equals_a_cache_that_already_holds_its_fresh_keys():
     np.testing.assert_allclose(ref.out, hit.out, atol=2e-5)
     assert all(np.array_equal(a, b) for a, b in zip(ref.selected, hit.selected))
     assert np.array_equal(ref.selected[miss], np.arange(n))            # a miss recomputes every token
+
+
+# ----------------------------------------------------------------------------- loop over layers
+def test_layer_loop_without_a_stop_is_independent_single_layers():
+    w = small_workload(lens=(20, 33, 16), question=5)
+    scales = [1.0, 0.5, 2.0]
+    recs = O.layer_loop(w, 0, 3, window=9, q_scales=scales)            # the window never fills: no stop
+    k_sh, v_c, _ = O.shifted_context(w, 0)
+    base = O.run_request(w, 0)
+    for l, rec in enumerate(recs):
+        assert rec["stop_layer"] is None and rec["focused"] is None
+        assert all(np.array_equal(a, b) for a, b in zip(rec["selected"], base.selected))
+        _, _, _, _, out, lse = O.fix_and_attend(w, 0, k_sh, v_c, base.selected, q=w.q.astype(np.float64) * scales[l])
+        np.testing.assert_allclose(rec["out"], out, atol=1e-13)
+        assert abs(rec["mass"].sum() - 5.0) < 1e-12
+    np.testing.assert_allclose(recs[0]["out"], base.out, atol=1e-13)
+
+
+def test_layer_loop_drops_unfocused_chunks_after_the_stop():
+    w = small_workload(lens=(20, 33, 16), question=5, fracs=(0.5, 0.5, 0.5))
+    recs = O.layer_loop(w, 0, 4, window=2, q_scales=[1.0, 1.0, 1.0, 1.0])
+    # identical layers: the same set twice -> stop at layer 2, and with 3 chunks Algorithm 1 keeps one
+    assert [r["stop_layer"] for r in recs] == [None, 2, 2, 2]
+    f = recs[1]["focused"]
+    assert len(f) == 1 and f == [int(np.argmax(recs[0]["mass"][:3]))]
+    sizes = [[len(s) for s in r["selected"]] for r in recs]
+    assert sizes[0] == sizes[1] == [10, 17, 8]
+    assert sizes[2] == sizes[3] == [n if c in f else 0 for c, n in enumerate([10, 17, 8])]
+    assert len(recs[2]["q_pos"]) == sum(sizes[2]) + 5                 # the question is always recomputed
