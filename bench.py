@@ -245,6 +245,15 @@ def main():
         ev[i + 1].record()
     torch.cuda.synchronize()
     question_mass_ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]))
+    # cc_sparse_prefill with the masses as a by-product of its attention kernel
+    batch.sparse_prefill_mass()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    ev[0].record()
+    for i in range(args.steps):
+        batch.sparse_prefill_mass()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    prefill_mass_ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]))
     # inter / intra sums between all segments, over the rows of the last cc_sparse_prefill
     batch.chunk_attention()
     n_ca = max(1, min(args.steps, 5))
@@ -311,6 +320,8 @@ def main():
         # has, and the question-to-chunk attention mass computed after cc_sparse_prefill
         "extra_calls": {"cc_select_from_scores": {"ms": from_scores_ms, "chunk_tokens": work["n_chunk_tok"]},
                         "cc_question_mass": {"ms": question_mass_ms, "segments": int(len(w.segments))},
+                        "cc_sparse_prefill_mass": {"ms": prefill_mass_ms,
+                                                   "over_cc_sparse_prefill_ms": prefill_mass_ms - stage_ms["sparse_prefill"]},
                         "cc_chunk_attention": {"ms": chunk_attention_ms, "segment_pairs": int(batch.pair_off[-1])},
                         "layerwise_preload": preload, "layer_loop": layer_loop},
     }

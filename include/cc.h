@@ -14,6 +14,8 @@
  *   cc_sparse_prefill  causal attention of the chosen tokens + question over the whole merged
  *                      paged KV, after writing their recomputed K, V into it
  *                      (Eq. (1), Sec. 3.4.3, Sec. 4 "Selective Token Recomputation")
+ *   cc_sparse_prefill_mass  cc_sparse_prefill that also returns the question's attention to every
+ *                      chunk (Sec. 3.2.2), as a by-product of the attention kernel where it can
  *   cc_scatter_kv      the write half of cc_sparse_prefill alone: K, V of chunks without a cache
  *                      (Sec. 3.4.1) go into the request's pages before the others are scored
  *   cc_question_mass   attention the question pays to every chunk in that layer, inter(C_i, U)
@@ -219,6 +221,31 @@ int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void*
                       const cc_segment* segs, int32_t n_segs,
                       const int32_t* req_seg_off, int32_t n_requests, int32_t n_ctx_tokens,
                       void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- (c'') partial prefill that also returns the question's attention to every chunk --------
+ * cc_sparse_prefill (same steps, same out and lse, bit for bit) plus seg_mass as cc_question_mass
+ * defines it, in one call.  Where the attention kernel that runs can give the masses as a
+ * by-product it does (the 64-row MFMA kernel: at the last key tile of every segment it stores the
+ * log-sum-exp over all keys so far for the question rows; a row's weight on a segment is then
+ * exp(cum_s - lse) - exp(cum_{s-1} - lse); rows it leaves to the other kernel because their
+ * logits overflowed its fixed softmax reference are walked again, rarely, by a scalar kernel);
+ * otherwise the masses come from cc_question_mass's pass after the attention.  The call is for
+ * the per-layer loop of Sec. 3.2.2, where inter_l(C_i, U) is wanted in every layer.
+ *   lse is required.  max_question_rows as for cc_question_mass; max_segs_per_req: most segments
+ *   of one request (host scalar).  seg_mass [n_segs] float.
+ *   workspace: cc_sparse_prefill_mass_workspace_bytes(ctx, n_ctx_tokens, n_segs, n_requests,
+ *   max_question_rows, max_segs_per_req). */
+size_t cc_sparse_prefill_mass_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_tokens, int32_t n_segs,
+                                              int32_t n_requests, int32_t max_question_rows,
+                                              int32_t max_segs_per_req);
+int cc_sparse_prefill_mass(cc_ctx* ctx, const void* q, const void* k_new, const void* v_new,
+                           const int32_t* q_pos, const int32_t* slot_map, const int32_t* cu_q,
+                           int32_t n_q_tot, int32_t max_q_per_req, int32_t max_question_rows,
+                           void* k_pool, void* v_pool, int32_t n_blocks, const int32_t* block_tab,
+                           const cc_segment* segs, int32_t n_segs,
+                           const int32_t* req_seg_off, int32_t n_requests, int32_t max_segs_per_req,
+                           int32_t n_ctx_tokens, void* out, float* lse, float* seg_mass,
+                           void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- (c') step 1 of cc_sparse_prefill alone --------------------------------------------------
  * Rotates k_new[j] to position q_pos[j] and writes it, with v_new[j], into physical slot

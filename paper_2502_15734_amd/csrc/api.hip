@@ -251,6 +251,68 @@ int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void*
   return cc::check_launch(ctx, fn);
 }
 
+size_t cc_sparse_prefill_mass_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_tokens, int32_t n_segs,
+                                              int32_t n_requests, int32_t max_question_rows,
+                                              int32_t max_segs_per_req) {
+  if (ctx == nullptr || n_ctx_tokens < 0 || n_segs < 0 || n_requests < 0 || max_question_rows < 0 ||
+      max_segs_per_req < 0)
+    return 0;
+  return cc::prefill_mass_bytes(ctx, n_ctx_tokens, n_segs, n_requests, max_tiles_for(n_ctx_tokens, n_segs),
+                                max_question_rows, max_segs_per_req) + 256;
+}
+
+int cc_sparse_prefill_mass(cc_ctx* ctx, const void* q, const void* k_new, const void* v_new,
+                           const int32_t* q_pos, const int32_t* slot_map, const int32_t* cu_q,
+                           int32_t n_q_tot, int32_t max_q_per_req, int32_t max_question_rows,
+                           void* k_pool, void* v_pool, int32_t n_blocks, const int32_t* block_tab,
+                           const cc_segment* segs, int32_t n_segs, const int32_t* req_seg_off,
+                           int32_t n_requests, int32_t max_segs_per_req, int32_t n_ctx_tokens, void* out,
+                           float* lse, float* seg_mass, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+  static const char* fn = "cc_sparse_prefill_mass";
+  if (ctx == nullptr) return CC_ERR_INVALID_ARG;
+  CC_REQUIRE(n_q_tot >= 0 && max_q_per_req >= 0 && n_segs >= 0 && n_requests >= 0 && n_ctx_tokens >= 0 &&
+                 max_question_rows >= 0 && max_segs_per_req >= 0, "negative count");
+  CC_REQUIRE(max_q_per_req <= n_q_tot && max_question_rows <= max_q_per_req, "row bounds are inconsistent");
+  if (n_segs == 0) return CC_OK;
+  CC_REQUIRE(seg_mass != nullptr, "null pointer");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (n_q_tot == 0) {
+    cc::launch_fill_zero(seg_mass, n_segs, st);
+    return cc::check_launch(ctx, fn);
+  }
+  CC_REQUIRE(q && k_new && v_new && q_pos && slot_map && cu_q && k_pool && v_pool && block_tab &&
+                 segs && req_seg_off && out && lse, "null pointer (lse is required here)");
+  CC_REQUIRE(n_blocks > 0 && n_requests > 0 && max_q_per_req > 0 && max_segs_per_req > 0, "sizes must be positive");
+  CC_REQUIRE(n_requests <= 65535 && n_segs <= 65535, "more than 65535 requests or segments in one call");
+  CC_REQUIRE(n_requests <= n_segs, "every request needs at least one segment");
+  CC_REQUIRE(n_q_tot <= n_ctx_tokens, "n_ctx_tokens must bound the rows of the compact list");
+  CC_REQUIRE(static_cast<int64_t>(n_segs) * max_question_rows <= 0x3fffffff, "n_segs * max_question_rows too large");
+  CC_REQUIRE(aligned16(q) && aligned16(k_new) && aligned16(v_new) && aligned16(k_pool) &&
+                 aligned16(v_pool) && aligned16(out), "tensors must be 16-byte aligned");
+  CC_REQUIRE(workspace != nullptr && aligned16(workspace), "workspace missing or misaligned");
+  if (workspace_bytes < cc_sparse_prefill_mass_workspace_bytes(ctx, n_ctx_tokens, n_segs, n_requests,
+                                                               max_question_rows, max_segs_per_req))
+    return fail(ctx, CC_ERR_WORKSPACE_TOO_SMALL,
+                "cc_sparse_prefill_mass: workspace smaller than cc_sparse_prefill_mass_workspace_bytes()");
+  cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_q_tot, k_pool, v_pool, n_blocks, st);
+  if (max_question_rows == 0) {                               // no question rows: plain attention, zero masses
+    if (ctx->impl != CC_IMPL_SCALAR && cc::attn_mfma_supported(ctx))
+      cc::launch_attn_mfma(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab,
+                           segs, n_segs, req_seg_off, n_requests, out, lse, workspace,
+                           max_tiles_for(n_ctx_tokens, n_segs), nullptr, st);
+    else
+      cc::launch_attn_scalar(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab,
+                             segs, req_seg_off, n_requests, out, lse, nullptr, st);
+    cc::launch_fill_zero(seg_mass, n_segs, st);
+    return cc::check_launch(ctx, fn);
+  }
+  cc::launch_prefill_mass(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, max_question_rows, max_segs_per_req,
+                          k_pool, v_pool, n_blocks, block_tab, segs, n_segs, req_seg_off, n_requests,
+                          n_ctx_tokens, out, lse, seg_mass, workspace, max_tiles_for(n_ctx_tokens, n_segs), st);
+  return cc::check_launch(ctx, fn);
+}
+
 int cc_scatter_kv(cc_ctx* ctx, const void* k_new, const void* v_new, const int32_t* q_pos,
                   const int32_t* slot_map, int32_t n_rows, void* k_pool, void* v_pool, int32_t n_blocks,
                   void* stream) {

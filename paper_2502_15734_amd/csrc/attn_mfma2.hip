@@ -118,7 +118,8 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
     const TileDesc* __restrict__ tiles, const int32_t* __restrict__ seg_tile_off, int max_tiles,
     const int32_t* __restrict__ order, const int32_t* __restrict__ req_seg_off, int hq, int hkv,
     int n_sub, int n_tiles_x, InvFreq inv_freq, bf16_t* __restrict__ out, float* __restrict__ lse,
-    int32_t* __restrict__ redo, const int32_t* __restrict__ q_map) {
+    int32_t* __restrict__ redo, const int32_t* __restrict__ q_map,
+    const int32_t* __restrict__ snap_index, float* __restrict__ cum, int s_max) {
   constexpr int TQ = 32 * QB;
   __shared__ uint4 lds_all[kBufs * kImage];
   const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
@@ -312,7 +313,8 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
     d.nvalid = __builtin_amdgcn_readlane(win.nvalid, l);
 #pragma unroll
     for (int i = 0; i < 4; ++i) d.blk[i] = __builtin_amdgcn_readlane(win.blk[i], l);
-    d.seg = 0; d.pad = 0;
+    d.seg = __builtin_amdgcn_readlane(win.seg, l);
+    d.pad = 0;
     return d;
   };
   auto image_off = [&](int t) __attribute__((always_inline)) { return (t & (kBufs - 1)) * (kImage * 16); };   // bytes
@@ -419,6 +421,25 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
   // on entry: parity 0 holds S of the tile's first block (masked) with the first half of its
   // exponentials done.  The last tile is peeled off, so the loop body is straight-line code apart
   // from the masking branches.
+  // By-product for rows that ask for it (snap_index >= 0; the question rows): when the tile that
+  // has just been closed is the last one of its segment, the log-sum-exp over all keys up to here
+  // goes to cum[snap row][head][segment's index in its request].  The reference never moves in this
+  // kernel, so these running sums subtract exactly.  (Rare: once per segment of the request.)
+  const int seg_first = cum != nullptr ? req_seg_off[order[blockIdx.y]] : 0;
+  // (segments without tokens have no tile: the value also stands for those between this tile's
+  // segment and the next tile's)
+  auto snapshot = [&](int seg, int seg_next) __attribute__((always_inline)) {
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      const float tot = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
+      const int sr = snap_index[row[qb]];
+      if (row_valid[qb] && hh == 0 && sr >= 0) {
+        const float v = kLn2 * (m_ref[qb] + __builtin_amdgcn_logf(tot));
+        for (int sl = max(seg - seg_first, 0); sl < min(seg_next - seg_first, s_max); ++sl)
+          cum[(static_cast<size_t>(sr) * hq + h) * s_max + sl] = v;
+      }
+    }
+  };
   auto tile_front = [&](auto next_tag, int t) __attribute__((always_inline)) {
     constexpr bool kNext = decltype(next_tag)::value;
     const int img = image_off(t);
@@ -452,6 +473,7 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
     // slot 3: S of the next tile's first block; second half of the second block's exponentials
     s_slot(img, nimg, true, 16, 0, [&](int kk, int qb) __attribute__((always_inline)) { exp_one(qb, 1, 8 + kk); });
     close_block();
+    if (cum != nullptr && d0.seg != d1.seg) snapshot(d0.seg, d1.seg);          // tile t was the last of its segment
     if (d1.nvalid < kTile || d1.kpos0 + kTile - 1 > p_min) mask_block(0, 0, d1.kpos0, d1.nvalid);
     // slot 4: PV of the second block; first half of the next block's exponentials
     pv_slot(img, nimg, true, 24, 1, [&](int st, int qb) __attribute__((always_inline)) { exp_one(qb, 0, st); });
@@ -517,7 +539,8 @@ bool attn_v2_supported(const cc_ctx* ctx) {
 void launch_attn_v2(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
                     int max_q_per_req, const void* k_pool, const void* v_pool, int n_blocks,
                     const Plan& pl, const int32_t* req_seg_off, int n_requests, void* out, float* lse,
-                    int32_t* redo, const int32_t* q_map, hipStream_t stream) {
+                    int32_t* redo, const int32_t* q_map, const int32_t* snap_index, float* cum, int s_max,
+                    hipStream_t stream) {
   constexpr int QB = 2;
   const int hkv = ctx->cfg.n_kv_heads, n_sub = ctx->cfg.n_q_heads / hkv / 4;
   const int n_tiles = (max_q_per_req + 32 * QB - 1) / (32 * QB);
@@ -525,7 +548,7 @@ void launch_attn_v2(const cc_ctx* ctx, const void* q, const int32_t* q_pos, cons
   hipLaunchKernelGGL((attn_v2_kernel<QB>), grid, dim3(256), 0, stream, static_cast<const bf16_t*>(q), q_pos,
                      cu_q, static_cast<const bf16_t*>(k_pool), static_cast<const bf16_t*>(v_pool), n_blocks,
                      pl.tiles, pl.seg_tile_off, pl.max_tiles, pl.order, req_seg_off, ctx->cfg.n_q_heads, hkv,
-                     n_sub, n_tiles, ctx->inv_freq, static_cast<bf16_t*>(out), lse, redo, q_map);
+                     n_sub, n_tiles, ctx->inv_freq, static_cast<bf16_t*>(out), lse, redo, q_map, snap_index, cum, s_max);
 }
 
 }  // namespace cc

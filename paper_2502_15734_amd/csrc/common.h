@@ -72,11 +72,23 @@ void launch_attn_scalar(const cc_ctx* ctx, const void* q, const int32_t* q_pos, 
                         const int32_t* req_seg_off, int n_requests, void* out, float* lse,
                         const int32_t* q_map, hipStream_t stream);
 bool attn_mfma_supported(const cc_ctx* ctx);
+// By-product of the attention launch (optional): for rows with snap_index >= 0 the wide kernel
+// writes cum[snap row][head][segment's index in its request] = log-sum-exp over all keys up to the
+// end of that segment.  On return `wide` says whether the wide kernel ran at all (else nothing was
+// written) and `redo` points at its per-tile flags (rows it left to the narrow kernel).
+struct AttnByProduct {
+  const int32_t* snap_index;
+  float* cum;
+  int s_max;
+  mutable bool wide;
+  mutable const int32_t* redo;
+};
 void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
                       int n_q_tot, int max_q_per_req, const void* k_pool, const void* v_pool,
                       int n_blocks, const int32_t* block_tab, const cc_segment* segs, int n_segs,
                       const int32_t* req_seg_off, int n_requests, void* out, float* lse,
-                      void* plan_ws, int max_tiles, const int32_t* q_map, hipStream_t stream);
+                      void* plan_ws, int max_tiles, const int32_t* q_map, hipStream_t stream,
+                      const AttnByProduct* by = nullptr);
 
 // attention mass of the question rows on every segment (focus.hip)
 void launch_fill_zero(float* p, int n, hipStream_t stream);
@@ -93,6 +105,16 @@ void launch_question_mass(const cc_ctx* ctx, const void* q, const int32_t* q_pos
                           const int32_t* block_tab, const cc_segment* segs, int n_segs,
                           const int32_t* req_seg_off, int n_requests, const float* lse, float* seg_mass,
                           void* workspace, int max_tiles, hipStream_t stream);
+
+// cc_sparse_prefill's attention with the question's per-segment masses as a by-product where the
+// kernels can give it (focus.hip)
+size_t prefill_mass_bytes(const cc_ctx* ctx, int n_ctx_tokens, int n_segs, int n_requests, int max_tiles,
+                          int max_question_rows, int s_max);
+void launch_prefill_mass(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
+                         int n_q_tot, int max_q_per_req, int max_question_rows, int s_max, const void* k_pool,
+                         const void* v_pool, int n_blocks, const int32_t* block_tab, const cc_segment* segs,
+                         int n_segs, const int32_t* req_seg_off, int n_requests, int n_ctx_tokens, void* out,
+                         float* lse, float* seg_mass, void* workspace, int max_tiles, hipStream_t stream);
 
 // attention for head groups that are a multiple of 4: 64 query rows per wavefront (attn_mfma2.hip)
 bool attn_v2_supported(const cc_ctx* ctx);

@@ -25,6 +25,7 @@
 #include <vector>
 
 #include "device_util.h"
+#include "mfma_tile.h"
 
 namespace cc {
 
@@ -265,9 +266,149 @@ __global__ __launch_bounds__(256) void self_sum_kernel(
   if (threadIdx.x == 0) self_mass[s] = tot / static_cast<float>(hq);
 }
 
-__global__ __launch_bounds__(256) void fill_zero_kernel(float* __restrict__ p, int n) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i < n) p[i] = 0.f;
+// ---- question rows of the batch, numbered request after request ("snap rows") ------------------------
+// m_req[r] = question rows of request r (at most max_rows)
+__global__ __launch_bounds__(256) void snap_count_kernel(
+    const int32_t* __restrict__ q_pos, const int32_t* __restrict__ cu_q,
+    const cc_segment* __restrict__ segs, const int32_t* __restrict__ req_seg_off, int max_rows,
+    int32_t* __restrict__ m_req) {
+  const int r = blockIdx.x;
+  const int qs = question_start(segs, req_seg_off, r);
+  int cnt = 0;
+  for (int j0 = cu_q[r]; j0 < cu_q[r + 1]; j0 += 256) {
+    const int j = j0 + threadIdx.x;
+    cnt += __syncthreads_count(j < cu_q[r + 1] && q_pos[j] >= qs);
+  }
+  if (threadIdx.x == 0) m_req[r] = min(cnt, max_rows);
+}
+
+// snap_base[r] = snap rows before request r; snap_base[n_requests] = their total
+__global__ __launch_bounds__(256) void snap_scan_kernel(int n_requests, const int32_t* __restrict__ m_req,
+                                                         int32_t* __restrict__ snap_base) {
+  __shared__ int carry_s;
+  if (threadIdx.x == 0) carry_s = 0;
+  __syncthreads();
+  for (int r0 = 0; r0 < n_requests; r0 += 256) {
+    const int r = r0 + threadIdx.x;
+    const int m = r < n_requests ? m_req[r] : 0;
+    int total;
+    const int incl = block_scan_256(m, &total);
+    const int carry = carry_s;
+    if (r < n_requests) snap_base[r] = carry + incl - m;
+    __syncthreads();
+    if (threadIdx.x == 0) carry_s = carry + total;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) snap_base[n_requests] = carry_s;
+}
+
+// snap_index[j] = snap row of list row j (-1: not a question row); snap_rows / snap_req: the way back
+__global__ __launch_bounds__(256) void snap_fill_kernel(
+    const int32_t* __restrict__ q_pos, const int32_t* __restrict__ cu_q,
+    const cc_segment* __restrict__ segs, const int32_t* __restrict__ req_seg_off,
+    const int32_t* __restrict__ snap_base, int32_t* __restrict__ snap_index,
+    int32_t* __restrict__ snap_rows, int32_t* __restrict__ snap_req) {
+  const int r = blockIdx.x;
+  const int base = snap_base[r], m = snap_base[r + 1] - base;
+  const int qs = question_start(segs, req_seg_off, r);
+  int done = 0;
+  for (int j0 = cu_q[r]; j0 < cu_q[r + 1]; j0 += 256) {      // (uniform trip count)
+    const int j = j0 + threadIdx.x;
+    const bool in = j < cu_q[r + 1];
+    const int take = (in && q_pos[j] >= qs) ? 1 : 0;
+    int total;
+    const int ord = done + block_scan_256(take, &total) - take;
+    if (in) snap_index[j] = (take && ord < m) ? base + ord : -1;
+    if (take && ord < m) {
+      snap_rows[base + ord] = j;
+      snap_req[base + ord] = r;
+    }
+    done += total;
+  }
+}
+
+// Cumulative log-sum-exp per segment for the snap rows the wide attention kernel did not finish
+// (its redo flags; every snap row when redo is NULL): one wavefront per snap row walks, head after
+// head, the request's keys in prompt order with a running maximum, lane i owning rotation pair
+// (i, i + d/2).  (Slow, and meant to be: it only ever runs for rows whose logits overflowed.)
+template <typename T, int D>
+__global__ __launch_bounds__(64) void cum_scalar_kernel(
+    const T* __restrict__ q, const int32_t* __restrict__ q_pos, const int32_t* __restrict__ cu_q,
+    const int32_t* __restrict__ snap_base, int n_requests, const int32_t* __restrict__ snap_rows,
+    const int32_t* __restrict__ snap_req, const int32_t* __restrict__ redo,
+    const T* __restrict__ k_pool, int n_blocks, const int32_t* __restrict__ block_tab,
+    const cc_segment* __restrict__ segs, const int32_t* __restrict__ req_seg_off, int hq, int hkv,
+    InvFreq inv_freq, float* __restrict__ cum, int s_max) {
+  const int u = blockIdx.x, lane = threadIdx.x;
+  if (u >= snap_base[n_requests]) return;
+  const int j = snap_rows[u], r = snap_req[u];
+  if (redo != nullptr && redo[redo_index(cu_q[r] + ((j - cu_q[r]) / 64) * 64)] == 0) return;
+  const int p = q_pos[j];
+  const bool own = lane < D / 2;
+  for (int h = 0; h < hq; ++h) {
+  const int kvh = h / (hq / hkv);
+  float qx = 0.f, qy = 0.f;
+  if (own) {
+    const T* qp = q + (static_cast<size_t>(j) * hq + h) * D;
+    float x = to_float(qp[lane]), y = to_float(qp[lane + D / 2]), c, sn;
+    rot_cos_sin(p, inv_freq.f[lane], &c, &sn);
+    qx = x * c - y * sn;
+    qy = y * c + x * sn;
+  }
+  const float scale = rsqrtf(static_cast<float>(D));
+  float m = -INFINITY, z = 0.f;
+  for (int s = req_seg_off[r]; s < req_seg_off[r + 1]; ++s) {
+    const cc_segment ks = segs[s];
+    const int n_vis = min(ks.n_tokens, p - ks.logical_start + 1);
+    for (int tk = 0; tk < n_vis; ++tk) {
+      const int blk = block_tab[ks.tab_off + tk / kBlock];
+      if (blk < 0 || blk >= n_blocks) continue;
+      const T* kp = k_pool + ((static_cast<size_t>(blk) * hkv + kvh) * kBlock + tk % kBlock) * D;
+      const float part = own ? qx * to_float(kp[lane]) + qy * to_float(kp[lane + D / 2]) : 0.f;
+      const float logit = wave_sum(part) * scale;
+      if (logit > m) {
+        z *= expf(m - logit);
+        m = logit;
+      }
+      z += expf(logit - m);
+    }
+    const int sl = s - req_seg_off[r];
+    if (lane == 0 && sl < s_max) cum[(static_cast<size_t>(u) * hq + h) * s_max + sl] = m + logf(z);
+  }
+  }
+}
+
+// seg_mass[s] from the cumulative log-sum-exps: weight on segment s = exp(cum_s - lse) - exp(cum_{s-1} - lse);
+// the request's last segment takes what is left (its own cum entry is never read: rows of a tile
+// end at different keys there).
+__global__ __launch_bounds__(256) void seg_mass_from_cum_kernel(
+    const cc_segment* __restrict__ segs, const int32_t* __restrict__ req_seg_off, int n_requests,
+    const int32_t* __restrict__ snap_base, const int32_t* __restrict__ snap_rows, int hq,
+    const float* __restrict__ cum, int s_max, const float* __restrict__ lse, float* __restrict__ seg_mass) {
+  const int s = blockIdx.x;
+  const int r = segs[s].req;
+  float acc = 0.f;
+  if (r >= 0 && r < n_requests) {
+    const int sl = s - req_seg_off[r], n_r = req_seg_off[r + 1] - req_seg_off[r];
+    const int base = snap_base[r], m = snap_base[r + 1] - base;
+    if (sl < s_max) {
+      for (int i = threadIdx.x; i < m * hq; i += 256) {
+        const int u = base + i / hq, h = i % hq;
+        const float total = lse[static_cast<size_t>(snap_rows[u]) * hq + h];
+        const float* c = cum + (static_cast<size_t>(u) * hq + h) * s_max;
+        const float upto = sl + 1 < n_r ? __expf(c[sl] - total) : 1.f;
+        const float before = sl > 0 ? __expf(c[sl - 1] - total) : 0.f;
+        acc += upto - before;
+      }
+    }
+  }
+  const float tot = block_sum_256(acc);
+  if (threadIdx.x == 0) seg_mass[s] = tot / static_cast<float>(hq);
+}
+
+__global__ __launch_bounds__(256) void fill_kernel(float* __restrict__ p, size_t n, float v) {
+  const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i < n) p[i] = v;
 }
 
 size_t up256(size_t v) { return (v + 255) / 256 * 256; }
@@ -282,7 +423,7 @@ struct ListBuffers {
 }  // namespace
 
 void launch_fill_zero(float* p, int n, hipStream_t stream) {
-  if (n > 0) hipLaunchKernelGGL(fill_zero_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, p, n);
+  if (n > 0) hipLaunchKernelGGL(fill_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, p, static_cast<size_t>(n), 0.f);
 }
 
 // workspace: tile plan | m_seg[n_segs+1] | cu_v[n_segs+1] | seg_iota[n_segs+1] | q_map[cap] |
@@ -377,6 +518,85 @@ void launch_chunk_attention(const cc_ctx* ctx, const void* q, const int32_t* q_p
 #undef CC_LAUNCH
     hipLaunchKernelGGL(self_sum_kernel, dim3(n_segs), dim3(256), 0, stream, q_pos, cu_q, segs, n_requests, hq,
                        b.row_self, self_mass);
+  }
+}
+
+// workspace of the prefill that also returns the question's masses:
+//   tile plan of the attention | m_req[n_requests+1] | snap_base[n_requests+1] | snap_index[n_q_tot] |
+//   snap_rows[cap] | snap_req[cap] | cum[cap][Hq][s_max] | workspace of launch_question_mass
+// with cap = n_requests * max_question_rows.
+size_t prefill_mass_bytes(const cc_ctx* ctx, int n_ctx_tokens, int n_segs, int n_requests, int max_tiles,
+                          int max_question_rows, int s_max) {
+  const size_t cap = static_cast<size_t>(n_requests) * max_question_rows;
+  return up256(mfma_plan_bytes(n_segs, max_tiles, n_ctx_tokens)) +
+         2 * up256(static_cast<size_t>(n_requests + 1) * sizeof(int32_t)) +
+         up256(static_cast<size_t>(n_ctx_tokens) * sizeof(int32_t)) + 2 * up256(cap * sizeof(int32_t)) +
+         up256(cap * ctx->cfg.n_q_heads * s_max * sizeof(float)) +
+         segment_mass_bytes(ctx, n_segs, max_tiles, max_question_rows, 0);
+}
+
+void launch_prefill_mass(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
+                         int n_q_tot, int max_q_per_req, int max_question_rows, int s_max, const void* k_pool,
+                         const void* v_pool, int n_blocks, const int32_t* block_tab, const cc_segment* segs,
+                         int n_segs, const int32_t* req_seg_off, int n_requests, int n_ctx_tokens, void* out,
+                         float* lse, float* seg_mass, void* workspace, int max_tiles, hipStream_t stream) {
+  const int hq = ctx->cfg.n_q_heads, hkv = ctx->cfg.n_kv_heads;
+  const size_t cap = static_cast<size_t>(n_requests) * max_question_rows;
+  char* w = static_cast<char*>(workspace);
+  void* plan_ws = w;
+  w += up256(mfma_plan_bytes(n_segs, max_tiles, n_ctx_tokens));
+  int32_t* m_req = reinterpret_cast<int32_t*>(w);
+  w += up256(static_cast<size_t>(n_requests + 1) * sizeof(int32_t));
+  int32_t* snap_base = reinterpret_cast<int32_t*>(w);
+  w += up256(static_cast<size_t>(n_requests + 1) * sizeof(int32_t));
+  int32_t* snap_index = reinterpret_cast<int32_t*>(w);
+  w += up256(static_cast<size_t>(n_ctx_tokens) * sizeof(int32_t));
+  int32_t* snap_rows = reinterpret_cast<int32_t*>(w);
+  w += up256(cap * sizeof(int32_t));
+  int32_t* snap_req = reinterpret_cast<int32_t*>(w);
+  w += up256(cap * sizeof(int32_t));
+  float* cum = reinterpret_cast<float*>(w);
+  w += up256(cap * hq * s_max * sizeof(float));
+  void* fallback_ws = w;
+
+  const bool mfma = ctx->impl != CC_IMPL_SCALAR && attn_mfma_supported(ctx);
+  AttnByProduct by{snap_index, cum, s_max, false, nullptr};
+  if (mfma) {
+    hipLaunchKernelGGL(snap_count_kernel, dim3(n_requests), dim3(256), 0, stream, q_pos, cu_q, segs, req_seg_off,
+                       max_question_rows, m_req);
+    hipLaunchKernelGGL(snap_scan_kernel, dim3(1), dim3(256), 0, stream, n_requests, m_req, snap_base);
+    hipLaunchKernelGGL(snap_fill_kernel, dim3(n_requests), dim3(256), 0, stream, q_pos, cu_q, segs, req_seg_off,
+                       snap_base, snap_index, snap_rows, snap_req);
+    // (a segment without tokens, or before the first tile, keeps "no key yet")
+    const size_t n_cum = cap * hq * s_max;
+    hipLaunchKernelGGL(fill_kernel, dim3(static_cast<unsigned>((n_cum + 255) / 256)), dim3(256), 0, stream, cum, n_cum,
+                       -INFINITY);
+    launch_attn_mfma(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab, segs,
+                     n_segs, req_seg_off, n_requests, out, lse, plan_ws, max_tiles, nullptr, stream, &by);
+  } else {
+    launch_attn_scalar(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab, segs,
+                       req_seg_off, n_requests, out, lse, nullptr, stream);
+  }
+  if (by.wide) {
+    // rows the wide kernel flagged (normally none: every wavefront reads one flag and leaves)
+    const bool bf = ctx->cfg.dtype == CC_BF16;
+    const int d = ctx->cfg.head_dim;
+#define CC_LAUNCH(T, D)                                                                                  \
+  hipLaunchKernelGGL((cum_scalar_kernel<T, D>), dim3(static_cast<unsigned>(cap)), dim3(64), 0, stream, \
+                     static_cast<const T*>(q), q_pos, cu_q, snap_base, n_requests, snap_rows, snap_req,   \
+                     by.redo, static_cast<const T*>(k_pool), n_blocks, block_tab, segs, req_seg_off, hq,  \
+                     hkv, ctx->inv_freq, cum, s_max)
+    if (bf && d == 128) CC_LAUNCH(bf16_t, 128);
+    else if (bf && d == 64) CC_LAUNCH(bf16_t, 64);
+    else if (!bf && d == 128) CC_LAUNCH(float, 128);
+    else CC_LAUNCH(float, 64);
+#undef CC_LAUNCH
+    hipLaunchKernelGGL(seg_mass_from_cum_kernel, dim3(n_segs), dim3(256), 0, stream, segs, req_seg_off, n_requests,
+                       snap_base, snap_rows, hq, cum, s_max, lse, seg_mass);
+  } else {
+    // the kernels that ran carry no by-product: the pass of its own
+    launch_question_mass(ctx, q, q_pos, cu_q, max_question_rows, k_pool, v_pool, n_blocks, block_tab, segs,
+                         n_segs, req_seg_off, n_requests, lse, seg_mass, fallback_ws, max_tiles, stream);
   }
 }
 

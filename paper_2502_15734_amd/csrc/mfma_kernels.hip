@@ -697,7 +697,8 @@ void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, co
                       int n_q_tot, int max_q_per_req, const void* k_pool, const void* v_pool,
                       int n_blocks, const int32_t* block_tab, const cc_segment* segs, int n_segs,
                       const int32_t* req_seg_off, int n_requests, void* out, float* lse,
-                      void* plan_ws, int max_tiles, const int32_t* q_map, hipStream_t stream) {
+                      void* plan_ws, int max_tiles, const int32_t* q_map, hipStream_t stream,
+                      const AttnByProduct* by) {
   // Wide kernel first where the head group allows it; the narrow kernel then redoes the 64-row
   // tiles the wide one flagged (normally none: its workgroups read one flag and exit).
   // (a grid too small to give every compute unit a wide workgroup runs faster on the narrow
@@ -709,7 +710,12 @@ void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, co
   const Plan pl = run_plan(plan_ws, segs, n_segs, req_seg_off, n_requests, block_tab, n_blocks, max_tiles, n_redo, stream);
   if (wide)
     launch_attn_v2(ctx, q, q_pos, cu_q, max_q_per_req, k_pool, v_pool, n_blocks, pl, req_seg_off, n_requests,
-                   out, lse, pl.redo, q_map, stream);
+                   out, lse, pl.redo, q_map, by != nullptr ? by->snap_index : nullptr,
+                   by != nullptr ? by->cum : nullptr, by != nullptr ? by->s_max : 0, stream);
+  if (by != nullptr) {
+    by->wide = wide;
+    by->redo = pl.redo;
+  }
   const int32_t* redo = pl.redo;
 #define CC_ARGS ctx, q, q_pos, cu_q, max_q_per_req, k_pool, v_pool, n_blocks, pl, segs, req_seg_off, n_requests, out, lse, redo, q_map, stream
   switch (ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads) {

@@ -68,8 +68,7 @@ class LayerLoop:
             s = float(self.q_scale(l))
             if s != 1.0 and b.n_q_tot:
                 b.q_c[: b.n_q_tot].mul_(s)
-            b.sparse_prefill()
-            mass = b.question_mass()
+            mass = b.sparse_prefill_mass()               # attention + the question's masses in one call
             self.mass_host.copy_(mass, non_blocking=True)
             self.mass_ready.record()
             if self.pre is not None:

@@ -170,8 +170,7 @@ class DeviceBatch:
                                 self.segments, self.req_seg_off, self.n_requests, self.n_tok, r(self.out), self.lse,
                                 self.ws_prefill)
 
-    def question_mass(self):
-        """inter(C_i, U) per segment, from the last sparse_prefill's lse (float32 [n_segs])."""
+    def _mass_buffers(self):
         n_segs = int(self.segments.shape[0])
         if not hasattr(self, "seg_mass"):
             seg = self.w.segments
@@ -179,6 +178,30 @@ class DeviceBatch:
             self.seg_mass = torch.zeros(max(1, n_segs), dtype=torch.float32, device=self.device)
             nbytes = self.ctx.question_mass_workspace_bytes(self.n_tok, n_segs, self.max_question_rows)
             self.ws_mass = torch.empty(max(256, nbytes), dtype=torch.uint8, device=self.device)
+        return n_segs
+
+    def sparse_prefill_mass(self):
+        """sparse_prefill and the question's masses per segment in one call (by-product where possible)."""
+        n_segs = self._mass_buffers()
+        if self.n_q_tot == 0:
+            self.seg_mass.zero_()
+            return self.seg_mass
+        if not hasattr(self, "ws_prefill_mass"):
+            self.max_segs_per_req = int(np.diff(self.w.req_seg_off).max())
+            nbytes = self.ctx.sparse_prefill_mass_workspace_bytes(self.n_tok, n_segs, self.n_requests,
+                                                                  self.max_question_rows, self.max_segs_per_req)
+            self.ws_prefill_mass = torch.empty(max(256, nbytes), dtype=torch.uint8, device=self.device)
+        r = self._rows
+        self.ctx.sparse_prefill_mass(r(self.q_c), r(self.k_c), r(self.v_c), self.q_pos, self.slot_map, self.cu_q,
+                                     self.max_q_per_req, min(self.max_question_rows, self.max_q_per_req), self.k_req,
+                                     self.v_req, self.req_tab, self.segments, self.req_seg_off, self.n_requests,
+                                     self.max_segs_per_req, self.n_tok, r(self.out), self.lse, self.seg_mass,
+                                     self.ws_prefill_mass)
+        return self.seg_mass
+
+    def question_mass(self):
+        """inter(C_i, U) per segment, from the last sparse_prefill's lse (float32 [n_segs])."""
+        self._mass_buffers()
         self.ctx.question_mass(self._rows(self.q_c), self.q_pos, self.cu_q, self.max_question_rows, self.k_req, self.v_req,
                                self.req_tab, self.segments, self.req_seg_off, self.n_requests, self.n_tok,
                                self.lse, self.seg_mass, self.ws_mass)

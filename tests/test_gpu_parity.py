@@ -84,6 +84,7 @@ def check_workload(w, impl, score_tol=5e-5):
     compare_prefill(b, res, "oracle selection")
     check_question_mass(w, b, [res[r].k_ctx for r in range(w.n_requests)])
     check_chunk_attention(w, b, res)
+    check_prefill_with_mass(w, b, [res[r].k_ctx for r in range(w.n_requests)])
 
     # ---- end to end with the library's own selection -----------------------------------------
     b2 = DeviceBatch(w, impl=impl, poison=True)
@@ -101,6 +102,10 @@ def check_question_mass(w, b, k_ctx_of, requests=None, exact=True):
     """cc_question_mass after cc_sparse_prefill on batch b against the oracle's inter(C_i, U)."""
     mass = b.question_mass().cpu().numpy()
     torch.cuda.synchronize()
+    check_question_mass_values(w, mass, k_ctx_of, requests, exact)
+
+
+def check_question_mass_values(w, mass, k_ctx_of, requests=None, exact=True):
     bf = w.spec.dtype == "bf16"
     for r in (range(w.n_requests) if requests is None else requests):
         s0, s1 = int(w.req_seg_off[r]), int(w.req_seg_off[r + 1])
@@ -114,6 +119,22 @@ def check_question_mass(w, b, k_ctx_of, requests=None, exact=True):
             err = np.abs(got - want)
             bound = (1e-2 if bf else 1e-4) * want + (1e-4 if bf else 1e-6) * max(1, m_r)
             assert np.all(err <= bound), f"request {r}: question mass {got} vs {want}"
+
+
+def check_prefill_with_mass(w, b, k_ctx_of, requests=None, exact=True):
+    """cc_sparse_prefill_mass on a batch that has just run cc_sparse_prefill + cc_question_mass: the
+    attention results must be the same bits, the masses the oracle's (and the other call's)."""
+    out1, lse1 = b.out.clone(), b.lse.clone()
+    m1 = b.seg_mass.clone()
+    b.seg_mass.fill_(float("nan"))
+    m2 = b.sparse_prefill_mass()
+    torch.cuda.synchronize()
+    n = b.n_q_tot
+    assert torch.equal(out1[:n], b.out[:n]) and torch.equal(lse1[:n], b.lse[:n])
+    assert torch.isfinite(m2).all()
+    bf = w.spec.dtype == "bf16"
+    assert (m1 - m2).abs().max().item() <= (2e-2 if bf else 2e-4)
+    check_question_mass_values(w, m2.cpu().numpy(), k_ctx_of, requests, exact)
 
 
 def check_chunk_attention(w, b, res):
@@ -351,6 +372,10 @@ def test_reference_repair_path_when_later_keys_dwarf_the_first_tile(kval):
         for c, sg in enumerate(H.chunk_segments(w, 0)):
             t0, n = int(sg[W.SEG_TOK]), int(sg[W.SEG_NTOK])
             assert np.abs(sc[t0:t0 + n] - res[0].scores[c]).max() <= 5e-5, f"{impl}: scores of chunk {c}"
+        # the question's masses, through the pass of its own and as a by-product (the rows whose
+        # reference overflowed take the scalar route there)
+        check_question_mass(w, b, [ref.k_ctx])
+        check_prefill_with_mass(w, b, [ref.k_ctx])
 
 
 def _projected_reference(w, b, r, gsel):
@@ -458,6 +483,7 @@ def test_full_size_configs_on_sampled_outputs(cid):
         # -- attention of the question to every chunk (the projected workload's question is too
         #    long for the oracle's row loops: there only the sums are checked)
         check_question_mass(w, b, {r: k_ctx}, requests=[r], exact=w.hidden is None)
+        check_prefill_with_mass(w, b, {r: k_ctx}, requests=[r], exact=w.hidden is None)
 
 
 class _SparseRows:
