@@ -30,8 +30,8 @@ MEASURED_MFMA_BF16_TFLOPS = 1880.0
 # HBM bytes per launch of each call's main kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # of this command scaled by a 512 MiB copy (profiles/hot_path_kernels_config3_8b_continuous_batch.md).
 MEASURED_TRAFFIC_BYTES = {
-    3: {"cc_rope_shift": (567.9 + 646.5) * 2 ** 20, "cc_select": (2653.0 + 34.3 + 17.3 + 1.3) * 2 ** 20,
-        "cc_sparse_prefill": (1042.9 + 319.6 + 165.8 + 159.0) * 2 ** 20},
+    3: {"cc_rope_shift": (568.3 + 646.5) * 2 ** 20, "cc_select": (2760.1 + 34.3 + 17.3 + 1.3) * 2 ** 20,
+        "cc_sparse_prefill": (1041.1 + 319.6 + 164.4 + 159.0) * 2 ** 20},
 }
 
 
@@ -166,6 +166,37 @@ def time_layerwise_preload(batch, step_ms: float, n_layers: int = 6) -> dict:
             "step_ms": step_ms, "serial_ms": serial_ms, "pipelined_ms": pipelined_ms}
 
 
+def time_extra_calls(batch, w, work, steps: int, ms_per_step: float, sparse_prefill_ms: float) -> dict:
+    """Entry points that are not part of the timed step, on the batch the step just ran on."""
+    import torch
+
+    def timed(fn, n):
+        fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+        ev[0].record()
+        for i in range(n):
+            fn()
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        return float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(n)]))
+
+    # selection from given scores (the scores cc_select just wrote, so the selection is unchanged)
+    from_scores_ms = timed(batch.select_from_scores, steps)
+    # attention of the question to every chunk: a pass of its own after cc_sparse_prefill ...
+    question_mass_ms = timed(batch.question_mass, steps)
+    # ... and as a by-product of cc_sparse_prefill's attention kernel
+    prefill_mass_ms = timed(batch.sparse_prefill_mass, steps)
+    # inter / intra sums between all segments, over the rows of the last cc_sparse_prefill
+    chunk_attention_ms = timed(batch.chunk_attention, max(1, min(steps, 5)))
+    preload = time_layerwise_preload(batch, ms_per_step)
+    layer_loop = time_layer_loop(w)
+    return {"cc_select_from_scores": {"ms": from_scores_ms, "chunk_tokens": work["n_chunk_tok"]},
+            "cc_question_mass": {"ms": question_mass_ms, "segments": int(len(w.segments))},
+            "cc_sparse_prefill_mass": {"ms": prefill_mass_ms, "over_cc_sparse_prefill_ms": prefill_mass_ms - sparse_prefill_ms},
+            "cc_chunk_attention": {"ms": chunk_attention_ms, "segment_pairs": int(batch.pair_off[-1])},
+            "layerwise_preload": preload, "layer_loop": layer_loop}
+
+
 def time_layer_loop(w, n_layers: int = 4, window: int = 2) -> dict:
     """The loop over layers with Algorithm 1 deciding the focused chunks (identical synthetic layers, so
     every request settles at layer `window`): rows recomputed and time per layer before and after."""
@@ -184,6 +215,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=3, help="benchmark config 1..5 (default 3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra-calls", action="store_true",
+                    help="skip the timings of entry points outside the step (used for profiles of the step's kernels)")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 512 MiB device copy (identity cc_gather_rows) so that a "
@@ -228,44 +261,8 @@ def main():
     tokens_per_s = work["recomputed_tokens"] / (dt / args.steps)
 
     stage_ms = time_stages(batch, args.steps)
-    # selection from given scores (the scores cc_select just wrote, so the selection is unchanged)
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    ev[0].record()
-    for i in range(args.steps):
-        batch.select_from_scores()
-        ev[i + 1].record()
-    torch.cuda.synchronize()
-    from_scores_ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]))
-    # attention of the question to every chunk, from the last cc_sparse_prefill's log-sum-exp
-    batch.question_mass()
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    ev[0].record()
-    for i in range(args.steps):
-        batch.question_mass()
-        ev[i + 1].record()
-    torch.cuda.synchronize()
-    question_mass_ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]))
-    # cc_sparse_prefill with the masses as a by-product of its attention kernel
-    batch.sparse_prefill_mass()
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    ev[0].record()
-    for i in range(args.steps):
-        batch.sparse_prefill_mass()
-        ev[i + 1].record()
-    torch.cuda.synchronize()
-    prefill_mass_ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]))
-    # inter / intra sums between all segments, over the rows of the last cc_sparse_prefill
-    batch.chunk_attention()
-    n_ca = max(1, min(args.steps, 5))
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n_ca + 1)]
-    ev[0].record()
-    for i in range(n_ca):
-        batch.chunk_attention()
-        ev[i + 1].record()
-    torch.cuda.synchronize()
-    chunk_attention_ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(n_ca)]))
-    preload = time_layerwise_preload(batch, ms_per_step)
-    layer_loop = time_layer_loop(w)
+    extra = None if args.no_extra_calls else time_extra_calls(batch, w, work, args.steps, ms_per_step,
+                                                               stage_ms["sparse_prefill"])
     q_pos = batch.q_pos.cpu().numpy()[: w.n_q_tot]
     attn_flops = attention_flops(w, q_pos)
     proj_flops = 0.0
@@ -316,14 +313,8 @@ def main():
         "roofline": roofline,
         "stages": stages,
         "sparse_prefill_tokens_per_s": w.n_q_tot / (stage_ms["sparse_prefill"] * 1e-3),
-        # not part of the step: the selection half of cc_select alone, on scores the caller already
-        # has, and the question-to-chunk attention mass computed after cc_sparse_prefill
-        "extra_calls": {"cc_select_from_scores": {"ms": from_scores_ms, "chunk_tokens": work["n_chunk_tok"]},
-                        "cc_question_mass": {"ms": question_mass_ms, "segments": int(len(w.segments))},
-                        "cc_sparse_prefill_mass": {"ms": prefill_mass_ms,
-                                                   "over_cc_sparse_prefill_ms": prefill_mass_ms - stage_ms["sparse_prefill"]},
-                        "cc_chunk_attention": {"ms": chunk_attention_ms, "segment_pairs": int(batch.pair_off[-1])},
-                        "layerwise_preload": preload, "layer_loop": layer_loop},
+        # not part of the step: the other entry points of the library, timed on the same batch
+        "extra_calls": extra,
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, args.cpu_budget)
