@@ -7,6 +7,8 @@
 // K-steps of 32 are double-buffered in LDS (2 x 32 KiB) with the next step's global loads held in
 // registers.  In the transposed product a lane holds 4 consecutive features of ONE token, so the
 // epilogue writes 8-byte pieces of an output row.  fp32 (and odd shapes): plain LDS-tiled kernel.
+#include <type_traits>
+
 #include "device_util.h"
 
 namespace cc {
@@ -154,6 +156,143 @@ __global__ __launch_bounds__(512, 2) void qkv_project_mfma_kernel(
   }
 }
 
+// ---- MFMA kernel, 128 x 128 outputs per wavefront -------------------------------------------------
+// Workgroup = 4 wavefronts (2 x 2), one per SIMD, 256 features x 256 tokens; a wavefront owns
+// 4 x 4 blocks of v_mfma_f32_32x32x16_bf16 (256 accumulation registers), so 8 operand reads from
+// LDS feed 16 MFMAs per 16-wide k-step - half the LDS traffic per MFMA of the kernel above.
+// K-steps of 32 go straight from global memory into a ring of four LDS images (32 KiB each,
+// global_load_lds: lane L of an instruction fills piece base + L, so an image is laid out in MFMA
+// operand order and every operand read is one contiguous KiB): iteration t starts the loads of
+// image t+3 and, before its barrier, waits for its own loads of image t+2.
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+
+__device__ __forceinline__ void gemm_load_to_lds(const void* src, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(src), "s"(lds_addr) : "memory", "m0");
+}
+__device__ __forceinline__ void gemm_mfma(f32x16& d, const u32x4& a, const u32x4& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(d) : "v"(a), "v"(b));
+}
+
+constexpr int kStages = 4;
+constexpr int kStageBytes = 32 * 1024;      // 32 operand groups of 1 KiB: W blocks 0..7 x 2 k-steps, x blocks 0..7 x 2 k-steps
+
+__global__ __launch_bounds__(256, 1) void qkv_project_mfma2_kernel(
+    const bf16_t* __restrict__ x, const bf16_t* __restrict__ w, int n_rows, int hidden, int nq, int nk,
+    bf16_t* __restrict__ q, bf16_t* __restrict__ k, bf16_t* __restrict__ v) {
+  __shared__ uint4 lds[kStages * kStageBytes / 16];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nl = lane & 31, hh = lane >> 5;
+  const int wn = wave & 1, wm = wave >> 1;             // feature half, token half of the workgroup tile
+  const int n0 = blockIdx.x * kTN, m0 = blockIdx.y * kTM;
+  const int n_k = hidden / kTK;
+
+  // ---- staging: wavefront w brings operand groups 8w .. 8w+7 of every image --------------------
+  // group g < 16: W block g/2, k-step g%2; g >= 16: x block (g-16)/2, k-step g%2.  Lane (nl, hh)
+  // of a group reads row 32 block + nl, 16 bytes at k = 16 step + 8 hh of the image's 32-wide slice.
+  const char* src[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int g = 8 * wave + j, blk = (g & 15) >> 1, step = g & 1;
+    const int r = 32 * blk + nl;
+    const bf16_t* row = g < 16 ? w + static_cast<size_t>(n0 + r) * hidden
+                               : x + static_cast<size_t>(min(m0 + r, n_rows - 1)) * hidden;
+    src[j] = reinterpret_cast<const char*>(row + 16 * step + 8 * hh);
+  }
+  typedef __attribute__((address_space(3))) const uint4 lds_piece;
+  const uint32_t lds_base = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_piece*)lds)));
+  auto dma_stage = [&](int t) __attribute__((always_inline)) {
+    const uint32_t dst = lds_base + (t & (kStages - 1)) * kStageBytes + (8 * wave) * 1024;
+    const size_t koff = static_cast<size_t>(min(t, n_k - 1)) * (kTK * sizeof(bf16_t));   // past the end: a harmless repeat
+#pragma unroll
+    for (int j = 0; j < 8; ++j) gemm_load_to_lds(src[j] + koff, dst + 1024 * j);
+  };
+  auto wait_loads = [&](auto newer) __attribute__((always_inline)) {
+    constexpr int kN = decltype(newer)::value;
+    __builtin_amdgcn_s_waitcnt((kN & 15) | ((kN >> 4) << 14) | (7 << 4) | (15 << 8));
+    asm volatile("" ::: "memory");
+  };
+  auto barrier = [&]() __attribute__((always_inline)) {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
+
+  f32x16 acc[4][4];                                    // [feature block][token block], accumulation registers
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) asm volatile("v_accvgpr_write_b32 %0, 0" : "=a"(acc[a][b][i]));
+
+  const char* lds_bytes = reinterpret_cast<const char*>(lds);
+  const int lane16 = lane * 16;
+  // operand group of this wavefront: W block 4 wn + a / x block 4 wm + b, k-step s of image t
+  auto read_a = [&](int t, int s, int a) __attribute__((always_inline)) {
+    return *reinterpret_cast<const u32x4*>(lds_bytes + (t & (kStages - 1)) * kStageBytes + ((4 * wn + a) * 2 + s) * 1024 + lane16);
+  };
+  auto read_b = [&](int t, int s, int b) __attribute__((always_inline)) {
+    return *reinterpret_cast<const u32x4*>(lds_bytes + (t & (kStages - 1)) * kStageBytes + (16 + (4 * wm + b) * 2 + s) * 1024 + lane16);
+  };
+
+  // ---- prologue: images 0, 1, 2 -----------------------------------------------------------------
+  dma_stage(0);
+  dma_stage(1);
+  dma_stage(2);
+  wait_loads(std::integral_constant<int, 0>{});
+  __syncthreads();
+  u32x4 opa[2][4], opb[2][4];                          // operands of the k-step in flight and of the next one
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { opa[0][i] = read_a(0, 0, i); opb[0][i] = read_b(0, 0, i); }
+
+  for (int t = 0; t < n_k; ++t) {
+    dma_stage(t + 3);
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      // operands of the next k-step (the other half of this image, or the first of the next one)
+      const int nt = s == 0 ? t : min(t + 1, n_k - 1), ns = s ^ 1;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { opa[s ^ 1][i] = read_a(nt, ns, i); opb[s ^ 1][i] = read_b(nt, ns, i); }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) gemm_mfma(acc[a][b], opa[s][a], opb[s][b]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // image t+2 (loads started one iteration ago) must be whole before anyone reads it
+    wait_loads(std::integral_constant<int, 8>{});
+    barrier();
+  }
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+
+  // D^T block (a, b): lane (nl, hh) holds token m0 + 128 wm + 32 b + nl, features
+  // n0 + 128 wn + 32 a + 8 (i/4) + 4 hh + i%4
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    const int row = m0 + wm * 128 + b * 32 + nl;
+    if (row >= n_rows) continue;
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      const int col0 = n0 + wn * 128 + a * 32;        // a 32-feature block never straddles q | k | v
+      bf16_t* base;
+      int c_in, width;
+      if (col0 < nq) { base = q; c_in = col0; width = nq; }
+      else if (col0 < nq + nk) { base = k; c_in = col0 - nq; width = nk; }
+      else { base = v; c_in = col0 - nq - nk; width = nk; }
+      bf16_t* op = base + static_cast<size_t>(row) * width + c_in + 4 * hh;
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        bf16_t v4[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v4[e] = static_cast<bf16_t>(acc[a][b][4 * g4 + e]);
+        *reinterpret_cast<uint2*>(op + 8 * g4) = *reinterpret_cast<uint2*>(v4);
+      }
+    }
+  }
+}
+
 }  // namespace
 
 void launch_qkv_project(const cc_ctx* ctx, const void* x, const void* w, int n_rows, int hidden,
@@ -163,6 +302,12 @@ void launch_qkv_project(const cc_ctx* ctx, const void* x, const void* w, int n_r
   if (ctx->cfg.dtype == CC_BF16 && ctx->impl != CC_IMPL_SCALAR && n_cols % kTN == 0 && hidden % kTK == 0 &&
       nq % 32 == 0 && nk % 32 == 0) {
     dim3 grid(n_cols / kTN, (n_rows + kTM - 1) / kTM);
+    if (hidden / kTK >= 3 && ctx->impl != CC_IMPL_MFMA_NARROW) {
+      hipLaunchKernelGGL(qkv_project_mfma2_kernel, grid, dim3(256), 0, stream,
+                         static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(w), n_rows, hidden, nq, nk,
+                         static_cast<bf16_t*>(q), static_cast<bf16_t*>(k), static_cast<bf16_t*>(v));
+      return;
+    }
     hipLaunchKernelGGL(qkv_project_mfma_kernel, grid, dim3(512), 0, stream,
                        static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(w), n_rows, hidden, nq, nk,
                        static_cast<bf16_t*>(q), static_cast<bf16_t*>(k), static_cast<bf16_t*>(v));
