@@ -398,12 +398,13 @@ def _projected_reference(w, b, r, gsel):
     return O.run_request(w, r, selected_override=gsel, k_new=kf, v_new=vf, q=qf)
 
 
+@pytest.mark.parametrize("impl", ["wide", "narrow"])      # the two MFMA projection kernels
 @pytest.mark.parametrize("scale", [0.06])
-def test_config5_scaled_with_projection(scale):
+def test_config5_scaled_with_projection(scale, impl):
     from paper_2502_15734_amd.pipeline import DeviceBatch
     w = W.config(5, scale)
     assert w.hidden is not None
-    b = DeviceBatch(w, impl=_impls()["wide"], poison=True)
+    b = DeviceBatch(w, impl=_impls()[impl], poison=True)
     b.step(); torch.cuda.synchronize()
     gsel = H.gpu_selection(w, b.sel_idx.cpu().numpy())
     res = O.run(w)
