@@ -66,8 +66,12 @@ def attention_flops(w, q_pos: np.ndarray) -> float:
 def time_stages(batch, steps: int):
     """Average ms of each library call over `steps` steps (HIP events on the calls' stream)."""
     import torch
-    names = ["rope_shift", "select", "gather", "sparse_prefill"]
-    fns = [batch.rope_shift, batch.select, batch.gather, batch.sparse_prefill]
+    if batch.projected or not batch.fused_gather:
+        names = ["rope_shift", "select", "gather", "sparse_prefill"]
+        fns = [batch.rope_shift, batch.select, batch.gather, batch.sparse_prefill]
+    else:           # per-token q / k_new / v_new are read through cc_select's row list: no gather call
+        names = ["rope_shift", "select", "sparse_prefill"]
+        fns = [batch.rope_shift, batch.select, batch.sparse_prefill_fused]
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(fns) + 1)] for _ in range(steps)]
     torch.cuda.synchronize()
     for i in range(steps):
@@ -180,6 +184,7 @@ def time_extra_calls(batch, w, work, steps: int, ms_per_step: float, sparse_pref
         torch.cuda.synchronize()
         return float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(n)]))
 
+    batch.gather()         # the calls below take the compact query rows
     # selection from given scores (the scores cc_select just wrote, so the selection is unchanged)
     from_scores_ms = timed(batch.select_from_scores, steps)
     # attention of the question to every chunk: a pass of its own after cc_sparse_prefill ...
@@ -275,16 +280,17 @@ def main():
                           "achieved": work["shift_bytes"] / (stage_ms["rope_shift"] * 1e-3) / 1e9},
         "cc_select": {"bound": "mfma", "ms": stage_ms["select"], "unit": "TFLOP/s", "peak": PEAK_MFMA_BF16_TFLOPS,
                       "achieved": work["score_flops"] / (stage_ms["select"] * 1e-3) / 1e12},
-        "cc_gather_rows(+cc_qkv_project)": {"bound": "mfma" if proj_flops else "hbm", "ms": stage_ms["gather"],
-                                            "unit": "TFLOP/s" if proj_flops else "GB/s",
-                                            "peak": PEAK_MFMA_BF16_TFLOPS if proj_flops else PEAK_HBM_GBS,
-                                            "achieved": (proj_flops / (stage_ms["gather"] * 1e-3) / 1e12) if proj_flops else
-                                            (2.0 * w.n_q_tot * (w.spec.n_q_heads + 2 * w.spec.n_kv_heads) * w.spec.head_dim *
-                                             (2 if w.spec.dtype == "bf16" else 4) / (stage_ms["gather"] * 1e-3) / 1e9)},
         "cc_sparse_prefill": {"bound": "mfma", "ms": stage_ms["sparse_prefill"], "unit": "TFLOP/s",
                               "peak": PEAK_MFMA_BF16_TFLOPS,
                               "achieved": attn_flops / (stage_ms["sparse_prefill"] * 1e-3) / 1e12},
     }
+    if "gather" in stage_ms:
+        row_bytes = (w.spec.n_q_heads + 2 * w.spec.n_kv_heads) * w.spec.head_dim * (2 if w.spec.dtype == "bf16" else 4)
+        stages["cc_gather_rows(+cc_qkv_project)"] = {
+            "bound": "mfma" if proj_flops else "hbm", "ms": stage_ms["gather"],
+            "unit": "TFLOP/s" if proj_flops else "GB/s", "peak": PEAK_MFMA_BF16_TFLOPS if proj_flops else PEAK_HBM_GBS,
+            "achieved": (proj_flops / (stage_ms["gather"] * 1e-3) / 1e12) if proj_flops else
+                        (2.0 * w.n_q_tot * row_bytes / (stage_ms["gather"] * 1e-3) / 1e9)}
     for s in stages.values():
         s["frac"] = s["achieved"] / s["peak"]
     # what a plain device-to-device copy of 512 MiB reaches on this machine, beside the HBM peak

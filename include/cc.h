@@ -209,14 +209,17 @@ int cc_qkv_project(cc_ctx* ctx, const void* x, const void* w_qkv, int32_t n_rows
  * rows of one request must be contiguous, and rows whose slots lie in the same 16-token block
  * must be adjacent (the order cc_select emits); otherwise any order inside a request is accepted.
  *   q [n_q_tot][Hq][d], k_new, v_new [n_q_tot][Hkv][d]; out like q; lse [n_q_tot][Hq] or NULL.
+ *   src_rows [n_q_tot] or NULL: if given, list row j reads row src_rows[j] of q, k_new and v_new
+ *   (per-token tensors, e.g. cc_select's q_row output) instead of row j of compact ones, which
+ *   saves the caller the gather; q_pos, slot_map, out and lse are always indexed by the list row.
  *   max_q_per_req: max rows of one request (host scalar, sizes the launch).
  *   n_ctx_tokens: sum of n_tokens over all segments, or any upper bound of it (host scalar; sizes
  *   the key-tile plan kept in the workspace).
  * Eq. (1), Sec. 3.4.3, Sec. 4 "Selective Token Recomputation". */
 size_t cc_sparse_prefill_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_tokens, int32_t n_segs);
 int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void* v_new,
-                      const int32_t* q_pos, const int32_t* slot_map, const int32_t* cu_q,
-                      int32_t n_q_tot, int32_t max_q_per_req,
+                      const int32_t* src_rows, const int32_t* q_pos, const int32_t* slot_map,
+                      const int32_t* cu_q, int32_t n_q_tot, int32_t max_q_per_req,
                       void* k_pool, void* v_pool, int32_t n_blocks, const int32_t* block_tab,
                       const cc_segment* segs, int32_t n_segs,
                       const int32_t* req_seg_off, int32_t n_requests, int32_t n_ctx_tokens,

@@ -75,7 +75,7 @@ def load_library() -> C.CDLL:
     lib.cc_qkv_project.restype = C.c_int
     lib.cc_sparse_prefill_workspace_bytes.argtypes = [vp, i32, i32]
     lib.cc_sparse_prefill_workspace_bytes.restype = sz
-    lib.cc_sparse_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, vp, i32,
+    lib.cc_sparse_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, vp, i32,
                                       vp, i32, i32, vp, vp, vp, sz, vp]
     lib.cc_sparse_prefill.restype = C.c_int
     lib.cc_sparse_prefill_mass_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32]
@@ -220,10 +220,12 @@ class Context:
         return int(self._lib.cc_sparse_prefill_workspace_bytes(self._h, n_ctx_tokens, n_segs))
 
     def sparse_prefill(self, q, k_new, v_new, q_pos, slot_map, cu_q, max_q_per_req, k_pool, v_pool,
-                       block_tab, segs, req_seg_off, n_requests, n_ctx_tokens, out, lse, workspace):
+                       block_tab, segs, req_seg_off, n_requests, n_ctx_tokens, out, lse, workspace, src_rows=None):
+        """src_rows: row of q / k_new / v_new each list row reads (None: they are compact, row j = list row j)."""
+        n_q_tot = q.shape[0] if src_rows is None else src_rows.shape[0]
         self._check(self._lib.cc_sparse_prefill(
-            self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(q_pos), _ptr(slot_map), _ptr(cu_q),
-            q.shape[0], max_q_per_req, _ptr(k_pool), _ptr(v_pool), k_pool.shape[0], _ptr(block_tab),
+            self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(src_rows), _ptr(q_pos), _ptr(slot_map), _ptr(cu_q),
+            n_q_tot, max_q_per_req, _ptr(k_pool), _ptr(v_pool), k_pool.shape[0], _ptr(block_tab),
             _ptr(segs), segs.shape[0], _ptr(req_seg_off), n_requests, n_ctx_tokens, _ptr(out), _ptr(lse),
             _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
 

@@ -216,8 +216,8 @@ size_t cc_sparse_prefill_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_tokens
 }
 
 int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void* v_new,
-                      const int32_t* q_pos, const int32_t* slot_map, const int32_t* cu_q,
-                      int32_t n_q_tot, int32_t max_q_per_req, void* k_pool, void* v_pool,
+                      const int32_t* src_rows, const int32_t* q_pos, const int32_t* slot_map,
+                      const int32_t* cu_q, int32_t n_q_tot, int32_t max_q_per_req, void* k_pool, void* v_pool,
                       int32_t n_blocks, const int32_t* block_tab, const cc_segment* segs,
                       int32_t n_segs, const int32_t* req_seg_off, int32_t n_requests,
                       int32_t n_ctx_tokens, void* out, float* lse, void* workspace,
@@ -240,14 +240,14 @@ int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void*
     return fail(ctx, CC_ERR_WORKSPACE_TOO_SMALL,
                 "cc_sparse_prefill: workspace smaller than cc_sparse_prefill_workspace_bytes()");
   hipStream_t st = static_cast<hipStream_t>(stream);
-  cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_q_tot, k_pool, v_pool, n_blocks, st);
+  cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_q_tot, k_pool, v_pool, n_blocks, src_rows, st);
   if (ctx->impl != CC_IMPL_SCALAR && cc::attn_mfma_supported(ctx))
     cc::launch_attn_mfma(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks,
                          block_tab, segs, n_segs, req_seg_off, n_requests, out, lse, workspace,
-                         max_tiles_for(n_ctx_tokens, n_segs), nullptr, st);
+                         max_tiles_for(n_ctx_tokens, n_segs), src_rows, 0, st);
   else
     cc::launch_attn_scalar(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks,
-                           block_tab, segs, req_seg_off, n_requests, out, lse, nullptr, st);
+                           block_tab, segs, req_seg_off, n_requests, out, lse, src_rows, 0, st);
   return cc::check_launch(ctx, fn);
 }
 
@@ -295,15 +295,15 @@ int cc_sparse_prefill_mass(cc_ctx* ctx, const void* q, const void* k_new, const 
                                                                max_question_rows, max_segs_per_req))
     return fail(ctx, CC_ERR_WORKSPACE_TOO_SMALL,
                 "cc_sparse_prefill_mass: workspace smaller than cc_sparse_prefill_mass_workspace_bytes()");
-  cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_q_tot, k_pool, v_pool, n_blocks, st);
+  cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_q_tot, k_pool, v_pool, n_blocks, nullptr, st);
   if (max_question_rows == 0) {                               // no question rows: plain attention, zero masses
     if (ctx->impl != CC_IMPL_SCALAR && cc::attn_mfma_supported(ctx))
       cc::launch_attn_mfma(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab,
                            segs, n_segs, req_seg_off, n_requests, out, lse, workspace,
-                           max_tiles_for(n_ctx_tokens, n_segs), nullptr, st);
+                           max_tiles_for(n_ctx_tokens, n_segs), nullptr, 0, st);
     else
       cc::launch_attn_scalar(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab,
-                             segs, req_seg_off, n_requests, out, lse, nullptr, st);
+                             segs, req_seg_off, n_requests, out, lse, nullptr, 0, st);
     cc::launch_fill_zero(seg_mass, n_segs, st);
     return cc::check_launch(ctx, fn);
   }
@@ -324,7 +324,7 @@ int cc_scatter_kv(cc_ctx* ctx, const void* k_new, const void* v_new, const int32
   CC_REQUIRE(n_blocks > 0, "sizes must be positive");
   CC_REQUIRE(aligned16(k_new) && aligned16(v_new) && aligned16(k_pool) && aligned16(v_pool),
              "tensors must be 16-byte aligned");
-  cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_rows, k_pool, v_pool, n_blocks,
+  cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_rows, k_pool, v_pool, n_blocks, nullptr,
                           static_cast<hipStream_t>(stream));
   return cc::check_launch(ctx, fn);
 }

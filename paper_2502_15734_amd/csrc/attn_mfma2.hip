@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
     const TileDesc* __restrict__ tiles, const int32_t* __restrict__ seg_tile_off, int max_tiles,
     const int32_t* __restrict__ order, const int32_t* __restrict__ req_seg_off, int hq, int hkv,
     int n_sub, int n_tiles_x, InvFreq inv_freq, bf16_t* __restrict__ out, float* __restrict__ lse,
-    int32_t* __restrict__ redo, const int32_t* __restrict__ q_map,
+    int32_t* __restrict__ redo, const int32_t* __restrict__ q_map, int map_pos,
     const int32_t* __restrict__ snap_index, float* __restrict__ cum, int s_max) {
   constexpr int TQ = 32 * QB;
   __shared__ uint4 lds_all[kBufs * kImage];
@@ -134,8 +134,8 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
   const int r = order[blockIdx.y];                           // longest contexts are dispatched first
   const int q0 = cu_q[r] + tile * TQ, q_end = cu_q[r + 1];
   if (q0 >= q_end) return;
-  // (with a row map, list row j takes its query and position from row q_map[j] of q and q_pos;
-  // results are always indexed by the list row)
+  // (with a row map, list row j takes its query from row q_map[j] of q - and, if map_pos, its
+  // position from q_pos[q_map[j]]; results are always indexed by the list row)
   int row[QB], src_row[QB], p[QB];
   bool row_valid[QB];
 #pragma unroll
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
     row[qb] = min(q0 + 32 * qb + n, q_end - 1);
     row_valid[qb] = q0 + 32 * qb + n < q_end;
     src_row[qb] = q_map != nullptr ? q_map[row[qb]] : row[qb];
-    p[qb] = q_pos[src_row[qb]];
+    p[qb] = q_pos[map_pos ? src_row[qb] : row[qb]];
   }
   int pmx = p[0], pmn = p[0];
 #pragma unroll
@@ -539,8 +539,8 @@ bool attn_v2_supported(const cc_ctx* ctx) {
 void launch_attn_v2(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
                     int max_q_per_req, const void* k_pool, const void* v_pool, int n_blocks,
                     const Plan& pl, const int32_t* req_seg_off, int n_requests, void* out, float* lse,
-                    int32_t* redo, const int32_t* q_map, const int32_t* snap_index, float* cum, int s_max,
-                    hipStream_t stream) {
+                    int32_t* redo, const int32_t* q_map, int map_pos, const int32_t* snap_index, float* cum,
+                    int s_max, hipStream_t stream) {
   constexpr int QB = 2;
   const int hkv = ctx->cfg.n_kv_heads, n_sub = ctx->cfg.n_q_heads / hkv / 4;
   const int n_tiles = (max_q_per_req + 32 * QB - 1) / (32 * QB);
@@ -548,7 +548,7 @@ void launch_attn_v2(const cc_ctx* ctx, const void* q, const int32_t* q_pos, cons
   hipLaunchKernelGGL((attn_v2_kernel<QB>), grid, dim3(256), 0, stream, static_cast<const bf16_t*>(q), q_pos,
                      cu_q, static_cast<const bf16_t*>(k_pool), static_cast<const bf16_t*>(v_pool), n_blocks,
                      pl.tiles, pl.seg_tile_off, pl.max_tiles, pl.order, req_seg_off, ctx->cfg.n_q_heads, hkv,
-                     n_sub, n_tiles, ctx->inv_freq, static_cast<bf16_t*>(out), lse, redo, q_map, snap_index, cum, s_max);
+                     n_sub, n_tiles, ctx->inv_freq, static_cast<bf16_t*>(out), lse, redo, q_map, map_pos, snap_index, cum, s_max);
 }
 
 }  // namespace cc

@@ -65,12 +65,12 @@ void launch_topn(const cc_ctx* ctx, const float* mass, const int32_t* block_tab,
 
 void launch_rope_scatter(const cc_ctx* ctx, const void* k_new, const void* v_new,
                          const int32_t* q_pos, const int32_t* slot_map, int n_q_tot, void* k_pool,
-                         void* v_pool, int n_blocks, hipStream_t stream);
+                         void* v_pool, int n_blocks, const int32_t* src_rows, hipStream_t stream);
 void launch_attn_scalar(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
                         int n_q_tot, int max_q_per_req, const void* k_pool, const void* v_pool,
                         int n_blocks, const int32_t* block_tab, const cc_segment* segs,
                         const int32_t* req_seg_off, int n_requests, void* out, float* lse,
-                        const int32_t* q_map, hipStream_t stream);
+                        const int32_t* q_map, int map_pos, hipStream_t stream);
 bool attn_mfma_supported(const cc_ctx* ctx);
 // By-product of the attention launch (optional): for rows with snap_index >= 0 the wide kernel
 // writes cum[snap row][head][segment's index in its request] = log-sum-exp over all keys up to the
@@ -87,7 +87,7 @@ void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, co
                       int n_q_tot, int max_q_per_req, const void* k_pool, const void* v_pool,
                       int n_blocks, const int32_t* block_tab, const cc_segment* segs, int n_segs,
                       const int32_t* req_seg_off, int n_requests, void* out, float* lse,
-                      void* plan_ws, int max_tiles, const int32_t* q_map, hipStream_t stream,
+                      void* plan_ws, int max_tiles, const int32_t* q_map, int map_pos, hipStream_t stream,
                       const AttnByProduct* by = nullptr);
 
 // attention mass of the question rows on every segment (focus.hip)

@@ -474,10 +474,10 @@ static void run_segment_list(const cc_ctx* ctx, const ListBuffers& b, const void
                      b.lse_seg);
   if (ctx->impl != CC_IMPL_SCALAR && attn_mfma_supported(ctx))
     launch_attn_mfma(ctx, q, q_pos, b.cu_v, cap, max_rows, k_pool, v_pool, n_blocks, block_tab, segs, n_segs,
-                     b.seg_iota, n_segs, nullptr, b.lse_seg, b.plan_ws, max_tiles, b.q_map, stream);
+                     b.seg_iota, n_segs, nullptr, b.lse_seg, b.plan_ws, max_tiles, b.q_map, 1, stream);
   else
     launch_attn_scalar(ctx, q, q_pos, b.cu_v, cap, max_rows, k_pool, v_pool, n_blocks, block_tab, segs,
-                       b.seg_iota, n_segs, nullptr, b.lse_seg, b.q_map, stream);
+                       b.seg_iota, n_segs, nullptr, b.lse_seg, b.q_map, 1, stream);
 }
 
 void launch_question_mass(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
@@ -572,10 +572,10 @@ void launch_prefill_mass(const cc_ctx* ctx, const void* q, const int32_t* q_pos,
     hipLaunchKernelGGL(fill_kernel, dim3(static_cast<unsigned>((n_cum + 255) / 256)), dim3(256), 0, stream, cum, n_cum,
                        -INFINITY);
     launch_attn_mfma(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab, segs,
-                     n_segs, req_seg_off, n_requests, out, lse, plan_ws, max_tiles, nullptr, stream, &by);
+                     n_segs, req_seg_off, n_requests, out, lse, plan_ws, max_tiles, nullptr, 0, stream, &by);
   } else {
     launch_attn_scalar(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab, segs,
-                       req_seg_off, n_requests, out, lse, nullptr, stream);
+                       req_seg_off, n_requests, out, lse, nullptr, 0, stream);
   }
   if (by.wide) {
     // rows the wide kernel flagged (normally none: every wavefront reads one flag and leaves)

@@ -78,7 +78,8 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
     const TileDesc* __restrict__ tiles, const int32_t* __restrict__ seg_tile_off, int max_tiles,
     const int32_t* __restrict__ order, const cc_segment* __restrict__ segs, const int32_t* __restrict__ req_seg_off, int hq, int hkv,
     int n_tiles_x, InvFreq inv_freq, bf16_t* __restrict__ out, float* __restrict__ lse,
-    float* __restrict__ mass, const int32_t* __restrict__ redo, const int32_t* __restrict__ q_map) {
+    float* __restrict__ mass, const int32_t* __restrict__ redo, const int32_t* __restrict__ q_map,
+    int map_pos) {
   constexpr int NT = 64 * G;
   constexpr int TQ = 32 * QB;                       // query tokens per workgroup
   constexpr bool kPrefetch = NT >= 256;
@@ -97,8 +98,8 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
   const int h = kvh * G + wave;
 
   // ---- which queries ------------------------------------------------------------------------
-  // (attention with a row map: list row j takes its query and position from row q_map[j] of q
-  // and q_pos; results are always indexed by the list row)
+  // (attention with a row map: list row j takes its query from row q_map[j] of q - and, if
+  // map_pos, its position from q_pos[q_map[j]]; results are always indexed by the list row)
   int row[QB], src_row[QB], p[QB], s_begin, s_end, s_self = -1;
   bool row_valid[QB];
   if constexpr (SCORE) {
@@ -130,7 +131,7 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
       row[qb] = min(q0 + 32 * qb + n, q_end - 1);
       row_valid[qb] = q0 + 32 * qb + n < q_end;
       src_row[qb] = q_map != nullptr ? q_map[row[qb]] : row[qb];
-      p[qb] = q_pos[src_row[qb]];
+      p[qb] = q_pos[map_pos ? src_row[qb] : row[qb]];
     }
     s_begin = req_seg_off[r];
     s_end = req_seg_off[r + 1];
@@ -616,14 +617,14 @@ void launch_attn_g(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const
                    int max_q_per_req, const void* k_pool, const void* v_pool, int n_blocks,
                    const Plan& pl, const cc_segment* segs, const int32_t* req_seg_off,
                    int n_requests, void* out, float* lse, const int32_t* redo, const int32_t* q_map,
-                   hipStream_t stream) {
+                   int map_pos, hipStream_t stream) {
   const int hkv = ctx->cfg.n_kv_heads, n_tiles = (max_q_per_req + 32 * kAttnQB - 1) / (32 * kAttnQB);
   dim3 grid(hkv * n_tiles, n_requests);
   hipLaunchKernelGGL((sparse_qk_kernel<G, false, kAttnQB>), grid, dim3(64 * G), 0, stream,
                      static_cast<const bf16_t*>(q), q_pos, cu_q, static_cast<const bf16_t*>(k_pool),
                      static_cast<const bf16_t*>(v_pool), n_blocks, pl.tiles, pl.seg_tile_off, pl.max_tiles,
                      pl.order, segs, req_seg_off, ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq,
-                     static_cast<bf16_t*>(out), lse, static_cast<float*>(nullptr), redo, q_map);
+                     static_cast<bf16_t*>(out), lse, static_cast<float*>(nullptr), redo, q_map, map_pos);
 }
 
 template <int G>
@@ -638,7 +639,7 @@ void launch_score_g(const cc_ctx* ctx, const void* q, const void* k_pool, int n_
                      static_cast<const bf16_t*>(nullptr), n_blocks, pl.tiles, pl.seg_tile_off, pl.max_tiles,
                      pl.order, segs, req_seg_off, ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq,
                      static_cast<bf16_t*>(nullptr), static_cast<float*>(nullptr), mass, redo,
-                     static_cast<const int32_t*>(nullptr));
+                     static_cast<const int32_t*>(nullptr), 0);
 }
 
 bool group_supported(const cc_ctx* ctx) {
@@ -697,7 +698,7 @@ void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, co
                       int n_q_tot, int max_q_per_req, const void* k_pool, const void* v_pool,
                       int n_blocks, const int32_t* block_tab, const cc_segment* segs, int n_segs,
                       const int32_t* req_seg_off, int n_requests, void* out, float* lse,
-                      void* plan_ws, int max_tiles, const int32_t* q_map, hipStream_t stream,
+                      void* plan_ws, int max_tiles, const int32_t* q_map, int map_pos, hipStream_t stream,
                       const AttnByProduct* by) {
   // Wide kernel first where the head group allows it; the narrow kernel then redoes the 64-row
   // tiles the wide one flagged (normally none: its workgroups read one flag and exit).
@@ -710,14 +711,14 @@ void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, co
   const Plan pl = run_plan(plan_ws, segs, n_segs, req_seg_off, n_requests, block_tab, n_blocks, max_tiles, n_redo, stream);
   if (wide)
     launch_attn_v2(ctx, q, q_pos, cu_q, max_q_per_req, k_pool, v_pool, n_blocks, pl, req_seg_off, n_requests,
-                   out, lse, pl.redo, q_map, by != nullptr ? by->snap_index : nullptr,
+                   out, lse, pl.redo, q_map, map_pos, by != nullptr ? by->snap_index : nullptr,
                    by != nullptr ? by->cum : nullptr, by != nullptr ? by->s_max : 0, stream);
   if (by != nullptr) {
     by->wide = wide;
     by->redo = pl.redo;
   }
   const int32_t* redo = pl.redo;
-#define CC_ARGS ctx, q, q_pos, cu_q, max_q_per_req, k_pool, v_pool, n_blocks, pl, segs, req_seg_off, n_requests, out, lse, redo, q_map, stream
+#define CC_ARGS ctx, q, q_pos, cu_q, max_q_per_req, k_pool, v_pool, n_blocks, pl, segs, req_seg_off, n_requests, out, lse, redo, q_map, map_pos, stream
   switch (ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads) {
     case 1: launch_attn_g<1>(CC_ARGS); break;
     case 2: launch_attn_g<2>(CC_ARGS); break;

@@ -204,8 +204,8 @@ inline size_t redo_entries(int n_q_tot) { return static_cast<size_t>(n_q_tot) / 
 void launch_attn_v2(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
                     int max_q_per_req, const void* k_pool, const void* v_pool, int n_blocks,
                     const Plan& pl, const int32_t* req_seg_off, int n_requests, void* out, float* lse,
-                    int32_t* redo, const int32_t* q_map, const int32_t* snap_index, float* cum, int s_max,
-                    hipStream_t stream);
+                    int32_t* redo, const int32_t* q_map, int map_pos, const int32_t* snap_index, float* cum,
+                    int s_max, hipStream_t stream);
 
 // The wide score kernel (128 tokens per wavefront, no softmax reference) flags 64-row granules of
 // the per-token tensors whose sums left the safe range; the narrow kernel redoes them.

@@ -50,7 +50,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void rope_scatter_kernel(
     const T* __restrict__ k_new, const T* __restrict__ v_new, const int32_t* __restrict__ q_pos,
     const int32_t* __restrict__ slot_map, int n_q_tot, int hkv, InvFreq inv_freq,
-    T* __restrict__ k_pool, T* __restrict__ v_pool, int n_blocks) {
+    T* __restrict__ k_pool, T* __restrict__ v_pool, int n_blocks, const int32_t* __restrict__ src_rows) {
   // slots of rows base-1 .. base+30: the row before the first candidate (is it the same block?) and
   // the 15 rows a run starting at the last candidate can still cover; -1 = no row / invalid slot
   __shared__ int sl[2 * kScatterRows];
@@ -79,7 +79,7 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(
       const int j = j0 + t;
       float cs, sn;
       rot_cos_sin(q_pos[j], inv_freq.f[i], &cs, &sn);
-      const T* kp = k_new + static_cast<size_t>(j) * hkv * D;
+      const T* kp = k_new + static_cast<size_t>(src_rows != nullptr ? src_rows[j] : j) * hkv * D;   // (row of k_new, v_new this list row reads)
       T* ko = k_pool + (static_cast<size_t>(blk) * hkv * kBlock + sl[c + 1 + t] % kBlock) * D;
       for (int h = 0; h < hkv; ++h) {
         const float x = to_float(kp[h * D + i]), y = to_float(kp[h * D + i + D / 2]);
@@ -98,7 +98,7 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(
         for (int v = 0; v < kVec; ++v) reinterpret_cast<uint4*>(e)[v] = rowp[v];
       }
       for (int t = 0; t < n_run; ++t) {
-        const T val = v_new[(static_cast<size_t>(j0 + t) * hkv + h) * D + dcol];
+        const T val = v_new[(static_cast<size_t>(src_rows != nullptr ? src_rows[j0 + t] : j0 + t) * hkv + h) * D + dcol];
         const int s_ = sl[c + 1 + t] % kBlock;
 #pragma unroll
         for (int k = 0; k < kBlock; ++k) if (k == s_) e[k] = val;
@@ -111,14 +111,14 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(
 
 void launch_rope_scatter(const cc_ctx* ctx, const void* k_new, const void* v_new,
                          const int32_t* q_pos, const int32_t* slot_map, int n_q_tot, void* k_pool,
-                         void* v_pool, int n_blocks, hipStream_t stream) {
+                         void* v_pool, int n_blocks, const int32_t* src_rows, hipStream_t stream) {
   if (n_q_tot <= 0) return;
   const bool bf = ctx->cfg.dtype == CC_BF16;
   const int d = ctx->cfg.head_dim, hkv = ctx->cfg.n_kv_heads;
 #define CC_LAUNCH(T, D)                                                                          \
   hipLaunchKernelGGL((rope_scatter_kernel<T, D>), dim3((n_q_tot + kScatterRows - 1) / kScatterRows), dim3(256), 0, stream,           \
                      static_cast<const T*>(k_new), static_cast<const T*>(v_new), q_pos, slot_map, \
-                     n_q_tot, hkv, ctx->inv_freq, static_cast<T*>(k_pool), static_cast<T*>(v_pool), n_blocks)
+                     n_q_tot, hkv, ctx->inv_freq, static_cast<T*>(k_pool), static_cast<T*>(v_pool), n_blocks, src_rows)
   if (bf && d == 128) CC_LAUNCH(bf16_t, 128);
   else if (bf && d == 64) CC_LAUNCH(bf16_t, 64);
   else if (!bf && d == 128) CC_LAUNCH(float, 128);
@@ -134,14 +134,15 @@ __global__ __launch_bounds__(64) void attn_scalar_kernel(
     int n_requests, const T* __restrict__ k_pool, const T* __restrict__ v_pool, int n_blocks,
     const int32_t* __restrict__ block_tab, const cc_segment* __restrict__ segs,
     const int32_t* __restrict__ req_seg_off, int hq, int hkv, InvFreq inv_freq,
-    T* __restrict__ out, float* __restrict__ lse, const int32_t* __restrict__ q_map) {
+    T* __restrict__ out, float* __restrict__ lse, const int32_t* __restrict__ q_map, int map_pos) {
   const int j = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
   int r = 0;
   while (r + 1 < n_requests && cu_q[r + 1] <= j) ++r;
   if (j >= cu_q[n_requests]) return;                 // (the list may be shorter than its capacity)
-  // with a row map, list row j takes its query and position from row q_map[j] of q and q_pos
+  // with a row map, list row j takes its query from row q_map[j] of q (and, if map_pos, its
+  // position from q_pos[q_map[j]])
   const int src = q_map != nullptr ? q_map[j] : j;
-  const int p = q_pos[src];
+  const int p = q_pos[map_pos ? src : j];
   const int kvh = h / (hq / hkv);
   const bool own = lane < D / 2;
   float qx = 0.f, qy = 0.f;
@@ -190,7 +191,7 @@ void launch_attn_scalar(const cc_ctx* ctx, const void* q, const int32_t* q_pos, 
                         int n_q_tot, int max_q_per_req, const void* k_pool, const void* v_pool,
                         int n_blocks, const int32_t* block_tab, const cc_segment* segs,
                         const int32_t* req_seg_off, int n_requests, void* out, float* lse,
-                        const int32_t* q_map, hipStream_t stream) {
+                        const int32_t* q_map, int map_pos, hipStream_t stream) {
   (void)max_q_per_req;
   if (n_q_tot <= 0) return;
   const bool bf = ctx->cfg.dtype == CC_BF16;
@@ -199,7 +200,7 @@ void launch_attn_scalar(const cc_ctx* ctx, const void* q, const int32_t* q_pos, 
   hipLaunchKernelGGL((attn_scalar_kernel<T, D>), dim3(n_q_tot, hq), dim3(64), 0, stream,        \
                      static_cast<const T*>(q), q_pos, cu_q, n_requests,                         \
                      static_cast<const T*>(k_pool), static_cast<const T*>(v_pool), n_blocks,    \
-                     block_tab, segs, req_seg_off, hq, hkv, ctx->inv_freq, static_cast<T*>(out), lse, q_map)
+                     block_tab, segs, req_seg_off, hq, hkv, ctx->inv_freq, static_cast<T*>(out), lse, q_map, map_pos)
   if (bf && d == 128) CC_LAUNCH(bf16_t, 128);
   else if (bf && d == 64) CC_LAUNCH(bf16_t, 64);
   else if (!bf && d == 128) CC_LAUNCH(float, 128);

@@ -22,12 +22,13 @@ def _dev(a: np.ndarray, dtype=None, device="cuda") -> torch.Tensor:
 
 class DeviceBatch:
     def __init__(self, w, device: str = "cuda", impl: int = CC_IMPL_AUTO, poison: bool = False,
-                 miss_segments=()):
+                 miss_segments=(), fused_gather: bool = True):
         """miss_segments: global indices of chunk segments that have NO chunk-cache in this batch: they
         are not shifted from the store; K, V of all their tokens are written into the request's pages
         (fill_miss) before the other chunks are scored."""
         sp = w.spec
         self.w = w
+        self.fused_gather = fused_gather
         self.device = device
         self.dt = torch.bfloat16 if sp.dtype == "bf16" else torch.float32
         self.ctx = Context(sp.n_q_heads, sp.n_kv_heads, sp.head_dim, sp.rope_theta,
@@ -161,6 +162,17 @@ class DeviceBatch:
             self.ctx.gather_rows(self.k_new, r(self.q_row), r(self.k_c))
             self.ctx.gather_rows(self.v_new, r(self.q_row), r(self.v_c))
 
+    def sparse_prefill_fused(self):
+        """cc_sparse_prefill straight on the per-token tensors, through cc_select's q_row list (no gather)."""
+        if self.n_q_tot == 0:
+            return
+        assert not self.projected
+        r = self._rows
+        self.ctx.sparse_prefill(self.q, self.k_new, self.v_new, self.q_pos, self.slot_map, self.cu_q,
+                                self.max_q_per_req, self.k_req, self.v_req, self.req_tab,
+                                self.segments, self.req_seg_off, self.n_requests, self.n_tok, r(self.out), self.lse,
+                                self.ws_prefill, src_rows=r(self.q_row))
+
     def sparse_prefill(self):
         if self.n_q_tot == 0:
             return
@@ -228,8 +240,11 @@ class DeviceBatch:
         self.rope_shift()
         self.fill_miss()
         self.select()
-        self.gather()
-        self.sparse_prefill()
+        if self.projected or not self.fused_gather:
+            self.gather()
+            self.sparse_prefill()
+        else:                      # q, k_new, v_new are given per token: read them through the row list
+            self.sparse_prefill_fused()
 
     # ---- test helper: impose a selection computed elsewhere ------------------------------------
     def set_selection(self, sel_idx: np.ndarray, q_row: np.ndarray, q_pos: np.ndarray, slot_map: np.ndarray):

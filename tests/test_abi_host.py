@@ -91,11 +91,11 @@ def test_calls_reject_bad_arguments_before_launch(lib):
     assert lib.cc_qkv_project(h, good, good, 4, 100, good, good, good, None) == -1
     # cc_sparse_prefill: null output, max_q_per_req > n_q_tot, empty query list
     ws = lib.cc_sparse_prefill_workspace_bytes(h, 100, 3)
-    args = [h, good, good, good, good, good, good, 10, 10, good, good, 8, good, good, 3, good, 1, 100]
+    args = [h, good, good, good, None, good, good, good, 10, 10, good, good, 8, good, good, 3, good, 1, 100]
     assert lib.cc_sparse_prefill(*args, None, None, good, ws, None) == -1
-    args[8] = 11
+    args[9] = 11
     assert lib.cc_sparse_prefill(*args, good, None, good, ws, None) == -1
-    args[7], args[8] = 0, 0
+    args[8], args[9] = 0, 0
     assert lib.cc_sparse_prefill(*args, good, None, good, ws, None) == 0
     # cc_scatter_kv: null pool, misaligned rows, nothing to do
     assert lib.cc_scatter_kv(h, good, good, good, good, 4, None, good, 8, None) == -1

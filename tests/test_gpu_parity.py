@@ -386,7 +386,8 @@ def test_reference_repair_path_when_later_keys_dwarf_the_first_tile(kval):
             t0, n = int(sg[W.SEG_TOK]), int(sg[W.SEG_NTOK])
             assert np.abs(sc[t0:t0 + n] - res[0].scores[c]).max() <= 5e-5, f"{impl}: scores of chunk {c}"
         # the question's masses, through the pass of its own and as a by-product (the rows whose
-        # reference overflowed take the scalar route there)
+        # reference overflowed take the scalar route there); both take the compact query rows
+        b.gather()
         check_question_mass(w, b, [ref.k_ctx])
         check_prefill_with_mass(w, b, [ref.k_ctx])
 
@@ -445,7 +446,9 @@ def test_full_size_configs_on_sampled_outputs(cid):
     from paper_2502_15734_amd.pipeline import DeviceBatch
     w = W.config(cid)
     b = DeviceBatch(w)
-    b.step(); torch.cuda.synchronize()
+    b.step()
+    b.gather()                                   # (compact query rows for the mass checks below)
+    torch.cuda.synchronize()
     rng = np.random.default_rng(100 + cid)
     sel = b.sel_idx.cpu().numpy(); scores = b.scores.cpu().numpy()
     out = b.out.float().cpu().numpy(); lse = b.lse.cpu().numpy()
