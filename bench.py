@@ -193,12 +193,15 @@ def time_extra_calls(batch, w, work, steps: int, ms_per_step: float, sparse_pref
     prefill_mass_ms = timed(batch.sparse_prefill_mass, steps)
     # inter / intra sums between all segments, over the rows of the last cc_sparse_prefill
     chunk_attention_ms = timed(batch.chunk_attention, max(1, min(steps, 5)))
+    # ... and the same sums as a by-product of cc_sparse_prefill's attention kernel
+    prefill_pairs_ms = timed(batch.sparse_prefill_pairs, steps)
     preload = time_layerwise_preload(batch, ms_per_step)
     layer_loop = time_layer_loop(w)
     return {"cc_select_from_scores": {"ms": from_scores_ms, "chunk_tokens": work["n_chunk_tok"]},
             "cc_question_mass": {"ms": question_mass_ms, "segments": int(len(w.segments))},
             "cc_sparse_prefill_mass": {"ms": prefill_mass_ms, "over_cc_sparse_prefill_ms": prefill_mass_ms - sparse_prefill_ms},
             "cc_chunk_attention": {"ms": chunk_attention_ms, "segment_pairs": int(batch.pair_off[-1])},
+            "cc_sparse_prefill_pairs": {"ms": prefill_pairs_ms, "over_cc_sparse_prefill_ms": prefill_pairs_ms - sparse_prefill_ms},
             "layerwise_preload": preload, "layer_loop": layer_loop}
 
 

@@ -250,6 +250,32 @@ int cc_sparse_prefill_mass(cc_ctx* ctx, const void* q, const void* k_new, const 
                            int32_t n_ctx_tokens, void* out, float* lse, float* seg_mass,
                            void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- (c3) partial prefill that also returns the segment-to-segment attention sums -----------
+ * cc_sparse_prefill (same steps, same out and lse, bit for bit) plus pair_mass and self_mass as
+ * cc_chunk_attention defines them and, if seg_mass is not NULL, seg_mass as cc_question_mass
+ * defines it (it is the row of the pair matrix that belongs to the request's question segment),
+ * in one call: the chunk-cache metadata of Sec. 3.4.3 at the cost of the prefill that produces
+ * the cache.  Where the 64-row MFMA kernel runs, the sums come from the by-product of
+ * cc_sparse_prefill_mass kept for EVERY row; otherwise from cc_chunk_attention's passes after the
+ * attention.  The by-product path needs the rows of segment s at [sel_off, sel_off + n_select) of
+ * the compact list, as cc_select lays them out.
+ *   lse is required.  pair_mass [n_pairs] and self_mass [n_segs] float, both required; n_pairs as
+ *   for cc_chunk_attention; max_segs_per_req: most segments of one request (host scalar).
+ *   workspace: cc_sparse_prefill_pairs_workspace_bytes(ctx, n_ctx_tokens, n_segs, n_q_tot,
+ *   max_q_per_req, max_segs_per_req); it holds max_segs_per_req floats per row and query head. */
+size_t cc_sparse_prefill_pairs_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_tokens, int32_t n_segs,
+                                               int32_t n_q_tot, int32_t max_q_per_req,
+                                               int32_t max_segs_per_req);
+int cc_sparse_prefill_pairs(cc_ctx* ctx, const void* q, const void* k_new, const void* v_new,
+                            const int32_t* q_pos, const int32_t* slot_map, const int32_t* cu_q,
+                            int32_t n_q_tot, int32_t max_q_per_req,
+                            void* k_pool, void* v_pool, int32_t n_blocks, const int32_t* block_tab,
+                            const cc_segment* segs, int32_t n_segs,
+                            const int32_t* req_seg_off, int32_t n_requests, int32_t max_segs_per_req,
+                            int32_t n_ctx_tokens, int32_t n_pairs, void* out, float* lse,
+                            float* seg_mass, float* pair_mass, float* self_mass,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- (c') step 1 of cc_sparse_prefill alone --------------------------------------------------
  * Rotates k_new[j] to position q_pos[j] and writes it, with v_new[j], into physical slot
  * slot_map[j] of the pools, for j < n_rows; nothing else.  For chunks that have NO chunk-cache

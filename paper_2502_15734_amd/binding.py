@@ -83,6 +83,11 @@ def load_library() -> C.CDLL:
     lib.cc_sparse_prefill_mass.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, i32, vp, vp, i32,
                                            vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.cc_sparse_prefill_mass.restype = C.c_int
+    lib.cc_sparse_prefill_pairs_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32]
+    lib.cc_sparse_prefill_pairs_workspace_bytes.restype = sz
+    lib.cc_sparse_prefill_pairs.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, vp, i32,
+                                            vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.cc_sparse_prefill_pairs.restype = C.c_int
     lib.cc_scatter_kv.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, i32, vp]
     lib.cc_scatter_kv.restype = C.c_int
     lib.cc_question_mass_workspace_bytes.argtypes = [vp, i32, i32, i32]
@@ -241,6 +246,20 @@ class Context:
             max_q_per_req, max_question_rows, _ptr(k_pool), _ptr(v_pool), k_pool.shape[0], _ptr(block_tab),
             _ptr(segs), segs.shape[0], _ptr(req_seg_off), n_requests, max_segs_per_req, n_ctx_tokens, _ptr(out),
             _ptr(lse), _ptr(seg_mass), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+    def sparse_prefill_pairs_workspace_bytes(self, n_ctx_tokens, n_segs, n_q_tot, max_q_per_req, max_segs_per_req):
+        return int(self._lib.cc_sparse_prefill_pairs_workspace_bytes(self._h, n_ctx_tokens, n_segs, n_q_tot,
+                                                                     max_q_per_req, max_segs_per_req))
+
+    def sparse_prefill_pairs(self, q, k_new, v_new, q_pos, slot_map, cu_q, max_q_per_req, k_pool, v_pool, block_tab,
+                             segs, req_seg_off, n_requests, max_segs_per_req, n_ctx_tokens, out, lse, seg_mass,
+                             pair_mass, self_mass, workspace):
+        self._check(self._lib.cc_sparse_prefill_pairs(
+            self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(q_pos), _ptr(slot_map), _ptr(cu_q), q.shape[0],
+            max_q_per_req, _ptr(k_pool), _ptr(v_pool), k_pool.shape[0], _ptr(block_tab), _ptr(segs), segs.shape[0],
+            _ptr(req_seg_off), n_requests, max_segs_per_req, n_ctx_tokens, pair_mass.shape[0], _ptr(out), _ptr(lse),
+            _ptr(seg_mass), _ptr(pair_mass), _ptr(self_mass), _ptr(workspace),
+            workspace.numel() * workspace.element_size(), _stream()))
 
     def scatter_kv(self, k_new, v_new, q_pos, slot_map, k_pool, v_pool):
         self._check(self._lib.cc_scatter_kv(self._h, _ptr(k_new), _ptr(v_new), _ptr(q_pos), _ptr(slot_map),

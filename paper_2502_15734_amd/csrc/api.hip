@@ -313,6 +313,62 @@ int cc_sparse_prefill_mass(cc_ctx* ctx, const void* q, const void* k_new, const 
   return cc::check_launch(ctx, fn);
 }
 
+size_t cc_sparse_prefill_pairs_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_tokens, int32_t n_segs,
+                                               int32_t n_q_tot, int32_t max_q_per_req,
+                                               int32_t max_segs_per_req) {
+  if (ctx == nullptr || n_ctx_tokens < 0 || n_segs < 0 || n_q_tot < 0 || max_q_per_req < 0 || max_segs_per_req < 0)
+    return 0;
+  return cc::prefill_pairs_bytes(ctx, n_ctx_tokens, n_segs, max_tiles_for(n_ctx_tokens, n_segs), n_q_tot,
+                                 max_q_per_req, max_segs_per_req) + 256;
+}
+
+int cc_sparse_prefill_pairs(cc_ctx* ctx, const void* q, const void* k_new, const void* v_new,
+                            const int32_t* q_pos, const int32_t* slot_map, const int32_t* cu_q,
+                            int32_t n_q_tot, int32_t max_q_per_req, void* k_pool, void* v_pool,
+                            int32_t n_blocks, const int32_t* block_tab, const cc_segment* segs,
+                            int32_t n_segs, const int32_t* req_seg_off, int32_t n_requests,
+                            int32_t max_segs_per_req, int32_t n_ctx_tokens, int32_t n_pairs, void* out,
+                            float* lse, float* seg_mass, float* pair_mass, float* self_mass,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+  static const char* fn = "cc_sparse_prefill_pairs";
+  if (ctx == nullptr) return CC_ERR_INVALID_ARG;
+  CC_REQUIRE(n_q_tot >= 0 && max_q_per_req >= 0 && n_segs >= 0 && n_requests >= 0 && n_ctx_tokens >= 0 &&
+                 max_segs_per_req >= 0 && n_pairs >= 0, "negative count");
+  CC_REQUIRE(max_q_per_req <= n_q_tot, "row bounds are inconsistent");
+  if (n_segs == 0) return CC_OK;
+  CC_REQUIRE(pair_mass != nullptr && self_mass != nullptr, "null pointer");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (n_q_tot == 0) {
+    if (n_pairs > 0) cc::launch_fill_zero(pair_mass, n_pairs, st);
+    cc::launch_fill_zero(self_mass, n_segs, st);
+    if (seg_mass != nullptr) cc::launch_fill_zero(seg_mass, n_segs, st);
+    return cc::check_launch(ctx, fn);
+  }
+  CC_REQUIRE(q && k_new && v_new && q_pos && slot_map && cu_q && k_pool && v_pool && block_tab &&
+                 segs && req_seg_off && out && lse, "null pointer (lse is required here)");
+  CC_REQUIRE(n_blocks > 0 && n_requests > 0 && max_q_per_req > 0 && max_segs_per_req > 0 && n_pairs > 0,
+             "sizes must be positive");
+  CC_REQUIRE(n_requests <= 65535 && n_segs <= 65535, "more than 65535 requests or segments in one call");
+  CC_REQUIRE(n_requests <= n_segs, "every request needs at least one segment");
+  CC_REQUIRE(n_q_tot <= n_ctx_tokens, "n_ctx_tokens must bound the rows of the compact list");
+  CC_REQUIRE(static_cast<int64_t>(n_segs) * max_q_per_req <= 0x3fffffff, "n_segs * max_q_per_req too large");
+  CC_REQUIRE(n_pairs >= n_segs, "n_pairs is smaller than the number of segments");
+  CC_REQUIRE(aligned16(q) && aligned16(k_new) && aligned16(v_new) && aligned16(k_pool) &&
+                 aligned16(v_pool) && aligned16(out), "tensors must be 16-byte aligned");
+  CC_REQUIRE(workspace != nullptr && aligned16(workspace), "workspace missing or misaligned");
+  if (workspace_bytes < cc_sparse_prefill_pairs_workspace_bytes(ctx, n_ctx_tokens, n_segs, n_q_tot,
+                                                                max_q_per_req, max_segs_per_req))
+    return fail(ctx, CC_ERR_WORKSPACE_TOO_SMALL,
+                "cc_sparse_prefill_pairs: workspace smaller than cc_sparse_prefill_pairs_workspace_bytes()");
+  cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_q_tot, k_pool, v_pool, n_blocks, nullptr, st);
+  cc::launch_fill_zero(pair_mass, n_pairs, st);               // pairs no row of the list falls into stay 0
+  cc::launch_prefill_pairs(ctx, q, q_pos, slot_map, cu_q, n_q_tot, max_q_per_req, max_segs_per_req, k_pool,
+                           v_pool, n_blocks, block_tab, segs, n_segs, req_seg_off, n_requests, n_ctx_tokens,
+                           out, lse, seg_mass, pair_mass, n_pairs, self_mass, workspace,
+                           max_tiles_for(n_ctx_tokens, n_segs), st);
+  return cc::check_launch(ctx, fn);
+}
+
 int cc_scatter_kv(cc_ctx* ctx, const void* k_new, const void* v_new, const int32_t* q_pos,
                   const int32_t* slot_map, int32_t n_rows, void* k_pool, void* v_pool, int32_t n_blocks,
                   void* stream) {

@@ -421,7 +421,7 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
   // on entry: parity 0 holds S of the tile's first block (masked) with the first half of its
   // exponentials done.  The last tile is peeled off, so the loop body is straight-line code apart
   // from the masking branches.
-  // By-product for rows that ask for it (snap_index >= 0; the question rows): when the tile that
+  // By-product for rows that ask for it (snap_index >= 0: the question rows; or every row): when the tile that
   // has just been closed is the last one of its segment, the log-sum-exp over all keys up to here
   // goes to cum[snap row][head][segment's index in its request].  The reference never moves in this
   // kernel, so these running sums subtract exactly.  (Rare: once per segment of the request.)
@@ -432,7 +432,7 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       const float tot = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
-      const int sr = snap_index[row[qb]];
+      const int sr = snap_index != nullptr ? snap_index[row[qb]] : row[qb];     // (no index: every row is a snap row)
       if (row_valid[qb] && hh == 0 && sr >= 0) {
         const float v = kLn2 * (m_ref[qb] + __builtin_amdgcn_logf(tot));
         for (int sl = max(seg - seg_first, 0); sl < min(seg_next - seg_first, s_max); ++sl)

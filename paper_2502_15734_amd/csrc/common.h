@@ -116,6 +116,16 @@ void launch_prefill_mass(const cc_ctx* ctx, const void* q, const int32_t* q_pos,
                          int n_segs, const int32_t* req_seg_off, int n_requests, int n_ctx_tokens, void* out,
                          float* lse, float* seg_mass, void* workspace, int max_tiles, hipStream_t stream);
 
+// ... and with the whole segment-to-segment matrix (every row's cumulative sums are kept)
+size_t prefill_pairs_bytes(const cc_ctx* ctx, int n_ctx_tokens, int n_segs, int max_tiles, int n_q_tot,
+                           int max_q_per_req, int s_max);
+void launch_prefill_pairs(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* slot_map,
+                          const int32_t* cu_q, int n_q_tot, int max_q_per_req, int s_max, const void* k_pool,
+                          const void* v_pool, int n_blocks, const int32_t* block_tab, const cc_segment* segs,
+                          int n_segs, const int32_t* req_seg_off, int n_requests, int n_ctx_tokens, void* out,
+                          float* lse, float* seg_mass, float* pair_mass, int n_pairs, float* self_mass,
+                          void* workspace, int max_tiles, hipStream_t stream);
+
 // attention for head groups that are a multiple of 4: 64 query rows per wavefront (attn_mfma2.hip)
 bool attn_v2_supported(const cc_ctx* ctx);
 // score stage for the same head groups: 128 tokens per wavefront (score_mfma2.hip)

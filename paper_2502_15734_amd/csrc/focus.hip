@@ -225,28 +225,44 @@ __global__ __launch_bounds__(256) void pair_mass_kernel(
 
 // self_mass[s] = (1/Hq) sum over the rows of the compact list that lie in segment s and over heads
 // of the weight the row puts on its own key: exp(q'.k_own / sqrt(d) - lse).  One wavefront per
-// (row, head); lane i owns rotation pair (i, i + d/2).  Written per row into row_self, then summed
-// per segment in a fixed order by self_sum_kernel.
+// row walks the heads; lane i owns rotation pair (i, i + d/2), whose angle it needs once per row.
+// The sum over heads is written per row into row_self, then summed per segment in a fixed order
+// by self_sum_kernel.
 template <typename T, int D>
 __global__ __launch_bounds__(64) void self_weight_kernel(
     const T* __restrict__ q, const int32_t* __restrict__ q_pos, const int32_t* __restrict__ slot_map,
     const T* __restrict__ k_pool, int n_blocks, int hq, int hkv, InvFreq inv_freq,
     const float* __restrict__ lse, float* __restrict__ row_self) {
-  const int j = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
+  const int j = blockIdx.x, lane = threadIdx.x;
   const int slot = slot_map[j];
-  float part = 0.f;
   const bool ok = slot >= 0 && slot / kBlock < n_blocks;
-  if (ok && lane < D / 2) {
-    const T* qp = q + (static_cast<size_t>(j) * hq + h) * D;
-    float x = to_float(qp[lane]), y = to_float(qp[lane + D / 2]), c, sn;
-    rot_cos_sin(q_pos[j], inv_freq.f[lane], &c, &sn);
-    const float qx = x * c - y * sn, qy = y * c + x * sn;
-    const int kvh = h / (hq / hkv);
-    const T* kp = k_pool + ((static_cast<size_t>(slot / kBlock) * hkv + kvh) * kBlock + slot % kBlock) * D;
-    part = qx * to_float(kp[lane]) + qy * to_float(kp[lane + D / 2]);
+  const bool own = lane < D / 2;
+  float c = 1.f, sn = 0.f;
+  if (ok && own) rot_cos_sin(q_pos[j], inv_freq.f[lane], &c, &sn);
+  const int group = hq / hkv;
+  float acc = 0.f;
+  if (ok) {
+    for (int kvh = 0; kvh < hkv; ++kvh) {
+      float kx = 0.f, ky = 0.f;
+      if (own) {
+        const T* kp = k_pool + ((static_cast<size_t>(slot / kBlock) * hkv + kvh) * kBlock + slot % kBlock) * D;
+        kx = to_float(kp[lane]);
+        ky = to_float(kp[lane + D / 2]);
+      }
+      for (int g = 0; g < group; ++g) {
+        const int h = kvh * group + g;
+        float part = 0.f;
+        if (own) {
+          const T* qp = q + (static_cast<size_t>(j) * hq + h) * D;
+          const float x = to_float(qp[lane]), y = to_float(qp[lane + D / 2]);
+          part = (x * c - y * sn) * kx + (y * c + x * sn) * ky;
+        }
+        const float logit = wave_sum(part) * rsqrtf(static_cast<float>(D));
+        acc += __expf(logit - lse[static_cast<size_t>(j) * hq + h]);
+      }
+    }
   }
-  const float logit = wave_sum(part) * rsqrtf(static_cast<float>(D));
-  if (lane == 0) row_self[static_cast<size_t>(j) * hq + h] = ok ? __expf(logit - lse[static_cast<size_t>(j) * hq + h]) : 0.f;
+  if (lane == 0) row_self[j] = acc;
 }
 
 __global__ __launch_bounds__(256) void self_sum_kernel(
@@ -257,9 +273,9 @@ __global__ __launch_bounds__(256) void self_sum_kernel(
   float acc = 0.f;
   if (sg.req >= 0 && sg.req < n_requests) {
     const int j0 = cu_q[sg.req], n = cu_q[sg.req + 1] - j0;
-    for (int i = threadIdx.x; i < n * hq; i += 256) {
-      const int u = i / hq, pos = q_pos[j0 + u];
-      if (pos >= sg.logical_start && pos < sg.logical_start + sg.n_tokens) acc += row_self[static_cast<size_t>(j0) * hq + i];
+    for (int u = threadIdx.x; u < n; u += 256) {
+      const int pos = q_pos[j0 + u];
+      if (pos >= sg.logical_start && pos < sg.logical_start + sg.n_tokens) acc += row_self[j0 + u];
     }
   }
   const float tot = block_sum_256(acc);
@@ -341,7 +357,12 @@ __global__ __launch_bounds__(64) void cum_scalar_kernel(
     InvFreq inv_freq, float* __restrict__ cum, int s_max) {
   const int u = blockIdx.x, lane = threadIdx.x;
   if (u >= snap_base[n_requests]) return;
-  const int j = snap_rows[u], r = snap_req[u];
+  // (no maps: every list row is a snap row, snap_base is cu_q itself)
+  const int j = snap_rows != nullptr ? snap_rows[u] : u;
+  int r = 0;
+  if (snap_req != nullptr) r = snap_req[u];
+  else
+    while (r + 1 < n_requests && cu_q[r + 1] <= j) ++r;
   if (redo != nullptr && redo[redo_index(cu_q[r] + ((j - cu_q[r]) / 64) * 64)] == 0) return;
   const int p = q_pos[j];
   const bool own = lane < D / 2;
@@ -406,6 +427,68 @@ __global__ __launch_bounds__(256) void seg_mass_from_cum_kernel(
   if (threadIdx.x == 0) seg_mass[s] = tot / static_cast<float>(hq);
 }
 
+// pair_mass from the cumulative log-sum-exps of EVERY row (snap row = list row): workgroup t sums,
+// over the rows of segment t (they sit at [sel_off, sel_off + n_select) of the list, as cc_select
+// lays them out) and all heads, the weight on each segment s <= t of the same request:
+// exp(cum_s - lse) - exp(cum_{s-1} - lse) for s < t, and what is left for s = t.
+__global__ __launch_bounds__(256) void pair_mass_from_cum_kernel(
+    const cc_segment* __restrict__ segs, const int32_t* __restrict__ req_seg_off, int n_requests, int n_q_tot,
+    int hq, const float* __restrict__ cum, int s_max, const float* __restrict__ lse,
+    float* __restrict__ pair_mass, int n_pairs) {
+  const int t = blockIdx.x, sl = blockIdx.y;               // (row segment, key segment's index in the request)
+  const cc_segment sg = segs[t];
+  const int r = sg.req;
+  if (r < 0 || r >= n_requests) return;
+  const int tl = t - req_seg_off[r];
+  if (sl > tl) return;
+  int pair_base = 0;
+  for (int r2 = 0; r2 < r; ++r2) {
+    const int n2 = req_seg_off[r2 + 1] - req_seg_off[r2];
+    pair_base += n2 * (n2 + 1) / 2;
+  }
+  const int row0 = max(sg.sel_off, 0), n_rows = max(min(sg.n_select, n_q_tot - row0), 0);
+  float acc = 0.f;
+  if (tl < s_max) {
+    for (int i = threadIdx.x; i < n_rows * hq; i += 256) {
+      const int u = row0 + i / hq, h = i % hq;
+      const float total = lse[static_cast<size_t>(u) * hq + h];
+      const float* c = cum + (static_cast<size_t>(u) * hq + h) * s_max;
+      const float upto = sl < tl ? __expf(c[sl] - total) : 1.f;
+      const float before = sl > 0 ? __expf(c[sl - 1] - total) : 0.f;
+      acc += upto - before;
+    }
+  }
+  const float tot = block_sum_256(acc);
+  const int pi = pair_base + tl * (tl + 1) / 2 + sl;
+  if (threadIdx.x == 0 && pi < n_pairs) pair_mass[pi] = tot / static_cast<float>(hq);
+}
+
+// seg_mass[s] = the entry of the pair matrix whose rows are the request's question segment
+__global__ __launch_bounds__(256) void seg_mass_from_pairs_kernel(
+    const cc_segment* __restrict__ segs, int n_segs, const int32_t* __restrict__ req_seg_off, int n_requests,
+    const float* __restrict__ pair_mass, int n_pairs, float* __restrict__ seg_mass) {
+  const int s = blockIdx.x * 256 + threadIdx.x;
+  if (s >= n_segs) return;
+  const int r = segs[s].req;
+  float v = 0.f;
+  if (r >= 0 && r < n_requests) {
+    int pair_base = 0;
+    for (int r2 = 0; r2 < r; ++r2) {
+      const int n2 = req_seg_off[r2 + 1] - req_seg_off[r2];
+      pair_base += n2 * (n2 + 1) / 2;
+    }
+    int tq = -1;                                           // the request's question segment (the last one of that kind)
+    for (int t = req_seg_off[r]; t < req_seg_off[r + 1]; ++t)
+      if (segs[t].kind == CC_SEG_QUESTION) tq = t - req_seg_off[r];
+    const int sl = s - req_seg_off[r];
+    if (tq >= sl) {
+      const int pi = pair_base + tq * (tq + 1) / 2 + sl;
+      if (pi < n_pairs) v = pair_mass[pi];
+    }
+  }
+  seg_mass[s] = v;
+}
+
 __global__ __launch_bounds__(256) void fill_kernel(float* __restrict__ p, size_t n, float v) {
   const size_t i = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
   if (i < n) p[i] = v;
@@ -427,7 +510,7 @@ void launch_fill_zero(float* p, int n, hipStream_t stream) {
 }
 
 // workspace: tile plan | m_seg[n_segs+1] | cu_v[n_segs+1] | seg_iota[n_segs+1] | q_map[cap] |
-//            row_seg[cap] | lse_seg[cap][Hq] | row_self[n_q_tot][Hq] (the last only for the pair matrix)
+//            row_seg[cap] | lse_seg[cap][Hq] | row_self[n_q_tot] (sized for Hq floats per row) (the last only for the pair matrix)
 size_t segment_mass_bytes(const cc_ctx* ctx, int n_segs, int max_tiles, int max_rows, int n_q_tot_self) {
   const size_t cap = static_cast<size_t>(n_segs) * max_rows;
   return up256(mfma_plan_bytes(n_segs, max_tiles, static_cast<int>(cap))) +
@@ -508,7 +591,7 @@ void launch_chunk_attention(const cc_ctx* ctx, const void* q, const int32_t* q_p
     const bool bf = ctx->cfg.dtype == CC_BF16;
     const int d = ctx->cfg.head_dim;
 #define CC_LAUNCH(T, D)                                                                              \
-  hipLaunchKernelGGL((self_weight_kernel<T, D>), dim3(n_q_tot, hq), dim3(64), 0, stream,             \
+  hipLaunchKernelGGL((self_weight_kernel<T, D>), dim3(n_q_tot), dim3(64), 0, stream,                 \
                      static_cast<const T*>(q), q_pos, slot_map, static_cast<const T*>(k_pool), n_blocks, \
                      hq, hkv, ctx->inv_freq, lse, b.row_self)
     if (bf && d == 128) CC_LAUNCH(bf16_t, 128);
@@ -598,6 +681,83 @@ void launch_prefill_mass(const cc_ctx* ctx, const void* q, const int32_t* q_pos,
     launch_question_mass(ctx, q, q_pos, cu_q, max_question_rows, k_pool, v_pool, n_blocks, block_tab, segs,
                          n_segs, req_seg_off, n_requests, lse, seg_mass, fallback_ws, max_tiles, stream);
   }
+}
+
+// workspace of the prefill that also returns the whole segment-to-segment matrix:
+//   tile plan of the attention | cum[n_q_tot][Hq][s_max] | row_self[n_q_tot] (sized for Hq floats per row) | workspace of launch_chunk_attention
+size_t prefill_pairs_bytes(const cc_ctx* ctx, int n_ctx_tokens, int n_segs, int max_tiles, int n_q_tot,
+                           int max_q_per_req, int s_max) {
+  const size_t hq = ctx->cfg.n_q_heads;
+  return up256(mfma_plan_bytes(n_segs, max_tiles, n_ctx_tokens)) +
+         up256(static_cast<size_t>(n_q_tot) * hq * s_max * sizeof(float)) +
+         up256(static_cast<size_t>(n_q_tot) * hq * sizeof(float)) +
+         segment_mass_bytes(ctx, n_segs, max_tiles, max_q_per_req, n_q_tot);
+}
+
+void launch_prefill_pairs(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* slot_map,
+                          const int32_t* cu_q, int n_q_tot, int max_q_per_req, int s_max, const void* k_pool,
+                          const void* v_pool, int n_blocks, const int32_t* block_tab, const cc_segment* segs,
+                          int n_segs, const int32_t* req_seg_off, int n_requests, int n_ctx_tokens, void* out,
+                          float* lse, float* seg_mass, float* pair_mass, int n_pairs, float* self_mass,
+                          void* workspace, int max_tiles, hipStream_t stream) {
+  const int hq = ctx->cfg.n_q_heads, hkv = ctx->cfg.n_kv_heads;
+  char* w = static_cast<char*>(workspace);
+  void* plan_ws = w;
+  w += up256(mfma_plan_bytes(n_segs, max_tiles, n_ctx_tokens));
+  float* cum = reinterpret_cast<float*>(w);
+  const size_t n_cum = static_cast<size_t>(n_q_tot) * hq * s_max;
+  w += up256(n_cum * sizeof(float));
+  float* row_self = reinterpret_cast<float*>(w);
+  w += up256(static_cast<size_t>(n_q_tot) * hq * sizeof(float));
+  void* fallback_ws = w;
+
+  const bool mfma = ctx->impl != CC_IMPL_SCALAR && attn_mfma_supported(ctx);
+  AttnByProduct by{nullptr, cum, s_max, false, nullptr};          // no index: every row is a snap row
+  if (mfma) {
+    hipLaunchKernelGGL(fill_kernel, dim3(static_cast<unsigned>((n_cum + 255) / 256)), dim3(256), 0, stream, cum, n_cum,
+                       -INFINITY);
+    launch_attn_mfma(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab, segs,
+                     n_segs, req_seg_off, n_requests, out, lse, plan_ws, max_tiles, nullptr, 0, stream, &by);
+  } else {
+    launch_attn_scalar(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab, segs,
+                       req_seg_off, n_requests, out, lse, nullptr, 0, stream);
+  }
+  const bool bf = ctx->cfg.dtype == CC_BF16;
+  const int d = ctx->cfg.head_dim;
+  if (by.wide) {
+#define CC_LAUNCH(T, D)                                                                                       \
+  hipLaunchKernelGGL((cum_scalar_kernel<T, D>), dim3(static_cast<unsigned>(n_q_tot)), dim3(64), 0, stream,     \
+                     static_cast<const T*>(q), q_pos, cu_q, cu_q, n_requests, static_cast<const int32_t*>(nullptr), \
+                     static_cast<const int32_t*>(nullptr), by.redo, static_cast<const T*>(k_pool), n_blocks,   \
+                     block_tab, segs, req_seg_off, hq, hkv, ctx->inv_freq, cum, s_max)
+    if (bf && d == 128) CC_LAUNCH(bf16_t, 128);
+    else if (bf && d == 64) CC_LAUNCH(bf16_t, 64);
+    else if (!bf && d == 128) CC_LAUNCH(float, 128);
+    else CC_LAUNCH(float, 64);
+#undef CC_LAUNCH
+    hipLaunchKernelGGL(pair_mass_from_cum_kernel, dim3(n_segs, s_max), dim3(256), 0, stream, segs, req_seg_off, n_requests,
+                       n_q_tot, hq, cum, s_max, lse, pair_mass, n_pairs);
+    if (self_mass != nullptr) {
+#define CC_LAUNCH(T, D)                                                                              \
+  hipLaunchKernelGGL((self_weight_kernel<T, D>), dim3(n_q_tot), dim3(64), 0, stream,                 \
+                     static_cast<const T*>(q), q_pos, slot_map, static_cast<const T*>(k_pool), n_blocks, \
+                     hq, hkv, ctx->inv_freq, lse, row_self)
+      if (bf && d == 128) CC_LAUNCH(bf16_t, 128);
+      else if (bf && d == 64) CC_LAUNCH(bf16_t, 64);
+      else if (!bf && d == 128) CC_LAUNCH(float, 128);
+      else CC_LAUNCH(float, 64);
+#undef CC_LAUNCH
+      hipLaunchKernelGGL(self_sum_kernel, dim3(n_segs), dim3(256), 0, stream, q_pos, cu_q, segs, n_requests, hq,
+                         row_self, self_mass);
+    }
+  } else {
+    launch_chunk_attention(ctx, q, q_pos, slot_map, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks,
+                           block_tab, segs, n_segs, req_seg_off, n_requests, lse, pair_mass, n_pairs, self_mass,
+                           fallback_ws, max_tiles, stream);
+  }
+  if (seg_mass != nullptr)
+    hipLaunchKernelGGL(seg_mass_from_pairs_kernel, dim3((n_segs + 255) / 256), dim3(256), 0, stream, segs, n_segs,
+                       req_seg_off, n_requests, pair_mass, n_pairs, seg_mass);
 }
 
 }  // namespace cc

@@ -219,20 +219,44 @@ class DeviceBatch:
                                self.lse, self.seg_mass, self.ws_mass)
         return self.seg_mass
 
-    def chunk_attention(self):
-        """Segment-to-segment attention sums of the last sparse_prefill's rows: (pair_mass, self_mass,
-        pair_off) with pair_off[r] the first pair of request r (pair (t, s) sits at t (t + 1) / 2 + s)."""
-        n_segs = int(self.segments.shape[0])
+    def _pair_buffers(self, n_segs):
         if not hasattr(self, "pair_mass"):
             n_r = np.diff(self.w.req_seg_off).astype(np.int64)
             self.pair_off = np.concatenate([[0], np.cumsum(n_r * (n_r + 1) // 2)])
             self.pair_mass = torch.zeros(max(1, int(self.pair_off[-1])), dtype=torch.float32, device=self.device)
             self.self_mass = torch.zeros(max(1, n_segs), dtype=torch.float32, device=self.device)
+
+    def chunk_attention(self):
+        """Segment-to-segment attention sums of the last sparse_prefill's rows: (pair_mass, self_mass,
+        pair_off) with pair_off[r] the first pair of request r (pair (t, s) sits at t (t + 1) / 2 + s)."""
+        n_segs = int(self.segments.shape[0])
+        self._pair_buffers(n_segs)
+        if not hasattr(self, "ws_pairs"):
             nbytes = self.ctx.chunk_attention_workspace_bytes(self.n_tok, n_segs, self.q_c.shape[0], self.max_q_per_req)
             self.ws_pairs = torch.empty(max(256, nbytes), dtype=torch.uint8, device=self.device)
         self.ctx.chunk_attention(self._rows(self.q_c), self.q_pos, self.slot_map, self.cu_q, self.max_q_per_req, self.k_req,
                                  self.v_req, self.req_tab, self.segments, self.req_seg_off, self.n_requests,
                                  self.n_tok, self.lse, self.pair_mass, self.self_mass, self.ws_pairs)
+        return self.pair_mass, self.self_mass, self.pair_off
+
+    def sparse_prefill_pairs(self):
+        """sparse_prefill and chunk_attention's sums (and the question's masses) in one call."""
+        n_segs = self._mass_buffers()
+        self._pair_buffers(n_segs)
+        if not hasattr(self, "ws_prefill_pairs"):
+            self.max_segs_per_req = int(np.diff(self.w.req_seg_off).max())
+            nbytes = self.ctx.sparse_prefill_pairs_workspace_bytes(self.n_tok, n_segs, self.q_c.shape[0],
+                                                                   self.max_q_per_req, self.max_segs_per_req)
+            self.ws_prefill_pairs = torch.empty(max(256, nbytes), dtype=torch.uint8, device=self.device)
+        if self.n_q_tot == 0:
+            self.pair_mass.zero_(); self.self_mass.zero_(); self.seg_mass.zero_()
+            return self.pair_mass, self.self_mass, self.pair_off
+        r = self._rows
+        self.ctx.sparse_prefill_pairs(r(self.q_c), r(self.k_c), r(self.v_c), self.q_pos, self.slot_map, self.cu_q,
+                                      self.max_q_per_req, self.k_req, self.v_req, self.req_tab, self.segments,
+                                      self.req_seg_off, self.n_requests, self.max_segs_per_req, self.n_tok,
+                                      r(self.out), self.lse, self.seg_mass, self.pair_mass, self.self_mass,
+                                      self.ws_prefill_pairs)
         return self.pair_mass, self.self_mass, self.pair_off
 
     def step(self):

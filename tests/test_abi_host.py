@@ -31,7 +31,8 @@ def test_every_declared_symbol_is_exported(lib):
             "cc_focus_create", "cc_focus_update", "cc_focus_destroy", "cc_focus_layer", "cc_chunk_attention",
             "cc_chunk_attention_workspace_bytes", "cc_chunk_ab", "cc_chunk_cci", "cc_chunk_reuse", "cc_preload_depth",
             "cc_preloader_create", "cc_preloader_set_layer", "cc_preloader_acquire", "cc_preloader_release",
-            "cc_preloader_issued", "cc_preloader_destroy"} <= set(names)
+            "cc_preloader_issued", "cc_preloader_destroy", "cc_sparse_prefill_mass", "cc_sparse_prefill_pairs",
+            "cc_sparse_prefill_pairs_workspace_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in cc.h but not exported"
 
@@ -122,6 +123,16 @@ def test_calls_reject_bad_arguments_before_launch(lib):
     ca[3] = good
     assert lib.cc_chunk_attention(*ca, 6, good, good, good, good, wc - 1, None) == -3
     assert lib.cc_chunk_attention(*ca, 0, good, good, good, good, wc, None) == 0
+    # cc_sparse_prefill_pairs: missing pair_mass, missing lse, too few pairs, tiny workspace, no segments
+    wp = lib.cc_sparse_prefill_pairs_workspace_bytes(h, 100, 3, 10, 10, 3)
+    assert wp >= 10 * 8 * 3 * 4
+    pa = [h, good, good, good, good, good, good, 10, 10, good, good, 8, good, good, 3, good, 1, 3, 100]
+    assert lib.cc_sparse_prefill_pairs(*pa, 6, good, good, good, None, good, good, wp, None) == -1
+    assert lib.cc_sparse_prefill_pairs(*pa, 6, good, None, good, good, good, good, wp, None) == -1
+    assert lib.cc_sparse_prefill_pairs(*pa, 2, good, good, good, good, good, good, wp, None) == -1
+    assert lib.cc_sparse_prefill_pairs(*pa, 6, good, good, None, good, good, good, wp - 1, None) == -3
+    pa[14] = 0
+    assert lib.cc_sparse_prefill_pairs(*pa, 6, good, good, good, good, good, good, wp, None) == 0
     # null context
     assert lib.cc_rope_shift(None, good, None, 4, good, None, 4, good, good, good, 1, 16, None) == -1
     assert lib.cc_set_impl(h, 99) == -1

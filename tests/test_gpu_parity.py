@@ -85,6 +85,7 @@ def check_workload(w, impl, score_tol=5e-5):
     check_question_mass(w, b, [res[r].k_ctx for r in range(w.n_requests)])
     check_chunk_attention(w, b, res)
     check_prefill_with_mass(w, b, [res[r].k_ctx for r in range(w.n_requests)])
+    check_prefill_with_pairs(w, b, res, [res[r].k_ctx for r in range(w.n_requests)])
 
     # ---- end to end with the library's own selection -----------------------------------------
     b2 = DeviceBatch(w, impl=impl, poison=True)
@@ -142,9 +143,30 @@ def check_chunk_attention(w, b, res):
     the oracle's inter / intra sums over the same rows."""
     pair, self_w, pair_off = b.chunk_attention()
     torch.cuda.synchronize()
-    pair = pair.cpu().numpy(); self_w = self_w.cpu().numpy()
+    check_pair_values(w, pair.cpu().numpy(), self_w.cpu().numpy(), pair_off, res)
+
+
+def check_prefill_with_pairs(w, b, res, k_ctx_of):
+    """cc_sparse_prefill_pairs on a batch that has just run cc_sparse_prefill: the attention results
+    must be the same bits; pair / self sums and the question's masses the oracle's."""
+    out1, lse1 = b.out.clone(), b.lse.clone()
+    b._mass_buffers()
+    b.seg_mass.fill_(float("nan"))
+    pair, self_w, pair_off = b.sparse_prefill_pairs()
+    pair_again = pair.clone()
+    torch.cuda.synchronize()
+    n = b.n_q_tot
+    assert torch.equal(out1[:n], b.out[:n]) and torch.equal(lse1[:n], b.lse[:n])
+    assert torch.isfinite(pair).all() and torch.isfinite(self_w).all() and torch.isfinite(b.seg_mass).all()
+    check_pair_values(w, pair.cpu().numpy(), self_w.cpu().numpy(), pair_off, res)
+    check_question_mass_values(w, b.seg_mass.cpu().numpy(), k_ctx_of)
+    b.sparse_prefill_pairs(); torch.cuda.synchronize()                  # same workspace, same answer
+    assert torch.equal(pair_again, b.pair_mass)
+
+
+def check_pair_values(w, pair, self_w, pair_off, res, requests=None):
     bf = w.spec.dtype == "bf16"
-    for r in range(w.n_requests):
+    for r in (range(w.n_requests) if requests is None else requests):
         s0, s1 = int(w.req_seg_off[r]), int(w.req_seg_off[r + 1])
         m, sw = O.segment_attention_matrix(w, r, res[r].k_ctx, res[r].q_pos, res[r].q_row)
         n_rows = np.zeros(s1 - s0)
@@ -501,6 +523,22 @@ def test_full_size_configs_on_sampled_outputs(cid):
         #    long for the oracle's row loops: there only the sums are checked)
         check_question_mass(w, b, {r: k_ctx}, requests=[r], exact=w.hidden is None)
         check_prefill_with_mass(w, b, {r: k_ctx}, requests=[r], exact=w.hidden is None)
+        # -- the segment-to-segment sums over all rows of the request, as a by-product of the
+        #    prefill (config 3; the other configurations' requests are too long for the oracle here)
+        if cid == 3:
+            from types import SimpleNamespace
+            pair, self_w, pair_off = b.sparse_prefill_pairs()
+            torch.cuda.synchronize()
+            assert torch.equal(torch.from_numpy(out).to(b.out.dtype), b.out[: out.shape[0]].cpu())
+            rows_r = SimpleNamespace(k_ctx=k_ctx, q_pos=b.q_pos.cpu().numpy()[q0:q1], q_row=b.q_row.cpu().numpy()[q0:q1])
+            check_pair_values(w, pair.cpu().numpy(), self_w.cpu().numpy(), pair_off, {r: rows_r}, requests=[r])
+    # the by-product and the passes of their own agree on every request, and each row's weights sum to 1
+    pair, self_w, pair_off = (t.clone() if torch.is_tensor(t) else t for t in b.sparse_prefill_pairs())
+    pair2, self_w2, _ = b.chunk_attention()
+    torch.cuda.synchronize()
+    assert (pair - pair2).abs().max().item() <= 2e-2 + 1e-3 * pair2.abs().max().item()
+    assert (self_w - self_w2).abs().max().item() <= 1e-3 * max(1.0, self_w2.abs().max().item())
+    assert abs(pair.sum().item() - b.n_q_tot) <= 3e-3 * b.n_q_tot
 
 
 class _SparseRows:
