@@ -62,6 +62,18 @@ And the reuse scores of Sec. 3.1 / 3.3, from the same attention weights:
           infinite ratio; CFO is clipped to [0, 1]; the ceiling carries the same 1e-9 guard as the
           workload generator's token budget.
 
+The rest of a layer, for the recomputed rows only (Sec. 2.1: the next hidden state comes from the
+token's own hidden state plus the feed-forward network applied to its attention output; Sec. 3.4.3:
+the attention output goes through the FFN to give the layer's output):
+
+  layer   the pre-normalised decoder layer of the models the paper runs (Llama-3):
+          x = rms_norm(h) -> Q, K, V -> attention -> h1 = h + o W_o^T ->
+          h2 = h1 + (silu(y W_gate^T) * (y W_up^T)) W_down^T with y = rms_norm(h1).
+          Reading: the paper writes the layer only in outline; the concrete operators are those
+          of the evaluated models (root-mean-square normalisation with a learned gain and eps
+          inside the root, gated SiLU feed-forward, no biases).  Only rows whose hidden state is
+          recomputed pass through it; every other token's K and V come from its chunk-cache.
+
 Parity pins (tests/test_oracle_pins.py): every function below is pinned by
 closed forms, invariants, limiting cases or brute force -- none is unpinned.
 The scoring *definition* (mean over heads, scores in the new context) is pinned
@@ -512,3 +524,36 @@ def qkv_project(hidden_rows: np.ndarray, w_qkv: np.ndarray, hq: int, hkv: int, d
     k = y[:, hq * d: (hq + hkv) * d].reshape(n, hkv, d)
     v = y[:, (hq + hkv) * d:].reshape(n, hkv, d)
     return q, k, v
+
+
+# --------------------------------------------------------------------------
+# the rest of the layer, for the recomputed rows (Sec. 2.1, Sec. 3.4.3)
+# --------------------------------------------------------------------------
+def rms_norm(x: np.ndarray, gain: np.ndarray, eps: float) -> np.ndarray:
+    """x / sqrt(mean(x^2) + eps) * gain over the last axis."""
+    x = np.asarray(x, dtype=np.float64)
+    return x / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + eps) * np.asarray(gain, dtype=np.float64)
+
+
+def linear(x: np.ndarray, w: np.ndarray) -> np.ndarray:
+    """x W^T with W [out_features, in_features]."""
+    return np.asarray(x, dtype=np.float64) @ np.asarray(w, dtype=np.float64).T
+
+
+def silu(x: np.ndarray) -> np.ndarray:
+    x = np.asarray(x, dtype=np.float64)
+    return x / (1.0 + np.exp(-x))
+
+
+def gated_ffn_in(y: np.ndarray, w_gate: np.ndarray, w_up: np.ndarray) -> np.ndarray:
+    """silu(y W_gate^T) * (y W_up^T): the input of the down projection."""
+    return silu(linear(y, w_gate)) * linear(y, w_up)
+
+
+def layer_tail(h_rows: np.ndarray, attn_out: np.ndarray, w_o, gain_ffn, w_gate, w_up, w_down, eps: float):
+    """Hidden state after the layer, for rows with hidden state h_rows [n, hidden] and attention
+    output attn_out [n, Hq, d]: h1 = h + o W_o^T, h2 = h1 + FFN(rms_norm(h1)).  Returns (h1, h2)."""
+    n = h_rows.shape[0]
+    h1 = np.asarray(h_rows, dtype=np.float64) + linear(np.asarray(attn_out, dtype=np.float64).reshape(n, -1), w_o)
+    h2 = h1 + linear(gated_ffn_in(rms_norm(h1, gain_ffn, eps), w_gate, w_up), w_down)
+    return h1, h2

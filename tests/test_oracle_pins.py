@@ -630,3 +630,75 @@ def test_layer_loop_drops_unfocused_chunks_after_the_stop():
     assert sizes[0] == sizes[1] == [10, 17, 8]
     assert sizes[2] == sizes[3] == [n if c in f else 0 for c, n in enumerate([10, 17, 8])]
     assert len(recs[2]["q_pos"]) == sum(sizes[2]) + 5                 # the question is always recomputed
+
+
+# ---- the rest of the layer (Sec. 2.1, Sec. 3.4.3) ---------------------------------------------------
+def test_rms_norm_against_the_library_routine_and_closed_forms():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((7, 48)); g = 1.0 + 0.1 * rng.standard_normal(48)
+    want = torch.nn.functional.rms_norm(torch.from_numpy(x), (48,), torch.from_numpy(g), eps=1e-5).numpy()
+    assert np.allclose(O.rms_norm(x, g, 1e-5), want, rtol=1e-12, atol=1e-14)
+    # a constant row has root mean square |c|: it comes out as sign(c) * gain (eps aside)
+    assert np.allclose(O.rms_norm(np.full((1, 48), -3.0), g, 0.0), -g)
+    # scale invariance without eps; with eps the zero row stays zero instead of dividing by zero
+    assert np.allclose(O.rms_norm(5.0 * x, g, 0.0), O.rms_norm(x, g, 0.0))
+    assert np.array_equal(O.rms_norm(np.zeros((2, 48)), g, 1e-5), np.zeros((2, 48)))
+    # eps sits inside the root: a row of ones gives gain / sqrt(1 + eps)
+    assert np.allclose(O.rms_norm(np.ones((1, 48)), g, 3.0), g / 2.0)
+
+
+def test_linear_is_x_times_w_transposed():
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal((5, 12)); w = rng.standard_normal((9, 12))
+    y = O.linear(x, w)
+    assert y.shape == (5, 9)
+    for i in range(5):
+        for o in range(9):
+            assert abs(y[i, o] - sum(x[i, c] * w[o, c] for c in range(12))) < 1e-12
+    # a transposed operand would fail here: W picks input feature 3 into output feature 0
+    w1 = np.zeros((2, 12)); w1[0, 3] = 1.0
+    assert np.array_equal(O.linear(x, w1)[:, 0], x[:, 3]) and not O.linear(x, w1)[:, 1].any()
+
+
+def test_silu_and_gated_ffn_input():
+    t = np.array([-30.0, -1.0, 0.0, 1.0, 30.0])
+    assert np.allclose(O.silu(t), torch.nn.functional.silu(torch.from_numpy(t)).numpy(), rtol=1e-13, atol=1e-15)
+    assert O.silu(np.array([0.0]))[0] == 0.0 and abs(O.silu(np.array([1.0]))[0] - 1.0 / (1.0 + math.exp(-1.0))) < 1e-15
+    rng = np.random.default_rng(7)
+    y = rng.standard_normal((4, 10)); wg = rng.standard_normal((6, 10)); wu = rng.standard_normal((6, 10))
+    a = O.gated_ffn_in(y, wg, wu)
+    for i in range(4):
+        for f in range(6):
+            gate, up = float(wg[f] @ y[i]), float(wu[f] @ y[i])
+            assert abs(a[i, f] - gate / (1.0 + math.exp(-gate)) * up) < 1e-12
+    # the activation is on the gate branch only: swapping the branches changes the result,
+    # a zero gate matrix switches the unit off, a zero up matrix too
+    assert not np.allclose(a, O.gated_ffn_in(y, wu, wg))
+    assert not O.gated_ffn_in(y, np.zeros_like(wg), wu).any() and not O.gated_ffn_in(y, wg, np.zeros_like(wu)).any()
+
+
+def test_layer_tail_residuals_and_a_library_layer():
+    rng = np.random.default_rng(8)
+    n, hq, d, hid, ffn = 6, 4, 8, 24, 40
+    h = rng.standard_normal((n, hid)); o = rng.standard_normal((n, hq, d))
+    w_o = rng.standard_normal((hid, hq * d)) * 0.2; g = 1.0 + 0.1 * rng.standard_normal(hid)
+    wg = rng.standard_normal((ffn, hid)) * 0.2; wu = rng.standard_normal((ffn, hid)) * 0.2
+    wd = rng.standard_normal((hid, ffn)) * 0.2
+    h1, h2 = O.layer_tail(h, o, w_o, g, wg, wu, wd, 1e-5)
+    # the same layer from the library's operators
+    T = torch.from_numpy
+    F = torch.nn.functional
+    t1 = T(h) + F.linear(T(o).reshape(n, -1), T(w_o))
+    y = F.rms_norm(t1, (hid,), T(g), eps=1e-5)
+    t2 = t1 + F.linear(F.silu(F.linear(y, T(wg))) * F.linear(y, T(wu)), T(wd))
+    assert np.allclose(h1, t1.numpy(), rtol=1e-12, atol=1e-13) and np.allclose(h2, t2.numpy(), rtol=1e-12, atol=1e-13)
+    # both residual connections: with no output projection and no down projection the state passes through
+    z1, z2 = O.layer_tail(h, o, np.zeros_like(w_o), g, wg, wu, np.zeros_like(wd), 1e-5)
+    assert np.array_equal(z1, h) and np.array_equal(z2, h)
+    # the second residual starts from h1, not from h
+    _, z2 = O.layer_tail(h, o, w_o, g, wg, wu, np.zeros_like(wd), 1e-5)
+    assert np.allclose(z2, h1)
+    # heads are concatenated head-major into the output projection's input
+    w_pick = np.zeros((hid, hq * d)); w_pick[0, 2 * d + 5] = 1.0
+    p1, _ = O.layer_tail(np.zeros_like(h), o, w_pick, g, wg, wu, np.zeros_like(wd), 1e-5)
+    assert np.allclose(p1[:, 0], o[:, 2, 5])

@@ -219,6 +219,35 @@ def build(spec: Spec) -> Workload:
         q=q, k_new=k_new, v_new=v_new, hidden=hidden, w_qkv=w_qkv)
 
 
+@dataclass
+class LayerWeights:
+    """Random weights of one decoder layer (row = output feature), drawn so that activations stay O(1)."""
+    gain_attn: np.ndarray        # [hidden]
+    gain_ffn: np.ndarray         # [hidden]
+    w_qkv: np.ndarray            # [(Hq+2Hkv)*d, hidden]
+    w_o: np.ndarray              # [hidden, Hq*d]
+    w_gate: np.ndarray           # [ffn, hidden]
+    w_up: np.ndarray             # [ffn, hidden]
+    w_down: np.ndarray           # [hidden, ffn]
+    eps: float
+
+
+def layer_weights(spec: Spec, hidden: int, ffn: int, layer: int = 0, qkv_scale: float = 0.02) -> LayerWeights:
+    """Weights of decoder layer `layer` for the given head geometry (seeded by spec.seed and layer)."""
+    Hq, Hkv, d = spec.n_q_heads, spec.n_kv_heads, spec.head_dim
+    ss = np.random.SeedSequence([spec.seed, 7919, layer]).spawn(7)
+    one = lambda a: round_to_bf16(np.float32(1.0) + a) if spec.dtype == "bf16" else (np.float32(1.0) + a).astype(np.float32)
+    return LayerWeights(
+        gain_attn=one(_draw(ss[0], (hidden,), 0.1, "f32")),
+        gain_ffn=one(_draw(ss[1], (hidden,), 0.1, "f32")),
+        w_qkv=_draw(ss[2], ((Hq + 2 * Hkv) * d, hidden), qkv_scale, spec.dtype),
+        w_o=_draw(ss[3], (hidden, Hq * d), 1.0 / math.sqrt(Hq * d), spec.dtype),
+        w_gate=_draw(ss[4], (ffn, hidden), 1.0 / math.sqrt(hidden), spec.dtype),
+        w_up=_draw(ss[5], (ffn, hidden), 1.0 / math.sqrt(hidden), spec.dtype),
+        w_down=_draw(ss[6], (hidden, ffn), 1.0 / math.sqrt(ffn), spec.dtype),
+        eps=1.0e-5)
+
+
 # ---------------------------------------------------------------------------
 # The five benchmark configurations, and scaled-down relatives for tests.
 # ---------------------------------------------------------------------------
