@@ -11,6 +11,8 @@
  *   cc_select_from_scores  keep the top N of scores the caller already has (Sec. 3.2.1)
  *   cc_gather_rows     compact the rows of the chosen tokens
  *   cc_qkv_project     Q, K, V of the chosen tokens only (Sec. 3.4.3)
+ *   cc_rms_norm, cc_linear, cc_gated_linear  the rest of a decoder layer for the chosen tokens:
+ *                      normalisation, output projection and feed-forward (Sec. 2.1, Sec. 3.4.3)
  *   cc_sparse_prefill  causal attention of the chosen tokens + question over the whole merged
  *                      paged KV, after writing their recomputed K, V into it
  *                      (Eq. (1), Sec. 3.4.3, Sec. 4 "Selective Token Recomputation")
@@ -197,6 +199,30 @@ int cc_gather_rows(cc_ctx* ctx, const void* src, int32_t n_src_rows, const int32
  * recomputation tokens). */
 int cc_qkv_project(cc_ctx* ctx, const void* x, const void* w_qkv, int32_t n_rows, int32_t hidden,
                    void* q, void* k, void* v, void* stream);
+
+/* ---- (b'') the rest of a decoder layer, for the rows that are recomputed ----------------------
+ * The hidden state of a recomputed token passes through the whole layer (Sec. 2.1: the next hidden
+ * state is the token's own plus the feed-forward network of its attention output; Sec. 3.4.3: the
+ * attention output goes through the FFN to give the layer output); the operators are those of the
+ * models the paper runs (Llama-3): with h the hidden states of the chosen rows,
+ *   x  = cc_rms_norm(h, gain_attn)               -> cc_qkv_project -> cc_sparse_prefill -> o
+ *   h1 = cc_linear(o, W_o, residual = h)
+ *   h2 = cc_linear(cc_gated_linear(cc_rms_norm(h1, gain_ffn), W_gate, W_up), W_down, residual = h1)
+ * All tensors are row-major in the context's dtype, weights [out_features][in_features], 16-byte
+ * aligned; sums are taken in fp32.
+ *   cc_rms_norm:     y[r][c] = x[r][c] / sqrt(mean_c(x[r][c]^2) + eps) * gain[c]; x, y [n_rows][hidden]
+ *                    (y may be x); hidden must be a multiple of 8 (bf16) / 4 (fp32).
+ *   cc_linear:       y [n_rows][n_out] = x [n_rows][n_in] W^T (+ residual [n_rows][n_out], or NULL;
+ *                    residual may be y itself, x may not).
+ *   cc_gated_linear: y [n_rows][n_ffn] = silu(x W_gate^T) * (x W_up^T), silu(t) = t / (1 + exp(-t)).
+ * bf16 with n_out (2 n_ffn for the gated form) a multiple of 256 and n_in a multiple of 32, at
+ * least 96: MFMA GEMM with 128 x 128 outputs per wavefront; otherwise a plain tiled kernel. */
+int cc_rms_norm(cc_ctx* ctx, const void* x, const void* gain, float eps, int32_t n_rows, int32_t hidden,
+                void* y, void* stream);
+int cc_linear(cc_ctx* ctx, const void* x, const void* w, const void* residual, int32_t n_rows,
+              int32_t n_in, int32_t n_out, void* y, void* stream);
+int cc_gated_linear(cc_ctx* ctx, const void* x, const void* w_gate, const void* w_up, int32_t n_rows,
+                    int32_t n_in, int32_t n_ffn, void* y, void* stream);
 
 /* ---- (c) partial prefill ------------------------------------------------------------------
  * For every row j < n_q_tot of the compact query list (requests delimited by cu_q):

@@ -78,6 +78,12 @@ def load_library() -> C.CDLL:
     lib.cc_sparse_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, vp, i32,
                                       vp, i32, i32, vp, vp, vp, sz, vp]
     lib.cc_sparse_prefill.restype = C.c_int
+    lib.cc_rms_norm.argtypes = [vp, vp, vp, C.c_float, i32, i32, vp, vp]
+    lib.cc_rms_norm.restype = C.c_int
+    lib.cc_linear.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp]
+    lib.cc_linear.restype = C.c_int
+    lib.cc_gated_linear.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp]
+    lib.cc_gated_linear.restype = C.c_int
     lib.cc_sparse_prefill_mass_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32]
     lib.cc_sparse_prefill_mass_workspace_bytes.restype = sz
     lib.cc_sparse_prefill_mass.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, i32, vp, vp, i32,
@@ -233,6 +239,21 @@ class Context:
             n_q_tot, max_q_per_req, _ptr(k_pool), _ptr(v_pool), k_pool.shape[0], _ptr(block_tab),
             _ptr(segs), segs.shape[0], _ptr(req_seg_off), n_requests, n_ctx_tokens, _ptr(out), _ptr(lse),
             _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+    # -- the rest of a decoder layer for the chosen rows ---------------------------------------------
+    def rms_norm(self, x, gain, eps, y):
+        self._check(self._lib.cc_rms_norm(self._h, _ptr(x), _ptr(gain), float(eps), x.shape[0], x.shape[1], _ptr(y),
+                                          _stream()))
+
+    def linear(self, x, w, y, residual=None):
+        """y = x w^T (+ residual); w [out_features, in_features]."""
+        self._check(self._lib.cc_linear(self._h, _ptr(x), _ptr(w), _ptr(residual), x.shape[0], w.shape[1], w.shape[0],
+                                        _ptr(y), _stream()))
+
+    def gated_linear(self, x, w_gate, w_up, y):
+        """y = silu(x w_gate^T) * (x w_up^T)."""
+        self._check(self._lib.cc_gated_linear(self._h, _ptr(x), _ptr(w_gate), _ptr(w_up), x.shape[0], w_gate.shape[1],
+                                              w_gate.shape[0], _ptr(y), _stream()))
 
     def sparse_prefill_mass_workspace_bytes(self, n_ctx_tokens, n_segs, n_requests, max_question_rows, max_segs_per_req):
         return int(self._lib.cc_sparse_prefill_mass_workspace_bytes(self._h, n_ctx_tokens, n_segs, n_requests,

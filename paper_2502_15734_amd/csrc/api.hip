@@ -209,6 +209,46 @@ int cc_qkv_project(cc_ctx* ctx, const void* x, const void* w_qkv, int32_t n_rows
   return cc::check_launch(ctx, fn);
 }
 
+int cc_rms_norm(cc_ctx* ctx, const void* x, const void* gain, float eps, int32_t n_rows, int32_t hidden,
+                void* y, void* stream) {
+  static const char* fn = "cc_rms_norm";
+  if (ctx == nullptr) return CC_ERR_INVALID_ARG;
+  CC_REQUIRE(n_rows >= 0 && hidden > 0, "bad sizes");
+  CC_REQUIRE(eps >= 0.f && eps == eps, "eps must not be negative");
+  CC_REQUIRE(hidden % (ctx->cfg.dtype == CC_BF16 ? 8 : 4) == 0, "hidden must be a multiple of 16 bytes of elements");
+  if (n_rows == 0) return CC_OK;
+  CC_REQUIRE(x && gain && y, "null pointer");
+  CC_REQUIRE(aligned16(x) && aligned16(gain) && aligned16(y), "tensors must be 16-byte aligned");
+  cc::launch_rms_norm(ctx, x, gain, eps, n_rows, hidden, y, static_cast<hipStream_t>(stream));
+  return cc::check_launch(ctx, fn);
+}
+
+int cc_linear(cc_ctx* ctx, const void* x, const void* w, const void* residual, int32_t n_rows,
+              int32_t n_in, int32_t n_out, void* y, void* stream) {
+  static const char* fn = "cc_linear";
+  if (ctx == nullptr) return CC_ERR_INVALID_ARG;
+  CC_REQUIRE(n_rows >= 0 && n_in > 0 && n_out > 0, "bad sizes");
+  if (n_rows == 0) return CC_OK;
+  CC_REQUIRE(x && w && y, "null pointer");
+  CC_REQUIRE(x != y, "x and y must not be the same tensor");
+  CC_REQUIRE(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(residual), "tensors must be 16-byte aligned");
+  cc::launch_linear(ctx, x, w, residual, n_rows, n_in, n_out, y, static_cast<hipStream_t>(stream));
+  return cc::check_launch(ctx, fn);
+}
+
+int cc_gated_linear(cc_ctx* ctx, const void* x, const void* w_gate, const void* w_up, int32_t n_rows,
+                    int32_t n_in, int32_t n_ffn, void* y, void* stream) {
+  static const char* fn = "cc_gated_linear";
+  if (ctx == nullptr) return CC_ERR_INVALID_ARG;
+  CC_REQUIRE(n_rows >= 0 && n_in > 0 && n_ffn > 0, "bad sizes");
+  if (n_rows == 0) return CC_OK;
+  CC_REQUIRE(x && w_gate && w_up && y, "null pointer");
+  CC_REQUIRE(x != y, "x and y must not be the same tensor");
+  CC_REQUIRE(aligned16(x) && aligned16(w_gate) && aligned16(w_up) && aligned16(y), "tensors must be 16-byte aligned");
+  cc::launch_gated_linear(ctx, x, w_gate, w_up, n_rows, n_in, n_ffn, y, static_cast<hipStream_t>(stream));
+  return cc::check_launch(ctx, fn);
+}
+
 size_t cc_sparse_prefill_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_tokens, int32_t n_segs) {
   if (ctx == nullptr || n_ctx_tokens < 0 || n_segs < 0) return 0;
   // queries are a subset of the context tokens, so n_ctx_tokens bounds the rows of the compact list

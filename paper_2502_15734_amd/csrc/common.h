@@ -133,5 +133,12 @@ bool score_v2_supported(const cc_ctx* ctx);
 
 void launch_qkv_project(const cc_ctx* ctx, const void* x, const void* w, int n_rows, int hidden,
                         void* q, void* k, void* v, hipStream_t stream);
+// the other dense products of a decoder layer, for the recomputed rows (Sec. 2.1, Sec. 3.4.3)
+void launch_linear(const cc_ctx* ctx, const void* x, const void* w, const void* residual, int n_rows, int n_in,
+                   int n_out, void* y, hipStream_t stream);
+void launch_gated_linear(const cc_ctx* ctx, const void* x, const void* w_gate, const void* w_up, int n_rows,
+                         int n_in, int n_ffn, void* y, hipStream_t stream);
+void launch_rms_norm(const cc_ctx* ctx, const void* x, const void* gain, float eps, int n_rows, int hidden, void* y,
+                     hipStream_t stream);
 
 }  // namespace cc

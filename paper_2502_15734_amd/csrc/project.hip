@@ -7,11 +7,24 @@
 // K-steps of 32 are double-buffered in LDS (2 x 32 KiB) with the next step's global loads held in
 // registers.  In the transposed product a lane holds 4 consecutive features of ONE token, so the
 // epilogue writes 8-byte pieces of an output row.  fp32 (and odd shapes): plain LDS-tiled kernel.
+//
+// The same GEMM kernels serve the other dense products of a decoder layer for the recomputed rows
+// (Sec. 2.1, Sec. 3.4.3): y = x W^T (+ residual) and the feed-forward input
+// silu(x W_gate^T) * (x W_up^T); only the epilogue and the rows of W a workgroup stages differ.
 #include <type_traits>
 
 #include "device_util.h"
 
 namespace cc {
+
+// what a GEMM kernel does with its accumulators
+enum { kOutQkv = 0, kOutLinear = 1, kOutGated = 2 };
+struct GemmOut {
+  void *o0, *o1, *o2;          // qkv: q, k, v; linear / gated: y in o0
+  const void* residual;        // linear: added to the product (may be y itself), or null
+  int nq, nk;                  // qkv: widths of q and of k (= v)
+  int width;                   // linear / gated: features of y
+};
 
 template <typename T>
 __device__ __forceinline__ void store_qkv(float v, int row, int col, int nq, int nk, T* q, T* k, T* vv) {
@@ -53,6 +66,57 @@ __global__ __launch_bounds__(256) void qkv_project_plain_kernel(
     for (int j = 0; j < 4; ++j) {
       const int r = row0 + ty * 4 + i, c = col0 + tx * 4 + j;
       if (r < n_rows && c < n_cols) store_qkv<T>(acc[i][j], r, c, nq, nk, q, k, v);
+    }
+}
+
+// ---- plain kernels of y = x W^T (+ residual) and of the gated feed-forward input ------------------
+template <typename T, bool GATED>
+__global__ __launch_bounds__(256) void linear_plain_kernel(
+    const T* __restrict__ x, const T* __restrict__ w, const T* __restrict__ w2, const T* residual,
+    int n_rows, int n_in, int n_out, T* y) {                      // (residual may be y itself)
+  __shared__ float xs[16][64 + 1];
+  __shared__ float ws[16][64 + 1];
+  __shared__ float us[GATED ? 16 : 1][64 + 1];
+  const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
+  const int row0 = blockIdx.y * 64, col0 = blockIdx.x * 64;
+  float acc[4][4] = {}, acc2[4][4] = {};
+  for (int k0 = 0; k0 < n_in; k0 += 16) {
+    for (int i = threadIdx.x; i < 64 * 16; i += 256) {
+      const int r = i / 16, kk = i % 16;
+      const bool kin = k0 + kk < n_in;
+      xs[kk][r] = (kin && row0 + r < n_rows) ? to_float(x[static_cast<size_t>(row0 + r) * n_in + k0 + kk]) : 0.f;
+      ws[kk][r] = (kin && col0 + r < n_out) ? to_float(w[static_cast<size_t>(col0 + r) * n_in + k0 + kk]) : 0.f;
+      if (GATED) us[kk][r] = (kin && col0 + r < n_out) ? to_float(w2[static_cast<size_t>(col0 + r) * n_in + k0 + kk]) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      float a[4], b[4], c[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        a[i] = xs[kk][ty * 4 + i];
+        b[i] = ws[kk][tx * 4 + i];
+        c[i] = GATED ? us[kk][tx * 4 + i] : 0.f;
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          acc[i][j] += a[i] * b[j];
+          if (GATED) acc2[i][j] += a[i] * c[j];
+        }
+    }
+    __syncthreads();
+  }
+  for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < 4; ++j) {
+      const int r = row0 + ty * 4 + i, c = col0 + tx * 4 + j;
+      if (r >= n_rows || c >= n_out) continue;
+      const size_t at = static_cast<size_t>(r) * n_out + c;
+      float v = acc[i][j];
+      if (GATED) v = v / (1.f + expf(-v)) * acc2[i][j];
+      else if (residual != nullptr) v += to_float(residual[at]);
+      y[at] = from_float<T>(v);
     }
 }
 
@@ -176,9 +240,10 @@ __device__ __forceinline__ void gemm_mfma(f32x16& d, const u32x4& a, const u32x4
 constexpr int kStages = 4;
 constexpr int kStageBytes = 32 * 1024;      // 32 operand groups of 1 KiB: W blocks 0..7 x 2 k-steps, x blocks 0..7 x 2 k-steps
 
-__global__ __launch_bounds__(256, 1) void qkv_project_mfma2_kernel(
-    const bf16_t* __restrict__ x, const bf16_t* __restrict__ w, int n_rows, int hidden, int nq, int nk,
-    bf16_t* __restrict__ q, bf16_t* __restrict__ k, bf16_t* __restrict__ v) {
+template <int MODE>
+__global__ __launch_bounds__(256, 1) void gemm_mfma2_kernel(
+    const bf16_t* __restrict__ x, const bf16_t* __restrict__ w, const bf16_t* __restrict__ w2, int n_rows,
+    int hidden, GemmOut out) {
   __shared__ uint4 lds[kStages * kStageBytes / 16];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -195,8 +260,15 @@ __global__ __launch_bounds__(256, 1) void qkv_project_mfma2_kernel(
   for (int j = 0; j < 8; ++j) {
     const int g = 8 * wave + j, blk = (g & 15) >> 1, step = g & 1;
     const int r = 32 * blk + nl;
-    const bf16_t* row = g < 16 ? w + static_cast<size_t>(n0 + r) * hidden
-                               : x + static_cast<size_t>(min(m0 + r, n_rows - 1)) * hidden;
+    const bf16_t* row;
+    if (g >= 16) row = x + static_cast<size_t>(min(m0 + r, n_rows - 1)) * hidden;
+    else if (MODE != kOutGated) row = w + static_cast<size_t>(n0 + r) * hidden;
+    else {
+      // gated: of a wavefront's four feature blocks, two are rows of W_gate and two the SAME rows
+      // of W_up, so that a lane ends up holding both factors of an output
+      const int f = n0 / 2 + 64 * (blk >> 2) + 32 * (blk & 1) + nl;
+      row = ((blk & 2) ? w2 : w) + static_cast<size_t>(f) * hidden;
+    }
     src[j] = reinterpret_cast<const char*>(row + 16 * step + 8 * hh);
   }
   typedef __attribute__((address_space(3))) const uint4 lds_piece;
@@ -273,20 +345,47 @@ __global__ __launch_bounds__(256, 1) void qkv_project_mfma2_kernel(
   for (int b = 0; b < 4; ++b) {
     const int row = m0 + wm * 128 + b * 32 + nl;
     if (row >= n_rows) continue;
+    if (MODE == kOutGated) {
+#pragma unroll
+      for (int a = 0; a < 2; ++a) {
+        bf16_t* op = static_cast<bf16_t*>(out.o0) + static_cast<size_t>(row) * out.width + n0 / 2 + wn * 64 + a * 32 + 4 * hh;
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          bf16_t v4[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float gate = acc[a][b][4 * g4 + e], up = acc[a + 2][b][4 * g4 + e];
+            v4[e] = static_cast<bf16_t>(gate / (1.f + __expf(-gate)) * up);
+          }
+          *reinterpret_cast<uint2*>(op + 8 * g4) = *reinterpret_cast<uint2*>(v4);
+        }
+      }
+      continue;
+    }
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
       const int col0 = n0 + wn * 128 + a * 32;        // a 32-feature block never straddles q | k | v
       bf16_t* base;
       int c_in, width;
-      if (col0 < nq) { base = q; c_in = col0; width = nq; }
-      else if (col0 < nq + nk) { base = k; c_in = col0 - nq; width = nk; }
-      else { base = v; c_in = col0 - nq - nk; width = nk; }
-      bf16_t* op = base + static_cast<size_t>(row) * width + c_in + 4 * hh;
+      if (MODE == kOutLinear) { base = static_cast<bf16_t*>(out.o0); c_in = col0; width = out.width; }
+      else if (col0 < out.nq) { base = static_cast<bf16_t*>(out.o0); c_in = col0; width = out.nq; }
+      else if (col0 < out.nq + out.nk) { base = static_cast<bf16_t*>(out.o1); c_in = col0 - out.nq; width = out.nk; }
+      else { base = static_cast<bf16_t*>(out.o2); c_in = col0 - out.nq - out.nk; width = out.nk; }
+      const size_t at = static_cast<size_t>(row) * width + c_in + 4 * hh;
+      bf16_t* op = base + at;
+      const bf16_t* rp = MODE == kOutLinear && out.residual != nullptr ? static_cast<const bf16_t*>(out.residual) + at : nullptr;
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
         bf16_t v4[4];
+        if (rp != nullptr) {
+          bf16_t r4[4];
+          *reinterpret_cast<uint2*>(r4) = *reinterpret_cast<const uint2*>(rp + 8 * g4);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v4[e] = static_cast<bf16_t>(acc[a][b][4 * g4 + e]);
+          for (int e = 0; e < 4; ++e) v4[e] = static_cast<bf16_t>(acc[a][b][4 * g4 + e] + static_cast<float>(r4[e]));
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v4[e] = static_cast<bf16_t>(acc[a][b][4 * g4 + e]);
+        }
         *reinterpret_cast<uint2*>(op + 8 * g4) = *reinterpret_cast<uint2*>(v4);
       }
     }
@@ -303,9 +402,9 @@ void launch_qkv_project(const cc_ctx* ctx, const void* x, const void* w, int n_r
       nq % 32 == 0 && nk % 32 == 0) {
     dim3 grid(n_cols / kTN, (n_rows + kTM - 1) / kTM);
     if (hidden / kTK >= 3 && ctx->impl != CC_IMPL_MFMA_NARROW) {
-      hipLaunchKernelGGL(qkv_project_mfma2_kernel, grid, dim3(256), 0, stream,
-                         static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(w), n_rows, hidden, nq, nk,
-                         static_cast<bf16_t*>(q), static_cast<bf16_t*>(k), static_cast<bf16_t*>(v));
+      hipLaunchKernelGGL(gemm_mfma2_kernel<kOutQkv>, grid, dim3(256), 0, stream, static_cast<const bf16_t*>(x),
+                         static_cast<const bf16_t*>(w), static_cast<const bf16_t*>(nullptr), n_rows, hidden,
+                         GemmOut{q, k, v, nullptr, nq, nk, 0});
       return;
     }
     hipLaunchKernelGGL(qkv_project_mfma_kernel, grid, dim3(512), 0, stream,
@@ -324,6 +423,101 @@ void launch_qkv_project(const cc_ctx* ctx, const void* x, const void* w, int n_r
                        static_cast<const float*>(x), static_cast<const float*>(w), n_rows, hidden,
                        n_cols, nq, nk, static_cast<float*>(q), static_cast<float*>(k),
                        static_cast<float*>(v));
+}
+
+// y [n_rows][n_out] = x [n_rows][n_in] W^T (+ residual [n_rows][n_out]); W [n_out][n_in]
+void launch_linear(const cc_ctx* ctx, const void* x, const void* w, const void* residual, int n_rows, int n_in,
+                   int n_out, void* y, hipStream_t stream) {
+  const bool bf = ctx->cfg.dtype == CC_BF16;
+  if (bf && ctx->impl != CC_IMPL_SCALAR && ctx->impl != CC_IMPL_MFMA_NARROW && n_out % kTN == 0 && n_in % kTK == 0 &&
+      n_in / kTK >= 3) {
+    dim3 grid(n_out / kTN, (n_rows + kTM - 1) / kTM);
+    hipLaunchKernelGGL(gemm_mfma2_kernel<kOutLinear>, grid, dim3(256), 0, stream, static_cast<const bf16_t*>(x),
+                       static_cast<const bf16_t*>(w), static_cast<const bf16_t*>(nullptr), n_rows, n_in,
+                       GemmOut{y, nullptr, nullptr, residual, 0, 0, n_out});
+    return;
+  }
+  dim3 grid((n_out + 63) / 64, (n_rows + 63) / 64);
+  if (bf)
+    hipLaunchKernelGGL((linear_plain_kernel<bf16_t, false>), grid, dim3(256), 0, stream, static_cast<const bf16_t*>(x),
+                       static_cast<const bf16_t*>(w), static_cast<const bf16_t*>(nullptr),
+                       static_cast<const bf16_t*>(residual), n_rows, n_in, n_out, static_cast<bf16_t*>(y));
+  else
+    hipLaunchKernelGGL((linear_plain_kernel<float, false>), grid, dim3(256), 0, stream, static_cast<const float*>(x),
+                       static_cast<const float*>(w), static_cast<const float*>(nullptr),
+                       static_cast<const float*>(residual), n_rows, n_in, n_out, static_cast<float*>(y));
+}
+
+// y [n_rows][n_ffn] = silu(x W_gate^T) * (x W_up^T); both W [n_ffn][n_in]
+void launch_gated_linear(const cc_ctx* ctx, const void* x, const void* w_gate, const void* w_up, int n_rows,
+                         int n_in, int n_ffn, void* y, hipStream_t stream) {
+  const bool bf = ctx->cfg.dtype == CC_BF16;
+  if (bf && ctx->impl != CC_IMPL_SCALAR && ctx->impl != CC_IMPL_MFMA_NARROW && (2 * n_ffn) % kTN == 0 &&
+      n_in % kTK == 0 && n_in / kTK >= 3) {
+    dim3 grid(2 * n_ffn / kTN, (n_rows + kTM - 1) / kTM);
+    hipLaunchKernelGGL(gemm_mfma2_kernel<kOutGated>, grid, dim3(256), 0, stream, static_cast<const bf16_t*>(x),
+                       static_cast<const bf16_t*>(w_gate), static_cast<const bf16_t*>(w_up), n_rows, n_in,
+                       GemmOut{y, nullptr, nullptr, nullptr, 0, 0, n_ffn});
+    return;
+  }
+  dim3 grid((n_ffn + 63) / 64, (n_rows + 63) / 64);
+  if (bf)
+    hipLaunchKernelGGL((linear_plain_kernel<bf16_t, true>), grid, dim3(256), 0, stream, static_cast<const bf16_t*>(x),
+                       static_cast<const bf16_t*>(w_gate), static_cast<const bf16_t*>(w_up),
+                       static_cast<const bf16_t*>(nullptr), n_rows, n_in, n_ffn, static_cast<bf16_t*>(y));
+  else
+    hipLaunchKernelGGL((linear_plain_kernel<float, true>), grid, dim3(256), 0, stream, static_cast<const float*>(x),
+                       static_cast<const float*>(w_gate), static_cast<const float*>(w_up),
+                       static_cast<const float*>(nullptr), n_rows, n_in, n_ffn, static_cast<float*>(y));
+}
+
+// ---- root-mean-square normalisation: y = x / sqrt(mean(x^2) + eps) * gain ---------------------------
+// One wavefront per row (four rows per workgroup); the row is read twice, the second time from
+// cache, so the kernel moves each row once in and once out of HBM.
+template <typename T>
+__global__ __launch_bounds__(256) void rms_norm_kernel(const T* x, const T* __restrict__ gain, float eps,
+                                                       int n_rows, int hidden, T* y) {          // (y may be x)
+  const int row = blockIdx.x * 4 + threadIdx.x / 64, lane = threadIdx.x % 64;
+  if (row >= n_rows) return;
+  constexpr int kPer = 16 / sizeof(T);                 // elements per 16-byte piece
+  const T* xr = x + static_cast<size_t>(row) * hidden;
+  T* yr = y + static_cast<size_t>(row) * hidden;
+  const bool wide = hidden % kPer == 0;                // rows then start on 16-byte boundaries (the call checks the bases)
+  float ss = 0.f;
+  if (wide) {
+    for (int p = lane; p < hidden / kPer; p += 64) {
+      T v[kPer];
+      *reinterpret_cast<uint4*>(v) = *reinterpret_cast<const uint4*>(xr + p * kPer);
+#pragma unroll
+      for (int e = 0; e < kPer; ++e) ss += to_float(v[e]) * to_float(v[e]);
+    }
+  } else {
+    for (int c = lane; c < hidden; c += 64) ss += to_float(xr[c]) * to_float(xr[c]);
+  }
+  const float scale = rsqrtf(wave_sum(ss) / static_cast<float>(hidden) + eps);
+  if (wide) {
+    for (int p = lane; p < hidden / kPer; p += 64) {
+      T v[kPer], g[kPer], o[kPer];
+      *reinterpret_cast<uint4*>(v) = *reinterpret_cast<const uint4*>(xr + p * kPer);
+      *reinterpret_cast<uint4*>(g) = *reinterpret_cast<const uint4*>(gain + p * kPer);
+#pragma unroll
+      for (int e = 0; e < kPer; ++e) o[e] = from_float<T>(to_float(v[e]) * scale * to_float(g[e]));
+      *reinterpret_cast<uint4*>(yr + p * kPer) = *reinterpret_cast<uint4*>(o);
+    }
+  } else {
+    for (int c = lane; c < hidden; c += 64) yr[c] = from_float<T>(to_float(xr[c]) * scale * to_float(gain[c]));
+  }
+}
+
+void launch_rms_norm(const cc_ctx* ctx, const void* x, const void* gain, float eps, int n_rows, int hidden, void* y,
+                     hipStream_t stream) {
+  const dim3 grid((n_rows + 3) / 4);
+  if (ctx->cfg.dtype == CC_BF16)
+    hipLaunchKernelGGL(rms_norm_kernel<bf16_t>, grid, dim3(256), 0, stream, static_cast<const bf16_t*>(x),
+                       static_cast<const bf16_t*>(gain), eps, n_rows, hidden, static_cast<bf16_t*>(y));
+  else
+    hipLaunchKernelGGL(rms_norm_kernel<float>, grid, dim3(256), 0, stream, static_cast<const float*>(x),
+                       static_cast<const float*>(gain), eps, n_rows, hidden, static_cast<float*>(y));
 }
 
 }  // namespace cc

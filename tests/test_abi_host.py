@@ -32,7 +32,7 @@ def test_every_declared_symbol_is_exported(lib):
             "cc_chunk_attention_workspace_bytes", "cc_chunk_ab", "cc_chunk_cci", "cc_chunk_reuse", "cc_preload_depth",
             "cc_preloader_create", "cc_preloader_set_layer", "cc_preloader_acquire", "cc_preloader_release",
             "cc_preloader_issued", "cc_preloader_destroy", "cc_sparse_prefill_mass", "cc_sparse_prefill_pairs",
-            "cc_sparse_prefill_pairs_workspace_bytes"} <= set(names)
+            "cc_sparse_prefill_pairs_workspace_bytes", "cc_rms_norm", "cc_linear", "cc_gated_linear"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in cc.h but not exported"
 
@@ -133,6 +133,19 @@ def test_calls_reject_bad_arguments_before_launch(lib):
     assert lib.cc_sparse_prefill_pairs(*pa, 6, good, good, None, good, good, good, wp - 1, None) == -3
     pa[14] = 0
     assert lib.cc_sparse_prefill_pairs(*pa, 6, good, good, good, good, good, good, wp, None) == 0
+    other = C.c_void_p(8192)
+    # the dense operators of the layer: null tensors, x == y, hidden off the 16-byte grid, negative eps, no rows
+    assert lib.cc_rms_norm(h, good, None, 1e-5, 4, 64, good, None) == -1
+    assert lib.cc_rms_norm(h, good, good, 1e-5, 4, 63, good, None) == -1
+    assert lib.cc_rms_norm(h, good, good, -1.0, 4, 64, good, None) == -1
+    assert lib.cc_rms_norm(h, good, good, 1e-5, 0, 64, good, None) == 0
+    assert lib.cc_linear(h, good, good, None, 4, 64, 64, good, None) == -1
+    assert lib.cc_linear(h, good, None, None, 4, 64, 64, other, None) == -1
+    assert lib.cc_linear(h, good, good, odd, 4, 64, 64, other, None) == -1
+    assert lib.cc_linear(h, good, good, None, 0, 64, 64, other, None) == 0
+    assert lib.cc_gated_linear(h, good, good, None, 4, 64, 64, other, None) == -1
+    assert lib.cc_gated_linear(h, good, good, good, 4, 0, 64, other, None) == -1
+    assert lib.cc_gated_linear(h, good, good, good, 0, 64, 64, other, None) == 0
     # null context
     assert lib.cc_rope_shift(None, good, None, 4, good, None, 4, good, good, good, 1, 16, None) == -1
     assert lib.cc_set_impl(h, 99) == -1
