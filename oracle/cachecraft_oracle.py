@@ -557,3 +557,34 @@ def layer_tail(h_rows: np.ndarray, attn_out: np.ndarray, w_o, gain_ffn, w_gate, 
     h1 = np.asarray(h_rows, dtype=np.float64) + linear(np.asarray(attn_out, dtype=np.float64).reshape(n, -1), w_o)
     h2 = h1 + linear(gated_ffn_in(rms_norm(h1, gain_ffn, eps), w_gate, w_up), w_down)
     return h1, h2
+
+
+def recompute_layers(w, r: int, selected, weights: Sequence, h_in: Optional[Sequence[np.ndarray]] = None):
+    """The chosen rows of request r through len(weights) decoder layers (every layer sees the same
+    synthetic chunk store): per layer x = rms_norm(h) -> Q, K, V of those rows -> fix + attend over
+    the re-positioned caches -> layer_tail.  The first layer's h are the rows of w.hidden; h_in[l],
+    if given, replaces the running state at the start of layer l (so that one layer can be checked
+    at a time).  Returns per layer a dict with h_in, x, out, lse, h1, h2."""
+    hq, hkv, d = w.spec.n_q_heads, w.spec.n_kv_heads, w.spec.head_dim
+    q_pos, q_row = query_list(w, r, selected)
+    k_sh, v_c, _ = shifted_context(w, r)
+    h = np.asarray(w.hidden[q_row], dtype=np.float64)
+    layers = []
+    for l, lw in enumerate(weights):
+        if h_in is not None and h_in[l] is not None:
+            h = np.asarray(h_in[l], dtype=np.float64)
+        x = rms_norm(h, lw.gain_attn, lw.eps)
+        qf, kf, vf = qkv_project(x, lw.w_qkv, hq, hkv, d)
+        full = lambda a: _rows_at(a, q_row, w.n_tok)
+        _, _, _, _, out, lse = fix_and_attend(w, r, k_sh, v_c, selected, k_new=full(kf), v_new=full(vf), q=full(qf))
+        h1, h2 = layer_tail(h, out, lw.w_o, lw.gain_ffn, lw.w_gate, lw.w_up, lw.w_down, lw.eps)
+        layers.append({"h_in": h, "x": x, "out": out, "lse": lse, "h1": h1, "h2": h2})
+        h = h2
+    return layers
+
+
+def _rows_at(a: np.ndarray, rows: np.ndarray, n_tok: int) -> np.ndarray:
+    """A per-token tensor [n_tok, ...] that holds a's rows at the given token rows (zero elsewhere)."""
+    t = np.zeros((n_tok,) + a.shape[1:], dtype=np.float64)
+    t[rows] = a
+    return t

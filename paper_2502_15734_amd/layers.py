@@ -1,11 +1,16 @@
-"""A loop over attention layers built from the library's calls (Sec. 3.4): per layer the chunk store
-arrives through the layer-wise preloader, cached keys are re-positioned, the chosen tokens are
-recomputed and attended, the question's attention to every chunk feeds Algorithm 1, and once a
-request's focused chunks are settled the other chunks of that request are no longer recomputed.
+"""Loops over layers built from the library's calls (Sec. 3.4).
 
-Argument marshalling and call order only; every step runs in libcachecraft.  The synthetic
-workloads hold ONE layer's tensors, so every layer reuses them with the queries scaled by a
-per-layer factor (a power of two, exact in bf16) to make the layers differ.
+LayerLoop (attention only): per layer the chunk store arrives through the layer-wise preloader,
+cached keys are re-positioned, the chosen tokens are recomputed and attended, the question's
+attention to every chunk feeds Algorithm 1, and once a request's focused chunks are settled the
+other chunks of that request are no longer recomputed.  The synthetic workloads hold ONE layer's
+tensors, so every layer reuses them with the queries scaled by a per-layer factor (a power of
+two, exact in bf16) to make the layers differ.
+
+DecoderLoop (whole layers): the hidden states of the chosen rows pass through normalisation,
+projections, the partial prefill and the feed-forward network of every layer.
+
+Argument marshalling and call order only; every step runs in libcachecraft.
 """
 from __future__ import annotations
 
@@ -16,6 +21,69 @@ import torch
 
 from .binding import CC_IMPL_AUTO, FocusTracker, Preloader, preload_depth
 from .pipeline import DeviceBatch
+
+
+class DecoderLoop:
+    """The hidden states of the chosen rows through whole decoder layers (Sec. 2.1, Sec. 3.4.3): per
+    layer cc_rms_norm -> cc_qkv_project -> cc_sparse_prefill over the re-positioned chunk-caches ->
+    cc_linear (output projection + residual) -> cc_rms_norm -> cc_gated_linear -> cc_linear (down
+    projection + residual).  The rows are chosen once, before the first layer, from the workload's
+    per-token queries (cc_select); every layer sees the same synthetic chunk store.
+    weights: one workload.LayerWeights per layer."""
+
+    def __init__(self, w, weights: Sequence, impl: int = CC_IMPL_AUTO, device: str = "cuda"):
+        assert w.hidden is not None, "the workload must carry hidden states"
+        self.w = w
+        self.batch = DeviceBatch(w, device=device, impl=impl)
+        b = self.batch
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device).to(b.dt)
+        self.weights = [{k: up(getattr(lw, k)) for k in ("gain_attn", "gain_ffn", "w_qkv", "w_o", "w_gate", "w_up", "w_down")}
+                        for lw in weights]
+        self.eps = [float(lw.eps) for lw in weights]
+        n, hidden, ffn = max(1, b.n_q_tot), w.hidden.shape[1], weights[0].w_gate.shape[0]
+        mk = lambda cols: torch.empty((n, cols), dtype=b.dt, device=device)
+        self.h, self.h1, self.x, self.act = mk(hidden), mk(hidden), mk(hidden), mk(ffn)
+
+    def run(self, keep: bool = False):
+        """Returns one record per layer (ms; with keep also h_in, out, lse, h1, h2 as numpy arrays)."""
+        b = self.batch
+        b.rope_shift()
+        b.select()
+        n = b.n_q_tot
+        records = []
+        if n == 0:
+            return records
+        r = b._rows
+        h, h1, x, act = r(self.h), r(self.h1), r(self.x), r(self.act)
+        o2 = r(b.out).view(h.shape[0], -1)
+        b.ctx.gather_rows(b.hidden, r(b.q_row), h)
+        for l, lw in enumerate(self.weights):
+            t0 = torch.cuda.Event(enable_timing=True); t1 = torch.cuda.Event(enable_timing=True)
+            t0.record()
+            rec = {"layer": l + 1, "rows": n}
+            if keep:
+                rec["h_in"] = h.float().cpu().numpy()
+            if l > 0:
+                b.rope_shift()                             # the next layer's chunk-caches, re-positioned
+            b.ctx.rms_norm(h, lw["gain_attn"], self.eps[l], x)
+            b.ctx.qkv_project(x, lw["w_qkv"], r(b.q_c), r(b.k_c), r(b.v_c))
+            b.sparse_prefill()
+            b.ctx.linear(o2, lw["w_o"], h1, residual=h)
+            b.ctx.rms_norm(h1, lw["gain_ffn"], self.eps[l], x)
+            b.ctx.gated_linear(x, lw["w_gate"], lw["w_up"], act)
+            b.ctx.linear(act, lw["w_down"], h, residual=h1)
+            t1.record()
+            rec["_events"] = (t0, t1)
+            if keep:
+                torch.cuda.synchronize()
+                rec.update(out=r(b.out).float().cpu().numpy(), lse=r(b.lse).cpu().numpy(),
+                           h1=h1.float().cpu().numpy(), h2=h.float().cpu().numpy())
+            records.append(rec)
+        torch.cuda.synchronize()
+        for rec in records:
+            t0, t1 = rec.pop("_events")
+            rec["ms"] = t0.elapsed_time(t1)
+        return records
 
 
 class LayerLoop:

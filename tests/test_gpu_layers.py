@@ -45,3 +45,39 @@ def test_layer_loop_matches_the_oracle(preload):
             np.testing.assert_allclose(rec["mass"][s0:s1], o["mass"], rtol=1e-2, atol=1e-3)
     assert recs[-1]["rows"] < recs[0]["rows"]                          # unfocused chunks are no longer recomputed
     loop.close()
+
+
+def _decoder_workload(dtype):
+    reqs = [W.RequestSpec([0, 1, 2, 3], [0.3, 0.2, 0.25, 0.4], 21), W.RequestSpec([3, 0, 4], [0.5, 0.15, 0.35], 40)]
+    hq, hkv, d = (8, 2, 128) if dtype == "bf16" else (4, 2, 64)
+    return W.custom("decoder", dtype, hq, hkv, d, 5.0e5, [100, 77, 130, 64, 201], [0, 5, 0, 17, 3], reqs,
+                    1.0 / math.sqrt(d), seed=43, hidden=256)
+
+
+@pytest.mark.parametrize("dtype,impl", [("f32", "auto"), ("bf16", "auto"), ("bf16", "scalar")])
+def test_decoder_loop_matches_the_oracle(dtype, impl):
+    """Hidden states of the chosen rows through three whole layers.  fp32: the oracle runs freely
+    beside the library.  bf16: every layer of the oracle starts from the library's own layer input
+    (the bar is per layer; bf16 roundings of one layer's output are the next layer's input)."""
+    import paper_2502_15734_amd as P
+    from paper_2502_15734_amd.layers import DecoderLoop
+    w = _decoder_workload(dtype)
+    ffn = 640 if dtype == "bf16" else 160
+    weights = [W.layer_weights(w.spec, 256, ffn, layer=l, qkv_scale=1.0 / 16) for l in range(3)]
+    loop = DecoderLoop(w, weights, impl={"auto": P.CC_IMPL_AUTO, "scalar": P.CC_IMPL_SCALAR}[impl])
+    recs = loop.run(keep=True)
+    assert len(recs) == 3
+    gsel = H.gpu_selection(w, loop.batch.sel_idx.cpu().numpy())
+    tol = H.TOL[dtype] if dtype == "bf16" else 2e-5
+    for r in range(w.n_requests):
+        q0, q1 = int(w.cu_q[r]), int(w.cu_q[r + 1])
+        forced = [rec["h_in"][q0:q1] for rec in recs] if dtype == "bf16" else None
+        ref = O.recompute_layers(w, r, gsel[r], weights, h_in=forced)
+        for l, (rec, o) in enumerate(zip(recs, ref)):
+            what = f"request {r} layer {l + 1}"
+            assert H.rel_l2(rec["h_in"][q0:q1], o["h_in"]) <= tol, what
+            assert H.rel_l2(rec["out"][q0:q1], o["out"]) <= tol, f"{what}: attention {H.rel_l2(rec['out'][q0:q1], o['out']):.3e}"
+            assert H.rel_l2(rec["h1"][q0:q1], o["h1"]) <= tol, what
+            assert H.rel_l2(rec["h2"][q0:q1], o["h2"]) <= tol, f"{what}: h2 {H.rel_l2(rec['h2'][q0:q1], o['h2']):.3e}"
+    # the layers do change the state
+    assert H.rel_l2(recs[0]["h2"], recs[0]["h_in"]) > 0.1

@@ -702,3 +702,48 @@ def test_layer_tail_residuals_and_a_library_layer():
     w_pick = np.zeros((hid, hq * d)); w_pick[0, 2 * d + 5] = 1.0
     p1, _ = O.layer_tail(np.zeros_like(h), o, w_pick, g, wg, wu, np.zeros_like(wd), 1e-5)
     assert np.allclose(p1[:, 0], o[:, 2, 5])
+
+
+def _tiny_projected(dtype="f32", hidden=None):
+    reqs = [W.RequestSpec([0, 1, 2], [0.3, 0.25, 0.4], 9), W.RequestSpec([2, 0], [0.5, 0.2], 5)]
+    hq, hkv, d = 4, 2, 64
+    return W.custom("tiny-layers", dtype, hq, hkv, d, 1.0e4, [40, 33, 50], [0, 7, 3], reqs, 0.5, seed=77,
+                    hidden=hidden or (hq + 2 * hkv) * d)
+
+
+def test_recompute_layers_attention_step_is_the_pinned_hot_path():
+    """With an identity projection, unit gains and rows of unit mean square the layer's Q, K, V are
+    slices of the hidden state, so its attention step must be run_request on those slices."""
+    w = _tiny_projected()
+    hq, hkv, d = w.spec.n_q_heads, w.spec.n_kv_heads, w.spec.head_dim
+    hid = w.hidden.shape[1]
+    w.hidden = (w.hidden / np.sqrt(np.mean(w.hidden.astype(np.float64) ** 2, axis=1, keepdims=True))).astype(np.float64)
+    lw = W.layer_weights(w.spec, hid, 96)
+    lw.w_qkv = np.eye(hid); lw.gain_attn = np.ones(hid); lw.eps = 0.0
+    for r in range(w.n_requests):
+        base = O.run_request(w, r)                               # selection from w.q, as the layer loop takes it
+        got = O.recompute_layers(w, r, base.selected, [lw])[0]
+        hd = w.hidden
+        ref = O.run_request(w, r, selected_override=base.selected, q=hd[:, : hq * d].reshape(-1, hq, d),
+                            k_new=hd[:, hq * d: (hq + hkv) * d].reshape(-1, hkv, d),
+                            v_new=hd[:, (hq + hkv) * d:].reshape(-1, hkv, d))
+        assert np.allclose(got["out"], ref.out, rtol=1e-10, atol=1e-12) and np.allclose(got["lse"], ref.lse, rtol=1e-10)
+
+
+def test_recompute_layers_chain_and_pass_through():
+    w = _tiny_projected(hidden=48)
+    ws = [W.layer_weights(w.spec, 48, 96, layer=l) for l in range(3)]
+    sel = O.run_request(w, 0).selected
+    ls = O.recompute_layers(w, 0, sel, ws)
+    q_pos, q_row = O.query_list(w, 0, sel)
+    assert np.array_equal(ls[0]["h_in"], w.hidden[q_row].astype(np.float64))
+    assert all(np.array_equal(ls[l + 1]["h_in"], ls[l]["h2"]) for l in range(2))          # the state is handed on
+    assert not np.allclose(ls[0]["out"], ls[1]["out"])                                     # and the layers differ
+    # each layer, fed its input alone, gives the same result (no hidden carry-over besides h)
+    again = O.recompute_layers(w, 0, sel, [ws[2]], h_in=[ls[2]["h_in"]])[0]
+    assert np.array_equal(again["h2"], ls[2]["h2"])
+    # with no output and no down projection the hidden state passes every layer unchanged
+    for lw in ws:
+        lw.w_o = np.zeros_like(lw.w_o); lw.w_down = np.zeros_like(lw.w_down)
+    ls = O.recompute_layers(w, 0, sel, ws)
+    assert np.array_equal(ls[2]["h2"], w.hidden[q_row].astype(np.float64))
