@@ -197,12 +197,59 @@ def time_extra_calls(batch, w, work, steps: int, ms_per_step: float, sparse_pref
     prefill_pairs_ms = timed(batch.sparse_prefill_pairs, steps)
     preload = time_layerwise_preload(batch, ms_per_step)
     layer_loop = time_layer_loop(w)
+    dense = time_decoder_dense(batch, w)
     return {"cc_select_from_scores": {"ms": from_scores_ms, "chunk_tokens": work["n_chunk_tok"]},
             "cc_question_mass": {"ms": question_mass_ms, "segments": int(len(w.segments))},
             "cc_sparse_prefill_mass": {"ms": prefill_mass_ms, "over_cc_sparse_prefill_ms": prefill_mass_ms - sparse_prefill_ms},
             "cc_chunk_attention": {"ms": chunk_attention_ms, "segment_pairs": int(batch.pair_off[-1])},
             "cc_sparse_prefill_pairs": {"ms": prefill_pairs_ms, "over_cc_sparse_prefill_ms": prefill_pairs_ms - sparse_prefill_ms},
-            "layerwise_preload": preload, "layer_loop": layer_loop}
+            "layerwise_preload": preload, "layer_loop": layer_loop, "decoder_layer_dense": dense}
+
+
+def time_decoder_dense(batch, w) -> dict:
+    """The dense operators that take the recomputed rows through the rest of a decoder layer, at the
+    model shape the workload's head geometry belongs to (8B: hidden 4096, feed-forward 14336; 70B:
+    8192 / 28672), on as many rows as the step recomputes.  Random inputs and weights."""
+    import torch
+    sp = w.spec
+    hq, d = sp.n_q_heads, sp.head_dim
+    hidden, ffn = (8192, 28672) if hq * d >= 8192 else (4096, 14336)
+    n = batch.n_q_tot
+    if n == 0 or sp.dtype != "bf16":
+        return {}
+    g = torch.Generator(device="cuda").manual_seed(1)
+    rnd = lambda *shape, s=1.0: (torch.randn(*shape, device="cuda", generator=g) * s).to(torch.bfloat16)
+    h, o = rnd(n, hidden), rnd(n, hq * d, s=0.5)
+    gain = (1.0 + 0.1 * torch.randn(hidden, device="cuda", generator=g)).to(torch.bfloat16)
+    w_o, w_gate = rnd(hidden, hq * d, s=(hq * d) ** -0.5), rnd(ffn, hidden, s=hidden ** -0.5)
+    w_up, w_down = rnd(ffn, hidden, s=hidden ** -0.5), rnd(hidden, ffn, s=ffn ** -0.5)
+    h1, x = torch.empty_like(h), torch.empty_like(h)
+    act = torch.empty((n, ffn), dtype=torch.bfloat16, device="cuda")
+    ctx = batch.ctx
+    calls = [("cc_rms_norm", lambda: ctx.rms_norm(h1, gain, 1e-5, x), None, 2.0 * n * hidden * 2),
+             ("cc_linear(output projection + residual)", lambda: ctx.linear(o, w_o, h1, residual=h), 2.0 * n * hidden * hq * d, None),
+             ("cc_gated_linear", lambda: ctx.gated_linear(x, w_gate, w_up, act), 2.0 * n * hidden * 2 * ffn, None),
+             ("cc_linear(down projection + residual)", lambda: ctx.linear(act, w_down, h, residual=h1), 2.0 * n * ffn * hidden, None)]
+    out = {"rows": n, "hidden": hidden, "ffn": ffn, "calls": {}}
+    total = 0.0
+    for name, fn, flops, nbytes in calls:
+        fn(); fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
+        ev[0].record()
+        for i in range(5):
+            fn()
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        ms = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(5)]))
+        total += ms
+        rec = {"ms": ms}
+        if flops is not None:
+            rec.update(TFLOPs=flops / ms / 1e9, frac_of_peak=flops / ms / 1e9 / PEAK_MFMA_BF16_TFLOPS)
+        else:
+            rec.update(GBps=nbytes / ms / 1e6, frac_of_peak=nbytes / ms / 1e6 / PEAK_HBM_GBS)
+        out["calls"][name] = rec
+    out["ms"] = total
+    return out
 
 
 def time_layer_loop(w, n_layers: int = 4, window: int = 2) -> dict:

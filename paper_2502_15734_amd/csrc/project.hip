@@ -237,6 +237,62 @@ __device__ __forceinline__ void gemm_mfma(f32x16& d, const u32x4& a, const u32x4
   asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(d) : "v"(a), "v"(b));
 }
 
+// Epilogue of the 128 x 128-per-wavefront kernels.  D^T block (a, b): lane (nl, hh) holds token
+// m0 + 128 wm + 32 b + nl, features n0 + 128 wn + 32 a + 8 (i/4) + 4 hh + i%4.
+template <int MODE>
+__device__ __forceinline__ void gemm_store_tile(f32x16 (&acc)[4][4], const GemmOut& out, int n_rows, int n0, int m0,
+                                                int wn, int wm, int nl, int hh) {
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    const int row = m0 + wm * 128 + b * 32 + nl;
+    if (row >= n_rows) continue;
+    if (MODE == kOutGated) {
+#pragma unroll
+      for (int a = 0; a < 2; ++a) {
+        bf16_t* op = static_cast<bf16_t*>(out.o0) + static_cast<size_t>(row) * out.width + n0 / 2 + wn * 64 + a * 32 + 4 * hh;
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          bf16_t v4[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float gate = acc[a][b][4 * g4 + e], up = acc[a + 2][b][4 * g4 + e];
+            v4[e] = static_cast<bf16_t>(gate / (1.f + __expf(-gate)) * up);
+          }
+          *reinterpret_cast<uint2*>(op + 8 * g4) = *reinterpret_cast<uint2*>(v4);
+        }
+      }
+      continue;
+    }
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      const int col0 = n0 + wn * 128 + a * 32;        // a 32-feature block never straddles q | k | v
+      bf16_t* base;
+      int c_in, width;
+      if (MODE == kOutLinear) { base = static_cast<bf16_t*>(out.o0); c_in = col0; width = out.width; }
+      else if (col0 < out.nq) { base = static_cast<bf16_t*>(out.o0); c_in = col0; width = out.nq; }
+      else if (col0 < out.nq + out.nk) { base = static_cast<bf16_t*>(out.o1); c_in = col0 - out.nq; width = out.nk; }
+      else { base = static_cast<bf16_t*>(out.o2); c_in = col0 - out.nq - out.nk; width = out.nk; }
+      const size_t at = static_cast<size_t>(row) * width + c_in + 4 * hh;
+      bf16_t* op = base + at;
+      const bf16_t* rp = MODE == kOutLinear && out.residual != nullptr ? static_cast<const bf16_t*>(out.residual) + at : nullptr;
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        bf16_t v4[4];
+        if (rp != nullptr) {
+          bf16_t r4[4];
+          *reinterpret_cast<uint2*>(r4) = *reinterpret_cast<const uint2*>(rp + 8 * g4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v4[e] = static_cast<bf16_t>(acc[a][b][4 * g4 + e] + static_cast<float>(r4[e]));
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v4[e] = static_cast<bf16_t>(acc[a][b][4 * g4 + e]);
+        }
+        *reinterpret_cast<uint2*>(op + 8 * g4) = *reinterpret_cast<uint2*>(v4);
+      }
+    }
+  }
+}
+
 constexpr int kStages = 4;
 constexpr int kStageBytes = 32 * 1024;      // 32 operand groups of 1 KiB: W blocks 0..7 x 2 k-steps, x blocks 0..7 x 2 k-steps
 
@@ -339,57 +395,136 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma2_kernel(
   }
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 
-  // D^T block (a, b): lane (nl, hh) holds token m0 + 128 wm + 32 b + nl, features
-  // n0 + 128 wn + 32 a + 8 (i/4) + 4 hh + i%4
+  gemm_store_tile<MODE>(acc, out, n_rows, n0, m0, wn, wm, nl, hh);
+}
+
+// ---- MFMA kernel, 128 x 128 outputs per wavefront, whole cache lines per load ----------------------
+// Same tile and accumulators as the kernel above; what changes is how the operands travel.  A k-stage
+// is 64 wide: 128 bytes = one cache line of every row of W and x.  A load instruction brings 8 rows
+// x 128 bytes (8 consecutive lanes share a line; the kernel above touches 32 lines for the same
+// kilobyte and needs every line in two stages), and the image in LDS is row-major, 128 bytes per
+// row.  Operand reads walk down 32 rows at one 16-byte piece, so piece c of row r is kept at
+// c ^ swz(r), swz(r) = ((r >> 1) & 7) ^ ((r & 1) << 2): any 8 or 16 consecutive rows then spread
+// over all banks.  The permutation is applied on the global side (lane -> piece of the line),
+// because the load fixes where a lane's bytes land in LDS.  Two images of 64 KiB; per stage the
+// wavefronts meet twice: once all loads of the next image have landed (its first operands are
+// read under the last k-step), and once everyone has left the current image (the loads after
+// next may overwrite it).
+constexpr int kTK3 = 64;
+constexpr int kStage3Bytes = (kTN + kTM) * kTK3 * 2;      // 64 KiB
+
+__device__ __forceinline__ int gemm_swz(int r) { return ((r >> 1) & 7) ^ ((r & 1) << 2); }
+
+template <int MODE>
+__global__ __launch_bounds__(256, 1) void gemm_mfma3_kernel(
+    const bf16_t* __restrict__ x, const bf16_t* __restrict__ w, const bf16_t* __restrict__ w2, int n_rows,
+    int hidden, GemmOut out) {
+  __shared__ uint4 lds[2 * kStage3Bytes / 16];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nl = lane & 31, hh = lane >> 5;
+  const int wn = wave & 1, wm = wave >> 1;
+  const int n0 = blockIdx.x * kTN, m0 = blockIdx.y * kTM;
+  const int n_k = hidden / kTK3;
+
+  // ---- staging: wavefront w brings image rows 128 w .. 128 w + 127 (rows 0..255: W, 256..511: x),
+  // 8 rows per instruction: lane L -> row 8 j + L / 8, LDS piece L % 8 of that row
+  const char* src[16];
 #pragma unroll
-  for (int b = 0; b < 4; ++b) {
-    const int row = m0 + wm * 128 + b * 32 + nl;
-    if (row >= n_rows) continue;
-    if (MODE == kOutGated) {
-#pragma unroll
-      for (int a = 0; a < 2; ++a) {
-        bf16_t* op = static_cast<bf16_t*>(out.o0) + static_cast<size_t>(row) * out.width + n0 / 2 + wn * 64 + a * 32 + 4 * hh;
-#pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-          bf16_t v4[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float gate = acc[a][b][4 * g4 + e], up = acc[a + 2][b][4 * g4 + e];
-            v4[e] = static_cast<bf16_t>(gate / (1.f + __expf(-gate)) * up);
-          }
-          *reinterpret_cast<uint2*>(op + 8 * g4) = *reinterpret_cast<uint2*>(v4);
-        }
-      }
-      continue;
+  for (int j = 0; j < 16; ++j) {
+    const int r = 128 * wave + 8 * j + (lane >> 3);            // image row
+    const bf16_t* row;
+    if (r >= kTN) row = x + static_cast<size_t>(min(m0 + r - kTN, n_rows - 1)) * hidden;
+    else if (MODE != kOutGated) row = w + static_cast<size_t>(n0 + r) * hidden;
+    else {
+      // gated: of a wavefront's four 32-feature blocks, two are rows of W_gate and two the SAME
+      // rows of W_up, so that a lane ends up holding both factors of an output
+      const int blk = r >> 5;
+      const int f = n0 / 2 + 64 * (blk >> 2) + 32 * (blk & 1) + (r & 31);
+      row = ((blk & 2) ? w2 : w) + static_cast<size_t>(f) * hidden;
     }
-#pragma unroll
-    for (int a = 0; a < 4; ++a) {
-      const int col0 = n0 + wn * 128 + a * 32;        // a 32-feature block never straddles q | k | v
-      bf16_t* base;
-      int c_in, width;
-      if (MODE == kOutLinear) { base = static_cast<bf16_t*>(out.o0); c_in = col0; width = out.width; }
-      else if (col0 < out.nq) { base = static_cast<bf16_t*>(out.o0); c_in = col0; width = out.nq; }
-      else if (col0 < out.nq + out.nk) { base = static_cast<bf16_t*>(out.o1); c_in = col0 - out.nq; width = out.nk; }
-      else { base = static_cast<bf16_t*>(out.o2); c_in = col0 - out.nq - out.nk; width = out.nk; }
-      const size_t at = static_cast<size_t>(row) * width + c_in + 4 * hh;
-      bf16_t* op = base + at;
-      const bf16_t* rp = MODE == kOutLinear && out.residual != nullptr ? static_cast<const bf16_t*>(out.residual) + at : nullptr;
-#pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        bf16_t v4[4];
-        if (rp != nullptr) {
-          bf16_t r4[4];
-          *reinterpret_cast<uint2*>(r4) = *reinterpret_cast<const uint2*>(rp + 8 * g4);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v4[e] = static_cast<bf16_t>(acc[a][b][4 * g4 + e] + static_cast<float>(r4[e]));
-        } else {
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v4[e] = static_cast<bf16_t>(acc[a][b][4 * g4 + e]);
-        }
-        *reinterpret_cast<uint2*>(op + 8 * g4) = *reinterpret_cast<uint2*>(v4);
-      }
-    }
+    src[j] = reinterpret_cast<const char*>(row) + 16 * ((lane & 7) ^ gemm_swz(r));
   }
+  typedef __attribute__((address_space(3))) const uint4 lds_piece;
+  const uint32_t lds_base = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_piece*)lds)));
+  // load j of stage t (past the last stage: a harmless repeat into the image nobody reads any more)
+  auto dma_one = [&](int t, int j) __attribute__((always_inline)) {
+    const uint32_t dst = lds_base + (t & 1) * kStage3Bytes + (128 * wave + 8 * j) * 128;
+    gemm_load_to_lds(src[j] + static_cast<size_t>(min(t, n_k - 1)) * (kTK3 * sizeof(bf16_t)), dst);
+  };
+  auto wait_all_loads = [&]() __attribute__((always_inline)) {
+    __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));       // vmcnt(0)
+    asm volatile("" ::: "memory");
+  };
+  auto barrier = [&]() __attribute__((always_inline)) {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) asm volatile("v_accvgpr_write_b32 %0, 0" : "=a"(acc[a][b][i]));
+
+  const char* lds_bytes = reinterpret_cast<const char*>(lds);
+  const int swz = gemm_swz(nl);                                // (block bases are multiples of 32 rows)
+  const int row_a = (128 * wn + nl) * 128, row_b = (kTN + 128 * wm + nl) * 128;
+  auto read_a = [&](int t, int s, int a) __attribute__((always_inline)) {
+    return *reinterpret_cast<const u32x4*>(lds_bytes + (t & 1) * kStage3Bytes + row_a + a * 4096 + (((2 * s + hh) ^ swz) << 4));
+  };
+  auto read_b = [&](int t, int s, int b) __attribute__((always_inline)) {
+    return *reinterpret_cast<const u32x4*>(lds_bytes + (t & 1) * kStage3Bytes + row_b + b * 4096 + (((2 * s + hh) ^ swz) << 4));
+  };
+
+#pragma unroll
+  for (int j = 0; j < 16; ++j) dma_one(0, j);
+  wait_all_loads();
+  __syncthreads();
+  u32x4 opa[2][4], opb[2][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { opa[0][i] = read_a(0, 0, i); opb[0][i] = read_b(0, 0, i); }
+
+  for (int t = 0; t < n_k; ++t) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int cur = s & 1, nxt = cur ^ 1;
+      // operands of the next k-step: the next piece pair of this image, or (s = 3) the first of
+      // the next image, whose loads the barrier below has seen land
+      if (s == 3) { wait_all_loads(); barrier(); }
+      const int nt = s == 3 ? t + 1 : t, ns = (s + 1) & 3;   // (past the last stage: the repeated image, unused)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { opa[nxt][i] = read_a(nt, ns, i); opb[nxt][i] = read_b(nt, ns, i); }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          gemm_mfma(acc[a][b], opa[cur][a], opb[cur][b]);
+          // the 16 loads of the next image go out under the MFMAs of the first two k-steps
+          if (s < 2 && (b & 1)) dma_one(t + 1, 8 * s + 2 * a + (b >> 1));
+        }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    barrier();                                          // everyone has left image t: it may be overwritten
+  }
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  gemm_store_tile<MODE>(acc, out, n_rows, n0, m0, wn, wm, nl, hh);
+}
+
+// the 128 x 128-per-wavefront kernels: whole-cache-line stages where the contraction length allows
+template <int MODE>
+void launch_gemm_wide(dim3 grid, hipStream_t stream, const void* x, const void* w, const void* w2, int n_rows, int n_in,
+                      const GemmOut& out) {
+  if (n_in % kTK3 == 0)
+    hipLaunchKernelGGL(gemm_mfma3_kernel<MODE>, grid, dim3(256), 0, stream, static_cast<const bf16_t*>(x),
+                       static_cast<const bf16_t*>(w), static_cast<const bf16_t*>(w2), n_rows, n_in, out);
+  else
+    hipLaunchKernelGGL(gemm_mfma2_kernel<MODE>, grid, dim3(256), 0, stream, static_cast<const bf16_t*>(x),
+                       static_cast<const bf16_t*>(w), static_cast<const bf16_t*>(w2), n_rows, n_in, out);
 }
 
 }  // namespace
@@ -402,9 +537,7 @@ void launch_qkv_project(const cc_ctx* ctx, const void* x, const void* w, int n_r
       nq % 32 == 0 && nk % 32 == 0) {
     dim3 grid(n_cols / kTN, (n_rows + kTM - 1) / kTM);
     if (hidden / kTK >= 3 && ctx->impl != CC_IMPL_MFMA_NARROW) {
-      hipLaunchKernelGGL(gemm_mfma2_kernel<kOutQkv>, grid, dim3(256), 0, stream, static_cast<const bf16_t*>(x),
-                         static_cast<const bf16_t*>(w), static_cast<const bf16_t*>(nullptr), n_rows, hidden,
-                         GemmOut{q, k, v, nullptr, nq, nk, 0});
+      launch_gemm_wide<kOutQkv>(grid, stream, x, w, nullptr, n_rows, hidden, GemmOut{q, k, v, nullptr, nq, nk, 0});
       return;
     }
     hipLaunchKernelGGL(qkv_project_mfma_kernel, grid, dim3(512), 0, stream,
@@ -432,9 +565,7 @@ void launch_linear(const cc_ctx* ctx, const void* x, const void* w, const void* 
   if (bf && ctx->impl != CC_IMPL_SCALAR && ctx->impl != CC_IMPL_MFMA_NARROW && n_out % kTN == 0 && n_in % kTK == 0 &&
       n_in / kTK >= 3) {
     dim3 grid(n_out / kTN, (n_rows + kTM - 1) / kTM);
-    hipLaunchKernelGGL(gemm_mfma2_kernel<kOutLinear>, grid, dim3(256), 0, stream, static_cast<const bf16_t*>(x),
-                       static_cast<const bf16_t*>(w), static_cast<const bf16_t*>(nullptr), n_rows, n_in,
-                       GemmOut{y, nullptr, nullptr, residual, 0, 0, n_out});
+    launch_gemm_wide<kOutLinear>(grid, stream, x, w, nullptr, n_rows, n_in, GemmOut{y, nullptr, nullptr, residual, 0, 0, n_out});
     return;
   }
   dim3 grid((n_out + 63) / 64, (n_rows + 63) / 64);
@@ -455,9 +586,7 @@ void launch_gated_linear(const cc_ctx* ctx, const void* x, const void* w_gate, c
   if (bf && ctx->impl != CC_IMPL_SCALAR && ctx->impl != CC_IMPL_MFMA_NARROW && (2 * n_ffn) % kTN == 0 &&
       n_in % kTK == 0 && n_in / kTK >= 3) {
     dim3 grid(2 * n_ffn / kTN, (n_rows + kTM - 1) / kTM);
-    hipLaunchKernelGGL(gemm_mfma2_kernel<kOutGated>, grid, dim3(256), 0, stream, static_cast<const bf16_t*>(x),
-                       static_cast<const bf16_t*>(w_gate), static_cast<const bf16_t*>(w_up), n_rows, n_in,
-                       GemmOut{y, nullptr, nullptr, nullptr, 0, 0, n_ffn});
+    launch_gemm_wide<kOutGated>(grid, stream, x, w_gate, w_up, n_rows, n_in, GemmOut{y, nullptr, nullptr, nullptr, 0, 0, n_ffn});
     return;
   }
   dim3 grid((n_ffn + 63) / 64, (n_rows + 63) / 64);
