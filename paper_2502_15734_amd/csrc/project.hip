@@ -415,16 +415,40 @@ constexpr int kStage3Bytes = (kTN + kTM) * kTK3 * 2;      // 64 KiB
 
 __device__ __forceinline__ int gemm_swz(int r) { return ((r >> 1) & 7) ^ ((r & 1) << 2); }
 
+//
+// Which tile a workgroup takes: workgroups are handed to the 8 XCDs in turn, each XCD with an L2 of
+// its own.  Workgroup L therefore takes entry (L % 8) * per_xcd + L / 8 of a tile order in which 32
+// consecutive entries (what one XCD runs at a time) form a block of 4 feature tiles x 8 token tiles:
+// the block's 32 workgroups ask their L2 for 12 different operand panels instead of up to 34
+// (L2 hit rate 48 % -> 82 %, memory reads a third; 3 - 7 % faster for the plain products).  The
+// gated product keeps the plain order (feature tile fastest): every blocked order tried was 5 - 10 %
+// slower there although it, too, cut the memory reads to a third.
+constexpr int kBlockN = 4, kBlockM = 8;
+
 template <int MODE>
 __global__ __launch_bounds__(256, 1) void gemm_mfma3_kernel(
     const bf16_t* __restrict__ x, const bf16_t* __restrict__ w, const bf16_t* __restrict__ w2, int n_rows,
-    int hidden, GemmOut out) {
+    int hidden, int tiles_n, int tiles_m, GemmOut out) {
   __shared__ uint4 lds[2 * kStage3Bytes / 16];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nl = lane & 31, hh = lane >> 5;
   const int wn = wave & 1, wm = wave >> 1;
-  const int n0 = blockIdx.x * kTN, m0 = blockIdx.y * kTM;
+  int n0, m0;
+  if (MODE == kOutGated) {                                 // (see above: plain order measured faster here)
+    if (blockIdx.x >= tiles_n * tiles_m) return;
+    n0 = (blockIdx.x % tiles_n) * kTN;
+    m0 = (blockIdx.x / tiles_n) * kTM;
+  } else {
+    const int entry = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    if (entry >= tiles_n * tiles_m) return;                // (the grid is padded to a multiple of 8)
+    const int strip = min(entry / (kBlockN * tiles_m), (tiles_n - 1) / kBlockN);   // strip of up to 4 feature tiles
+    const int strip_w = min(kBlockN, tiles_n - strip * kBlockN);
+    const int in_strip = entry - strip * kBlockN * tiles_m;
+    const int blk = in_strip / (strip_w * kBlockM), in_blk = in_strip - blk * strip_w * kBlockM;
+    n0 = (strip * kBlockN + in_blk % strip_w) * kTN;
+    m0 = (blk * kBlockM + in_blk / strip_w) * kTM;
+  }
   const int n_k = hidden / kTK3;
 
   // ---- staging: wavefront w brings image rows 128 w .. 128 w + 127 (rows 0..255: W, 256..511: x),
@@ -520,8 +544,9 @@ template <int MODE>
 void launch_gemm_wide(dim3 grid, hipStream_t stream, const void* x, const void* w, const void* w2, int n_rows, int n_in,
                       const GemmOut& out) {
   if (n_in % kTK3 == 0)
-    hipLaunchKernelGGL(gemm_mfma3_kernel<MODE>, grid, dim3(256), 0, stream, static_cast<const bf16_t*>(x),
-                       static_cast<const bf16_t*>(w), static_cast<const bf16_t*>(w2), n_rows, n_in, out);
+    hipLaunchKernelGGL(gemm_mfma3_kernel<MODE>, dim3((grid.x * grid.y + 7) / 8 * 8), dim3(256), 0, stream,
+                       static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(w), static_cast<const bf16_t*>(w2),
+                       n_rows, n_in, static_cast<int>(grid.x), static_cast<int>(grid.y), out);
   else
     hipLaunchKernelGGL(gemm_mfma2_kernel<MODE>, grid, dim3(256), 0, stream, static_cast<const bf16_t*>(x),
                        static_cast<const bf16_t*>(w), static_cast<const bf16_t*>(w2), n_rows, n_in, out);
