@@ -626,40 +626,73 @@ void launch_gated_linear(const cc_ctx* ctx, const void* x, const void* w_gate, c
 }
 
 // ---- root-mean-square normalisation: y = x / sqrt(mean(x^2) + eps) * gain ---------------------------
-// One wavefront per row (four rows per workgroup); the row is read twice, the second time from
-// cache, so the kernel moves each row once in and once out of HBM.
+// One wavefront per row (four rows per workgroup).  Rows of up to 64 x 16 pieces of 16 bytes stay
+// in registers between the sum of squares and the scaling, so each row moves once in and once out
+// of HBM; longer rows are read a second time.
+// the elements of a 16-byte piece as floats, and back, without taking the piece's address (which
+// would move a register array to scratch memory)
+__device__ __forceinline__ void piece_to_floats(const uint4& p, float (&f)[8], bf16_t*) {
+  const uint32_t u[4] = {p.x, p.y, p.z, p.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    f[2 * i] = __uint_as_float(u[i] << 16);
+    f[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ void piece_to_floats(const uint4& p, float (&f)[4], float*) {
+  f[0] = __uint_as_float(p.x); f[1] = __uint_as_float(p.y); f[2] = __uint_as_float(p.z); f[3] = __uint_as_float(p.w);
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void rms_norm_kernel(const T* x, const T* __restrict__ gain, float eps,
                                                        int n_rows, int hidden, T* y) {          // (y may be x)
   const int row = blockIdx.x * 4 + threadIdx.x / 64, lane = threadIdx.x % 64;
   if (row >= n_rows) return;
   constexpr int kPer = 16 / sizeof(T);                 // elements per 16-byte piece
+  constexpr int kKeep = 16;                            // pieces a lane keeps
   const T* xr = x + static_cast<size_t>(row) * hidden;
   T* yr = y + static_cast<size_t>(row) * hidden;
-  const bool wide = hidden % kPer == 0;                // rows then start on 16-byte boundaries (the call checks the bases)
+  const int n_pieces = hidden / kPer;                  // (the call checks that hidden is a multiple of kPer)
+  const bool keep = n_pieces <= 64 * kKeep;
+  uint4 held[kKeep];
   float ss = 0.f;
-  if (wide) {
-    for (int p = lane; p < hidden / kPer; p += 64) {
+  if (keep) {
+#pragma unroll
+    for (int i = 0; i < kKeep; ++i) {
+      const int p = lane + 64 * i;
+      held[i] = p < n_pieces ? *reinterpret_cast<const uint4*>(xr + p * kPer) : uint4{0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int i = 0; i < kKeep; ++i) {
+      float f[kPer];
+      piece_to_floats(held[i], f, static_cast<T*>(nullptr));
+#pragma unroll
+      for (int e = 0; e < kPer; ++e) ss += f[e] * f[e];
+    }
+  } else {
+    for (int p = lane; p < n_pieces; p += 64) {
       T v[kPer];
       *reinterpret_cast<uint4*>(v) = *reinterpret_cast<const uint4*>(xr + p * kPer);
 #pragma unroll
       for (int e = 0; e < kPer; ++e) ss += to_float(v[e]) * to_float(v[e]);
     }
-  } else {
-    for (int c = lane; c < hidden; c += 64) ss += to_float(xr[c]) * to_float(xr[c]);
   }
   const float scale = rsqrtf(wave_sum(ss) / static_cast<float>(hidden) + eps);
-  if (wide) {
-    for (int p = lane; p < hidden / kPer; p += 64) {
-      T v[kPer], g[kPer], o[kPer];
-      *reinterpret_cast<uint4*>(v) = *reinterpret_cast<const uint4*>(xr + p * kPer);
-      *reinterpret_cast<uint4*>(g) = *reinterpret_cast<const uint4*>(gain + p * kPer);
+  auto scaled = [&](const uint4& in, int p) __attribute__((always_inline)) {
+    float f[kPer], g[kPer];
+    T o[kPer];
+    piece_to_floats(in, f, static_cast<T*>(nullptr));
+    piece_to_floats(*reinterpret_cast<const uint4*>(gain + p * kPer), g, static_cast<T*>(nullptr));
 #pragma unroll
-      for (int e = 0; e < kPer; ++e) o[e] = from_float<T>(to_float(v[e]) * scale * to_float(g[e]));
-      *reinterpret_cast<uint4*>(yr + p * kPer) = *reinterpret_cast<uint4*>(o);
-    }
+    for (int e = 0; e < kPer; ++e) o[e] = from_float<T>(f[e] * scale * g[e]);
+    *reinterpret_cast<uint4*>(yr + p * kPer) = *reinterpret_cast<uint4*>(o);
+  };
+  if (keep) {
+#pragma unroll
+    for (int i = 0; i < kKeep; ++i)
+      if (lane + 64 * i < n_pieces) scaled(held[i], lane + 64 * i);
   } else {
-    for (int c = lane; c < hidden; c += 64) yr[c] = from_float<T>(to_float(xr[c]) * scale * to_float(gain[c]));
+    for (int p = lane; p < n_pieces; p += 64) scaled(*reinterpret_cast<const uint4*>(xr + p * kPer), p);
   }
 }
 

@@ -36,7 +36,8 @@ def _host(t):
 
 
 @pytest.mark.parametrize("dtype,rows,hidden", [("bf16", 1, 256), ("bf16", 37, 4096), ("bf16", 301, 40),
-                                               ("f32", 5, 36), ("f32", 130, 1024)])
+                                               ("f32", 5, 36), ("f32", 130, 1024), ("bf16", 9, 8192),
+                                               ("bf16", 3, 16384), ("f32", 6, 8192)])   # rows kept in registers / read twice
 def test_rms_norm(dtype, rows, hidden):
     rng = np.random.default_rng(rows + hidden)
     x = _draw(rng, (rows, hidden), 1.5, dtype)
