@@ -407,9 +407,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma2_kernel(
 // c ^ swz(r), swz(r) = ((r >> 1) & 7) ^ ((r & 1) << 2): any 8 or 16 consecutive rows then spread
 // over all banks.  The permutation is applied on the global side (lane -> piece of the line),
 // because the load fixes where a lane's bytes land in LDS.  Two images of 64 KiB; per stage the
-// wavefronts meet twice: once all loads of the next image have landed (its first operands are
-// read under the last k-step), and once everyone has left the current image (the loads after
-// next may overwrite it).
+// wavefronts meet once, at its end.
 constexpr int kTK3 = 64;
 constexpr int kStage3Bytes = (kTN + kTM) * kTK3 * 2;      // 64 KiB
 
@@ -516,24 +514,31 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma3_kernel(
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       const int cur = s & 1, nxt = cur ^ 1;
-      // operands of the next k-step: the next piece pair of this image, or (s = 3) the first of
-      // the next image, whose loads the barrier below has seen land
-      if (s == 3) { wait_all_loads(); barrier(); }
-      const int nt = s == 3 ? t + 1 : t, ns = (s + 1) & 3;   // (past the last stage: the repeated image, unused)
+      if (s < 3) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) { opa[nxt][i] = read_a(nt, ns, i); opb[nxt][i] = read_b(nt, ns, i); }
+        for (int i = 0; i < 4; ++i) { opa[nxt][i] = read_a(t, s + 1, i); opb[nxt][i] = read_b(t, s + 1, i); }
+      }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int a = 0; a < 4; ++a)
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
           gemm_mfma(acc[a][b], opa[cur][a], opb[cur][b]);
-          // the 16 loads of the next image go out under the MFMAs of the first two k-steps
+          // The 16 loads of the next image go out under the MFMAs of the first two k-steps.
+          // Measured alternatives: all 16 under the first k-step +2 %, spread over all four +8 %;
+          // a barrier before the last k-step (the next stage's first operands then come in under
+          // MFMAs, but the loads have one k-step less to land) +4 %; that plus a second barrier
+          // at the end of the stage +6 %.
           if (s < 2 && (b & 1)) dma_one(t + 1, 8 * s + 2 * a + (b >> 1));
         }
       __builtin_amdgcn_sched_barrier(0);
     }
-    barrier();                                          // everyone has left image t: it may be overwritten
+    // all loads of image t+1 have landed and everyone has left image t (the loads of the stage
+    // after next may overwrite it); the next stage's first operands are read behind the barrier
+    wait_all_loads();
+    barrier();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { opa[0][i] = read_a(t + 1, 0, i); opb[0][i] = read_b(t + 1, 0, i); }
   }
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
   gemm_store_tile<MODE>(acc, out, n_rows, n0, m0, wn, wm, nl, hh);
