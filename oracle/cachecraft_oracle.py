@@ -559,16 +559,24 @@ def layer_tail(h_rows: np.ndarray, attn_out: np.ndarray, w_o, gain_ffn, w_gate, 
     return h1, h2
 
 
-def recompute_layers(w, r: int, selected, weights: Sequence, h_in: Optional[Sequence[np.ndarray]] = None):
+def recompute_layers(w, r: int, selected, weights: Sequence, h_in: Optional[Sequence[np.ndarray]] = None,
+                     window: Optional[int] = None):
     """The chosen rows of request r through len(weights) decoder layers (every layer sees the same
     synthetic chunk store): per layer x = rms_norm(h) -> Q, K, V of those rows -> fix + attend over
     the re-positioned caches -> layer_tail.  The first layer's h are the rows of w.hidden; h_in[l],
     if given, replaces the running state at the start of layer l (so that one layer can be checked
-    at a time).  Returns per layer a dict with h_in, x, out, lse, h1, h2."""
+    at a time).  With a window, the question's attention to the chunks in every layer feeds
+    Algorithm 1 and, from the layer after the focused set settles, the other chunks' rows are
+    dropped (Sec. 3.2.2): their hidden states are not carried further.
+    Returns per layer a dict with selected, q_pos, h_in, x, out, lse, h1, h2 (+ mass, stop_layer, focused)."""
     hq, hkv, d = w.spec.n_q_heads, w.spec.n_kv_heads, w.spec.head_dim
+    selected = [np.asarray(s_) for s_ in selected]
     q_pos, q_row = query_list(w, r, selected)
     k_sh, v_c, _ = shifted_context(w, r)
+    segs = _segments_of(w, r)
+    chunk_ids = [i for i, sg in enumerate(segs) if sg[1] == 0]
     h = np.asarray(w.hidden[q_row], dtype=np.float64)
+    inter_hist, stop_layer, focused = [], None, None
     layers = []
     for l, lw in enumerate(weights):
         if h_in is not None and h_in[l] is not None:
@@ -576,10 +584,28 @@ def recompute_layers(w, r: int, selected, weights: Sequence, h_in: Optional[Sequ
         x = rms_norm(h, lw.gain_attn, lw.eps)
         qf, kf, vf = qkv_project(x, lw.w_qkv, hq, hkv, d)
         full = lambda a: _rows_at(a, q_row, w.n_tok)
-        _, _, _, _, out, lse = fix_and_attend(w, r, k_sh, v_c, selected, k_new=full(kf), v_new=full(vf), q=full(qf))
+        k_ctx, _, _, _, out, lse = fix_and_attend(w, r, k_sh, v_c, selected, k_new=full(kf), v_new=full(vf), q=full(qf))
         h1, h2 = layer_tail(h, out, lw.w_o, lw.gain_ffn, lw.w_gate, lw.w_up, lw.w_down, lw.eps)
-        layers.append({"h_in": h, "x": x, "out": out, "lse": lse, "h1": h1, "h2": h2})
+        rec = {"selected": selected, "q_pos": q_pos, "h_in": h, "x": x, "out": out, "lse": lse, "h1": h1, "h2": h2}
         h = h2
+        if window is not None:
+            mass = question_chunk_mass(w, r, k_ctx, q=full(qf))
+            rec["mass"] = mass
+            if stop_layer is None and chunk_ids:
+                inter_hist.append([mass[i] for i in chunk_ids])
+                f, l_star, _ = predict_focused(inter_hist, window)
+                if f is not None:
+                    stop_layer, focused = l_star, f
+                    # rows of the chunks that are not focused leave the list; the others keep their order
+                    keep = np.ones(len(q_pos), dtype=bool)
+                    for c, i in enumerate(chunk_ids):
+                        if c not in f:
+                            keep &= ~((q_pos >= segs[i][2]) & (q_pos < segs[i][2] + segs[i][3]))
+                    selected = [sel if c in f else np.zeros(0, dtype=np.int64) for c, sel in enumerate(selected)]
+                    h = h[keep]
+                    q_pos, q_row = query_list(w, r, selected)
+            rec["stop_layer"], rec["focused"] = stop_layer, focused
+        layers.append(rec)
     return layers
 
 

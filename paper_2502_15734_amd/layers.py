@@ -29,11 +29,15 @@ class DecoderLoop:
     cc_linear (output projection + residual) -> cc_rms_norm -> cc_gated_linear -> cc_linear (down
     projection + residual).  The rows are chosen once, before the first layer, from the workload's
     per-token queries (cc_select); every layer sees the same synthetic chunk store.
-    weights: one workload.LayerWeights per layer."""
+    weights: one workload.LayerWeights per layer.
+    window: if given, the question's attention to every chunk (a by-product of the attention call)
+    feeds Algorithm 1 in every layer; once a request's focused chunks are settled, the rows of its
+    other chunks leave the list (Sec. 3.2.2) and the surviving rows' hidden states are compacted."""
 
-    def __init__(self, w, weights: Sequence, impl: int = CC_IMPL_AUTO, device: str = "cuda"):
+    def __init__(self, w, weights: Sequence, window: Optional[int] = None, impl: int = CC_IMPL_AUTO,
+                 device: str = "cuda"):
         assert w.hidden is not None, "the workload must carry hidden states"
-        self.w = w
+        self.w, self.window = w, window
         self.batch = DeviceBatch(w, device=device, impl=impl)
         b = self.batch
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device).to(b.dt)
@@ -42,32 +46,59 @@ class DecoderLoop:
         self.eps = [float(lw.eps) for lw in weights]
         n, hidden, ffn = max(1, b.n_q_tot), w.hidden.shape[1], weights[0].w_gate.shape[0]
         mk = lambda cols: torch.empty((n, cols), dtype=b.dt, device=device)
-        self.h, self.h1, self.x, self.act = mk(hidden), mk(hidden), mk(hidden), mk(ffn)
+        self.h, self.h1, self.x, self.act, self.h_alt = mk(hidden), mk(hidden), mk(hidden), mk(ffn), mk(hidden)
+        seg = w.segments
+        self.chunk_segs = [[s for s in range(int(w.req_seg_off[r]), int(w.req_seg_off[r + 1])) if seg[s][1] == 0]
+                           for r in range(w.n_requests)]
+        self.trackers = [FocusTracker(max(1, len(c)), window) for c in self.chunk_segs] if window else []
+        self.budget = np.array(seg[:, 5], dtype=np.int64)
+        self.stop_layer: List[Optional[int]] = [None] * w.n_requests
+        self.focused: List[Optional[List[int]]] = [None] * w.n_requests
+        self.keep_idx = torch.zeros(n, dtype=torch.int32, device=device)
+
+    def _drop_rows(self, new_budget):
+        """New budgets: rebuild the row list (same scores, same order) and compact the hidden states."""
+        b = self.batch
+        old = np.array(getattr(b, "_seg_host", self.w.segments), copy=True)
+        b.set_budget(new_budget)
+        new = b._seg_host
+        keep = np.concatenate([np.arange(int(o[7]), int(o[7]) + int(nw[5])) for o, nw in zip(old, new)] or
+                              [np.zeros(0)]).astype(np.int32)
+        assert len(keep) == b.n_q_tot
+        if b.n_q_tot:
+            self.keep_idx[: len(keep)].copy_(torch.from_numpy(keep))
+            b.ctx.gather_rows(self.h, self.keep_idx[: len(keep)], self.h_alt[: len(keep)])
+            self.h, self.h_alt = self.h_alt, self.h
+            b.select_from_scores()
 
     def run(self, keep: bool = False):
-        """Returns one record per layer (ms; with keep also h_in, out, lse, h1, h2 as numpy arrays)."""
+        """Returns one record per layer (ms, rows; with keep also h_in, out, lse, h1, h2 as numpy arrays)."""
         b = self.batch
         b.rope_shift()
         b.select()
-        n = b.n_q_tot
         records = []
-        if n == 0:
-            return records
-        r = b._rows
-        h, h1, x, act = r(self.h), r(self.h1), r(self.x), r(self.act)
-        o2 = r(b.out).view(h.shape[0], -1)
-        b.ctx.gather_rows(b.hidden, r(b.q_row), h)
         for l, lw in enumerate(self.weights):
+            n = b.n_q_tot
+            if n == 0:
+                break
             t0 = torch.cuda.Event(enable_timing=True); t1 = torch.cuda.Event(enable_timing=True)
             t0.record()
+            h, h1, x, act = self.h[:n], self.h1[:n], self.x[:n], self.act[:n]
+            o2 = b.out[:n].view(n, -1)
+            if l == 0:
+                b.ctx.gather_rows(b.hidden, b.q_row[:n], h)
+            else:
+                b.rope_shift()                             # the next layer's chunk-caches, re-positioned
             rec = {"layer": l + 1, "rows": n}
             if keep:
                 rec["h_in"] = h.float().cpu().numpy()
-            if l > 0:
-                b.rope_shift()                             # the next layer's chunk-caches, re-positioned
+                rec["cu_q"] = np.array(getattr(b, "cu_q_host", self.w.cu_q), copy=True)
             b.ctx.rms_norm(h, lw["gain_attn"], self.eps[l], x)
-            b.ctx.qkv_project(x, lw["w_qkv"], r(b.q_c), r(b.k_c), r(b.v_c))
-            b.sparse_prefill()
+            b.ctx.qkv_project(x, lw["w_qkv"], b.q_c[:n], b.k_c[:n], b.v_c[:n])
+            if self.window:
+                mass = b.sparse_prefill_mass()
+            else:
+                b.sparse_prefill()
             b.ctx.linear(o2, lw["w_o"], h1, residual=h)
             b.ctx.rms_norm(h1, lw["gain_ffn"], self.eps[l], x)
             b.ctx.gated_linear(x, lw["w_gate"], lw["w_up"], act)
@@ -76,14 +107,37 @@ class DecoderLoop:
             rec["_events"] = (t0, t1)
             if keep:
                 torch.cuda.synchronize()
-                rec.update(out=r(b.out).float().cpu().numpy(), lse=r(b.lse).cpu().numpy(),
+                rec.update(out=b.out[:n].float().cpu().numpy(), lse=b.lse[:n].cpu().numpy(),
                            h1=h1.float().cpu().numpy(), h2=h.float().cpu().numpy())
+            if self.window:
+                m = mass.cpu().numpy()                     # (synchronises; Algorithm 1 runs on the host)
+                rec["mass"] = m[: len(self.w.segments)].copy()
+                changed = False
+                for r, segs in enumerate(self.chunk_segs):
+                    if self.stop_layer[r] is not None or not segs:
+                        continue
+                    stop, focused = self.trackers[r].update([float(m[s]) for s in segs])
+                    if stop:
+                        self.stop_layer[r], self.focused[r] = l + 1, focused
+                        for i, sgi in enumerate(segs):
+                            if i not in focused and self.budget[sgi]:
+                                self.budget[sgi] = 0
+                                changed = True
+                rec["stop_layer"] = list(self.stop_layer)
+                rec["focused"] = [None if f is None else list(f) for f in self.focused]
+                if changed and l + 1 < len(self.weights):
+                    self._drop_rows(self.budget)
             records.append(rec)
         torch.cuda.synchronize()
         for rec in records:
             t0, t1 = rec.pop("_events")
             rec["ms"] = t0.elapsed_time(t1)
         return records
+
+    def close(self):
+        for t in self.trackers:
+            t.close()
+        self.trackers = []
 
 
 class LayerLoop:

@@ -81,3 +81,38 @@ def test_decoder_loop_matches_the_oracle(dtype, impl):
             assert H.rel_l2(rec["h2"][q0:q1], o["h2"]) <= tol, f"{what}: h2 {H.rel_l2(rec['h2'][q0:q1], o['h2']):.3e}"
     # the layers do change the state
     assert H.rel_l2(recs[0]["h2"], recs[0]["h_in"]) > 0.1
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_decoder_loop_with_early_termination(dtype):
+    """Whole layers with Algorithm 1 deciding the focused chunks: from the layer after the stop the
+    other chunks' rows leave the list and the survivors' hidden states are compacted."""
+    from paper_2502_15734_amd.layers import DecoderLoop
+    w = _decoder_workload(dtype)
+    ffn = 640 if dtype == "bf16" else 160
+    weights = [W.layer_weights(w.spec, 256, ffn, layer=l, qkv_scale=1.0 / 16) for l in range(4)]
+    loop = DecoderLoop(w, weights, window=2)
+    recs = loop.run(keep=True)
+    assert len(recs) == 4
+    tol = H.TOL[dtype] if dtype == "bf16" else 2e-5
+    # the rows layer 1 chose (the later lists are subsets of them)
+    loop2 = DecoderLoop(w, weights[:1])
+    loop2.run()
+    gsel = H.gpu_selection(w, loop2.batch.sel_idx.cpu().numpy())
+    for r in range(w.n_requests):
+        forced = None
+        if dtype == "bf16":
+            forced = [rec["h_in"][int(rec["cu_q"][r]): int(rec["cu_q"][r + 1])] for rec in recs]
+        ref = O.recompute_layers(w, r, gsel[r], weights, h_in=forced, window=2)
+        for l, (rec, o) in enumerate(zip(recs, ref)):
+            what = f"request {r} layer {l + 1}"
+            q0, q1 = int(rec["cu_q"][r]), int(rec["cu_q"][r + 1])
+            assert q1 - q0 == len(o["q_pos"]), f"{what}: rows {q1 - q0} vs {len(o['q_pos'])}"
+            assert rec["stop_layer"][r] == o["stop_layer"] and rec["focused"][r] == o["focused"], what
+            assert H.rel_l2(rec["h_in"][q0:q1], o["h_in"]) <= tol, what
+            assert H.rel_l2(rec["out"][q0:q1], o["out"]) <= tol, what
+            assert H.rel_l2(rec["h2"][q0:q1], o["h2"]) <= tol, f"{what}: h2 {H.rel_l2(rec['h2'][q0:q1], o['h2']):.3e}"
+            s0, s1 = int(w.req_seg_off[r]), int(w.req_seg_off[r + 1])
+            np.testing.assert_allclose(rec["mass"][s0:s1], o["mass"], rtol=1e-2 if dtype == "bf16" else 1e-4, atol=1e-3)
+    assert recs[-1]["rows"] < recs[0]["rows"]
+    loop.close()

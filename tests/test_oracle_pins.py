@@ -747,3 +747,36 @@ def test_recompute_layers_chain_and_pass_through():
         lw.w_o = np.zeros_like(lw.w_o); lw.w_down = np.zeros_like(lw.w_down)
     ls = O.recompute_layers(w, 0, sel, ws)
     assert np.array_equal(ls[2]["h2"], w.hidden[q_row].astype(np.float64))
+
+
+def test_recompute_layers_early_termination_matches_the_attention_only_loop():
+    """With an identity projection and no output / down projection the hidden state never changes, so
+    every layer is the same attention: the windowed recompute must then stop, drop rows and report
+    masses exactly as layer_loop (pinned above) does on the hidden state's slices."""
+    import copy
+    w = _tiny_projected()
+    hq, hkv, d = w.spec.n_q_heads, w.spec.n_kv_heads, w.spec.head_dim
+    hid = w.hidden.shape[1]
+    w.hidden = (w.hidden / np.sqrt(np.mean(w.hidden.astype(np.float64) ** 2, axis=1, keepdims=True))).astype(np.float64)
+    lw = W.layer_weights(w.spec, hid, 96)
+    lw.w_qkv = np.eye(hid); lw.gain_attn = np.ones(hid); lw.eps = 0.0
+    lw.w_o = np.zeros_like(lw.w_o); lw.w_down = np.zeros_like(lw.w_down)
+    w2 = copy.copy(w)
+    w2.q = w.hidden[:, : hq * d].reshape(-1, hq, d)
+    w2.k_new = w.hidden[:, hq * d: (hq + hkv) * d].reshape(-1, hkv, d)
+    w2.v_new = w.hidden[:, (hq + hkv) * d:].reshape(-1, hkv, d)
+    for r in range(w.n_requests):
+        ref = O.layer_loop(w2, r, 4, 2, [1.0] * 4)
+        got = O.recompute_layers(w, r, ref[0]["selected"], [lw] * 4, window=2)
+        assert ref[1]["stop_layer"] == 2, "identical layers settle at the window"
+        for a, b in zip(got, ref):
+            assert a["stop_layer"] == b["stop_layer"] and a["focused"] == b["focused"]
+            assert np.array_equal(a["q_pos"], b["q_pos"])
+            assert np.allclose(a["mass"], b["mass"], rtol=1e-10, atol=1e-13)
+            assert np.allclose(a["out"], b["out"], rtol=1e-10, atol=1e-12)
+        # rows were really dropped where a chunk lost its focus, and the survivors kept their state
+        n0, n3 = len(got[0]["q_pos"]), len(got[3]["q_pos"])
+        n_chunks = len(ref[0]["selected"])
+        if len(got[3]["focused"]) < n_chunks and any(len(s) for c, s in enumerate(ref[0]["selected"]) if c not in got[3]["focused"]):
+            assert n3 < n0
+        assert np.array_equal(got[3]["h_in"], w.hidden[O.query_list(w, r, got[3]["selected"])[1]])
