@@ -198,12 +198,13 @@ def time_extra_calls(batch, w, work, steps: int, ms_per_step: float, sparse_pref
     preload = time_layerwise_preload(batch, ms_per_step)
     layer_loop = time_layer_loop(w)
     dense = time_decoder_dense(batch, w)
+    decoder = time_decoder_loop(w)
     return {"cc_select_from_scores": {"ms": from_scores_ms, "chunk_tokens": work["n_chunk_tok"]},
             "cc_question_mass": {"ms": question_mass_ms, "segments": int(len(w.segments))},
             "cc_sparse_prefill_mass": {"ms": prefill_mass_ms, "over_cc_sparse_prefill_ms": prefill_mass_ms - sparse_prefill_ms},
             "cc_chunk_attention": {"ms": chunk_attention_ms, "segment_pairs": int(batch.pair_off[-1])},
             "cc_sparse_prefill_pairs": {"ms": prefill_pairs_ms, "over_cc_sparse_prefill_ms": prefill_pairs_ms - sparse_prefill_ms},
-            "layerwise_preload": preload, "layer_loop": layer_loop, "decoder_layer_dense": dense}
+            "layerwise_preload": preload, "layer_loop": layer_loop, "decoder_layer_dense": dense, "decoder_loop": decoder}
 
 
 def time_decoder_dense(batch, w) -> dict:
@@ -250,6 +251,23 @@ def time_decoder_dense(batch, w) -> dict:
         out["calls"][name] = rec
     out["ms"] = total
     return out
+
+
+def time_decoder_loop(w, n_layers: int = 2) -> dict:
+    """Whole decoder layers for the recomputed rows of a workload that carries hidden states (config 5):
+    norm, QKV projection, partial prefill, output projection, feed-forward; feed-forward width 3.5 x hidden."""
+    import workload as W
+    from paper_2502_15734_amd.layers import DecoderLoop
+    if w.hidden is None or w.spec.dtype != "bf16":
+        return {}
+    hidden = int(w.hidden.shape[1])
+    ffn = hidden * 7 // 2
+    weights = [W.layer_weights(w.spec, hidden, ffn, layer=l) for l in range(n_layers)]
+    loop = DecoderLoop(w, weights)
+    loop.run()                                            # warm-up
+    recs = loop.run()
+    loop.close()
+    return {"hidden": hidden, "ffn": ffn, "layers": [{"layer": r["layer"], "rows": r["rows"], "ms": r["ms"]} for r in recs]}
 
 
 def time_layer_loop(w, n_layers: int = 4, window: int = 2) -> dict:

@@ -35,7 +35,9 @@ class DecoderLoop:
     other chunks leave the list (Sec. 3.2.2) and the surviving rows' hidden states are compacted."""
 
     def __init__(self, w, weights: Sequence, window: Optional[int] = None, impl: int = CC_IMPL_AUTO,
-                 device: str = "cuda"):
+                 device: str = "cuda", preload: bool = False, depth: int = 1):
+        """preload: every layer's chunk store comes from pinned host memory through the layer-wise
+        preloader (Algorithm 2), `depth` layers ahead of the one being computed."""
         assert w.hidden is not None, "the workload must carry hidden states"
         self.w, self.window = w, window
         self.batch = DeviceBatch(w, device=device, impl=impl)
@@ -55,6 +57,26 @@ class DecoderLoop:
         self.stop_layer: List[Optional[int]] = [None] * w.n_requests
         self.focused: List[Optional[List[int]]] = [None] * w.n_requests
         self.keep_idx = torch.zeros(n, dtype=torch.int32, device=device)
+        self.pre = None
+        if preload:
+            n_layers = len(weights)
+            self.k_host, self.v_host = b.k_store.cpu().pin_memory(), b.v_store.cpu().pin_memory()
+            n_slots = min(depth + 1, n_layers)
+            self.slots = [(torch.empty_like(b.k_store), torch.empty_like(b.v_store)) for _ in range(n_slots)]
+            self.pre = (Preloader(n_layers, depth, n_slots), Preloader(n_layers, depth, n_slots))
+            for l in range(n_layers):
+                self.pre[0].set_layer(l, self.k_host, self.slots[l % n_slots][0])
+                self.pre[1].set_layer(l, self.v_host, self.slots[l % n_slots][1])
+
+    def _shift(self, l):
+        """Layer l's chunk-caches (waiting for the preloader's copy if there is one), re-positioned."""
+        b = self.batch
+        if self.pre is not None:
+            self.pre[0].acquire(l); self.pre[1].acquire(l)
+            b.k_store, b.v_store = self.slots[l % len(self.slots)]
+        b.rope_shift()
+        if self.pre is not None:                               # the store slot is free once the shift has read it
+            self.pre[0].release(l); self.pre[1].release(l)
 
     def _drop_rows(self, new_budget):
         """New budgets: rebuild the row list (same scores, same order) and compact the hidden states."""
@@ -74,7 +96,7 @@ class DecoderLoop:
     def run(self, keep: bool = False):
         """Returns one record per layer (ms, rows; with keep also h_in, out, lse, h1, h2 as numpy arrays)."""
         b = self.batch
-        b.rope_shift()
+        self._shift(0)
         b.select()
         records = []
         for l, lw in enumerate(self.weights):
@@ -88,7 +110,7 @@ class DecoderLoop:
             if l == 0:
                 b.ctx.gather_rows(b.hidden, b.q_row[:n], h)
             else:
-                b.rope_shift()                             # the next layer's chunk-caches, re-positioned
+                self._shift(l)
             rec = {"layer": l + 1, "rows": n}
             if keep:
                 rec["h_in"] = h.float().cpu().numpy()
@@ -138,6 +160,10 @@ class DecoderLoop:
         for t in self.trackers:
             t.close()
         self.trackers = []
+        if self.pre is not None:
+            for p in self.pre:
+                p.close()
+            self.pre = None
 
 
 class LayerLoop:

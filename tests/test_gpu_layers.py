@@ -83,15 +83,15 @@ def test_decoder_loop_matches_the_oracle(dtype, impl):
     assert H.rel_l2(recs[0]["h2"], recs[0]["h_in"]) > 0.1
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_decoder_loop_with_early_termination(dtype):
+@pytest.mark.parametrize("dtype,preload", [("f32", False), ("bf16", False), ("bf16", True)])
+def test_decoder_loop_with_early_termination(dtype, preload):
     """Whole layers with Algorithm 1 deciding the focused chunks: from the layer after the stop the
     other chunks' rows leave the list and the survivors' hidden states are compacted."""
     from paper_2502_15734_amd.layers import DecoderLoop
     w = _decoder_workload(dtype)
     ffn = 640 if dtype == "bf16" else 160
     weights = [W.layer_weights(w.spec, 256, ffn, layer=l, qkv_scale=1.0 / 16) for l in range(4)]
-    loop = DecoderLoop(w, weights, window=2)
+    loop = DecoderLoop(w, weights, window=2, preload=preload, depth=2)
     recs = loop.run(keep=True)
     assert len(recs) == 4
     tol = H.TOL[dtype] if dtype == "bf16" else 2e-5
