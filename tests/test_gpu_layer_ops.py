@@ -58,7 +58,9 @@ def test_rms_norm(dtype, rows, hidden):
 
 LINEAR_CASES = [("f32", "auto", 37, 40, 50), ("f32", "auto", 130, 64, 256), ("bf16", "auto", 300, 256, 512),
                 ("bf16", "auto", 256, 96, 256), ("bf16", "auto", 41, 72, 40), ("bf16", "scalar", 70, 256, 256),
-                ("bf16", "narrow", 70, 256, 256), ("bf16", "wide", 513, 1024, 768)]
+                ("bf16", "narrow", 70, 256, 256), ("bf16", "wide", 513, 1024, 768),
+                ("bf16", "auto", 1, 64, 256), ("bf16", "auto", 257, 128, 256),      # one and two 64-wide stages
+                ("bf16", "auto", 2300, 192, 1280)]                                  # tile blocks with ragged edges
 
 
 @pytest.mark.parametrize("dtype,impl,rows,n_in,n_out", LINEAR_CASES)
@@ -82,7 +84,7 @@ def test_linear_with_and_without_residual(dtype, impl, rows, n_in, n_out):
 
 
 GATED_CASES = [("f32", "auto", 37, 40, 50), ("bf16", "auto", 300, 256, 384), ("bf16", "auto", 41, 72, 40),
-               ("bf16", "scalar", 70, 256, 128), ("bf16", "wide", 513, 512, 640)]
+               ("bf16", "scalar", 70, 256, 128), ("bf16", "wide", 513, 512, 640), ("bf16", "auto", 5, 64, 128)]
 
 
 @pytest.mark.parametrize("dtype,impl,rows,n_in,n_ffn", GATED_CASES)
