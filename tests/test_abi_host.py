@@ -98,6 +98,13 @@ def test_calls_reject_bad_arguments_before_launch(lib):
     assert lib.cc_sparse_prefill(*args, good, None, good, ws, None) == -1
     args[8], args[9] = 0, 0
     assert lib.cc_sparse_prefill(*args, good, None, good, ws, None) == 0
+    # grid limits: more than 65535 requests (cc_sparse_prefill) or segments (cc_select) in one call are refused
+    big = [h, good, good, good, None, good, good, good, 70000, 10, good, good, 8, good, good, 70000, good, 70000, 70000]
+    wsb = lib.cc_sparse_prefill_workspace_bytes(h, 70000, 70000)
+    assert lib.cc_sparse_prefill(*big, good, None, good, wsb, None) == -1 and b"65535" in lib.cc_last_error(h)
+    need_big = lib.cc_select_workspace_bytes(h, 70000, 70000)
+    assert lib.cc_select(h, good, 70000, good, 8, good, good, 70000, good, 1, 64, good, None, None, None, 10,
+                         None, good, need_big, None) == -1 and b"65535" in lib.cc_last_error(h)
     # cc_scatter_kv: null pool, misaligned rows, nothing to do
     assert lib.cc_scatter_kv(h, good, good, good, good, 4, None, good, 8, None) == -1
     assert lib.cc_scatter_kv(h, odd, good, good, good, 4, good, good, 8, None) == -1
