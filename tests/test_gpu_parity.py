@@ -552,3 +552,32 @@ class _SparseRows:
 
 def _scatter_rows(a, rows, n_tok, nh, d):
     return _SparseRows(a, rows)
+
+
+def test_step_replays_in_a_hip_graph():
+    """The whole step only enqueues kernels on the caller's stream (no allocation, no memset, no
+    synchronisation), so a caller may capture it; every replay, with eager work in between, must
+    give the eager result bit for bit."""
+    from paper_2502_15734_amd.pipeline import DeviceBatch
+    w = W.config(3, scale=0.25)
+    b = DeviceBatch(w)
+    b.step(); torch.cuda.synchronize()
+    n = b.n_q_tot
+    want = [t.clone() for t in (b.out[:n], b.lse[:n], b.sel_idx[:n], b.scores, b.k_req, b.v_req)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        b.step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        b.step()
+    for rep in range(3):
+        b.out.fill_(float("nan")); b.lse.zero_(); b.sel_idx.zero_(); b.scores.zero_()
+        b.k_req.zero_(); b.v_req.zero_()              # (the state the eager step started from)
+        torch.cuda.synchronize()
+        graph.replay(); torch.cuda.synchronize()
+        got = (b.out[:n], b.lse[:n], b.sel_idx[:n], b.scores, b.k_req, b.v_req)
+        for i, (g, e) in enumerate(zip(got, want)):
+            assert torch.equal(g.view(torch.uint8), e.view(torch.uint8)), f"replay {rep}, tensor {i}"
