@@ -146,7 +146,7 @@ def check_chunk_attention(w, b, res):
     check_pair_values(w, pair.cpu().numpy(), self_w.cpu().numpy(), pair_off, res)
 
 
-def check_prefill_with_pairs(w, b, res, k_ctx_of):
+def check_prefill_with_pairs(w, b, res, k_ctx_of, check_self=True):
     """cc_sparse_prefill_pairs on a batch that has just run cc_sparse_prefill: the attention results
     must be the same bits; pair / self sums and the question's masses the oracle's."""
     out1, lse1 = b.out.clone(), b.lse.clone()
@@ -158,13 +158,13 @@ def check_prefill_with_pairs(w, b, res, k_ctx_of):
     n = b.n_q_tot
     assert torch.equal(out1[:n], b.out[:n]) and torch.equal(lse1[:n], b.lse[:n])
     assert torch.isfinite(pair).all() and torch.isfinite(self_w).all() and torch.isfinite(b.seg_mass).all()
-    check_pair_values(w, pair.cpu().numpy(), self_w.cpu().numpy(), pair_off, res)
+    check_pair_values(w, pair.cpu().numpy(), self_w.cpu().numpy(), pair_off, res, check_self=check_self)
     check_question_mass_values(w, b.seg_mass.cpu().numpy(), k_ctx_of)
     b.sparse_prefill_pairs(); torch.cuda.synchronize()                  # same workspace, same answer
     assert torch.equal(pair_again, b.pair_mass)
 
 
-def check_pair_values(w, pair, self_w, pair_off, res, requests=None):
+def check_pair_values(w, pair, self_w, pair_off, res, requests=None, check_self=True):
     bf = w.spec.dtype == "bf16"
     for r in (range(w.n_requests) if requests is None else requests):
         s0, s1 = int(w.req_seg_off[r]), int(w.req_seg_off[r + 1])
@@ -178,7 +178,8 @@ def check_pair_values(w, pair, self_w, pair_off, res, requests=None):
             bound = (1e-2 if bf else 1e-4) * m[t, :t + 1] + (1e-4 if bf else 1e-6) * max(1.0, n_rows[t])
             assert np.all(np.abs(row - m[t, :t + 1]) <= bound), f"request {r} segment {t}: {row} vs {m[t, :t + 1]}"
             assert abs(row.sum() - n_rows[t]) <= (3e-3 if bf else 2e-5) * max(1.0, n_rows[t])
-            assert abs(self_w[s0 + t] - sw[t]) <= (1e-2 if bf else 1e-4) * sw[t] + (1e-4 if bf else 1e-6) * max(1.0, n_rows[t])
+            if check_self:
+                assert abs(self_w[s0 + t] - sw[t]) <= (1e-2 if bf else 1e-4) * sw[t] + (1e-4 if bf else 1e-6) * max(1.0, n_rows[t])
 
 
 def _impls():
@@ -412,6 +413,10 @@ def test_reference_repair_path_when_later_keys_dwarf_the_first_tile(kval):
         b.gather()
         check_question_mass(w, b, [ref.k_ctx])
         check_prefill_with_mass(w, b, [ref.k_ctx])
+        # ... and the whole segment-to-segment matrix as a by-product (overflowed rows by the scalar route)
+        # (a row's weight on its own key is not compared here: the first 64 rows' logits sit on bf16 keys of
+        #  magnitude 50, whose rounding moves exp(logit - lse) by more than 10 %)
+        check_prefill_with_pairs(w, b, [ref], [ref.k_ctx], check_self=False)
 
 
 def _projected_reference(w, b, r, gsel):
