@@ -24,6 +24,8 @@
  *                      (Sec. 3.2.2); cc_focus_* turns it into the set of focused chunks (Algorithm 1)
  *   cc_preloader_*     layer-wise preloading of chunk-caches from host memory on a copy stream
  *                      (Sec. 3.4.2, Algorithm 2)
+ *   cc_sparse_prefill_pairs  cc_sparse_prefill that also returns cc_chunk_attention's sums (the chunk-cache
+ *                      metadata of Sec. 3.4.3) as a by-product of the attention kernel where it can
  *   cc_chunk_attention inter / intra attention sums between the segments of a prompt (Eq. (2), (3));
  *                      cc_chunk_ab / cc_chunk_cci / cc_chunk_reuse: CCI, beta, gamma, beta', CFO and
  *                      the token budget from them on the host (Sec. 3.1, 3.3)
