@@ -420,7 +420,9 @@ __device__ __forceinline__ int gemm_swz(int r) { return ((r >> 1) & 7) ^ ((r & 1
 // the block's 32 workgroups ask their L2 for 12 different operand panels instead of up to 34
 // (L2 hit rate 48 % -> 82 %, memory reads a third; 3 - 7 % faster for the plain products).  The
 // gated product keeps the plain order (feature tile fastest): every blocked order tried was 5 - 10 %
-// slower there although it, too, cut the memory reads to a third.
+// slower there although it, too, cut the reads that leave the L2s to a third - in the plain order
+// all XCDs walk the same rows of token tiles together, so the activations stream from HBM once,
+// and an XCD keeps to one fixed set of weight panels, which the memory-side cache can hold.
 constexpr int kBlockN = 4, kBlockM = 8;
 
 template <int MODE>
