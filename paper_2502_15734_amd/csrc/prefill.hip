@@ -44,18 +44,19 @@ void launch_gather_rows(const void* src, int n_src_rows, const int32_t* row_idx,
 //   slots -- and isolated 2-byte stores cost a full memory write each, so every (head, dim) row
 //   of the block is read, patched with the run's tokens in registers, and written back whole.
 //   This needs all rows of a block to sit in ONE run.
-constexpr int kScatterRows = 16;     // candidate rows per workgroup
+constexpr int kScatterRows = 16;     // candidate rows per workgroup (4 or 8 measured the same, 1 or 2 slower)
 
 template <typename T, int D>
 __global__ __launch_bounds__(256) void rope_scatter_kernel(
     const T* __restrict__ k_new, const T* __restrict__ v_new, const int32_t* __restrict__ q_pos,
     const int32_t* __restrict__ slot_map, int n_q_tot, int hkv, InvFreq inv_freq,
     T* __restrict__ k_pool, T* __restrict__ v_pool, int n_blocks, const int32_t* __restrict__ src_rows) {
-  // slots of rows base-1 .. base+30: the row before the first candidate (is it the same block?) and
-  // the 15 rows a run starting at the last candidate can still cover; -1 = no row / invalid slot
-  __shared__ int sl[2 * kScatterRows];
+  // slots of rows base-1 .. base+kScatterRows+14: the row before the first candidate (is it the same
+  // block?) and the 15 rows a run starting at the last candidate can still cover; -1 = no row /
+  // invalid slot
+  __shared__ int sl[kScatterRows + kBlock];
   const int tid = threadIdx.x, base = blockIdx.x * kScatterRows;
-  if (tid < 2 * kScatterRows) {
+  if (tid < kScatterRows + kBlock) {
     const int j = base - 1 + tid;
     int v = -1;
     if (j >= 0 && j < n_q_tot) {
@@ -78,7 +79,8 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(
       const int t = idx / (D / 2), i = idx % (D / 2);
       const int j = j0 + t;
       float cs, sn;
-      rot_cos_sin(q_pos[j], inv_freq.f[i], &cs, &sn);
+      if (sizeof(T) == 2) rot_cos_sin_fast(q_pos[j], inv_freq.f[i], &cs, &sn);   // (the result is rounded to bf16)
+      else rot_cos_sin(q_pos[j], inv_freq.f[i], &cs, &sn);
       const T* kp = k_new + static_cast<size_t>(src_rows != nullptr ? src_rows[j] : j) * hkv * D;   // (row of k_new, v_new this list row reads)
       T* ko = k_pool + (static_cast<size_t>(blk) * hkv * kBlock + sl[c + 1 + t] % kBlock) * D;
       for (int h = 0; h < hkv; ++h) {
