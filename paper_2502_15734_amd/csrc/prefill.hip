@@ -38,8 +38,7 @@ void launch_gather_rows(const void* src, int n_src_rows, const int32_t* row_idx,
 // list that fall into the same 16-token block are adjacent (the order cc_select emits) and form a
 // run.  A workgroup looks at 16 consecutive rows and handles every run that STARTS among them (a
 // run may reach into the next workgroup's rows; it is still handled where it starts).
-//   K rows are token-major and written directly; the rotation angle of a (token, pair) is
-//   computed once and used for all KV heads.
+//   K rows are token-major and written directly, in 16-byte pieces.
 //   The V block is dimension-major -- a token is one element in each of the block's d rows of 16
 //   slots -- and isolated 2-byte stores cost a full memory write each, so every (head, dim) row
 //   of the block is read, patched with the run's tokens in registers, and written back whole.
@@ -74,20 +73,28 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(
     int n_run = 1;
     while (n_run < kBlock && sl[c + 1 + n_run] >= 0 && sl[c + 1 + n_run] / kBlock == blk) ++n_run;
     const int j0 = base + c;
-    // K: one (token, pair) per thread and step, all KV heads
-    for (int idx = tid; idx < n_run * (D / 2); idx += 256) {
-      const int t = idx / (D / 2), i = idx % (D / 2);
-      const int j = j0 + t;
-      float cs, sn;
-      if (sizeof(T) == 2) rot_cos_sin_fast(q_pos[j], inv_freq.f[i], &cs, &sn);   // (the result is rounded to bf16)
-      else rot_cos_sin(q_pos[j], inv_freq.f[i], &cs, &sn);
-      const T* kp = k_new + static_cast<size_t>(src_rows != nullptr ? src_rows[j] : j) * hkv * D;   // (row of k_new, v_new this list row reads)
-      T* ko = k_pool + (static_cast<size_t>(blk) * hkv * kBlock + sl[c + 1 + t] % kBlock) * D;
-      for (int h = 0; h < hkv; ++h) {
-        const float x = to_float(kp[h * D + i]), y = to_float(kp[h * D + i + D / 2]);
-        ko[static_cast<size_t>(h) * kBlock * D + i] = from_float<T>(x * cs - y * sn);
-        ko[static_cast<size_t>(h) * kBlock * D + i + D / 2] = from_float<T>(y * cs + x * sn);
+    // K: one (token, KV head, 16-byte piece of the head's first half) per thread and step, together
+    // with the matching piece of the second half: two 16-byte loads, kPer rotations, two 16-byte stores
+    constexpr int kPer = 16 / sizeof(T), kPieces = D / 2 / kPer;
+    for (int idx = tid; idx < n_run * hkv * kPieces; idx += 256) {
+      const int p = idx % kPieces, h = (idx / kPieces) % hkv, t = idx / (kPieces * hkv);
+      const int j = j0 + t, pos = q_pos[j];
+      const T* kp = k_new + (static_cast<size_t>(src_rows != nullptr ? src_rows[j] : j) * hkv + h) * D + kPer * p;   // (row of k_new, v_new this list row reads)
+      T* ko = k_pool + ((static_cast<size_t>(blk) * hkv + h) * kBlock + sl[c + 1 + t] % kBlock) * D + kPer * p;
+      T x[kPer], y[kPer], ox[kPer], oy[kPer];
+      *reinterpret_cast<uint4*>(x) = *reinterpret_cast<const uint4*>(kp);
+      *reinterpret_cast<uint4*>(y) = *reinterpret_cast<const uint4*>(kp + D / 2);
+#pragma unroll
+      for (int e = 0; e < kPer; ++e) {
+        float cs, sn;
+        if (sizeof(T) == 2) rot_cos_sin_fast(pos, inv_freq.f[kPer * p + e], &cs, &sn);   // (the result is rounded to bf16)
+        else rot_cos_sin(pos, inv_freq.f[kPer * p + e], &cs, &sn);
+        const float xv = to_float(x[e]), yv = to_float(y[e]);
+        ox[e] = from_float<T>(xv * cs - yv * sn);
+        oy[e] = from_float<T>(yv * cs + xv * sn);
       }
+      *reinterpret_cast<uint4*>(ko) = *reinterpret_cast<uint4*>(ox);
+      *reinterpret_cast<uint4*>(ko + D / 2) = *reinterpret_cast<uint4*>(oy);
     }
     // V: one (head, dim) row of 16 slots per thread and step
     constexpr int kVec = kBlock * sizeof(T) / 16;          // 16-byte vectors per row
