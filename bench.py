@@ -30,8 +30,8 @@ MEASURED_MFMA_BF16_TFLOPS = 1880.0
 # HBM bytes per launch of each call's main kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # of this command scaled by a 512 MiB copy (profiles/hot_path_kernels_config3_8b_continuous_batch.md).
 MEASURED_TRAFFIC_BYTES = {
-    3: {"cc_rope_shift": (568.3 + 646.5) * 2 ** 20, "cc_select": (2760.5 + 34.3 + 17.3 + 1.3) * 2 ** 20,
-        "cc_sparse_prefill": (1044.5 + 319.6 + 165.0 + 159.0) * 2 ** 20},
+    3: {"cc_rope_shift": (568.1 + 646.5) * 2 ** 20, "cc_select": (2763.1 + 34.3 + 17.3 + 1.3) * 2 ** 20,
+        "cc_sparse_prefill": (1044.0 + 319.6 + 165.1 + 159.0) * 2 ** 20},
 }
 
 
