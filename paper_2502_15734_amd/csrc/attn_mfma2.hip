@@ -51,7 +51,10 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 
 constexpr int kImage = 2048;    // 16-byte pieces per tile image (K: 1024, V: 1024)
 constexpr int kBufs = 4;
-constexpr int kDepth = 4;       // operand reads in flight ahead of the MFMAs
+#ifndef CC_RING_DEPTH
+#define CC_RING_DEPTH 4
+#endif
+constexpr int kDepth = CC_RING_DEPTH;       // operand reads in flight ahead of the MFMAs
 // p = exp2(S - reference) may be large (fp32 and bf16 share the exponent range); a block sum
 // beyond this leaves no headroom for the row sum and O
 constexpr float kSafeSum = 1.0e30f;
@@ -302,19 +305,40 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
   };
 
   // ---- descriptors and staging --------------------------------------------------------------------
-  // The descriptors of 64 consecutive tiles sit in vector registers, one tile per lane, and are
-  // handed out with v_readlane: no memory access per tile.
+  // What the loop needs of 64 consecutive tiles sits in vector registers, one tile per lane, and is
+  // handed out with v_readlane: no memory access per tile.  The pages this wavefront brings in (its
+  // V page and the two pages of its K groups) are picked once per window, so that a tile's
+  // descriptor is a handful of scalars and never an indexed array.
+  struct HotDesc {
+    int kpos0;     // logical position of the tile's first key
+    int nvalid;    // keys of the tile that exist
+    int seg;       // segment of the tile
+    int own;       // physical block of V page `wave` (-1: none)
+    int ka, kb;    // physical blocks of the two pages of the K block this wavefront feeds
+    int edge;      // the tile has padding slots or missing pages
+  };
   int win_base = 0;
-  TileDesc win = fetch_desc(tiles, j_begin + min(lane, n_t - 1), max_tiles);
+  int w_kpos0, w_nvalid, w_seg, w_own, w_ka, w_kb, w_edge;
+  auto fill_window = [&](int base) __attribute__((always_inline)) {
+    const TileDesc v = fetch_desc(tiles, j_begin + min(base + lane, n_t - 1), max_tiles);
+    const int b0 = v.blk[0], b1 = v.blk[1], b2 = v.blk[2], b3 = v.blk[3];
+    w_kpos0 = v.kpos0; w_nvalid = v.nvalid; w_seg = v.seg;
+    w_own = wave == 0 ? b0 : wave == 1 ? b1 : wave == 2 ? b2 : b3;
+    w_ka = wave >= 2 ? b2 : b0;
+    w_kb = wave >= 2 ? b3 : b1;
+    w_edge = (v.nvalid < kTile || (b0 | b1 | b2 | b3) < 0) ? 1 : 0;
+  };
+  fill_window(0);
   auto desc_of = [&](int t) __attribute__((always_inline)) {           // t in [win_base, win_base + 64)
     const int l = t - win_base;
-    TileDesc d;
-    d.kpos0 = __builtin_amdgcn_readlane(win.kpos0, l);
-    d.nvalid = __builtin_amdgcn_readlane(win.nvalid, l);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) d.blk[i] = __builtin_amdgcn_readlane(win.blk[i], l);
-    d.seg = __builtin_amdgcn_readlane(win.seg, l);
-    d.pad = 0;
+    HotDesc d;
+    d.kpos0 = __builtin_amdgcn_readlane(w_kpos0, l);
+    d.nvalid = __builtin_amdgcn_readlane(w_nvalid, l);
+    d.seg = __builtin_amdgcn_readlane(w_seg, l);
+    d.own = __builtin_amdgcn_readlane(w_own, l);
+    d.ka = __builtin_amdgcn_readlane(w_ka, l);
+    d.kb = __builtin_amdgcn_readlane(w_kb, l);
+    d.edge = __builtin_amdgcn_readlane(w_edge, l);
     return d;
   };
   auto image_off = [&](int t) __attribute__((always_inline)) { return (t & (kBufs - 1)) * (kImage * 16); };   // bytes
@@ -330,38 +354,36 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
   const int v_lane_off = n * 32 + hh * 16;
   typedef __attribute__((address_space(3))) const uint4 lds_piece;
   const uint32_t lds_base = uniform(static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_piece*)lds_all)));   // LDS byte address
-  // (selections instead of indexing: the descriptor lives in scalar registers)
-  auto own_page = [&](const TileDesc& d) __attribute__((always_inline)) {
-    return wave == 0 ? d.blk[0] : wave == 1 ? d.blk[1] : wave == 2 ? d.blk[2] : d.blk[3];
-  };
   const char* k_src = nullptr;                                           // of the tile being loaded
   const char* v_src = nullptr;
   uint32_t k_dst = 0;
-  auto dma_begin = [&](const TileDesc& d, int img_off) __attribute__((always_inline)) {
-    const bool upper = wave >= 2;                                        // K block this wavefront feeds
-    const size_t o0 = static_cast<size_t>(max(upper ? d.blk[2] : d.blk[0], 0)) * blk_bytes;
-    const size_t o1 = static_cast<size_t>(max(upper ? d.blk[3] : d.blk[1], 0)) * blk_bytes;
+  auto dma_begin = [&](const HotDesc& d, int img_off) __attribute__((always_inline)) {
+    const size_t o0 = static_cast<size_t>(max(d.ka, 0)) * blk_bytes;
+    const size_t o1 = static_cast<size_t>(max(d.kb, 0)) * blk_bytes;
     k_src = k_head + (k_second_page ? o1 : o0) + k_lane_off + (wave & 1) * 128;
-    v_src = v_head + static_cast<size_t>(max(own_page(d), 0)) * blk_bytes + v_lane_off;
+    v_src = v_head + static_cast<size_t>(max(d.own, 0)) * blk_bytes + v_lane_off;
     k_dst = lds_base + img_off + (4 * wave) * 1024;
   };
   auto dma_part = [&](int j) __attribute__((always_inline)) {           // j = 0..3: one K group, one V group
     load_to_lds(k_src + 32 * j, k_dst + 1024 * j);
     load_to_lds(v_src + 1024 * j, k_dst + 16 * 1024 + 1024 * j);
   };
-  auto dma_tile = [&](const TileDesc& d, int img_off) __attribute__((always_inline)) {
+  auto dma_tile = [&](const HotDesc& d, int img_off) __attribute__((always_inline)) {
     dma_begin(d, img_off);
 #pragma unroll
     for (int j = 0; j < 4; ++j) dma_part(j);
   };
   // blank the padding slots of the V page this wavefront loaded (rare; after its loads have landed)
-  auto blank_padding = [&](const TileDesc& d, int img_off) __attribute__((always_inline)) {
-    if (d.nvalid < kTile || (d.blk[0] | d.blk[1] | d.blk[2] | d.blk[3]) < 0) {
-      const int nv = own_page(d) < 0 ? 0 : min(max(d.nvalid - kBlock * wave, 0), kBlock);
+  auto blank_padding = [&](const HotDesc& d, int img_off) __attribute__((always_inline)) {
+    if (d.edge) {
+      const int nv = d.own < 0 ? 0 : min(max(d.nvalid - kBlock * wave, 0), kBlock);
       if (nv < kBlock) {
         uint4* vp = reinterpret_cast<uint4*>(const_cast<char*>(lds_bytes) + img_off + (16 + 4 * wave) * 1024 + lane16);
 #pragma unroll
         for (int j = 0; j < 4; ++j) vp[j * 64] = zero_pad_slots(vp[j * 64], hh, nv);
+        // (a rare branch leaves nothing pending, so that the code behind the join waits for no more
+        // than the straight path does)
+        __builtin_amdgcn_s_waitcnt((15) | (3 << 14) | (7 << 4) | (0 << 8));      // lgkmcnt(0)
       }
     }
   };
@@ -378,7 +400,7 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
   };
 
   // prologue: images 0, 1, 2; S of block 0 and the first half of its exponentials
-  TileDesc d0 = desc_of(0), d1 = desc_of(min(1, n_t - 1)), d2 = desc_of(min(2, n_t - 1)), d3 = d2;
+  HotDesc d0 = desc_of(0), d1 = desc_of(min(1, n_t - 1)), d2 = desc_of(min(2, n_t - 1)), d3 = d2;
   dma_tile(d0, image_off(0));
   dma_tile(d1, image_off(1));
   dma_tile(d2, image_off(2));
@@ -439,6 +461,7 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
           cum[(static_cast<size_t>(sr) * hq + h) * s_max + sl] = v;
       }
     }
+    __builtin_amdgcn_s_waitcnt((15) | (3 << 14) | (7 << 4) | (0 << 8));          // lgkmcnt(0): see blank_padding
   };
   auto tile_front = [&](auto next_tag, int t) __attribute__((always_inline)) {
     constexpr bool kNext = decltype(next_tag)::value;
@@ -466,7 +489,7 @@ __global__ __launch_bounds__(256, 1) void attn_v2_kernel(
     const int img = image_off(t), nimg = image_off(t + 1);
     if (t + 3 - win_base >= 64) {                        // next 64 descriptors (rare)
       win_base += 64;
-      win = fetch_desc(tiles, j_begin + min(win_base + lane, n_t - 1), max_tiles);
+      fill_window(win_base);
       __builtin_amdgcn_s_waitcnt((7 << 4) | (15 << 8));      // vmcnt(0) here, so the hot path never waits for it
     }
     tile_front(NextT{}, t);
