@@ -35,7 +35,8 @@ class _Config(C.Structure):
 
 
 def library_path() -> str:
-    return os.path.join(_HERE, "libcachecraft.so")
+    """The in-tree library; CACHECRAFT_LIBRARY names another build of it (kernel experiments)."""
+    return os.environ.get("CACHECRAFT_LIBRARY") or os.path.join(_HERE, "libcachecraft.so")
 
 
 def load_library() -> C.CDLL:
