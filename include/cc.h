@@ -197,8 +197,8 @@ int cc_gather_rows(cc_ctx* ctx, const void* src, int32_t n_src_rows, const int32
  * [q | k | v] = x W^T with x [n_rows][hidden] and W [(Hq + 2 Hkv) d][hidden] row-major (one row
  * of `hidden` weights per output feature: q heads, then k heads, then v heads -- both operands
  * have the contraction index contiguous, which is what the matrix cores want); outputs
- * q [n_rows][Hq][d], k, v [n_rows][Hkv][d].  hidden must be a multiple of 64.  Sec. 3.4.3 (K, V and Q are computed only for new and
- * recomputation tokens). */
+ * q [n_rows][Hq][d], k, v [n_rows][Hkv][d].  hidden must be a multiple of 64.  The projection is
+ * restricted to the rows of the compact list (Sec. 3.4.3). */
 int cc_qkv_project(cc_ctx* ctx, const void* x, const void* w_qkv, int32_t n_rows, int32_t hidden,
                    void* q, void* k, void* v, void* stream);
 

@@ -268,6 +268,7 @@ int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void*
              "negative count");
   CC_REQUIRE(max_q_per_req <= n_q_tot, "max_q_per_req exceeds n_q_tot");
   if (n_q_tot == 0) return CC_OK;
+  CC_REQUIRE(n_q_tot <= n_ctx_tokens, "n_ctx_tokens must bound the rows of the compact list");
   CC_REQUIRE(q && k_new && v_new && q_pos && slot_map && cu_q && k_pool && v_pool && block_tab &&
                  segs && req_seg_off && out, "null pointer");
   CC_REQUIRE(n_blocks > 0 && n_requests > 0 && n_segs > 0 && max_q_per_req > 0, "sizes must be positive");

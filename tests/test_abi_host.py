@@ -98,6 +98,9 @@ def test_calls_reject_bad_arguments_before_launch(lib):
     assert lib.cc_sparse_prefill(*args, good, None, good, ws, None) == -1
     args[8], args[9] = 0, 0
     assert lib.cc_sparse_prefill(*args, good, None, good, ws, None) == 0
+    # rows of the compact list beyond n_ctx_tokens (the redo flags in the workspace are sized by it)
+    few = [h, good, good, good, None, good, good, good, 10, 10, good, good, 8, good, good, 3, good, 1, 9]
+    assert lib.cc_sparse_prefill(*few, good, None, good, ws, None) == -1 and b"n_ctx_tokens" in lib.cc_last_error(h)
     # grid limits: more than 65535 requests (cc_sparse_prefill) or segments (cc_select) in one call are refused
     big = [h, good, good, good, None, good, good, good, 70000, 10, good, good, 8, good, good, 70000, good, 70000, 70000]
     wsb = lib.cc_sparse_prefill_workspace_bytes(h, 70000, 70000)
