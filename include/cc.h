@@ -253,6 +253,29 @@ int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void*
                       const int32_t* req_seg_off, int32_t n_requests, int32_t n_ctx_tokens,
                       void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- (c') cc_sparse_prefill for callers that cannot allocate ---------------------------------
+ * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc: the
+ * same call (same kernels, same results bit for bit) without a workspace argument.  The key-tile
+ * plan and the redo flags go into an array of CC_STATIC_SCRATCH_BYTES that is part of the
+ * library's code object: every GPU the library runs on holds one copy until the process ends.
+ * The call allocates nothing and frees nothing.  The array's address on a device is looked up
+ * once, by cc_create for the device current then, else by the first call on that device (that
+ * look-up, not the call, is what must stay outside a graph capture).
+ *   Limit: cc_sparse_prefill_workspace_bytes(ctx, n_ctx_tokens, n_segs) <= CC_STATIC_SCRATCH_BYTES
+ *   (about 30 000 key tiles: two million context tokens per call); larger batches return
+ *   CC_ERR_WORKSPACE_TOO_SMALL before any launch.
+ *   All calls on one GPU share that GPU's array, on every stream and from every context: two calls
+ *   whose kernels may overlap on one GPU race.  Calls ordered on one stream are safe (each call
+ *   rewrites all it reads, including the flags that must start at zero). */
+#define CC_STATIC_SCRATCH_BYTES (1u << 20)
+int cc_sparse_prefill_static(cc_ctx* ctx, const void* q, const void* k_new, const void* v_new,
+                             const int32_t* src_rows, const int32_t* q_pos, const int32_t* slot_map,
+                             const int32_t* cu_q, int32_t n_q_tot, int32_t max_q_per_req,
+                             void* k_pool, void* v_pool, int32_t n_blocks, const int32_t* block_tab,
+                             const cc_segment* segs, int32_t n_segs,
+                             const int32_t* req_seg_off, int32_t n_requests, int32_t n_ctx_tokens,
+                             void* out, float* lse, void* stream);
+
 /* ---- (c'') partial prefill that also returns the question's attention to every chunk --------
  * cc_sparse_prefill (same steps, same out and lse, bit for bit) plus seg_mass as cc_question_mass
  * defines it, in one call.  Where the attention kernel that runs can give the masses as a

@@ -79,6 +79,9 @@ def load_library() -> C.CDLL:
     lib.cc_sparse_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, vp, i32,
                                       vp, i32, i32, vp, vp, vp, sz, vp]
     lib.cc_sparse_prefill.restype = C.c_int
+    lib.cc_sparse_prefill_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, vp, i32,
+                                             vp, i32, i32, vp, vp, vp]
+    lib.cc_sparse_prefill_static.restype = C.c_int
     lib.cc_rms_norm.argtypes = [vp, vp, vp, C.c_float, i32, i32, vp, vp]
     lib.cc_rms_norm.restype = C.c_int
     lib.cc_linear.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp]
@@ -240,6 +243,15 @@ class Context:
             n_q_tot, max_q_per_req, _ptr(k_pool), _ptr(v_pool), k_pool.shape[0], _ptr(block_tab),
             _ptr(segs), segs.shape[0], _ptr(req_seg_off), n_requests, n_ctx_tokens, _ptr(out), _ptr(lse),
             _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+    def sparse_prefill_static(self, q, k_new, v_new, q_pos, slot_map, cu_q, max_q_per_req, k_pool, v_pool,
+                              block_tab, segs, req_seg_off, n_requests, n_ctx_tokens, out, lse, src_rows=None):
+        """cc_sparse_prefill without a workspace: the plan goes into the library's built-in scratch array."""
+        n_q_tot = q.shape[0] if src_rows is None else src_rows.shape[0]
+        self._check(self._lib.cc_sparse_prefill_static(
+            self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(src_rows), _ptr(q_pos), _ptr(slot_map), _ptr(cu_q),
+            n_q_tot, max_q_per_req, _ptr(k_pool), _ptr(v_pool), k_pool.shape[0], _ptr(block_tab),
+            _ptr(segs), segs.shape[0], _ptr(req_seg_off), n_requests, n_ctx_tokens, _ptr(out), _ptr(lse), _stream()))
 
     # -- the rest of a decoder layer for the chosen rows ---------------------------------------------
     def rms_norm(self, x, gain, eps, y):

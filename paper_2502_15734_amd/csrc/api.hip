@@ -1,6 +1,7 @@
 // C ABI of libcachecraft: argument checks and kernel dispatch.  See include/cc.h.
 #include <cmath>
 #include <cstdio>
+#include <mutex>
 #include <new>
 
 #include "common.h"
@@ -20,6 +21,32 @@ int check_launch(cc_ctx* ctx, const char* what) {
 }
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- scratch of cc_sparse_prefill_static --------------------------------------------------------
+// A device array that lives in the library's code object: every GPU the library runs on holds its
+// own copy, at its own address, until the process ends.  In host code the array's name is only a
+// handle for hipGetSymbolAddress; kernels and copies get the address that call returned.
+static __device__ __align__(256) unsigned char scratch[CC_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::mutex scratch_mutex;
+static void* scratch_of_device[kMaxDevices];      // resolved once per device, with that device current
+
+// Address of the current device's scratch array (nullptr + *err set if it cannot be resolved).
+static void* static_scratch(hipError_t* err) {
+  int dev = -1;
+  *err = hipGetDevice(&dev);
+  if (*err != hipSuccess) return nullptr;
+  if (dev < 0 || dev >= kMaxDevices) { *err = hipErrorInvalidDevice; return nullptr; }
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (scratch_of_device[dev] == nullptr) {
+    void* p = nullptr;
+    *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (*err != hipSuccess) return nullptr;
+    scratch_of_device[dev] = p;
+  }
+  return scratch_of_device[dev];
+}
 
 }  // namespace cc
 
@@ -61,6 +88,12 @@ int cc_create(cc_ctx** out, const cc_config* cfg) {
   const int half = cfg->head_dim / 2;
   for (int i = 0; i < cc::kMaxHalf; ++i)
     ctx->inv_freq.f[i] = i < half ? std::pow(cfg->rope_theta, -2.0 * i / cfg->head_dim) : 0.0;
+  // The scratch array of cc_sparse_prefill_static is looked up here for the device that is current
+  // now, so that the call itself finds it ready (a process without a GPU simply has none; the call
+  // looks again on its first use on any other device).
+  hipError_t scratch_err;
+  (void)cc::static_scratch(&scratch_err);
+  (void)hipGetLastError();
   *out = ctx;
   return CC_OK;
 }
@@ -290,6 +323,35 @@ int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void*
     cc::launch_attn_scalar(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks,
                            block_tab, segs, req_seg_off, n_requests, out, lse, src_rows, 0, st);
   return cc::check_launch(ctx, fn);
+}
+
+int cc_sparse_prefill_static(cc_ctx* ctx, const void* q, const void* k_new, const void* v_new,
+                             const int32_t* src_rows, const int32_t* q_pos, const int32_t* slot_map,
+                             const int32_t* cu_q, int32_t n_q_tot, int32_t max_q_per_req, void* k_pool,
+                             void* v_pool, int32_t n_blocks, const int32_t* block_tab,
+                             const cc_segment* segs, int32_t n_segs, const int32_t* req_seg_off,
+                             int32_t n_requests, int32_t n_ctx_tokens, void* out, float* lse,
+                             void* stream) {
+  static const char* fn = "cc_sparse_prefill_static";
+  if (ctx == nullptr) return CC_ERR_INVALID_ARG;
+  CC_REQUIRE(n_ctx_tokens >= 0 && n_segs >= 0, "negative count");
+  const size_t need = cc_sparse_prefill_workspace_bytes(ctx, n_ctx_tokens, n_segs);
+  if (need > CC_STATIC_SCRATCH_BYTES)
+    return fail(ctx, CC_ERR_WORKSPACE_TOO_SMALL,
+                "cc_sparse_prefill_static: the key-tile plan of this batch needs " + std::to_string(need) +
+                    " bytes, the built-in scratch holds " + std::to_string(CC_STATIC_SCRATCH_BYTES) +
+                    " (use cc_sparse_prefill with a workspace)");
+  if (n_q_tot == 0) return CC_OK;
+  hipError_t err = hipSuccess;
+  void* ws = cc::static_scratch(&err);
+  if (ws == nullptr)
+    return fail(ctx, CC_ERR_HIP, std::string("cc_sparse_prefill_static: scratch array not available: ") +
+                                     hipGetErrorString(err));
+  // (the plan kernels rewrite every part of the scratch the attention kernels read, including the
+  // flags that must start at zero, so nothing of an earlier call survives into this one)
+  return cc_sparse_prefill(ctx, q, k_new, v_new, src_rows, q_pos, slot_map, cu_q, n_q_tot, max_q_per_req, k_pool,
+                           v_pool, n_blocks, block_tab, segs, n_segs, req_seg_off, n_requests, n_ctx_tokens, out,
+                           lse, ws, CC_STATIC_SCRATCH_BYTES, stream);
 }
 
 size_t cc_sparse_prefill_mass_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_tokens, int32_t n_segs,

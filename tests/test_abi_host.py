@@ -32,7 +32,8 @@ def test_every_declared_symbol_is_exported(lib):
             "cc_chunk_attention_workspace_bytes", "cc_chunk_ab", "cc_chunk_cci", "cc_chunk_reuse", "cc_preload_depth",
             "cc_preloader_create", "cc_preloader_set_layer", "cc_preloader_acquire", "cc_preloader_release",
             "cc_preloader_issued", "cc_preloader_destroy", "cc_sparse_prefill_mass", "cc_sparse_prefill_pairs",
-            "cc_sparse_prefill_pairs_workspace_bytes", "cc_rms_norm", "cc_linear", "cc_gated_linear"} <= set(names)
+            "cc_sparse_prefill_pairs_workspace_bytes", "cc_rms_norm", "cc_linear", "cc_gated_linear",
+            "cc_sparse_prefill_static"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in cc.h but not exported"
 
@@ -101,6 +102,13 @@ def test_calls_reject_bad_arguments_before_launch(lib):
     # rows of the compact list beyond n_ctx_tokens (the redo flags in the workspace are sized by it)
     few = [h, good, good, good, None, good, good, good, 10, 10, good, good, 8, good, good, 3, good, 1, 9]
     assert lib.cc_sparse_prefill(*few, good, None, good, ws, None) == -1 and b"n_ctx_tokens" in lib.cc_last_error(h)
+    # cc_sparse_prefill_static: a plan larger than the built-in scratch is refused before anything else happens;
+    # an empty query list is fine
+    assert lib.cc_sparse_prefill_static(h, good, good, good, None, good, good, good, 10, 10, good, good, 8, good, good,
+                                        3, good, 1, 4_000_000, good, None, None) == -3
+    assert b"scratch" in lib.cc_last_error(h)
+    assert lib.cc_sparse_prefill_static(h, good, good, good, None, good, good, good, 0, 0, good, good, 8, good, good,
+                                        3, good, 1, 100, good, None, None) == 0
     # grid limits: more than 65535 requests (cc_sparse_prefill) or segments (cc_select) in one call are refused
     big = [h, good, good, good, None, good, good, good, 70000, 10, good, good, 8, good, good, 70000, good, 70000, 70000]
     wsb = lib.cc_sparse_prefill_workspace_bytes(h, 70000, 70000)
