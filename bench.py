@@ -27,12 +27,36 @@ PEAK_FP32_VALU_TFLOPS = 157.3
 # data: the same loop on constant operands reaches 2380); quoted beside the vendor peak, never
 # instead of it.
 MEASURED_MFMA_BF16_TFLOPS = 1880.0
-# HBM bytes per launch of each call's main kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# of this command scaled by a 512 MiB copy (profiles/hot_path_kernels_config3_8b_continuous_batch.md).
-MEASURED_TRAFFIC_BYTES = {
-    3: {"cc_rope_shift": (568.1 + 646.5) * 2 ** 20, "cc_select": (2763.1 + 34.3 + 17.3 + 1.3) * 2 ** 20,
-        "cc_sparse_prefill": (1044.0 + 319.6 + 165.1 + 159.0) * 2 ** 20},
-}
+# Tracked rocprofv3 summary of the default workload: its "HBM traffic per launch" table (FETCH_SIZE / WRITE_SIZE
+# scaled by a copy of known size) is where roofline.traffic comes from - it is not measured in this run.
+TRAFFIC_PROFILE = os.path.join("profiles", "hot_path_kernels_config3_8b_continuous_batch.md")
+TRAFFIC_WORKLOAD = 3
+KERNELS_OF_CALL = {"cc_rope_shift": ("rope_shift_kernel",), "cc_select": ("score_v2_kernel", "topn_kernel", "sparse_qk_kernel<G=4,SCORE"),
+                   "cc_sparse_prefill": ("attn_v2_kernel", "rope_scatter_kernel", "sparse_qk_kernel<G=4,ATTN")}
+
+
+def profiled_traffic_bytes(call: str):
+    """HBM bytes per launch (read + written) of the kernels of one library call, summed from the tracked
+    profile summary's traffic table; None if the file or the rows are missing."""
+    path = os.path.join(ROOT, TRAFFIC_PROFILE)
+    if not os.path.exists(path) or call not in KERNELS_OF_CALL:
+        return None
+    total, found, in_table = 0.0, False, False
+    for line in open(path):
+        if line.startswith("## HBM traffic per launch"):
+            in_table = True
+            continue
+        if in_table and line.startswith("## "):
+            break
+        if in_table and line.startswith("|") and "---" not in line and "FETCH_SIZE raw" not in line:
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if len(cells) >= 5 and any(k in cells[0] for k in KERNELS_OF_CALL[call]):
+                try:
+                    total += (float(cells[2]) + float(cells[4])) * 2 ** 20
+                    found = True
+                except ValueError:
+                    pass
+    return total if found else None
 
 
 def algorithmic_work(w):
@@ -84,28 +108,89 @@ def time_stages(batch, steps: int):
             for j, n in enumerate(names)}
 
 
-def cpu_baseline(w, budget_s: float = 20.0):
-    """The fp64 oracle as it stands, on a bounded sample: whole requests, in order, until about
-    `budget_s` seconds of CPU work are spent (at least one request)."""
+def _gpu_request_state(w, batch, r):
+    """What the GPU left for request r after a step: chosen index sets per chunk, attention output, and the
+    logical K / V of the request as its pages now hold them."""
+    import workload as W
     from oracle import cachecraft_oracle as O
-    t0 = time.perf_counter()
+    sel = batch.sel_idx.cpu().numpy()
+    segs = [w.segments[i] for i in range(int(w.req_seg_off[r]), int(w.req_seg_off[r + 1]))]
+    sets = [np.asarray(sel[int(sg[W.SEG_SEL]): int(sg[W.SEG_SEL]) + int(sg[W.SEG_NSEL])], dtype=np.int64)
+            for sg in segs if sg[W.SEG_KIND] == W.KIND_CHUNK]
+    q0, q1 = int(w.cu_q[r]), int(w.cu_q[r + 1])
+    out = batch.out[q0:q1].float().cpu().numpy()
+    import torch
+    mine = np.unique(np.concatenate([np.asarray(w.req_tab[int(sg[W.SEG_TAB]): int(sg[W.SEG_TAB]) + (int(sg[W.SEG_NTOK]) + 15) // 16],
+                                               dtype=np.int64) for sg in segs]))
+    idx = torch.as_tensor(mine, device=batch.k_req.device)
+    k_pages = batch.k_req.index_select(0, idx).float().cpu().numpy()      # only this request's pages travel to the host
+    v_pages = batch.v_req.index_select(0, idx).float().cpu().numpy()
+    n_ctx = int(segs[-1][W.SEG_START] + segs[-1][W.SEG_NTOK])
+    hkv, d = w.spec.n_kv_heads, w.spec.head_dim
+    k = np.zeros((n_ctx, hkv, d)); v = np.zeros((n_ctx, hkv, d))
+    for sg in segs:
+        st, n, tab = int(sg[W.SEG_START]), int(sg[W.SEG_NTOK]), int(sg[W.SEG_TAB])
+        blk = np.searchsorted(mine, np.asarray(w.req_tab[tab: tab + (n + 15) // 16], dtype=np.int64))
+        k[st:st + n] = O.read_k_pages(k_pages, blk, n)
+        v[st:st + n] = O.read_v_pages(v_pages, blk, n)
+    return sets, out, k, v
+
+
+def cpu_baseline(w, batch=None, budget_s: float = 20.0):
+    """The fp64 oracle as it stands, on a bounded sample: whole requests, in order, until about
+    `budget_s` seconds of CPU work are spent (at least one request).  With `batch` (the device batch the
+    timed steps ran on) the same requests also give the parity block: the GPU's index sets against the
+    oracle's (differences outside the 1e-4 tie band count), and its attention output and fixed K / V
+    against the oracle run on the GPU's own sets (untimed)."""
+    from oracle import cachecraft_oracle as O
+    spent = 0.0
     tokens = 0
     done = 0
+    tie_gap = 1e-4
+    err2 = {"out": 0.0, "k": 0.0, "v": 0.0}
+    ref2 = {"out": 0.0, "k": 0.0, "v": 0.0}
+    set_mismatch, set_diff_in_band = 0, 0
     for r in range(w.n_requests):
-        O.run_request(w, r)
+        t0 = time.perf_counter()
+        res = O.run_request(w, r)
+        spent += time.perf_counter() - t0
         tokens += int(w.cu_q[r + 1] - w.cu_q[r])
         done += 1
-        if time.perf_counter() - t0 > budget_s:
+        if batch is not None:
+            sets, out, k, v = _gpu_request_state(w, batch, r)
+            same = True
+            for g, o, sc in zip(sets, res.selected, res.scores):
+                diff = np.setxor1d(g, o)
+                if len(diff):
+                    same = False
+                    nth = np.sort(sc)[::-1][len(o) - 1]
+                    outside = int((np.abs(sc[diff] - nth) > tie_gap).sum())
+                    set_mismatch += outside
+                    set_diff_in_band += len(diff) - outside
+            if not same:                  # ties broken differently: the oracle attends over the GPU's own sets
+                k_sh, v_c, _ = O.shifted_context(w, r)
+                k_ctx, v_ctx, _, _, o_out, _ = O.fix_and_attend(w, r, k_sh, v_c, sets)
+            else:
+                k_ctx, v_ctx, o_out = res.k_ctx, res.v_ctx, res.out
+            for name, got, ref in (("out", out, o_out), ("k", k, k_ctx), ("v", v, v_ctx)):
+                err2[name] += float(((got - ref) ** 2).sum()); ref2[name] += float((ref ** 2).sum())
+        if spent > budget_s:
             break
-    dt = time.perf_counter() - t0
     try:
         import threadpoolctl
         cores = max((p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()), default=1)
     except Exception:
         cores = os.cpu_count() or 1
-    return {"value": tokens / dt, "unit": "recomputed tokens/s", "cores": int(cores), "kind": "oracle",
+    base = {"value": tokens / spent, "unit": "recomputed tokens/s", "cores": int(cores), "kind": "oracle",
             "sample": f"first {done} of {w.n_requests} requests, all stages (shift, score, select, fix, attend), "
-                      f"{tokens} recomputed tokens in {dt:.1f} s"}
+                      f"{tokens} recomputed tokens in {spent:.1f} s"}
+    parity = None
+    if batch is not None:
+        rel = lambda n: float(np.sqrt(err2[n] / ref2[n])) if ref2[n] > 0 else 0.0
+        parity = {"requests": done, "out_rel_l2": rel("out"), "k_rel_l2": rel("k"), "v_rel_l2": rel("v"),
+                  "set_mismatches_outside_tie_band": set_mismatch, "set_differences_inside_tie_band": set_diff_in_band,
+                  "bar": {"rel_l2": 1e-2 if w.spec.dtype == "bf16" else 1e-5, "tie_gap": tie_gap}}
+    return base, parity
 
 
 def measured_copy_gbs(mib: int = 512, iters: int = 5) -> float:
@@ -281,68 +366,15 @@ def time_layer_loop(w, n_layers: int = 4, window: int = 2) -> dict:
             "requests_settled": sum(1 for s in recs[-1]["stop_layer"] if s is not None)}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", type=int, default=3, help="benchmark config 1..5 (default 3)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extra-calls", action="store_true",
-                    help="skip the timings of entry points outside the step (used for profiles of the step's kernels)")
-    ap.add_argument("--cpu-budget", type=float, default=20.0)
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also launch one plain 512 MiB device copy (identity cc_gather_rows) so that a "
-                         "rocprofv3 --pmc run of this command has a kernel of known HBM traffic to scale by")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
-
-    import torch
-    import workload as W
-    import paper_2502_15734_amd as P
-    from paper_2502_15734_amd.pipeline import DeviceBatch
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    P.load_library()
-    w = W.config(args.workload)
-    batch = DeviceBatch(w)
+def stage_figures(w, batch, stage_ms):
+    """Per library call: ms, achieved algorithmic rate, fraction of the published peak."""
     work = algorithmic_work(w)
-
-    if args.calibrate_copy:
-        rows, row_bytes = 1 << 15, 1 << 14                      # 32768 rows x 16 KiB = 512 MiB
-        src = torch.empty((rows, row_bytes), dtype=torch.uint8, device="cuda").fill_(1)
-        dst = torch.empty_like(src)
-        idx = torch.arange(rows, dtype=torch.int32, device="cuda")
-        batch.ctx.gather_rows(src, idx, dst)
-        torch.cuda.synchronize()
-        del src, dst, idx
-
-    for _ in range(args.warmup):
-        batch.step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        batch.step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
-    tokens_per_s = work["recomputed_tokens"] / (dt / args.steps)
-
-    stage_ms = time_stages(batch, args.steps)
-    extra = None if args.no_extra_calls else time_extra_calls(batch, w, work, args.steps, ms_per_step,
-                                                               stage_ms["sparse_prefill"])
     q_pos = batch.q_pos.cpu().numpy()[: w.n_q_tot]
     attn_flops = attention_flops(w, q_pos)
     proj_flops = 0.0
     if w.hidden is not None:
         sp = w.spec
         proj_flops = 2.0 * w.hidden.shape[1] * (sp.n_q_heads + 2 * sp.n_kv_heads) * sp.head_dim * w.n_q_tot
-
     stages = {
         "cc_rope_shift": {"bound": "hbm", "ms": stage_ms["rope_shift"], "unit": "GB/s", "peak": PEAK_HBM_GBS,
                           "achieved": work["shift_bytes"] / (stage_ms["rope_shift"] * 1e-3) / 1e9},
@@ -359,8 +391,81 @@ def main():
             "unit": "TFLOP/s" if proj_flops else "GB/s", "peak": PEAK_MFMA_BF16_TFLOPS if proj_flops else PEAK_HBM_GBS,
             "achieved": (proj_flops / (stage_ms["gather"] * 1e-3) / 1e12) if proj_flops else
                         (2.0 * w.n_q_tot * row_bytes / (stage_ms["gather"] * 1e-3) / 1e9)}
-    for s in stages.values():
-        s["frac"] = s["achieved"] / s["peak"]
+    if w.spec.dtype != "bf16":          # the fp32 workload runs on the plain kernels: vector ALU, not MFMA
+        for k in ("cc_select", "cc_sparse_prefill"):
+            stages[k].update(bound="alu", peak=PEAK_FP32_VALU_TFLOPS)
+    for st in stages.values():
+        st["frac"] = st["achieved"] / st["peak"]
+    return stages, work
+
+
+def run_workload(wid: int, steps: int, warmup: int):
+    """Build workload `wid` on the device, run `warmup` + `steps` whole steps, then time every call of the step."""
+    import torch
+    import workload as W
+    from paper_2502_15734_amd.pipeline import DeviceBatch
+    w = W.config(wid)
+    batch = DeviceBatch(w)
+    for _ in range(warmup):
+        batch.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        batch.step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    stage_ms = time_stages(batch, steps)
+    stages, work = stage_figures(w, batch, stage_ms)
+    return w, batch, work, dt / steps * 1e3, stage_ms, stages
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=3, help="benchmark config 1..5 (default 3)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra-calls", action="store_true",
+                    help="skip the timings of entry points outside the step (used for profiles of the step's kernels)")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="skip the short runs of the other workloads (configs 2, 4, 5) reported under per_config")
+    ap.add_argument("--cpu-budget", type=float, default=20.0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain 512 MiB device copy (identity cc_gather_rows) so that a "
+                         "rocprofv3 --pmc run of this command has a kernel of known HBM traffic to scale by")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workload as W
+    import paper_2502_15734_amd as P
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    P.load_library()
+
+    if args.calibrate_copy:
+        from paper_2502_15734_amd.binding import CC_BF16, Context
+        rows, row_bytes = 1 << 15, 1 << 14                      # 32768 rows x 16 KiB = 512 MiB
+        src = torch.empty((rows, row_bytes), dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        idx = torch.arange(rows, dtype=torch.int32, device="cuda")
+        Context(32, 8, 128, 5.0e5, CC_BF16).gather_rows(src, idx, dst)
+        torch.cuda.synchronize()
+        del src, dst, idx
+
+    w, batch, work, ms_per_step, stage_ms, stages = run_workload(args.workload, args.steps, args.warmup)
+    tokens_per_s = work["recomputed_tokens"] / (ms_per_step * 1e-3)
+    extra = None if args.no_extra_calls else time_extra_calls(batch, w, work, args.steps, ms_per_step,
+                                                               stage_ms["sparse_prefill"])
+    if extra is not None:                  # the extra calls ran on the batch: restore the state a step leaves
+        batch.step()
+        torch.cuda.synchronize()
     # what a plain device-to-device copy of 512 MiB reaches on this box, beside the HBM peak
     copy_gbs = measured_copy_gbs()
     stages["cc_rope_shift"]["measured_copy_GBps"] = copy_gbs
@@ -370,28 +475,46 @@ def main():
     kernel_of = {"cc_select": "score_v2_kernel (+ top-N, plan, redo pass: ~2 % of the call)",
                  "cc_sparse_prefill": "attn_v2_kernel (+ rope_scatter, plan, redo pass: ~8 % of the call)",
                  "cc_rope_shift": "rope_shift_kernel", "cc_gather_rows(+cc_qkv_project)": "qkv_project / gather_rows"}
+    traffic = profiled_traffic_bytes(dominant) if args.workload == TRAFFIC_WORKLOAD else None
     roofline = {"kernel": kernel_of[dominant], "call": dominant, "bound": dom["bound"], "achieved": dom["achieved"],
-                "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"],
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get(dominant), "avg_ms": dom["ms"]}
+                "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"], "traffic": traffic,
+                "traffic_source": (TRAFFIC_PROFILE + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, "
+                                   "scaled by a copy of known size; not measured in this run)") if traffic is not None else None,
+                "avg_ms": dom["ms"]}
     if dom["bound"] == "mfma":
         roofline["frac_of_measured_mfma_rate"] = dom["achieved"] / MEASURED_MFMA_BF16_TFLOPS
+
+    # the other workloads the benchmark spec names, a few steps each (config 1 is the tiny fp32 case of the tests)
+    per_config = None
+    if not args.no_per_config:
+        per_config = {}
+        for wid, n_steps in ((2, 20), (4, 5), (5, 3)):
+            if wid == args.workload:
+                continue
+            w2, b2, work2, ms2, _, stages2 = run_workload(wid, n_steps, 2)
+            per_config[W.CONFIG_NAMES[wid]] = {
+                "steps": n_steps, "ms_per_step": ms2, "recomputed_tokens": work2["recomputed_tokens"],
+                "tokens_per_s": work2["recomputed_tokens"] / (ms2 * 1e-3), "dtype": w2.spec.dtype,
+                "stages": {k: {kk: v[kk] for kk in ("ms", "bound", "achieved", "unit", "peak", "frac")} for k, v in stages2.items()}}
+            del w2, b2
+            torch.cuda.empty_cache()
 
     result = {
         "metric": "recomputed tokens/sec in selective chunk prefill",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.spec.dtype, "data": "synthetic",
-        "config": {"workload": W.CONFIG_NAMES[args.workload], "config_id": args.workload,
-                   "n_requests": w.n_requests, "prompt_tokens": w.n_tok, "recomputed_tokens": w.n_q_tot,
-                   "n_q_heads": w.spec.n_q_heads, "n_kv_heads": w.spec.n_kv_heads, "head_dim": w.spec.head_dim},
+        "config": {"workload": W.CONFIG_NAMES[args.workload]},
         "roofline": roofline,
         "stages": stages,
+        "workload_size": {"requests": w.n_requests, "prompt_tokens": w.n_tok, "recomputed_tokens": w.n_q_tot},
         "sparse_prefill_tokens_per_s": w.n_q_tot / (stage_ms["sparse_prefill"] * 1e-3),
+        "per_config": per_config,
         # not part of the step: the other entry points of the library, timed on the same batch
         "extra_calls": extra,
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, args.cpu_budget)
+        result["cpu_baseline"], result["parity"] = cpu_baseline(w, batch, args.cpu_budget)
     print(json.dumps(result))
 
 
