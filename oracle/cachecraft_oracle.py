@@ -198,6 +198,31 @@ def causal_attention_rows(q_rot: np.ndarray, pos: np.ndarray, k_ctx: np.ndarray,
     return out, lse
 
 
+def causal_attention_rows_dense(q_rot: np.ndarray, pos: np.ndarray, k_ctx: np.ndarray, v_ctx: np.ndarray):
+    """causal_attention_rows for many rows at once: per head one logit matrix [n, max(pos)+1] with the
+    keys behind each row's position set to -inf, a row-wise softmax, and one product with V.  The same
+    definition (Eq. (1) per token, scale 1/sqrt(d)) written with matrices instead of a loop over rows;
+    used where thousands of rows of a long prompt are checked.
+    """
+    n, hq, d = q_rot.shape
+    g = hq // k_ctx.shape[1]
+    out = np.zeros((n, hq, d), dtype=np.float64)
+    lse = np.zeros((n, hq), dtype=np.float64)
+    if n == 0:
+        return out, lse
+    n_keys = int(pos.max()) + 1
+    hidden = np.arange(n_keys)[None, :] > np.asarray(pos)[:, None]
+    for h in range(hq):
+        s = q_rot[:, h, :] @ k_ctx[:n_keys, h // g, :].T / np.sqrt(np.float64(d))
+        s[hidden] = -np.inf
+        m = s.max(axis=1, keepdims=True)
+        e = np.exp(s - m)
+        z = e.sum(axis=1, keepdims=True)
+        out[:, h, :] = (e / z) @ v_ctx[:n_keys, h // g, :]
+        lse[:, h] = (m + np.log(z))[:, 0]
+    return out, lse
+
+
 # --------------------------------------------------------------------------
 # whole path on a workload (the structure produced by workload.generate.build)
 # --------------------------------------------------------------------------
@@ -280,8 +305,9 @@ def query_list(w, r: int, selected: Sequence[np.ndarray]):
 
 
 def fix_and_attend(w, r: int, k_shifted, v_cached, selected, k_new=None, v_new=None, q=None,
-                   only_queries: Optional[np.ndarray] = None):
-    """Steps fix + attend for request r given the chosen token sets."""
+                   only_queries: Optional[np.ndarray] = None, dense: bool = False):
+    """Steps fix + attend for request r given the chosen token sets (dense: the matrix form of the
+    attention, for many rows of a long prompt)."""
     theta = w.spec.rope_theta
     k_new = w.k_new if k_new is None else k_new
     v_new = w.v_new if v_new is None else v_new
@@ -293,7 +319,8 @@ def fix_and_attend(w, r: int, k_shifted, v_cached, selected, k_new=None, v_new=N
         v_ctx[q_pos] = np.asarray(v_new[q_row], dtype=np.float64)
     which = np.arange(len(q_pos)) if only_queries is None else np.asarray(only_queries, dtype=np.int64)
     q_rot = rotate(np.asarray(q[q_row[which]], dtype=np.float64), q_pos[which], theta)
-    out, lse = causal_attention_rows(q_rot, q_pos[which], k_ctx, v_ctx)
+    attend = causal_attention_rows_dense if dense else causal_attention_rows
+    out, lse = attend(q_rot, q_pos[which], k_ctx, v_ctx)
     return k_ctx, v_ctx, q_pos, q_row, out, lse
 
 

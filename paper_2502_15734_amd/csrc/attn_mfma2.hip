@@ -18,12 +18,13 @@
 // Schedule.  Keys advance in 32-key blocks b = 0, 1, 2, ... (two per 64-key tile).  The matrix pipe
 // sees   S(b+1), PV(b), S(b+2), PV(b+1), ...   16 MFMAs each, and under every MFMA one exponential
 // of a block whose S is already complete: the first half of exp(b) under PV(b-1), the second half
-// under S(b+1).  Per element that is ONE v_exp_f32: the reference is already subtracted (it enters
-// through the C operand of the block's first MFMA), and per pair of elements one pack to bf16 and
-// one v_dot2c_f32_bf16 that adds the two packed values to the row sum - so numerator and
-// denominator of the softmax see the same rounded probabilities.  The pack of a pair runs one
-// step late, in front of the next exponential, so that no instruction reads a transcendental
-// result right behind its issue.
+// under S(b+1).  Per element that is one v_exp_f32 and one add into the row sum: the reference is
+// already subtracted (it enters through the C operand of the block's first MFMA).  The row sum
+// takes the unrounded exponentials (summing the bf16 roundings instead - one v_dot2c_f32_bf16 per
+// pair - was measured too: it biases the log-sum-exp by up to 1.4e-3 when the weights are nearly
+// uniform, and saves nothing that shows).  The pack of a pair to bf16 and its two adds run one step
+// late, in front of the next exponential, so that no instruction reads a transcendental result
+// right behind its issue.
 //
 // Softmax reference: m_ref = maximum of the row's first 32-key block, for the whole row (fp32 and
 // bf16 share the exponent range, so p = exp2(S - m_ref) may grow to 1e30 without loss).  Rows whose
@@ -68,7 +69,6 @@ static_assert(kDepth % 2 == 0 && kDepth >= 4 && kDepth <= 8, "operand reads are 
 // p = exp2(S - reference) may be large (fp32 and bf16 share the exponent range); a row sum
 // beyond this leaves no headroom for O
 constexpr float kSafeSum = 1.0e30f;
-constexpr uint32_t kOnesBf16 = 0x3f803f80u;   // (1.0, 1.0) as a packed bf16 pair
 
 // MFMA forms with fixed register classes (the compiler's own choice shuffles accumulators between
 // the two register files once a wavefront uses more than 256 registers): S accumulates in vector
@@ -113,21 +113,15 @@ __device__ __forceinline__ void dma_two(uint32_t voff, const char* base, uint32_
                :: "v"(voff), "s"(base), "s"(m0v), "n"(IMM0), "n"(IMM1) : "memory", "m0");
 }
 // The exponentials.  exp_only: t = exp2(s).  exp_behind_pack: first the pair that is still pending
-// (e = its even element, v = its odd one) is packed to bf16 and added to the row sum, then
+// (e = its even element, v = its odd one) is packed to bf16 and both are added to the row sum, then
 // e = exp2(s).  Written out so that each stays where it is placed, under one MFMA (the compiler
 // otherwise lumps the exponentials of a block together or sinks them to their use).
 __device__ __forceinline__ void exp_only(float& t, float s) {
   asm volatile("v_exp_f32 %0, %1" : "=v"(t) : "v"(s));
 }
 __device__ __forceinline__ void exp_behind_pack(uint32_t& pk, float& l, float& e, float v, float s) {
-  asm volatile("v_cvt_pk_bf16_f32 %0, %2, %3\n\tv_dot2c_f32_bf16 %1, %4, %0\n\tv_exp_f32 %2, %5"
-               : "=&v"(pk), "+v"(l), "+v"(e) : "v"(v), "s"(kOnesBf16), "v"(s));
-}
-// the pending pair alone (behind a row's last exponential; the idle slot covers the wait state a
-// transcendental result needs)
-__device__ __forceinline__ void pack_pending(uint32_t& pk, float& l, float e, float v) {
-  asm volatile("s_nop 0\n\tv_cvt_pk_bf16_f32 %0, %2, %3\n\tv_dot2c_f32_bf16 %1, %4, %0"
-               : "=&v"(pk), "+v"(l) : "v"(e), "v"(v), "s"(kOnesBf16));
+  asm volatile("v_cvt_pk_bf16_f32 %0, %2, %3\n\tv_add_f32 %1, %1, %2\n\tv_add_f32 %1, %1, %3\n\tv_exp_f32 %2, %4"
+               : "=&v"(pk), "+v"(l), "+v"(e) : "v"(v), "v"(s));
 }
 // one 16-byte LDS piece straight into accumulation registers
 __device__ __forceinline__ u32x4 lds_to_acc(const uint4* p) {
@@ -142,8 +136,6 @@ template <int N>
 __device__ __forceinline__ void wait_lds() {
   __builtin_amdgcn_s_waitcnt(15 | (3 << 14) | (7 << 4) | (N << 8));
 }
-// bf16 rounding of a value, back in fp32 (what a packed element contributes to the row sum)
-__device__ __forceinline__ float rounded_bf16(float v) { return static_cast<float>(static_cast<bf16_t>(v)); }
 
 // QB = 2: 4 wavefronts, each one head x 64 rows (one wavefront per SIMD, up to 512 registers);
 // QB = 1: 8 wavefronts, each one head x 32 rows (two per SIMD, up to 256 registers each): the workgroup
@@ -512,7 +504,7 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_v2_kernel(
     const int seg = __builtin_amdgcn_readlane(w_seg, l), seg_next = __builtin_amdgcn_readlane(w_seg_next, l);
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-      const float mine = lsum[qb] + (rounded_bf16(ev[qb]) + rounded_bf16(vodd[qb]));
+      const float mine = lsum[qb] + (ev[qb] + vodd[qb]);
       const float tot = mine + __shfl_xor(mine, 32, 64);
       const int sr = snap_index != nullptr ? snap_index[row[qb]] : row[qb];     // (no index: every row is a snap row)
       if (row_valid[qb] && hh == 0 && sr >= 0) {

@@ -79,6 +79,16 @@ def test_decoder_loop_matches_the_oracle(dtype, impl):
             assert H.rel_l2(rec["out"][q0:q1], o["out"]) <= tol, f"{what}: attention {H.rel_l2(rec['out'][q0:q1], o['out']):.3e}"
             assert H.rel_l2(rec["h1"][q0:q1], o["h1"]) <= tol, what
             assert H.rel_l2(rec["h2"][q0:q1], o["h2"]) <= tol, f"{what}: h2 {H.rel_l2(rec['h2'][q0:q1], o['h2']):.3e}"
+    # bf16, free-running: the oracle carries its own fp64 state from layer to layer while the library
+    # carries bf16 roundings; every layer adds its own rounding (each of its operators is inside
+    # the per-layer bar above) to what it inherited, so the gap may grow by about one bar per layer
+    if dtype == "bf16":
+        for r in range(w.n_requests):
+            q0, q1 = int(w.cu_q[r]), int(w.cu_q[r + 1])
+            free = O.recompute_layers(w, r, gsel[r], weights)
+            for l, (rec, o) in enumerate(zip(recs, free)):
+                drift = H.rel_l2(rec["h2"][q0:q1], o["h2"])
+                assert drift <= tol * (l + 1), f"request {r} layer {l + 1}: free-running drift {drift:.3e}"
     # the layers do change the state
     assert H.rel_l2(recs[0]["h2"], recs[0]["h_in"]) > 0.1
 

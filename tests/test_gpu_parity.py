@@ -546,6 +546,116 @@ def test_full_size_configs_on_sampled_outputs(cid):
     assert abs(pair.sum().item() - b.n_q_tot) <= 3e-3 * b.n_q_tot
 
 
+@pytest.mark.parametrize("cid", [3, 4, 5])
+def test_full_size_configs_every_request(cid):
+    """Every request of the benchmark configurations at full size, in the launch configuration bench.py
+    times: scores and index set of the chunk that ends deepest in the prompt (plus a second chunk for
+    every fourth request), the request's whole K / V after the fix, and the attention output of all
+    question rows and 256 sampled chosen rows (oracle on the library's own selection).  The oracle's
+    per-request work runs in a few host threads."""
+    from concurrent.futures import ThreadPoolExecutor
+    from paper_2502_15734_amd.pipeline import DeviceBatch
+    w = W.config(cid)
+    b = DeviceBatch(w)
+    b.step()
+    torch.cuda.synchronize()
+    sel = b.sel_idx.cpu().numpy(); scores = b.scores.cpu().numpy()
+    out = b.out.float().cpu().numpy(); lse = b.lse.cpu().numpy()
+    q_row_all = b.q_row.cpu().numpy()
+    kp, vp = _pools(b)
+    gsel = H.gpu_selection(w, sel)
+    hq, hkv, d = w.spec.n_q_heads, w.spec.n_kv_heads, w.spec.head_dim
+
+    def check_request(r):
+        rng = np.random.default_rng(1000 * cid + r)
+        k_sh, v_c, n_ctx = O.shifted_context(w, r)
+        segs = H.all_segments(w, r)
+        chunk_ids = [i for i, sg in enumerate(segs) if sg[W.SEG_KIND] == W.KIND_CHUNK]
+        # -- scores and index sets: the deepest chunk, and for every fourth request one more
+        which_chunks = {chunk_ids[-1]}
+        if r % 4 == 0 and len(chunk_ids) > 2:
+            which_chunks.add(chunk_ids[1 + int(rng.integers(len(chunk_ids) - 2))])
+        for ci in sorted(which_chunks):
+            sg = segs[ci]
+            sc = O.score_request(w, r, k_sh, only_segments=[ci])[chunk_ids.index(ci)]
+            t0, n = int(sg[W.SEG_TOK]), int(sg[W.SEG_NTOK])
+            err = float(np.abs(scores[t0:t0 + n] - sc).max())
+            assert err <= 5e-5, f"config {cid} request {r} segment {ci}: score error {err:.2e}"
+            g = gsel[r][chunk_ids.index(ci)]
+            o = O.top_n(sc, int(sg[W.SEG_NSEL]))
+            assert len(g) == len(o) and np.all(np.diff(g) > 0)
+            diff = np.setxor1d(g, o)
+            if len(diff):
+                nth = np.sort(sc)[::-1][int(sg[W.SEG_NSEL]) - 1]
+                assert np.abs(sc[diff] - nth).max() <= H.TIE_GAP, f"config {cid} request {r} segment {ci}: index set"
+        # -- attention: every question row and 256 of the chosen rows
+        q0, q1 = int(w.cu_q[r]), int(w.cu_q[r + 1])
+        n_question = int(segs[-1][W.SEG_NTOK]) if segs[-1][W.SEG_KIND] != W.KIND_CHUNK else 0
+        n_chosen = q1 - q0 - n_question
+        chosen = np.sort(rng.choice(n_chosen, size=min(256, n_chosen), replace=False))
+        which = np.concatenate([chosen, np.arange(n_chosen, q1 - q0)]).astype(np.int64)
+        if w.hidden is not None:
+            rows = q_row_all[q0:q1]
+            qf, kf, vf = O.qkv_project(w.hidden[rows].astype(np.float64), w.w_qkv.astype(np.float64), hq, hkv, d)
+            full = lambda a, nh: _scatter_rows(a, rows, w.n_tok, nh, d)
+            ref = O.fix_and_attend(w, r, k_sh, v_c, gsel[r], k_new=full(kf, hkv), v_new=full(vf, hkv), q=full(qf, hq),
+                                   only_queries=which, dense=True)
+        else:
+            ref = O.fix_and_attend(w, r, k_sh, v_c, gsel[r], only_queries=which, dense=True)
+        k_ctx, v_ctx, _, _, o_ref, l_ref = ref
+        e = H.rel_l2(out[q0:q1][which], o_ref)
+        assert e <= 1e-2, f"config {cid} request {r}: out rel L2 {e:.3e} over {len(which)} rows"
+        lse_err = float(np.abs(lse[q0:q1][which] - l_ref).max())
+        assert lse_err <= (2e-3 if w.hidden is None else 1e-2), f"config {cid} request {r}: lse error {lse_err:.3e}"
+        # -- the request's whole K / V after the fix
+        k_gpu, v_gpu = H.request_context_from_pools(w, r, kp, vp)
+        assert H.rel_l2(k_gpu, k_ctx) <= 1e-2 and H.rel_l2(v_gpu, v_ctx) <= 1e-2, f"config {cid} request {r}: K / V"
+        return len(which)
+
+    with ThreadPoolExecutor(max_workers=6) as ex:
+        rows_checked = list(ex.map(check_request, range(w.n_requests)))
+    assert len(rows_checked) == w.n_requests and min(rows_checked) >= 32
+
+
+def test_wide_and_narrow_kernels_agree_tightly_at_full_size():
+    """Tripwire for the hand-scheduled MFMA kernels (their hazards are invisible to the compiler): the
+    wide and the narrow kernels compute the same sums in different orders, so on the same full-size
+    batch they must agree far inside the 1e-2 bar the oracle comparison uses - a stale operand or a
+    matrix result read too early in either family shows here first."""
+    import paper_2502_15734_amd as P
+    from paper_2502_15734_amd.pipeline import DeviceBatch
+    w = W.config(3)
+    got = {}
+    for name, impl in (("wide", P.CC_IMPL_MFMA_WIDE), ("narrow", P.CC_IMPL_MFMA_NARROW)):
+        b = DeviceBatch(w, impl=impl)
+        b.rope_shift(); b.select()
+        torch.cuda.synchronize()
+        got[name + "_scores"] = b.scores.clone()
+        if name == "narrow":                  # same rows in both runs: the narrow run attends over the wide run's selection
+            for dst, src in ((b.sel_idx, got["sel"]), (b.q_row, got["q_row"]), (b.q_pos, got["q_pos"]), (b.slot_map, got["slot"])):
+                dst.copy_(src)
+        else:
+            got["sel"], got["q_row"], got["q_pos"], got["slot"] = (t.clone() for t in (b.sel_idx, b.q_row, b.q_pos, b.slot_map))
+        b.sparse_prefill_fused()
+        torch.cuda.synchronize()
+        got[name + "_out"], got[name + "_lse"] = b.out.float().clone(), b.lse.clone()
+        got[name + "_k"], got[name + "_v"] = b.k_req.clone(), b.v_req.clone()
+        del b
+    score_gap = (got["wide_scores"] - got["narrow_scores"]).abs().max().item()
+    assert score_gap <= 2e-6, f"scores differ by {score_gap:.2e}"
+    lse_gap = (got["wide_lse"] - got["narrow_lse"]).abs().max().item()
+    assert lse_gap <= 5e-5, f"lse differs by {lse_gap:.2e}"
+    num = (got["wide_out"] - got["narrow_out"]).double().pow(2).sum().sqrt().item()
+    den = got["narrow_out"].double().pow(2).sum().sqrt().item()
+    assert num / den <= 4e-3, f"attention outputs differ by rel L2 {num / den:.2e}"      # (both round to bf16: ~2.8e-3)
+    # worst single row (a stale operand hits few rows hard rather than all rows a little)
+    row_num = (got["wide_out"] - got["narrow_out"]).double().pow(2).sum(dim=(1, 2)).sqrt()
+    row_den = got["narrow_out"].double().pow(2).sum(dim=(1, 2)).sqrt()
+    worst = (row_num / row_den).max().item()
+    assert worst <= 5e-2, f"worst row differs by rel L2 {worst:.2e}"
+    assert torch.equal(got["wide_k"], got["narrow_k"]) and torch.equal(got["wide_v"], got["narrow_v"])
+
+
 class _SparseRows:
     """Row-indexable stand-in for a [n_tok, H, d] tensor of which only some rows exist."""
     def __init__(self, data, rows):

@@ -272,6 +272,29 @@ def test_zero_recompute_at_cached_offsets_leaves_cache_unchanged():
     np.testing.assert_allclose(res.out, ref, atol=1e-12)
 
 
+def test_dense_attention_form_on_row_subsets():
+    """The matrix form of the attention (many rows at once): on every row of a prompt it is the library's
+    causal attention; on a subset of rows in any order it gives those rows of it, and its log-sum-exp is
+    that of the library softmax denominator; a row at position 0 returns the first value row."""
+    rng = np.random.default_rng(21)
+    n, hq, hkv, d = 53, 6, 2, 16
+    q = rng.standard_normal((n, hq, d)); k = rng.standard_normal((n, hkv, d)); v = rng.standard_normal((n, hkv, d))
+    full = dense_causal_gqa(q, k, v)
+    out, lse = O.causal_attention_rows_dense(q, np.arange(n), k, v)
+    np.testing.assert_allclose(out, full, atol=1e-12)
+    rows = np.array([40, 0, 7, 52, 7])
+    out_s, lse_s = O.causal_attention_rows_dense(q[rows], rows, k, v)
+    np.testing.assert_allclose(out_s, full[rows], atol=1e-12)
+    np.testing.assert_allclose(out_s[1], np.repeat(v[0], hq // hkv, axis=0), atol=1e-14)
+    for j, p in enumerate(rows):
+        for h in range(hq):
+            logits = torch.from_numpy(k[: p + 1, h // (hq // hkv)] @ q[p, h] / math.sqrt(d))
+            assert abs(float(torch.logsumexp(logits, 0)) - lse_s[j, h]) < 1e-12
+    # no rows: empty results
+    o0, l0 = O.causal_attention_rows_dense(q[:0], rows[:0], k, v)
+    assert o0.shape == (0, hq, d) and l0.shape == (0, hq)
+
+
 def test_attention_invariant_to_a_global_position_offset():
     base = small_workload(offsets=(0, 0, 0))
     k_sh, v_c, _ = O.shifted_context(base, 0)
