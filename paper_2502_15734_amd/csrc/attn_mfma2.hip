@@ -36,12 +36,13 @@
 // the global address each lane is given).  Wavefront w brings page w (16 tokens) of the tile, K and
 // V, each with four instructions whose addresses are one scalar base + one per-lane constant + an
 // immediate: no vector arithmetic per tile.  Image of a tile (16-byte pieces):
-//   K piece (page pg, k-step kk, half hh, MFMA row r of the page):
-//       ((pg/2*4 + kk/2)*2 + pg%2)*64 + ((kk%2)*2 + hh)*16 + r
-//     (an instruction = 16 token slots x 64 bytes: whole halves of cache lines)
+//   K piece (MFMA row m of 32-key block b, k-step kk, half hh):
+//       ((b*2 + kk/4)*4 + m/8)*64 + ((kk%4)*2 + (hh ^ (m/8)%2))*8 + m%8
+//     (an instruction = 8 token slots x 128 bytes: whole cache lines; with 64-byte runs per slot the
+//     K loads cost three times what the V loads cost for the same bytes)
 //   V piece (page pg, 32-dim group db, half hh, dim n):  1024 + (pg*4+db)*64 + hh*32 + n
-// An MFMA operand read takes, per half-wavefront, contiguous runs of 256 bytes (K) or one
-// contiguous KiB (V): no bank conflicts.  In iteration t the wavefronts read image t and (for S of
+// An MFMA operand read takes contiguous runs of 128 bytes that alternate between the two halves
+// of the 256-byte bank sweep (K) or one contiguous KiB (V): no bank conflicts.  In iteration t the wavefronts read image t and (for S of
 // the next tile's first block) image t+1 and start the loads of image t+3; before the iteration's
 // barrier each wavefront waits until its loads of image t+2 have landed.  One s_barrier per tile.
 // Block padding: K padding never reaches a product (its S entries are masked by selection); V
@@ -234,7 +235,7 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_v2_kernel(
 
   const char* lds_bytes = reinterpret_cast<const char*>(lds_all);
   // byte offsets of this lane's operand pieces inside an image (see the layout above)
-  const int k_rd = (n >> 4) * 1024 + hh * 256 + (n & 15) * 16;
+  const int k_rd = (n >> 3) * 1024 + (hh ^ ((n >> 3) & 1)) * 128 + (n & 7) * 16;
   const int v_rd = 16384 + lane * 16;
   float m_ref[QB], lsum[QB], ev[QB], vodd[QB];
   f32x16 cinit[QB];                   // -m_ref in all 16 registers: the C operand that opens an S block
@@ -260,7 +261,7 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_v2_kernel(
   // used), and one wait in front of every even step covers that step and the next.
   u32x4 ring[kDepth];
   auto k_piece = [&](int img_off, int b, int kk) __attribute__((always_inline)) {
-    return *reinterpret_cast<const u32x4*>(lds_bytes + img_off + k_rd + b * 8192 + (kk >> 1) * 2048 + (kk & 1) * 512);
+    return *reinterpret_cast<const u32x4*>(lds_bytes + img_off + k_rd + b * 8192 + (kk >> 2) * 4096 + (kk & 3) * 256);
   };
   auto v_piece = [&](int img_off, int j) __attribute__((always_inline)) {      // j = page * 4 + dim group
     return *reinterpret_cast<const u32x4*>(lds_bytes + img_off + v_rd + j * 1024);
@@ -361,18 +362,20 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_v2_kernel(
   auto image_off = [&](int t) __attribute__((always_inline)) { return (t & (kBufs - 1)) * (kImage * 16); };   // bytes
   // Loads of one tile, straight into image `img_off`: wavefront w brings page w % 4 - K and V if
   // there are four wavefronts, else K (w < 4) or V.
-  //   K: lane L reads token slot swap23(L % 16), 16 bytes at dim 32 j + 8 (L / 16), for j = 0..3
+  //   K: instruction (rg, kq) brings rows 8 rg .. 8 rg + 7 of the page (row r sits in token slot
+  //      swap23(r)), 128 bytes each at dim 64 kq: lane L reads row 8 rg + L % 8, piece (L / 8) ^ rg
   //   V: lane (hh, n) reads slots 8hh.. of dim row 32 j + n
   const size_t blk_bytes = static_cast<size_t>(hkv) * (kBlock * kD) * sizeof(bf16_t);
   const char* k_head = reinterpret_cast<const char*>(k_pool) + static_cast<size_t>(kvh) * (kBlock * kD * sizeof(bf16_t));
   const char* v_head = reinterpret_cast<const char*>(v_pool) + static_cast<size_t>(kvh) * (kBlock * kD * sizeof(bf16_t));
-  const uint32_t k_voff = swap23(lane & 15) * (kD * 2) + (lane >> 4) * 16;
+  const uint32_t k_voff0 = swap23(lane & 7) * (kD * 2) + (lane >> 3) * 16;
+  const uint32_t k_voff1 = swap23(8 + (lane & 7)) * (kD * 2) + ((lane >> 3) ^ 1) * 16;
   const uint32_t v_voff = n * 32 + hh * 16;
   typedef __attribute__((address_space(3))) const uint4 lds_piece;
   const uint32_t lds_base = uniform(static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_piece*)lds_all)));   // LDS byte address
   const int page = whead;
   const bool brings_k = QB == 2 || wave < 4, brings_v = QB == 2 || wave >= 4;
-  const uint32_t k_img = lds_base + ((page >> 1) * 8 + (page & 1)) * 1024;   // this wavefront's first K group in image 0
+  const uint32_t k_img = lds_base + ((page >> 1) * 8 + (page & 1) * 2) * 1024;   // this wavefront's first K group in image 0
   const uint32_t v_img = lds_base + (16 + 4 * page) * 1024;                   // ... and its V page
   const char* k_src = nullptr;                                                // page of the tile being loaded (scalar)
   const char* v_src = nullptr;
@@ -384,13 +387,14 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_v2_kernel(
     k_dst = k_img + img_off;
     v_dst = v_img + img_off;
   };
-  // (the K groups of one page are 2 KiB apart in the image and 64 bytes apart in memory)
+  // (the two halves of a row are 4 KiB apart in the image and 128 bytes apart in memory; the two
+  // row groups of a page are neighbours in the image)
   auto dma_k = [&](int j) __attribute__((always_inline)) {
     if (!brings_k) return;
-    if (j == 0) dma_one<0>(k_voff, k_src, k_dst);
-    else if (j == 1) dma_one<64>(k_voff, k_src, k_dst + 1 * (2048 - 64));
-    else if (j == 2) dma_one<128>(k_voff, k_src, k_dst + 2 * (2048 - 64));
-    else dma_one<192>(k_voff, k_src, k_dst + 3 * (2048 - 64));
+    if (j == 0) dma_one<0>(k_voff0, k_src, k_dst);
+    else if (j == 1) dma_one<128>(k_voff0, k_src, k_dst + (4096 - 128));
+    else if (j == 2) dma_one<0>(k_voff1, k_src, k_dst + 1024);
+    else dma_one<128>(k_voff1, k_src, k_dst + 1024 + (4096 - 128));
   };
   auto dma_v = [&](int half) __attribute__((always_inline)) {
     if (!brings_v) return;
