@@ -217,8 +217,8 @@ int cc_qkv_project(cc_ctx* ctx, const void* x, const void* w_qkv, int32_t n_rows
  *   cc_linear:       y [n_rows][n_out] = x [n_rows][n_in] W^T (+ residual [n_rows][n_out], or NULL;
  *                    residual may be y itself, x may not).
  *   cc_gated_linear: y [n_rows][n_ffn] = silu(x W_gate^T) * (x W_up^T), silu(t) = t / (1 + exp(-t)).
- * bf16 with n_out (2 n_ffn for the gated form) a multiple of 256 and n_in a multiple of 32, at
- * least 96: MFMA GEMM with 128 x 128 outputs per wavefront; otherwise a plain tiled kernel. */
+ * bf16 with n_out (2 n_ffn for the gated form) a multiple of 256 and n_in a multiple of 64, at
+ * least 128: MFMA GEMM with 128 x 128 outputs per wavefront; otherwise a plain tiled kernel. */
 int cc_rms_norm(cc_ctx* ctx, const void* x, const void* gain, float eps, int32_t n_rows, int32_t hidden,
                 void* y, void* stream);
 int cc_linear(cc_ctx* ctx, const void* x, const void* w, const void* residual, int32_t n_rows,
@@ -285,6 +285,8 @@ int cc_sparse_prefill_static(cc_ctx* ctx, const void* q, const void* k_new, cons
  * logits overflowed its fixed softmax reference are walked again, rarely, by a scalar kernel);
  * otherwise the masses come from cc_question_mass's pass after the attention.  The call is for
  * the per-layer loop of Sec. 3.2.2, where inter_l(C_i, U) is wanted in every layer.
+ *   src_rows as for cc_sparse_prefill (NULL: q, k_new, v_new are compact); every pass of the call,
+ *   the by-product path and the passes after the attention alike, reads q through it.
  *   lse is required.  max_question_rows as for cc_question_mass; max_segs_per_req: most segments
  *   of one request (host scalar).  seg_mass [n_segs] float.
  *   workspace: cc_sparse_prefill_mass_workspace_bytes(ctx, n_ctx_tokens, n_segs, n_requests,
@@ -293,7 +295,8 @@ size_t cc_sparse_prefill_mass_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_t
                                               int32_t n_requests, int32_t max_question_rows,
                                               int32_t max_segs_per_req);
 int cc_sparse_prefill_mass(cc_ctx* ctx, const void* q, const void* k_new, const void* v_new,
-                           const int32_t* q_pos, const int32_t* slot_map, const int32_t* cu_q,
+                           const int32_t* src_rows, const int32_t* q_pos, const int32_t* slot_map,
+                           const int32_t* cu_q,
                            int32_t n_q_tot, int32_t max_q_per_req, int32_t max_question_rows,
                            void* k_pool, void* v_pool, int32_t n_blocks, const int32_t* block_tab,
                            const cc_segment* segs, int32_t n_segs,
@@ -310,6 +313,7 @@ int cc_sparse_prefill_mass(cc_ctx* ctx, const void* q, const void* k_new, const 
  * cc_sparse_prefill_mass kept for EVERY row; otherwise from cc_chunk_attention's passes after the
  * attention.  The by-product path needs the rows of segment s at [sel_off, sel_off + n_select) of
  * the compact list, as cc_select lays them out.
+ *   src_rows as for cc_sparse_prefill_mass.
  *   lse is required.  pair_mass [n_pairs] and self_mass [n_segs] float, both required; n_pairs as
  *   for cc_chunk_attention; max_segs_per_req: most segments of one request (host scalar).
  *   workspace: cc_sparse_prefill_pairs_workspace_bytes(ctx, n_ctx_tokens, n_segs, n_q_tot,
@@ -318,7 +322,8 @@ size_t cc_sparse_prefill_pairs_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_
                                                int32_t n_q_tot, int32_t max_q_per_req,
                                                int32_t max_segs_per_req);
 int cc_sparse_prefill_pairs(cc_ctx* ctx, const void* q, const void* k_new, const void* v_new,
-                            const int32_t* q_pos, const int32_t* slot_map, const int32_t* cu_q,
+                            const int32_t* src_rows, const int32_t* q_pos, const int32_t* slot_map,
+                            const int32_t* cu_q,
                             int32_t n_q_tot, int32_t max_q_per_req,
                             void* k_pool, void* v_pool, int32_t n_blocks, const int32_t* block_tab,
                             const cc_segment* segs, int32_t n_segs,

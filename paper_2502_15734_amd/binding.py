@@ -90,12 +90,12 @@ def load_library() -> C.CDLL:
     lib.cc_gated_linear.restype = C.c_int
     lib.cc_sparse_prefill_mass_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32]
     lib.cc_sparse_prefill_mass_workspace_bytes.restype = sz
-    lib.cc_sparse_prefill_mass.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, i32, vp, vp, i32,
+    lib.cc_sparse_prefill_mass.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, i32, vp, vp, i32,
                                            vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.cc_sparse_prefill_mass.restype = C.c_int
     lib.cc_sparse_prefill_pairs_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32]
     lib.cc_sparse_prefill_pairs_workspace_bytes.restype = sz
-    lib.cc_sparse_prefill_pairs.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, vp, i32,
+    lib.cc_sparse_prefill_pairs.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, vp, i32,
                                             vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.cc_sparse_prefill_pairs.restype = C.c_int
     lib.cc_scatter_kv.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, i32, vp]
@@ -274,10 +274,11 @@ class Context:
 
     def sparse_prefill_mass(self, q, k_new, v_new, q_pos, slot_map, cu_q, max_q_per_req, max_question_rows, k_pool,
                             v_pool, block_tab, segs, req_seg_off, n_requests, max_segs_per_req, n_ctx_tokens, out,
-                            lse, seg_mass, workspace):
+                            lse, seg_mass, workspace, src_rows=None):
+        n_q_tot = q.shape[0] if src_rows is None else src_rows.shape[0]
         self._check(self._lib.cc_sparse_prefill_mass(
-            self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(q_pos), _ptr(slot_map), _ptr(cu_q), q.shape[0],
-            max_q_per_req, max_question_rows, _ptr(k_pool), _ptr(v_pool), k_pool.shape[0], _ptr(block_tab),
+            self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(src_rows), _ptr(q_pos), _ptr(slot_map), _ptr(cu_q),
+            n_q_tot, max_q_per_req, max_question_rows, _ptr(k_pool), _ptr(v_pool), k_pool.shape[0], _ptr(block_tab),
             _ptr(segs), segs.shape[0], _ptr(req_seg_off), n_requests, max_segs_per_req, n_ctx_tokens, _ptr(out),
             _ptr(lse), _ptr(seg_mass), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
@@ -287,10 +288,11 @@ class Context:
 
     def sparse_prefill_pairs(self, q, k_new, v_new, q_pos, slot_map, cu_q, max_q_per_req, k_pool, v_pool, block_tab,
                              segs, req_seg_off, n_requests, max_segs_per_req, n_ctx_tokens, out, lse, seg_mass,
-                             pair_mass, self_mass, workspace):
+                             pair_mass, self_mass, workspace, src_rows=None):
+        n_q_tot = q.shape[0] if src_rows is None else src_rows.shape[0]
         self._check(self._lib.cc_sparse_prefill_pairs(
-            self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(q_pos), _ptr(slot_map), _ptr(cu_q), q.shape[0],
-            max_q_per_req, _ptr(k_pool), _ptr(v_pool), k_pool.shape[0], _ptr(block_tab), _ptr(segs), segs.shape[0],
+            self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(src_rows), _ptr(q_pos), _ptr(slot_map), _ptr(cu_q),
+            n_q_tot, max_q_per_req, _ptr(k_pool), _ptr(v_pool), k_pool.shape[0], _ptr(block_tab), _ptr(segs), segs.shape[0],
             _ptr(req_seg_off), n_requests, max_segs_per_req, n_ctx_tokens, pair_mass.shape[0], _ptr(out), _ptr(lse),
             _ptr(seg_mass), _ptr(pair_mass), _ptr(self_mass), _ptr(workspace),
             workspace.numel() * workspace.element_size(), _stream()))

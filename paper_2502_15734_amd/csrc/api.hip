@@ -365,7 +365,7 @@ size_t cc_sparse_prefill_mass_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_t
 }
 
 int cc_sparse_prefill_mass(cc_ctx* ctx, const void* q, const void* k_new, const void* v_new,
-                           const int32_t* q_pos, const int32_t* slot_map, const int32_t* cu_q,
+                           const int32_t* src_rows, const int32_t* q_pos, const int32_t* slot_map, const int32_t* cu_q,
                            int32_t n_q_tot, int32_t max_q_per_req, int32_t max_question_rows,
                            void* k_pool, void* v_pool, int32_t n_blocks, const int32_t* block_tab,
                            const cc_segment* segs, int32_t n_segs, const int32_t* req_seg_off,
@@ -398,19 +398,19 @@ int cc_sparse_prefill_mass(cc_ctx* ctx, const void* q, const void* k_new, const 
                                                                max_question_rows, max_segs_per_req))
     return fail(ctx, CC_ERR_WORKSPACE_TOO_SMALL,
                 "cc_sparse_prefill_mass: workspace smaller than cc_sparse_prefill_mass_workspace_bytes()");
-  cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_q_tot, k_pool, v_pool, n_blocks, nullptr, st);
+  cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_q_tot, k_pool, v_pool, n_blocks, src_rows, st);
   if (max_question_rows == 0) {                               // no question rows: plain attention, zero masses
     if (ctx->impl != CC_IMPL_SCALAR && cc::attn_mfma_supported(ctx))
       cc::launch_attn_mfma(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab,
                            segs, n_segs, req_seg_off, n_requests, out, lse, workspace,
-                           max_tiles_for(n_ctx_tokens, n_segs), nullptr, 0, st);
+                           max_tiles_for(n_ctx_tokens, n_segs), src_rows, 0, st);
     else
       cc::launch_attn_scalar(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab,
-                             segs, req_seg_off, n_requests, out, lse, nullptr, 0, st);
+                             segs, req_seg_off, n_requests, out, lse, src_rows, 0, st);
     cc::launch_fill_zero(seg_mass, n_segs, st);
     return cc::check_launch(ctx, fn);
   }
-  cc::launch_prefill_mass(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, max_question_rows, max_segs_per_req,
+  cc::launch_prefill_mass(ctx, q, src_rows, q_pos, cu_q, n_q_tot, max_q_per_req, max_question_rows, max_segs_per_req,
                           k_pool, v_pool, n_blocks, block_tab, segs, n_segs, req_seg_off, n_requests,
                           n_ctx_tokens, out, lse, seg_mass, workspace, max_tiles_for(n_ctx_tokens, n_segs), st);
   return cc::check_launch(ctx, fn);
@@ -426,7 +426,7 @@ size_t cc_sparse_prefill_pairs_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_
 }
 
 int cc_sparse_prefill_pairs(cc_ctx* ctx, const void* q, const void* k_new, const void* v_new,
-                            const int32_t* q_pos, const int32_t* slot_map, const int32_t* cu_q,
+                            const int32_t* src_rows, const int32_t* q_pos, const int32_t* slot_map, const int32_t* cu_q,
                             int32_t n_q_tot, int32_t max_q_per_req, void* k_pool, void* v_pool,
                             int32_t n_blocks, const int32_t* block_tab, const cc_segment* segs,
                             int32_t n_segs, const int32_t* req_seg_off, int32_t n_requests,
@@ -463,9 +463,9 @@ int cc_sparse_prefill_pairs(cc_ctx* ctx, const void* q, const void* k_new, const
                                                                 max_q_per_req, max_segs_per_req))
     return fail(ctx, CC_ERR_WORKSPACE_TOO_SMALL,
                 "cc_sparse_prefill_pairs: workspace smaller than cc_sparse_prefill_pairs_workspace_bytes()");
-  cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_q_tot, k_pool, v_pool, n_blocks, nullptr, st);
+  cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_q_tot, k_pool, v_pool, n_blocks, src_rows, st);
   cc::launch_fill_zero(pair_mass, n_pairs, st);               // pairs no row of the list falls into stay 0
-  cc::launch_prefill_pairs(ctx, q, q_pos, slot_map, cu_q, n_q_tot, max_q_per_req, max_segs_per_req, k_pool,
+  cc::launch_prefill_pairs(ctx, q, src_rows, q_pos, slot_map, cu_q, n_q_tot, max_q_per_req, max_segs_per_req, k_pool,
                            v_pool, n_blocks, block_tab, segs, n_segs, req_seg_off, n_requests, n_ctx_tokens,
                            out, lse, seg_mass, pair_mass, n_pairs, self_mass, workspace,
                            max_tiles_for(n_ctx_tokens, n_segs), st);
@@ -522,7 +522,7 @@ int cc_question_mass(cc_ctx* ctx, const void* q, const int32_t* q_pos, const int
   if (workspace_bytes < cc_question_mass_workspace_bytes(ctx, n_ctx_tokens, n_segs, max_question_rows))
     return fail(ctx, CC_ERR_WORKSPACE_TOO_SMALL,
                 "cc_question_mass: workspace smaller than cc_question_mass_workspace_bytes()");
-  cc::launch_question_mass(ctx, q, q_pos, cu_q, max_question_rows, k_pool, v_pool, n_blocks, block_tab, segs,
+  cc::launch_question_mass(ctx, q, nullptr, q_pos, cu_q, max_question_rows, k_pool, v_pool, n_blocks, block_tab, segs,
                            n_segs, req_seg_off, n_requests, lse, seg_mass, workspace,
                            max_tiles_for(n_ctx_tokens, n_segs), st);
   return cc::check_launch(ctx, fn);
@@ -566,7 +566,7 @@ int cc_chunk_attention(cc_ctx* ctx, const void* q, const int32_t* q_pos, const i
   cc::launch_fill_zero(pair_mass, n_pairs, st);             // pairs no row of the list falls into stay 0
   if (self_mass != nullptr) cc::launch_fill_zero(self_mass, n_segs, st);
   if (n_q_tot == 0) return cc::check_launch(ctx, fn);
-  cc::launch_chunk_attention(ctx, q, q_pos, slot_map, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks,
+  cc::launch_chunk_attention(ctx, q, nullptr, q_pos, slot_map, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks,
                              block_tab, segs, n_segs, req_seg_off, n_requests, lse, pair_mass, n_pairs, self_mass,
                              workspace, max_tiles_for(n_ctx_tokens, n_segs), st);
   return cc::check_launch(ctx, fn);

@@ -94,13 +94,14 @@ void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, co
 void launch_fill_zero(float* p, int n, hipStream_t stream);
 // n_q_tot_self: rows of the compact list when the self weights are wanted too (else 0)
 size_t segment_mass_bytes(const cc_ctx* ctx, int n_segs, int max_tiles, int max_rows, int n_q_tot_self);
-void launch_chunk_attention(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* slot_map,
+// (src_rows, where given: list row j reads row src_rows[j] of q; NULL: q is compact)
+void launch_chunk_attention(const cc_ctx* ctx, const void* q, const int32_t* src_rows, const int32_t* q_pos, const int32_t* slot_map,
                             const int32_t* cu_q, int n_q_tot, int max_q_per_req, const void* k_pool,
                             const void* v_pool, int n_blocks, const int32_t* block_tab, const cc_segment* segs,
                             int n_segs, const int32_t* req_seg_off, int n_requests, const float* lse,
                             float* pair_mass, int n_pairs, float* self_mass, void* workspace, int max_tiles,
                             hipStream_t stream);
-void launch_question_mass(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
+void launch_question_mass(const cc_ctx* ctx, const void* q, const int32_t* src_rows, const int32_t* q_pos, const int32_t* cu_q,
                           int max_question_rows, const void* k_pool, const void* v_pool, int n_blocks,
                           const int32_t* block_tab, const cc_segment* segs, int n_segs,
                           const int32_t* req_seg_off, int n_requests, const float* lse, float* seg_mass,
@@ -110,7 +111,7 @@ void launch_question_mass(const cc_ctx* ctx, const void* q, const int32_t* q_pos
 // kernels can give it (focus.hip)
 size_t prefill_mass_bytes(const cc_ctx* ctx, int n_ctx_tokens, int n_segs, int n_requests, int max_tiles,
                           int max_question_rows, int s_max);
-void launch_prefill_mass(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
+void launch_prefill_mass(const cc_ctx* ctx, const void* q, const int32_t* src_rows, const int32_t* q_pos, const int32_t* cu_q,
                          int n_q_tot, int max_q_per_req, int max_question_rows, int s_max, const void* k_pool,
                          const void* v_pool, int n_blocks, const int32_t* block_tab, const cc_segment* segs,
                          int n_segs, const int32_t* req_seg_off, int n_requests, int n_ctx_tokens, void* out,
@@ -119,7 +120,7 @@ void launch_prefill_mass(const cc_ctx* ctx, const void* q, const int32_t* q_pos,
 // ... and with the whole segment-to-segment matrix (every row's cumulative sums are kept)
 size_t prefill_pairs_bytes(const cc_ctx* ctx, int n_ctx_tokens, int n_segs, int max_tiles, int n_q_tot,
                            int max_q_per_req, int s_max);
-void launch_prefill_pairs(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* slot_map,
+void launch_prefill_pairs(const cc_ctx* ctx, const void* q, const int32_t* src_rows, const int32_t* q_pos, const int32_t* slot_map,
                           const int32_t* cu_q, int n_q_tot, int max_q_per_req, int s_max, const void* k_pool,
                           const void* v_pool, int n_blocks, const int32_t* block_tab, const cc_segment* segs,
                           int n_segs, const int32_t* req_seg_off, int n_requests, int n_ctx_tokens, void* out,

@@ -230,10 +230,11 @@ __global__ __launch_bounds__(256) void pair_mass_kernel(
 // by self_sum_kernel.
 template <typename T, int D>
 __global__ __launch_bounds__(64) void self_weight_kernel(
-    const T* __restrict__ q, const int32_t* __restrict__ q_pos, const int32_t* __restrict__ slot_map,
-    const T* __restrict__ k_pool, int n_blocks, int hq, int hkv, InvFreq inv_freq,
-    const float* __restrict__ lse, float* __restrict__ row_self) {
+    const T* __restrict__ q, const int32_t* __restrict__ src_rows, const int32_t* __restrict__ q_pos,
+    const int32_t* __restrict__ slot_map, const T* __restrict__ k_pool, int n_blocks, int hq, int hkv,
+    InvFreq inv_freq, const float* __restrict__ lse, float* __restrict__ row_self) {
   const int j = blockIdx.x, lane = threadIdx.x;
+  const int jq = src_rows != nullptr ? src_rows[j] : j;       // row of q the list row reads
   const int slot = slot_map[j];
   const bool ok = slot >= 0 && slot / kBlock < n_blocks;
   const bool own = lane < D / 2;
@@ -253,7 +254,7 @@ __global__ __launch_bounds__(64) void self_weight_kernel(
         const int h = kvh * group + g;
         float part = 0.f;
         if (own) {
-          const T* qp = q + (static_cast<size_t>(j) * hq + h) * D;
+          const T* qp = q + (static_cast<size_t>(jq) * hq + h) * D;
           const float x = to_float(qp[lane]), y = to_float(qp[lane + D / 2]);
           part = (x * c - y * sn) * kx + (y * c + x * sn) * ky;
         }
@@ -349,7 +350,8 @@ __global__ __launch_bounds__(256) void snap_fill_kernel(
 // (i, i + d/2).  (Slow, and meant to be: it only ever runs for rows whose logits overflowed.)
 template <typename T, int D>
 __global__ __launch_bounds__(64) void cum_scalar_kernel(
-    const T* __restrict__ q, const int32_t* __restrict__ q_pos, const int32_t* __restrict__ cu_q,
+    const T* __restrict__ q, const int32_t* __restrict__ src_rows, const int32_t* __restrict__ q_pos,
+    const int32_t* __restrict__ cu_q,
     const int32_t* __restrict__ snap_base, int n_requests, const int32_t* __restrict__ snap_rows,
     const int32_t* __restrict__ snap_req, const int32_t* __restrict__ redo,
     const T* __restrict__ k_pool, int n_blocks, const int32_t* __restrict__ block_tab,
@@ -370,7 +372,7 @@ __global__ __launch_bounds__(64) void cum_scalar_kernel(
   const int kvh = h / (hq / hkv);
   float qx = 0.f, qy = 0.f;
   if (own) {
-    const T* qp = q + (static_cast<size_t>(j) * hq + h) * D;
+    const T* qp = q + (static_cast<size_t>(src_rows != nullptr ? src_rows[j] : j) * hq + h) * D;
     float x = to_float(qp[lane]), y = to_float(qp[lane + D / 2]), c, sn;
     rot_cos_sin(p, inv_freq.f[lane], &c, &sn);
     qx = x * c - y * sn;
@@ -494,12 +496,25 @@ __global__ __launch_bounds__(256) void fill_kernel(float* __restrict__ p, size_t
   if (i < n) p[i] = v;
 }
 
+// entry row j (of cu_v[n_segs] in all): q row src_rows[q_map[j]], position q_pos[q_map[j]]
+__global__ __launch_bounds__(256) void fold_maps_kernel(const int32_t* __restrict__ cu_v, int n_segs,
+                                                         const int32_t* __restrict__ q_map,
+                                                         const int32_t* __restrict__ src_rows,
+                                                         const int32_t* __restrict__ q_pos,
+                                                         int32_t* __restrict__ q_map_src, int32_t* __restrict__ pos_src) {
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= cu_v[n_segs]) return;
+  const int row = q_map[j];
+  q_map_src[j] = src_rows[row];
+  pos_src[j] = q_pos[row];
+}
+
 size_t up256(size_t v) { return (v + 255) / 256 * 256; }
 
 // the workspace, cut up
 struct ListBuffers {
   void* plan_ws;
-  int32_t *m_seg, *cu_v, *seg_iota, *q_map, *row_seg;
+  int32_t *m_seg, *cu_v, *seg_iota, *q_map, *row_seg, *q_map_src, *pos_src;
   float *lse_seg, *row_self;
 };
 
@@ -510,11 +525,11 @@ void launch_fill_zero(float* p, int n, hipStream_t stream) {
 }
 
 // workspace: tile plan | m_seg[n_segs+1] | cu_v[n_segs+1] | seg_iota[n_segs+1] | q_map[cap] |
-//            row_seg[cap] | lse_seg[cap][Hq] | row_self[n_q_tot] (sized for Hq floats per row) (the last only for the pair matrix)
+//            row_seg[cap] | q_map_src[cap] | pos_src[cap] | lse_seg[cap][Hq] | row_self[n_q_tot] (sized for Hq floats per row) (the last only for the pair matrix)
 size_t segment_mass_bytes(const cc_ctx* ctx, int n_segs, int max_tiles, int max_rows, int n_q_tot_self) {
   const size_t cap = static_cast<size_t>(n_segs) * max_rows;
   return up256(mfma_plan_bytes(n_segs, max_tiles, static_cast<int>(cap))) +
-         3 * up256(static_cast<size_t>(n_segs + 1) * sizeof(int32_t)) + 2 * up256(cap * sizeof(int32_t)) +
+         3 * up256(static_cast<size_t>(n_segs + 1) * sizeof(int32_t)) + 4 * up256(cap * sizeof(int32_t)) +
          up256(cap * ctx->cfg.n_q_heads * sizeof(float)) +
          up256(static_cast<size_t>(n_q_tot_self) * ctx->cfg.n_q_heads * sizeof(float));
 }
@@ -535,6 +550,10 @@ static ListBuffers cut_workspace(const cc_ctx* ctx, void* workspace, int n_segs,
   w += up256(cap * sizeof(int32_t));
   b.row_seg = reinterpret_cast<int32_t*>(w);
   w += up256(cap * sizeof(int32_t));
+  b.q_map_src = reinterpret_cast<int32_t*>(w);
+  w += up256(cap * sizeof(int32_t));
+  b.pos_src = reinterpret_cast<int32_t*>(w);
+  w += up256(cap * sizeof(int32_t));
   b.lse_seg = reinterpret_cast<float*>(w);
   w += up256(cap * ctx->cfg.n_q_heads * sizeof(float));
   b.row_self = reinterpret_cast<float*>(w);
@@ -542,8 +561,8 @@ static ListBuffers cut_workspace(const cc_ctx* ctx, void* workspace, int n_segs,
 }
 
 // builds the list of one-segment requests and runs the attention kernels over it (log-sum-exp only)
-static void run_segment_list(const cc_ctx* ctx, const ListBuffers& b, const void* q, const int32_t* q_pos,
-                             const int32_t* cu_q, int max_rows, bool question_only, const void* k_pool,
+static void run_segment_list(const cc_ctx* ctx, const ListBuffers& b, const void* q, const int32_t* src_rows,
+                             const int32_t* q_pos, const int32_t* cu_q, int max_rows, bool question_only, const void* k_pool,
                              const void* v_pool, int n_blocks, const int32_t* block_tab, const cc_segment* segs,
                              int n_segs, const int32_t* req_seg_off, int n_requests, int max_tiles,
                              hipStream_t stream) {
@@ -555,27 +574,38 @@ static void run_segment_list(const cc_ctx* ctx, const ListBuffers& b, const void
   hipLaunchKernelGGL(row_map_kernel, dim3(n_segs), dim3(256), 0, stream, q_pos, cu_q, segs, req_seg_off,
                      n_requests, b.cu_v, hq, question_only, b.q_map, question_only ? nullptr : b.row_seg,
                      b.lse_seg);
+  // The kernels take one row map: entry row j reads q and q_pos at row q_map[j].  When the list rows
+  // themselves read q through src_rows, the two maps are folded into one and the positions are
+  // laid out by entry row, so that the kernels index them directly.
+  const int32_t* map = b.q_map;
+  const int32_t* pos = q_pos;
+  int map_pos = 1;
+  if (src_rows != nullptr) {
+    hipLaunchKernelGGL(fold_maps_kernel, dim3((cap + 255) / 256), dim3(256), 0, stream, b.cu_v, n_segs, b.q_map,
+                       src_rows, q_pos, b.q_map_src, b.pos_src);
+    map = b.q_map_src; pos = b.pos_src; map_pos = 0;
+  }
   if (ctx->impl != CC_IMPL_SCALAR && attn_mfma_supported(ctx))
-    launch_attn_mfma(ctx, q, q_pos, b.cu_v, cap, max_rows, k_pool, v_pool, n_blocks, block_tab, segs, n_segs,
-                     b.seg_iota, n_segs, nullptr, b.lse_seg, b.plan_ws, max_tiles, b.q_map, 1, stream);
+    launch_attn_mfma(ctx, q, pos, b.cu_v, cap, max_rows, k_pool, v_pool, n_blocks, block_tab, segs, n_segs,
+                     b.seg_iota, n_segs, nullptr, b.lse_seg, b.plan_ws, max_tiles, map, map_pos, stream);
   else
-    launch_attn_scalar(ctx, q, q_pos, b.cu_v, cap, max_rows, k_pool, v_pool, n_blocks, block_tab, segs,
-                       b.seg_iota, n_segs, nullptr, b.lse_seg, b.q_map, 1, stream);
+    launch_attn_scalar(ctx, q, pos, b.cu_v, cap, max_rows, k_pool, v_pool, n_blocks, block_tab, segs,
+                       b.seg_iota, n_segs, nullptr, b.lse_seg, map, map_pos, stream);
 }
 
-void launch_question_mass(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
+void launch_question_mass(const cc_ctx* ctx, const void* q, const int32_t* src_rows, const int32_t* q_pos, const int32_t* cu_q,
                           int max_question_rows, const void* k_pool, const void* v_pool, int n_blocks,
                           const int32_t* block_tab, const cc_segment* segs, int n_segs,
                           const int32_t* req_seg_off, int n_requests, const float* lse, float* seg_mass,
                           void* workspace, int max_tiles, hipStream_t stream) {
   const ListBuffers b = cut_workspace(ctx, workspace, n_segs, max_tiles, max_question_rows);
-  run_segment_list(ctx, b, q, q_pos, cu_q, max_question_rows, true, k_pool, v_pool, n_blocks, block_tab, segs,
+  run_segment_list(ctx, b, q, src_rows, q_pos, cu_q, max_question_rows, true, k_pool, v_pool, n_blocks, block_tab, segs,
                    n_segs, req_seg_off, n_requests, max_tiles, stream);
   hipLaunchKernelGGL(seg_mass_kernel, dim3(n_segs), dim3(256), 0, stream, b.cu_v, b.q_map, ctx->cfg.n_q_heads,
                      b.lse_seg, lse, seg_mass);
 }
 
-void launch_chunk_attention(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* slot_map,
+void launch_chunk_attention(const cc_ctx* ctx, const void* q, const int32_t* src_rows, const int32_t* q_pos, const int32_t* slot_map,
                             const int32_t* cu_q, int n_q_tot, int max_q_per_req, const void* k_pool,
                             const void* v_pool, int n_blocks, const int32_t* block_tab, const cc_segment* segs,
                             int n_segs, const int32_t* req_seg_off, int n_requests, const float* lse,
@@ -583,7 +613,7 @@ void launch_chunk_attention(const cc_ctx* ctx, const void* q, const int32_t* q_p
                             hipStream_t stream) {
   const ListBuffers b = cut_workspace(ctx, workspace, n_segs, max_tiles, max_q_per_req);
   const int hq = ctx->cfg.n_q_heads, hkv = ctx->cfg.n_kv_heads;
-  run_segment_list(ctx, b, q, q_pos, cu_q, max_q_per_req, false, k_pool, v_pool, n_blocks, block_tab, segs,
+  run_segment_list(ctx, b, q, src_rows, q_pos, cu_q, max_q_per_req, false, k_pool, v_pool, n_blocks, block_tab, segs,
                    n_segs, req_seg_off, n_requests, max_tiles, stream);
   hipLaunchKernelGGL(pair_mass_kernel, dim3(n_segs), dim3(256), 0, stream, segs, req_seg_off, n_requests,
                      b.cu_v, b.q_map, b.row_seg, hq, b.lse_seg, lse, pair_mass, n_pairs);
@@ -592,7 +622,7 @@ void launch_chunk_attention(const cc_ctx* ctx, const void* q, const int32_t* q_p
     const int d = ctx->cfg.head_dim;
 #define CC_LAUNCH(T, D)                                                                              \
   hipLaunchKernelGGL((self_weight_kernel<T, D>), dim3(n_q_tot), dim3(64), 0, stream,                 \
-                     static_cast<const T*>(q), q_pos, slot_map, static_cast<const T*>(k_pool), n_blocks, \
+                     static_cast<const T*>(q), src_rows, q_pos, slot_map, static_cast<const T*>(k_pool), n_blocks, \
                      hq, hkv, ctx->inv_freq, lse, b.row_self)
     if (bf && d == 128) CC_LAUNCH(bf16_t, 128);
     else if (bf && d == 64) CC_LAUNCH(bf16_t, 64);
@@ -618,7 +648,7 @@ size_t prefill_mass_bytes(const cc_ctx* ctx, int n_ctx_tokens, int n_segs, int n
          segment_mass_bytes(ctx, n_segs, max_tiles, max_question_rows, 0);
 }
 
-void launch_prefill_mass(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
+void launch_prefill_mass(const cc_ctx* ctx, const void* q, const int32_t* src_rows, const int32_t* q_pos, const int32_t* cu_q,
                          int n_q_tot, int max_q_per_req, int max_question_rows, int s_max, const void* k_pool,
                          const void* v_pool, int n_blocks, const int32_t* block_tab, const cc_segment* segs,
                          int n_segs, const int32_t* req_seg_off, int n_requests, int n_ctx_tokens, void* out,
@@ -655,10 +685,10 @@ void launch_prefill_mass(const cc_ctx* ctx, const void* q, const int32_t* q_pos,
     hipLaunchKernelGGL(fill_kernel, dim3(static_cast<unsigned>((n_cum + 255) / 256)), dim3(256), 0, stream, cum, n_cum,
                        -INFINITY);
     launch_attn_mfma(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab, segs,
-                     n_segs, req_seg_off, n_requests, out, lse, plan_ws, max_tiles, nullptr, 0, stream, &by);
+                     n_segs, req_seg_off, n_requests, out, lse, plan_ws, max_tiles, src_rows, 0, stream, &by);
   } else {
     launch_attn_scalar(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab, segs,
-                       req_seg_off, n_requests, out, lse, nullptr, 0, stream);
+                       req_seg_off, n_requests, out, lse, src_rows, 0, stream);
   }
   if (by.wide) {
     // rows the wide kernel flagged (normally none: every wavefront reads one flag and leaves)
@@ -666,7 +696,7 @@ void launch_prefill_mass(const cc_ctx* ctx, const void* q, const int32_t* q_pos,
     const int d = ctx->cfg.head_dim;
 #define CC_LAUNCH(T, D)                                                                                  \
   hipLaunchKernelGGL((cum_scalar_kernel<T, D>), dim3(static_cast<unsigned>(cap)), dim3(64), 0, stream, \
-                     static_cast<const T*>(q), q_pos, cu_q, snap_base, n_requests, snap_rows, snap_req,   \
+                     static_cast<const T*>(q), src_rows, q_pos, cu_q, snap_base, n_requests, snap_rows, snap_req,   \
                      by.redo, static_cast<const T*>(k_pool), n_blocks, block_tab, segs, req_seg_off, hq,  \
                      hkv, ctx->inv_freq, cum, s_max)
     if (bf && d == 128) CC_LAUNCH(bf16_t, 128);
@@ -678,7 +708,7 @@ void launch_prefill_mass(const cc_ctx* ctx, const void* q, const int32_t* q_pos,
                        snap_base, snap_rows, hq, cum, s_max, lse, seg_mass);
   } else {
     // the kernels that ran carry no by-product: the pass of its own
-    launch_question_mass(ctx, q, q_pos, cu_q, max_question_rows, k_pool, v_pool, n_blocks, block_tab, segs,
+    launch_question_mass(ctx, q, src_rows, q_pos, cu_q, max_question_rows, k_pool, v_pool, n_blocks, block_tab, segs,
                          n_segs, req_seg_off, n_requests, lse, seg_mass, fallback_ws, max_tiles, stream);
   }
 }
@@ -694,7 +724,7 @@ size_t prefill_pairs_bytes(const cc_ctx* ctx, int n_ctx_tokens, int n_segs, int 
          segment_mass_bytes(ctx, n_segs, max_tiles, max_q_per_req, n_q_tot);
 }
 
-void launch_prefill_pairs(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* slot_map,
+void launch_prefill_pairs(const cc_ctx* ctx, const void* q, const int32_t* src_rows, const int32_t* q_pos, const int32_t* slot_map,
                           const int32_t* cu_q, int n_q_tot, int max_q_per_req, int s_max, const void* k_pool,
                           const void* v_pool, int n_blocks, const int32_t* block_tab, const cc_segment* segs,
                           int n_segs, const int32_t* req_seg_off, int n_requests, int n_ctx_tokens, void* out,
@@ -717,17 +747,17 @@ void launch_prefill_pairs(const cc_ctx* ctx, const void* q, const int32_t* q_pos
     hipLaunchKernelGGL(fill_kernel, dim3(static_cast<unsigned>((n_cum + 255) / 256)), dim3(256), 0, stream, cum, n_cum,
                        -INFINITY);
     launch_attn_mfma(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab, segs,
-                     n_segs, req_seg_off, n_requests, out, lse, plan_ws, max_tiles, nullptr, 0, stream, &by);
+                     n_segs, req_seg_off, n_requests, out, lse, plan_ws, max_tiles, src_rows, 0, stream, &by);
   } else {
     launch_attn_scalar(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab, segs,
-                       req_seg_off, n_requests, out, lse, nullptr, 0, stream);
+                       req_seg_off, n_requests, out, lse, src_rows, 0, stream);
   }
   const bool bf = ctx->cfg.dtype == CC_BF16;
   const int d = ctx->cfg.head_dim;
   if (by.wide) {
 #define CC_LAUNCH(T, D)                                                                                       \
   hipLaunchKernelGGL((cum_scalar_kernel<T, D>), dim3(static_cast<unsigned>(n_q_tot)), dim3(64), 0, stream,     \
-                     static_cast<const T*>(q), q_pos, cu_q, cu_q, n_requests, static_cast<const int32_t*>(nullptr), \
+                     static_cast<const T*>(q), src_rows, q_pos, cu_q, cu_q, n_requests, static_cast<const int32_t*>(nullptr), \
                      static_cast<const int32_t*>(nullptr), by.redo, static_cast<const T*>(k_pool), n_blocks,   \
                      block_tab, segs, req_seg_off, hq, hkv, ctx->inv_freq, cum, s_max)
     if (bf && d == 128) CC_LAUNCH(bf16_t, 128);
@@ -740,7 +770,7 @@ void launch_prefill_pairs(const cc_ctx* ctx, const void* q, const int32_t* q_pos
     if (self_mass != nullptr) {
 #define CC_LAUNCH(T, D)                                                                              \
   hipLaunchKernelGGL((self_weight_kernel<T, D>), dim3(n_q_tot), dim3(64), 0, stream,                 \
-                     static_cast<const T*>(q), q_pos, slot_map, static_cast<const T*>(k_pool), n_blocks, \
+                     static_cast<const T*>(q), src_rows, q_pos, slot_map, static_cast<const T*>(k_pool), n_blocks, \
                      hq, hkv, ctx->inv_freq, lse, row_self)
       if (bf && d == 128) CC_LAUNCH(bf16_t, 128);
       else if (bf && d == 64) CC_LAUNCH(bf16_t, 64);
@@ -751,7 +781,7 @@ void launch_prefill_pairs(const cc_ctx* ctx, const void* q, const int32_t* q_pos
                          row_self, self_mass);
     }
   } else {
-    launch_chunk_attention(ctx, q, q_pos, slot_map, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks,
+    launch_chunk_attention(ctx, q, src_rows, q_pos, slot_map, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks,
                            block_tab, segs, n_segs, req_seg_off, n_requests, lse, pair_mass, n_pairs, self_mass,
                            fallback_ws, max_tiles, stream);
   }

@@ -123,111 +123,12 @@ __global__ __launch_bounds__(256) void linear_plain_kernel(
 // ---- MFMA kernel (bf16) -----------------------------------------------------------------------
 namespace {
 
-constexpr int kTN = 256, kTM = 256, kTK = 32;         // workgroup tile: features x tokens x k-step
-constexpr int kTilePieces = (kTN + kTM) * kTK * 2 / 16;   // 16-byte pieces per k-step image (2048)
-
-// A row of a k-step image is 32 bf16 = 4 pieces of 16 bytes; piece c of row r is kept at
-// c ^ ((r >> 1) & 3), which makes both the staging writes and the MFMA operand reads (32 rows,
-// same piece) touch all LDS banks evenly.
-__device__ __forceinline__ int gemm_piece(int r, int c) { return r * 4 + (c ^ ((r >> 1) & 3)); }
-
-__global__ __launch_bounds__(512, 2) void qkv_project_mfma_kernel(
-    const bf16_t* __restrict__ x, const bf16_t* __restrict__ w, int n_rows, int hidden, int nq, int nk,
-    bf16_t* __restrict__ q, bf16_t* __restrict__ k, bf16_t* __restrict__ v) {
-  __shared__ uint4 lds[2 * kTilePieces];               // [buffer][W rows 0..255 | x rows 0..255][4 pieces]
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int nl = lane & 31, hh = lane >> 5;
-  const int wn = wave & 3, wm = wave >> 2;             // 4 x 2 wavefronts: 64 features x 128 tokens each
-  const int n0 = blockIdx.x * kTN, m0 = blockIdx.y * kTM;
-
-  // staging: thread t owns pieces t, t+512, t+1024, t+1536 of the image: rows t/4 (+128 ...), piece t%4
-  const bf16_t* src[4];
-  int dst[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int pc = tid + 512 * i, r = pc >> 2, c = pc & 3;      // r in [0, 512): W rows then x rows
-    if (r < kTN) src[i] = w + static_cast<size_t>(n0 + r) * hidden + c * 8;
-    else src[i] = x + static_cast<size_t>(min(m0 + r - kTN, n_rows - 1)) * hidden + c * 8;
-    dst[i] = (r < kTN ? 0 : kTN * 4) + gemm_piece(r < kTN ? r : r - kTN, c);
-  }
-  uint4 reg[4];
-  f32x16 acc[2][4];
-#pragma unroll
-  for (int a = 0; a < 2; ++a)
-#pragma unroll
-    for (int b = 0; b < 4; ++b)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
-
-  const int n_k = hidden / kTK;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) reg[i] = *reinterpret_cast<const uint4*>(src[i]);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) lds[dst[i]] = reg[i];
-  __syncthreads();
-  for (int ks = 0; ks < n_k; ++ks) {
-    const uint4* img = lds + (ks & 1) * kTilePieces;
-    if (ks + 1 < n_k) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) reg[i] = *reinterpret_cast<const uint4*>(src[i] + (ks + 1) * kTK);
-    }
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {                   // two 16-wide k-steps
-      bf16x8 af[2], bfr[4];
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-        af[a] = __builtin_bit_cast(bf16x8, img[gemm_piece(wn * 64 + a * 32 + nl, 2 * kk + hh)]);
-#pragma unroll
-      for (int b = 0; b < 4; ++b)
-        bfr[b] = __builtin_bit_cast(bf16x8, img[kTN * 4 + gemm_piece(wm * 128 + b * 32 + nl, 2 * kk + hh)]);
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
-    }
-    if (ks + 1 < n_k) {
-      uint4* nxt = lds + ((ks + 1) & 1) * kTilePieces;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) nxt[dst[i]] = reg[i];
-    }
-    __syncthreads();
-  }
-
-  // D^T block (a, b): lane (nl, hh) holds token m0 + wm*128 + b*32 + nl, features
-  // n0 + wn*64 + a*32 + 8*(i/4) + 4*hh + i%4
-#pragma unroll
-  for (int b = 0; b < 4; ++b) {
-    const int row = m0 + wm * 128 + b * 32 + nl;
-    if (row >= n_rows) continue;
-#pragma unroll
-    for (int a = 0; a < 2; ++a) {
-      const int col0 = n0 + wn * 64 + a * 32;         // a 32-feature block never straddles q | k | v
-      bf16_t* base;
-      int c_in, width;
-      if (col0 < nq) { base = q; c_in = col0; width = nq; }
-      else if (col0 < nq + nk) { base = k; c_in = col0 - nq; width = nk; }
-      else { base = v; c_in = col0 - nq - nk; width = nk; }
-      bf16_t* op = base + static_cast<size_t>(row) * width + c_in + 4 * hh;
-#pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4) {
-        bf16_t v4[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v4[e] = static_cast<bf16_t>(acc[a][b][4 * g4 + e]);
-        *reinterpret_cast<uint2*>(op + 8 * g4) = *reinterpret_cast<uint2*>(v4);
-      }
-    }
-  }
-}
+constexpr int kTN = 256, kTM = 256;                   // workgroup tile: features x tokens
 
 // ---- MFMA kernel, 128 x 128 outputs per wavefront -------------------------------------------------
 // Workgroup = 4 wavefronts (2 x 2), one per SIMD, 256 features x 256 tokens; a wavefront owns
 // 4 x 4 blocks of v_mfma_f32_32x32x16_bf16 (256 accumulation registers), so 8 operand reads from
-// LDS feed 16 MFMAs per 16-wide k-step - half the LDS traffic per MFMA of the kernel above.
-// K-steps of 32 go straight from global memory into a ring of four LDS images (32 KiB each,
-// global_load_lds: lane L of an instruction fills piece base + L, so an image is laid out in MFMA
-// operand order and every operand read is one contiguous KiB): iteration t starts the loads of
-// image t+3 and, before its barrier, waits for its own loads of image t+2.
+// LDS feed 16 MFMAs per 16-wide k-step.
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 
 __device__ __forceinline__ void gemm_load_to_lds(const void* src, uint32_t lds_addr) {
@@ -293,117 +194,12 @@ __device__ __forceinline__ void gemm_store_tile(f32x16 (&acc)[4][4], const GemmO
   }
 }
 
-constexpr int kStages = 4;
-constexpr int kStageBytes = 32 * 1024;      // 32 operand groups of 1 KiB: W blocks 0..7 x 2 k-steps, x blocks 0..7 x 2 k-steps
-
-template <int MODE>
-__global__ __launch_bounds__(256, 1) void gemm_mfma2_kernel(
-    const bf16_t* __restrict__ x, const bf16_t* __restrict__ w, const bf16_t* __restrict__ w2, int n_rows,
-    int hidden, GemmOut out) {
-  __shared__ uint4 lds[kStages * kStageBytes / 16];
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int nl = lane & 31, hh = lane >> 5;
-  const int wn = wave & 1, wm = wave >> 1;             // feature half, token half of the workgroup tile
-  const int n0 = blockIdx.x * kTN, m0 = blockIdx.y * kTM;
-  const int n_k = hidden / kTK;
-
-  // ---- staging: wavefront w brings operand groups 8w .. 8w+7 of every image --------------------
-  // group g < 16: W block g/2, k-step g%2; g >= 16: x block (g-16)/2, k-step g%2.  Lane (nl, hh)
-  // of a group reads row 32 block + nl, 16 bytes at k = 16 step + 8 hh of the image's 32-wide slice.
-  const char* src[8];
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int g = 8 * wave + j, blk = (g & 15) >> 1, step = g & 1;
-    const int r = 32 * blk + nl;
-    const bf16_t* row;
-    if (g >= 16) row = x + static_cast<size_t>(min(m0 + r, n_rows - 1)) * hidden;
-    else if (MODE != kOutGated) row = w + static_cast<size_t>(n0 + r) * hidden;
-    else {
-      // gated: of a wavefront's four feature blocks, two are rows of W_gate and two the SAME rows
-      // of W_up, so that a lane ends up holding both factors of an output
-      const int f = n0 / 2 + 64 * (blk >> 2) + 32 * (blk & 1) + nl;
-      row = ((blk & 2) ? w2 : w) + static_cast<size_t>(f) * hidden;
-    }
-    src[j] = reinterpret_cast<const char*>(row + 16 * step + 8 * hh);
-  }
-  typedef __attribute__((address_space(3))) const uint4 lds_piece;
-  const uint32_t lds_base = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_piece*)lds)));
-  auto dma_stage = [&](int t) __attribute__((always_inline)) {
-    const uint32_t dst = lds_base + (t & (kStages - 1)) * kStageBytes + (8 * wave) * 1024;
-    const size_t koff = static_cast<size_t>(min(t, n_k - 1)) * (kTK * sizeof(bf16_t));   // past the end: a harmless repeat
-#pragma unroll
-    for (int j = 0; j < 8; ++j) gemm_load_to_lds(src[j] + koff, dst + 1024 * j);
-  };
-  auto wait_loads = [&](auto newer) __attribute__((always_inline)) {
-    constexpr int kN = decltype(newer)::value;
-    __builtin_amdgcn_s_waitcnt((kN & 15) | ((kN >> 4) << 14) | (7 << 4) | (15 << 8));
-    asm volatile("" ::: "memory");
-  };
-  auto barrier = [&]() __attribute__((always_inline)) {
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-  };
-
-  f32x16 acc[4][4];                                    // [feature block][token block], accumulation registers
-#pragma unroll
-  for (int a = 0; a < 4; ++a)
-#pragma unroll
-    for (int b = 0; b < 4; ++b)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) asm volatile("v_accvgpr_write_b32 %0, 0" : "=a"(acc[a][b][i]));
-
-  const char* lds_bytes = reinterpret_cast<const char*>(lds);
-  const int lane16 = lane * 16;
-  // operand group of this wavefront: W block 4 wn + a / x block 4 wm + b, k-step s of image t
-  auto read_a = [&](int t, int s, int a) __attribute__((always_inline)) {
-    return *reinterpret_cast<const u32x4*>(lds_bytes + (t & (kStages - 1)) * kStageBytes + ((4 * wn + a) * 2 + s) * 1024 + lane16);
-  };
-  auto read_b = [&](int t, int s, int b) __attribute__((always_inline)) {
-    return *reinterpret_cast<const u32x4*>(lds_bytes + (t & (kStages - 1)) * kStageBytes + (16 + (4 * wm + b) * 2 + s) * 1024 + lane16);
-  };
-
-  // ---- prologue: images 0, 1, 2 -----------------------------------------------------------------
-  dma_stage(0);
-  dma_stage(1);
-  dma_stage(2);
-  wait_loads(std::integral_constant<int, 0>{});
-  __syncthreads();
-  u32x4 opa[2][4], opb[2][4];                          // operands of the k-step in flight and of the next one
-#pragma unroll
-  for (int i = 0; i < 4; ++i) { opa[0][i] = read_a(0, 0, i); opb[0][i] = read_b(0, 0, i); }
-
-  for (int t = 0; t < n_k; ++t) {
-    dma_stage(t + 3);
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      // operands of the next k-step (the other half of this image, or the first of the next one)
-      const int nt = s == 0 ? t : min(t + 1, n_k - 1), ns = s ^ 1;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) { opa[s ^ 1][i] = read_a(nt, ns, i); opb[s ^ 1][i] = read_b(nt, ns, i); }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b) gemm_mfma(acc[a][b], opa[s][a], opb[s][b]);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // image t+2 (loads started one iteration ago) must be whole before anyone reads it
-    wait_loads(std::integral_constant<int, 8>{});
-    barrier();
-  }
-  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
-
-  gemm_store_tile<MODE>(acc, out, n_rows, n0, m0, wn, wm, nl, hh);
-}
-
-// ---- MFMA kernel, 128 x 128 outputs per wavefront, whole cache lines per load ----------------------
-// Same tile and accumulators as the kernel above; what changes is how the operands travel.  A k-stage
-// is 64 wide: 128 bytes = one cache line of every row of W and x.  A load instruction brings 8 rows
-// x 128 bytes (8 consecutive lanes share a line; the kernel above touches 32 lines for the same
-// kilobyte and needs every line in two stages), and the image in LDS is row-major, 128 bytes per
-// row.  Operand reads walk down 32 rows at one 16-byte piece, so piece c of row r is kept at
+// Operands go straight from global memory into LDS (global_load_lds: lane L of an instruction fills
+// piece base + L), whole cache lines per load.  A k-stage is 64 wide: 128 bytes = one cache line of
+// every row of W and x.  A load instruction brings 8 rows x 128 bytes (8 consecutive lanes share a
+// line; an image laid out in MFMA operand order instead - 32 rows x 32 bytes per instruction - was
+// measured: it touches 32 lines for the same kilobyte, needs every line in two stages, and ran the
+// gated product in 9.96 ms instead of 6.94), and the image in LDS is row-major, 128 bytes per row.  Operand reads walk down 32 rows at one 16-byte piece, so piece c of row r is kept at
 // c ^ swz(r), swz(r) = ((r >> 1) & 7) ^ ((r & 1) << 2): any 8 or 16 consecutive rows then spread
 // over all banks.  The permutation is applied on the global side (lane -> piece of the line),
 // because the load fixes where a lane's bytes land in LDS.  Two images of 64 KiB; per stage the
@@ -546,18 +342,17 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma3_kernel(
   gemm_store_tile<MODE>(acc, out, n_rows, n0, m0, wn, wm, nl, hh);
 }
 
-// the 128 x 128-per-wavefront kernels: whole-cache-line stages where the contraction length allows
+// the 128 x 128-per-wavefront kernel (contraction length a multiple of 64)
 template <int MODE>
 void launch_gemm_wide(dim3 grid, hipStream_t stream, const void* x, const void* w, const void* w2, int n_rows, int n_in,
                       const GemmOut& out) {
-  if (n_in % kTK3 == 0)
-    hipLaunchKernelGGL(gemm_mfma3_kernel<MODE>, dim3((grid.x * grid.y + 7) / 8 * 8), dim3(256), 0, stream,
-                       static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(w), static_cast<const bf16_t*>(w2),
-                       n_rows, n_in, static_cast<int>(grid.x), static_cast<int>(grid.y), out);
-  else
-    hipLaunchKernelGGL(gemm_mfma2_kernel<MODE>, grid, dim3(256), 0, stream, static_cast<const bf16_t*>(x),
-                       static_cast<const bf16_t*>(w), static_cast<const bf16_t*>(w2), n_rows, n_in, out);
+  hipLaunchKernelGGL(gemm_mfma3_kernel<MODE>, dim3((grid.x * grid.y + 7) / 8 * 8), dim3(256), 0, stream,
+                     static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(w), static_cast<const bf16_t*>(w2),
+                     n_rows, n_in, static_cast<int>(grid.x), static_cast<int>(grid.y), out);
 }
+
+// the MFMA GEMM takes outputs in tiles of 256 features and contraction lengths in stages of 64, at least two
+inline bool gemm_wide_fits(int n_features, int n_in) { return n_features % kTN == 0 && n_in % kTK3 == 0 && n_in >= 2 * kTK3; }
 
 }  // namespace
 
@@ -565,16 +360,10 @@ void launch_qkv_project(const cc_ctx* ctx, const void* x, const void* w, int n_r
                         void* q, void* k, void* v, hipStream_t stream) {
   const int d = ctx->cfg.head_dim;
   const int nq = ctx->cfg.n_q_heads * d, nk = ctx->cfg.n_kv_heads * d, n_cols = nq + 2 * nk;
-  if (ctx->cfg.dtype == CC_BF16 && ctx->impl != CC_IMPL_SCALAR && n_cols % kTN == 0 && hidden % kTK == 0 &&
+  if (ctx->cfg.dtype == CC_BF16 && ctx->impl != CC_IMPL_SCALAR && gemm_wide_fits(n_cols, hidden) &&
       nq % 32 == 0 && nk % 32 == 0) {
     dim3 grid(n_cols / kTN, (n_rows + kTM - 1) / kTM);
-    if (hidden / kTK >= 3 && ctx->impl != CC_IMPL_MFMA_NARROW) {
-      launch_gemm_wide<kOutQkv>(grid, stream, x, w, nullptr, n_rows, hidden, GemmOut{q, k, v, nullptr, nq, nk, 0});
-      return;
-    }
-    hipLaunchKernelGGL(qkv_project_mfma_kernel, grid, dim3(512), 0, stream,
-                       static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(w), n_rows, hidden, nq, nk,
-                       static_cast<bf16_t*>(q), static_cast<bf16_t*>(k), static_cast<bf16_t*>(v));
+    launch_gemm_wide<kOutQkv>(grid, stream, x, w, nullptr, n_rows, hidden, GemmOut{q, k, v, nullptr, nq, nk, 0});
     return;
   }
   dim3 grid((n_cols + 63) / 64, (n_rows + 63) / 64);
@@ -594,8 +383,7 @@ void launch_qkv_project(const cc_ctx* ctx, const void* x, const void* w, int n_r
 void launch_linear(const cc_ctx* ctx, const void* x, const void* w, const void* residual, int n_rows, int n_in,
                    int n_out, void* y, hipStream_t stream) {
   const bool bf = ctx->cfg.dtype == CC_BF16;
-  if (bf && ctx->impl != CC_IMPL_SCALAR && ctx->impl != CC_IMPL_MFMA_NARROW && n_out % kTN == 0 && n_in % kTK == 0 &&
-      n_in / kTK >= 3) {
+  if (bf && ctx->impl != CC_IMPL_SCALAR && gemm_wide_fits(n_out, n_in)) {
     dim3 grid(n_out / kTN, (n_rows + kTM - 1) / kTM);
     launch_gemm_wide<kOutLinear>(grid, stream, x, w, nullptr, n_rows, n_in, GemmOut{y, nullptr, nullptr, residual, 0, 0, n_out});
     return;
@@ -615,8 +403,7 @@ void launch_linear(const cc_ctx* ctx, const void* x, const void* w, const void* 
 void launch_gated_linear(const cc_ctx* ctx, const void* x, const void* w_gate, const void* w_up, int n_rows,
                          int n_in, int n_ffn, void* y, hipStream_t stream) {
   const bool bf = ctx->cfg.dtype == CC_BF16;
-  if (bf && ctx->impl != CC_IMPL_SCALAR && ctx->impl != CC_IMPL_MFMA_NARROW && (2 * n_ffn) % kTN == 0 &&
-      n_in % kTK == 0 && n_in / kTK >= 3) {
+  if (bf && ctx->impl != CC_IMPL_SCALAR && gemm_wide_fits(2 * n_ffn, n_in)) {
     dim3 grid(2 * n_ffn / kTN, (n_rows + kTM - 1) / kTM);
     launch_gemm_wide<kOutGated>(grid, stream, x, w_gate, w_up, n_rows, n_in, GemmOut{y, nullptr, nullptr, nullptr, 0, 0, n_ffn});
     return;

@@ -3,9 +3,9 @@
 LayerLoop (attention only): per layer the chunk store arrives through the layer-wise preloader,
 cached keys are re-positioned, the chosen tokens are recomputed and attended, the question's
 attention to every chunk feeds Algorithm 1, and once a request's focused chunks are settled the
-other chunks of that request are no longer recomputed.  The synthetic workloads hold ONE layer's
-tensors, so every layer reuses them with the queries scaled by a per-layer factor (a power of
-two, exact in bf16) to make the layers differ.
+other chunks of that request are no longer recomputed.  The batch holds ONE layer's per-token
+tensors; a caller that has a different set per layer installs it through the loop's layer_inputs
+hook.
 
 DecoderLoop (whole layers): the hidden states of the chosen rows pass through normalisation,
 projections, the partial prefill and the feed-forward network of every layer.
@@ -167,10 +167,15 @@ class DecoderLoop:
 
 
 class LayerLoop:
-    def __init__(self, w, n_layers: int, window: int, q_scale: Callable[[int], float] = lambda l: 1.0,
+    def __init__(self, w, n_layers: int, window: int,
+                 layer_inputs: Optional[Callable[[int, DeviceBatch], None]] = None,
                  impl: int = CC_IMPL_AUTO, preload: bool = True, depth: Optional[int] = None,
                  device: str = "cuda"):
-        self.w, self.n_layers, self.window, self.q_scale = w, n_layers, window, q_scale
+        """layer_inputs(l, batch), if given, runs before layer l's attention on the stream the loop
+        uses; it may overwrite batch.q / batch.k_new / batch.v_new (or batch.hidden) in place with
+        layer l's tensors.  The attention reads them per token through the row list: the loop
+        makes no compact copies unless the workload is projected from hidden states."""
+        self.w, self.n_layers, self.window, self.layer_inputs = w, n_layers, window, layer_inputs
         self.batch = DeviceBatch(w, device=device, impl=impl)
         b = self.batch
         seg = w.segments
@@ -212,11 +217,11 @@ class LayerLoop:
                 b.select()
             else:
                 b.select_from_scores()
-            b.gather()
-            s = float(self.q_scale(l))
-            if s != 1.0 and b.n_q_tot:
-                b.q_c[: b.n_q_tot].mul_(s)
-            mass = b.sparse_prefill_mass()               # attention + the question's masses in one call
+            if self.layer_inputs is not None:
+                self.layer_inputs(l, b)
+            if b.projected:
+                b.gather()
+            mass = b.sparse_prefill_mass(fused=not b.projected)   # attention + the question's masses in one call
             self.mass_host.copy_(mass, non_blocking=True)
             self.mass_ready.record()
             if self.pre is not None:

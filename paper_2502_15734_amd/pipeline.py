@@ -192,8 +192,18 @@ class DeviceBatch:
             self.ws_mass = torch.empty(max(256, nbytes), dtype=torch.uint8, device=self.device)
         return n_segs
 
-    def sparse_prefill_mass(self):
-        """sparse_prefill and the question's masses per segment in one call (by-product where possible)."""
+    def _qkv_args(self, fused):
+        """(q, k_new, v_new, src_rows) of a prefill call: compact rows, or the per-token tensors read
+        through cc_select's row list."""
+        r = self._rows
+        if fused:
+            assert not self.projected, "a projected workload has no per-token q, k, v"
+            return self.q, self.k_new, self.v_new, r(self.q_row)
+        return r(self.q_c), r(self.k_c), r(self.v_c), None
+
+    def sparse_prefill_mass(self, fused: bool = False):
+        """sparse_prefill and the question's masses per segment in one call (by-product where possible).
+        fused: read q, k_new, v_new per token through the row list instead of the gathered copies."""
         n_segs = self._mass_buffers()
         if self.n_q_tot == 0:
             self.seg_mass.zero_()
@@ -204,11 +214,12 @@ class DeviceBatch:
                                                                   self.max_question_rows, self.max_segs_per_req)
             self.ws_prefill_mass = torch.empty(max(256, nbytes), dtype=torch.uint8, device=self.device)
         r = self._rows
-        self.ctx.sparse_prefill_mass(r(self.q_c), r(self.k_c), r(self.v_c), self.q_pos, self.slot_map, self.cu_q,
+        q, k_new, v_new, src_rows = self._qkv_args(fused)
+        self.ctx.sparse_prefill_mass(q, k_new, v_new, self.q_pos, self.slot_map, self.cu_q,
                                      self.max_q_per_req, min(self.max_question_rows, self.max_q_per_req), self.k_req,
                                      self.v_req, self.req_tab, self.segments, self.req_seg_off, self.n_requests,
                                      self.max_segs_per_req, self.n_tok, r(self.out), self.lse, self.seg_mass,
-                                     self.ws_prefill_mass)
+                                     self.ws_prefill_mass, src_rows=src_rows)
         return self.seg_mass
 
     def question_mass(self):
@@ -239,7 +250,7 @@ class DeviceBatch:
                                  self.n_tok, self.lse, self.pair_mass, self.self_mass, self.ws_pairs)
         return self.pair_mass, self.self_mass, self.pair_off
 
-    def sparse_prefill_pairs(self):
+    def sparse_prefill_pairs(self, fused: bool = False):
         """sparse_prefill and chunk_attention's sums (and the question's masses) in one call."""
         n_segs = self._mass_buffers()
         self._pair_buffers(n_segs)
@@ -252,11 +263,12 @@ class DeviceBatch:
             self.pair_mass.zero_(); self.self_mass.zero_(); self.seg_mass.zero_()
             return self.pair_mass, self.self_mass, self.pair_off
         r = self._rows
-        self.ctx.sparse_prefill_pairs(r(self.q_c), r(self.k_c), r(self.v_c), self.q_pos, self.slot_map, self.cu_q,
+        q, k_new, v_new, src_rows = self._qkv_args(fused)
+        self.ctx.sparse_prefill_pairs(q, k_new, v_new, self.q_pos, self.slot_map, self.cu_q,
                                       self.max_q_per_req, self.k_req, self.v_req, self.req_tab, self.segments,
                                       self.req_seg_off, self.n_requests, self.max_segs_per_req, self.n_tok,
                                       r(self.out), self.lse, self.seg_mass, self.pair_mass, self.self_mass,
-                                      self.ws_prefill_pairs)
+                                      self.ws_prefill_pairs, src_rows=src_rows)
         return self.pair_mass, self.self_mass, self.pair_off
 
     def step(self):

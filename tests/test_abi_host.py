@@ -144,12 +144,12 @@ def test_calls_reject_bad_arguments_before_launch(lib):
     # cc_sparse_prefill_pairs: missing pair_mass, missing lse, too few pairs, tiny workspace, no segments
     wp = lib.cc_sparse_prefill_pairs_workspace_bytes(h, 100, 3, 10, 10, 3)
     assert wp >= 10 * 8 * 3 * 4
-    pa = [h, good, good, good, good, good, good, 10, 10, good, good, 8, good, good, 3, good, 1, 3, 100]
+    pa = [h, good, good, good, None, good, good, good, 10, 10, good, good, 8, good, good, 3, good, 1, 3, 100]
     assert lib.cc_sparse_prefill_pairs(*pa, 6, good, good, good, None, good, good, wp, None) == -1
     assert lib.cc_sparse_prefill_pairs(*pa, 6, good, None, good, good, good, good, wp, None) == -1
     assert lib.cc_sparse_prefill_pairs(*pa, 2, good, good, good, good, good, good, wp, None) == -1
     assert lib.cc_sparse_prefill_pairs(*pa, 6, good, good, None, good, good, good, wp - 1, None) == -3
-    pa[14] = 0
+    pa[15] = 0
     assert lib.cc_sparse_prefill_pairs(*pa, 6, good, good, good, good, good, good, wp, None) == 0
     other = C.c_void_p(8192)
     # the dense operators of the layer: null tensors, x == y, hidden off the 16-byte grid, negative eps, no rows

@@ -29,7 +29,16 @@ def test_layer_loop_matches_the_oracle(preload):
     ref = [O.layer_loop(w, r, n_layers, window, [scale(l) for l in range(n_layers)],
                         scores=[scores[int(sg[W.SEG_TOK]): int(sg[W.SEG_TOK]) + int(sg[W.SEG_NTOK])].astype(np.float64)
                                 for sg in H.chunk_segments(w, r)]) for r in range(w.n_requests)]
-    loop = LayerLoop(w, n_layers, window, q_scale=scale, preload=preload, depth=2)
+    # every layer reuses the workload's one set of tensors; to make the layers differ, layer l's
+    # queries are the workload's times a power of two (exact in bf16), installed per layer
+    q0 = {}
+
+    def layer_inputs(l, b):
+        if "q" not in q0:
+            q0["q"] = b.q.clone()
+        torch.mul(q0["q"], scale(l), out=b.q)
+
+    loop = LayerLoop(w, n_layers, window, layer_inputs=layer_inputs, preload=preload, depth=2)
     recs = loop.run(scores=scores, keep_outputs=True)
     assert any(rec["stop_layer"][0] is not None for rec in recs), "the test should reach a stop"
     for l, rec in enumerate(recs):

@@ -136,6 +136,13 @@ def check_prefill_with_mass(w, b, k_ctx_of, requests=None, exact=True):
     bf = w.spec.dtype == "bf16"
     assert (m1 - m2).abs().max().item() <= (2e-2 if bf else 2e-4)
     check_question_mass_values(w, m2.cpu().numpy(), k_ctx_of, requests, exact)
+    if not b.projected:
+        # the same call on the per-token tensors through src_rows: every pass reads the same rows
+        m2, out2, lse2 = m2.clone(), b.out.clone(), b.lse.clone()
+        b.out.zero_(); b.lse.zero_(); b.seg_mass.fill_(float("nan"))
+        m3 = b.sparse_prefill_mass(fused=True)
+        torch.cuda.synchronize()
+        assert torch.equal(out2[:n], b.out[:n]) and torch.equal(lse2[:n], b.lse[:n]) and torch.equal(m2, m3)
 
 
 def check_chunk_attention(w, b, res):
@@ -162,6 +169,15 @@ def check_prefill_with_pairs(w, b, res, k_ctx_of, check_self=True):
     check_question_mass_values(w, b.seg_mass.cpu().numpy(), k_ctx_of)
     b.sparse_prefill_pairs(); torch.cuda.synchronize()                  # same workspace, same answer
     assert torch.equal(pair_again, b.pair_mass)
+    if not b.projected:
+        # and on the per-token tensors through src_rows
+        self_again, mass_again = b.self_mass.clone(), b.seg_mass.clone()
+        b.out.zero_(); b.lse.zero_(); b.seg_mass.fill_(float("nan")); b.pair_mass.fill_(float("nan"))
+        b.self_mass.fill_(float("nan"))
+        b.sparse_prefill_pairs(fused=True); torch.cuda.synchronize()
+        assert torch.equal(out1[:n], b.out[:n]) and torch.equal(lse1[:n], b.lse[:n])
+        assert torch.equal(pair_again, b.pair_mass) and torch.equal(mass_again, b.seg_mass)
+        assert torch.equal(self_again, b.self_mass)
 
 
 def check_pair_values(w, pair, self_w, pair_off, res, requests=None, check_self=True):
