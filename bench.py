@@ -124,7 +124,7 @@ def _gpu_request_state(w, batch, r):
                                                dtype=np.int64) for sg in segs]))
     idx = torch.as_tensor(mine, device=batch.k_req.device)
     k_pages = batch.k_req.index_select(0, idx).float().cpu().numpy()      # only this request's pages travel to the host
-    v_pages = batch.v_req.index_select(0, idx).float().cpu().numpy()
+    v_pages = batch.values_pool().index_select(0, idx).float().cpu().numpy()
     n_ctx = int(segs[-1][W.SEG_START] + segs[-1][W.SEG_NTOK])
     hkv, d = w.spec.n_kv_heads, w.spec.head_dim
     k = np.zeros((n_ctx, hkv, d)); v = np.zeros((n_ctx, hkv, d))

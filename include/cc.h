@@ -129,13 +129,20 @@ int cc_set_impl(cc_ctx* ctx, int impl);
  * destination may be the same allocation as long as the block ids differ.
  *   descs [n_instances] device; block tables device int32; max_tokens = max n_tokens (host).
  *   n_src_blocks / n_dst_blocks: pool sizes in blocks; a table entry outside them is skipped.
+ *   v_map [n_dst_blocks] device int32 or NULL.  If given, both V pools must be NULL and no value is
+ *   moved: for every page the call handles it records v_map[destination block] = source block,
+ *   i.e. "the values that go with the keys now in this block are still those of that stored
+ *   block" (values carry no position, so the stored ones are the right ones).  cc_sparse_prefill
+ *   and its variants take the map through cc_shared_values and copy a page's values only when one
+ *   of its tokens is recomputed (copy-on-write).  Entries of blocks the call does not handle are
+ *   left alone: the caller sets the map to -1 once, before the first call.
  * Sec. 3.4.3, Sec. 4 "RPE Management". */
 int cc_rope_shift(cc_ctx* ctx,
                   const void* k_src_pool, const void* v_src_pool, int32_t n_src_blocks,
                   void* k_dst_pool, void* v_dst_pool, int32_t n_dst_blocks,
                   const int32_t* src_block_tab, const int32_t* dst_block_tab,
                   const cc_shift_desc* descs, int32_t n_instances, int32_t max_tokens,
-                  void* stream);
+                  int32_t* v_map, void* stream);
 
 /* ---- (a') place keys that were stored WITHOUT rotation ---------------------------------------
  * The store variant the paper describes (Sec. 4 "RPE Management": the rotation is taken off
@@ -149,7 +156,7 @@ int cc_rope_place(cc_ctx* ctx,
                   void* k_dst_pool, void* v_dst_pool, int32_t n_dst_blocks,
                   const int32_t* src_block_tab, const int32_t* dst_block_tab,
                   const cc_shift_desc* descs, int32_t n_instances, int32_t max_tokens,
-                  void* stream);
+                  int32_t* v_map, void* stream);
 
 /* ---- (b) choose the tokens to recompute ---------------------------------------------------
  * For every chunk segment with logical_start > 0 and every token t (position p = start + t):
@@ -226,6 +233,21 @@ int cc_linear(cc_ctx* ctx, const void* x, const void* w, const void* residual, i
 int cc_gated_linear(cc_ctx* ctx, const void* x, const void* w_gate, const void* w_up, int32_t n_rows,
                     int32_t n_in, int32_t n_ffn, void* y, void* stream);
 
+/* ---- values that stay in the chunk store (copy-on-write) ------------------------------------
+ * Optional argument of cc_sparse_prefill and its variants (NULL: every page's values are in
+ * v_pool).  While v_map[b] >= 0, the values of the page whose KEYS sit in block b of k_pool are
+ * those of block v_map[b] of v_shared (cc_rope_shift writes such entries instead of copying V);
+ * otherwise they are in block b of v_pool.  Step 1 of the call (the write of the recomputed rows)
+ * copies a page's values from v_shared into block b of v_pool the first time it writes a row of
+ * that page, and sets v_map[b] = -1; step 2 reads every page's values from where the map says.
+ * v_shared is never written.  A host struct; the arrays it points at are device memory.
+ * Sec. 3.4.3 (only the recomputed tokens' K, V are new; Sec. 4: values need no re-positioning). */
+typedef struct cc_shared_values {
+  const void* v_shared;      /* pool of stored blocks, same block layout as v_pool               */
+  int32_t n_shared_blocks;   /* its size in blocks; a map entry outside it counts as -1          */
+  int32_t* v_map;            /* [n_blocks of k_pool / v_pool], read and updated by the call      */
+} cc_shared_values;
+
 /* ---- (c) partial prefill ------------------------------------------------------------------
  * For every row j < n_q_tot of the compact query list (requests delimited by cu_q):
  *   1. rotate k_new[j] to position q_pos[j] and write it, with v_new[j], into physical slot
@@ -243,6 +265,7 @@ int cc_gated_linear(cc_ctx* ctx, const void* x, const void* w_gate, const void* 
  *   max_q_per_req: max rows of one request (host scalar, sizes the launch).
  *   n_ctx_tokens: sum of n_tokens over all segments, or any upper bound of it (host scalar; sizes
  *   the key-tile plan kept in the workspace).
+ *   shared: see cc_shared_values (NULL: none).
  * Eq. (1), Sec. 3.4.3, Sec. 4 "Selective Token Recomputation". */
 size_t cc_sparse_prefill_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_tokens, int32_t n_segs);
 int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void* v_new,
@@ -251,7 +274,8 @@ int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void*
                       void* k_pool, void* v_pool, int32_t n_blocks, const int32_t* block_tab,
                       const cc_segment* segs, int32_t n_segs,
                       const int32_t* req_seg_off, int32_t n_requests, int32_t n_ctx_tokens,
-                      void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream);
+                      const cc_shared_values* shared, void* out, float* lse,
+                      void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- (c') cc_sparse_prefill for callers that cannot allocate ---------------------------------
  * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc: the
@@ -274,7 +298,7 @@ int cc_sparse_prefill_static(cc_ctx* ctx, const void* q, const void* k_new, cons
                              void* k_pool, void* v_pool, int32_t n_blocks, const int32_t* block_tab,
                              const cc_segment* segs, int32_t n_segs,
                              const int32_t* req_seg_off, int32_t n_requests, int32_t n_ctx_tokens,
-                             void* out, float* lse, void* stream);
+                             const cc_shared_values* shared, void* out, float* lse, void* stream);
 
 /* ---- (c'') partial prefill that also returns the question's attention to every chunk --------
  * cc_sparse_prefill (same steps, same out and lse, bit for bit) plus seg_mass as cc_question_mass
@@ -301,7 +325,8 @@ int cc_sparse_prefill_mass(cc_ctx* ctx, const void* q, const void* k_new, const 
                            void* k_pool, void* v_pool, int32_t n_blocks, const int32_t* block_tab,
                            const cc_segment* segs, int32_t n_segs,
                            const int32_t* req_seg_off, int32_t n_requests, int32_t max_segs_per_req,
-                           int32_t n_ctx_tokens, void* out, float* lse, float* seg_mass,
+                           int32_t n_ctx_tokens, const cc_shared_values* shared,
+                           void* out, float* lse, float* seg_mass,
                            void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- (c3) partial prefill that also returns the segment-to-segment attention sums -----------
@@ -328,7 +353,8 @@ int cc_sparse_prefill_pairs(cc_ctx* ctx, const void* q, const void* k_new, const
                             void* k_pool, void* v_pool, int32_t n_blocks, const int32_t* block_tab,
                             const cc_segment* segs, int32_t n_segs,
                             const int32_t* req_seg_off, int32_t n_requests, int32_t max_segs_per_req,
-                            int32_t n_ctx_tokens, int32_t n_pairs, void* out, float* lse,
+                            int32_t n_ctx_tokens, int32_t n_pairs, const cc_shared_values* shared,
+                            void* out, float* lse,
                             float* seg_mass, float* pair_mass, float* self_mass,
                             void* workspace, size_t workspace_bytes, void* stream);
 

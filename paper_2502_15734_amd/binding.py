@@ -59,8 +59,8 @@ def load_library() -> C.CDLL:
     lib.cc_last_error.restype = C.c_char_p
     lib.cc_set_impl.argtypes = [vp, C.c_int]
     lib.cc_set_impl.restype = C.c_int
-    lib.cc_rope_shift.argtypes = [vp, vp, vp, i32, vp, vp, i32, vp, vp, vp, i32, i32, vp]
-    lib.cc_rope_place.argtypes = [vp, vp, vp, i32, vp, vp, i32, vp, vp, vp, i32, i32, vp]
+    lib.cc_rope_shift.argtypes = [vp, vp, vp, i32, vp, vp, i32, vp, vp, vp, i32, i32, vp, vp]
+    lib.cc_rope_place.argtypes = [vp, vp, vp, i32, vp, vp, i32, vp, vp, vp, i32, i32, vp, vp]
     lib.cc_rope_place.restype = C.c_int
     lib.cc_rope_shift.restype = C.c_int
     lib.cc_select_workspace_bytes.argtypes = [vp, i32, i32]
@@ -77,10 +77,10 @@ def load_library() -> C.CDLL:
     lib.cc_sparse_prefill_workspace_bytes.argtypes = [vp, i32, i32]
     lib.cc_sparse_prefill_workspace_bytes.restype = sz
     lib.cc_sparse_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, vp, i32,
-                                      vp, i32, i32, vp, vp, vp, sz, vp]
+                                      vp, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.cc_sparse_prefill.restype = C.c_int
     lib.cc_sparse_prefill_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, vp, i32,
-                                             vp, i32, i32, vp, vp, vp]
+                                             vp, i32, i32, vp, vp, vp, vp]
     lib.cc_sparse_prefill_static.restype = C.c_int
     lib.cc_rms_norm.argtypes = [vp, vp, vp, C.c_float, i32, i32, vp, vp]
     lib.cc_rms_norm.restype = C.c_int
@@ -91,12 +91,12 @@ def load_library() -> C.CDLL:
     lib.cc_sparse_prefill_mass_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32]
     lib.cc_sparse_prefill_mass_workspace_bytes.restype = sz
     lib.cc_sparse_prefill_mass.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, vp, vp, i32, vp, vp, i32,
-                                           vp, i32, i32, i32, vp, vp, vp, vp, sz, vp]
+                                           vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.cc_sparse_prefill_mass.restype = C.c_int
     lib.cc_sparse_prefill_pairs_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32]
     lib.cc_sparse_prefill_pairs_workspace_bytes.restype = sz
     lib.cc_sparse_prefill_pairs.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, vp, i32,
-                                            vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+                                            vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.cc_sparse_prefill_pairs.restype = C.c_int
     lib.cc_scatter_kv.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, i32, vp]
     lib.cc_scatter_kv.restype = C.c_int
@@ -144,6 +144,19 @@ def load_library() -> C.CDLL:
     return lib
 
 
+class SharedValues(C.Structure):
+    """cc_shared_values: values that stay in the chunk store until a token of their page is recomputed."""
+    _fields_ = [("v_shared", C.c_void_p), ("n_shared_blocks", C.c_int32), ("v_map", C.c_void_p)]
+
+
+def _shared(shared):
+    """(v_shared pool, v_map) or None -> pointer to a cc_shared_values (kept alive by the caller's frame)."""
+    if shared is None:
+        return None
+    v_shared, v_map = shared
+    return C.byref(SharedValues(_ptr(v_shared), v_shared.shape[0], _ptr(v_map)))
+
+
 def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
     if t is None:
         return None
@@ -189,16 +202,17 @@ class Context:
         self._check(self._lib.cc_set_impl(self._h, impl))
 
     # -- cc_rope_shift ---------------------------------------------------------------------
-    def rope_shift(self, k_src, v_src, k_dst, v_dst, src_tab, dst_tab, descs, n_instances, max_tokens):
+    def rope_shift(self, k_src, v_src, k_dst, v_dst, src_tab, dst_tab, descs, n_instances, max_tokens, v_map=None):
+        """v_map: if given (v_src and v_dst None), values stay in the store and the map records where."""
         self._check(self._lib.cc_rope_shift(
             self._h, _ptr(k_src), _ptr(v_src), k_src.shape[0], _ptr(k_dst), _ptr(v_dst), k_dst.shape[0],
-            _ptr(src_tab), _ptr(dst_tab), _ptr(descs), n_instances, max_tokens, _stream()))
+            _ptr(src_tab), _ptr(dst_tab), _ptr(descs), n_instances, max_tokens, _ptr(v_map), _stream()))
 
-    def rope_place(self, k_src, v_src, k_dst, v_dst, src_tab, dst_tab, descs, n_instances, max_tokens):
+    def rope_place(self, k_src, v_src, k_dst, v_dst, src_tab, dst_tab, descs, n_instances, max_tokens, v_map=None):
         """cc_rope_shift for a store of unrotated keys: descs' delta_pos is the new position of token 0."""
         self._check(self._lib.cc_rope_place(
             self._h, _ptr(k_src), _ptr(v_src), k_src.shape[0], _ptr(k_dst), _ptr(v_dst), k_dst.shape[0],
-            _ptr(src_tab), _ptr(dst_tab), _ptr(descs), n_instances, max_tokens, _stream()))
+            _ptr(src_tab), _ptr(dst_tab), _ptr(descs), n_instances, max_tokens, _ptr(v_map), _stream()))
 
     # -- cc_select ---------------------------------------------------------------------------
     def select_workspace_bytes(self, n_tok: int, n_segs: int) -> int:
@@ -235,23 +249,27 @@ class Context:
         return int(self._lib.cc_sparse_prefill_workspace_bytes(self._h, n_ctx_tokens, n_segs))
 
     def sparse_prefill(self, q, k_new, v_new, q_pos, slot_map, cu_q, max_q_per_req, k_pool, v_pool,
-                       block_tab, segs, req_seg_off, n_requests, n_ctx_tokens, out, lse, workspace, src_rows=None):
-        """src_rows: row of q / k_new / v_new each list row reads (None: they are compact, row j = list row j)."""
+                       block_tab, segs, req_seg_off, n_requests, n_ctx_tokens, out, lse, workspace, src_rows=None,
+                       shared=None):
+        """src_rows: row of q / k_new / v_new each list row reads (None: they are compact, row j = list row j).
+        shared: (v_shared pool, v_map) for values that stay in the chunk store (cc_shared_values), or None."""
         n_q_tot = q.shape[0] if src_rows is None else src_rows.shape[0]
         self._check(self._lib.cc_sparse_prefill(
             self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(src_rows), _ptr(q_pos), _ptr(slot_map), _ptr(cu_q),
             n_q_tot, max_q_per_req, _ptr(k_pool), _ptr(v_pool), k_pool.shape[0], _ptr(block_tab),
-            _ptr(segs), segs.shape[0], _ptr(req_seg_off), n_requests, n_ctx_tokens, _ptr(out), _ptr(lse),
+            _ptr(segs), segs.shape[0], _ptr(req_seg_off), n_requests, n_ctx_tokens, _shared(shared), _ptr(out), _ptr(lse),
             _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
     def sparse_prefill_static(self, q, k_new, v_new, q_pos, slot_map, cu_q, max_q_per_req, k_pool, v_pool,
-                              block_tab, segs, req_seg_off, n_requests, n_ctx_tokens, out, lse, src_rows=None):
+                              block_tab, segs, req_seg_off, n_requests, n_ctx_tokens, out, lse, src_rows=None,
+                              shared=None):
         """cc_sparse_prefill without a workspace: the plan goes into the library's built-in scratch array."""
         n_q_tot = q.shape[0] if src_rows is None else src_rows.shape[0]
         self._check(self._lib.cc_sparse_prefill_static(
             self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(src_rows), _ptr(q_pos), _ptr(slot_map), _ptr(cu_q),
             n_q_tot, max_q_per_req, _ptr(k_pool), _ptr(v_pool), k_pool.shape[0], _ptr(block_tab),
-            _ptr(segs), segs.shape[0], _ptr(req_seg_off), n_requests, n_ctx_tokens, _ptr(out), _ptr(lse), _stream()))
+            _ptr(segs), segs.shape[0], _ptr(req_seg_off), n_requests, n_ctx_tokens, _shared(shared), _ptr(out),
+            _ptr(lse), _stream()))
 
     # -- the rest of a decoder layer for the chosen rows ---------------------------------------------
     def rms_norm(self, x, gain, eps, y):
@@ -274,13 +292,13 @@ class Context:
 
     def sparse_prefill_mass(self, q, k_new, v_new, q_pos, slot_map, cu_q, max_q_per_req, max_question_rows, k_pool,
                             v_pool, block_tab, segs, req_seg_off, n_requests, max_segs_per_req, n_ctx_tokens, out,
-                            lse, seg_mass, workspace, src_rows=None):
+                            lse, seg_mass, workspace, src_rows=None, shared=None):
         n_q_tot = q.shape[0] if src_rows is None else src_rows.shape[0]
         self._check(self._lib.cc_sparse_prefill_mass(
             self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(src_rows), _ptr(q_pos), _ptr(slot_map), _ptr(cu_q),
             n_q_tot, max_q_per_req, max_question_rows, _ptr(k_pool), _ptr(v_pool), k_pool.shape[0], _ptr(block_tab),
-            _ptr(segs), segs.shape[0], _ptr(req_seg_off), n_requests, max_segs_per_req, n_ctx_tokens, _ptr(out),
-            _ptr(lse), _ptr(seg_mass), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+            _ptr(segs), segs.shape[0], _ptr(req_seg_off), n_requests, max_segs_per_req, n_ctx_tokens, _shared(shared),
+            _ptr(out), _ptr(lse), _ptr(seg_mass), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
     def sparse_prefill_pairs_workspace_bytes(self, n_ctx_tokens, n_segs, n_q_tot, max_q_per_req, max_segs_per_req):
         return int(self._lib.cc_sparse_prefill_pairs_workspace_bytes(self._h, n_ctx_tokens, n_segs, n_q_tot,
@@ -288,12 +306,13 @@ class Context:
 
     def sparse_prefill_pairs(self, q, k_new, v_new, q_pos, slot_map, cu_q, max_q_per_req, k_pool, v_pool, block_tab,
                              segs, req_seg_off, n_requests, max_segs_per_req, n_ctx_tokens, out, lse, seg_mass,
-                             pair_mass, self_mass, workspace, src_rows=None):
+                             pair_mass, self_mass, workspace, src_rows=None, shared=None):
         n_q_tot = q.shape[0] if src_rows is None else src_rows.shape[0]
         self._check(self._lib.cc_sparse_prefill_pairs(
             self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(src_rows), _ptr(q_pos), _ptr(slot_map), _ptr(cu_q),
             n_q_tot, max_q_per_req, _ptr(k_pool), _ptr(v_pool), k_pool.shape[0], _ptr(block_tab), _ptr(segs), segs.shape[0],
-            _ptr(req_seg_off), n_requests, max_segs_per_req, n_ctx_tokens, pair_mass.shape[0], _ptr(out), _ptr(lse),
+            _ptr(req_seg_off), n_requests, max_segs_per_req, n_ctx_tokens, pair_mass.shape[0], _shared(shared),
+            _ptr(out), _ptr(lse),
             _ptr(seg_mass), _ptr(pair_mass), _ptr(self_mass), _ptr(workspace),
             workspace.numel() * workspace.element_size(), _stream()))
 

@@ -113,7 +113,8 @@ int cc_set_impl(cc_ctx* ctx, int impl) {
 static int rope_move(cc_ctx* ctx, const char* fn, bool absolute, const void* k_src_pool,
                      const void* v_src_pool, int32_t n_src_blocks, void* k_dst_pool, void* v_dst_pool,
                      int32_t n_dst_blocks, const int32_t* src_block_tab, const int32_t* dst_block_tab,
-                     const cc_shift_desc* descs, int32_t n_instances, int32_t max_tokens, void* stream) {
+                     const cc_shift_desc* descs, int32_t n_instances, int32_t max_tokens, int32_t* v_map,
+                     void* stream) {
   if (ctx == nullptr) return CC_ERR_INVALID_ARG;
   CC_REQUIRE(n_instances >= 0 && max_tokens >= 0, "negative count");
   CC_REQUIRE(n_instances <= 65535, "more than 65535 chunk instances in one call");
@@ -123,9 +124,10 @@ static int rope_move(cc_ctx* ctx, const char* fn, bool absolute, const void* k_s
   CC_REQUIRE(aligned16(k_src_pool) && aligned16(k_dst_pool) && aligned16(v_src_pool) && aligned16(v_dst_pool),
              "pools must be 16-byte aligned");
   CC_REQUIRE(n_src_blocks > 0 && n_dst_blocks > 0, "pool sizes must be positive");
+  CC_REQUIRE(v_map == nullptr || v_dst_pool == nullptr, "with a value map the values are not copied: pass no V pools");
   cc::launch_rope_shift(ctx, k_src_pool, v_src_pool, n_src_blocks, k_dst_pool, v_dst_pool,
                         n_dst_blocks, src_block_tab, dst_block_tab, descs, n_instances, max_tokens,
-                        absolute, static_cast<hipStream_t>(stream));
+                        absolute, v_map, static_cast<hipStream_t>(stream));
   return cc::check_launch(ctx, fn);
 }
 
@@ -133,18 +135,18 @@ int cc_rope_shift(cc_ctx* ctx, const void* k_src_pool, const void* v_src_pool, i
                   void* k_dst_pool, void* v_dst_pool, int32_t n_dst_blocks,
                   const int32_t* src_block_tab, const int32_t* dst_block_tab,
                   const cc_shift_desc* descs, int32_t n_instances, int32_t max_tokens,
-                  void* stream) {
+                  int32_t* v_map, void* stream) {
   return rope_move(ctx, "cc_rope_shift", false, k_src_pool, v_src_pool, n_src_blocks, k_dst_pool, v_dst_pool,
-                   n_dst_blocks, src_block_tab, dst_block_tab, descs, n_instances, max_tokens, stream);
+                   n_dst_blocks, src_block_tab, dst_block_tab, descs, n_instances, max_tokens, v_map, stream);
 }
 
 int cc_rope_place(cc_ctx* ctx, const void* k_src_pool, const void* v_src_pool, int32_t n_src_blocks,
                   void* k_dst_pool, void* v_dst_pool, int32_t n_dst_blocks,
                   const int32_t* src_block_tab, const int32_t* dst_block_tab,
                   const cc_shift_desc* descs, int32_t n_instances, int32_t max_tokens,
-                  void* stream) {
+                  int32_t* v_map, void* stream) {
   return rope_move(ctx, "cc_rope_place", true, k_src_pool, v_src_pool, n_src_blocks, k_dst_pool, v_dst_pool,
-                   n_dst_blocks, src_block_tab, dst_block_tab, descs, n_instances, max_tokens, stream);
+                   n_dst_blocks, src_block_tab, dst_block_tab, descs, n_instances, max_tokens, v_map, stream);
 }
 
 // upper bound on the number of 64-key tiles of n_tok tokens spread over n_segs segments
@@ -282,6 +284,21 @@ int cc_gated_linear(cc_ctx* ctx, const void* x, const void* w_gate, const void* 
   return cc::check_launch(ctx, fn);
 }
 
+// the caller's cc_shared_values (or NULL) as the launchers take it; false (error recorded) if it is malformed
+static bool value_source(cc_ctx* ctx, const char* fn, const cc_shared_values* shared, cc::ValueSource* vs) {
+  *vs = cc::ValueSource();
+  if (shared == nullptr) return true;
+  if (shared->v_shared == nullptr || shared->v_map == nullptr || shared->n_shared_blocks <= 0 ||
+      !aligned16(shared->v_shared)) {
+    fail(ctx, CC_ERR_INVALID_ARG, std::string(fn) + ": shared values need a 16-byte aligned pool, its size in blocks and a value map");
+    return false;
+  }
+  vs->v_shared = shared->v_shared;
+  vs->n_shared_blocks = shared->n_shared_blocks;
+  vs->v_map = shared->v_map;
+  return true;
+}
+
 size_t cc_sparse_prefill_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_tokens, int32_t n_segs) {
   if (ctx == nullptr || n_ctx_tokens < 0 || n_segs < 0) return 0;
   // queries are a subset of the context tokens, so n_ctx_tokens bounds the rows of the compact list
@@ -293,8 +310,8 @@ int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void*
                       const int32_t* cu_q, int32_t n_q_tot, int32_t max_q_per_req, void* k_pool, void* v_pool,
                       int32_t n_blocks, const int32_t* block_tab, const cc_segment* segs,
                       int32_t n_segs, const int32_t* req_seg_off, int32_t n_requests,
-                      int32_t n_ctx_tokens, void* out, float* lse, void* workspace,
-                      size_t workspace_bytes, void* stream) {
+                      int32_t n_ctx_tokens, const cc_shared_values* shared, void* out, float* lse,
+                      void* workspace, size_t workspace_bytes, void* stream) {
   static const char* fn = "cc_sparse_prefill";
   if (ctx == nullptr) return CC_ERR_INVALID_ARG;
   CC_REQUIRE(n_q_tot >= 0 && max_q_per_req >= 0 && n_segs >= 0 && n_requests >= 0 && n_ctx_tokens >= 0,
@@ -313,15 +330,17 @@ int cc_sparse_prefill(cc_ctx* ctx, const void* q, const void* k_new, const void*
   if (workspace_bytes < cc_sparse_prefill_workspace_bytes(ctx, n_ctx_tokens, n_segs))
     return fail(ctx, CC_ERR_WORKSPACE_TOO_SMALL,
                 "cc_sparse_prefill: workspace smaller than cc_sparse_prefill_workspace_bytes()");
+  cc::ValueSource vs;
+  if (!value_source(ctx, fn, shared, &vs)) return CC_ERR_INVALID_ARG;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_q_tot, k_pool, v_pool, n_blocks, src_rows, st);
+  cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_q_tot, k_pool, v_pool, n_blocks, src_rows, st, vs);
   if (ctx->impl != CC_IMPL_SCALAR && cc::attn_mfma_supported(ctx))
     cc::launch_attn_mfma(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks,
                          block_tab, segs, n_segs, req_seg_off, n_requests, out, lse, workspace,
-                         max_tiles_for(n_ctx_tokens, n_segs), src_rows, 0, st);
+                         max_tiles_for(n_ctx_tokens, n_segs), src_rows, 0, st, nullptr, vs);
   else
     cc::launch_attn_scalar(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks,
-                           block_tab, segs, req_seg_off, n_requests, out, lse, src_rows, 0, st);
+                           block_tab, segs, req_seg_off, n_requests, out, lse, src_rows, 0, st, vs);
   return cc::check_launch(ctx, fn);
 }
 
@@ -330,8 +349,8 @@ int cc_sparse_prefill_static(cc_ctx* ctx, const void* q, const void* k_new, cons
                              const int32_t* cu_q, int32_t n_q_tot, int32_t max_q_per_req, void* k_pool,
                              void* v_pool, int32_t n_blocks, const int32_t* block_tab,
                              const cc_segment* segs, int32_t n_segs, const int32_t* req_seg_off,
-                             int32_t n_requests, int32_t n_ctx_tokens, void* out, float* lse,
-                             void* stream) {
+                             int32_t n_requests, int32_t n_ctx_tokens, const cc_shared_values* shared,
+                             void* out, float* lse, void* stream) {
   static const char* fn = "cc_sparse_prefill_static";
   if (ctx == nullptr) return CC_ERR_INVALID_ARG;
   CC_REQUIRE(n_ctx_tokens >= 0 && n_segs >= 0, "negative count");
@@ -350,8 +369,8 @@ int cc_sparse_prefill_static(cc_ctx* ctx, const void* q, const void* k_new, cons
   // (the plan kernels rewrite every part of the scratch the attention kernels read, including the
   // flags that must start at zero, so nothing of an earlier call survives into this one)
   return cc_sparse_prefill(ctx, q, k_new, v_new, src_rows, q_pos, slot_map, cu_q, n_q_tot, max_q_per_req, k_pool,
-                           v_pool, n_blocks, block_tab, segs, n_segs, req_seg_off, n_requests, n_ctx_tokens, out,
-                           lse, ws, CC_STATIC_SCRATCH_BYTES, stream);
+                           v_pool, n_blocks, block_tab, segs, n_segs, req_seg_off, n_requests, n_ctx_tokens, shared,
+                           out, lse, ws, CC_STATIC_SCRATCH_BYTES, stream);
 }
 
 size_t cc_sparse_prefill_mass_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_tokens, int32_t n_segs,
@@ -369,7 +388,8 @@ int cc_sparse_prefill_mass(cc_ctx* ctx, const void* q, const void* k_new, const 
                            int32_t n_q_tot, int32_t max_q_per_req, int32_t max_question_rows,
                            void* k_pool, void* v_pool, int32_t n_blocks, const int32_t* block_tab,
                            const cc_segment* segs, int32_t n_segs, const int32_t* req_seg_off,
-                           int32_t n_requests, int32_t max_segs_per_req, int32_t n_ctx_tokens, void* out,
+                           int32_t n_requests, int32_t max_segs_per_req, int32_t n_ctx_tokens,
+                           const cc_shared_values* shared, void* out,
                            float* lse, float* seg_mass, void* workspace, size_t workspace_bytes,
                            void* stream) {
   static const char* fn = "cc_sparse_prefill_mass";
@@ -398,21 +418,23 @@ int cc_sparse_prefill_mass(cc_ctx* ctx, const void* q, const void* k_new, const 
                                                                max_question_rows, max_segs_per_req))
     return fail(ctx, CC_ERR_WORKSPACE_TOO_SMALL,
                 "cc_sparse_prefill_mass: workspace smaller than cc_sparse_prefill_mass_workspace_bytes()");
-  cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_q_tot, k_pool, v_pool, n_blocks, src_rows, st);
+  cc::ValueSource vs;
+  if (!value_source(ctx, fn, shared, &vs)) return CC_ERR_INVALID_ARG;
+  cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_q_tot, k_pool, v_pool, n_blocks, src_rows, st, vs);
   if (max_question_rows == 0) {                               // no question rows: plain attention, zero masses
     if (ctx->impl != CC_IMPL_SCALAR && cc::attn_mfma_supported(ctx))
       cc::launch_attn_mfma(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab,
                            segs, n_segs, req_seg_off, n_requests, out, lse, workspace,
-                           max_tiles_for(n_ctx_tokens, n_segs), src_rows, 0, st);
+                           max_tiles_for(n_ctx_tokens, n_segs), src_rows, 0, st, nullptr, vs);
     else
       cc::launch_attn_scalar(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab,
-                             segs, req_seg_off, n_requests, out, lse, src_rows, 0, st);
+                             segs, req_seg_off, n_requests, out, lse, src_rows, 0, st, vs);
     cc::launch_fill_zero(seg_mass, n_segs, st);
     return cc::check_launch(ctx, fn);
   }
   cc::launch_prefill_mass(ctx, q, src_rows, q_pos, cu_q, n_q_tot, max_q_per_req, max_question_rows, max_segs_per_req,
                           k_pool, v_pool, n_blocks, block_tab, segs, n_segs, req_seg_off, n_requests,
-                          n_ctx_tokens, out, lse, seg_mass, workspace, max_tiles_for(n_ctx_tokens, n_segs), st);
+                          n_ctx_tokens, out, lse, seg_mass, workspace, max_tiles_for(n_ctx_tokens, n_segs), st, vs);
   return cc::check_launch(ctx, fn);
 }
 
@@ -430,7 +452,8 @@ int cc_sparse_prefill_pairs(cc_ctx* ctx, const void* q, const void* k_new, const
                             int32_t n_q_tot, int32_t max_q_per_req, void* k_pool, void* v_pool,
                             int32_t n_blocks, const int32_t* block_tab, const cc_segment* segs,
                             int32_t n_segs, const int32_t* req_seg_off, int32_t n_requests,
-                            int32_t max_segs_per_req, int32_t n_ctx_tokens, int32_t n_pairs, void* out,
+                            int32_t max_segs_per_req, int32_t n_ctx_tokens, int32_t n_pairs,
+                            const cc_shared_values* shared, void* out,
                             float* lse, float* seg_mass, float* pair_mass, float* self_mass,
                             void* workspace, size_t workspace_bytes, void* stream) {
   static const char* fn = "cc_sparse_prefill_pairs";
@@ -463,12 +486,14 @@ int cc_sparse_prefill_pairs(cc_ctx* ctx, const void* q, const void* k_new, const
                                                                 max_q_per_req, max_segs_per_req))
     return fail(ctx, CC_ERR_WORKSPACE_TOO_SMALL,
                 "cc_sparse_prefill_pairs: workspace smaller than cc_sparse_prefill_pairs_workspace_bytes()");
-  cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_q_tot, k_pool, v_pool, n_blocks, src_rows, st);
+  cc::ValueSource vs;
+  if (!value_source(ctx, fn, shared, &vs)) return CC_ERR_INVALID_ARG;
+  cc::launch_rope_scatter(ctx, k_new, v_new, q_pos, slot_map, n_q_tot, k_pool, v_pool, n_blocks, src_rows, st, vs);
   cc::launch_fill_zero(pair_mass, n_pairs, st);               // pairs no row of the list falls into stay 0
   cc::launch_prefill_pairs(ctx, q, src_rows, q_pos, slot_map, cu_q, n_q_tot, max_q_per_req, max_segs_per_req, k_pool,
                            v_pool, n_blocks, block_tab, segs, n_segs, req_seg_off, n_requests, n_ctx_tokens,
                            out, lse, seg_mass, pair_mass, n_pairs, self_mass, workspace,
-                           max_tiles_for(n_ctx_tokens, n_segs), st);
+                           max_tiles_for(n_ctx_tokens, n_segs), st, vs);
   return cc::check_launch(ctx, fn);
 }
 

@@ -151,7 +151,8 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_v2_kernel(
     const int32_t* __restrict__ order, const int32_t* __restrict__ req_seg_off, int hq, int hkv,
     int n_sub, int n_tiles_x, InvFreq inv_freq, bf16_t* __restrict__ out, float* __restrict__ lse,
     int32_t* __restrict__ redo, const int32_t* __restrict__ q_map, int map_pos,
-    const int32_t* __restrict__ snap_index, float* __restrict__ cum, int s_max) {
+    const int32_t* __restrict__ snap_index, float* __restrict__ cum, int s_max,
+    const bf16_t* __restrict__ v_shared, int n_shared_blocks, const int32_t* __restrict__ v_map) {
   constexpr int TQ = 64;                    // query rows per workgroup
   constexpr int NT = 512 / QB;              // threads
   __shared__ uint4 lds_all[kBufs * kImage];
@@ -344,7 +345,10 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_v2_kernel(
   //   flag 2: the tile has padding slots or missing pages
   //   flag 4: the next tile belongs to another segment
   int win_base = 0;
-  int w_kpos0, w_nvalid, w_seg, w_seg_next, w_own, w_flags;
+  // w_own: block of the page this wavefront brings in (-1: none); w_vown: where that page's values
+  // are - the same block of v_pool, or (<= -2) block -2 - w_vown of v_shared while the value map
+  // still points there (copy-on-write pending)
+  int w_kpos0, w_nvalid, w_seg, w_seg_next, w_own, w_vown, w_flags;
   auto fill_window = [&](int base) __attribute__((always_inline)) {
     const int jl = min(base + lane, n_t - 1);
     const TileDesc v = fetch_desc(tiles, j_begin + jl, max_tiles);
@@ -354,6 +358,11 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_v2_kernel(
     asm volatile("" : "+v"(jn));                   // (a vector load, like the descriptor itself: see fetch_desc)
     w_seg_next = tiles[jn].seg;
     w_own = whead == 0 ? b0 : whead == 1 ? b1 : whead == 2 ? b2 : b3;
+    w_vown = w_own;
+    if (v_map != nullptr && w_own >= 0) {
+      const int m = v_map[w_own];
+      if (m >= 0 && m < n_shared_blocks) w_vown = -2 - m;
+    }
     const bool edge = v.nvalid < kTile || (b0 | b1 | b2 | b3) < 0;
     w_flags = ((edge || v.kpos0 + kTile - 1 > p_min) ? 1 : 0) | (edge ? 2 : 0) | (w_seg_next != v.seg ? 4 : 0);
   };
@@ -368,6 +377,8 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_v2_kernel(
   const size_t blk_bytes = static_cast<size_t>(hkv) * (kBlock * kD) * sizeof(bf16_t);
   const char* k_head = reinterpret_cast<const char*>(k_pool) + static_cast<size_t>(kvh) * (kBlock * kD * sizeof(bf16_t));
   const char* v_head = reinterpret_cast<const char*>(v_pool) + static_cast<size_t>(kvh) * (kBlock * kD * sizeof(bf16_t));
+  const char* v_head_shared = v_shared == nullptr ? v_head
+      : reinterpret_cast<const char*>(v_shared) + static_cast<size_t>(kvh) * (kBlock * kD * sizeof(bf16_t));
   const uint32_t k_voff0 = swap23(lane & 7) * (kD * 2) + (lane >> 3) * 16;
   const uint32_t k_voff1 = swap23(8 + (lane & 7)) * (kD * 2) + ((lane >> 3) ^ 1) * 16;
   const uint32_t v_voff = n * 32 + hh * 16;
@@ -380,10 +391,11 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_v2_kernel(
   const char* k_src = nullptr;                                                // page of the tile being loaded (scalar)
   const char* v_src = nullptr;
   uint32_t k_dst = 0, v_dst = 0;
-  auto dma_begin = [&](int own, int img_off) __attribute__((always_inline)) {
-    const size_t off = static_cast<size_t>(max(own, 0)) * blk_bytes;
-    k_src = k_head + off;
-    v_src = v_head + off;
+  auto dma_begin = [&](int l, int img_off) __attribute__((always_inline)) {          // l: the tile's lane in the window
+    const int own = __builtin_amdgcn_readlane(w_own, l), vown = __builtin_amdgcn_readlane(w_vown, l);
+    k_src = k_head + static_cast<size_t>(max(own, 0)) * blk_bytes;
+    v_src = vown <= -2 ? v_head_shared + static_cast<size_t>(-2 - vown) * blk_bytes
+                       : v_head + static_cast<size_t>(max(vown, 0)) * blk_bytes;
     k_dst = k_img + img_off;
     v_dst = v_img + img_off;
   };
@@ -402,7 +414,7 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_v2_kernel(
     else dma_two<2048, 3072>(v_voff, v_src, v_dst);
   };
   auto dma_tile = [&](int t, int img_off) __attribute__((always_inline)) {
-    dma_begin(__builtin_amdgcn_readlane(w_own, lane_of(t)), img_off);
+    dma_begin(lane_of(t), img_off);
 #pragma unroll
     for (int j = 0; j < 4; ++j) dma_k(j);
     dma_v(0);
@@ -535,7 +547,7 @@ __global__ __launch_bounds__(512 / QB, 1) void attn_v2_kernel(
       if (qb == QB - 1) {
         if (kk == 0) {
           f_far = __builtin_amdgcn_readlane(w_flags, lane_of(t + 2));
-          dma_begin(__builtin_amdgcn_readlane(w_own, lane_of(t + 3)), image_off(t + 3));
+          dma_begin(lane_of(t + 3), image_off(t + 3));
         }
         if (kk >= 1 && kk <= 4) dma_k(kk - 1);
         if (kk == 5) dma_v(0);
@@ -613,7 +625,7 @@ void launch_attn_v2(const cc_ctx* ctx, const void* q, const int32_t* q_pos, cons
                     int max_q_per_req, const void* k_pool, const void* v_pool, int n_blocks,
                     const Plan& pl, const int32_t* req_seg_off, int n_requests, void* out, float* lse,
                     int32_t* redo, const int32_t* q_map, int map_pos, const int32_t* snap_index, float* cum,
-                    int s_max, hipStream_t stream) {
+                    int s_max, hipStream_t stream, const ValueSource& vs) {
   const int hkv = ctx->cfg.n_kv_heads, n_sub = ctx->cfg.n_q_heads / hkv / 4;
   const int n_tiles = (max_q_per_req + 63) / 64;
   dim3 grid(hkv * n_sub * n_tiles, n_requests);
@@ -623,7 +635,8 @@ void launch_attn_v2(const cc_ctx* ctx, const void* q, const int32_t* q_pos, cons
   hipLaunchKernelGGL((attn_v2_kernel<QB>), grid, dim3(512 / QB), 0, stream, static_cast<const bf16_t*>(q), q_pos,
                      cu_q, static_cast<const bf16_t*>(k_pool), static_cast<const bf16_t*>(v_pool), n_blocks,
                      pl.tiles, pl.seg_tile_off, pl.max_tiles, pl.order, req_seg_off, ctx->cfg.n_q_heads, hkv,
-                     n_sub, n_tiles, ctx->inv_freq, static_cast<bf16_t*>(out), lse, redo, q_map, map_pos, snap_index, cum, s_max);
+                     n_sub, n_tiles, ctx->inv_freq, static_cast<bf16_t*>(out), lse, redo, q_map, map_pos, snap_index, cum, s_max,
+                     static_cast<const bf16_t*>(vs.v_shared), vs.n_shared_blocks, static_cast<const int32_t*>(vs.v_map));
 }
 
 }  // namespace cc

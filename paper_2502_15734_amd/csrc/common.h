@@ -34,11 +34,20 @@ int fail(cc_ctx* ctx, int status, const std::string& msg);
 int check_launch(cc_ctx* ctx, const char* what);
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Values that were not copied into the request's pages (copy-on-write, cc_shared_values): while
+// v_map[b] >= 0 the values of the page whose keys sit in block b of k_pool are those of block
+// v_map[b] of v_shared; otherwise they are in block b of v_pool.  v_map == NULL: always v_pool.
+struct ValueSource {
+  const void* v_shared = nullptr;
+  int n_shared_blocks = 0;
+  int32_t* v_map = nullptr;
+};
+
 // ---- launchers implemented in the .hip files -------------------------------------------------
 void launch_rope_shift(const cc_ctx* ctx, const void* k_src, const void* v_src, int n_src_blocks,
                        void* k_dst, void* v_dst, int n_dst_blocks, const int32_t* src_tab,
                        const int32_t* dst_tab, const cc_shift_desc* descs, int n_instances,
-                       int max_tokens, bool absolute, hipStream_t stream);
+                       int max_tokens, bool absolute, int32_t* v_map, hipStream_t stream);
 
 void launch_gather_rows(const void* src, int n_src_rows, const int32_t* row_idx, int n_rows,
                         size_t row_bytes, void* dst, hipStream_t stream);
@@ -65,12 +74,14 @@ void launch_topn(const cc_ctx* ctx, const float* mass, const int32_t* block_tab,
 
 void launch_rope_scatter(const cc_ctx* ctx, const void* k_new, const void* v_new,
                          const int32_t* q_pos, const int32_t* slot_map, int n_q_tot, void* k_pool,
-                         void* v_pool, int n_blocks, const int32_t* src_rows, hipStream_t stream);
+                         void* v_pool, int n_blocks, const int32_t* src_rows, hipStream_t stream,
+                         const ValueSource& vs = ValueSource());
 void launch_attn_scalar(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
                         int n_q_tot, int max_q_per_req, const void* k_pool, const void* v_pool,
                         int n_blocks, const int32_t* block_tab, const cc_segment* segs,
                         const int32_t* req_seg_off, int n_requests, void* out, float* lse,
-                        const int32_t* q_map, int map_pos, hipStream_t stream);
+                        const int32_t* q_map, int map_pos, hipStream_t stream,
+                        const ValueSource& vs = ValueSource());
 bool attn_mfma_supported(const cc_ctx* ctx);
 // By-product of the attention launch (optional): for rows with snap_index >= 0 the wide kernel
 // writes cum[snap row][head][segment's index in its request] = log-sum-exp over all keys up to the
@@ -88,7 +99,7 @@ void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, co
                       int n_blocks, const int32_t* block_tab, const cc_segment* segs, int n_segs,
                       const int32_t* req_seg_off, int n_requests, void* out, float* lse,
                       void* plan_ws, int max_tiles, const int32_t* q_map, int map_pos, hipStream_t stream,
-                      const AttnByProduct* by = nullptr);
+                      const AttnByProduct* by = nullptr, const ValueSource& vs = ValueSource());
 
 // attention mass of the question rows on every segment (focus.hip)
 void launch_fill_zero(float* p, int n, hipStream_t stream);
@@ -115,7 +126,8 @@ void launch_prefill_mass(const cc_ctx* ctx, const void* q, const int32_t* src_ro
                          int n_q_tot, int max_q_per_req, int max_question_rows, int s_max, const void* k_pool,
                          const void* v_pool, int n_blocks, const int32_t* block_tab, const cc_segment* segs,
                          int n_segs, const int32_t* req_seg_off, int n_requests, int n_ctx_tokens, void* out,
-                         float* lse, float* seg_mass, void* workspace, int max_tiles, hipStream_t stream);
+                         float* lse, float* seg_mass, void* workspace, int max_tiles, hipStream_t stream,
+                         const ValueSource& vs = ValueSource());
 
 // ... and with the whole segment-to-segment matrix (every row's cumulative sums are kept)
 size_t prefill_pairs_bytes(const cc_ctx* ctx, int n_ctx_tokens, int n_segs, int max_tiles, int n_q_tot,
@@ -125,7 +137,8 @@ void launch_prefill_pairs(const cc_ctx* ctx, const void* q, const int32_t* src_r
                           const void* v_pool, int n_blocks, const int32_t* block_tab, const cc_segment* segs,
                           int n_segs, const int32_t* req_seg_off, int n_requests, int n_ctx_tokens, void* out,
                           float* lse, float* seg_mass, float* pair_mass, int n_pairs, float* self_mass,
-                          void* workspace, int max_tiles, hipStream_t stream);
+                          void* workspace, int max_tiles, hipStream_t stream,
+                          const ValueSource& vs = ValueSource());
 
 // attention for head groups that are a multiple of 4: 64 query rows per wavefront (attn_mfma2.hip)
 bool attn_v2_supported(const cc_ctx* ctx);

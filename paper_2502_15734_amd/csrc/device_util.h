@@ -43,6 +43,19 @@ __device__ __forceinline__ void rot_cos_sin_fast(int pos, double inv_freq, float
   *s = __builtin_amdgcn_sinf(tf);
 }
 
+// Where the values of the page whose keys sit in block blk of the key pool are: block blk of v_own,
+// or, while the value map still points at a stored block (copy-on-write pending), that block of
+// v_shared.  Returns the first element of the block (all KV heads).
+template <typename T>
+__device__ __forceinline__ const T* value_block(const T* v_own, const T* v_shared, int n_shared_blocks,
+                                                const int32_t* v_map, int blk, size_t block_elems) {
+  if (v_map != nullptr) {
+    const int m = v_map[blk];
+    if (m >= 0 && m < n_shared_blocks) return v_shared + static_cast<size_t>(m) * block_elems;
+  }
+  return v_own + static_cast<size_t>(blk) * block_elems;
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

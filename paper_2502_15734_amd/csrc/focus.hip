@@ -652,7 +652,8 @@ void launch_prefill_mass(const cc_ctx* ctx, const void* q, const int32_t* src_ro
                          int n_q_tot, int max_q_per_req, int max_question_rows, int s_max, const void* k_pool,
                          const void* v_pool, int n_blocks, const int32_t* block_tab, const cc_segment* segs,
                          int n_segs, const int32_t* req_seg_off, int n_requests, int n_ctx_tokens, void* out,
-                         float* lse, float* seg_mass, void* workspace, int max_tiles, hipStream_t stream) {
+                         float* lse, float* seg_mass, void* workspace, int max_tiles, hipStream_t stream,
+                         const ValueSource& vs) {
   const int hq = ctx->cfg.n_q_heads, hkv = ctx->cfg.n_kv_heads;
   const size_t cap = static_cast<size_t>(n_requests) * max_question_rows;
   char* w = static_cast<char*>(workspace);
@@ -685,10 +686,10 @@ void launch_prefill_mass(const cc_ctx* ctx, const void* q, const int32_t* src_ro
     hipLaunchKernelGGL(fill_kernel, dim3(static_cast<unsigned>((n_cum + 255) / 256)), dim3(256), 0, stream, cum, n_cum,
                        -INFINITY);
     launch_attn_mfma(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab, segs,
-                     n_segs, req_seg_off, n_requests, out, lse, plan_ws, max_tiles, src_rows, 0, stream, &by);
+                     n_segs, req_seg_off, n_requests, out, lse, plan_ws, max_tiles, src_rows, 0, stream, &by, vs);
   } else {
     launch_attn_scalar(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab, segs,
-                       req_seg_off, n_requests, out, lse, src_rows, 0, stream);
+                       req_seg_off, n_requests, out, lse, src_rows, 0, stream, vs);
   }
   if (by.wide) {
     // rows the wide kernel flagged (normally none: every wavefront reads one flag and leaves)
@@ -729,7 +730,7 @@ void launch_prefill_pairs(const cc_ctx* ctx, const void* q, const int32_t* src_r
                           const void* v_pool, int n_blocks, const int32_t* block_tab, const cc_segment* segs,
                           int n_segs, const int32_t* req_seg_off, int n_requests, int n_ctx_tokens, void* out,
                           float* lse, float* seg_mass, float* pair_mass, int n_pairs, float* self_mass,
-                          void* workspace, int max_tiles, hipStream_t stream) {
+                          void* workspace, int max_tiles, hipStream_t stream, const ValueSource& vs) {
   const int hq = ctx->cfg.n_q_heads, hkv = ctx->cfg.n_kv_heads;
   char* w = static_cast<char*>(workspace);
   void* plan_ws = w;
@@ -747,10 +748,10 @@ void launch_prefill_pairs(const cc_ctx* ctx, const void* q, const int32_t* src_r
     hipLaunchKernelGGL(fill_kernel, dim3(static_cast<unsigned>((n_cum + 255) / 256)), dim3(256), 0, stream, cum, n_cum,
                        -INFINITY);
     launch_attn_mfma(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab, segs,
-                     n_segs, req_seg_off, n_requests, out, lse, plan_ws, max_tiles, src_rows, 0, stream, &by);
+                     n_segs, req_seg_off, n_requests, out, lse, plan_ws, max_tiles, src_rows, 0, stream, &by, vs);
   } else {
     launch_attn_scalar(ctx, q, q_pos, cu_q, n_q_tot, max_q_per_req, k_pool, v_pool, n_blocks, block_tab, segs,
-                       req_seg_off, n_requests, out, lse, src_rows, 0, stream);
+                       req_seg_off, n_requests, out, lse, src_rows, 0, stream, vs);
   }
   const bool bf = ctx->cfg.dtype == CC_BF16;
   const int d = ctx->cfg.head_dim;

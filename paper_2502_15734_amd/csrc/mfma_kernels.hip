@@ -42,7 +42,9 @@ namespace {
 template <int NT, bool WITH_V>
 __device__ __forceinline__ void stage_direct(uint4* lds, const bf16_t* __restrict__ k_pool,
                                              const bf16_t* __restrict__ v_pool, int n_blocks,
-                                             const TileDesc& d, int hkv, int kvh, int tid) {
+                                             const TileDesc& d, int hkv, int kvh, int tid,
+                                             const bf16_t* __restrict__ v_shared, int n_shared_blocks,
+                                             const int32_t* __restrict__ v_map) {
   const int nvalid = d.nvalid;
   constexpr int kPieces = WITH_V ? 2048 : 1024;
 #pragma unroll 4
@@ -59,7 +61,9 @@ __device__ __forceinline__ void stage_direct(uint4* lds, const bf16_t* __restric
       if (!is_v) {
         if ((cc_ >> 4) < nv) val = *reinterpret_cast<const uint4*>(k_pool + off);
       } else {
-        val = *reinterpret_cast<const uint4*>(v_pool + off);
+        const bf16_t* vb = value_block<bf16_t>(v_pool, v_shared, n_shared_blocks, v_map, blk,
+                                               static_cast<size_t>(hkv) * (kBlock * kD));
+        val = *reinterpret_cast<const uint4*>(vb + static_cast<size_t>(kvh) * (kBlock * kD) + cc_ * 8);
         if (nv < kBlock) val = zero_pad_slots(val, cc_ & 1, nv);
       }
     }
@@ -79,7 +83,7 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
     const int32_t* __restrict__ order, const cc_segment* __restrict__ segs, const int32_t* __restrict__ req_seg_off, int hq, int hkv,
     int n_tiles_x, InvFreq inv_freq, bf16_t* __restrict__ out, float* __restrict__ lse,
     float* __restrict__ mass, const int32_t* __restrict__ redo, const int32_t* __restrict__ q_map,
-    int map_pos) {
+    int map_pos, const bf16_t* __restrict__ v_shared, int n_shared_blocks, const int32_t* __restrict__ v_map) {
   constexpr int NT = 64 * G;
   constexpr int TQ = 32 * QB;                       // query tokens per workgroup
   constexpr bool kPrefetch = NT >= 256;
@@ -339,13 +343,14 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
   auto usable = [&](const TileDesc& d, int j) { return j < j_end && uniform(d.kpos0) <= p_max; };
 
   Stager<kPrefetch ? NT : 256, !SCORE> stg;
-  if constexpr (kPrefetch) stg.init(k_pool, v_pool, n_blocks, hkv, kvh, tid);
+  if constexpr (kPrefetch) stg.init(k_pool, v_pool, n_blocks, hkv, kvh, tid, v_shared, n_shared_blocks, v_map);
   auto stage_load = [&](const TileDesc& d) {            // global -> registers
     if constexpr (kPrefetch) stg.load(d);
   };
   auto stage_store = [&](const TileDesc& d, int b_) {   // registers (or global) -> LDS image b_
     if constexpr (kPrefetch) stg.store(lds_all + b_ * kImage);
-    else stage_direct<NT, !SCORE>(lds_all + b_ * kImage, k_pool, v_pool, n_blocks, d, hkv, kvh, tid);
+    else stage_direct<NT, !SCORE>(lds_all + b_ * kImage, k_pool, v_pool, n_blocks, d, hkv, kvh, tid, v_shared,
+                                  n_shared_blocks, v_map);
   };
 
   int j = j_begin;
@@ -617,14 +622,15 @@ void launch_attn_g(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const
                    int max_q_per_req, const void* k_pool, const void* v_pool, int n_blocks,
                    const Plan& pl, const cc_segment* segs, const int32_t* req_seg_off,
                    int n_requests, void* out, float* lse, const int32_t* redo, const int32_t* q_map,
-                   int map_pos, hipStream_t stream) {
+                   int map_pos, hipStream_t stream, const ValueSource& vs) {
   const int hkv = ctx->cfg.n_kv_heads, n_tiles = (max_q_per_req + 32 * kAttnQB - 1) / (32 * kAttnQB);
   dim3 grid(hkv * n_tiles, n_requests);
   hipLaunchKernelGGL((sparse_qk_kernel<G, false, kAttnQB>), grid, dim3(64 * G), 0, stream,
                      static_cast<const bf16_t*>(q), q_pos, cu_q, static_cast<const bf16_t*>(k_pool),
                      static_cast<const bf16_t*>(v_pool), n_blocks, pl.tiles, pl.seg_tile_off, pl.max_tiles,
                      pl.order, segs, req_seg_off, ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq,
-                     static_cast<bf16_t*>(out), lse, static_cast<float*>(nullptr), redo, q_map, map_pos);
+                     static_cast<bf16_t*>(out), lse, static_cast<float*>(nullptr), redo, q_map, map_pos,
+                     static_cast<const bf16_t*>(vs.v_shared), vs.n_shared_blocks, static_cast<const int32_t*>(vs.v_map));
 }
 
 template <int G>
@@ -639,7 +645,8 @@ void launch_score_g(const cc_ctx* ctx, const void* q, const void* k_pool, int n_
                      static_cast<const bf16_t*>(nullptr), n_blocks, pl.tiles, pl.seg_tile_off, pl.max_tiles,
                      pl.order, segs, req_seg_off, ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq,
                      static_cast<bf16_t*>(nullptr), static_cast<float*>(nullptr), mass, redo,
-                     static_cast<const int32_t*>(nullptr), 0);
+                     static_cast<const int32_t*>(nullptr), 0, static_cast<const bf16_t*>(nullptr), 0,
+                     static_cast<const int32_t*>(nullptr));
 }
 
 bool group_supported(const cc_ctx* ctx) {
@@ -699,7 +706,7 @@ void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, co
                       int n_blocks, const int32_t* block_tab, const cc_segment* segs, int n_segs,
                       const int32_t* req_seg_off, int n_requests, void* out, float* lse,
                       void* plan_ws, int max_tiles, const int32_t* q_map, int map_pos, hipStream_t stream,
-                      const AttnByProduct* by) {
+                      const AttnByProduct* by, const ValueSource& vs) {
   // Wide kernel first where the head group allows it; the narrow kernel then redoes the 64-row
   // tiles the wide one flagged (normally none: its workgroups read one flag and exit).
   // (a grid too small to give every compute unit a wide workgroup runs faster on the narrow
@@ -712,13 +719,13 @@ void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, co
   if (wide)
     launch_attn_v2(ctx, q, q_pos, cu_q, max_q_per_req, k_pool, v_pool, n_blocks, pl, req_seg_off, n_requests,
                    out, lse, pl.redo, q_map, map_pos, by != nullptr ? by->snap_index : nullptr,
-                   by != nullptr ? by->cum : nullptr, by != nullptr ? by->s_max : 0, stream);
+                   by != nullptr ? by->cum : nullptr, by != nullptr ? by->s_max : 0, stream, vs);
   if (by != nullptr) {
     by->wide = wide;
     by->redo = pl.redo;
   }
   const int32_t* redo = pl.redo;
-#define CC_ARGS ctx, q, q_pos, cu_q, max_q_per_req, k_pool, v_pool, n_blocks, pl, segs, req_seg_off, n_requests, out, lse, redo, q_map, map_pos, stream
+#define CC_ARGS ctx, q, q_pos, cu_q, max_q_per_req, k_pool, v_pool, n_blocks, pl, segs, req_seg_off, n_requests, out, lse, redo, q_map, map_pos, stream, vs
   switch (ctx->cfg.n_q_heads / ctx->cfg.n_kv_heads) {
     case 1: launch_attn_g<1>(CC_ARGS); break;
     case 2: launch_attn_g<2>(CC_ARGS); break;

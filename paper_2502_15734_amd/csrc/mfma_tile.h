@@ -96,17 +96,33 @@ struct Stager {
   uint4 reg[PER];
   const bf16_t* k_src;   // pool + head offset + this thread's piece
   const bf16_t* v_src;
+  const bf16_t* v_src_shared;   // the same piece of a block of the shared value pool
+  const int32_t* v_map;         // see value_block()
   size_t blk_stride;     // elements per block (all heads)
-  int n_blocks, in_page, pg0;
+  int n_blocks, n_shared_blocks, in_page, pg0;
 
   __device__ __forceinline__ void init(const bf16_t* k_pool, const bf16_t* v_pool, int n_blocks_,
-                                       int hkv, int kvh, int tid) {
+                                       int hkv, int kvh, int tid, const bf16_t* v_shared = nullptr,
+                                       int n_shared_blocks_ = 0, const int32_t* v_map_ = nullptr) {
+    v_map = v_map_;
+    n_shared_blocks = n_shared_blocks_;
+    v_src_shared = (WITH_V && v_shared != nullptr)
+                       ? v_shared + static_cast<size_t>(kvh) * (kBlock * kD) + (tid & 255) * 8 : nullptr;
     in_page = tid & 255;
     pg0 = NT == 512 ? uniform(tid >> 8) * 2 : 0;             // first page this thread stages
     k_src = k_pool + static_cast<size_t>(kvh) * (kBlock * kD) + in_page * 8;
     v_src = WITH_V ? v_pool + static_cast<size_t>(kvh) * (kBlock * kD) + in_page * 8 : nullptr;
     blk_stride = static_cast<size_t>(hkv) * (kBlock * kD);
     n_blocks = n_blocks_;
+  }
+
+  // this thread's piece of the values that belong to key block blk (a valid block id)
+  __device__ __forceinline__ const bf16_t* value_piece(int blk) const {
+    if (v_map != nullptr) {
+      const int m = uniform(v_map[blk]);
+      if (m >= 0 && m < n_shared_blocks) return v_src_shared + static_cast<size_t>(m) * blk_stride;
+    }
+    return v_src + static_cast<size_t>(blk) * blk_stride;
   }
 
   __device__ __forceinline__ void load(const TileDesc& d) {
@@ -123,7 +139,7 @@ struct Stager {
       for (int j = 0; j < kPagesPerThread; ++j) {
         reg[j] = *reinterpret_cast<const uint4*>(k_src + static_cast<size_t>(blk[j]) * blk_stride);
         if constexpr (WITH_V)
-          reg[kPagesPerThread + j] = *reinterpret_cast<const uint4*>(v_src + static_cast<size_t>(blk[j]) * blk_stride);
+          reg[kPagesPerThread + j] = *reinterpret_cast<const uint4*>(value_piece(blk[j]));
       }
       return;
     }
@@ -137,7 +153,7 @@ struct Stager {
         if ((in_page >> 4) < nv)                             // token slot of this K piece
           kv = *reinterpret_cast<const uint4*>(k_src + static_cast<size_t>(blk[j]) * blk_stride);
         if constexpr (WITH_V) {
-          vv = *reinterpret_cast<const uint4*>(v_src + static_cast<size_t>(blk[j]) * blk_stride);
+          vv = *reinterpret_cast<const uint4*>(value_piece(blk[j]));
           if (nv < kBlock) vv = zero_pad_slots(vv, in_page & 1, nv);
         }
       }
@@ -205,7 +221,7 @@ void launch_attn_v2(const cc_ctx* ctx, const void* q, const int32_t* q_pos, cons
                     int max_q_per_req, const void* k_pool, const void* v_pool, int n_blocks,
                     const Plan& pl, const int32_t* req_seg_off, int n_requests, void* out, float* lse,
                     int32_t* redo, const int32_t* q_map, int map_pos, const int32_t* snap_index, float* cum,
-                    int s_max, hipStream_t stream);
+                    int s_max, hipStream_t stream, const ValueSource& vs);
 
 // The wide score kernel (128 tokens per wavefront, no softmax reference) flags 64-row granules of
 // the per-token tensors whose sums left the safe range; the narrow kernel redoes them.

@@ -49,7 +49,8 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void rope_scatter_kernel(
     const T* __restrict__ k_new, const T* __restrict__ v_new, const int32_t* __restrict__ q_pos,
     const int32_t* __restrict__ slot_map, int n_q_tot, int hkv, InvFreq inv_freq,
-    T* __restrict__ k_pool, T* __restrict__ v_pool, int n_blocks, const int32_t* __restrict__ src_rows) {
+    T* __restrict__ k_pool, T* __restrict__ v_pool, int n_blocks, const int32_t* __restrict__ src_rows,
+    const T* __restrict__ v_shared, int n_shared_blocks, int32_t* __restrict__ v_map) {
   // slots of rows base-1 .. base+kScatterRows+14: the row before the first candidate (is it the same
   // block?) and the 15 rows a run starting at the last candidate can still cover; -1 = no row /
   // invalid slot
@@ -96,15 +97,22 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(
       *reinterpret_cast<uint4*>(ko) = *reinterpret_cast<uint4*>(ox);
       *reinterpret_cast<uint4*>(ko + D / 2) = *reinterpret_cast<uint4*>(oy);
     }
-    // V: one (head, dim) row of 16 slots per thread and step
+    // V: one (head, dim) row of 16 slots per thread and step.  The rows that are patched come
+    // from the block that holds the page's values now: the request's own block, or - the first
+    // time a token of the page is recomputed - the stored block the value map still points at
+    // (copy-on-write; the map entry is cleared once the whole block has been written).
     constexpr int kVec = kBlock * sizeof(T) / 16;          // 16-byte vectors per row
+    const size_t block_elems = static_cast<size_t>(hkv) * D * kBlock;
+    const T* v_from = value_block<T>(v_pool, v_shared, n_shared_blocks, v_map, blk, block_elems);
+    const bool pending = v_from != v_pool + static_cast<size_t>(blk) * block_elems;
     for (int idx = tid; idx < hkv * D; idx += 256) {
       const int h = idx / D, dcol = idx % D;
       uint4* rowp = reinterpret_cast<uint4*>(v_pool + ((static_cast<size_t>(blk) * hkv + h) * D + dcol) * kBlock);
+      const uint4* fromp = reinterpret_cast<const uint4*>(v_from + (static_cast<size_t>(h) * D + dcol) * kBlock);
       T e[kBlock];
       if (n_run < kBlock) {
 #pragma unroll
-        for (int v = 0; v < kVec; ++v) reinterpret_cast<uint4*>(e)[v] = rowp[v];
+        for (int v = 0; v < kVec; ++v) reinterpret_cast<uint4*>(e)[v] = fromp[v];
       }
       for (int t = 0; t < n_run; ++t) {
         const T val = v_new[(static_cast<size_t>(src_rows != nullptr ? src_rows[j0 + t] : j0 + t) * hkv + h) * D + dcol];
@@ -115,19 +123,25 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(
 #pragma unroll
       for (int v = 0; v < kVec; ++v) rowp[v] = reinterpret_cast<uint4*>(e)[v];
     }
+    if (pending) {                       // (workgroup-uniform)
+      __syncthreads();                   // every thread has looked the block up
+      if (tid == 0) v_map[blk] = -1;
+    }
   }
 }
 
 void launch_rope_scatter(const cc_ctx* ctx, const void* k_new, const void* v_new,
                          const int32_t* q_pos, const int32_t* slot_map, int n_q_tot, void* k_pool,
-                         void* v_pool, int n_blocks, const int32_t* src_rows, hipStream_t stream) {
+                         void* v_pool, int n_blocks, const int32_t* src_rows, hipStream_t stream,
+                         const ValueSource& vs) {
   if (n_q_tot <= 0) return;
   const bool bf = ctx->cfg.dtype == CC_BF16;
   const int d = ctx->cfg.head_dim, hkv = ctx->cfg.n_kv_heads;
 #define CC_LAUNCH(T, D)                                                                          \
   hipLaunchKernelGGL((rope_scatter_kernel<T, D>), dim3((n_q_tot + kScatterRows - 1) / kScatterRows), dim3(256), 0, stream,           \
                      static_cast<const T*>(k_new), static_cast<const T*>(v_new), q_pos, slot_map, \
-                     n_q_tot, hkv, ctx->inv_freq, static_cast<T*>(k_pool), static_cast<T*>(v_pool), n_blocks, src_rows)
+                     n_q_tot, hkv, ctx->inv_freq, static_cast<T*>(k_pool), static_cast<T*>(v_pool), n_blocks, src_rows, \
+                     static_cast<const T*>(vs.v_shared), vs.n_shared_blocks, vs.v_map)
   if (bf && d == 128) CC_LAUNCH(bf16_t, 128);
   else if (bf && d == 64) CC_LAUNCH(bf16_t, 64);
   else if (!bf && d == 128) CC_LAUNCH(float, 128);
@@ -143,7 +157,8 @@ __global__ __launch_bounds__(64) void attn_scalar_kernel(
     int n_requests, const T* __restrict__ k_pool, const T* __restrict__ v_pool, int n_blocks,
     const int32_t* __restrict__ block_tab, const cc_segment* __restrict__ segs,
     const int32_t* __restrict__ req_seg_off, int hq, int hkv, InvFreq inv_freq,
-    T* __restrict__ out, float* __restrict__ lse, const int32_t* __restrict__ q_map, int map_pos) {
+    T* __restrict__ out, float* __restrict__ lse, const int32_t* __restrict__ q_map, int map_pos,
+    const T* __restrict__ v_shared, int n_shared_blocks, const int32_t* __restrict__ v_map) {
   const int j = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
   int r = 0;
   while (r + 1 < n_requests && cu_q[r + 1] <= j) ++r;
@@ -182,7 +197,8 @@ __global__ __launch_bounds__(64) void attn_scalar_kernel(
       const float e = expf(logit - m);
       z += e;
       if (own) {
-        const T* vp = v_pool + bh * D * kBlock + tk % kBlock;
+        const T* vp = value_block<T>(v_pool, v_shared, n_shared_blocks, v_map, blk, static_cast<size_t>(hkv) * D * kBlock) +
+                      static_cast<size_t>(kvh) * D * kBlock + tk % kBlock;
         ox += e * to_float(vp[static_cast<size_t>(lane) * kBlock]);
         oy += e * to_float(vp[static_cast<size_t>(lane + D / 2) * kBlock]);
       }
@@ -200,7 +216,7 @@ void launch_attn_scalar(const cc_ctx* ctx, const void* q, const int32_t* q_pos, 
                         int n_q_tot, int max_q_per_req, const void* k_pool, const void* v_pool,
                         int n_blocks, const int32_t* block_tab, const cc_segment* segs,
                         const int32_t* req_seg_off, int n_requests, void* out, float* lse,
-                        const int32_t* q_map, int map_pos, hipStream_t stream) {
+                        const int32_t* q_map, int map_pos, hipStream_t stream, const ValueSource& vs) {
   (void)max_q_per_req;
   if (n_q_tot <= 0) return;
   const bool bf = ctx->cfg.dtype == CC_BF16;
@@ -209,7 +225,8 @@ void launch_attn_scalar(const cc_ctx* ctx, const void* q, const int32_t* q_pos, 
   hipLaunchKernelGGL((attn_scalar_kernel<T, D>), dim3(n_q_tot, hq), dim3(64), 0, stream,        \
                      static_cast<const T*>(q), q_pos, cu_q, n_requests,                         \
                      static_cast<const T*>(k_pool), static_cast<const T*>(v_pool), n_blocks,    \
-                     block_tab, segs, req_seg_off, hq, hkv, ctx->inv_freq, static_cast<T*>(out), lse, q_map, map_pos)
+                     block_tab, segs, req_seg_off, hq, hkv, ctx->inv_freq, static_cast<T*>(out), lse, q_map, map_pos, \
+                     static_cast<const T*>(vs.v_shared), vs.n_shared_blocks, vs.v_map)
   if (bf && d == 128) CC_LAUNCH(bf16_t, 128);
   else if (bf && d == 64) CC_LAUNCH(bf16_t, 64);
   else if (!bf && d == 128) CC_LAUNCH(float, 128);

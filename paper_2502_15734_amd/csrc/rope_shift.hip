@@ -32,7 +32,7 @@ __global__ __launch_bounds__(256) void rope_shift_kernel(
     const T* __restrict__ k_src, const T* __restrict__ v_src, int n_src_blocks,
     T* __restrict__ k_dst, T* __restrict__ v_dst, int n_dst_blocks,
     const int32_t* __restrict__ src_tab, const int32_t* __restrict__ dst_tab,
-    const cc_shift_desc* __restrict__ descs, int hkv, InvFreq inv_freq) {
+    const cc_shift_desc* __restrict__ descs, int hkv, InvFreq inv_freq, int32_t* __restrict__ v_map) {
   constexpr int N = Vec16<T>::N;          // elements per 16-byte vector
   constexpr int UPR = (D / 2) / N;        // vector pairs per (head, token) row
   static_assert(256 % UPR == 0, "a lane must keep its pair group across iterations");
@@ -55,7 +55,10 @@ __global__ __launch_bounds__(256) void rope_shift_kernel(
   const int turn = ABSOLUTE ? dsc.delta_pos + page * kBlock + (tid / UPR) % kBlock : dsc.delta_pos;
   // values carry no position: plain block copy.  Its first loads go out before the trigonometry.
   constexpr int UV = 8;                   // 16-byte loads of a lane in flight
-  const bool has_v = v_src != nullptr && v_dst != nullptr;
+  // (with a value map the values stay where they are: the map records which stored block holds
+  //  the values of the page whose keys now sit in block db)
+  const bool has_v = v_map == nullptr && v_src != nullptr && v_dst != nullptr;
+  if (v_map != nullptr && threadIdx.x == 0) v_map[db] = sb;
   const vec16* vs = reinterpret_cast<const vec16*>(v_src + sb * page_elems);
   const int n_vec = static_cast<int>(page_elems / N);
   vec16 tv[UV];
@@ -129,21 +132,21 @@ template <typename T, int D, bool ABSOLUTE>
 static void launch_t(const cc_ctx* ctx, const void* k_src, const void* v_src, int n_src_blocks,
                      void* k_dst, void* v_dst, int n_dst_blocks, const int32_t* src_tab,
                      const int32_t* dst_tab, const cc_shift_desc* descs, int n_instances,
-                     int max_tokens, hipStream_t stream) {
+                     int max_tokens, int32_t* v_map, hipStream_t stream) {
   dim3 grid((max_tokens + kBlock - 1) / kBlock, n_instances);
   hipLaunchKernelGGL((rope_shift_kernel<T, D, ABSOLUTE>), grid, dim3(256), 0, stream,
                      static_cast<const T*>(k_src), static_cast<const T*>(v_src), n_src_blocks,
                      static_cast<T*>(k_dst), static_cast<T*>(v_dst), n_dst_blocks, src_tab, dst_tab,
-                     descs, ctx->cfg.n_kv_heads, ctx->inv_freq);
+                     descs, ctx->cfg.n_kv_heads, ctx->inv_freq, v_map);
 }
 
 void launch_rope_shift(const cc_ctx* ctx, const void* k_src, const void* v_src, int n_src_blocks,
                        void* k_dst, void* v_dst, int n_dst_blocks, const int32_t* src_tab,
                        const int32_t* dst_tab, const cc_shift_desc* descs, int n_instances,
-                       int max_tokens, bool absolute, hipStream_t stream) {
+                       int max_tokens, bool absolute, int32_t* v_map, hipStream_t stream) {
   const bool bf = ctx->cfg.dtype == CC_BF16;
   const int d = ctx->cfg.head_dim;
-#define CC_ARGS ctx, k_src, v_src, n_src_blocks, k_dst, v_dst, n_dst_blocks, src_tab, dst_tab, descs, n_instances, max_tokens, stream
+#define CC_ARGS ctx, k_src, v_src, n_src_blocks, k_dst, v_dst, n_dst_blocks, src_tab, dst_tab, descs, n_instances, max_tokens, v_map, stream
   if (absolute) {
     if (bf && d == 128) launch_t<bf16_t, 128, true>(CC_ARGS);
     else if (bf && d == 64) launch_t<bf16_t, 64, true>(CC_ARGS);

@@ -75,8 +75,10 @@ class DecoderLoop:
             self.pre[0].acquire(l); self.pre[1].acquire(l)
             b.k_store, b.v_store = self.slots[l % len(self.slots)]
         b.rope_shift()
-        if self.pre is not None:                               # the store slot is free once the shift has read it
-            self.pre[0].release(l); self.pre[1].release(l)
+        if self.pre is not None:                               # the key slot is free once the shift has read it;
+            self.pre[0].release(l)                             # the values are read by the attention, unless copied
+            if not b.cow:
+                self.pre[1].release(l)
 
     def _drop_rows(self, new_budget):
         """New budgets: rebuild the row list (same scores, same order) and compact the hidden states."""
@@ -121,6 +123,8 @@ class DecoderLoop:
                 mass = b.sparse_prefill_mass()
             else:
                 b.sparse_prefill()
+            if self.pre is not None and b.cow:
+                self.pre[1].release(l)
             b.ctx.linear(o2, lw["w_o"], h1, residual=h)
             b.ctx.rms_norm(h1, lw["gain_ffn"], self.eps[l], x)
             b.ctx.gated_linear(x, lw["w_gate"], lw["w_up"], act)

@@ -22,13 +22,17 @@ def _dev(a: np.ndarray, dtype=None, device="cuda") -> torch.Tensor:
 
 class DeviceBatch:
     def __init__(self, w, device: str = "cuda", impl: int = CC_IMPL_AUTO, poison: bool = False,
-                 miss_segments=(), fused_gather: bool = True):
-        """miss_segments: global indices of chunk segments that have NO chunk-cache in this batch: they
+                 miss_segments=(), fused_gather: bool = True, cow: bool = True):
+        """cow: values of cached chunks stay in the store (cc_rope_shift only records where they are);
+        cc_sparse_prefill copies a page's values into the request's pool when it recomputes one of its
+        tokens and reads all the others from the store (cc_shared_values).
+        miss_segments: global indices of chunk segments that have NO chunk-cache in this batch: they
         are not shifted from the store; K, V of all their tokens are written into the request's pages
         (fill_miss) before the other chunks are scored."""
         sp = w.spec
         self.w = w
         self.fused_gather = fused_gather
+        self.cow = cow
         self.device = device
         self.dt = torch.bfloat16 if sp.dtype == "bf16" else torch.float32
         self.ctx = Context(sp.n_q_heads, sp.n_kv_heads, sp.head_dim, sp.rope_theta,
@@ -43,6 +47,8 @@ class DeviceBatch:
         fill = float("nan") if poison else 0.0
         self.k_req = torch.full((nb, hkv, 16, d), fill, dtype=dt, device=device)
         self.v_req = torch.full((nb, hkv, d, 16), fill, dtype=dt, device=device)
+        # stored block that still holds the values of a request page (-1: the request's own block does)
+        self.v_map = torch.full((nb,), -1, dtype=torch.int32, device=device)
         # metadata
         self.store_tab = _dev(w.store_tab, None, device)
         self.req_tab = _dev(w.req_tab, None, device)
@@ -98,9 +104,24 @@ class DeviceBatch:
 
     # ---- the calls, in path order ------------------------------------------------------------
     def rope_shift(self, with_v: bool = True):
-        self.ctx.rope_shift(self.k_store, self.v_store if with_v else None, self.k_req,
-                            self.v_req if with_v else None, self.store_tab, self.req_tab,
-                            self.shift_descs, self.n_instances, self.max_shift_tokens)
+        copy_v = with_v and not self.cow
+        self.ctx.rope_shift(self.k_store, self.v_store if copy_v else None, self.k_req,
+                            self.v_req if copy_v else None, self.store_tab, self.req_tab,
+                            self.shift_descs, self.n_instances, self.max_shift_tokens,
+                            v_map=self.v_map if (with_v and self.cow) else None)
+
+    @property
+    def shared(self):
+        """Argument `shared` of the prefill calls."""
+        return (self.v_store, self.v_map) if self.cow else None
+
+    def values_pool(self):
+        """The request's value pages as the attention sees them (stored blocks resolved): a copy."""
+        v = self.v_req.clone()
+        if self.cow:
+            idx = torch.nonzero(self.v_map >= 0).flatten()
+            v[idx] = self.v_store[self.v_map[idx].long()]
+        return v
 
     def fill_miss(self):
         """K, V of every token of the chunks without a cache, into the request's pages."""
@@ -171,7 +192,7 @@ class DeviceBatch:
         self.ctx.sparse_prefill(self.q, self.k_new, self.v_new, self.q_pos, self.slot_map, self.cu_q,
                                 self.max_q_per_req, self.k_req, self.v_req, self.req_tab,
                                 self.segments, self.req_seg_off, self.n_requests, self.n_tok, r(self.out), self.lse,
-                                self.ws_prefill, src_rows=r(self.q_row))
+                                self.ws_prefill, src_rows=r(self.q_row), shared=self.shared)
 
     def sparse_prefill(self):
         if self.n_q_tot == 0:
@@ -180,7 +201,7 @@ class DeviceBatch:
         self.ctx.sparse_prefill(r(self.q_c), r(self.k_c), r(self.v_c), self.q_pos, self.slot_map, self.cu_q,
                                 self.max_q_per_req, self.k_req, self.v_req, self.req_tab,
                                 self.segments, self.req_seg_off, self.n_requests, self.n_tok, r(self.out), self.lse,
-                                self.ws_prefill)
+                                self.ws_prefill, shared=self.shared)
 
     def _mass_buffers(self):
         n_segs = int(self.segments.shape[0])
@@ -219,7 +240,7 @@ class DeviceBatch:
                                      self.max_q_per_req, min(self.max_question_rows, self.max_q_per_req), self.k_req,
                                      self.v_req, self.req_tab, self.segments, self.req_seg_off, self.n_requests,
                                      self.max_segs_per_req, self.n_tok, r(self.out), self.lse, self.seg_mass,
-                                     self.ws_prefill_mass, src_rows=src_rows)
+                                     self.ws_prefill_mass, src_rows=src_rows, shared=self.shared)
         return self.seg_mass
 
     def question_mass(self):
@@ -268,7 +289,7 @@ class DeviceBatch:
                                       self.max_q_per_req, self.k_req, self.v_req, self.req_tab, self.segments,
                                       self.req_seg_off, self.n_requests, self.max_segs_per_req, self.n_tok,
                                       r(self.out), self.lse, self.seg_mass, self.pair_mass, self.self_mass,
-                                      self.ws_prefill_pairs, src_rows=src_rows)
+                                      self.ws_prefill_pairs, src_rows=src_rows, shared=self.shared)
         return self.pair_mass, self.self_mass, self.pair_off
 
     def step(self):

@@ -65,14 +65,17 @@ def test_calls_reject_bad_arguments_before_launch(lib):
     good = C.c_void_p(4096)          # a well-aligned non-null address; never dereferenced on these paths
     odd = C.c_void_p(4100)
     # cc_rope_shift: null pool, misaligned pool, V given on one side only, negative count
-    assert lib.cc_rope_shift(h, None, None, 4, good, None, 4, good, good, good, 1, 16, None) == -1
+    assert lib.cc_rope_shift(h, None, None, 4, good, None, 4, good, good, good, 1, 16, None, None) == -1
     assert b"null" in lib.cc_last_error(h)
-    assert lib.cc_rope_shift(h, odd, None, 4, good, None, 4, good, good, good, 1, 16, None) == -1
-    assert lib.cc_rope_shift(h, good, good, 4, good, None, 4, good, good, good, 1, 16, None) == -1
-    assert lib.cc_rope_shift(h, good, None, 4, good, None, 4, good, good, good, -1, 16, None) == -1
-    assert lib.cc_rope_shift(h, good, None, 4, good, None, 4, good, good, good, 0, 16, None) == 0   # empty batch
-    assert lib.cc_rope_place(h, None, None, 4, good, None, 4, good, good, good, 1, 16, None) == -1
-    assert lib.cc_rope_place(h, good, None, 4, good, None, 4, good, good, good, 0, 16, None) == 0
+    assert lib.cc_rope_shift(h, odd, None, 4, good, None, 4, good, good, good, 1, 16, None, None) == -1
+    assert lib.cc_rope_shift(h, good, good, 4, good, None, 4, good, good, good, 1, 16, None, None) == -1
+    assert lib.cc_rope_shift(h, good, None, 4, good, None, 4, good, good, good, -1, 16, None, None) == -1
+    assert lib.cc_rope_shift(h, good, None, 4, good, None, 4, good, good, good, 0, 16, None, None) == 0   # empty batch
+    # a value map together with V pools (values are either copied or mapped, not both)
+    assert lib.cc_rope_shift(h, good, good, 4, good, good, 4, good, good, good, 1, 16, good, None) == -1
+    assert b"value map" in lib.cc_last_error(h)
+    assert lib.cc_rope_place(h, None, None, 4, good, None, 4, good, good, good, 1, 16, None, None) == -1
+    assert lib.cc_rope_place(h, good, None, 4, good, None, 4, good, good, good, 0, 16, None, None) == 0
     # cc_select: workspace too small / missing
     need = lib.cc_select_workspace_bytes(h, 100, 3)
     assert need >= 100 * 8 * 4
@@ -93,24 +96,31 @@ def test_calls_reject_bad_arguments_before_launch(lib):
     assert lib.cc_qkv_project(h, good, good, 4, 100, good, good, good, None) == -1
     # cc_sparse_prefill: null output, max_q_per_req > n_q_tot, empty query list
     ws = lib.cc_sparse_prefill_workspace_bytes(h, 100, 3)
-    args = [h, good, good, good, None, good, good, good, 10, 10, good, good, 8, good, good, 3, good, 1, 100]
+    args = [h, good, good, good, None, good, good, good, 10, 10, good, good, 8, good, good, 3, good, 1, 100, None]
     assert lib.cc_sparse_prefill(*args, None, None, good, ws, None) == -1
     args[9] = 11
     assert lib.cc_sparse_prefill(*args, good, None, good, ws, None) == -1
     args[8], args[9] = 0, 0
     assert lib.cc_sparse_prefill(*args, good, None, good, ws, None) == 0
+    # shared values without a map, or with an empty pool
+    from paper_2502_15734_amd.binding import SharedValues
+    args[8], args[9] = 10, 10
+    for bad in (SharedValues(4096, 8, None), SharedValues(None, 8, 4096), SharedValues(4096, 0, 4096), SharedValues(4100, 8, 4096)):
+        args[19] = C.byref(bad)
+        assert lib.cc_sparse_prefill(*args, good, None, good, ws, None) == -1 and b"shared values" in lib.cc_last_error(h)
+    args[19] = None
     # rows of the compact list beyond n_ctx_tokens (the redo flags in the workspace are sized by it)
-    few = [h, good, good, good, None, good, good, good, 10, 10, good, good, 8, good, good, 3, good, 1, 9]
+    few = [h, good, good, good, None, good, good, good, 10, 10, good, good, 8, good, good, 3, good, 1, 9, None]
     assert lib.cc_sparse_prefill(*few, good, None, good, ws, None) == -1 and b"n_ctx_tokens" in lib.cc_last_error(h)
     # cc_sparse_prefill_static: a plan larger than the built-in scratch is refused before anything else happens;
     # an empty query list is fine
     assert lib.cc_sparse_prefill_static(h, good, good, good, None, good, good, good, 10, 10, good, good, 8, good, good,
-                                        3, good, 1, 4_000_000, good, None, None) == -3
+                                        3, good, 1, 4_000_000, None, good, None, None) == -3
     assert b"scratch" in lib.cc_last_error(h)
     assert lib.cc_sparse_prefill_static(h, good, good, good, None, good, good, good, 0, 0, good, good, 8, good, good,
-                                        3, good, 1, 100, good, None, None) == 0
+                                        3, good, 1, 100, None, good, None, None) == 0
     # grid limits: more than 65535 requests (cc_sparse_prefill) or segments (cc_select) in one call are refused
-    big = [h, good, good, good, None, good, good, good, 70000, 10, good, good, 8, good, good, 70000, good, 70000, 70000]
+    big = [h, good, good, good, None, good, good, good, 70000, 10, good, good, 8, good, good, 70000, good, 70000, 70000, None]
     wsb = lib.cc_sparse_prefill_workspace_bytes(h, 70000, 70000)
     assert lib.cc_sparse_prefill(*big, good, None, good, wsb, None) == -1 and b"65535" in lib.cc_last_error(h)
     need_big = lib.cc_select_workspace_bytes(h, 70000, 70000)
@@ -145,12 +155,12 @@ def test_calls_reject_bad_arguments_before_launch(lib):
     wp = lib.cc_sparse_prefill_pairs_workspace_bytes(h, 100, 3, 10, 10, 3)
     assert wp >= 10 * 8 * 3 * 4
     pa = [h, good, good, good, None, good, good, good, 10, 10, good, good, 8, good, good, 3, good, 1, 3, 100]
-    assert lib.cc_sparse_prefill_pairs(*pa, 6, good, good, good, None, good, good, wp, None) == -1
-    assert lib.cc_sparse_prefill_pairs(*pa, 6, good, None, good, good, good, good, wp, None) == -1
-    assert lib.cc_sparse_prefill_pairs(*pa, 2, good, good, good, good, good, good, wp, None) == -1
-    assert lib.cc_sparse_prefill_pairs(*pa, 6, good, good, None, good, good, good, wp - 1, None) == -3
+    assert lib.cc_sparse_prefill_pairs(*pa, 6, None, good, good, good, None, good, good, wp, None) == -1
+    assert lib.cc_sparse_prefill_pairs(*pa, 6, None, good, None, good, good, good, good, wp, None) == -1
+    assert lib.cc_sparse_prefill_pairs(*pa, 2, None, good, good, good, good, good, good, wp, None) == -1
+    assert lib.cc_sparse_prefill_pairs(*pa, 6, None, good, good, None, good, good, good, wp - 1, None) == -3
     pa[15] = 0
-    assert lib.cc_sparse_prefill_pairs(*pa, 6, good, good, good, good, good, good, wp, None) == 0
+    assert lib.cc_sparse_prefill_pairs(*pa, 6, None, good, good, good, good, good, good, wp, None) == 0
     other = C.c_void_p(8192)
     # the dense operators of the layer: null tensors, x == y, hidden off the 16-byte grid, negative eps, no rows
     assert lib.cc_rms_norm(h, good, None, 1e-5, 4, 64, good, None) == -1
@@ -165,7 +175,7 @@ def test_calls_reject_bad_arguments_before_launch(lib):
     assert lib.cc_gated_linear(h, good, good, good, 4, 0, 64, other, None) == -1
     assert lib.cc_gated_linear(h, good, good, good, 0, 64, 64, other, None) == 0
     # null context
-    assert lib.cc_rope_shift(None, good, None, 4, good, None, 4, good, good, good, 1, 16, None) == -1
+    assert lib.cc_rope_shift(None, good, None, 4, good, None, 4, good, good, good, 1, 16, None, None) == -1
     assert lib.cc_set_impl(h, 99) == -1
     for impl in (P.CC_IMPL_MFMA_NARROW, P.CC_IMPL_MFMA_WIDE, P.CC_IMPL_SCALAR, P.CC_IMPL_AUTO):
         assert lib.cc_set_impl(h, impl) == 0

@@ -13,7 +13,8 @@ pytestmark = pytest.mark.gpu
 
 
 def _pools(batch):
-    return batch.k_req.float().cpu().numpy(), batch.v_req.float().cpu().numpy()
+    """The request's pages as the attention sees them (values that stay in the store resolved)."""
+    return batch.k_req.float().cpu().numpy(), batch.values_pool().float().cpu().numpy()
 
 
 def check_workload(w, impl, score_tol=5e-5):
@@ -260,6 +261,52 @@ def test_zero_shift_is_bit_exact():
             dst = w.req_tab[tab: tab + (n + 15) // 16]
             assert np.array_equal(O.read_k_pages(kp, dst, n), O.read_k_pages(w.k_store, src, n))
             assert np.array_equal(O.read_v_pages(vp, dst, n), O.read_v_pages(w.v_store, src, n))
+
+
+@pytest.mark.parametrize("impl", ["auto", "scalar", "narrow", "wide"])
+@pytest.mark.parametrize("fused", [True, False])
+def test_values_stay_in_the_store_until_a_token_of_their_page_is_recomputed(impl, fused):
+    """cc_rope_shift with a value map moves no value; cc_sparse_prefill copies a page's values the
+    first time it writes a row of that page and reads all the others from the store.  The results
+    are those of the copying path, bit for bit; pages without a recomputed token are never written."""
+    from paper_2502_15734_amd.pipeline import DeviceBatch
+    reqs = [W.RequestSpec([0, 1, 2, 3], [0.3, 0.05, 0.25, 0.0], 21), W.RequestSpec([3, 0, 4], [0.5, 0.15, 0.1], 40)]
+    w = W.custom("cow", "bf16", 8, 2, 128, 5.0e5, [100, 77, 130, 64, 201], [0, 5, 0, 17, 3], reqs, 0.35, seed=47)
+    a = DeviceBatch(w, impl=_impls()[impl], poison=True, cow=False, fused_gather=fused)
+    b = DeviceBatch(w, impl=_impls()[impl], poison=True, cow=True, fused_gather=fused)
+    b.rope_shift(); torch.cuda.synchronize()
+    assert torch.isnan(b.v_req.float()).all(), "the shift must not write values when it fills the map"
+    # every page of a reused chunk points at the stored block its keys came from
+    vm = b.v_map.cpu().numpy()
+    for dsc in w.shift_descs:
+        src, dst, n = int(dsc[W.SHIFT_SRC_TAB]), int(dsc[W.SHIFT_DST_TAB]), int(dsc[W.SHIFT_NTOK])
+        for pg in range((n + 15) // 16):
+            assert vm[w.req_tab[dst + pg]] == w.store_tab[src + pg]
+    a.step(); b.step(); torch.cuda.synchronize()
+    n = a.n_q_tot
+    assert n == b.n_q_tot and torch.equal(a.sel_idx[:n], b.sel_idx[:n])
+    assert torch.equal(a.out[:n], b.out[:n]) and torch.equal(a.lse[:n], b.lse[:n])
+    assert torch.equal(a.k_req.nan_to_num(nan=-7.0), b.k_req.nan_to_num(nan=-7.0))
+    assert torch.equal(a.v_req.nan_to_num(nan=-7.0), b.values_pool().nan_to_num(nan=-7.0))
+    # pages with a recomputed row are the request's own now; the others were never written
+    vm = b.v_map.cpu().numpy()
+    touched = np.zeros(b.v_req.shape[0], dtype=bool)
+    touched[np.unique(b.slot_map[:n].cpu().numpy() // 16)] = True
+    chunk_pages = np.zeros_like(touched)
+    for dsc in w.shift_descs:
+        dst, ntok = int(dsc[W.SHIFT_DST_TAB]), int(dsc[W.SHIFT_NTOK])
+        chunk_pages[w.req_tab[dst: dst + (ntok + 15) // 16]] = True
+    assert (vm[touched] == -1).all()
+    assert (vm[chunk_pages & ~touched] >= 0).all() and (chunk_pages & ~touched).any()
+    untouched = torch.as_tensor(np.nonzero(chunk_pages & ~touched)[0], device=b.v_req.device)
+    assert torch.isnan(b.v_req[untouched].float()).all()
+    # the by-product variants take the same argument
+    m_a, m_b = a.sparse_prefill_mass(fused=fused).clone(), b.sparse_prefill_mass(fused=fused).clone()
+    p_a = [t.clone() for t in a.sparse_prefill_pairs(fused=fused)[:2]]
+    p_b = [t.clone() for t in b.sparse_prefill_pairs(fused=fused)[:2]]
+    torch.cuda.synchronize()
+    assert torch.equal(m_a, m_b) and all(torch.equal(x, y) for x, y in zip(p_a, p_b))
+    assert torch.equal(a.out[:n], b.out[:n]) and torch.equal(a.lse[:n], b.lse[:n])
 
 
 @pytest.mark.parametrize("impl", ["auto", "wide", "scalar"])
