@@ -43,6 +43,9 @@ void launch_gather_rows(const void* src, int n_src_rows, const int32_t* row_idx,
 //   slots -- and isolated 2-byte stores cost a full memory write each, so every (head, dim) row
 //   of the block is read, patched with the run's tokens in registers, and written back whole.
 //   This needs all rows of a block to sit in ONE run.
+// Per run the source row, position and slot of every token are looked up once and kept in LDS; a
+// thread then issues all the loads of its items before it uses the first (the items of a run are
+// independent), so that the kernel is bound by bytes and not by a chain of load latencies.
 constexpr int kScatterRows = 16;     // candidate rows per workgroup (4 or 8 measured the same, 1 or 2 slower)
 
 template <typename T, int D>
@@ -55,6 +58,8 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(
   // block?) and the 15 rows a run starting at the last candidate can still cover; -1 = no row /
   // invalid slot
   __shared__ int sl[kScatterRows + kBlock];
+  __shared__ int run_row[kBlock], run_pos[kBlock], run_slot[kBlock];   // by token of the run
+  __shared__ int row_of_slot[kBlock];                                  // by slot of the block (-1: not in the run)
   const int tid = threadIdx.x, base = blockIdx.x * kScatterRows;
   if (tid < kScatterRows + kBlock) {
     const int j = base - 1 + tid;
@@ -74,29 +79,60 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(
     int n_run = 1;
     while (n_run < kBlock && sl[c + 1 + n_run] >= 0 && sl[c + 1 + n_run] / kBlock == blk) ++n_run;
     const int j0 = base + c;
-    // K: one (token, KV head, 16-byte piece of the head's first half) per thread and step, together
-    // with the matching piece of the second half: two 16-byte loads, kPer rotations, two 16-byte stores
-    constexpr int kPer = 16 / sizeof(T), kPieces = D / 2 / kPer;
-    for (int idx = tid; idx < n_run * hkv * kPieces; idx += 256) {
-      const int p = idx % kPieces, h = (idx / kPieces) % hkv, t = idx / (kPieces * hkv);
-      const int j = j0 + t, pos = q_pos[j];
-      const T* kp = k_new + (static_cast<size_t>(src_rows != nullptr ? src_rows[j] : j) * hkv + h) * D + kPer * p;   // (row of k_new, v_new this list row reads)
-      T* ko = k_pool + ((static_cast<size_t>(blk) * hkv + h) * kBlock + sl[c + 1 + t] % kBlock) * D + kPer * p;
-      T x[kPer], y[kPer], ox[kPer], oy[kPer];
-      *reinterpret_cast<uint4*>(x) = *reinterpret_cast<const uint4*>(kp);
-      *reinterpret_cast<uint4*>(y) = *reinterpret_cast<const uint4*>(kp + D / 2);
-#pragma unroll
-      for (int e = 0; e < kPer; ++e) {
-        float cs, sn;
-        if (sizeof(T) == 2) rot_cos_sin_fast(pos, inv_freq.f[kPer * p + e], &cs, &sn);   // (the result is rounded to bf16)
-        else rot_cos_sin(pos, inv_freq.f[kPer * p + e], &cs, &sn);
-        const float xv = to_float(x[e]), yv = to_float(y[e]);
-        ox[e] = from_float<T>(xv * cs - yv * sn);
-        oy[e] = from_float<T>(yv * cs + xv * sn);
+    __syncthreads();                                       // (the previous run's readers are done)
+    if (tid < kBlock) {
+      row_of_slot[tid] = -1;
+      if (tid < n_run) {
+        run_row[tid] = src_rows != nullptr ? src_rows[j0 + tid] : j0 + tid;   // (row of k_new, v_new this list row reads)
+        run_pos[tid] = q_pos[j0 + tid];
+        run_slot[tid] = sl[c + 1 + tid] % kBlock;
       }
-      *reinterpret_cast<uint4*>(ko) = *reinterpret_cast<uint4*>(ox);
-      *reinterpret_cast<uint4*>(ko + D / 2) = *reinterpret_cast<uint4*>(oy);
     }
+    __syncthreads();
+    if (tid < n_run) row_of_slot[run_slot[tid]] = run_row[tid];
+    __syncthreads();
+
+    // K: one (token, KV head, 16-byte piece of the head's first half) per thread and item, together
+    // with the matching piece of the second half: two 16-byte loads, kPer rotations, two 16-byte stores
+    constexpr int kPer = 16 / sizeof(T), kPieces = D / 2 / kPer, kItems = 4;
+    const int n_items = n_run * hkv * kPieces;
+    for (int i0 = tid; i0 < n_items; i0 += 256 * kItems) {
+      uint4 xv[kItems], yv[kItems];
+#pragma unroll
+      for (int u = 0; u < kItems; ++u) {
+        const int idx = i0 + 256 * u;
+        if (idx < n_items) {
+          const int p = idx % kPieces, h = (idx / kPieces) % hkv, t = idx / (kPieces * hkv);
+          const T* kp = k_new + (static_cast<size_t>(run_row[t]) * hkv + h) * D + kPer * p;
+          xv[u] = *reinterpret_cast<const uint4*>(kp);
+          yv[u] = *reinterpret_cast<const uint4*>(kp + D / 2);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kItems; ++u) {
+        const int idx = i0 + 256 * u;
+        if (idx < n_items) {
+          const int p = idx % kPieces, h = (idx / kPieces) % hkv, t = idx / (kPieces * hkv);
+          const int pos = run_pos[t];
+          T* ko = k_pool + ((static_cast<size_t>(blk) * hkv + h) * kBlock + run_slot[t]) * D + kPer * p;
+          T x[kPer], y[kPer], ox[kPer], oy[kPer];
+          *reinterpret_cast<uint4*>(x) = xv[u];
+          *reinterpret_cast<uint4*>(y) = yv[u];
+#pragma unroll
+          for (int e = 0; e < kPer; ++e) {
+            float cs, sn;
+            if (sizeof(T) == 2) rot_cos_sin_fast(pos, inv_freq.f[kPer * p + e], &cs, &sn);   // (the result is rounded to bf16)
+            else rot_cos_sin(pos, inv_freq.f[kPer * p + e], &cs, &sn);
+            const float xf = to_float(x[e]), yf = to_float(y[e]);
+            ox[e] = from_float<T>(xf * cs - yf * sn);
+            oy[e] = from_float<T>(yf * cs + xf * sn);
+          }
+          *reinterpret_cast<uint4*>(ko) = *reinterpret_cast<uint4*>(ox);
+          *reinterpret_cast<uint4*>(ko + D / 2) = *reinterpret_cast<uint4*>(oy);
+        }
+      }
+    }
+
     // V: one (head, dim) row of 16 slots per thread and step.  The rows that are patched come
     // from the block that holds the page's values now: the request's own block, or - the first
     // time a token of the page is recomputed - the stored block the value map still points at
@@ -105,6 +141,9 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(
     const size_t block_elems = static_cast<size_t>(hkv) * D * kBlock;
     const T* v_from = value_block<T>(v_pool, v_shared, n_shared_blocks, v_map, blk, block_elems);
     const bool pending = v_from != v_pool + static_cast<size_t>(blk) * block_elems;
+    int src_of[kBlock];                                    // (workgroup-uniform: scalar registers)
+#pragma unroll
+    for (int k = 0; k < kBlock; ++k) src_of[k] = __builtin_amdgcn_readfirstlane(row_of_slot[k]);
     for (int idx = tid; idx < hkv * D; idx += 256) {
       const int h = idx / D, dcol = idx % D;
       uint4* rowp = reinterpret_cast<uint4*>(v_pool + ((static_cast<size_t>(blk) * hkv + h) * D + dcol) * kBlock);
@@ -114,12 +153,10 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(
 #pragma unroll
         for (int v = 0; v < kVec; ++v) reinterpret_cast<uint4*>(e)[v] = fromp[v];
       }
-      for (int t = 0; t < n_run; ++t) {
-        const T val = v_new[(static_cast<size_t>(src_rows != nullptr ? src_rows[j0 + t] : j0 + t) * hkv + h) * D + dcol];
-        const int s_ = sl[c + 1 + t] % kBlock;
+      const T* vcol = v_new + static_cast<size_t>(h) * D + dcol;
 #pragma unroll
-        for (int k = 0; k < kBlock; ++k) if (k == s_) e[k] = val;
-      }
+      for (int k = 0; k < kBlock; ++k)
+        if (src_of[k] >= 0) e[k] = vcol[static_cast<size_t>(src_of[k]) * hkv * D];
 #pragma unroll
       for (int v = 0; v < kVec; ++v) rowp[v] = reinterpret_cast<uint4*>(e)[v];
     }
