@@ -75,7 +75,12 @@ __device__ __forceinline__ void stage_direct(uint4* lds, const bf16_t* __restric
 //                the softmax mass that falls on keys of earlier segments (Eq. (2), Eq. (10)).
 // SCORE = false: queries are 32*QB rows of the compact query list; result is the attention
 //                output and log-sum-exp (Eq. (1)).
-template <int G, bool SCORE, int QB>
+// REDO = true : second pass behind the wide kernels.  One workgroup per segment (score) or request
+//                (attention) looks up, in parallel, which of its row tiles the wide kernel flagged
+//                and walks those, one KV head after the other; without flags - the normal case -
+//                it is gone after one round of loads, so the pass costs a few hundred short
+//                workgroups instead of one per (tile, KV head).
+template <int G, bool SCORE, int QB, bool REDO>
 __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
     const bf16_t* __restrict__ q, const int32_t* __restrict__ q_pos, const int32_t* __restrict__ cu_q,
     const bf16_t* __restrict__ k_pool, const bf16_t* __restrict__ v_pool, int n_blocks,
@@ -97,8 +102,41 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
   __shared__ uint4 lds_all[kBufs * kImage];
   const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
   const int n = lane & 31, hh = lane >> 5;
-  const int kvh = blockIdx.x % hkv;
-  const int tile = n_tiles_x - 1 - blockIdx.x / hkv;       // late (long) tiles are dispatched first
+  // ---- which row tiles ----------------------------------------------------------------------
+  const int y_item = order[blockIdx.y];     // segment (score; heaviest first) or request (attention; longest context first)
+  cc_segment sg_own = {};
+  int q_first = 0, q_end = 0;
+  if constexpr (SCORE) sg_own = segs[y_item];
+  else { q_first = cu_q[y_item]; q_end = cu_q[y_item + 1]; }
+  // is row tile t of this item flagged for the second pass?
+  auto flagged = [&](int t) {
+    if constexpr (SCORE) {
+      const int t0 = t * TQ;
+      if (sg_own.kind != CC_SEG_CHUNK || t0 >= sg_own.n_tokens || sg_own.logical_start == 0) return false;
+      return (redo[(sg_own.tok_off + t0) >> 6] | redo[(sg_own.tok_off + t0 + TQ - 1) >> 6]) != 0;
+    } else {
+      if (q_first + t * TQ >= q_end) return false;
+      return redo[redo_index(q_first + (t * TQ / 64) * 64)] != 0;
+    }
+  };
+  __shared__ int todo[REDO ? NT : 1];
+  __shared__ int n_todo;
+  const int n_rounds = REDO ? (n_tiles_x + NT - 1) / NT : 1;
+  for (int round = 0; round < n_rounds; ++round) {
+  int n_work = 1;
+  if constexpr (REDO) {
+    __syncthreads();                                  // (the previous round's list has been walked)
+    if (tid == 0) n_todo = 0;
+    __syncthreads();
+    const int t = round * NT + tid;
+    if (t < n_tiles_x && flagged(t)) todo[atomicAdd(&n_todo, 1)] = t;
+    __syncthreads();
+    n_work = n_todo * hkv;
+  }
+  for (int work = 0; work < n_work; ++work) {
+  if constexpr (REDO) __syncthreads();                // (LDS images of the previous tile are free)
+  const int kvh = REDO ? work % hkv : blockIdx.x % hkv;
+  const int tile = REDO ? todo[work / hkv] : n_tiles_x - 1 - blockIdx.x / hkv;       // late (long) tiles are dispatched first
   const int h = kvh * G + wave;
 
   // ---- which queries ------------------------------------------------------------------------
@@ -107,12 +145,10 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
   int row[QB], src_row[QB], p[QB], s_begin, s_end, s_self = -1;
   bool row_valid[QB];
   if constexpr (SCORE) {
-    const int seg_id = order[blockIdx.y];              // heaviest segments are dispatched first
-    const cc_segment sg = segs[seg_id];
+    const int seg_id = y_item;
+    const cc_segment sg = sg_own;
     const int t0 = tile * TQ;
-    if (sg.kind != CC_SEG_CHUNK || t0 >= sg.n_tokens || sg.logical_start == 0) return;
-    // second pass behind the wide kernel: only the 64-row granules it flagged
-    if (redo != nullptr && (redo[(sg.tok_off + t0) >> 6] | redo[(sg.tok_off + t0 + TQ - 1) >> 6]) == 0) return;
+    if (sg.kind != CC_SEG_CHUNK || t0 >= sg.n_tokens || sg.logical_start == 0) continue;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       const int t = min(t0 + 32 * qb + n, sg.n_tokens - 1);
@@ -125,11 +161,9 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
     s_self = seg_id;
     s_end = s_self + 1;
   } else {
-    const int r = order[blockIdx.y];                   // longest contexts are dispatched first
-    const int q0 = cu_q[r] + tile * TQ, q_end = cu_q[r + 1];
-    if (q0 >= q_end) return;
-    // second pass behind the wide kernel: only the 64-row tiles it flagged
-    if (redo != nullptr && redo[redo_index(cu_q[r] + (tile * TQ / 64) * 64)] == 0) return;
+    const int r = y_item;
+    const int q0 = q_first + tile * TQ;
+    if (q0 >= q_end) continue;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
       row[qb] = min(q0 + 32 * qb + n, q_end - 1);
@@ -493,6 +527,8 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
       }
     }
   }
+  }   // work items of the round
+  }   // rounds
 }
 
 // ---- plan: the key tiles of every segment, in prompt order ---------------------------------------
@@ -624,13 +660,17 @@ void launch_attn_g(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const
                    int n_requests, void* out, float* lse, const int32_t* redo, const int32_t* q_map,
                    int map_pos, hipStream_t stream, const ValueSource& vs) {
   const int hkv = ctx->cfg.n_kv_heads, n_tiles = (max_q_per_req + 32 * kAttnQB - 1) / (32 * kAttnQB);
-  dim3 grid(hkv * n_tiles, n_requests);
-  hipLaunchKernelGGL((sparse_qk_kernel<G, false, kAttnQB>), grid, dim3(64 * G), 0, stream,
-                     static_cast<const bf16_t*>(q), q_pos, cu_q, static_cast<const bf16_t*>(k_pool),
-                     static_cast<const bf16_t*>(v_pool), n_blocks, pl.tiles, pl.seg_tile_off, pl.max_tiles,
-                     pl.order, segs, req_seg_off, ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq,
-                     static_cast<bf16_t*>(out), lse, static_cast<float*>(nullptr), redo, q_map, map_pos,
-                     static_cast<const bf16_t*>(vs.v_shared), vs.n_shared_blocks, static_cast<const int32_t*>(vs.v_map));
+#define CC_KARGS static_cast<const bf16_t*>(q), q_pos, cu_q, static_cast<const bf16_t*>(k_pool),                 \
+                 static_cast<const bf16_t*>(v_pool), n_blocks, pl.tiles, pl.seg_tile_off, pl.max_tiles,         \
+                 pl.order, segs, req_seg_off, ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq,                  \
+                 static_cast<bf16_t*>(out), lse, static_cast<float*>(nullptr), redo, q_map, map_pos,            \
+                 static_cast<const bf16_t*>(vs.v_shared), vs.n_shared_blocks, static_cast<const int32_t*>(vs.v_map)
+  if (redo != nullptr)
+    hipLaunchKernelGGL((sparse_qk_kernel<G, false, kAttnQB, true>), dim3(1, n_requests), dim3(64 * G), 0, stream, CC_KARGS);
+  else
+    hipLaunchKernelGGL((sparse_qk_kernel<G, false, kAttnQB, false>), dim3(hkv * n_tiles, n_requests), dim3(64 * G), 0,
+                       stream, CC_KARGS);
+#undef CC_KARGS
 }
 
 template <int G>
@@ -638,15 +678,19 @@ void launch_score_g(const cc_ctx* ctx, const void* q, const void* k_pool, int n_
                     const cc_segment* segs, int n_segs, const int32_t* req_seg_off, int max_seg_tokens,
                     float* mass, const int32_t* redo, hipStream_t stream) {
   const int hkv = ctx->cfg.n_kv_heads, n_tiles = (max_seg_tokens + 32 * kScoreQB - 1) / (32 * kScoreQB);
-  dim3 grid(hkv * n_tiles, n_segs);
-  hipLaunchKernelGGL((sparse_qk_kernel<G, true, kScoreQB>), grid, dim3(64 * G), 0, stream,
-                     static_cast<const bf16_t*>(q), static_cast<const int32_t*>(nullptr),
-                     static_cast<const int32_t*>(nullptr), static_cast<const bf16_t*>(k_pool),
-                     static_cast<const bf16_t*>(nullptr), n_blocks, pl.tiles, pl.seg_tile_off, pl.max_tiles,
-                     pl.order, segs, req_seg_off, ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq,
-                     static_cast<bf16_t*>(nullptr), static_cast<float*>(nullptr), mass, redo,
-                     static_cast<const int32_t*>(nullptr), 0, static_cast<const bf16_t*>(nullptr), 0,
-                     static_cast<const int32_t*>(nullptr));
+#define CC_KARGS static_cast<const bf16_t*>(q), static_cast<const int32_t*>(nullptr),                             \
+                 static_cast<const int32_t*>(nullptr), static_cast<const bf16_t*>(k_pool),                      \
+                 static_cast<const bf16_t*>(nullptr), n_blocks, pl.tiles, pl.seg_tile_off, pl.max_tiles,        \
+                 pl.order, segs, req_seg_off, ctx->cfg.n_q_heads, hkv, n_tiles, ctx->inv_freq,                  \
+                 static_cast<bf16_t*>(nullptr), static_cast<float*>(nullptr), mass, redo,                       \
+                 static_cast<const int32_t*>(nullptr), 0, static_cast<const bf16_t*>(nullptr), 0,               \
+                 static_cast<const int32_t*>(nullptr)
+  if (redo != nullptr)
+    hipLaunchKernelGGL((sparse_qk_kernel<G, true, kScoreQB, true>), dim3(1, n_segs), dim3(64 * G), 0, stream, CC_KARGS);
+  else
+    hipLaunchKernelGGL((sparse_qk_kernel<G, true, kScoreQB, false>), dim3(hkv * n_tiles, n_segs), dim3(64 * G), 0, stream,
+                       CC_KARGS);
+#undef CC_KARGS
 }
 
 bool group_supported(const cc_ctx* ctx) {

@@ -139,8 +139,19 @@ __global__ __launch_bounds__(kTopnThreads) void topn_kernel(
     if (given) {                            // scores supplied by the caller, one per token
       sc = mass[static_cast<size_t>(sg.tok_off) + i];
     } else if (sg.logical_start > 0) {
+      // (summed head by head in index order whatever the load width, so the result does not
+      //  depend on it)
       const float* mp = mass + (static_cast<size_t>(sg.tok_off) + i) * hq;
-      for (int h = 0; h < hq; ++h) sc += mp[h];
+      if ((hq & 3) == 0) {
+        const float4* mp4 = reinterpret_cast<const float4*>(mp);
+#pragma unroll 8
+        for (int h4 = 0; h4 < hq / 4; ++h4) {
+          const float4 v = mp4[h4];
+          sc += v.x; sc += v.y; sc += v.z; sc += v.w;
+        }
+      } else {
+        for (int h = 0; h < hq; ++h) sc += mp[h];
+      }
       sc *= inv_h;
     }
     if (scores) scores[sg.tok_off + i] = sc;
@@ -149,12 +160,21 @@ __global__ __launch_bounds__(kTopnThreads) void topn_kernel(
   __syncthreads();
   if (n_sel == 0) return;
   // N-th largest key, most significant bit first
+  // (a wavefront counts with ballots; the four wavefront counts meet in LDS, in two alternating
+  //  sets of cells so that one barrier per round is enough)
+  __shared__ int round_cnt[2][4];
   uint32_t thr = 0;
   for (int bit = 31; bit >= 0; --bit) {
     const uint32_t cand = thr | (1u << bit);
     int cnt = 0;
-    for (int i = tid; i < n; i += kTopnThreads) cnt += keys[i] >= cand;
-    if (block_sum_i(cnt, red) >= n_sel) thr = cand;
+    for (int i0 = 0; i0 < n; i0 += kTopnThreads) {
+      const int i = i0 + tid;
+      cnt += __popcll(__ballot(i < n && keys[i] >= cand));
+    }
+    int* cell = round_cnt[bit & 1];
+    if ((tid & 63) == 0) cell[tid >> 6] = cnt;
+    __syncthreads();
+    if (cell[0] + cell[1] + cell[2] + cell[3] >= n_sel) thr = cand;
   }
   int cnt = 0;
   for (int i = tid; i < n; i += kTopnThreads) cnt += keys[i] > thr;
