@@ -22,11 +22,12 @@ sys.path.insert(0, ROOT)
 PEAK_MFMA_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E
 PEAK_FP32_VALU_TFLOPS = 157.3
-# Back-to-back v_mfma_f32_32x32x16_bf16 on all 1024 SIMDs sustains this on the box with random bf16
-# operands in vector registers (the clock the chip holds under matrix load depends on the operand
-# data: the same loop on constant operands reaches 2380); quoted beside the vendor peak, never
-# instead of it.
-MEASURED_MFMA_BF16_TFLOPS = 1880.0
+# Back-to-back v_mfma_f32_32x32x16_bf16 on all 1024 SIMDs, two wavefronts per SIMD, four independent
+# accumulators each, random bf16 operands in vector registers, nothing else in the loop, sustains this
+# on the box over several milliseconds (1490 with one wavefront per SIMD; the clock the chip holds
+# under matrix load depends on the operand data: constant operands run ~25 % faster).  Quoted beside
+# the vendor peak, never instead of it.
+MEASURED_MFMA_BF16_TFLOPS = 1700.0
 # Tracked rocprofv3 summary of the default workload: its "HBM traffic per launch" table (FETCH_SIZE / WRITE_SIZE
 # scaled by a copy of known size) is where roofline.traffic comes from - it is not measured in this run.
 TRAFFIC_PROFILE = os.path.join("profiles", "hot_path_kernels_config3_8b_continuous_batch.md")
@@ -59,8 +60,9 @@ def profiled_traffic_bytes(call: str):
     return total if found else None
 
 
-def algorithmic_work(w):
-    """Algorithmic flops / bytes of each stage for workload w (only causally visible keys count)."""
+def algorithmic_work(w, cow: bool = True):
+    """Algorithmic flops / bytes of each stage for workload w (only causally visible keys count).
+    cow: values stay in the chunk store, so the shift moves keys only."""
     import workload as W
     sp = w.spec
     hq, hkv, d = sp.n_q_heads, sp.n_kv_heads, sp.head_dim
@@ -76,7 +78,7 @@ def algorithmic_work(w):
             score_pairs += n * st + n * (n + 1) // 2
     return {
         "n_chunk_tok": n_chunk_tok,
-        "shift_bytes": n_chunk_tok * hkv * d * e * 2 * 2,      # K read+write and V read+write
+        "shift_bytes": n_chunk_tok * hkv * d * e * 2 * (1 if cow else 2),      # K read+write (and V read+write)
         "score_flops": 2.0 * d * hq * score_pairs,
         "recomputed_tokens": w.n_q_tot,
     }
@@ -368,7 +370,7 @@ def time_layer_loop(w, n_layers: int = 4, window: int = 2) -> dict:
 
 def stage_figures(w, batch, stage_ms):
     """Per library call: ms, achieved algorithmic rate, fraction of the published peak."""
-    work = algorithmic_work(w)
+    work = algorithmic_work(w, batch.cow)
     q_pos = batch.q_pos.cpu().numpy()[: w.n_q_tot]
     attn_flops = attention_flops(w, q_pos)
     proj_flops = 0.0
@@ -472,8 +474,8 @@ def main():
     stages["cc_rope_shift"]["frac_of_measured_copy"] = stages["cc_rope_shift"]["achieved"] / copy_gbs
     dominant = max(stages, key=lambda k: stages[k]["ms"])
     dom = stages[dominant]
-    kernel_of = {"cc_select": "score_v2_kernel (+ top-N, plan, redo pass: ~2 % of the call)",
-                 "cc_sparse_prefill": "attn_v2_kernel (+ rope_scatter, plan, redo pass: ~8 % of the call)",
+    kernel_of = {"cc_select": "score_v2_kernel (+ top-N, plan, second pass: ~2 % of the call)",
+                 "cc_sparse_prefill": "attn_v2_kernel (+ rope_scatter, plan, second pass: ~5 % of the call)",
                  "cc_rope_shift": "rope_shift_kernel", "cc_gather_rows(+cc_qkv_project)": "qkv_project / gather_rows"}
     traffic = profiled_traffic_bytes(dominant) if args.workload == TRAFFIC_WORKLOAD else None
     roofline = {"kernel": kernel_of[dominant], "call": dominant, "bound": dom["bound"], "achieved": dom["achieved"],

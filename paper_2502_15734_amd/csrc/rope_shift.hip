@@ -67,31 +67,40 @@ __global__ __launch_bounds__(256) void rope_shift_kernel(
     for (int u = 0; u < UV; ++u)
       if (tid + u * 256 < n_vec) tv[u] = load16(vs + tid + u * 256);
   }
+  // ... and so do the loads of the first group of key rows
+  constexpr int RPI = 256 / UPR;          // rows the workgroup covers per pass
+  constexpr int U = 4;                    // passes whose loads are issued together
+  const int rows = hkv * kBlock;          // (head, slot) rows of the block
+  // (padding slots are neither read nor written; a lane's slot is the same in every pass)
+  const bool lane_valid = ((tid / UPR) % kBlock) < n_valid;
+  vec16 xv[U], yv[U];
+  auto load_rows = [&](int row0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int row = row0 + u * RPI;
+      if (row < rows) {
+        const T* px = ks + row * D + c * N;
+        xv[u] = load16(px);
+        yv[u] = load16(px + D / 2);
+      }
+    }
+  };
+  if (lane_valid) load_rows(tid / UPR);
   float cs[N], sn[N];
   double freq[N];                         // (read together: one wait, not one per frequency)
 #pragma unroll
   for (int j = 0; j < N; ++j) freq[j] = inv_freq.f[c * N + j];
 #pragma unroll
-  for (int j = 0; j < N; ++j) rot_cos_sin(turn, freq[j], &cs[j], &sn[j]);
+  for (int j = 0; j < N; ++j) {
+    if (sizeof(T) == 2) rot_cos_sin_fast(turn, freq[j], &cs[j], &sn[j]);   // (the result is rounded to bf16)
+    else rot_cos_sin(turn, freq[j], &cs[j], &sn[j]);
+  }
 
   // Every lane issues all the loads of a group of rows before it turns and stores the first of them,
   // so that several 16-byte requests per lane are in flight.
-  constexpr int RPI = 256 / UPR;          // rows the workgroup covers per pass
-  constexpr int U = 4;                    // passes whose loads are issued together
-  const int rows = hkv * kBlock;          // (head, slot) rows of the block
-  // (padding slots are neither read nor written; a lane's slot is the same in every pass)
-  if (((tid / UPR) % kBlock) < n_valid) {
+  if (lane_valid) {
     for (int row0 = tid / UPR; row0 < rows; row0 += U * RPI) {
-      vec16 xv[U], yv[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int row = row0 + u * RPI;
-        if (row < rows) {
-          const T* px = ks + row * D + c * N;
-          xv[u] = load16(px);
-          yv[u] = load16(px + D / 2);
-        }
-      }
+      if (row0 != tid / UPR) load_rows(row0);
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int row = row0 + u * RPI;
