@@ -18,6 +18,7 @@
  *                      (Eq. (1), Sec. 3.4.3, Sec. 4 "Selective Token Recomputation")
  *   cc_sparse_prefill_mass  cc_sparse_prefill that also returns the question's attention to every
  *                      chunk (Sec. 3.2.2), as a by-product of the attention kernel where it can
+ *   cc_check_query_list  checks the row order the write of recomputed K, V relies on
  *   cc_scatter_kv      the write half of cc_sparse_prefill alone: K, V of chunks without a cache
  *                      (Sec. 3.4.1) go into the request's pages before the others are scored
  *   cc_question_mass   attention the question pays to every chunk in that layer, inter(C_i, U)
@@ -365,6 +366,18 @@ int cc_sparse_prefill_pairs(cc_ctx* ctx, const void* q, const void* k_new, const
  * computed for every token and must be in the request's pages before cc_select scores the chunks
  * behind them.  Rows whose slots lie in the same 16-token block must be adjacent, as for
  * cc_sparse_prefill.  k_new, v_new [n_rows][Hkv][d]. */
+/* Check of the order cc_sparse_prefill, its variants and cc_scatter_kv rely on (they do not check
+ * it themselves: two separate runs of rows in one block would be written by two workgroups that
+ * each rewrite whole value rows of the block).  *n_violations (device int32) receives the number
+ * of runs of adjacent rows that name a block an earlier run has named already: 0 for a list in
+ * cc_select's order, or any order that keeps the rows of a block together.  Rows with a slot
+ * outside the pool are ignored here as they are by the scatter.  For callers that build the list
+ * themselves; read the result when convenient (the call only enqueues).
+ *   workspace: cc_check_query_list_workspace_bytes(ctx, n_blocks) (one int32 per block). */
+size_t cc_check_query_list_workspace_bytes(const cc_ctx* ctx, int32_t n_blocks);
+int cc_check_query_list(cc_ctx* ctx, const int32_t* slot_map, int32_t n_rows, int32_t n_blocks,
+                        int32_t* n_violations, void* workspace, size_t workspace_bytes, void* stream);
+
 int cc_scatter_kv(cc_ctx* ctx, const void* k_new, const void* v_new, const int32_t* q_pos,
                   const int32_t* slot_map, int32_t n_rows, void* k_pool, void* v_pool, int32_t n_blocks,
                   void* stream);

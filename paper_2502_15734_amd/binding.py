@@ -98,6 +98,10 @@ def load_library() -> C.CDLL:
     lib.cc_sparse_prefill_pairs.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, vp, i32,
                                             vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.cc_sparse_prefill_pairs.restype = C.c_int
+    lib.cc_check_query_list_workspace_bytes.argtypes = [vp, i32]
+    lib.cc_check_query_list_workspace_bytes.restype = sz
+    lib.cc_check_query_list.argtypes = [vp, vp, i32, i32, vp, vp, sz, vp]
+    lib.cc_check_query_list.restype = C.c_int
     lib.cc_scatter_kv.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, i32, vp]
     lib.cc_scatter_kv.restype = C.c_int
     lib.cc_question_mass_workspace_bytes.argtypes = [vp, i32, i32, i32]
@@ -315,6 +319,16 @@ class Context:
             _ptr(out), _ptr(lse),
             _ptr(seg_mass), _ptr(pair_mass), _ptr(self_mass), _ptr(workspace),
             workspace.numel() * workspace.element_size(), _stream()))
+
+    def check_query_list(self, slot_map, n_blocks) -> int:
+        """Number of runs of adjacent list rows that name a block an earlier run named (0 = the order the
+        scatter relies on).  Synchronises to read the count."""
+        nbytes = int(self._lib.cc_check_query_list_workspace_bytes(self._h, n_blocks))
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=slot_map.device)
+        count = torch.zeros(1, dtype=torch.int32, device=slot_map.device)
+        self._check(self._lib.cc_check_query_list(self._h, _ptr(slot_map), slot_map.shape[0], n_blocks, _ptr(count),
+                                                  _ptr(ws), nbytes, _stream()))
+        return int(count.item())
 
     def scatter_kv(self, k_new, v_new, q_pos, slot_map, k_pool, v_pool):
         self._check(self._lib.cc_scatter_kv(self._h, _ptr(k_new), _ptr(v_new), _ptr(q_pos), _ptr(slot_map),

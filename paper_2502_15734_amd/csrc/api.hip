@@ -513,6 +513,26 @@ int cc_scatter_kv(cc_ctx* ctx, const void* k_new, const void* v_new, const int32
   return cc::check_launch(ctx, fn);
 }
 
+size_t cc_check_query_list_workspace_bytes(const cc_ctx* ctx, int32_t n_blocks) {
+  if (ctx == nullptr || n_blocks < 0) return 0;
+  return cc::align_up(static_cast<size_t>(n_blocks) * sizeof(int32_t), 256) + 256;
+}
+
+int cc_check_query_list(cc_ctx* ctx, const int32_t* slot_map, int32_t n_rows, int32_t n_blocks,
+                        int32_t* n_violations, void* workspace, size_t workspace_bytes, void* stream) {
+  static const char* fn = "cc_check_query_list";
+  if (ctx == nullptr) return CC_ERR_INVALID_ARG;
+  CC_REQUIRE(n_rows >= 0 && n_blocks > 0, "negative count or empty pool");
+  CC_REQUIRE(n_violations != nullptr && (slot_map != nullptr || n_rows == 0), "null pointer");
+  CC_REQUIRE(workspace != nullptr && aligned16(workspace), "workspace missing or misaligned");
+  if (workspace_bytes < cc_check_query_list_workspace_bytes(ctx, n_blocks))
+    return fail(ctx, CC_ERR_WORKSPACE_TOO_SMALL,
+                "cc_check_query_list: workspace smaller than cc_check_query_list_workspace_bytes()");
+  cc::launch_list_order_check(slot_map, n_rows, n_blocks, static_cast<int32_t*>(workspace), n_violations,
+                              static_cast<hipStream_t>(stream));
+  return cc::check_launch(ctx, fn);
+}
+
 size_t cc_question_mass_workspace_bytes(const cc_ctx* ctx, int32_t n_ctx_tokens, int32_t n_segs,
                                         int32_t max_question_rows) {
   if (ctx == nullptr || n_ctx_tokens < 0 || n_segs < 0 || max_question_rows < 0) return 0;

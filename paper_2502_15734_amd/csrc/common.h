@@ -76,6 +76,8 @@ void launch_rope_scatter(const cc_ctx* ctx, const void* k_new, const void* v_new
                          const int32_t* q_pos, const int32_t* slot_map, int n_q_tot, void* k_pool,
                          void* v_pool, int n_blocks, const int32_t* src_rows, hipStream_t stream,
                          const ValueSource& vs = ValueSource());
+void launch_list_order_check(const int32_t* slot_map, int n_rows, int n_blocks, int32_t* mark,
+                             int32_t* n_violations, hipStream_t stream);
 void launch_attn_scalar(const cc_ctx* ctx, const void* q, const int32_t* q_pos, const int32_t* cu_q,
                         int n_q_tot, int max_q_per_req, const void* k_pool, const void* v_pool,
                         int n_blocks, const int32_t* block_tab, const cc_segment* segs,

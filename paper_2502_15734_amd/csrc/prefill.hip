@@ -167,6 +167,37 @@ __global__ __launch_bounds__(256) void rope_scatter_kernel(
   }
 }
 
+// Check of the order the scatter relies on: the rows of a 16-token block must form ONE run of
+// adjacent list rows.  mark[block] (-1 on entry) takes the first row of the first run that names
+// the block; every further run that names it counts as a violation.
+__global__ __launch_bounds__(256) void fill_int_kernel(int32_t* __restrict__ p, int n, int32_t v) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+__global__ __launch_bounds__(256) void list_order_kernel(const int32_t* __restrict__ slot_map, int n_rows,
+                                                          int n_blocks, int32_t* __restrict__ mark,
+                                                          int32_t* __restrict__ n_violations) {
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= n_rows) return;
+  const int slot = slot_map[j];
+  if (slot < 0 || slot >= n_blocks * kBlock) return;            // (such rows are skipped by the scatter too)
+  const int blk = slot / kBlock;
+  if (j > 0) {
+    const int prev = slot_map[j - 1];
+    if (prev >= 0 && prev < n_blocks * kBlock && prev / kBlock == blk) return;   // not the first row of its run
+  }
+  if (atomicCAS(&mark[blk], -1, j) != -1) atomicAdd(n_violations, 1);
+}
+
+void launch_list_order_check(const int32_t* slot_map, int n_rows, int n_blocks, int32_t* mark,
+                             int32_t* n_violations, hipStream_t stream) {
+  hipLaunchKernelGGL(fill_int_kernel, dim3((n_blocks + 255) / 256), dim3(256), 0, stream, mark, n_blocks, -1);
+  hipLaunchKernelGGL(fill_int_kernel, dim3(1), dim3(256), 0, stream, n_violations, 1, 0);
+  if (n_rows > 0)
+    hipLaunchKernelGGL(list_order_kernel, dim3((n_rows + 255) / 256), dim3(256), 0, stream, slot_map, n_rows,
+                       n_blocks, mark, n_violations);
+}
+
 void launch_rope_scatter(const cc_ctx* ctx, const void* k_new, const void* v_new,
                          const int32_t* q_pos, const int32_t* slot_map, int n_q_tot, void* k_pool,
                          void* v_pool, int n_blocks, const int32_t* src_rows, hipStream_t stream,

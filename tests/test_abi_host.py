@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported(lib):
             "cc_preloader_create", "cc_preloader_set_layer", "cc_preloader_acquire", "cc_preloader_release",
             "cc_preloader_issued", "cc_preloader_destroy", "cc_sparse_prefill_mass", "cc_sparse_prefill_pairs",
             "cc_sparse_prefill_pairs_workspace_bytes", "cc_rms_norm", "cc_linear", "cc_gated_linear",
-            "cc_sparse_prefill_static"} <= set(names)
+            "cc_sparse_prefill_static", "cc_check_query_list", "cc_check_query_list_workspace_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in cc.h but not exported"
 
@@ -126,6 +126,12 @@ def test_calls_reject_bad_arguments_before_launch(lib):
     need_big = lib.cc_select_workspace_bytes(h, 70000, 70000)
     assert lib.cc_select(h, good, 70000, good, 8, good, good, 70000, good, 1, 64, good, None, None, None, 10,
                          None, good, need_big, None) == -1 and b"65535" in lib.cc_last_error(h)
+    # cc_check_query_list: missing result, tiny workspace
+    wq = lib.cc_check_query_list_workspace_bytes(h, 100)
+    assert wq >= 400
+    assert lib.cc_check_query_list(h, good, 10, 100, None, good, wq, None) == -1
+    assert lib.cc_check_query_list(h, good, 10, 100, good, good, wq - 1, None) == -3
+    assert lib.cc_check_query_list(h, good, 10, 0, good, good, wq, None) == -1
     # cc_scatter_kv: null pool, misaligned rows, nothing to do
     assert lib.cc_scatter_kv(h, good, good, good, good, 4, None, good, 8, None) == -1
     assert lib.cc_scatter_kv(h, odd, good, good, good, 4, good, good, 8, None) == -1

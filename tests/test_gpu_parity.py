@@ -263,6 +263,34 @@ def test_zero_shift_is_bit_exact():
             assert np.array_equal(O.read_v_pages(vp, dst, n), O.read_v_pages(w.v_store, src, n))
 
 
+def test_query_list_order_check():
+    """cc_check_query_list: cc_select's lists pass; a list whose rows of one block are split into two
+    runs is reported (that order would make two workgroups of the scatter rewrite the same value rows)."""
+    from paper_2502_15734_amd.pipeline import DeviceBatch
+    w = W.config(3, 0.08)
+    b = DeviceBatch(w)
+    b.rope_shift(); b.select(); torch.cuda.synchronize()
+    n, nb = b.n_q_tot, b.k_req.shape[0]
+    assert b.ctx.check_query_list(b.slot_map[:n], nb) == 0
+    slots = b.slot_map[:n].cpu().numpy().copy()
+    blocks = slots // 16
+    # a block with at least two rows: move its last row behind a row of another block
+    j = next(i for i in range(1, n - 1) if blocks[i] == blocks[i - 1] and blocks[i + 1] != blocks[i])
+    slots[[j, j + 1]] = slots[[j + 1, j]]
+    # (the block is split for sure; the other block too if it has further rows behind the swapped one)
+    assert b.ctx.check_query_list(torch.from_numpy(slots).to(b.slot_map.device), nb) in (1, 2)
+    # a row with a slot outside the pool ends a run, as it does in the scatter: harmless at the edge of a
+    # block's rows, a violation in the middle of them
+    slots = b.slot_map[:n].cpu().numpy().copy()
+    edge = next(i for i in range(1, n - 1) if blocks[i] != blocks[i - 1])
+    slots[edge] = -1
+    assert b.ctx.check_query_list(torch.from_numpy(slots).to(b.slot_map.device), nb) == 0
+    mid = next(i for i in range(1, n - 1) if blocks[i] == blocks[i - 1] and blocks[i] == blocks[i + 1])
+    slots[mid] = -1
+    assert b.ctx.check_query_list(torch.from_numpy(slots).to(b.slot_map.device), nb) == 1
+    assert b.ctx.check_query_list(b.slot_map[:0], nb) == 0
+
+
 @pytest.mark.parametrize("impl", ["auto", "scalar", "narrow", "wide"])
 @pytest.mark.parametrize("fused", [True, False])
 def test_values_stay_in_the_store_until_a_token_of_their_page_is_recomputed(impl, fused):
