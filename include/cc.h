@@ -118,7 +118,8 @@ const char* cc_last_error(const cc_ctx* ctx);
  * CC_IMPL_SCALAR forces the plain ones, CC_IMPL_MFMA_NARROW the MFMA kernels that give a
  * wavefront 32 query rows (64 tokens in the score stage; the only MFMA form for head groups of
  * 1 or 2), CC_IMPL_MFMA_WIDE the ones that give it 64 (128) even where AUTO would find the
- * launch too small for them (head groups that are a multiple of 4; narrow otherwise). */
+ * launch of the score stage too small for them (head groups that are a multiple of 4; narrow
+ * otherwise). */
 int cc_set_impl(cc_ctx* ctx, int impl);
 
 /* ---- (a) re-position cached keys ----------------------------------------------------------

@@ -735,8 +735,12 @@ Plan run_plan(void* ws, const cc_segment* segs, int n_segs, const int32_t* req_s
   return pl;
 }
 
-// fewest workgroups for which the wide kernels are chosen: 1.5 per compute unit of an MI355X
-constexpr int kMinWideGrid = 384;
+// Fewest workgroups for which the wide SCORE kernel is chosen (three per compute unit of an MI355X:
+// below that the narrow kernel's twice as many, half as long workgroups fill the machine better;
+// measured on batches of 1-8 requests, 32 and 64 query heads: 10-25 % for the narrow kernel at
+// 200-600 workgroups, equal at ~800, 5-15 % for the wide one above).  The wide ATTENTION kernel is
+// faster at every size measured, down to 64 workgroups (7-25 %), so it has no such limit.
+constexpr int kMinWideGrid = 768;
 
 bool attn_mfma_supported(const cc_ctx* ctx) { return group_supported(ctx); }
 bool score_mfma_supported(const cc_ctx* ctx) { return group_supported(ctx); }
@@ -753,11 +757,7 @@ void launch_attn_mfma(const cc_ctx* ctx, const void* q, const int32_t* q_pos, co
                       const AttnByProduct* by, const ValueSource& vs) {
   // Wide kernel first where the head group allows it; the narrow kernel then redoes the 64-row
   // tiles the wide one flagged (normally none: its workgroups read one flag and exit).
-  // (a grid too small to give every compute unit a wide workgroup runs faster on the narrow
-  // kernel's twice as many, half as long workgroups)
-  const int wide_wgs = ctx->cfg.n_q_heads / 4 * ((max_q_per_req + 63) / 64) * n_requests;
-  const bool wide = ctx->impl != CC_IMPL_MFMA_NARROW && attn_v2_supported(ctx) &&
-                    (wide_wgs >= kMinWideGrid || ctx->impl == CC_IMPL_MFMA_WIDE);
+  const bool wide = ctx->impl != CC_IMPL_MFMA_NARROW && attn_v2_supported(ctx);
   const int n_redo = wide ? static_cast<int>(redo_entries(n_q_tot)) : 0;
   const Plan pl = run_plan(plan_ws, segs, n_segs, req_seg_off, n_requests, block_tab, n_blocks, max_tiles, n_redo, stream);
   if (wide)
