@@ -532,9 +532,10 @@ __global__ __launch_bounds__(64 * G, 2) void sparse_qk_kernel(
 }
 
 // ---- plan: the key tiles of every segment, in prompt order ---------------------------------------
-// seg_tile_off[s] = number of tiles before segment s (exclusive scan of ceil(n_tokens/64)).
-__global__ __launch_bounds__(256) void plan_scan_kernel(const cc_segment* __restrict__ segs, int n_segs,
-                                                         int32_t* __restrict__ seg_tile_off) {
+// seg_tile_off[s] = number of tiles before segment s (exclusive scan of ceil(n_tokens/64)); run by
+// one whole workgroup of 256 threads, into global memory or into LDS.
+__device__ __forceinline__ void plan_scan(const cc_segment* __restrict__ segs, int n_segs,
+                                          int32_t* seg_tile_off) {
   __shared__ int wsum[4];
   __shared__ int carry_s;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -559,15 +560,20 @@ __global__ __launch_bounds__(256) void plan_scan_kernel(const cc_segment* __rest
     __syncthreads();
   }
   if (tid == 0) seg_tile_off[n_segs] = carry_s;
+  __syncthreads();
 }
 
-__global__ __launch_bounds__(256) void plan_fill_kernel(const cc_segment* __restrict__ segs, int n_segs,
-                                                         const int32_t* __restrict__ seg_tile_off,
-                                                         const int32_t* __restrict__ block_tab, int n_blocks,
-                                                         int max_tiles, TileDesc* __restrict__ tiles,
-                                                         int32_t* __restrict__ redo, int n_redo) {
-  const int j = blockIdx.x * 256 + threadIdx.x;
-  for (int i = j; i < n_redo; i += gridDim.x * 256) redo[i] = 0;
+__global__ __launch_bounds__(256) void plan_scan_kernel(const cc_segment* __restrict__ segs, int n_segs,
+                                                         int32_t* __restrict__ seg_tile_off) {
+  plan_scan(segs, n_segs, seg_tile_off);
+}
+
+// descriptor of tile j (and the redo flags cleared, spread over the n_fill workgroups that do this)
+__device__ __forceinline__ void plan_fill(const cc_segment* __restrict__ segs, int n_segs,
+                                          const int32_t* seg_tile_off, const int32_t* __restrict__ block_tab,
+                                          int n_blocks, int max_tiles, TileDesc* __restrict__ tiles,
+                                          int32_t* __restrict__ redo, int n_redo, int j, int n_fill) {
+  for (int i = j; i < n_redo; i += n_fill * 256) redo[i] = 0;
   if (j >= min(seg_tile_off[n_segs], max_tiles)) return;
   int lo = 0, hi = n_segs - 1;                       // last segment with seg_tile_off[s] <= j
   while (lo < hi) {
@@ -589,6 +595,15 @@ __global__ __launch_bounds__(256) void plan_fill_kernel(const cc_segment* __rest
   tiles[j] = d;
 }
 
+__global__ __launch_bounds__(256) void plan_fill_kernel(const cc_segment* __restrict__ segs, int n_segs,
+                                                         const int32_t* __restrict__ seg_tile_off,
+                                                         const int32_t* __restrict__ block_tab, int n_blocks,
+                                                         int max_tiles, TileDesc* __restrict__ tiles,
+                                                         int32_t* __restrict__ redo, int n_redo) {
+  plan_fill(segs, n_segs, seg_tile_off, block_tab, n_blocks, max_tiles, tiles, redo, n_redo,
+            blockIdx.x * 256 + threadIdx.x, gridDim.x);
+}
+
 // Dispatch order of the grid's y index: items sorted by decreasing key-side work, so that the last
 // workgroups to start are the short ones.  BY_REQUEST: item = request, key = end of its context;
 // otherwise item = segment, key = end of the segment (0 for segments that are not scored).
@@ -597,17 +612,17 @@ __global__ __launch_bounds__(256) void plan_fill_kernel(const cc_segment* __rest
 constexpr int kMaxOrdered = 4096;
 
 //
-// Beside order[] the kernel writes one 32-byte work item per rank, so that a workgroup of the
+// Beside order[] one 32-byte work item per rank is written, so that a workgroup of the
 // wide kernels finds everything it needs to start with ONE load instead of a chain of dependent
-// ones (order -> segment -> request -> tile offsets).
+// ones (order -> segment -> request -> tile offsets).  Called by whole workgroups; `block` is the
+// workgroup's index among those that do this.
 template <bool BY_REQUEST>
-__global__ __launch_bounds__(256) void plan_order_kernel(const cc_segment* __restrict__ segs,
-                                                          const int32_t* __restrict__ req_seg_off,
-                                                          const int32_t* __restrict__ seg_tile_off,
-                                                          int n_items, int32_t* __restrict__ order,
-                                                          WorkItem* __restrict__ items) {
+__device__ __forceinline__ void plan_order(const cc_segment* __restrict__ segs,
+                                           const int32_t* __restrict__ req_seg_off,
+                                           const int32_t* seg_tile_off, int n_items,
+                                           int32_t* __restrict__ order, WorkItem* __restrict__ items, int block) {
   __shared__ int key[kMaxOrdered];
-  const int i = blockIdx.x * 256 + threadIdx.x;
+  const int i = block * 256 + threadIdx.x;
   auto emit = [&](int rank, int item) {
     order[rank] = item;
     WorkItem w;
@@ -648,6 +663,40 @@ __global__ __launch_bounds__(256) void plan_order_kernel(const cc_segment* __res
     rank += (other > mine || (other == mine && j < i)) ? 1 : 0;
   }
   emit(rank, i);
+}
+
+template <bool BY_REQUEST>
+__global__ __launch_bounds__(256) void plan_order_kernel(const cc_segment* __restrict__ segs,
+                                                          const int32_t* __restrict__ req_seg_off,
+                                                          const int32_t* __restrict__ seg_tile_off,
+                                                          int n_items, int32_t* __restrict__ order,
+                                                          WorkItem* __restrict__ items) {
+  plan_order<BY_REQUEST>(segs, req_seg_off, seg_tile_off, n_items, order, items, blockIdx.x);
+}
+
+// The whole plan in ONE launch, for batches of up to kPlanFused segments: every workgroup repeats
+// the (tiny) scan into LDS, then the first n_fill workgroups write descriptors and the others the
+// dispatch order.  Two launches and two waits between dependent kernels fewer per call, which is
+// what a single request's step (a dozen kernels of a few microseconds) is made of.
+constexpr int kPlanFused = 1024;
+
+template <bool BY_REQUEST>
+__global__ __launch_bounds__(256) void plan_fused_kernel(const cc_segment* __restrict__ segs, int n_segs,
+                                                          const int32_t* __restrict__ req_seg_off, int n_items,
+                                                          const int32_t* __restrict__ block_tab, int n_blocks,
+                                                          int max_tiles, int32_t* __restrict__ seg_tile_off,
+                                                          int32_t* __restrict__ order, WorkItem* __restrict__ items,
+                                                          TileDesc* __restrict__ tiles, int32_t* __restrict__ redo,
+                                                          int n_redo, int n_fill) {
+  __shared__ int32_t s_off[kPlanFused + 1];
+  plan_scan(segs, n_segs, s_off);
+  if (blockIdx.x == 0)
+    for (int s = threadIdx.x; s <= n_segs; s += 256) seg_tile_off[s] = s_off[s];
+  if (static_cast<int>(blockIdx.x) < n_fill)
+    plan_fill(segs, n_segs, s_off, block_tab, n_blocks, max_tiles, tiles, redo, n_redo,
+              blockIdx.x * 256 + threadIdx.x, n_fill);
+  else
+    plan_order<BY_REQUEST>(segs, req_seg_off, s_off, n_items, order, items, blockIdx.x - n_fill);
 }
 
 constexpr int kAttnQB = 1;     // 32 query tokens per workgroup in the attention kernel
@@ -723,6 +772,18 @@ Plan run_plan(void* ws, const cc_segment* segs, int n_segs, const int32_t* req_s
   pl.tiles = reinterpret_cast<TileDesc*>(static_cast<char*>(ws) + plan_head_bytes(n_segs));
   pl.max_tiles = max_tiles;
   pl.redo = n_redo > 0 ? reinterpret_cast<int32_t*>(pl.tiles + max_tiles) : nullptr;
+  if (n_segs <= kPlanFused) {
+    const int n_fill = (max_tiles + 255) / 256;
+    if (n_requests > 0)
+      hipLaunchKernelGGL(plan_fused_kernel<true>, dim3(n_fill + (n_requests + 255) / 256), dim3(256), 0, stream, segs,
+                         n_segs, req_seg_off, n_requests, block_tab, n_blocks, max_tiles, pl.seg_tile_off, pl.order,
+                         pl.items, pl.tiles, pl.redo, n_redo, n_fill);
+    else
+      hipLaunchKernelGGL(plan_fused_kernel<false>, dim3(n_fill + (n_segs + 255) / 256), dim3(256), 0, stream, segs,
+                         n_segs, req_seg_off, n_segs, block_tab, n_blocks, max_tiles, pl.seg_tile_off, pl.order,
+                         pl.items, pl.tiles, pl.redo, n_redo, n_fill);
+    return pl;
+  }
   hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(256), 0, stream, segs, n_segs, pl.seg_tile_off);
   if (n_requests > 0)                                  // attention: the grid's y index walks requests
     hipLaunchKernelGGL(plan_order_kernel<true>, dim3((n_requests + 255) / 256), dim3(256), 0, stream, segs,

@@ -447,12 +447,13 @@ def test_select_from_given_scores_is_exact():
 
 @pytest.mark.parametrize("impl", ["auto", "wide"])
 def test_many_small_requests(impl):
-    # more requests (300) and segments (900) than one workgroup scans in a single pass: the plan,
-    # list and snap-row kernels loop; every request is tiny, with a ragged chunk and a short question
+    # more requests (350) and segments (1050) than one workgroup scans in a single pass, and more
+    # segments than the one-launch plan takes (1024: the three plan kernels run separately here):
+    # the plan, list and snap-row kernels loop; every request is tiny, with a ragged chunk and a short question
     rng = np.random.default_rng(9)
     lens = [int(v) for v in rng.integers(17, 90, size=40)]
     reqs = [W.RequestSpec([int(c) for c in rng.choice(40, size=2, replace=False)],
-                          [float(f) for f in rng.uniform(0.1, 0.6, size=2)], int(rng.integers(1, 9))) for _ in range(300)]
+                          [float(f) for f in rng.uniform(0.1, 0.6, size=2)], int(rng.integers(1, 9))) for _ in range(350)]
     w = W.custom("many", "bf16", 8, 2, 128, 5.0e5, lens, [int(v) for v in rng.integers(0, 30, size=40)], reqs,
                  1.0 / math.sqrt(128), seed=90)
     check_workload(w, _impls()[impl])
