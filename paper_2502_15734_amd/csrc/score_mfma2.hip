@@ -84,6 +84,12 @@ __device__ __forceinline__ u32x4 lds_to_acc(const uint4* p) {
   return r;
 }
 
+// RAGGED = false: the workgroups whose four column blocks all hold tokens of the chunk (straight-line
+//                  loop body; a chunk's last workgroup leaves at once if it holds fewer).
+// RAGGED = true : one workgroup per (segment, head group) for exactly those last workgroups: the
+//                  column blocks past the chunk's end cost no MFMA and no exponential (uniform
+//                  branches around them, which the straight-line form does not have to carry).
+template <bool RAGGED>
 __global__ __launch_bounds__(256, 2) void score_v2_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k_pool, int n_blocks,
     const TileDesc* __restrict__ tiles, int max_tiles,
@@ -93,7 +99,6 @@ __global__ __launch_bounds__(256, 2) void score_v2_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
   const int n = lane & 31, hh = lane >> 5;
   const int per_tile = hkv * n_sub;
-  const int tile = n_tiles_x - 1 - blockIdx.x / per_tile;    // late (long) tiles are dispatched first
   const int rem = blockIdx.x % per_tile;
   const int kvh = rem % hkv, hsub = rem / hkv;
   const int h = kvh * (4 * n_sub) + hsub * 4 + wave;
@@ -105,8 +110,13 @@ __global__ __launch_bounds__(256, 2) void score_v2_kernel(
   const uint4 i0 = ip[0], i1 = ip[1];
   const int sg_kind = uniform(i0.y), sg_start = uniform(i0.z), sg_ntok = uniform(i0.w);
   const int sg_tok_off = uniform(i1.x), j_begin = uniform(i1.y), j_own = uniform(i1.z);
+  // (RAGGED: the grid has one x-row per head group, and the tile is the chunk's last)
+  const int tile = RAGGED ? max(sg_ntok - 1, 0) / kTQ : n_tiles_x - 1 - blockIdx.x / per_tile;    // late (long) tiles are dispatched first
   const int t0 = tile * kTQ;
   if (sg_kind != CC_SEG_CHUNK || t0 >= sg_ntok || sg_start == 0) return;
+  // column blocks that hold tokens of the chunk
+  const int n_cols = uniform((min(t0 + kTQ, sg_ntok) - t0 + 31) >> 5);
+  if (RAGGED ? n_cols == kQB : n_cols < kQB) return;
   // token of column block qb in this lane (clamped into the chunk)
   auto token = [&](int qb) __attribute__((always_inline)) { return min(t0 + 32 * qb + n, sg_ntok - 1); };
   const int p_min = sg_start + t0;
@@ -235,8 +245,10 @@ __global__ __launch_bounds__(256, 2) void score_v2_kernel(
     for (int kk = 0; kk < 8; ++kk) {
 #pragma unroll
       for (int qb = 0; qb < kQB; ++qb) {
-        if (kk == 0) mfma_s_first(sacc[qb], ring[kk % kDepth], qreg[qb][kk]);
-        else mfma_s_acc(sacc[qb], ring[kk % kDepth], qreg[qb][kk]);
+        if (!RAGGED || qb < n_cols) {
+          if (kk == 0) mfma_s_first(sacc[qb], ring[kk % kDepth], qreg[qb][kk]);
+          else mfma_s_acc(sacc[qb], ring[kk % kDepth], qreg[qb][kk]);
+        }
       }
       const int s = kk + kDepth;
       ring[kk % kDepth] = s < 8 ? piece(img_off, blk * 8 + s) : piece(nimg_off, nblk * 8 + (s - 8));
@@ -248,6 +260,7 @@ __global__ __launch_bounds__(256, 2) void score_v2_kernel(
     if (d.nvalid < kTile || d.kpos0 + kTile - 1 > p_min) {
 #pragma unroll
       for (int qb = 0; qb < kQB; ++qb) {
+        if (RAGGED && qb >= n_cols) continue;
         int lim = min(d.nvalid - 1, sg_start + token(qb) - d.kpos0) - 8 * hh - 32 * blk;
         asm volatile("" : "+v"(lim));
 #pragma unroll
@@ -257,9 +270,11 @@ __global__ __launch_bounds__(256, 2) void score_v2_kernel(
     }
     // (an overflow shows in the sums: inf stays inf)
 #pragma unroll
-    for (int qb = 0; qb < kQB; ++qb)
+    for (int qb = 0; qb < kQB; ++qb) {
+      if (RAGGED && qb >= n_cols) continue;
 #pragma unroll
       for (int j = 0; j < 8; ++j) exp2_sum2(l_run[qb], sacc[qb][2 * j], sacc[qb][2 * j + 1]);
+    }
   };
 
   // ---- prologue: images 0, 1, 2 ---------------------------------------------------------------------
@@ -306,7 +321,7 @@ __global__ __launch_bounds__(256, 2) void score_v2_kernel(
     lt[qb] = l_run[qb] + __shfl_xor(l_run[qb], 32, 64);
     lp[qb] = l_prior[qb] + __shfl_xor(l_prior[qb], 32, 64);
     const float tot = lp[qb] + lt[qb];
-    bad = bad || !(tot > kTinySum && tot < kSafeSum);
+    bad = bad || (qb < n_cols && !(tot > kTinySum && tot < kSafeSum));
   }
   // tokens whose sums left the safe range are redone by the kernel that carries a reference
   if (__any(bad)) {
@@ -333,10 +348,18 @@ void launch_score_v2(const cc_ctx* ctx, const void* q, const void* k_pool, int n
   const int hkv = ctx->cfg.n_kv_heads, n_sub = ctx->cfg.n_q_heads / hkv / 4;
   const int n_tiles = (max_seg_tokens + kTQ - 1) / kTQ;
   dim3 grid(hkv * n_sub * n_tiles, n_segs);
-  hipLaunchKernelGGL(score_v2_kernel, grid, dim3(256), 0, stream, static_cast<const bf16_t*>(q),
+  // The chunks' last, partly empty workgroups run as a launch of their own behind the others, so that
+  // the straight-line body of the full workgroups does not have to carry the branches that skip empty
+  // column blocks (inside one kernel those branches, or a second copy of the loop, cost the full
+  // workgroups 4-5 %).  (Run beside the first launch on a second stream instead, the second launch
+  // gains another 1 % of the call on the 8B batch: not worth a stream of the library's own.)
+  hipLaunchKernelGGL(score_v2_kernel<false>, grid, dim3(256), 0, stream, static_cast<const bf16_t*>(q),
                      static_cast<const bf16_t*>(k_pool), n_blocks, pl.tiles, pl.max_tiles,
                      pl.items, ctx->cfg.n_q_heads, hkv, n_sub, n_tiles, ctx->inv_freq,
                      mass, redo);
+  hipLaunchKernelGGL(score_v2_kernel<true>, dim3(hkv * n_sub, n_segs), dim3(256), 0, stream,
+                     static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k_pool), n_blocks, pl.tiles,
+                     pl.max_tiles, pl.items, ctx->cfg.n_q_heads, hkv, n_sub, n_tiles, ctx->inv_freq, mass, redo);
 }
 
 }  // namespace cc
