@@ -152,7 +152,8 @@ int cc_rope_shift(cc_ctx* ctx,
  * Same arguments and layout as cc_rope_shift, but the source keys carry no rotation and token t of
  * instance i is rotated by (delta_pos + t) * theta^(-2i/d): delta_pos is read as the NEW position
  * of the instance's token 0.  Equivalent to cc_rope_shift on a store that was rotated at cached
- * positions c + t with delta_pos = new - c (the rotations compose).  V as in cc_rope_shift. */
+ * positions c + t with delta_pos = new - c (the rotations compose).  V and v_map as in
+ * cc_rope_shift. */
 int cc_rope_place(cc_ctx* ctx,
                   const void* k_src_pool, const void* v_src_pool, int32_t n_src_blocks,
                   void* k_dst_pool, void* v_dst_pool, int32_t n_dst_blocks,

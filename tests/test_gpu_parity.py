@@ -310,6 +310,12 @@ def test_values_stay_in_the_store_until_a_token_of_their_page_is_recomputed(impl
         src, dst, n = int(dsc[W.SHIFT_SRC_TAB]), int(dsc[W.SHIFT_DST_TAB]), int(dsc[W.SHIFT_NTOK])
         for pg in range((n + 15) // 16):
             assert vm[w.req_tab[dst + pg]] == w.store_tab[src + pg]
+    # cc_rope_place fills the map in the same way (it differs in the keys' rotation only)
+    vm_place = torch.full_like(b.v_map, -1)
+    b.ctx.rope_place(b.k_store, None, b.k_req, None, b.store_tab, b.req_tab, b.shift_descs, b.n_instances,
+                     b.max_shift_tokens, v_map=vm_place)
+    torch.cuda.synchronize()
+    assert torch.equal(vm_place, b.v_map)
     a.step(); b.step(); torch.cuda.synchronize()
     n = a.n_q_tot
     assert n == b.n_q_tot and torch.equal(a.sel_idx[:n], b.sel_idx[:n])
