@@ -1,4 +1,7 @@
-"""Builds libcachecraft.so (HIP, gfx950) in-tree with hipcc.  `python -m paper_2502_15734_amd.build`."""
+"""Builds libcachecraft.so (HIP, gfx950) in-tree with hipcc.  `python -m paper_2502_15734_amd.build`.
+`--probes` also builds the stand-alone micro-benchmarks under probes/ (what the chip sustains for the
+instruction mixes and access patterns of the kernels: MFMA streams, LDS traffic, plain copies, the
+cost of turning a query tile); they are not part of the library."""
 from __future__ import annotations
 
 import os
@@ -52,5 +55,32 @@ def build(verbose: bool = True, extra_flags=()) -> str:
     return LIB
 
 
+PROBES = os.path.join(HERE, "probes")
+
+
+def build_probes(verbose: bool = True):
+    """One executable per probes/*.hip, into _build/probes/.  Returns their paths."""
+    out_dir = os.path.join(BUILD, "probes")
+    os.makedirs(out_dir, exist_ok=True)
+    cc = hipcc()
+
+    def one(src: str) -> str:
+        exe = os.path.join(out_dir, src[:-4])
+        res = subprocess.run([cc, "-O3", "-std=c++17", "--offload-arch=gfx950", "-w", "-Xclang", "-target-feature", "-Xclang",
+                              "-packed-fp32-ops", os.path.join(PROBES, src), "-o", exe], capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError(f"hipcc failed on probes/{src}:\n{res.stderr}")
+        return exe
+
+    srcs = sorted(f for f in os.listdir(PROBES) if f.endswith(".hip"))
+    with ThreadPoolExecutor(max_workers=min(8, max(1, len(srcs)))) as ex:
+        exes = list(ex.map(one, srcs))
+    if verbose:
+        print("built " + " ".join(os.path.relpath(e, ROOT) for e in exes))
+    return exes
+
+
 if __name__ == "__main__":
     build()
+    if "--probes" in sys.argv:
+        build_probes()
