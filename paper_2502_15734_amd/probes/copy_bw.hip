@@ -27,7 +27,7 @@ __global__ __launch_bounds__(256) void copy_s(const vec16* __restrict__ s, vec16
 }
 // the K part of rope_shift without arithmetic: a workgroup moves one 32 KiB page of 128 rows x 256 B; lane (r, c) of pass u
 // reads 16 bytes at row (r + 32u) * 256 + 16c and the 16 bytes 128 further on
-template <bool NTS, int PAGE_KIB>
+template <bool NTS, int PAGE_KIB, bool NTL = false>
 __global__ __launch_bounds__(256) void copy_xy(const vec16* __restrict__ s, vec16* __restrict__ d, size_t n) {
   constexpr int ROWS = PAGE_KIB * 4;                       // rows of 256 B per page
   const size_t page = (size_t)blockIdx.x * (PAGE_KIB * 64);   // in vec16
@@ -36,7 +36,10 @@ __global__ __launch_bounds__(256) void copy_xy(const vec16* __restrict__ s, vec1
   for (int row0 = r; row0 < ROWS; row0 += 128) {
     vec16 x[4], y[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) if (row0 + 32 * u < ROWS) { x[u] = s[page + (row0 + 32 * u) * 16 + c]; y[u] = s[page + (row0 + 32 * u) * 16 + c + 8]; }
+    for (int u = 0; u < 4; ++u) if (row0 + 32 * u < ROWS) {
+      const vec16* px = s + page + (row0 + 32 * u) * 16 + c;
+      x[u] = NTL ? __builtin_nontemporal_load(px) : *px; y[u] = NTL ? __builtin_nontemporal_load(px + 8) : px[8];
+    }
 #pragma unroll
     for (int u = 0; u < 4; ++u) if (row0 + 32 * u < ROWS) {
       vec16 a = x[u] + y[u], b = x[u] ^ y[u];
@@ -76,7 +79,49 @@ template <typename F> float timeit(F f, int reps) {
   hipEventRecord(a); for (int i = 0; i < reps; ++i) f(); hipEventRecord(b); hipEventSynchronize(b);
   float ms; hipEventElapsedTime(&ms, a, b); return ms / reps;
 }
+// A short copy with cold caches: `mib` MiB moved once per measurement, a 1 GiB copy of other buffers before each one.
+template <typename F> float cold(F f, vec16* fa, vec16* fb, size_t fn, int reps) {
+  hipEvent_t a, b; (void)hipEventCreate(&a); (void)hipEventCreate(&b);
+  float best = 1e9f, sum = 0.f;
+  for (int i = 0; i < reps; ++i) {
+    copy_k<4, false, false><<<(unsigned)((fn + 1023) / 1024), 256>>>(fa, fb, fn);
+    (void)hipEventRecord(a); f(); (void)hipEventRecord(b); (void)hipEventSynchronize(b);
+    float ms; (void)hipEventElapsedTime(&ms, a, b);
+    if (i > 0) { sum += ms; best = ms < best ? ms : best; }
+  }
+  return sum / (reps - 1);
+}
+
 int main() {
+  {
+    const size_t fbytes = (size_t)1 << 30, fn = fbytes / 16;
+    vec16 *fa, *fb; (void)hipMalloc(&fa, fbytes); (void)hipMalloc(&fb, fbytes); (void)hipMemset(fa, 1, fbytes);
+    for (size_t mib : {160, 512}) {
+      size_t bytes = mib << 20, n = bytes / 16;
+      vec16 *s, *d; (void)hipMalloc(&s, bytes); (void)hipMalloc(&d, bytes); (void)hipMemset(s, 1, bytes); (void)hipMemset(d, 0, bytes);
+      { unsigned g = (unsigned)(n / (32 * 64)); float ms = cold([&] { copy_xy<true, 32><<<g, 256>>>(s, d, n); }, fa, fb, fn, 8);
+        printf("cold %4zu MiB %-28s %.3f ms  %.2f TB/s\n", mib, "xy pattern 32 KiB nt-store", ms, 2.0 * bytes / ms * 1e-9); }
+      { unsigned g = (unsigned)(n / (16 * 64)); float ms = cold([&] { copy_xy<true, 16><<<g, 256>>>(s, d, n); }, fa, fb, fn, 8);
+        printf("cold %4zu MiB %-28s %.3f ms  %.2f TB/s\n", mib, "xy pattern 16 KiB nt-store", ms, 2.0 * bytes / ms * 1e-9); }
+      { unsigned g = (unsigned)(n / (8 * 64)); float ms = cold([&] { copy_xy<true, 8><<<g, 256>>>(s, d, n); }, fa, fb, fn, 8);
+        printf("cold %4zu MiB %-28s %.3f ms  %.2f TB/s\n", mib, "xy pattern 8 KiB nt-store", ms, 2.0 * bytes / ms * 1e-9); }
+      { unsigned g = (unsigned)(n / (8 * 64)); float ms = cold([&] { copy_xy<true, 8, true><<<g, 256>>>(s, d, n); }, fa, fb, fn, 8);
+        printf("cold %4zu MiB %-28s %.3f ms  %.2f TB/s\n", mib, "xy pattern 8 KiB nt-both", ms, 2.0 * bytes / ms * 1e-9); }
+      { unsigned g = (unsigned)(n / (32 * 64)); float ms = cold([&] { copy_xy<true, 32, true><<<g, 256>>>(s, d, n); }, fa, fb, fn, 8);
+        printf("cold %4zu MiB %-28s %.3f ms  %.2f TB/s\n", mib, "xy pattern 32 KiB nt-both", ms, 2.0 * bytes / ms * 1e-9); }
+      { unsigned g = (unsigned)((n + 255) / 256); float ms = cold([&] { copy_k<1, true, false><<<g, 256>>>(s, d, n); }, fa, fb, fn, 8);
+        printf("cold %4zu MiB %-28s %.3f ms  %.2f TB/s\n", mib, "copy U1 nt-store", ms, 2.0 * bytes / ms * 1e-9); }
+      { unsigned g = (unsigned)((n + 255) / 256); float ms = cold([&] { copy_k<1, false, false><<<g, 256>>>(s, d, n); }, fa, fb, fn, 8);
+        printf("cold %4zu MiB %-28s %.3f ms  %.2f TB/s\n", mib, "copy U1", ms, 2.0 * bytes / ms * 1e-9); }
+      { unsigned g = (unsigned)((n + 255) / 256); float ms = cold([&] { copy_k<1, true, true><<<g, 256>>>(s, d, n); }, fa, fb, fn, 8);
+        printf("cold %4zu MiB %-28s %.3f ms  %.2f TB/s\n", mib, "copy U1 nt-both", ms, 2.0 * bytes / ms * 1e-9); }
+      { unsigned g = (unsigned)((n + 1023) / 1024); float ms = cold([&] { copy_k<4, true, true><<<g, 256>>>(s, d, n); }, fa, fb, fn, 8);
+        printf("cold %4zu MiB %-28s %.3f ms  %.2f TB/s\n", mib, "copy U4 nt-both", ms, 2.0 * bytes / ms * 1e-9); }
+      fflush(stdout);
+      (void)hipFree(s); (void)hipFree(d);
+    }
+    (void)hipFree(fa); (void)hipFree(fb);
+  }
   for (size_t mib : {1024}) {
     size_t bytes = mib << 20, n = bytes / 16;
     vec16 *s, *d; hipMalloc(&s, bytes); hipMalloc(&d, bytes); hipMemset(s, 1, bytes); hipMemset(d, 0, bytes);
