@@ -16,6 +16,9 @@
  *   cc_sparse_prefill  causal attention of the chosen tokens + question over the whole merged
  *                      paged KV, after writing their recomputed K, V into it
  *                      (Eq. (1), Sec. 3.4.3, Sec. 4 "Selective Token Recomputation")
+ *                      (cc_shared_values: the values of reused chunks may stay in the chunk store
+ *                      until one of their tokens is recomputed; cc_sparse_prefill_static: the same
+ *                      call for callers that cannot allocate)
  *   cc_sparse_prefill_mass  cc_sparse_prefill that also returns the question's attention to every
  *                      chunk (Sec. 3.2.2), as a by-product of the attention kernel where it can
  *   cc_check_query_list  checks the row order the write of recomputed K, V relies on
@@ -34,7 +37,8 @@
  * Conventions
  *   - Every tensor and every metadata array is DEVICE memory owned by the caller; the library
  *     never allocates, frees or synchronises.  Scratch comes from a caller-supplied workspace
- *     whose size the matching *_workspace_bytes() call returns.  Pointers must be 16-byte aligned.
+ *     whose size the matching *_workspace_bytes() call returns (cc_sparse_prefill_static keeps
+ *     its scratch in an array of the library's own).  Pointers must be 16-byte aligned.
  *   - Every call only enqueues kernels on `stream` (a hipStream_t passed as void*; NULL = the
  *     default stream) and returns.  Arguments that are visible from host scalars are checked
  *     before any launch; on error nothing is enqueued and nothing is written.
